@@ -1,0 +1,126 @@
+"""CPU oracle for C = act(A.B + bias): ctypes front end of oracle_gemm.c.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke entry point and by
+the benchmark's cpu_baseline leg; the product package never imports it, and it
+imports nothing from the product package.  See oracle_gemm.c for the
+definition it follows (the paper's Table 4 tasks 1, 2, 10 and the naive
+row-major matmul of its case-study appendix) and its arithmetic (fp64).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import numpy as np
+
+from .build import build as _build
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
+LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build())
+        i64, vp, dp = C.c_int64, C.c_void_p, C.POINTER(C.c_double)
+        L.oracle_gemm_epilogue.restype = C.c_int
+        L.oracle_gemm_epilogue.argtypes = [i64, i64, i64, i64, vp, i64, i64, vp, i64, i64,
+                                           vp, i64, vp, vp, C.c_int, C.c_int, C.c_int]
+        L.oracle_gemm_epilogue_sampled.restype = C.c_int
+        L.oracle_gemm_epilogue_sampled.argtypes = [i64, vp, vp, vp, i64, i64, i64, i64,
+                                                   vp, i64, i64, vp, i64, i64, vp, i64, vp, vp,
+                                                   C.c_int, C.c_int, C.c_int]
+        L.oracle_act.restype = C.c_double
+        L.oracle_act.argtypes = [C.c_double, C.c_int]
+        L.oracle_bf16_from_double.restype = C.c_uint16
+        L.oracle_bf16_from_double.argtypes = [C.c_double]
+        L.oracle_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _check_operand(x, dtype, what):
+    want = np.float32 if dtype == F32 else np.uint16
+    if x.dtype != want or not x.flags.c_contiguous:
+        raise TypeError(f"{what}: need C-contiguous {want.__name__} storage, got {x.dtype}")
+
+
+def _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB):
+    """Leading dimensions / strides default to those of dense [batch, rows, ld] arrays."""
+    a_col, b_col = (layout >> 1) & 1, layout & 1
+    if lda is None:
+        lda = A.shape[-1]
+    if ldb is None:
+        ldb = B.shape[-1]
+    if strideA is None:
+        strideA = (K if a_col else M) * lda if batch > 1 else 0
+    if strideB is None:
+        strideB = (N if b_col else K) * ldb if batch > 1 else 0
+    return lda, ldb, strideA, strideB
+
+
+def gemm_epilogue(A, B, bias, M, N, K, *, dtype=F32, act=ACT_NONE, layout=LAYOUT_RR, batch=1,
+                  lda=None, ldb=None, strideA=None, strideB=None, strideBias=None,
+                  want_absden=False):
+    """Y[batch, M, N] (fp64) = act(A.B + bias); optionally also |bias| + sum|a b|."""
+    _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
+    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if strideBias is None:
+            strideBias = N if (batch > 1 and bias.size >= batch * N) else 0
+    else:
+        strideBias = 0
+    Y = np.empty((batch, M, N), dtype=np.float64)
+    D = np.empty((batch, M, N), dtype=np.float64) if want_absden else None
+    rc = lib().oracle_gemm_epilogue(batch, M, N, K, _ptr(A), lda, strideA, _ptr(B), ldb, strideB,
+                                    _ptr(bias), strideBias, _ptr(Y), _ptr(D), layout, dtype, act)
+    if rc != 0:
+        raise ValueError("oracle_gemm_epilogue rejected its arguments")
+    return (Y, D) if want_absden else Y
+
+
+def gemm_epilogue_sampled(sb, si, sj, A, B, bias, M, N, K, *, dtype=F32, act=ACT_NONE,
+                          layout=LAYOUT_RR, batch=1, lda=None, ldb=None, strideA=None,
+                          strideB=None, strideBias=None, want_absden=False):
+    """The same definition evaluated only at entries (sb[t], si[t], sj[t])."""
+    _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
+    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if strideBias is None:
+            strideBias = N if (batch > 1 and bias.size >= batch * N) else 0
+    else:
+        strideBias = 0
+    sb = np.ascontiguousarray(sb, dtype=np.int64)
+    si = np.ascontiguousarray(si, dtype=np.int64)
+    sj = np.ascontiguousarray(sj, dtype=np.int64)
+    Y = np.empty(sb.shape[0], dtype=np.float64)
+    D = np.empty(sb.shape[0], dtype=np.float64) if want_absden else None
+    rc = lib().oracle_gemm_epilogue_sampled(sb.shape[0], _ptr(sb), _ptr(si), _ptr(sj), batch, M, N, K,
+                                            _ptr(A), lda, strideA, _ptr(B), ldb, strideB,
+                                            _ptr(bias), strideBias, _ptr(Y), _ptr(D), layout, dtype, act)
+    if rc != 0:
+        raise ValueError("oracle_gemm_epilogue_sampled rejected its arguments")
+    return (Y, D) if want_absden else Y
+
+
+def act(z, kind):
+    f = lib().oracle_act
+    return np.vectorize(lambda v: f(float(v), kind), otypes=[np.float64])(np.asarray(z, dtype=np.float64))
+
+
+def bf16_from_double(y):
+    """uint16 bit patterns of the bf16 nearest (ties to even) to each fp64 value."""
+    f = lib().oracle_bf16_from_double
+    return np.vectorize(lambda v: f(float(v)), otypes=[np.uint16])(np.asarray(y, dtype=np.float64))
+
+
+def num_threads():
+    return lib().oracle_num_threads()

@@ -1,0 +1,223 @@
+/*
+ * CPU oracle for the fused dense contraction  Y = act(A.B + bias).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the checker that the GPU library is
+ * compared against; nothing on the product path may call it, and it shares no
+ * code, header, table or constant with the HIP sources.
+ *
+ * What it computes is the plain definition: the paper's Matrix Multiplication
+ * task (Table 4, task 2: A is M x K, B is K x N, C = A x B is M x N) in the
+ * row-major indexing of the naive kernel of its matmul case study (appendix
+ * "One-task kernel snapshots", first listing: C[row,col] = sum_k A[row,k] *
+ * B[k,col]), valid for any M, N as in the second listing's guard.  The fused
+ * epilogue adds a length-N bias broadcast down the rows and applies ReLU
+ * (Table 4, task 10: max(0,x)), SiLU x*sigmoid(x) with the sigmoid of Table 4,
+ * task 1 (1/(1+exp(-x))), or the tanh form of GELU,
+ *     0.5 x (1 + tanh( sqrt(2/pi) (x + 0.044715 x^3) )).
+ * Bias, SiLU, GELU, bf16 storage and batching are not in the paper; they are
+ * the standard definitions named by this repository's benchmark configuration.
+ *
+ * Arithmetic: the stored fp32 / bf16 inputs are widened exactly to fp64; every
+ * product of two of them is exact in fp64 (at most 48 significant bits); the
+ * sum runs over k ascending in one fp64 accumulator starting from +0.0; the
+ * bias is added after the sum; activations use fp64 libm.  The result is kept
+ * in fp64 (no rounding to the output type), so it stands for the exact value
+ * to within about K * 2^-53 * sum|a b|.
+ *
+ * Loop nests.  When B's rows are contiguous (B stored K x N) the nest is
+ * i, k, j with a row of N accumulators, when B's columns are contiguous
+ * (B stored N x K) it is i, j, k.  Either way each output entry receives the
+ * same sequence of fp64 operations: acc += a[i,k]*b[k,j] for k = 0..K-1.
+ * OpenMP only distributes (batch, row) pairs over threads.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
+/* bit 0 of layout: B is column-major; bit 1: A is column-major */
+
+static double widen(const void *base, int64_t idx, int dtype)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+double oracle_act(double z, int act)
+{
+    switch (act) {
+    case ORACLE_ACT_NONE:
+        return z;
+    case ORACLE_ACT_RELU:
+        return z > 0.0 ? z : 0.0;
+    case ORACLE_ACT_GELU_TANH: {
+        const double pi = 3.14159265358979323846;
+        const double c = sqrt(2.0 / pi);
+        return 0.5 * z * (1.0 + tanh(c * (z + 0.044715 * z * z * z)));
+    }
+    case ORACLE_ACT_SILU:
+        return z * (1.0 / (1.0 + exp(-z)));
+    default:
+        return NAN;
+    }
+}
+
+/* Round a double to the nearest bf16 (ties to even), straight from the fp64
+ * value so that no intermediate fp32 rounding can double-round.  Returns the
+ * 16 bits.  Overflow gives infinity; NaN gives a quiet NaN. */
+uint16_t oracle_bf16_from_double(double x)
+{
+    if (isnan(x))
+        return 0x7FC0;
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    double a = fabs(x);
+    if (a == 0.0)
+        return sign;
+    if (isinf(a))
+        return sign | 0x7F80;
+    int e;
+    (void)frexp(a, &e);                /* a = m * 2^e, m in [0.5, 1) */
+    int exp_unb = e - 1;               /* a = (2m) * 2^(e-1), 2m in [1, 2) */
+    int q;                             /* a is rounded to a multiple of 2^q */
+    if (exp_unb < -126)
+        q = -126 - 7;                  /* subnormal spacing 2^-133 */
+    else
+        q = exp_unb - 7;               /* 8 significant bits */
+    double scaled = ldexp(a, -q);      /* exact */
+    double r = nearbyint(scaled);      /* default rounding mode: nearest even */
+    double v = ldexp(r, q);
+    if (v >= ldexp(1.0, 128))
+        return sign | 0x7F80;
+    /* v is exactly representable in bf16, hence in fp32 */
+    float f = (float)v;
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    return sign | (uint16_t)(bits >> 16);
+}
+
+/*
+ * Full evaluation.
+ *   A      : A[i,k] at A[b*strideA + i*lda + k]   (A row-major)  or  [.. + k*lda + i] (column-major)
+ *   B      : B[k,j] at B[b*strideB + k*ldb + j]   (B row-major)  or  [.. + j*ldb + k] (column-major)
+ *   bias   : bias[j] at bias[b*strideBias + j], fp32, NULL = zeros
+ *   Y      : fp64, Y[(b*M + i)*N + j] = act(z)
+ *   absden : optional fp64 of the same shape, |bias_j| + sum_k |a_ik b_kj|
+ * Returns 0, or -1 on a bad enum / negative size.
+ */
+int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
+                         const void *A, int64_t lda, int64_t strideA,
+                         const void *B, int64_t ldb, int64_t strideB,
+                         const float *bias, int64_t strideBias,
+                         double *Y, double *absden,
+                         int layout, int dtype, int act)
+{
+    if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
+        (dtype != ORACLE_F32 && dtype != ORACLE_BF16) || act < 0 || act > 3)
+        return -1;
+    const int a_col = (layout >> 1) & 1, b_col = layout & 1;
+    const int64_t rows = batch * M;
+
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double *den = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t bi = 0; bi < rows; ++bi) {
+            const int64_t b = bi / M, i = bi % M;
+            const int64_t a0 = b * strideA, b0 = b * strideB;
+            if (!b_col) {
+                for (int64_t j = 0; j < N; ++j) { acc[j] = 0.0; den[j] = 0.0; }
+                for (int64_t k = 0; k < K; ++k) {
+                    const double a = widen(A, a0 + (a_col ? k * lda + i : i * lda + k), dtype);
+                    const int64_t brow = b0 + k * ldb;
+                    for (int64_t j = 0; j < N; ++j) {
+                        const double p = a * widen(B, brow + j, dtype);
+                        acc[j] += p;
+                        den[j] += fabs(p);
+                    }
+                }
+            } else {
+                for (int64_t j = 0; j < N; ++j) {
+                    double s = 0.0, d = 0.0;
+                    const int64_t bcol = b0 + j * ldb;
+                    for (int64_t k = 0; k < K; ++k) {
+                        const double a = widen(A, a0 + (a_col ? k * lda + i : i * lda + k), dtype);
+                        const double p = a * widen(B, bcol + k, dtype);
+                        s += p;
+                        d += fabs(p);
+                    }
+                    acc[j] = s;
+                    den[j] = d;
+                }
+            }
+            for (int64_t j = 0; j < N; ++j) {
+                const double bj = bias ? (double)bias[b * strideBias + j] : 0.0;
+                const double z = acc[j] + bj;
+                Y[bi * N + j] = oracle_act(z, act);
+                if (absden)
+                    absden[bi * N + j] = den[j] + fabs(bj);
+            }
+        }
+        free(acc);
+        free(den);
+    }
+    return 0;
+}
+
+/*
+ * Sampled evaluation: the same definition at `count` chosen entries
+ * (sb[t], si[t], sj[t]); Y[t] and absden[t] (optional) receive the values.
+ */
+int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t *si, const int64_t *sj,
+                                 int64_t batch, int64_t M, int64_t N, int64_t K,
+                                 const void *A, int64_t lda, int64_t strideA,
+                                 const void *B, int64_t ldb, int64_t strideB,
+                                 const float *bias, int64_t strideBias,
+                                 double *Y, double *absden,
+                                 int layout, int dtype, int act)
+{
+    if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
+        (dtype != ORACLE_F32 && dtype != ORACLE_BF16) || act < 0 || act > 3)
+        return -1;
+    for (int64_t t = 0; t < count; ++t)
+        if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)
+            return -1;
+    const int a_col = (layout >> 1) & 1, b_col = layout & 1;
+
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < count; ++t) {
+        const int64_t b = sb[t], i = si[t], j = sj[t];
+        const int64_t a0 = b * strideA, b0 = b * strideB;
+        double s = 0.0, d = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const double a = widen(A, a0 + (a_col ? k * lda + i : i * lda + k), dtype);
+            const double bb = widen(B, b0 + (b_col ? j * ldb + k : k * ldb + j), dtype);
+            const double p = a * bb;
+            s += p;
+            d += fabs(p);
+        }
+        const double bj = bias ? (double)bias[b * strideBias + j] : 0.0;
+        Y[t] = oracle_act(s + bj, act);
+        if (absden)
+            absden[t] = d + fabs(bj);
+    }
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

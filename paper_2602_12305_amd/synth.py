@@ -1,0 +1,247 @@
+"""Seeded synthetic inputs for C = act(A.B + bias).
+
+Counter-based generation: every element is a pure function of
+(seed, tensor tag, batch, logical row, logical column), so storage order,
+chunking and threading cannot change the data, and a column-major buffer
+holds the same matrix as a row-major one.
+
+This module holds no arithmetic of the operator itself (no products, sums,
+bias or activation).  It is the only code the CPU checker and the GPU path
+have in common: both read the host arrays made here.
+
+The paper evaluates Matrix Multiplication (Table 4, task 2) on a task suite
+whose sizes and inputs it does not print; the five workloads below are the
+synthetic stand-ins, with the shapes and distributions fixed by the benchmark
+configuration of this repository.
+"""
+
+from __future__ import annotations
+
+import concurrent.futures as _cf
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_MAX_DIM = 1 << 24  # rows, cols < 2^24 ; batch < 2^16 (packed into one 64-bit counter)
+
+
+def _mix64(x: np.ndarray) -> np.ndarray:
+    """64-bit avalanche finaliser of SplitMix64 (Steele, Lea, Flood 2014)."""
+    x = (x ^ (x >> np.uint64(30))) * _M1
+    x = (x ^ (x >> np.uint64(27))) * _M2
+    return x ^ (x >> np.uint64(31))
+
+
+def _tag_hash(tag: str) -> np.uint64:
+    """FNV-1a over the tag's bytes."""
+    h = 0xCBF29CE484222325
+    for byte in tag.encode("utf-8"):
+        h = ((h ^ byte) * 0x100000001B3) & 0xFFFFFFFFFFFFFFFF
+    return np.uint64(h)
+
+
+def _key(seed: int, tag: str, stream: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = np.array([np.uint64(seed & 0xFFFFFFFFFFFFFFFF)], dtype=np.uint64)
+        k = _mix64(k + _GOLDEN) ^ _tag_hash(tag)
+        k = _mix64(k + np.uint64(stream + 1) * _GOLDEN)
+    return k[0]
+
+
+def _counters(batch: int, r0: int, r1: int, cols: int) -> np.ndarray:
+    r = np.arange(r0, r1, dtype=np.uint64)[:, None]
+    c = np.arange(cols, dtype=np.uint64)[None, :]
+    return (np.uint64(batch) << np.uint64(48)) | (r << np.uint64(24)) | c
+
+
+def _u01(key: np.uint64, ctr: np.ndarray) -> np.ndarray:
+    """53-bit uniform in [0, 1) as fp64."""
+    with np.errstate(over="ignore"):
+        h = _mix64(key ^ _mix64(ctr * _GOLDEN + _GOLDEN))
+    return (h >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+def _fill(kind, seed, tag, batch, rows, cols, p0, p1, out):
+    """out[batch, rows, cols] fp32 <- distribution `kind`, rounded once to fp32."""
+    if rows >= _MAX_DIM or cols >= _MAX_DIM or batch >= (1 << 16):
+        raise ValueError("dimension too large for the packed counter")
+    k0, k1 = _key(seed, tag, 0), _key(seed, tag, 1)
+    chunk = max(1, min(rows, (1 << 21) // max(cols, 1)))
+    jobs = [(b, r0, min(rows, r0 + chunk)) for b in range(batch) for r0 in range(0, rows, chunk)]
+
+    def work(job):
+        b, r0, r1 = job
+        ctr = _counters(b, r0, r1, cols)
+        u = _u01(k0, ctr)
+        if kind == "uniform":        # U[p0, p1)
+            v = p0 + (p1 - p0) * u
+        elif kind == "normal":       # N(p0, p1^2), Box-Muller, cosine branch only
+            v = _u01(k1, ctr)
+            v = p0 + p1 * np.sqrt(-2.0 * np.log1p(-u)) * np.cos(2.0 * np.pi * v)
+        elif kind == "integers":     # integers in [p0, p1], each equally likely
+            v = np.floor(p0 + (p1 - p0 + 1) * u)
+        else:
+            raise ValueError(kind)
+        out[b, r0:r1, :] = v.astype(np.float32)
+
+    if len(jobs) == 1:
+        work(jobs[0])
+    else:
+        with _cf.ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(work, jobs))
+    return out
+
+
+def _gen(kind, seed, tag, rows, cols, p0, p1, batch=None):
+    nb = 1 if batch is None else batch
+    out = np.empty((nb, rows, cols), dtype=np.float32)
+    _fill(kind, seed, tag, nb, rows, cols, p0, p1, out)
+    return out[0] if batch is None else out
+
+
+def uniform(seed, tag, rows, cols, lo=-1.0, hi=1.0, batch=None):
+    """fp32 matrix (or [batch, rows, cols] stack) iid U[lo, hi)."""
+    return _gen("uniform", seed, tag, rows, cols, float(lo), float(hi), batch)
+
+
+def normal(seed, tag, rows, cols, mean=0.0, std=1.0, batch=None):
+    """fp32 matrix iid N(mean, std^2)."""
+    return _gen("normal", seed, tag, rows, cols, float(mean), float(std), batch)
+
+
+def integers(seed, tag, rows, cols, lo=-3, hi=3, batch=None):
+    """fp32 matrix of iid integers in [lo, hi] (exactly representable in bf16 for |v| <= 256)."""
+    return _gen("integers", seed, tag, rows, cols, float(lo), float(hi), batch)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest, ties to even); returns the uint16 bit patterns.
+    NaN stays NaN (quiet bit forced), overflow rounds to infinity."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = ((u.astype(np.uint64) + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+    nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    return np.where(nan, ((u >> np.uint32(16)) | np.uint32(0x40)).astype(np.uint16), r)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
+    """(b, i, j) int64 triples to verify when the full output is too large to check:
+    `count` iid uniform draws, plus the four corners of every batch's first and last
+    matrix and the last row/column entry of every tile row/column, so that no
+    workgroup tile goes unchecked."""
+    k = _key(seed, "sample", 0)
+    ctr = np.arange(3 * count, dtype=np.uint64)
+    u = _u01(k, ctr).reshape(3, count)
+    b = np.minimum((u[0] * batch).astype(np.int64), batch - 1)
+    i = np.minimum((u[1] * M).astype(np.int64), M - 1)
+    j = np.minimum((u[2] * N).astype(np.int64), N - 1)
+    eb, ei, ej = [], [], []
+    for bb in sorted({0, batch - 1}):
+        for ii in (0, M - 1):
+            for jj in (0, N - 1):
+                eb.append(bb); ei.append(ii); ej.append(jj)
+        rows = sorted({min(M - 1, t + tile_m - 1) for t in range(0, M, tile_m)})
+        cols = sorted({min(N - 1, t + tile_n - 1) for t in range(0, N, tile_n)})
+        for ii in rows:
+            for jj in cols:
+                eb.append(bb); ei.append(ii); ej.append(jj)
+    b = np.concatenate([b, np.asarray(eb, dtype=np.int64)])
+    i = np.concatenate([i, np.asarray(ei, dtype=np.int64)])
+    j = np.concatenate([j, np.asarray(ej, dtype=np.int64)])
+    return b, i, j
+
+
+# ----------------------------------------------------------------------------------------------
+# The five workloads
+
+DTYPE_F32, DTYPE_BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
+LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
+
+
+@dataclass
+class Workload:
+    """Host arrays in storage order.  A is stored [M, lda] (row-major) or [K, lda]
+    (column-major); B likewise [K, ldb] or [N, ldb]; bias [batch, N] fp32; element
+    type fp32, or uint16 holding bf16 bits."""
+    name: str
+    batch: int
+    M: int
+    N: int
+    K: int
+    dtype: int
+    act: int
+    layout: int
+    seed: int
+    A: np.ndarray = field(repr=False)
+    B: np.ndarray = field(repr=False)
+    bias: np.ndarray = field(repr=False)
+    check: str = "full"          # "full" or "sampled"
+
+    @property
+    def flops(self):
+        return 2 * self.batch * self.M * self.N * self.K
+
+    @property
+    def algorithmic_bytes(self):
+        """One read of A, B and bias, one write of C."""
+        es = 4 if self.dtype == DTYPE_F32 else 2
+        per = (self.M * self.K + self.K * self.N + self.M * self.N) * es + 4 * self.N
+        return self.batch * per
+
+
+def _store(x, dtype, transpose=False):
+    if transpose:
+        x = np.ascontiguousarray(np.swapaxes(x, -1, -2))
+    return f32_to_bf16_bits(x) if dtype == DTYPE_BF16 else np.ascontiguousarray(x)
+
+
+WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
+             "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
+
+
+def make_workload(name: str, scale: int = 1) -> Workload:
+    """Build one of the five workloads.  `scale` > 1 divides every dimension (for
+    quick functional runs at the same distributions); the distributions' parameters that
+    depend on K (config 2's variance 1/K) follow the scaled K."""
+    s = scale
+    if name == "c1_f32_256_relu":
+        M = N = K = 256 // s
+        return Workload(name, 1, M, N, K, DTYPE_F32, ACT_RELU, LAYOUT_RR, 0,
+                        _store(uniform(0, "A", M, K), DTYPE_F32),
+                        _store(uniform(0, "B", K, N), DTYPE_F32),
+                        uniform(0, "bias", 1, N))
+    if name == "c2_f32_skinny16_silu":
+        M, N, K = 16, 16384 // s, 16384 // s
+        sd = K ** -0.5
+        return Workload(name, 1, M, N, K, DTYPE_F32, ACT_SILU, LAYOUT_RR, 1,
+                        _store(normal(1, "A", M, K, 0.0, sd), DTYPE_F32),
+                        _store(normal(1, "B", K, N, 0.0, sd), DTYPE_F32),
+                        uniform(1, "bias", 1, N, -0.1, 0.1))
+    if name == "c3_f32_4096_rc_gelu":
+        M = N = K = 4096 // s
+        return Workload(name, 1, M, N, K, DTYPE_F32, ACT_GELU_TANH, LAYOUT_RC, 2,
+                        _store(uniform(2, "A", M, K), DTYPE_F32),
+                        _store(uniform(2, "B", K, N), DTYPE_F32, transpose=True),
+                        normal(2, "bias", 1, N), check="full" if s >= 4 else "sampled")
+    if name == "c4_bf16_8192_silu":
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_RR, 3,
+                        _store(normal(3, "A", M, K), DTYPE_BF16),
+                        _store(normal(3, "B", K, N), DTYPE_BF16),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c5_bf16_batched32_relu":
+        nb, M, N, K = 32, 2048 // s, 2048 // s, 512 // s
+        return Workload(name, nb, M, N, K, DTYPE_BF16, ACT_RELU, LAYOUT_RR, 4,
+                        _store(uniform(4, "A", M, K, batch=nb), DTYPE_BF16),
+                        _store(uniform(4, "B", K, N, batch=nb), DTYPE_BF16),
+                        uniform(4, "bias", 1, N, batch=nb).reshape(nb, N),
+                        check="full" if s >= 4 else "sampled")
+    raise KeyError(name)
