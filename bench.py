@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of C = act(A.B + bias) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+
+A step is one call of the library on one seeded synthetic workload (inputs resident in
+HBM before the timed region; two rotating buffer sets so that consecutive steps do not
+re-read the same bytes from cache).  The default workload is the memory-bound skinny
+configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and adds
+them under "workloads".  One JSON line is printed.
+
+The "roofline" object prices the dominant kernel of the workload against the published
+MI355X peak (HBM 8 TB/s, dense bf16 MFMA 2516.6 TFLOP/s, fp32 MFMA 157.3 TFLOP/s) using
+algorithmic bytes / flops (one read of A, B, bias, one write of C; 2*M*N*K flops).
+"cpu_baseline" is the fp64 CPU oracle timed on this host as it stands.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6}          # fp32 MFMA, bf16 MFMA (dense)
+# which roof bounds each workload (flop per byte against the ridge of its dtype)
+BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
+         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma"}
+DTYPE_NAME = {0: "f32", 1: "bf16"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_f32_skinny16_silu")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads")
+    ap.add_argument("--variant", type=int, default=-1, help="force one kernel variant (default: dispatcher)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this library runs on one GPU; there is no multi-GPU path to time (use --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_12305_amd import binding as ob
+    from paper_2602_12305_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    def to_dev(x):
+        return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+
+    def time_workload(name, steps, warmup):
+        w = synth.make_workload(name)
+        lda, ldb = w.A.shape[-1], w.B.shape[-1]
+        sA = w.A.shape[-2] * lda if w.batch > 1 else 0
+        sB = w.B.shape[-2] * ldb if w.batch > 1 else 0
+        sBias = w.N if w.batch > 1 else 0
+        sets = []
+        for _ in range(2):
+            Cd = torch.empty((w.batch, w.M, w.N), dtype=torch.float32 if w.dtype == 0 else torch.int16, device="cuda")
+            sets.append((to_dev(w.A), to_dev(w.B), to_dev(w.bias), Cd))
+        probe = (w.batch, w.M, w.N, w.K, sets[0][0], lda, sA, sets[0][1], ldb, sB, sets[0][2], sBias,
+                 sets[0][3], w.N, w.M * w.N, w.layout, w.dtype, w.act)
+        vid = args.variant if args.variant >= 0 else ob.optiml_select_variant(*probe)
+
+        def step(i):
+            Ad, Bd, bd, Cd = sets[i & 1]
+            ob.optiml_gemm_epilogue_variant(w.batch, w.M, w.N, w.K, Ad, lda, sA, Bd, ldb, sB, bd, sBias,
+                                            Cd, w.N, w.M * w.N, w.layout, w.dtype, w.act, vid)
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+        ms = max(wall_ms, dev_ms) / steps          # whole-step time, host view
+        kernel_ms = dev_ms / steps                 # HIP events on the launch stream
+        gbs = w.algorithmic_bytes / (kernel_ms * 1e-3) / 1e9
+        tfl = w.flops / (kernel_ms * 1e-3) / 1e12
+        bound = BOUND[name]
+        roof = {"bound": bound,
+                "achieved": round(gbs if bound == "hbm" else tfl, 3),
+                "peak": PEAK_HBM_GBS if bound == "hbm" else PEAK_TFLOPS[w.dtype],
+                "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                "frac": round((gbs / PEAK_HBM_GBS) if bound == "hbm" else (tfl / PEAK_TFLOPS[w.dtype]), 4),
+                "traffic": None,
+                "kernel": ob.optiml_variant_name(vid),
+                "kernel_ms": round(kernel_ms, 5)}
+        res = {"workload": name, "variant": ob.optiml_variant_name(vid), "ms_per_step": round(ms, 5),
+               "GB/s": round(w.algorithmic_bytes / (ms * 1e-3) / 1e9, 2), "TFLOP/s": round(w.flops / (ms * 1e-3) / 1e12, 3),
+               "hbm_frac": round(gbs / PEAK_HBM_GBS, 4), "mfma_frac": round(tfl / PEAK_TFLOPS[w.dtype], 4),
+               "dtype": DTYPE_NAME[w.dtype], "roofline": roof}
+        return w, sets, res
+
+    w, sets, head = time_workload(args.workload, args.steps, args.warmup)
+    bound = BOUND[args.workload]
+    out = {
+        "metric": "GB/s (algorithmic bytes) of act(A.B+bias)" if bound == "hbm" else "TFLOP/s of act(A.B+bias)",
+        "value": head["GB/s"] if bound == "hbm" else head["TFLOP/s"],
+        "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "batch": w.batch, "M": w.M, "N": w.N, "K": w.K,
+                   "layout": ["rr", "rc", "cr", "cc"][w.layout], "act": ["none", "relu", "gelu_tanh", "silu"][w.act],
+                   "variant": head["variant"]},
+        "TFLOP/s": head["TFLOP/s"], "GB/s": head["GB/s"],
+        "roofline": head["roofline"],
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample of the same workload: whole output if that is about 5e10 multiply-adds
+        # or fewer, else seeded sampled entries
+        macs = w.flops // 2
+        t0 = time.perf_counter()
+        if macs <= 8e10:
+            ref = oracle.gemm_epilogue(w.A, w.B, w.bias, w.M, w.N, w.K, dtype=w.dtype, act=w.act, layout=w.layout,
+                                       batch=w.batch)
+            secs = time.perf_counter() - t0
+            frac, sample = 1.0, "whole workload"
+            got = sets[(args.steps - 1) & 1][3].cpu().numpy()
+            idx = None
+        else:
+            sb, si, sj = synth.sample_entries(w.seed, 1 << 20, w.batch, w.M, w.N)
+            ref = oracle.gemm_epilogue_sampled(sb, si, sj, w.A, w.B, w.bias, w.M, w.N, w.K, dtype=w.dtype, act=w.act,
+                                               layout=w.layout, batch=w.batch)
+            secs = time.perf_counter() - t0
+            frac = len(sb) / float(w.batch * w.M * w.N)
+            sample = f"{len(sb)} sampled output entries of {w.batch * w.M * w.N}"
+            got = sets[(args.steps - 1) & 1][3].cpu().numpy()
+            idx = (sb, si, sj)
+        if w.dtype == 1:
+            got = synth.bf16_bits_to_f32(got.view(np.uint16))
+        got = got.astype(np.float64)
+        if idx is not None:
+            got = got[idx]
+        rho = float(np.sqrt(np.mean(ref * ref)))
+        e1 = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rho)))
+        full_secs = secs / frac
+        cpu_val = (w.algorithmic_bytes / 1e9 if bound == "hbm" else w.flops / 1e12) / full_secs
+        out["cpu_baseline"] = {"value": float(f"{cpu_val:.4g}"), "unit": out["unit"], "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": sample, "seconds": round(secs, 3)}
+        out["parity_e1"] = float(f"{e1:.3e}")
+    del sets
+
+    if args.all:
+        out["workloads"] = {}
+        for name in synth.WORKLOADS:
+            if name == args.workload:
+                out["workloads"][name] = head
+                continue
+            _, s, r = time_workload(name, args.steps, args.warmup)
+            del s
+            torch.cuda.empty_cache()
+            out["workloads"][name] = r
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

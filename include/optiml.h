@@ -1,0 +1,172 @@
+/*
+ * optiml.h - C-ABI of the MI355X (gfx950) library for the fused dense contraction
+ *
+ *                     C = act(A . B + bias)
+ *
+ * The operation is the Matrix Multiplication task of the OptiML paper (Table 4,
+ * task 2: A is M x K, B is K x N, C = A x B is M x N, 32-bit floats), in the
+ * row-major convention of its matmul case study (appendix "One-task kernel
+ * snapshots": C[row*N+col] = sum_k A[row*K+k] * B[k*N+col], any M and N as in
+ * the guarded listing there), with a fused epilogue: a length-N bias added to
+ * every row of the product, then an elementwise activation - ReLU max(0,x)
+ * (Table 4, task 10), SiLU x*sigmoid(x) with sigmoid(x) = 1/(1+exp(-x))
+ * (Table 4, task 1), or the tanh form of GELU
+ * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).  Bias, SiLU, GELU, bf16
+ * storage, column-major operands and batching extend the paper's task; they
+ * take their standard definitions.
+ *
+ * Conventions for every entry point
+ *   Pointers   A, B, bias, C are DEVICE pointers owned by the caller.  The library
+ *              keeps no reference after the call's work has run, never frees or
+ *              reallocates them.  C must not overlap A, B or bias (not checked).
+ *   Units      lda, ldb, ldc and all strides are in ELEMENTS of the operand's type.
+ *   Layouts    C is always row-major: C[i,j] at C[i*ldc + j], ldc >= N.
+ *              A row-major: A[i,k] at A[i*lda + k], lda >= K;
+ *              A column-major: A[i,k] at A[k*lda + i], lda >= M.
+ *              B row-major: B[k,j] at B[k*ldb + j], ldb >= N;
+ *              B column-major: B[k,j] at B[j*ldb + k], ldb >= K.
+ *   dtype      OPTIML_F32: A, B, C are float.  OPTIML_BF16: A, B, C are bfloat16
+ *              (16-bit storage); products are accumulated in fp32, bias is added
+ *              and the activation applied in fp32, and C is rounded once, to nearest
+ *              even.  bias is always float; NULL means no bias.
+ *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
+ *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
+ *   Stream     `stream` is a hipStream_t passed as void* (NULL = the default
+ *              stream).  Calls only enqueue work and never synchronise with the
+ *              host; buffers must stay valid until the stream has run the work.
+ *   Alignment  Any alignment and any ld is accepted.  The fast kernels need
+ *              16-byte aligned bases and ld (and batch strides) that keep rows
+ *              16-byte aligned; other arguments are served by a guarded
+ *              element-wise kernel with the same results to rounding.
+ *   Results    Repeating a call with the same arguments gives bitwise the same C
+ *              (no floating-point atomics; split-K partial sums are combined in a
+ *              fixed order).
+ *   Workspace  Split-K kernels keep partial sums in one per-device buffer that the
+ *              library allocates on first need and grows when a larger one is
+ *              needed (the only allocation the library ever makes); calls that use
+ *              it are ordered by the stream they are enqueued on, and two streams
+ *              must not run split-K calls on one device at the same time.
+ *   Errors     The return value is an optiml_status_t; nothing is thrown or
+ *              aborted.  OPTIML_ERR_INVALID_ARG: a NULL A/B (with K > 0) or C, a
+ *              negative size or stride, an ld shorter than the row it spans, an
+ *              unknown enum - decided on the host BEFORE any GPU call, so it is
+ *              reportable on a machine without a GPU.  OPTIML_ERR_UNSUPPORTED: a
+ *              forced variant cannot run this shape / alignment.  OPTIML_ERR_HIP:
+ *              the runtime refused a launch; optiml_last_hip_error() has the code.
+ */
+#ifndef OPTIML_H
+#define OPTIML_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1 } optiml_dtype_t;
+
+typedef enum {
+    OPTIML_ACT_NONE = 0,
+    OPTIML_ACT_RELU = 1,
+    OPTIML_ACT_GELU_TANH = 2,
+    OPTIML_ACT_SILU = 3
+} optiml_act_t;
+
+/* bit 0: B is column-major; bit 1: A is column-major */
+typedef enum {
+    OPTIML_LAYOUT_RR = 0,
+    OPTIML_LAYOUT_RC = 1,
+    OPTIML_LAYOUT_CR = 2,
+    OPTIML_LAYOUT_CC = 3
+} optiml_layout_t;
+
+typedef enum {
+    OPTIML_OK = 0,
+    OPTIML_ERR_INVALID_ARG = -1,
+    OPTIML_ERR_UNSUPPORTED = -2,
+    OPTIML_ERR_HIP = -3
+} optiml_status_t;
+
+/*
+ * C[M x N] = act(A[M x K] . B[K x N] + bias[N]), every operand row-major:
+ * the paper's task 2 with the fused epilogue described above.
+ */
+int optiml_gemm_epilogue(int64_t M, int64_t N, int64_t K,
+                         const void *A, int64_t lda,
+                         const void *B, int64_t ldb,
+                         const float *bias,
+                         void *C, int64_t ldc,
+                         int dtype, int act, void *stream);
+
+/* The same with a storage layout for A and B (optiml_layout_t). */
+int optiml_gemm_epilogue_ex(int64_t M, int64_t N, int64_t K,
+                            const void *A, int64_t lda,
+                            const void *B, int64_t ldb,
+                            const float *bias,
+                            void *C, int64_t ldc,
+                            int layout, int dtype, int act, void *stream);
+
+/*
+ * `batch` independent problems of one shape: problem b uses A + b*strideA,
+ * B + b*strideB, bias + b*strideBias and C + b*strideC.  strideA or strideB may
+ * be 0 (operand shared by all problems); strideBias 0 shares one bias vector.
+ * strideC must be >= (M-1)*ldc + N when batch > 1 (outputs may not overlap).
+ */
+int optiml_gemm_epilogue_strided_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
+                                         const void *A, int64_t lda, int64_t strideA,
+                                         const void *B, int64_t ldb, int64_t strideB,
+                                         const float *bias, int64_t strideBias,
+                                         void *C, int64_t ldc, int64_t strideC,
+                                         int layout, int dtype, int act, void *stream);
+
+/*
+ * Kernel variants (tile shapes, split factors, the guarded fallback), for the
+ * profiler-driven sweep in the spirit of the paper's search over kernel
+ * candidates (section 3.2: each candidate is checked, timed and profiled).
+ * Ids are 0 .. optiml_variant_count()-1 and stable within one build.
+ */
+int optiml_variant_count(void);
+
+/* Name of a variant; static storage, never freed by the caller; NULL if id is out of range. */
+const char *optiml_variant_name(int variant_id);
+
+/*
+ * Which variant the dispatcher would run for these arguments (>= 0), or a negative
+ * optiml_status_t.  Pure host logic: touches no GPU, reads no device memory; the
+ * pointers are used for their alignment only.
+ */
+int optiml_select_variant(int64_t batch, int64_t M, int64_t N, int64_t K,
+                          const void *A, int64_t lda, int64_t strideA,
+                          const void *B, int64_t ldb, int64_t strideB,
+                          const float *bias, int64_t strideBias,
+                          void *C, int64_t ldc, int64_t strideC,
+                          int layout, int dtype, int act);
+
+/* OPTIML_OK if `variant_id` can run these arguments, OPTIML_ERR_UNSUPPORTED if not. Host only. */
+int optiml_variant_supports(int variant_id,
+                            int64_t batch, int64_t M, int64_t N, int64_t K,
+                            const void *A, int64_t lda, int64_t strideA,
+                            const void *B, int64_t ldb, int64_t strideB,
+                            const float *bias, int64_t strideBias,
+                            void *C, int64_t ldc, int64_t strideC,
+                            int layout, int dtype, int act);
+
+/* optiml_gemm_epilogue_strided_batched through one chosen variant. */
+int optiml_gemm_epilogue_variant(int64_t batch, int64_t M, int64_t N, int64_t K,
+                                 const void *A, int64_t lda, int64_t strideA,
+                                 const void *B, int64_t ldb, int64_t strideB,
+                                 const float *bias, int64_t strideBias,
+                                 void *C, int64_t ldc, int64_t strideC,
+                                 int layout, int dtype, int act, void *stream,
+                                 int variant_id);
+
+/* Human-readable text for a status code; static storage. */
+const char *optiml_status_string(int status);
+
+/* The hipError_t behind the calling thread's most recent OPTIML_ERR_HIP (0 if none). */
+int optiml_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTIML_H */

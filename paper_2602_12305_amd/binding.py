@@ -1,0 +1,142 @@
+"""ctypes binding of liboptiml.so: the same entry points as include/optiml.h.
+
+Argument marshalling only.  Operands may be torch tensors on the GPU (their
+data_ptr() is passed) or plain integers holding device addresses; shapes,
+leading dimensions and strides are always explicit, in elements.  Nothing is
+computed here and there is no fallback: if the shared library is missing, the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
+LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "liboptiml.so")
+
+_i64, _vp, _int = C.c_int64, C.c_void_p, C.c_int
+_PROBLEM = [_i64, _i64, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _i64, _int, _int, _int]
+
+SIGNATURES = {
+    "optiml_gemm_epilogue": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int, _vp]),
+    "optiml_gemm_epilogue_ex": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int, _int, _vp]),
+    "optiml_gemm_epilogue_strided_batched": (_int, _PROBLEM + [_vp]),
+    "optiml_variant_count": (_int, []),
+    "optiml_variant_name": (C.c_char_p, [_int]),
+    "optiml_select_variant": (_int, _PROBLEM),
+    "optiml_variant_supports": (_int, [_int] + _PROBLEM),
+    "optiml_gemm_epilogue_variant": (_int, _PROBLEM + [_vp, _int]),
+    "optiml_status_string": (C.c_char_p, [_int]),
+    "optiml_last_hip_error": (_int, []),
+}
+
+_lib = None
+
+
+class OptimlError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        text = lib().optiml_status_string(status).decode()
+        if status == ERR_HIP:
+            text += f" (hipError_t {lib().optiml_last_hip_error()})"
+        super().__init__(f"optiml status {status}: {text}")
+
+
+def lib():
+    """The loaded shared library (opened on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_12305_amd.csrc.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _addr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status):
+    if status != OK:
+        raise OptimlError(status)
+    return status
+
+
+def optiml_gemm_epilogue(M, N, K, A, lda, B, ldb, bias, Cout, ldc, dtype, act, stream=None):
+    return _check(lib().optiml_gemm_epilogue(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(Cout), ldc,
+                                             dtype, act, _stream(stream)))
+
+
+def optiml_gemm_epilogue_ex(M, N, K, A, lda, B, ldb, bias, Cout, ldc, layout, dtype, act, stream=None):
+    return _check(lib().optiml_gemm_epilogue_ex(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(Cout), ldc,
+                                                layout, dtype, act, _stream(stream)))
+
+
+def optiml_gemm_epilogue_strided_batched(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
+                                         Cout, ldc, strideC, layout, dtype, act, stream=None):
+    return _check(lib().optiml_gemm_epilogue_strided_batched(
+        batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB, _addr(bias), strideBias,
+        _addr(Cout), ldc, strideC, layout, dtype, act, _stream(stream)))
+
+
+def optiml_gemm_epilogue_variant(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
+                                 Cout, ldc, strideC, layout, dtype, act, variant_id, stream=None):
+    return _check(lib().optiml_gemm_epilogue_variant(
+        batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB, _addr(bias), strideBias,
+        _addr(Cout), ldc, strideC, layout, dtype, act, _stream(stream), variant_id))
+
+
+def optiml_select_variant(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
+                          Cout, ldc, strideC, layout, dtype, act):
+    """Variant id the dispatcher would use (>= 0) or a negative status; host logic only."""
+    return lib().optiml_select_variant(batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB,
+                                       _addr(bias), strideBias, _addr(Cout), ldc, strideC, layout, dtype, act)
+
+
+def optiml_variant_supports(variant_id, batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
+                            Cout, ldc, strideC, layout, dtype, act):
+    return lib().optiml_variant_supports(variant_id, batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB,
+                                         _addr(bias), strideBias, _addr(Cout), ldc, strideC, layout, dtype, act)
+
+
+def optiml_variant_count():
+    return lib().optiml_variant_count()
+
+
+def optiml_variant_name(variant_id):
+    s = lib().optiml_variant_name(variant_id)
+    return None if s is None else s.decode()
+
+
+def optiml_status_string(status):
+    return lib().optiml_status_string(status).decode()
+
+
+def optiml_last_hip_error():
+    return lib().optiml_last_hip_error()
+
+
+def variant_names():
+    return [optiml_variant_name(i) for i in range(optiml_variant_count())]

@@ -1,0 +1,248 @@
+// C-ABI entry points: argument validation (host integers only, before any GPU
+// call), variant selection, launch.  See include/optiml.h for the contract.
+#include "../../include/optiml.h"
+#include "common.hpp"
+
+#include <mutex>
+#include <vector>
+
+namespace optiml {
+
+namespace {
+
+thread_local int tls_last_hip_error = 0;
+
+struct Table {
+    std::vector<const Variant *> v;
+    int first_skinny = 0, first_tile = 0;
+    Table()
+    {
+        for (int i = 0; i < kNumGenericVariants; ++i) v.push_back(&generic_variants()[i]);
+        first_skinny = (int)v.size();
+        for (int i = 0; i < kNumSkinnyVariants; ++i) v.push_back(&skinny_variants()[i]);
+        first_tile = (int)v.size();
+        for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
+    }
+};
+
+const Table &table()
+{
+    static const Table t;
+    return t;
+}
+
+bool enum_ok(int layout, int dtype, int act)
+{
+    return layout >= 0 && layout <= 3 && (dtype == DT_F32 || dtype == DT_BF16) && act >= 0 && act <= 3;
+}
+
+// OPTIML_OK when the arguments describe a valid problem (possibly an empty one).
+int validate(const Problem &p)
+{
+    if (!enum_ok(p.layout, p.dtype, p.act)) return OPTIML_ERR_INVALID_ARG;
+    if (p.batch < 0 || p.M < 0 || p.N < 0 || p.K < 0) return OPTIML_ERR_INVALID_ARG;
+    if (p.strideA < 0 || p.strideB < 0 || p.strideBias < 0 || p.strideC < 0) return OPTIML_ERR_INVALID_ARG;
+    if (p.lda < 0 || p.ldb < 0 || p.ldc < 0) return OPTIML_ERR_INVALID_ARG;
+    if (p.batch == 0 || p.M == 0 || p.N == 0) return OPTIML_OK;
+    if (!p.C || p.ldc < p.N) return OPTIML_ERR_INVALID_ARG;
+    if (p.batch > 1 && p.strideC < (p.M - 1) * p.ldc + p.N) return OPTIML_ERR_INVALID_ARG;
+    if (p.K > 0) {
+        if (!p.A || !p.B) return OPTIML_ERR_INVALID_ARG;
+        if (p.lda < (p.a_col() ? p.M : p.K)) return OPTIML_ERR_INVALID_ARG;
+        if (p.ldb < (p.b_col() ? p.K : p.N)) return OPTIML_ERR_INVALID_ARG;
+    }
+    return OPTIML_OK;
+}
+
+bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
+
+// Preference order: the streaming split-K kernels for at most 16 rows; then the MFMA tile
+// kernels - the largest C block that still gives every CU a workgroup, else the smallest
+// block offered (each (dtype, layout) lists its blocks from large to small); then the fallback.
+int select(const Problem &p)
+{
+    const Table &t = table();
+    constexpr int64_t kComputeUnits = 256;
+    if (p.K > 0 && vector_friendly(p)) {
+        if (p.M <= 16)
+            for (int i = t.first_skinny; i < t.first_tile; ++i)
+                if (t.v[i]->supports(p)) return i;
+        int best = -1;
+        for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
+            if (!t.v[i]->supports(p)) continue;
+            best = i;
+            const int64_t blocks = ((p.M + t.v[i]->bm - 1) / t.v[i]->bm) * ((p.N + t.v[i]->bn - 1) / t.v[i]->bn) * p.batch;
+            if (blocks >= kComputeUnits) break;
+        }
+        if (best >= 0) return best;
+    }
+    for (int i = 0; i < t.first_skinny; ++i)
+        if (t.v[i]->supports(p)) return i;
+    return OPTIML_ERR_UNSUPPORTED;
+}
+
+int run(const Problem &p, int variant_id, void *stream)
+{
+    const Table &t = table();
+    if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
+    if (!t.v[variant_id]->supports(p)) return OPTIML_ERR_UNSUPPORTED;
+    hipError_t e = t.v[variant_id]->launch(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
+Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, int64_t strideA,
+             const void *B, int64_t ldb, int64_t strideB, const float *bias, int64_t strideBias,
+             void *C, int64_t ldc, int64_t strideC, int layout, int dtype, int act)
+{
+    Problem p;
+    p.batch = batch; p.M = M; p.N = N; p.K = K;
+    p.A = A; p.lda = lda; p.strideA = strideA;
+    p.B = B; p.ldb = ldb; p.strideB = strideB;
+    p.bias = bias; p.strideBias = strideBias;
+    p.C = C; p.ldc = ldc; p.strideC = strideC;
+    p.layout = layout; p.dtype = dtype; p.act = act;
+    return p;
+}
+
+struct DeviceScratch { void *ptr = nullptr; size_t bytes = 0; };
+std::mutex g_scratch_mutex;
+DeviceScratch g_scratch[64];
+
+}  // namespace
+
+bool vector_friendly(const Problem &p)
+{
+    const int64_t chunk = 16 / p.esize();
+    auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    if (!aligned(p.A) || !aligned(p.B) || !aligned(p.C)) return false;
+    if (p.lda % chunk || p.ldb % chunk || p.ldc % chunk) return false;
+    if (p.batch > 1 && (p.strideA % chunk || p.strideB % chunk || p.strideC % chunk)) return false;
+    if (p.bias && (!aligned(p.bias) || (p.batch > 1 && p.strideBias % 4))) return false;
+    return true;
+}
+
+hipError_t workspace(size_t bytes, void **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    DeviceScratch &s = g_scratch[dev];
+    if (s.bytes < bytes) {
+        if (s.ptr) {
+            e = hipFree(s.ptr);      // waits for work that may still read the old buffer
+            s.ptr = nullptr; s.bytes = 0;
+            if (e != hipSuccess) return e;
+        }
+        const size_t want = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+        e = hipMalloc(&s.ptr, want);
+        if (e != hipSuccess) { s.ptr = nullptr; return e; }
+        s.bytes = want;
+    }
+    *ptr = s.ptr;
+    return hipSuccess;
+}
+
+}  // namespace optiml
+
+using namespace optiml;
+
+extern "C" {
+
+int optiml_gemm_epilogue_strided_batched(int64_t batch, int64_t M, int64_t N, int64_t K,
+                                         const void *A, int64_t lda, int64_t strideA,
+                                         const void *B, int64_t ldb, int64_t strideB,
+                                         const float *bias, int64_t strideBias,
+                                         void *C, int64_t ldc, int64_t strideC,
+                                         int layout, int dtype, int act, void *stream)
+{
+    const Problem p = make(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias, C, ldc, strideC,
+                           layout, dtype, act);
+    const int st = validate(p);
+    if (st != OPTIML_OK || is_empty(p)) return st;
+    const int id = select(p);
+    if (id < 0) return id;
+    return run(p, id, stream);
+}
+
+int optiml_gemm_epilogue_ex(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                            int64_t ldb, const float *bias, void *C, int64_t ldc, int layout, int dtype,
+                            int act, void *stream)
+{
+    return optiml_gemm_epilogue_strided_batched(1, M, N, K, A, lda, 0, B, ldb, 0, bias, 0, C, ldc, 0, layout,
+                                                dtype, act, stream);
+}
+
+int optiml_gemm_epilogue(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                         const float *bias, void *C, int64_t ldc, int dtype, int act, void *stream)
+{
+    return optiml_gemm_epilogue_ex(M, N, K, A, lda, B, ldb, bias, C, ldc, OPTIML_LAYOUT_RR, dtype, act, stream);
+}
+
+int optiml_variant_count(void) { return (int)table().v.size(); }
+
+const char *optiml_variant_name(int id)
+{
+    const Table &t = table();
+    return (id >= 0 && id < (int)t.v.size()) ? t.v[id]->name : nullptr;
+}
+
+int optiml_select_variant(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                          int64_t strideA, const void *B, int64_t ldb, int64_t strideB, const float *bias,
+                          int64_t strideBias, void *C, int64_t ldc, int64_t strideC, int layout, int dtype,
+                          int act)
+{
+    const Problem p = make(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias, C, ldc, strideC,
+                           layout, dtype, act);
+    const int st = validate(p);
+    if (st != OPTIML_OK) return st;
+    return select(p);
+}
+
+int optiml_variant_supports(int variant_id, int64_t batch, int64_t M, int64_t N, int64_t K, const void *A,
+                            int64_t lda, int64_t strideA, const void *B, int64_t ldb, int64_t strideB,
+                            const float *bias, int64_t strideBias, void *C, int64_t ldc, int64_t strideC,
+                            int layout, int dtype, int act)
+{
+    const Problem p = make(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias, C, ldc, strideC,
+                           layout, dtype, act);
+    const int st = validate(p);
+    if (st != OPTIML_OK) return st;
+    const Table &t = table();
+    if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
+    return t.v[variant_id]->supports(p) ? OPTIML_OK : OPTIML_ERR_UNSUPPORTED;
+}
+
+int optiml_gemm_epilogue_variant(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                                 int64_t strideA, const void *B, int64_t ldb, int64_t strideB,
+                                 const float *bias, int64_t strideBias, void *C, int64_t ldc, int64_t strideC,
+                                 int layout, int dtype, int act, void *stream, int variant_id)
+{
+    const Problem p = make(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias, C, ldc, strideC,
+                           layout, dtype, act);
+    const int st = validate(p);
+    if (st != OPTIML_OK) return st;
+    if (variant_id < 0 || variant_id >= optiml_variant_count()) return OPTIML_ERR_INVALID_ARG;
+    if (is_empty(p)) return OPTIML_OK;
+    return run(p, variant_id, stream);
+}
+
+const char *optiml_status_string(int status)
+{
+    switch (status) {
+    case OPTIML_OK: return "ok";
+    case OPTIML_ERR_INVALID_ARG: return "invalid argument";
+    case OPTIML_ERR_UNSUPPORTED: return "variant does not support these arguments";
+    case OPTIML_ERR_HIP: return "HIP runtime error (see optiml_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int optiml_last_hip_error(void) { return tls_last_hip_error; }
+
+}  // extern "C"

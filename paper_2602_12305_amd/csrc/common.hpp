@@ -1,0 +1,46 @@
+// Shared host/device declarations of the library: the problem descriptor that
+// every kernel launcher receives and the variant table entry.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace optiml {
+
+enum : int { DT_F32 = 0, DT_BF16 = 1 };
+enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
+
+// C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.
+struct Problem {
+    int64_t batch, M, N, K;
+    const void *A; int64_t lda, strideA;
+    const void *B; int64_t ldb, strideB;
+    const float *bias; int64_t strideBias;
+    void *C; int64_t ldc, strideC;
+    int layout;   // bit 0: B column-major, bit 1: A column-major
+    int dtype, act;
+    bool a_col() const { return (layout & 2) != 0; }
+    bool b_col() const { return (layout & 1) != 0; }
+    int esize() const { return dtype == DT_F32 ? 4 : 2; }
+};
+
+struct Variant {
+    const char *name;
+    bool (*supports)(const Problem &);
+    hipError_t (*launch)(const Problem &, hipStream_t);
+    int bm, bn;   // C block computed by one workgroup (0, 0 where that does not apply)
+};
+
+// every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks
+bool vector_friendly(const Problem &p);
+
+// per-device scratch for split-K partial sums (grown on demand, never shrunk)
+hipError_t workspace(size_t bytes, void **ptr);
+
+// tables defined next to the kernels they launch
+const Variant *generic_variants();         extern const int kNumGenericVariants;
+const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 12;
+// the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
+const Variant *tile_variants();            extern const int kNumTileVariants;
+constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
+
+}  // namespace optiml

@@ -1,0 +1,121 @@
+// Guarded fallback kernel: any M, N, K, layout, leading dimension and alignment.
+// It has the semantics of the paper's task 2 with a bounds check on every access
+// (the case-study appendix guards each output the same way) plus the fused
+// epilogue, and serves every argument set that the MFMA and streaming kernels
+// decline.  Design: a 256-thread workgroup owns a 64x64 block of C; each thread
+// keeps a 4x4 block of fp32 accumulators in registers; 16-deep k-slices of A and
+// B pass through LDS stored k-major, so the inner product reads two 4-vectors
+// per k and does 16 FMAs.  All global accesses are scalar and guarded; elements
+// outside the problem read as zero.
+#include "common.hpp"
+#include "epilogue.hpp"
+
+namespace optiml {
+namespace {
+
+constexpr int GT = 64;   // C block edge
+constexpr int GK = 16;   // k-slice depth
+constexpr int PADDED = GT + 4;
+
+template <typename E> __device__ __forceinline__ float widen(E v);
+template <> __device__ __forceinline__ float widen<float>(float v) { return v; }
+template <> __device__ __forceinline__ float widen<unsigned short>(unsigned short v) { return bf16_to_f32(v); }
+
+__device__ __forceinline__ void put(float *p, float y) { *p = y; }
+__device__ __forceinline__ void put(unsigned short *p, float y) { *p = f32_to_bf16(y); }
+
+template <typename E>
+__global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_m, int64_t y0)
+{
+    __shared__ float As[GK][PADDED];   // As[k][row]
+    __shared__ float Bs[GK][PADDED];   // Bs[k][col]
+    const int tid = threadIdx.x;
+    const int ty = tid >> 4, tx = tid & 15;
+    const int64_t by = y0 + blockIdx.y;
+    const int64_t b = by / blocks_m;
+    const int64_t row0 = (by % blocks_m) * GT, col0 = (int64_t)blockIdx.x * GT;
+    const E *A = static_cast<const E *>(p.A) + b * p.strideA;
+    const E *B = static_cast<const E *>(p.B) + b * p.strideB;
+    const bool a_col = (p.layout & 2) != 0, b_col = (p.layout & 1) != 0;
+
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < p.K; k0 += GK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + 256 * i;            // 1024 elements per slice
+            // consecutive threads walk the operand's contiguous storage direction
+            const int ar = a_col ? (e & 63) : (e >> 4), ak = a_col ? (e >> 6) : (e & 15);
+            const int64_t gr = row0 + ar, gk = k0 + ak;
+            float v = 0.0f;
+            if (gr < p.M && gk < p.K)
+                v = widen<E>(a_col ? A[gk * p.lda + gr] : A[gr * p.lda + gk]);
+            As[ak][ar] = v;
+            const int bc = b_col ? (e >> 4) : (e & 63), bk = b_col ? (e & 15) : (e >> 6);
+            const int64_t gc = col0 + bc, gkb = k0 + bk;
+            float w = 0.0f;
+            if (gc < p.N && gkb < p.K)
+                w = widen<E>(b_col ? B[gc * p.ldb + gkb] : B[gkb * p.ldb + gc]);
+            Bs[bk][bc] = w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            float a[4], c[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; c[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = fmaf(a[i], c[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    E *C = static_cast<E *>(p.C) + b * p.strideC;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t col = col0 + tx * 4 + j;
+        if (col >= p.N) continue;
+        const float bj = p.bias ? p.bias[b * p.strideBias + col] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t row = row0 + ty * 4 + i;
+            if (row < p.M)
+                put(&C[row * p.ldc + col], apply_act(acc[i][j] + bj, p.act));
+        }
+    }
+}
+
+bool generic_supports(const Problem &p)
+{
+    return (p.N + GT - 1) / GT <= 0x7fffffffLL;
+}
+
+// grid.y holds (batch, row block) pairs, at most 65535 per launch
+hipError_t generic_launch(const Problem &p, hipStream_t s)
+{
+    const int64_t blocks_m = (p.M + GT - 1) / GT, blocks_n = (p.N + GT - 1) / GT;
+    const int64_t total_y = blocks_m * p.batch;
+    for (int64_t y0 = 0; y0 < total_y; y0 += 65535) {
+        const int64_t ny = total_y - y0 < 65535 ? total_y - y0 : 65535;
+        dim3 grid((unsigned)blocks_n, (unsigned)ny), block(256);
+        if (p.dtype == DT_F32)
+            hipLaunchKernelGGL(generic_kernel<float>, grid, block, 0, s, p, blocks_m, y0);
+        else
+            hipLaunchKernelGGL(generic_kernel<unsigned short>, grid, block, 0, s, p, blocks_m, y0);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+const Variant *generic_variants()
+{
+    static const Variant v[] = {{"generic_64x64", generic_supports, generic_launch, 0, 0}};
+    return v;
+}
+const int kNumGenericVariants = 1;
+
+}  // namespace optiml

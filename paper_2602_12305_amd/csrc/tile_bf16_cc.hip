@@ -1,0 +1,7 @@
+// MFMA tile kernels, bf16 inputs, layout cc (A column-major, B column-major).
+#define TILE_DT optiml::DT_BF16
+#define TILE_A_KC false
+#define TILE_B_KC true
+#define TILE_TAG "bf16_cc"
+#define TILE_SYMBOL kTile_bf16_cc
+#include "tile_instances.inc"

@@ -1,0 +1,7 @@
+// MFMA tile kernels, bf16 inputs, layout cr (A column-major, B row-major).
+#define TILE_DT optiml::DT_BF16
+#define TILE_A_KC false
+#define TILE_B_KC false
+#define TILE_TAG "bf16_cr"
+#define TILE_SYMBOL kTile_bf16_cr
+#include "tile_instances.inc"

@@ -1,0 +1,29 @@
+// Gathers the per-(dtype, layout) MFMA tile tables into one list.
+#include "common.hpp"
+
+namespace optiml {
+
+const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc();
+const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
+
+namespace {
+struct Gather {
+    Variant v[8 * kTilesPerUnit];
+    Gather()
+    {
+        const Variant *units[8] = {kTile_f32_rr(),  kTile_f32_rc(),  kTile_f32_cr(),  kTile_f32_cc(),
+                                   kTile_bf16_rr(), kTile_bf16_rc(), kTile_bf16_cr(), kTile_bf16_cc()};
+        for (int u = 0; u < 8; ++u)
+            for (int i = 0; i < kTilesPerUnit; ++i) v[u * kTilesPerUnit + i] = units[u][i];
+    }
+};
+}  // namespace
+
+const Variant *tile_variants()
+{
+    static const Gather g;
+    return g.v;
+}
+const int kNumTileVariants = 8 * kTilesPerUnit;
+
+}  // namespace optiml

@@ -1,0 +1,124 @@
+"""The C-ABI boundary on a machine without a GPU: the library loads, exports every
+declared symbol, and every invalid-argument path answers before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_12305_amd import binding as ob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "optiml.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(optiml_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(ob.LIB_PATH)
+    names = declared_symbols()
+    assert len(names) == 10
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(ob.SIGNATURES) == names
+
+
+def test_variant_table():
+    n = ob.optiml_variant_count()
+    names = ob.variant_names()
+    assert n == len(names) >= 3 and len(set(names)) == n
+    assert names[0].startswith("generic")
+    assert ob.optiml_variant_name(-1) is None and ob.optiml_variant_name(n) is None
+    assert any(s.startswith("skinny_f32") for s in names)
+    for dt in ("f32", "bf16"):
+        for lay in ("rr", "rc", "cr", "cc"):
+            assert any(s.startswith(f"tile_{dt}_{lay}_") for s in names)
+
+
+def test_status_strings():
+    assert ob.optiml_status_string(0) == "ok"
+    for s in (-1, -2, -3, 7):
+        assert ob.optiml_status_string(s)
+    assert ob.optiml_last_hip_error() == 0
+
+
+P = 0x10000  # a fake, 16-byte aligned device address: never dereferenced on these paths
+
+
+def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBias=0, C=P, ldc=8, sC=0,
+         layout=0, dtype=0, act=0):
+    return ob.lib().optiml_gemm_epilogue_strided_batched(batch, M, N, K, A, lda, sA, B, ldb, sB, bias, sBias,
+                                                         C, ldc, sC, layout, dtype, act, None)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(M=-1), dict(N=-1), dict(K=-1), dict(batch=-1),
+    dict(A=None), dict(B=None), dict(C=None),
+    dict(lda=7), dict(ldb=7), dict(ldc=7),
+    dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
+    dict(layout=4), dict(layout=-1), dict(dtype=2), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
+    dict(batch=2, sC=63), dict(batch=2, sC=0),
+])
+def test_invalid_arguments_are_rejected_on_the_host(kw):
+    assert call(**kw) == ob.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw", [dict(M=0), dict(N=0), dict(batch=0), dict(M=0, A=None, C=None)])
+def test_empty_problems_are_ok_without_a_gpu(kw):
+    assert call(**kw) == ob.OK
+
+
+def test_plain_and_ex_entry_points_validate_too():
+    L = ob.lib()
+    assert L.optiml_gemm_epilogue(8, 8, 8, P, 8, P, 8, None, None, 8, 0, 0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_gemm_epilogue(8, 8, 8, P, 8, P, 4, None, P, 8, 0, 0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_gemm_epilogue_ex(8, 8, 8, P, 8, P, 8, None, P, 8, 9, 0, 0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_gemm_epilogue(0, 8, 8, None, 8, None, 8, None, None, 8, 0, 0, None) == ob.OK
+    assert L.optiml_gemm_epilogue_variant(1, 8, 8, 8, P, 8, 0, P, 8, 0, None, 0, P, 8, 0, 0, 0, 0, None, 9999) == ob.ERR_INVALID_ARG
+    with pytest.raises(ob.OptimlError):
+        ob.optiml_gemm_epilogue(8, 8, 8, P, 8, P, 8, None, 0, 8, 0, 0, stream=0)
+
+
+def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bias=P):
+    a_col, b_col = (layout >> 1) & 1, layout & 1
+    lda = lda if lda is not None else (M if a_col else K)
+    ldb = ldb if ldb is not None else (K if b_col else N)
+    ldc = ldc if ldc is not None else N
+    v = ob.optiml_select_variant(batch, M, N, K, A, lda, M * K, P, ldb, K * N, bias, N, P, ldc, M * ldc, layout, dtype, 0)
+    return ob.optiml_variant_name(v) if v >= 0 else v
+
+
+def test_dispatch_by_shape_dtype_layout_alignment():
+    assert sel(1, 16, 16384, 16384).startswith("skinny_f32")
+    assert sel(1, 8, 4096, 4096).startswith("skinny_f32")
+    assert sel(1, 4096, 4096, 4096, layout=1).startswith("tile_f32_rc_256x256")
+    assert sel(1, 8192, 8192, 8192, dtype=1).startswith("tile_bf16_rr_256x256")
+    assert sel(32, 2048, 2048, 512, dtype=1).startswith("tile_bf16_rr_256x256")
+    assert sel(1, 256, 256, 256).startswith("tile_f32_rr_128x128")       # too few blocks for larger tiles
+    assert sel(1, 1024, 1024, 64, layout=3, dtype=1).startswith("tile_bf16_cc_")
+    # K = 0, misaligned base, odd leading dimension, ragged contiguous extent -> guarded fallback
+    assert sel(1, 64, 64, 0).startswith("generic")
+    assert sel(1, 512, 512, 512, A=P + 4).startswith("generic")
+    assert sel(1, 512, 512, 512, lda=513).startswith("generic")
+    assert sel(1, 512, 510, 512, ldb=512, ldc=512).startswith("generic")  # N % 4 != 0 with row-major B
+    assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("tile_f32_rc")   # fine when k is contiguous
+    assert sel(1, 16, 1024, 1022, lda=1024).startswith("generic")
+    assert sel(1, 16, 1024, 1024, dtype=1).startswith("tile_bf16_rr")      # skinny path is fp32 only
+    assert sel(1, 8, 8, 8, layout=7) == ob.ERR_INVALID_ARG
+
+
+def test_variant_supports_is_host_only_and_consistent():
+    names = ob.variant_names()
+    args = (1, 16, 1024, 1024, P, 1024, 0, P, 1024, 0, P, 0, P, 1024, 0, 0, 0, 0)
+    ok = [n for i, n in enumerate(names) if ob.optiml_variant_supports(i, *args) == ob.OK]
+    assert any(n.startswith("generic") for n in ok) and any(n.startswith("skinny") for n in ok)
+    assert all(not n.startswith("tile_bf16") for n in ok) and all("_rc_" not in n for n in ok)
+    assert ob.optiml_variant_supports(len(names), *args) == ob.ERR_INVALID_ARG
+    bf16 = (1, 16, 1024, 1024, P, 1024, 0, P, 1024, 0, P, 0, P, 1024, 0, 0, 1, 0)
+    sk = next(i for i, n in enumerate(names) if n.startswith("skinny"))
+    assert ob.optiml_variant_supports(sk, *bf16) == ob.ERR_UNSUPPORTED
+    assert ob.lib().optiml_gemm_epilogue_variant(*bf16, None, sk) == ob.ERR_UNSUPPORTED

@@ -1,0 +1,259 @@
+"""Parity of the HIP library with the CPU oracle, element by element, through the C-ABI.
+
+Tiers follow the paper's test plan for candidate kernels (section 3.2, "TestPlan"):
+L0 smoke and edge cases, L1 seeded randomized shapes with tolerances, L2 metamorphic
+relations.  Sizes are small enough for the oracle to finish in well under a second
+and large enough to span several workgroup tiles with ragged edges and a k tail.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_12305_amd import binding as ob
+from paper_2602_12305_amd import synth
+from gpu_harness import TOL, check_against_oracle, run_gpu, to_dev
+from helpers import e1, store
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = synth.DTYPE_F32, synth.DTYPE_BF16
+ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
+LAYOUT_OF = {"rr": 0, "rc": 1, "cr": 2, "cc": 3}
+
+
+def variant_ids(prefix):
+    return [i for i, n in enumerate(ob.variant_names()) if n.startswith(prefix)]
+
+
+def all_variants():
+    return list(enumerate(ob.variant_names()))
+
+
+def problem_for(name):
+    """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
+    if name.startswith("skinny"):
+        return F32, 0, 13, 1000, 1224
+    if name.startswith("tile"):
+        _, dt, lay = name.split("_")[:3]
+        dtype = F32 if dt == "f32" else BF16
+        ch = 4 if dtype == F32 else 8
+        M, N, K = 300, 392, 200      # multiples of 8 where a contiguous extent needs it
+        layout = LAYOUT_OF[lay]
+        if layout & 2:
+            M = 296                   # A column-major: M is the contiguous extent
+        return dtype, layout, M, N, K
+    return F32, 3, 77, 91, 53
+
+
+# ---- L1: every variant, forced, against the oracle ------------------------------------------
+@pytest.mark.parametrize("vid,name", all_variants())
+def test_every_variant_matches_oracle(vid, name):
+    dtype, layout, M, N, K = problem_for(name)
+    A = synth.uniform(100 + vid, "A", M, K); B = synth.uniform(100 + vid, "B", K, N)
+    bias = synth.uniform(100 + vid, "bias", 1, N)[0]
+    for act in ACTS:
+        check_against_oracle(A, B, bias, dtype=dtype, act=act, layout=layout, variant=vid)
+    check_against_oracle(A, B, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, ldc_pad=8)
+
+
+@pytest.mark.parametrize("vid,name", all_variants())
+def test_every_variant_is_exact_on_integers(vid, name):
+    dtype, layout, M, N, K = problem_for(name)
+    A = synth.integers(200 + vid, "A", M, K); B = synth.integers(200 + vid, "B", K, N)
+    bias = synth.integers(200 + vid, "bias", 1, N, -5, 5)[0]
+    for act in (synth.ACT_NONE, synth.ACT_RELU):
+        check_against_oracle(A, B, bias, dtype=dtype, act=act, layout=layout, variant=vid, exact=True)
+
+
+@pytest.mark.parametrize("vid,name", all_variants())
+def test_every_variant_batched_and_repeatable(vid, name):
+    dtype, layout, M, N, K = problem_for(name)
+    batch = 3
+    A = synth.normal(300 + vid, "A", M, K, batch=batch); B = synth.normal(300 + vid, "B", K, N, batch=batch)
+    bias = synth.normal(300 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
+    As = store(A, dtype, (layout >> 1) & 1); Bs = store(B, dtype, layout & 1)
+    Y1, _, C1 = run_gpu(As, Bs, bias, batch, M, N, K, dtype, synth.ACT_SILU, layout, variant=vid)
+    Y2, _, C2 = run_gpu(As, Bs, bias, batch, M, N, K, dtype, synth.ACT_SILU, layout, variant=vid)
+    assert torch.equal(C1, C2)                                      # bitwise repeatable
+    ref = oracle.gemm_epilogue(As, Bs, bias, M, N, K, dtype=dtype, act=synth.ACT_SILU, layout=layout, batch=batch)
+    assert e1(Y1, ref) <= TOL[dtype]
+    for b in range(batch):                                           # batched == loop of singles, bitwise
+        Yb, _, _ = run_gpu(As[b], Bs[b], bias[b], 1, M, N, K, dtype, synth.ACT_SILU, layout, variant=vid)
+        assert np.array_equal(Yb[0], Y1[b])
+
+
+# ---- L1: dispatcher over seeded random shapes, all layouts / dtypes / acts / paddings --------
+def fuzz_cases():
+    rng = np.random.default_rng(2602)
+    edge = [1, 2, 3, 7, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+    cases = []
+    for t in range(48):
+        M = int(rng.choice(edge)) if t % 3 else int(rng.integers(1, 400))
+        N = int(rng.choice(edge)) if t % 3 == 1 else int(rng.integers(1, 400))
+        K = int(rng.choice(edge)) if t % 3 == 2 else int(rng.integers(1, 300))
+        cases.append((t, M, N, K, int(rng.integers(0, 4)), int(rng.integers(0, 2)), int(rng.integers(0, 4)),
+                      int(rng.choice([0, 0, 1, 4, 8])), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("t,M,N,K,layout,dtype,act,pad,use_bias", fuzz_cases())
+def test_dispatch_random_shapes(t, M, N, K, layout, dtype, act, pad, use_bias):
+    A = synth.uniform(400 + t, "A", M, K); B = synth.uniform(400 + t, "B", K, N)
+    bias = synth.uniform(400 + t, "bias", 1, N)[0] if use_bias else None
+    check_against_oracle(A, B, bias, dtype=dtype, act=act, layout=layout, pad=pad, ldc_pad=pad)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+def test_dispatch_aligned_multi_tile_shapes(dtype, layout):
+    # shapes the MFMA kernels take (aligned, multiples of 8), several tiles in both directions,
+    # K not a multiple of the k-tile
+    for (M, N, K) in [(520, 264, 72), (264, 776, 328), (1032, 1048, 40)]:
+        A = synth.normal(500, "A", M, K); B = synth.normal(500, "B", K, N); bias = synth.normal(500, "bias", 1, N)[0]
+        v = ob.optiml_select_variant(1, M, N, K, 0x1000, A.shape[0] if layout & 2 else K, 0, 0x1000,
+                                     K if layout & 1 else N, 0, 0x1000, 0, 0x1000, N, 0, layout, dtype, 2)
+        assert ob.optiml_variant_name(v).startswith("tile_")
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout,
+                             entry="ex")
+
+
+def test_plain_entry_point_is_row_major():
+    A = synth.uniform(600, "A", 70, 50); B = synth.uniform(600, "B", 50, 90); bias = synth.uniform(600, "bias", 1, 90)[0]
+    for dtype in (F32, BF16):
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_RELU, layout=0, entry="plain")
+
+
+# ---- L0: edge cases -------------------------------------------------------------------------
+def test_identity_and_permutation_are_exact():
+    K, N = 200, 136
+    B = synth.uniform(700, "B", K, N)
+    P = np.zeros((K, K), dtype=np.float32); P[np.arange(K), np.random.default_rng(1).permutation(K)] = 1
+    for dtype, layout in itertools.product((F32, BF16), range(4)):
+        check_against_oracle(np.eye(K, dtype=np.float32), B, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, exact=True)
+        check_against_oracle(P, B, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, exact=True)
+        check_against_oracle(B.T.copy(), P, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, exact=True)
+
+
+def test_alternating_signs_catch_a_lost_k_tail():
+    # a_ik = (-1)^k, b = 1: z = 0 (K even) or 1 (K odd); any dropped or doubled k shows
+    for K in (8, 64, 72, 200, 264, 1000, 1001):
+        for M, N in ((16, 512), (264, 264)):
+            A = np.tile(np.where(np.arange(K) % 2 == 0, 1.0, -1.0).astype(np.float32), (M, 1))
+            B = np.ones((K, N), dtype=np.float32)
+            for dtype in (F32, BF16):
+                check_against_oracle(A, B, None, dtype=dtype, act=synth.ACT_NONE, layout=0, exact=True)
+
+
+def test_K_zero_is_activation_of_bias_and_null_bias_is_zero():
+    M, N = 20, 24
+    bias = synth.uniform(800, "bias", 1, N, -3, 3)[0]
+    A = np.zeros((M, 0), dtype=np.float32); B = np.zeros((0, N), dtype=np.float32)
+    for dtype, act in itertools.product((F32, BF16), ACTS):
+        As = store(A, dtype); Bs = store(B, dtype)
+        Cd_args = dict(batch=1, M=M, N=N, K=0)
+        from gpu_harness import alloc_c, c_values
+        Cd = alloc_c(1, M, N, dtype)
+        ob.optiml_gemm_epilogue(M, N, 0, None, 0, None, N, to_dev(bias), Cd, N, dtype, act)
+        torch.cuda.synchronize()
+        Y, _ = c_values(Cd, dtype, N)
+        ref = oracle.gemm_epilogue(As.reshape(M, 0), Bs.reshape(0, N), bias, M, N, 0, dtype=dtype, act=act, lda=0, ldb=N)
+        assert e1(Y, ref) <= TOL[dtype]
+        Cd = alloc_c(1, M, N, dtype)
+        ob.optiml_gemm_epilogue(M, N, 0, None, 0, None, N, None, Cd, N, dtype, act)
+        torch.cuda.synchronize()
+        assert np.all(c_values(Cd, dtype, N)[0] == 0.0)
+
+
+def test_empty_outputs_write_nothing():
+    from gpu_harness import alloc_c
+    Cd = alloc_c(1, 4, 4, F32)
+    before = Cd.clone()
+    ob.optiml_gemm_epilogue(0, 4, 4, Cd, 4, Cd, 4, None, Cd, 4, F32, 0)
+    ob.optiml_gemm_epilogue(4, 0, 4, Cd, 4, Cd, 4, None, Cd, 4, F32, 0)
+    ob.optiml_gemm_epilogue_strided_batched(0, 4, 4, 4, Cd, 4, 0, Cd, 4, 0, None, 0, Cd, 4, 16, 0, F32, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(Cd, before)
+
+
+def test_large_pre_activations_stay_finite():
+    # |z| of several hundred: SiLU and GELU must give z (positive side) or 0 (negative side), never NaN
+    M, N, K = 64, 64, 64
+    A = np.full((M, K), 3.0, dtype=np.float32); A[::2] = -3.0
+    B = np.full((K, N), 2.5, dtype=np.float32)
+    for dtype, act in itertools.product((F32, BF16), (synth.ACT_SILU, synth.ACT_GELU_TANH)):
+        As = store(A, dtype); Bs = store(B, dtype)
+        Y, _, _ = run_gpu(As, Bs, None, 1, M, N, K, dtype, act, 0)
+        assert np.all(np.isfinite(Y))
+        assert np.all(Y[0, 1::2] == 480.0) and np.all(Y[0, ::2] == 0.0)
+
+
+def test_shared_operands_with_zero_strides():
+    batch, M, N, K = 4, 40, 48, 56
+    A = synth.uniform(900, "A", M, K, batch=batch); B = synth.uniform(900, "B", K, N); bias = synth.uniform(900, "bias", 1, N)[0]
+    for dtype in (F32, BF16):
+        As = store(A, dtype); Bs = store(B, dtype)
+        Y, _, _ = run_gpu(As, Bs, bias, batch, M, N, K, dtype, synth.ACT_RELU, 0, strideB=0, strideBias=0)
+        ref = oracle.gemm_epilogue(As, Bs, bias, M, N, K, dtype=dtype, act=synth.ACT_RELU, batch=batch, strideB=0, strideBias=0)
+        assert e1(Y, ref) <= TOL[dtype]
+
+
+def test_runs_on_a_side_stream():
+    M, N, K = 128, 256, 192
+    A = synth.uniform(1000, "A", M, K); B = synth.uniform(1000, "B", K, N)
+    Ad, Bd = to_dev(A), to_dev(B)
+    Cd = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        ob.optiml_gemm_epilogue(M, N, K, Ad, K, Bd, N, None, Cd, N, F32, 0)      # binding takes the current stream
+    ob.optiml_gemm_epilogue(M, N, K, Ad, K, Bd, N, None, Cd, N, F32, 0, stream=s)
+    s.synchronize()
+    ref = oracle.gemm_epilogue(A, B, None, M, N, K)
+    assert e1(Cd.cpu().numpy(), ref) <= 1e-5
+
+
+# ---- L2: metamorphic relations on the GPU path ----------------------------------------------
+def test_power_of_two_scaling_is_exact_on_gpu():
+    M, N, K = 264, 264, 136
+    A = synth.uniform(1100, "A", M, K); B = synth.uniform(1100, "B", K, N); bias = synth.uniform(1100, "bias", 1, N)[0]
+    for dtype in (F32, BF16):
+        base, _, _ = run_gpu(store(A, dtype), store(B, dtype), bias, 1, M, N, K, dtype, synth.ACT_RELU, 0)
+        for p in (-2, 3):
+            s = np.float32(2.0 ** p)
+            Y, _, _ = run_gpu(store(A * s, dtype), store(B, dtype), bias * s, 1, M, N, K, dtype, synth.ACT_RELU, 0)
+            assert np.array_equal(Y, base * float(s))
+
+
+def test_transpose_duality_between_layouts():
+    # the same logical problem through all four storage layouts gives the same result to rounding
+    M, N, K = 264, 272, 200
+    A = synth.uniform(1200, "A", M, K); B = synth.uniform(1200, "B", K, N)
+    ref = oracle.gemm_epilogue(A, B, None, M, N, K)
+    for layout in range(4):
+        Y, _, _ = run_gpu(store(A, F32, (layout >> 1) & 1), store(B, F32, layout & 1), None, 1, M, N, K, F32, 0, layout)
+        assert e1(Y, ref) <= 1e-5
+
+
+def test_row_permutation_equivariance():
+    M, N, K = 264, 264, 200
+    A = synth.uniform(1300, "A", M, K); B = synth.uniform(1300, "B", K, N)
+    # permute blocks of 8 rows: the rows of C move with them
+    perm = np.arange(M).reshape(-1, 8)[np.random.default_rng(2).permutation(M // 8)].ravel()
+    Y, _, _ = run_gpu(store(A, F32), store(B, F32), None, 1, M, N, K, F32, synth.ACT_SILU, 0)
+    Yp, _, _ = run_gpu(store(A[perm], F32), store(B, F32), None, 1, M, N, K, F32, synth.ACT_SILU, 0)
+    assert e1(Yp[0], Y[0][perm]) <= 1e-6
+
+
+@pytest.mark.parametrize("vid", variant_ids("skinny"))
+def test_skinny_variants_with_grid_split_k(vid):
+    # K long enough that the automatic split uses several workgroups per column block, and
+    # M = 16 rows exactly; a second shape has a ragged last column block and a k tail
+    for (M, N, K) in ((16, 512, 8192), (5, 328, 4100)):
+        A = synth.normal(1400 + vid, "A", M, K, 0.0, K ** -0.5); B = synth.normal(1400 + vid, "B", K, N, 0.0, K ** -0.5)
+        bias = synth.uniform(1400 + vid, "bias", 1, N, -0.1, 0.1)[0]
+        check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
+        Ai = synth.integers(1400 + vid, "Ai", M, K); Bi = synth.integers(1400 + vid, "Bi", K, N)
+        check_against_oracle(Ai, Bi, None, dtype=F32, act=synth.ACT_NONE, layout=0, variant=vid, exact=True)

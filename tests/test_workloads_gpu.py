@@ -1,0 +1,86 @@
+"""The five benchmark workloads at full size, in the launch configuration bench.py times
+(the dispatcher's choice), against the CPU oracle: every entry where the oracle finishes in
+seconds, otherwise 65,536 seeded sampled entries plus tile corners.  Each shape is also run
+on integer-valued inputs, where any fp32 summation order must reproduce the exact result."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_12305_amd import binding as ob
+from paper_2602_12305_amd import synth
+from gpu_harness import TOL, c_values, alloc_c, to_dev
+from helpers import e1
+
+pytestmark = pytest.mark.gpu
+
+
+def run_workload(w):
+    lda, ldb = w.A.shape[-1], w.B.shape[-1]
+    sA = w.A.shape[-2] * lda if w.batch > 1 else 0
+    sB = w.B.shape[-2] * ldb if w.batch > 1 else 0
+    Ad, Bd, bd = to_dev(w.A), to_dev(w.B), to_dev(w.bias)
+    Cd = alloc_c(w.batch, w.M, w.N, w.dtype)
+    ob.optiml_gemm_epilogue_strided_batched(w.batch, w.M, w.N, w.K, Ad, lda, sA, Bd, ldb, sB, bd, w.N if w.batch > 1 else 0,
+                                            Cd, w.N, w.M * w.N, w.layout, w.dtype, w.act)
+    torch.cuda.synchronize()
+    first = Cd.clone()
+    ob.optiml_gemm_epilogue_strided_batched(w.batch, w.M, w.N, w.K, Ad, lda, sA, Bd, ldb, sB, bd, w.N if w.batch > 1 else 0,
+                                            Cd, w.N, w.M * w.N, w.layout, w.dtype, w.act)
+    torch.cuda.synchronize()
+    assert torch.equal(first, Cd), "two runs of the same call differ bitwise"
+    del Ad, Bd
+    return c_values(Cd, w.dtype, w.N)[0]
+
+
+def reference(w, Y):
+    """(gpu values, oracle values) over the checked entries."""
+    if w.check == "full":
+        ref = oracle.gemm_epilogue(w.A, w.B, w.bias, w.M, w.N, w.K, dtype=w.dtype, act=w.act, layout=w.layout, batch=w.batch)
+        return Y, ref
+    sb, si, sj = synth.sample_entries(w.seed, 65536, w.batch, w.M, w.N)
+    ref = oracle.gemm_epilogue_sampled(sb, si, sj, w.A, w.B, w.bias, w.M, w.N, w.K, dtype=w.dtype, act=w.act,
+                                       layout=w.layout, batch=w.batch)
+    return Y[sb, si, sj], ref
+
+
+FULL_CHECK = {"c1_f32_256_relu": "full", "c2_f32_skinny16_silu": "full", "c3_f32_4096_rc_gelu": "full",
+              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full"}
+
+
+@pytest.mark.parametrize("name", synth.WORKLOADS)
+def test_workload_matches_oracle(name):
+    w = synth.make_workload(name)
+    w.check = FULL_CHECK[name]
+    Y = run_workload(w)
+    got, ref = reference(w, Y)
+    assert np.all(np.isfinite(Y))
+    err = e1(got, ref)
+    print(f"{name}: E1 = {err:.3e} over {ref.size} entries ({w.check})")
+    assert err <= TOL[w.dtype]
+    if w.dtype == synth.DTYPE_BF16:
+        # each output is within one bf16 step of the correctly rounded exact value
+        want = synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64)
+        ulp = np.abs(want) * 2.0 ** -7 + 1e-30
+        assert np.all(np.abs(got - want) <= ulp)
+
+
+@pytest.mark.parametrize("name", synth.WORKLOADS)
+def test_workload_shape_is_exact_on_integers(name):
+    w = synth.make_workload(name, scale=1 if name in ("c1_f32_256_relu", "c5_bf16_batched32_relu") else 1)
+    lead = (w.batch,) if w.batch > 1 else ()
+    def ints(tag, rows, cols, transpose):
+        x = synth.integers(w.seed + 77, tag, rows, cols, batch=w.batch if w.batch > 1 else None)
+        if transpose:
+            x = np.ascontiguousarray(np.swapaxes(x, -1, -2))
+        return synth.f32_to_bf16_bits(x) if w.dtype == synth.DTYPE_BF16 else x
+    w.A = ints("A", w.M, w.K, bool(w.layout & 2))
+    w.B = ints("B", w.K, w.N, bool(w.layout & 1))
+    w.bias = synth.integers(w.seed + 77, "bias", 1, w.N, -5, 5, batch=w.batch).reshape(w.batch, w.N)
+    w.act = synth.ACT_RELU
+    w.check = "sampled"
+    Y = run_workload(w)
+    got, ref = reference(w, Y)
+    if w.dtype == synth.DTYPE_BF16:
+        ref = synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64)
+    assert np.array_equal(got, ref)
