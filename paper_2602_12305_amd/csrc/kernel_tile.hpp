@@ -249,28 +249,57 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
         if (more) fetch(kt + 1);
 
         const char *a_base = cur + a_wave, *b_base = cur + C::A_BYTES + b_wave;
+        if constexpr (C::dt == DT_BF16) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uintx4 fa[TM], fb[TN];
+            for (int s = 0; s < 4; ++s) {
+                uintx4 fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const uintx4 *>(a_base + i * 32 * 128 + frag_off[s]);
+                for (int i = 0; i < TM; ++i)
+                    fa[i] = *reinterpret_cast<const uintx4 *>(a_base + i * 32 * 128 + frag_off[s]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const uintx4 *>(b_base + j * 32 * 128 + frag_off[s]);
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = *reinterpret_cast<const uintx4 *>(b_base + j * 32 * 128 + frag_off[s]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    if constexpr (C::dt == DT_BF16) {
+                    for (int i = 0; i < TM; ++i)
                         acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[j]),
                                                                             __builtin_bit_cast(bf16x8, fa[i]),
                                                                             acc[j][i], 0, 0, 0);
-                    } else {
+            }
+        } else {
+            // fp32: the 32 k of this tile are summed into fresh accumulators (two independent
+            // MFMA chains at a time) and then added to the running sums on the vector ALU.
+            // Blocked summation keeps the rounding error of a long k loop near
+            // sqrt(K * 32) * 2^-24 instead of K * 2^-24 relative to the terms' size.
+            static_assert(C::dt != DT_F32 || TM % 2 == 0, "fp32 path pairs MFMA tiles along m");
+            uintx4 fa[4][TM], fb[4][TN];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[j][e]),
-                                                                             __uint_as_float(fa[i][e]), acc[j][i], 0,
-                                                                             0, 0);
-                    }
+            for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[s][i] = *reinterpret_cast<const uintx4 *>(a_base + i * 32 * 128 + frag_off[s]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[s][j] = *reinterpret_cast<const uintx4 *>(b_base + j * 32 * 128 + frag_off[s]);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; i += 2) {
+                    floatx16 t0, t1;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) { t0[r] = 0.0f; t1[r] = 0.0f; }
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float b = __uint_as_float(fb[s][j][e]);
+                            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, __uint_as_float(fa[s][i][e]), t0, 0, 0, 0);
+                            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, __uint_as_float(fa[s][i + 1][e]), t1, 0, 0, 0);
+                        }
+                    acc[j][i] += t0;
+                    acc[j][i + 1] += t1;
                 }
         }
 

@@ -1,5 +1,6 @@
 // MFMA tile kernels, f32 inputs, layout cr (A column-major, B row-major).
 #define TILE_DT optiml::DT_F32
+#define TILE_IS_F32 1
 #define TILE_A_KC false
 #define TILE_B_KC false
 #define TILE_TAG "f32_cr"
