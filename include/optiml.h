@@ -160,6 +160,22 @@ int optiml_gemm_epilogue_variant(int64_t batch, int64_t M, int64_t N, int64_t K,
                                  int layout, int dtype, int act, void *stream,
                                  int variant_id);
 
+/*
+ * Registers per lane, scratch (spill) bytes per lane and static LDS bytes per workgroup of a
+ * variant's main kernel, as the HIP runtime reports them: the inputs of the register and
+ * spill guardrails in the paper's reward (section 3.2, "Guardrails").  Any out pointer may be
+ * NULL.  Needs a GPU (the code object is loaded); OPTIML_ERR_HIP if the query fails.
+ */
+int optiml_variant_resources(int variant_id, int *num_regs, int *scratch_bytes, int *lds_bytes);
+
+/*
+ * Plain device-to-device copy of nbytes (a multiple of 16; both pointers 16-byte aligned) with
+ * 128-bit loads and stores: the Matrix Copy task of the paper's Table 4 (task 13).  It exists
+ * to measure the HBM bandwidth a streaming kernel can reach on this GPU and to calibrate the
+ * profiler's byte counters against a transfer of known size.  Enqueued on `stream`.
+ */
+int optiml_copy_bytes(void *dst, const void *src, int64_t nbytes, void *stream);
+
 /* Human-readable text for a status code; static storage. */
 const char *optiml_status_string(int status);
 

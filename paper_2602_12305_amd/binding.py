@@ -30,6 +30,8 @@ SIGNATURES = {
     "optiml_select_variant": (_int, _PROBLEM),
     "optiml_variant_supports": (_int, [_int] + _PROBLEM),
     "optiml_gemm_epilogue_variant": (_int, _PROBLEM + [_vp, _int]),
+    "optiml_variant_resources": (_int, [_int, C.POINTER(_int), C.POINTER(_int), C.POINTER(_int)]),
+    "optiml_copy_bytes": (_int, [_vp, _vp, _i64, _vp]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -53,6 +55,12 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_12305_amd.csrc.build` "
                               "(there is no fallback path)")
+        # PyTorch carries its own HIP runtime; load it first so that the library binds to that
+        # copy (two runtimes in one process do not share a device context)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(L, name)
@@ -128,6 +136,17 @@ def optiml_variant_count():
 def optiml_variant_name(variant_id):
     s = lib().optiml_variant_name(variant_id)
     return None if s is None else s.decode()
+
+
+def optiml_variant_resources(variant_id):
+    """(registers per lane, scratch bytes per lane, static LDS bytes) of a variant's main kernel."""
+    r, sc, l = _int(0), _int(0), _int(0)
+    _check(lib().optiml_variant_resources(variant_id, C.byref(r), C.byref(sc), C.byref(l)))
+    return r.value, sc.value, l.value
+
+
+def optiml_copy_bytes(dst, src, nbytes, stream=None):
+    return _check(lib().optiml_copy_bytes(_addr(dst), _addr(src), nbytes, _stream(stream)))
 
 
 def optiml_status_string(status):

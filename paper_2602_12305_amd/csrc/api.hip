@@ -57,8 +57,9 @@ int validate(const Problem &p)
 bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 
 // Preference order: the streaming split-K kernels for at most 16 rows; then the MFMA tile
-// kernels - the largest C block that still gives every CU a workgroup, else the smallest
-// block offered (each (dtype, layout) lists its blocks from large to small); then the fallback.
+// kernels in table order (direct-to-LDS kernels before staged ones, large C blocks before
+// small) - the first whose grid gives every CU a workgroup, else the one with most
+// workgroups; then the fallback.
 int select(const Problem &p)
 {
     const Table &t = table();
@@ -68,11 +69,12 @@ int select(const Problem &p)
             for (int i = t.first_skinny; i < t.first_tile; ++i)
                 if (t.v[i]->supports(p)) return i;
         int best = -1;
+        int64_t best_blocks = -1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
             if (!t.v[i]->supports(p)) continue;
-            best = i;
             const int64_t blocks = ((p.M + t.v[i]->bm - 1) / t.v[i]->bm) * ((p.N + t.v[i]->bn - 1) / t.v[i]->bn) * p.batch;
-            if (blocks >= kComputeUnits) break;
+            if (blocks >= kComputeUnits) return i;
+            if (blocks > best_blocks) { best = i; best_blocks = blocks; }
         }
         if (best >= 0) return best;
     }
@@ -230,6 +232,49 @@ int optiml_gemm_epilogue_variant(int64_t batch, int64_t M, int64_t N, int64_t K,
     if (variant_id < 0 || variant_id >= optiml_variant_count()) return OPTIML_ERR_INVALID_ARG;
     if (is_empty(p)) return OPTIML_OK;
     return run(p, variant_id, stream);
+}
+
+int optiml_variant_resources(int variant_id, int *num_regs, int *scratch_bytes, int *lds_bytes)
+{
+    const Table &t = table();
+    if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, t.v[variant_id]->kernel);
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    if (num_regs) *num_regs = attr.numRegs;
+    if (scratch_bytes) *scratch_bytes = (int)attr.localSizeBytes;
+    if (lds_bytes) *lds_bytes = (int)attr.sharedSizeBytes;
+    return OPTIML_OK;
+}
+
+namespace optiml {
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *src, uint4 *dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace optiml
+
+int optiml_copy_bytes(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (nbytes < 0 || nbytes % 16 != 0) return OPTIML_ERR_INVALID_ARG;
+    if (nbytes == 0) return OPTIML_OK;
+    if (!dst || !src || (reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+        return OPTIML_ERR_INVALID_ARG;
+    const int64_t n16 = nbytes / 16;
+    int64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;      // grid-stride: 32 workgroups per CU
+    hipLaunchKernelGGL(optiml::copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
 }
 
 const char *optiml_status_string(int status)

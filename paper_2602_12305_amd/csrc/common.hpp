@@ -28,6 +28,7 @@ struct Variant {
     bool (*supports)(const Problem &);
     hipError_t (*launch)(const Problem &, hipStream_t);
     int bm, bn;   // C block computed by one workgroup (0, 0 where that does not apply)
+    const void *kernel;   // host handle of the variant's main kernel, for hipFuncGetAttributes
 };
 
 // every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks
@@ -42,5 +43,6 @@ const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 12
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
+constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
 
 }  // namespace optiml

@@ -113,7 +113,8 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
 
 const Variant *generic_variants()
 {
-    static const Variant v[] = {{"generic_64x64", generic_supports, generic_launch, 0, 0}};
+    static const Variant v[] = {{"generic_64x64", generic_supports, generic_launch, 0, 0,
+                                 reinterpret_cast<const void *>(&generic_kernel<float>)}};
     return v;
 }
 const int kNumGenericVariants = 1;

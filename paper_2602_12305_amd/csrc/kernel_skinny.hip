@@ -281,7 +281,7 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
 
 #define SKINNY(WN, WK, CG, NT, SPLIT)                                                     \
     {"skinny_f32_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT, skinny_supports, \
-     skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0}
+     skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0, reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT>)}
 
 // The first entry is the dispatcher's choice; the rest are there for the sweep.
 const Variant *skinny_variants()

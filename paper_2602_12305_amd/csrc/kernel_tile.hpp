@@ -12,10 +12,12 @@
 // LDS format (both operands, both dtypes).  A tile is ROWS x 128 bytes: row r is
 // one row of A (an m index) or one column of B (an n index), and holds BK
 // consecutive k (32 fp32 or 64 bf16) as eight 16-byte chunks; chunk c of row r
-// lives at byte r*128 + ((c ^ (r & 7)) << 4).  Eight lanes that touch eight
-// consecutive rows at one logical chunk, or one row at eight chunks, then cover
-// all 32 banks once: both the 128-bit stores that fill the tile and the 128-bit
-// fragment loads are conflict-free.
+// lives at byte r*128 + ((c ^ ((r >> 1) & 7)) << 4).  The LDS of gfx950 has 64
+// four-byte banks (a 128-bit access is served 16 lanes at a time, 256 bytes per
+// clock, measured), so a row pair spans all banks once; with the key taken from
+// r >> 1, sixteen lanes that touch sixteen consecutive rows at one logical chunk,
+// or two rows at eight chunks each, hit every bank exactly once: both the 128-bit
+// stores that fill the tile and the 128-bit fragment loads are conflict-free.
 //
 // Filling a tile.  If k is the operand's contiguous direction in memory (A
 // row-major, B column-major) a thread copies 16-byte chunks as they are.  If not
@@ -135,7 +137,7 @@ struct Loader {
             for (int i = 0; i < PER_THREAD; ++i) {
                 const int id = tid + i * THREADS;
                 const int c = id & 7, r = id >> 3;
-                *reinterpret_cast<uintx4 *>(lds + r * 128 + ((c ^ (r & 7)) << 4)) = reg[i];
+                *reinterpret_cast<uintx4 *>(lds + r * 128 + ((c ^ ((r >> 1) & 7)) << 4)) = reg[i];
             }
         } else {
 #pragma unroll
@@ -164,7 +166,7 @@ struct Loader {
 #pragma unroll
                 for (int n = 0; n < CH; ++n) {
                     const int r = ng * CH + n;
-                    *reinterpret_cast<uintx4 *>(lds + r * 128 + ((kc ^ (r & 7)) << 4)) = out[n];
+                    *reinterpret_cast<uintx4 *>(lds + r * 128 + ((kc ^ ((r >> 1) & 7)) << 4)) = out[n];
                 }
             }
         }
@@ -216,11 +218,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.0f;
 
-    // per-lane fragment addressing: row lane%32 of a 32-row fragment, chunk (2s + lane/32) ^ (lane & 7)
+    // per-lane fragment addressing: row lane%32 of a 32-row fragment, chunk (2s + lane/32) ^ ((row >> 1) & 7)
     const int frag_row = lane & 31, half = lane >> 5;
     int frag_off[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) frag_off[s] = frag_row * 128 + (((2 * s + half) ^ (lane & 7)) << 4);
+    for (int s = 0; s < 4; ++s) frag_off[s] = frag_row * 128 + (((2 * s + half) ^ ((frag_row >> 1) & 7)) << 4);
     const int a_wave = wm * (C::BM / C::WM) * 128, b_wave = wn * (C::BN / C::WN) * 128;
 
     const int64_t nk = (p.K + BK - 1) / BK;

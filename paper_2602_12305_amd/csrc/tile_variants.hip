@@ -5,16 +5,23 @@ namespace optiml {
 
 const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc();
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
+const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc();
 
 namespace {
 struct Gather {
-    Variant v[8 * kTilesPerUnit];
+    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit];
     Gather()
     {
+        // the direct-to-LDS kernels come first: where they apply the dispatcher prefers them
+        constexpr int D = 2 * kDirectPerUnit;
+        for (int i = 0; i < kDirectPerUnit; ++i) {
+            v[i] = kDirect_bf16_rr()[i];
+            v[kDirectPerUnit + i] = kDirect_bf16_rc()[i];
+        }
         const Variant *units[8] = {kTile_f32_rr(),  kTile_f32_rc(),  kTile_f32_cr(),  kTile_f32_cc(),
                                    kTile_bf16_rr(), kTile_bf16_rc(), kTile_bf16_cr(), kTile_bf16_cc()};
         for (int u = 0; u < 8; ++u)
-            for (int i = 0; i < kTilesPerUnit; ++i) v[u * kTilesPerUnit + i] = units[u][i];
+            for (int i = 0; i < kTilesPerUnit; ++i) v[D + u * kTilesPerUnit + i] = units[u][i];
     }
 };
 }  // namespace
@@ -24,6 +31,6 @@ const Variant *tile_variants()
     static const Gather g;
     return g.v;
 }
-const int kNumTileVariants = 8 * kTilesPerUnit;
+const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit;
 
 }  // namespace optiml

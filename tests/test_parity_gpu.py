@@ -36,6 +36,9 @@ def problem_for(name):
     """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
     if name.startswith("skinny"):
         return F32, 0, 13, 1000, 1224
+    if name.startswith("direct"):
+        _, dt, lay = name.split("_")[:3]
+        return BF16, LAYOUT_OF[lay], 300, 392, 320          # K a multiple of 64
     if name.startswith("tile"):
         _, dt, lay = name.split("_")[:3]
         dtype = F32 if dt == "f32" else BF16
