@@ -8,10 +8,24 @@
 
 namespace optiml {
 
+// exp(-x) to about 2 ulp from the hardware base-2 exponential: the product -x*log2(e) is
+// formed with its rounding error (fma) and the error is applied as a first-order correction.
+// Saturates to +inf / 0 outside the fp32 range, which is what the sigmoid below wants.
+__device__ __forceinline__ float exp_neg(float x)
+{
+    const float l2e_hi = -1.44269502162933349609375f;     // -log2(e) rounded to fp32
+    const float l2e_lo = -1.925963033500011e-08f;          // -(log2(e) - fp32(log2(e)))
+    const float t = x * l2e_hi;
+    const float r = fmaf(x, l2e_hi, -t) + x * l2e_lo;      // what the rounded product lost
+    const float p = __builtin_amdgcn_exp2f(t);
+    return p * fmaf(r, 0.693147180559945f, 1.0f);          // 2^(t+r) = 2^t (1 + r ln 2 + ...); inf stays inf
+}
+
 __device__ __forceinline__ float sigmoidf_(float x)
 {
-    // expf(-x) overflows to +inf for x < -88.7 and the quotient is then +0: the right limit
-    return 1.0f / (1.0f + expf(-x));
+    // exp(-x) overflows to +inf for x < -88.7 and the reciprocal is then +0: the right limit.
+    // v_rcp_f32 is accurate to 1 ulp.
+    return __builtin_amdgcn_rcpf(1.0f + exp_neg(x));
 }
 
 __device__ __forceinline__ float apply_act(float z, int act)
@@ -39,6 +53,16 @@ __device__ __forceinline__ unsigned short f32_to_bf16(float f)
         return (unsigned short)((u >> 16) | 0x40u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (unsigned short)(u >> 16);
+}
+
+// two fp32 -> two bf16 packed in one dword (lo in bits 0..15), round to nearest even:
+// the conversion instruction of gfx950 (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned int f32x2_to_bf16x2(float lo, float hi)
+{
+    typedef float floatx2_ __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_ __attribute__((ext_vector_type(2)));
+    const bf16x2_ v = __builtin_convertvector(floatx2_{lo, hi}, bf16x2_);
+    return __builtin_bit_cast(unsigned int, v);
 }
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b)

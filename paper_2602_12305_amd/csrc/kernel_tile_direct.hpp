@@ -269,47 +269,67 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
     }
     if (kt < nk) tile_step<C>(ctx, A + last * 128, B + last * b_step, stage1, stage0, acc);
 
-    // epilogue: register r of acc[j][i] is Z[m][n], m = mw + 32 i + lane%32,
-    // n = nw + 32 j + 8 (r/4) + 4 (lane/32) + r%4
+    // Epilogue.  Register r of acc[j][i] is Z[m][n] with m = mw + 32 i + lane%32 and
+    // n = nw + 32 j + 8 (r/4) + 4 (lane/32) + r%4: a lane owns short runs of one row, which
+    // would make 8-byte stores scattered over 32 rows.  Each wave therefore passes its tile
+    // through a private LDS slab, 32 rows at a time (bias, activation and the rounding to bf16
+    // happen in registers first), and reads it back with 16 bytes per lane along the rows, so
+    // that every global store instruction writes whole 128-byte lines.  The slab rows are
+    // padded by 16 bytes to spread the 32 row-strided writes over the banks.  All waves have
+    // passed the k loop's last barrier, so the operand stages are free to reuse.
     const int64_t mw = m0 + wm * C::WTM, nw = n0 + wn * C::WTN;
     const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
     char *Cb = p.C + batch * p.strideC * 2;
+    constexpr int PITCH = C::WTN * 2 + 16;                       // bytes per slab row
+    constexpr int CPR = C::WTN / 8;                              // 16-byte chunks per row
+    constexpr int READS = 32 * CPR / 64;                         // wave-wide 1 KiB reads per slab
+    lds_char *slab = (lds_char *)lds + wave * (32 * PITCH);
+    float bj[TN][4][4];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const int64_t n = nw + 32 * j + 8 * gq + 4 * half;
-            if (n >= p.N) continue;
-            const bool whole = n + 3 < p.N;
-            float bj[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (bias) {
-                if (whole) {
-                    const floatx4 v = *reinterpret_cast<const floatx4 *>(bias + n);
-                    bj[0] = v[0]; bj[1] = v[1]; bj[2] = v[2]; bj[3] = v[3];
-                } else {
+            if (bias && n + 3 < p.N) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(bias + n);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < p.N) bj[e] = bias[n + e];
-                }
+                for (int e = 0; e < 4; ++e) bj[j][gq][e] = v[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bj[j][gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
+            }
+        }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
+                *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
+                    slab + frag_row * PITCH + (32 * j + 8 * gq + 4 * half) * 2) =
+                    uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
             }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int64_t m = mw + 32 * i + frag_row;
-                if (m >= p.M) continue;
-                unsigned short h[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16(apply_act(acc[j][i][4 * gq + e] + bj[e], p.act));
+        for (int q = 0; q < READS; ++q) {
+            const int id = q * 64 + lane, row = id / CPR, chunk = id % CPR;
+            const uintx4 v = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(slab + row * PITCH + chunk * 16);
+            const int64_t m = mw + 32 * i + row, n = nw + chunk * 8;
+            if (m < p.M && n < p.N) {
                 char *dst = Cb + (m * p.ldc + n) * 2;
-                if (whole) {
-                    *reinterpret_cast<uintx2 *>(dst) =
-                        uintx2{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
+                if (n + 8 <= p.N) {
+                    *reinterpret_cast<uintx4 *>(dst) = v;
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < p.N) reinterpret_cast<unsigned short *>(dst)[e] = h[e];
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < p.N)
+                            reinterpret_cast<unsigned short *>(dst)[e] = (unsigned short)(v[e >> 1] >> ((e & 1) * 16));
                 }
             }
         }
+    }
 #endif
 }
 

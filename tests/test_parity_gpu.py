@@ -260,3 +260,27 @@ def test_skinny_variants_with_grid_split_k(vid):
         check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
         Ai = synth.integers(1400 + vid, "Ai", M, K); Bi = synth.integers(1400 + vid, "Bi", K, N)
         check_against_oracle(Ai, Bi, None, dtype=F32, act=synth.ACT_NONE, layout=0, variant=vid, exact=True)
+
+
+def test_bf16_output_rounding_ties_and_specials():
+    # A = 0, so z = bias exactly: the stored bf16 must be the nearest-even rounding of the fp32 bias,
+    # including exact ties, values just off a tie, subnormals of bf16 and the overflow threshold
+    rng = np.random.default_rng(9)
+    base = synth.bf16_bits_to_f32(rng.integers(0x0080, 0x7F00, size=2048, dtype=np.uint16)).astype(np.float64)
+    step = np.abs(base) * 2.0 ** -8                       # half a bf16 step or a quarter, by mantissa parity
+    vals = np.concatenate([base + step, base - step, base + step * (1 + 2.0 ** -10), base + step * (1 - 2.0 ** -10),
+                           -(base + step), [0.0, 1e-40, -1e-40, 3.3895e38, 3.39e38, -3.4e38, 65504.0]])
+    bias = vals.astype(np.float32)
+    N = (bias.size + 7) // 8 * 8
+    bias = np.concatenate([bias, np.zeros(N - bias.size, dtype=np.float32)])
+    M, K = 40, 64
+    A = np.zeros((M, K), dtype=np.float32); B = np.zeros((K, N), dtype=np.float32)
+    for vid, name in all_variants():
+        if "bf16_rr" not in name and not name.startswith("generic"):
+            continue
+        Y, _, Cd = run_gpu(store(A, BF16), store(B, BF16), bias, 1, M, N, K, BF16, synth.ACT_NONE, 0, variant=vid)
+        from gpu_harness import to_host
+        got = to_host(Cd)[0]
+        want = oracle.bf16_from_double(bias.astype(np.float64))
+        bad = np.argwhere(got != np.broadcast_to(want, got.shape))
+        assert bad.size == 0, (name, [(float(bias[j]), hex(int(got[i, j])), hex(int(want[j]))) for i, j in bad[:6]])
