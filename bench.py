@@ -31,6 +31,27 @@ BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_r
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma"}
 DTYPE_NAME = {0: "f32", 1: "bf16"}
 
+# HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# passes (KiB per dispatch, scaled by what the same counters read for the library's 1 GiB copy
+# kernel: FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000; summaries under profiles/).  An entry is only
+# reported while the kernel sources still hash to the value recorded with it.
+TRAFFIC = {
+    ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk4_cg2_nt1_split0"):
+        {"bytes": int((528467 * 2.0 + 4096 + 2106.13 * 2.0 + 1024) * 1024), "src": "bad5c786d0fff247"},
+    ("c4_bf16_8192_silu", "direct_bf16_rr_256x256_w2x4"):
+        {"bytes": int((1.05111e6 * 2.0 + 131072) * 1024), "src": "bad5c786d0fff247"},
+}
+
+
+def kernel_source_hash():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2602_12305_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(d, "*.hip")) + glob.glob(os.path.join(d, "*.hpp")) + glob.glob(os.path.join(d, "*.inc"))):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -41,6 +62,9 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads")
     ap.add_argument("--variant", type=int, default=-1, help="force one kernel variant (default: dispatcher)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-gib", type=float, default=0.0,
+                    help="instead of a workload, time the library's plain copy kernel on this many GiB "
+                         "(HBM ceiling and calibration of the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on one GPU; there is no multi-GPU path to time (use --gpus 1)",
@@ -58,6 +82,26 @@ def main():
 
     def to_dev(x):
         return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+
+    if args.copy_gib > 0:
+        nbytes = int(args.copy_gib * (1 << 30)) // 16 * 16
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for _ in range(args.warmup):
+            ob.optiml_copy_bytes(dst, src, nbytes)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            ob.optiml_copy_bytes(dst, src, nbytes)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"metric": "GB/s of a plain device copy (bytes read + bytes written)", "unit": "GB/s",
+                          "value": round(2 * nbytes / (ms * 1e-3) / 1e9, 1), "bytes_read": nbytes,
+                          "bytes_written": nbytes, "ms_per_step": round(ms, 5), "steps": args.steps,
+                          "frac_of_8TBs": round(2 * nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}))
+        return
 
     def time_workload(name, steps, warmup):
         w = synth.make_workload(name)
@@ -95,12 +139,14 @@ def main():
         gbs = w.algorithmic_bytes / (kernel_ms * 1e-3) / 1e9
         tfl = w.flops / (kernel_ms * 1e-3) / 1e12
         bound = BOUND[name]
+        tr = TRAFFIC.get((name, ob.optiml_variant_name(vid)))
+        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash() else None
         roof = {"bound": bound,
                 "achieved": round(gbs if bound == "hbm" else tfl, 3),
                 "peak": PEAK_HBM_GBS if bound == "hbm" else PEAK_TFLOPS[w.dtype],
                 "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
                 "frac": round((gbs / PEAK_HBM_GBS) if bound == "hbm" else (tfl / PEAK_TFLOPS[w.dtype]), 4),
-                "traffic": None,
+                "traffic": traffic,
                 "kernel": ob.optiml_variant_name(vid),
                 "kernel_ms": round(kernel_ms, 5)}
         res = {"workload": name, "variant": ob.optiml_variant_name(vid), "ms_per_step": round(ms, 5),

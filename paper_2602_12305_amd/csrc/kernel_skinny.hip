@@ -287,9 +287,9 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
 const Variant *skinny_variants()
 {
     static const Variant v[kNumSkinnyVariants] = {
-        SKINNY(1, 8, 1, 0, 1),  SKINNY(1, 8, 1, 1, 1),  SKINNY(1, 16, 1, 0, 1), SKINNY(1, 4, 1, 0, 2),
-        SKINNY(1, 4, 1, 0, 0),  SKINNY(2, 4, 1, 0, 0),  SKINNY(4, 2, 1, 0, 0),  SKINNY(4, 1, 1, 0, 0),
-        SKINNY(1, 4, 2, 0, 0),  SKINNY(2, 4, 2, 0, 0),  SKINNY(1, 8, 2, 0, 1),  SKINNY(4, 4, 1, 1, 0),
+        SKINNY(1, 4, 2, 1, 0),  SKINNY(1, 4, 2, 0, 0),  SKINNY(4, 1, 1, 1, 0),  SKINNY(2, 4, 1, 1, 0),
+        SKINNY(1, 8, 1, 1, 1),  SKINNY(1, 8, 1, 0, 1),  SKINNY(1, 16, 1, 1, 1), SKINNY(1, 4, 1, 1, 2),
+        SKINNY(4, 4, 1, 1, 0),  SKINNY(2, 2, 2, 1, 0),  SKINNY(8, 1, 1, 1, 0),  SKINNY(4, 1, 2, 1, 0),
     };
     return v;
 }
