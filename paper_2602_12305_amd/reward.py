@@ -20,7 +20,8 @@ HBM bytes, inst = executed instructions.
 
 Readings where the paper is silent: alpha_t = 0.40 (its "time mixing" entry) is used as
 the tanh sensitivity; beta_time = 1, beta_proxy = 0.25, beta_llm = 0 (no LLM judge here);
-all guardrail lambdas = 1; rho_max = 256 architectural VGPRs; inflation threshold 1.5x.
+all guardrail lambdas = 1; rho_max = 512 registers per lane (the unified VGPR + AGPR file of
+a CDNA SIMD at one wave, as hipFuncGetAttributes counts them); inflation threshold 1.5x.
 A term that regresses is charged its regression penalty weight times the size of the
 regression (on top of the negative progress term).
 """
@@ -34,7 +35,7 @@ ALPHA_T = 0.40
 DELTA = 7.5
 BETA_TIME, BETA_PROXY, BETA_LLM = 1.0, 0.25, 0.0
 LAMBDA_SPILL = LAMBDA_REGS = LAMBDA_WORK = 1.0
-RHO_MAX = 256
+RHO_MAX = 512
 INFLATION = 1.5
 
 # progress weights: sm, dram, tex, l1, dram_bytes, inst

@@ -50,11 +50,11 @@ def test_clip_and_missing_metrics():
 def test_guardrails_and_rejection():
     base = R.Profile(1.0, dram_bytes=100, inst=100, regs=64, scratch_bytes=0)
     assert R.guard_penalty(base, R.Profile(1.0, scratch_bytes=16)) == 1.0
-    assert R.guard_penalty(base, R.Profile(1.0, regs=257)) == 1.0
-    assert R.guard_penalty(base, R.Profile(1.0, regs=256)) == 0.0
+    assert R.guard_penalty(base, R.Profile(1.0, regs=513)) == 1.0
+    assert R.guard_penalty(base, R.Profile(1.0, regs=512)) == 0.0
     assert R.guard_penalty(base, R.Profile(1.0, dram_bytes=151)) == 1.0
     assert R.guard_penalty(base, R.Profile(1.0, dram_bytes=150, inst=150)) == 0.0
-    assert R.guard_penalty(base, R.Profile(1.0, dram_bytes=151, inst=151, regs=300, scratch_bytes=4)) == 3.0
+    assert R.guard_penalty(base, R.Profile(1.0, dram_bytes=151, inst=151, regs=600, scratch_bytes=4)) == 3.0
     assert R.total_reward(base, R.Profile(0.5, correct=False)) == -math.inf
     assert not R.keep(base, R.Profile(0.995)) and not R.keep(base, R.Profile(0.5, correct=False))
     # a faster but spilling candidate scores below a slightly slower clean one
