@@ -1,0 +1,375 @@
+// bf16 MFMA tile kernel with a ring of small LDS stages fed by direct global->LDS loads:
+// 256x256 C block, 8 waves (2 x 4, wave tile 128 x 64), k-tiles of 32, NS stages of 32 KiB.
+//
+// Why a ring.  The two-stage kernel of kernel_tile_direct.hpp has at most one 64 KiB tile in
+// flight per CU while it multiplies the other, and measurement shows its load path alone
+// (L2 -> LDS, about a microsecond of latency under load) takes longer than its MFMAs.  With
+// NS stages of half the depth, NS-2 stages are in flight while one is multiplied and one is
+// being released: 64 KiB (NS = 4) or 96 KiB (NS = 5) in flight at the same LDS footprint per
+// byte in use, at the price of a barrier every 32 instead of every 64 k.
+//
+// Per k-tile t (stage t % NS):   wait until at most (NS-2) stages' worth of this wave's loads
+// are outstanding (loads complete in order, so tile t has landed); barrier (everybody's part of
+// tile t has landed and everybody has finished tile t-1); start the loads of tile t+NS-1 into
+// the stage tile t-1 occupied; multiply tile t.  Past the end the loads re-fetch the last tile
+// (in bounds, never read) so that the wait counts stay uniform.
+//
+// Each stage is its own __shared__ array and each step is an inlined function with
+// restrict-qualified stage pointers: that is what lets the compiler prove that the in-flight DMA
+// writes cannot touch the stage being read, so it does not drain the loads before every
+// fragment read.
+//
+// LDS formats.  A (and column-major B): 256 rows x 64 bytes, 16-byte chunk c of row r at
+// r*64 + ((c ^ ((r >> 2) & 3)) << 4): sixteen consecutive rows at one logical chunk cover the 64
+// banks once.  Row-major B: 32 k-rows x 512 bytes, chunk c of row k at k*512 + ((c ^ 2(k&3)) << 4),
+// read with ds_read_b64_tr_b16 (see kernel_tile_direct.hpp for its lane layout).
+#pragma once
+#include "common.hpp"
+#include "epilogue.hpp"
+
+namespace optiml {
+namespace ring {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+struct Params {
+    int64_t M, N, K, batch;
+    const char *A; int64_t lda, strideA;
+    const char *B; int64_t ldb, strideB;
+    const float *bias; int64_t strideBias;
+    char *C; int64_t ldc, strideC;
+    int64_t tiles_m, tiles_n;
+    int act;
+};
+
+template <int NS_, bool B_KC_>
+struct Cfg {
+    static constexpr int NS = NS_;
+    static constexpr bool B_KC = B_KC_;
+    static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = 4, NW = 8, THREADS = 512;
+    static constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
+    static constexpr int A_BYTES = BM * 64, B_BYTES = BN * 64, STAGE_BYTES = A_BYTES + B_BYTES;   // 32 KiB
+    static constexpr int A_INSTR = A_BYTES / 1024 / NW, B_INSTR = B_BYTES / 1024 / NW;            // 2 + 2
+    static constexpr int LOADS = A_INSTR + B_INSTR;                                               // per wave per stage
+    static_assert(NS >= 3 && NS <= 5, "ring depth");
+};
+
+#if defined(__HIP_DEVICE_COMPILE__)
+
+__device__ __forceinline__ const char *scalar_ptr(const char *q)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(q);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+
+// s_waitcnt vmcnt(N) lgkmcnt(0) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, lgkmcnt in 11:8,
+// expcnt in 6:4 left at its maximum): at most N of this wave's loads outstanding, and every LDS
+// read it issued has returned.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier without the fences of __syncthreads(): a workgroup-scope release fence makes
+// the compiler drain every outstanding LDS-DMA load (vmcnt(0)), which is exactly the prefetch
+// depth this kernel is built to keep.  What the barrier must order is covered explicitly: the
+// wait before it (this wave's part of the tile has landed in LDS and its LDS reads of the
+// previous tile have returned), and the empty asm statements keep the compiler from moving
+// memory operations across.
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <class C>
+struct Ctx {
+    uint32_t a_off[C::A_INSTR], b_off[C::B_INSTR];
+    int a_frag[2], tr_cb[C::TN];
+    int wave, a_wave, b_wave_kc, tr_row;
+};
+
+// One wave-wide LDS-DMA load: lane l copies 16 bytes from base + off(l) to LDS byte lds_addr + 16 l.
+// Written as assembly so that the loads stay out of the compiler's wait-count bookkeeping: it
+// cannot tell which ring stage a fragment read touches once more than a handful of these are
+// in flight, and then drains all of them (vmcnt(0)) in front of LDS reads.  The kernel counts
+// them itself (wait_vmcnt below).  base and lds_addr are wave-uniform.
+__device__ __forceinline__ void dma_load16(const char *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+template <class C>
+__device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
+                                            lds_char *__restrict__ dst)
+{
+    ga = scalar_ptr(ga);
+    gb = scalar_ptr(gb);
+    const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dst) + c.wave * 1024);
+#pragma unroll
+    for (int i = 0; i < C::A_INSTR; ++i) dma_load16(ga, c.a_off[i], d + i * C::NW * 1024);
+#pragma unroll
+    for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
+}
+
+// One k-tile of 32: see the file header for the order of events.
+template <class C>
+__device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
+                                          lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
+                                          floatx16 (&acc)[C::TN][C::TM])
+{
+    constexpr int TM = C::TM, TN = C::TN;
+    wait_vmcnt<(C::NS - 2) * C::LOADS>();
+    block_barrier();
+    issue_stage<C>(c, ga, gb, dma);
+    __builtin_amdgcn_sched_barrier(0);      // the loads go out before the tile is multiplied
+
+    const lds_char *sa = rd + c.a_wave;
+    const lds_char *sb = rd + C::A_BYTES;
+    uintx4 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[s][i] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(sa + i * 32 * 64 + c.a_frag[s]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (C::B_KC) {
+                fb[s][j] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(
+                    sb + c.b_wave_kc + j * 32 * 64 + c.a_frag[s]);
+            } else {
+                const lds_char *q0 = sb + (16 * s + c.tr_row) * (C::BN * 2) + c.tr_cb[j];
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(q0));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4 *)(q0 + 4 * (C::BN * 2)));
+                const uintx2 l2 = __builtin_bit_cast(uintx2, lo), h2 = __builtin_bit_cast(uintx2, hi);
+                fb[s][j] = uintx4{l2[0], l2[1], h2[0], h2[1]};
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[s][j]),
+                                                                    __builtin_bit_cast(bf16x8, fa[s][i]), acc[j][i], 0, 0, 0);
+}
+#endif
+
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // one array per ring stage (distinct objects: see the file header); unused ones cost nothing
+    __shared__ __attribute__((aligned(1024))) char st0[C::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char st1[C::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char st2[C::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char st3[C::NS > 3 ? C::STAGE_BYTES : 1024];
+    __shared__ __attribute__((aligned(1024))) char st4[C::NS > 4 ? C::STAGE_BYTES : 1024];
+    constexpr int TM = C::TM, TN = C::TN, NW = C::NW, NS = C::NS;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % C::WM, wn = wave / C::WM;
+
+    // workgroup -> tile: undo the round-robin over 8 XCDs, then bands of 8 tile rows
+    int64_t tile_id;
+    {
+        const int64_t total = p.tiles_m * p.tiles_n * p.batch;
+        const int64_t bid = blockIdx.x, x = bid & 7, loc = bid >> 3;
+        const int64_t q8 = total >> 3, r8 = total & 7;
+        tile_id = x * q8 + (x < r8 ? x : r8) + loc;
+    }
+    const int64_t per_batch = p.tiles_m * p.tiles_n;
+    const int64_t batch = tile_id / per_batch;
+    int64_t t = tile_id % per_batch;
+    constexpr int BAND = 8;
+    const int64_t band = t / (BAND * p.tiles_n), first = band * BAND;
+    const int64_t rows_in_band = p.tiles_m - first < BAND ? p.tiles_m - first : BAND;
+    t -= band * BAND * p.tiles_n;
+    const int64_t tile_m = first + t % rows_in_band, tile_n = t / rows_in_band;
+    const int64_t m0 = tile_m * C::BM, n0 = tile_n * C::BN;
+
+    const char *A = p.A + batch * p.strideA * 2;
+    const char *B = p.B + batch * p.strideB * 2;
+
+    Ctx<C> ctx;
+    ctx.wave = wave;
+    // A and column-major B: load q covers LDS rows 16q..16q+15; lane l fills row 16q + l/4, slot l%4
+#pragma unroll
+    for (int i = 0; i < C::A_INSTR; ++i) {
+        const int q = wave + i * NW, r = 16 * q + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        int64_t row = m0 + r;
+        row = row < p.M ? row : p.M - 1;
+        ctx.a_off[i] = (uint32_t)(row * p.lda * 2 + c * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < C::B_INSTR; ++i) {
+        const int q = wave + i * NW;
+        if constexpr (C::B_KC) {
+            const int r = 16 * q + (lane >> 2);
+            const int c = (lane & 3) ^ ((r >> 2) & 3);
+            int64_t row = n0 + r;
+            row = row < p.N ? row : p.N - 1;
+            ctx.b_off[i] = (uint32_t)(row * p.ldb * 2 + c * 16);
+        } else {
+            const int pidx = q * 64 + lane, k = pidx >> 5;          // 32 chunks per k-row
+            const int c = (pidx & 31) ^ (2 * (k & 3));
+            int64_t col = n0 + c * 8;
+            col = col + 8 <= p.N ? col : p.N - 8;
+            ctx.b_off[i] = (uint32_t)((k * p.ldb + col) * 2);
+        }
+    }
+    const int64_t b_step = C::B_KC ? 64 : 32 * p.ldb * 2;           // bytes per k-tile
+
+    floatx16 acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.0f;
+
+    const int frag_row = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) ctx.a_frag[s] = frag_row * 64 + (((2 * s + half) ^ ((frag_row >> 2) & 3)) << 4);
+    ctx.a_wave = wm * C::WTM * 64;
+    ctx.b_wave_kc = wn * C::WTN * 64;
+    const int g = lane >> 4, jj = lane & 15;
+    ctx.tr_row = 8 * (g >> 1) + (jj >> 2);
+    const int tr_col = wn * C::WTN + 16 * (g & 1) + 4 * (jj & 3);
+    const int tr_key = 2 * (jj >> 2);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = tr_col + 32 * j;
+        ctx.tr_cb[j] = (((col >> 3) ^ tr_key) << 4) + ((col & 7) << 1);
+    }
+
+    lds_char *stage[5] = {(lds_char *)st0, (lds_char *)st1, (lds_char *)st2, (lds_char *)st3, (lds_char *)st4};
+    const int64_t nk = p.K / 32, last = nk - 1;            // nk >= NS - 1
+    auto ga = [&](int64_t kt) { return A + (kt < last ? kt : last) * 64; };
+    auto gb = [&](int64_t kt) { return B + (kt < last ? kt : last) * b_step; };
+
+    // prologue: tiles 0 .. NS-2
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_stage<C>(ctx, ga(s), gb(s), stage[s]);
+
+    int64_t kt = 0;
+    for (; kt + NS <= nk; kt += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s], acc);
+    }
+    // the last nk % NS tiles, same stage order
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (kt + s < nk)
+            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s], acc);
+    wait_vmcnt<0>();
+    __syncthreads();                         // every load has landed, every wave is done with the stages
+
+    // Epilogue: bias, activation, bf16 conversion in registers; then each wave passes its tile
+    // through a private 32-row slab (128 bytes per row, 16-byte chunks XOR-swizzled by row >> 1)
+    // in stage 0 and stores whole 128-byte lines.  See kernel_tile_direct.hpp.
+    const int64_t mw = m0 + wm * C::WTM, nw = n0 + wn * C::WTN;
+    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
+    char *Cb = p.C + batch * p.strideC * 2;
+    lds_char *slab = (lds_char *)st0 + wave * 4096;
+    float bj[TN][4][4];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int64_t n = nw + 32 * j + 8 * gq + 4 * half;
+            if (bias && n + 3 < p.N) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(bias + n);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bj[j][gq][e] = v[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bj[j][gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
+            }
+        }
+    const int wkey = (frag_row >> 1) & 7;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
+                *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
+                    slab + frag_row * 128 + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
+                    uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
+            }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int id = q * 64 + lane, row = id >> 3, chunk = id & 7;
+            const uintx4 v = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(
+                slab + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+            const int64_t m = mw + 32 * i + row, n = nw + chunk * 8;
+            if (m < p.M && n < p.N) {
+                char *dst = Cb + (m * p.ldc + n) * 2;
+                if (n + 8 <= p.N) {
+                    *reinterpret_cast<uintx4 *>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < p.N)
+                            reinterpret_cast<unsigned short *>(dst)[e] = (unsigned short)(v[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+    }
+#endif
+}
+
+template <class C>
+bool supports(const Problem &p)
+{
+    if (p.dtype != DT_BF16 || p.a_col() || p.b_col() != C::B_KC) return false;
+    if (p.K < 32 * C::NS || p.K % 32 != 0 || !vector_friendly(p)) return false;
+    if (!C::B_KC && (p.N % 8 != 0)) return false;
+    const int64_t a_span = p.M * p.lda * 2, b_span = (C::B_KC ? p.N : 32) * p.ldb * 2 + p.N * 2;
+    if (a_span >= (int64_t(1) << 31) || b_span >= (int64_t(1) << 31)) return false;
+    const int64_t tiles = ((p.M + C::BM - 1) / C::BM) * ((p.N + C::BN - 1) / C::BN);
+    if (tiles <= 0 || p.batch > 0x7fffffffLL / tiles) return false;
+    return true;
+}
+
+template <class C>
+hipError_t launch(const Problem &p, hipStream_t stream)
+{
+    Params q;
+    q.M = p.M; q.N = p.N; q.K = p.K; q.batch = p.batch;
+    q.A = static_cast<const char *>(p.A); q.lda = p.lda; q.strideA = p.strideA;
+    q.B = static_cast<const char *>(p.B); q.ldb = p.ldb; q.strideB = p.strideB;
+    q.bias = p.bias; q.strideBias = p.strideBias;
+    q.C = static_cast<char *>(p.C); q.ldc = p.ldc; q.strideC = p.strideC;
+    q.tiles_m = (p.M + C::BM - 1) / C::BM;
+    q.tiles_n = (p.N + C::BN - 1) / C::BN;
+    q.act = p.act;
+    const int64_t total = q.tiles_m * q.tiles_n * p.batch;
+    hipLaunchKernelGGL(gemm_ring_kernel<C>, dim3((unsigned)total), dim3(C::THREADS), 0, stream, q);
+    return hipGetLastError();
+}
+
+}  // namespace ring
+}  // namespace optiml

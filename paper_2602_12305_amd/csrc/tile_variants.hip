@@ -6,17 +6,22 @@ namespace optiml {
 const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc();
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
 const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc();
+const Variant *kRing_bf16_rr(), *kRing_bf16_rc();
 
 namespace {
 struct Gather {
-    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit];
+    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit];
     Gather()
     {
         // the direct-to-LDS kernels come first: where they apply the dispatcher prefers them
-        constexpr int D = 2 * kDirectPerUnit;
+        constexpr int R = 2 * kRingPerUnit, D = R + 2 * kDirectPerUnit;
+        for (int i = 0; i < kRingPerUnit; ++i) {
+            v[i] = kRing_bf16_rr()[i];
+            v[kRingPerUnit + i] = kRing_bf16_rc()[i];
+        }
         for (int i = 0; i < kDirectPerUnit; ++i) {
-            v[i] = kDirect_bf16_rr()[i];
-            v[kDirectPerUnit + i] = kDirect_bf16_rc()[i];
+            v[R + i] = kDirect_bf16_rr()[i];
+            v[R + kDirectPerUnit + i] = kDirect_bf16_rc()[i];
         }
         const Variant *units[8] = {kTile_f32_rr(),  kTile_f32_rc(),  kTile_f32_cr(),  kTile_f32_cc(),
                                    kTile_bf16_rr(), kTile_bf16_rc(), kTile_bf16_cr(), kTile_bf16_cc()};
@@ -31,6 +36,6 @@ const Variant *tile_variants()
     static const Gather g;
     return g.v;
 }
-const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit;
+const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit;
 
 }  // namespace optiml

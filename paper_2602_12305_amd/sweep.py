@@ -47,7 +47,7 @@ def _args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--match", default="", help="only variants whose name contains this")
     ap.add_argument("--out", default="")
     ap.add_argument("--pmc", action="store_true", help="collect rocprofv3 counters per variant")

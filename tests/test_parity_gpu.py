@@ -36,6 +36,10 @@ def problem_for(name):
     """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
     if name.startswith("skinny"):
         return F32, 0, 13, 1000, 1224
+    if name.startswith("ring"):
+        _, dt, lay = name.split("_")[:3]
+        ns = int(name.rsplit("ns", 1)[1])
+        return BF16, LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
         return BF16, LAYOUT_OF[lay], 300, 392, 320          # K a multiple of 64
