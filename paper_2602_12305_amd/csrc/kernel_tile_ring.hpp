@@ -21,8 +21,11 @@
 //
 // LDS formats.  A (and column-major B): 256 rows x 64 bytes, 16-byte chunk c of row r at
 // r*64 + ((c ^ ((r >> 2) & 3)) << 4): sixteen consecutive rows at one logical chunk cover the 64
-// banks once.  Row-major B: 32 k-rows x 512 bytes, chunk c of row k at k*512 + ((c ^ 2(k&3)) << 4),
-// read with ds_read_b64_tr_b16 (see kernel_tile_direct.hpp for its lane layout).
+// banks once.  Row-major B: 32 k-rows x 512 bytes, chunk c of row k at k*512 + ((c ^ 4(k&3)) << 4):
+// the four k-rows that a 16-lane group of ds_read_b64_tr_b16 touches (see kernel_tile_direct.hpp
+// for its lane layout) sit in four different 64-byte bank groups, and so do those of the
+// neighbouring group that reads the next 16 columns (measured 165 B/clk against 128 B/clk with a
+// 32-byte shift per row).
 #pragma once
 #include "common.hpp"
 #include "epilogue.hpp"
@@ -48,16 +51,19 @@ struct Params {
     int act;
 };
 
-template <int NS_, bool B_KC_>
+template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4>
 struct Cfg {
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
-    static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = 4, NW = 8, THREADS = 512;
-    static constexpr int WTM = 128, WTN = 64, TM = 4, TN = 2;
+    static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier
+    static constexpr int AHEAD = PF_ ? NS_ - 3 : NS_ - 2;   // stages allowed in flight at the barrier
+    static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = WN_, NW = WM * WN, THREADS = 64 * NW;
+    static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     static constexpr int A_BYTES = BM * 64, B_BYTES = BN * 64, STAGE_BYTES = A_BYTES + B_BYTES;   // 32 KiB
-    static constexpr int A_INSTR = A_BYTES / 1024 / NW, B_INSTR = B_BYTES / 1024 / NW;            // 2 + 2
+    static constexpr int A_INSTR = A_BYTES / 1024 / NW, B_INSTR = B_BYTES / 1024 / NW;
     static constexpr int LOADS = A_INSTR + B_INSTR;                                               // per wave per stage
-    static_assert(NS >= 3 && NS <= 5, "ring depth");
+    static_assert(NS >= 3 && NS <= 5 && (!PF_ || NS_ >= 4), "ring depth");
+    static_assert(WN == 2 || WN == 4, "2 x 2 or 2 x 4 waves");
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -109,7 +115,7 @@ __device__ __forceinline__ void dma_load16(const char *base, uint32_t off, uint3
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(off), "s"(base), "s"(lds_addr)
-                 : "memory", "m0");
+                 : "m0");
 }
 
 template <class C>
@@ -125,49 +131,98 @@ __device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *__restr
     for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
 }
 
-// One k-tile of 32: see the file header for the order of events.
+template <class C>
+struct Frags {
+    uintx4 a[C::TM], b[C::TN];
+};
+
+// MFMA operands of k-step s (16 k) of the tile held in stage `rd`
+template <class C>
+__device__ __forceinline__ void load_frags(const Ctx<C> &c, const lds_char *rd, int s, Frags<C> &f)
+{
+    const lds_char *sa = rd + c.a_wave;
+    const lds_char *sb = rd + C::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+        f.a[i] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(sa + i * 32 * 64 + c.a_frag[s]);
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+        if constexpr (C::B_KC) {
+            f.b[j] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(
+                sb + c.b_wave_kc + j * 32 * 64 + c.a_frag[s]);
+        } else {
+            const lds_char *q0 = sb + (16 * s + c.tr_row) * (C::BN * 2) + c.tr_cb[j];
+            const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(q0));
+            const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) shortx4 *)(q0 + 4 * (C::BN * 2)));
+            const uintx2 l2 = __builtin_bit_cast(uintx2, lo), h2 = __builtin_bit_cast(uintx2, hi);
+            f.b[j] = uintx4{l2[0], l2[1], h2[0], h2[1]};
+        }
+    }
+}
+
+template <class C, int J0 = 0, int J1 = C::TN>
+__device__ __forceinline__ void mma_frags(const Frags<C> &f, floatx16 (&acc)[C::TN][C::TM])
+{
+#pragma unroll
+    for (int j = J0; j < J1; ++j)
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.b[j]),
+                                                                __builtin_bit_cast(bf16x8, f.a[i]), acc[j][i], 0, 0, 0);
+}
+
+// One k-tile of 32: see the file header for the order of events.  With C::PF the operands of
+// the tile's first k-step arrive in `f0` (fetched during the previous step) and the step ends by
+// fetching the next tile's first k-step from `nxt`, which the barrier at the top has made
+// visible one tile early: the MFMAs then start right after the barrier instead of waiting for
+// LDS.
 template <class C>
 __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
                                           lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
+                                          const lds_char *__restrict__ nxt, Frags<C> &f0,
                                           floatx16 (&acc)[C::TN][C::TM])
 {
-    constexpr int TM = C::TM, TN = C::TN;
-    wait_vmcnt<(C::NS - 2) * C::LOADS>();
+    wait_vmcnt<C::AHEAD * C::LOADS>();
     block_barrier();
+    Frags<C> f1;
+    if constexpr (C::PF) {
+        // The MFMAs of the first k-step start right behind the barrier (their operands are in
+        // f0 already); the loads of the new tile are issued in two batches between MFMA groups,
+        // where the matrix pipe has a backlog to hide the issue slots.
+        ga = scalar_ptr(ga);
+        gb = scalar_ptr(gb);
+        const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dma) + c.wave * 1024);
+        constexpr int NR = C::TM + (C::B_KC ? C::TN : 2 * C::TN), H = C::TN / 2, NMH = C::TM * H;
+        load_frags<C>(c, rd, 1, f1);
+        mma_frags<C, 0, H>(f0, acc);
+#pragma unroll
+        for (int i = 0; i < NMH; ++i) {            // second k-step's operands under these MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, (NR + NMH - 1) / NMH, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < C::A_INSTR; ++i) dma_load16(ga, c.a_off[i], d + i * C::NW * 1024);
+        mma_frags<C, H, C::TN>(f0, acc);
+#pragma unroll
+        for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
+        load_frags<C>(c, nxt, 0, f0);
+        mma_frags<C>(f1, acc);
+#pragma unroll
+        for (int i = 0; i < 2 * NMH; ++i) {        // next tile's first operands under these MFMAs
+            if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        return;
+    }
     issue_stage<C>(c, ga, gb, dma);
     __builtin_amdgcn_sched_barrier(0);      // the loads go out before the tile is multiplied
-
-    const lds_char *sa = rd + c.a_wave;
-    const lds_char *sb = rd + C::A_BYTES;
-    uintx4 fa[2][TM], fb[2][TN];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[s][i] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(sa + i * 32 * 64 + c.a_frag[s]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if constexpr (C::B_KC) {
-                fb[s][j] = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(
-                    sb + c.b_wave_kc + j * 32 * 64 + c.a_frag[s]);
-            } else {
-                const lds_char *q0 = sb + (16 * s + c.tr_row) * (C::BN * 2) + c.tr_cb[j];
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(q0));
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4 *)(q0 + 4 * (C::BN * 2)));
-                const uintx2 l2 = __builtin_bit_cast(uintx2, lo), h2 = __builtin_bit_cast(uintx2, hi);
-                fb[s][j] = uintx4{l2[0], l2[1], h2[0], h2[1]};
-            }
-        }
+    {
+        load_frags<C>(c, rd, 0, f0);
+        load_frags<C>(c, rd, 1, f1);
+        mma_frags<C>(f0, acc);
+        mma_frags<C>(f1, acc);
     }
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[s][j]),
-                                                                    __builtin_bit_cast(bf16x8, fa[s][i]), acc[j][i], 0, 0, 0);
 }
 #endif
 
@@ -229,7 +284,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             ctx.b_off[i] = (uint32_t)(row * p.ldb * 2 + c * 16);
         } else {
             const int pidx = q * 64 + lane, k = pidx >> 5;          // 32 chunks per k-row
-            const int c = (pidx & 31) ^ (2 * (k & 3));
+            const int c = (pidx & 31) ^ (4 * (k & 3));
             int64_t col = n0 + c * 8;
             col = col + 8 <= p.N ? col : p.N - 8;
             ctx.b_off[i] = (uint32_t)((k * p.ldb + col) * 2);
@@ -253,7 +308,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     const int g = lane >> 4, jj = lane & 15;
     ctx.tr_row = 8 * (g >> 1) + (jj >> 2);
     const int tr_col = wn * C::WTN + 16 * (g & 1) + 4 * (jj & 3);
-    const int tr_key = 2 * (jj >> 2);
+    const int tr_key = 4 * (jj >> 2);                        // 4 * (row & 3)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = tr_col + 32 * j;
@@ -268,28 +323,38 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     // prologue: tiles 0 .. NS-2
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) issue_stage<C>(ctx, ga(s), gb(s), stage[s]);
+    Frags<C> f0;
+    if constexpr (C::PF) {
+        wait_vmcnt<(NS - 2) * C::LOADS>();   // tile 0 has landed
+        block_barrier();
+        load_frags<C>(ctx, stage[0], 0, f0);
+    }
 
     int64_t kt = 0;
     for (; kt + NS <= nk; kt += NS) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s], acc);
+            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
+                         stage[(s + 1) % NS], f0, acc);
     }
     // the last nk % NS tiles, same stage order
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (kt + s < nk)
-            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s], acc);
+            ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
+                         stage[(s + 1) % NS], f0, acc);
     wait_vmcnt<0>();
     __syncthreads();                         // every load has landed, every wave is done with the stages
 
     // Epilogue: bias, activation, bf16 conversion in registers; then each wave passes its tile
-    // through a private 32-row slab (128 bytes per row, 16-byte chunks XOR-swizzled by row >> 1)
+    // through a private 32-row slab (WTN*2 bytes per row, 16-byte chunks XOR-swizzled by the row)
     // in stage 0 and stores whole 128-byte lines.  See kernel_tile_direct.hpp.
     const int64_t mw = m0 + wm * C::WTM, nw = n0 + wn * C::WTN;
     const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
     char *Cb = p.C + batch * p.strideC * 2;
-    lds_char *slab = (lds_char *)st0 + wave * 4096;
+    constexpr int CPR = C::WTN / 8, PITCH = C::WTN * 2;       // 16-byte chunks and bytes per slab row
+    constexpr int READS = 32 * CPR / 64;
+    lds_char *slab = (lds_char *)st0 + wave * (32 * PITCH);  // NW * 32 * PITCH = 32 KiB = one stage
     float bj[TN][4][4];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -305,7 +370,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
                 for (int e = 0; e < 4; ++e) bj[j][gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
             }
         }
-    const int wkey = (frag_row >> 1) & 7;
+    auto slab_key = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
+    const int wkey = slab_key(frag_row);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -316,14 +382,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
-                    slab + frag_row * 128 + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
+                    slab + frag_row * PITCH + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
                     uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
             }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int id = q * 64 + lane, row = id >> 3, chunk = id & 7;
+        for (int q = 0; q < READS; ++q) {
+            const int id = q * 64 + lane, row = id / CPR, chunk = id % CPR;
             const uintx4 v = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(
-                slab + row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4));
+                slab + row * PITCH + ((chunk ^ slab_key(row)) << 4));
             const int64_t m = mw + 32 * i + row, n = nw + chunk * 8;
             if (m < p.M && n < p.N) {
                 char *dst = Cb + (m * p.ldc + n) * 2;

@@ -38,7 +38,7 @@ def problem_for(name):
         return F32, 0, 13, 1000, 1224
     if name.startswith("ring"):
         _, dt, lay = name.split("_")[:3]
-        ns = int(name.rsplit("ns", 1)[1])
+        ns = int(name.rsplit("ns", 1)[1][0])
         return BF16, LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
