@@ -45,6 +45,28 @@ __device__ __forceinline__ float apply_act(float z, int act)
     }
 }
 
+// The same activations for results that are rounded to bf16 (relative step 2^-8): the
+// exponential is the bare v_exp_f32 of -x*log2(e), whose argument rounding costs at most
+// 6e-8*|x| of relative error, five orders below the output format's resolution.
+__device__ __forceinline__ float sigmoid_bf16out(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.44269502162933349609375f));
+}
+
+__device__ __forceinline__ float apply_act_bf16out(float z, int act)
+{
+    switch (act) {
+    case ACT_RELU:
+        return z > 0.0f ? z : 0.0f;
+    case ACT_SILU:
+        return z * sigmoid_bf16out(z);
+    case ACT_GELU_TANH:
+        return z * sigmoid_bf16out(1.5957691216057308f * fmaf(0.044715f * z * z, z, z));
+    default:
+        return z;
+    }
+}
+
 // fp32 -> bf16 bits, round to nearest even; NaN stays a (quiet) NaN
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
 {

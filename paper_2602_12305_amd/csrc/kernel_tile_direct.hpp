@@ -307,7 +307,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
             for (int gq = 0; gq < 4; ++gq) {
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
+                for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (32 * j + 8 * gq + 4 * half) * 2) =
                     uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};

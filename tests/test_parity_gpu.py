@@ -277,7 +277,7 @@ def test_bf16_output_rounding_ties_and_specials():
     bias = vals.astype(np.float32)
     N = (bias.size + 7) // 8 * 8
     bias = np.concatenate([bias, np.zeros(N - bias.size, dtype=np.float32)])
-    M, K = 40, 64
+    M, K = 40, 192
     A = np.zeros((M, K), dtype=np.float32); B = np.zeros((K, N), dtype=np.float32)
     for vid, name in all_variants():
         if "bf16_rr" not in name and not name.startswith("generic"):
