@@ -34,22 +34,23 @@ DTYPE_NAME = {0: "f32", 1: "bf16"}
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB per dispatch, scaled by what the same counters read for the library's 1 GiB copy
 # kernel: FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000; summaries under profiles/).  An entry is only
-# reported while the kernel sources still hash to the value recorded with it.
+# reported while the sources of that kernel still hash to the value recorded with it.
+SKINNY_SRC = ("kernel_skinny.hip", "epilogue.hpp", "common.hpp")
+RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "epilogue.hpp", "common.hpp")
 TRAFFIC = {
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk4_cg2_nt1_split0"):
-        {"bytes": int((528467 * 2.0 + 4096 + 2106.13 * 2.0 + 1024) * 1024), "src": "bad5c786d0fff247"},
-    ("c4_bf16_8192_silu", "direct_bf16_rr_256x256_w2x4"):
-        {"bytes": int((1.05111e6 * 2.0 + 131072) * 1024), "src": "bad5c786d0fff247"},
+        {"bytes": int((528467 * 2.0 + 4096 + 2106.13 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "d3d0d3646d1ca64d"},
+    ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
+        {"bytes": int((791064 * 2.0 + 131072) * 1024), "files": RING_SRC, "src": "6d62aa854c8665b7"},
 }
 
 
-def kernel_source_hash():
-    import glob
+def kernel_source_hash(files):
     import hashlib
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2602_12305_amd", "csrc")
-    for f in sorted(glob.glob(os.path.join(d, "*.hip")) + glob.glob(os.path.join(d, "*.hpp")) + glob.glob(os.path.join(d, "*.inc"))):
-        h.update(open(f, "rb").read())
+    for f in files:
+        h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -140,7 +141,7 @@ def main():
         tfl = w.flops / (kernel_ms * 1e-3) / 1e12
         bound = BOUND[name]
         tr = TRAFFIC.get((name, ob.optiml_variant_name(vid)))
-        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash() else None
+        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash(tr["files"]) else None
         roof = {"bound": bound,
                 "achieved": round(gbs if bound == "hbm" else tfl, 3),
                 "peak": PEAK_HBM_GBS if bound == "hbm" else PEAK_TFLOPS[w.dtype],
