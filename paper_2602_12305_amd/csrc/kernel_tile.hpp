@@ -218,6 +218,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.0f;
 
+    // fp32 only: sums of the current block of k-tiles
+    constexpr int FLUSH = 4;
+    constexpr bool F32 = C::dt == DT_F32;
+    floatx16 part[F32 ? TN : 1][F32 ? TM : 1];
+
     // per-lane fragment addressing: row lane%32 of a 32-row fragment, chunk (2s + lane/32) ^ ((row >> 1) & 7)
     const int frag_row = lane & 31, half = lane >> 5;
     int frag_off[4];
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
     }
     __syncthreads();
 
-    for (int64_t kt = 0; kt < nk; ++kt) {
+    auto k_tile = [&](int64_t kt) {
         const char *cur = lds + (kt & 1) * C::STAGE_BYTES;
         char *nxt = lds + ((kt + 1) & 1) * C::STAGE_BYTES;
         const bool more = kt + 1 < nk;
@@ -270,11 +275,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                                                                             acc[j][i], 0, 0, 0);
             }
         } else {
-            // fp32: the 32 k of this tile are summed into fresh accumulators (two independent
-            // MFMA chains at a time) and then added to the running sums on the vector ALU.
-            // Blocked summation keeps the rounding error of a long k loop near
-            // sqrt(K * 32) * 2^-24 instead of K * 2^-24 relative to the terms' size.
-            static_assert(C::dt != DT_F32 || TM % 2 == 0, "fp32 path pairs MFMA tiles along m");
+            // fp32: k-tiles are summed into a second accumulator set that is added to the
+            // running sums on the vector ALU every FLUSH k-tiles (128 k) and cleared.  Blocked
+            // summation keeps the rounding error of a long k loop near sqrt(K * 128) * 2^-24
+            // instead of K * 2^-24 relative to the terms' size; the additions cost about 5 % of
+            // a block's MFMA time.
             uintx4 fa[4][TM], fb[4][TN];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
@@ -286,23 +291,16 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                     fb[s][j] = *reinterpret_cast<const uintx4 *>(b_base + j * 32 * 128 + frag_off[s]);
             }
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int i = 0; i < TM; i += 2) {
-                    floatx16 t0, t1;
+                for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) { t0[r] = 0.0f; t1[r] = 0.0f; }
+                    for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int s = 0; s < 4; ++s)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float b = __uint_as_float(fb[s][j][e]);
-                            t0 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, __uint_as_float(fa[s][i][e]), t0, 0, 0, 0);
-                            t1 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, __uint_as_float(fa[s][i + 1][e]), t1, 0, 0, 0);
-                        }
-                    acc[j][i] += t0;
-                    acc[j][i + 1] += t1;
-                }
+                        for (int i = 0; i < TM; ++i)
+                            part[j][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[s][j][e]),
+                                                                              __uint_as_float(fa[s][i][e]),
+                                                                              part[j][i], 0, 0, 0);
         }
 
         if (more) {
@@ -310,6 +308,25 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
             lb.store(nxt + C::A_BYTES, tid);
         }
         __syncthreads();
+    };
+
+    if constexpr (F32) {
+        for (int64_t kb = 0; kb < nk; kb += FLUSH) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) part[j][i][r] = 0.0f;
+            const int64_t ke = kb + FLUSH < nk ? kb + FLUSH : nk;
+            for (int64_t kt = kb; kt < ke; ++kt) k_tile(kt);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[j][i] += part[j][i];
+        }
+    } else {
+        for (int64_t kt = 0; kt < nk; ++kt) k_tile(kt);
     }
 
     // epilogue: register r of acc[j][i] is Z[m][n], m = mw + 32 i + lane%32,
