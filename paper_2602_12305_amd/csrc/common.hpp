@@ -45,5 +45,6 @@ const Variant *tile_variants();            extern const int kNumTileVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
 constexpr int kRingPerUnit = 6;            // ring-of-stages bf16 kernels per B layout
+constexpr int kRingF32PerUnit = 3;         // ring-of-stages fp32 kernels per B layout
 
 }  // namespace optiml

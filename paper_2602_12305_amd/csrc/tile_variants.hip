@@ -7,14 +7,19 @@ const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc()
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
 const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc();
 const Variant *kRing_bf16_rr(), *kRing_bf16_rc();
+const Variant *kRing_f32_rr(), *kRing_f32_rc();
 
 namespace {
 struct Gather {
-    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit];
+    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit + 2 * kRingF32PerUnit];
     Gather()
     {
         // the direct-to-LDS kernels come first: where they apply the dispatcher prefers them
-        constexpr int R = 2 * kRingPerUnit, D = R + 2 * kDirectPerUnit;
+        constexpr int R = 2 * kRingPerUnit, F = R + 2 * kDirectPerUnit, D = F + 2 * kRingF32PerUnit;
+        for (int i = 0; i < kRingF32PerUnit; ++i) {
+            v[F + i] = kRing_f32_rr()[i];
+            v[F + kRingF32PerUnit + i] = kRing_f32_rc()[i];
+        }
         for (int i = 0; i < kRingPerUnit; ++i) {
             v[i] = kRing_bf16_rr()[i];
             v[kRingPerUnit + i] = kRing_bf16_rc()[i];
@@ -36,6 +41,6 @@ const Variant *tile_variants()
     static const Gather g;
     return g.v;
 }
-const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit;
+const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit + 2 * kRingF32PerUnit;
 
 }  // namespace optiml

@@ -39,6 +39,10 @@ def problem_for(name):
     if name.startswith("ring"):
         _, dt, lay = name.split("_")[:3]
         ns = int(name.rsplit("ns", 1)[1][0])
+        if dt == "f32":
+            # two whole summation blocks, one partial block, and a tail shorter than the ring
+            nk = 2 * (8 // ns) * ns + ns + (ns - 1)
+            return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
         return BF16, LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
