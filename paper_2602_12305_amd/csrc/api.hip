@@ -127,6 +127,19 @@ bool vector_friendly(const Problem &p)
     return true;
 }
 
+int compute_units()
+{
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
 hipError_t workspace(size_t bytes, void **ptr)
 {
     int dev = 0;

@@ -34,6 +34,9 @@ struct Variant {
 // every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks
 bool vector_friendly(const Problem &p);
 
+// number of compute units of the current device (256 if the query fails)
+int compute_units();
+
 // per-device scratch for split-K partial sums (grown on demand, never shrunk)
 hipError_t workspace(size_t bytes, void **ptr);
 
@@ -44,7 +47,7 @@ const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 12
 const Variant *tile_variants();            extern const int kNumTileVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
-constexpr int kRingPerUnit = 6;            // ring-of-stages bf16 kernels per B layout
+constexpr int kRingPerUnit = 8;            // ring-of-stages bf16 kernels per B layout (one-tile and persistent)
 constexpr int kRingF32PerUnit = 3;         // ring-of-stages fp32 kernels per B layout
 
 }  // namespace optiml

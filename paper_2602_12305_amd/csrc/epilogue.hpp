@@ -4,6 +4,8 @@
 // through the identity 0.5*(1 + tanh(u)) = sigmoid(2u) so that large |z| cannot
 // produce inf/inf.
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace optiml {
@@ -64,6 +66,21 @@ __device__ __forceinline__ float apply_act_bf16out(float z, int act)
         return z * sigmoid_bf16out(1.5957691216057308f * fmaf(0.044715f * z * z, z, z));
     default:
         return z;
+    }
+}
+
+// Calls f(std::integral_constant<int, ACT>{}) with the run-time activation code turned into a
+// compile-time constant.  The tile kernels wrap their whole epilogue in this: a switch per
+// output element compiles to a compare-and-branch chain per element (measured: 6.6 us per
+// 256x256 tile, more than the arithmetic), one switch per tile costs nothing.
+template <class F>
+__device__ __forceinline__ void dispatch_act(int act, F &&f)
+{
+    switch (act) {
+    case ACT_RELU: f(std::integral_constant<int, ACT_RELU>{}); break;
+    case ACT_SILU: f(std::integral_constant<int, ACT_SILU>{}); break;
+    case ACT_GELU_TANH: f(std::integral_constant<int, ACT_GELU_TANH>{}); break;
+    default: f(std::integral_constant<int, ACT_NONE>{}); break;
     }
 }
 

@@ -255,13 +255,15 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
         }
     }
     const int wkey = (frag_row >> 1) & 7;
+    dispatch_act(p.act, [&](auto act_tag) {
+    constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             floatx4 y;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[i][4 * gq + e] + bj[gq][e], p.act);
+            for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[i][4 * gq + e] + bj[gq][e], ACT);
             *reinterpret_cast<__attribute__((address_space(3))) floatx4 *>(
                 slab + frag_row * 128 + (((2 * gq + half) ^ wkey) << 4)) = y;
         }
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
             if (m < p.M && n < p.N) {
                 float *dst = reinterpret_cast<float *>(Cb) + m * p.ldc + n;
                 if (n + 4 <= p.N) {
-                    *reinterpret_cast<floatx4 *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(dst));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -283,6 +285,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
             }
         }
     }
+    });
 #endif
 }
 

@@ -334,6 +334,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
     const int64_t mw = m0 + wm * (C::BM / C::WM), nw = n0 + wn * (C::BN / C::WN);
     const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
     char *Cb = p.C + batch * p.strideC * ES;
+    dispatch_act(p.act, [&](auto act_tag) {
+    constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -358,7 +360,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                 if (m >= p.M) continue;
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * g + e] + bj[e], p.act);
+                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * g + e] + bj[e], ACT);
                 char *dst = Cb + (m * p.ldc + n) * ES;
                 if constexpr (C::dt == DT_F32) {
                     if (whole) {
@@ -383,6 +385,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                 }
             }
         }
+    });
 }
 
 // ---- host side -----------------------------------------------------------------------------

@@ -299,6 +299,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
                 for (int e = 0; e < 4; ++e) bj[j][gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
             }
         }
+    dispatch_act(p.act, [&](auto act_tag) {
+    constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
             for (int gq = 0; gq < 4; ++gq) {
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
+                for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], ACT);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (32 * j + 8 * gq + 4 * half) * 2) =
                     uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
@@ -330,6 +332,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
             }
         }
     }
+    });
 #endif
 }
 

@@ -177,13 +177,17 @@ __device__ __forceinline__ void mma_frags(const Frags<C> &f, floatx16 (&acc)[C::
 // fetching the next tile's first k-step from `nxt`, which the barrier at the top has made
 // visible one tile early: the MFMAs then start right after the barrier instead of waiting for
 // LDS.
-template <class C>
+// EXTRA: vector-memory operations of this wave, other than ring loads, that were issued after
+// the loads this step waits for and may still be outstanding (they complete in issue order, so
+// the count to wait for grows by that many).
+template <class C, int EXTRA = 0>
 __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
                                           lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
                                           const lds_char *__restrict__ nxt, Frags<C> &f0,
                                           floatx16 (&acc)[C::TN][C::TM])
 {
-    wait_vmcnt<C::AHEAD * C::LOADS>();
+    static_assert(C::AHEAD * C::LOADS + EXTRA <= 63, "vmcnt is a 6-bit counter");
+    wait_vmcnt<C::AHEAD * C::LOADS + EXTRA>();
     block_barrier();
     Frags<C> f1;
     if constexpr (C::PF) {
@@ -372,6 +376,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
         }
     auto slab_key = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
     const int wkey = slab_key(frag_row);
+    dispatch_act(p.act, [&](auto act_tag) {
+    constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             for (int gq = 0; gq < 4; ++gq) {
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], p.act);
+                for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], ACT);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
                     uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
@@ -394,7 +400,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             if (m < p.M && n < p.N) {
                 char *dst = Cb + (m * p.ldc + n) * 2;
                 if (n + 8 <= p.N) {
-                    *reinterpret_cast<uintx4 *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(dst));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
@@ -404,6 +410,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             }
         }
     }
+    });
 #endif
 }
 

@@ -96,6 +96,28 @@ def test_every_variant_batched_and_repeatable(vid, name):
         assert np.array_equal(Yb[0], Y1[b])
 
 
+# ---- L1: persistent kernels: more C tiles than CUs, so workgroups walk several tiles ----------
+@pytest.mark.parametrize("vid", variant_ids("ringp"))
+def test_persistent_variants_walk_several_tiles(vid):
+    """9 x (5 x 7) = 315 tiles of 256 x 256 on 256 CUs: some workgroups compute two tiles, in every
+    order of whole and edge tiles (M and N are ragged), with per-batch bias; then the same without a
+    bias on integer inputs (exact), where a tile computed from the wrong panel cannot hide."""
+    name = ob.optiml_variant_name(vid)
+    layout = LAYOUT_OF[name.split("_")[2]]
+    batch, M, N, K = 9, 1100, 1544, 224
+    A = synth.normal(700 + vid, "A", M, K, batch=batch); B = synth.normal(700 + vid, "B", K, N, batch=batch)
+    bias = synth.normal(700 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=BF16, act=synth.ACT_SILU, layout=layout, variant=vid)
+    check_against_oracle(A, B, bias, dtype=BF16, act=synth.ACT_GELU_TANH, layout=layout, variant=vid, ldc_pad=8)
+    Ai = synth.integers(710 + vid, "A", M, K, batch=batch); Bi = synth.integers(710 + vid, "B", K, N, batch=batch)
+    check_against_oracle(Ai, Bi, None, dtype=BF16, act=synth.ACT_RELU, layout=layout, variant=vid, exact=True)
+    # all tiles whole, four per workgroup
+    batch, M, N, K = 16, 2048, 2048, 192
+    Ai = synth.integers(720 + vid, "A", M, K, -2, 2, batch=batch); Bi = synth.integers(720 + vid, "B", K, N, -2, 2, batch=batch)
+    bi = synth.integers(720 + vid, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
+    check_against_oracle(Ai, Bi, bi, dtype=BF16, act=synth.ACT_NONE, layout=layout, variant=vid, exact=True)
+
+
 # ---- L1: dispatcher over seeded random shapes, all layouts / dtypes / acts / paddings --------
 def fuzz_cases():
     rng = np.random.default_rng(2602)
