@@ -68,6 +68,8 @@ int select(const Problem &p)
         if (p.M <= 16)
             for (int i = t.first_skinny; i < t.first_tile; ++i)
                 if (t.v[i]->supports(p)) return i;
+        for (int i = t.first_tile; i < (int)t.v.size(); ++i)
+            if (t.v[i]->prefers && t.v[i]->prefers(p) && t.v[i]->supports(p)) return i;
         int best = -1;
         int64_t best_blocks = -1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {

@@ -29,6 +29,9 @@ struct Variant {
     hipError_t (*launch)(const Problem &, hipStream_t);
     int bm, bn;   // C block computed by one workgroup (0, 0 where that does not apply)
     const void *kernel;   // host handle of the variant's main kernel, for hipFuncGetAttributes
+    // optional: true for problems on which this variant was measured faster than the ones
+    // before it in the table; the dispatcher asks these first
+    bool (*prefers)(const Problem &) = nullptr;
 };
 
 // every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks
@@ -47,7 +50,7 @@ const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 12
 const Variant *tile_variants();            extern const int kNumTileVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
-constexpr int kRingPerUnit = 8;            // ring-of-stages bf16 kernels per B layout (one-tile and persistent)
+constexpr int kRingPerUnit = 4;            // ring-of-stages bf16 kernels per B layout (three one-tile, one persistent)
 constexpr int kRingF32PerUnit = 3;         // ring-of-stages fp32 kernels per B layout
 
 }  // namespace optiml

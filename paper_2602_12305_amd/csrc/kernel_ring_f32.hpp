@@ -121,7 +121,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
     __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
     constexpr int TM = C::TM, NW = C::NW, NS = C::NS;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar
     const int wm = wave % C::WM, wn = wave / C::WM;
 
     // workgroup -> tile: undo the round-robin over 8 XCDs, then bands of 8 tile rows

@@ -242,7 +242,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     __shared__ __attribute__((aligned(1024))) char st4[C::NS > 4 ? C::STAGE_BYTES : 1024];
     constexpr int TM = C::TM, TN = C::TN, NW = C::NW, NS = C::NS;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar
     const int wm = wave % C::WM, wn = wave / C::WM;
 
     // workgroup -> tile: undo the round-robin over 8 XCDs, then bands of 8 tile rows
