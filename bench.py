@@ -37,11 +37,18 @@ DTYPE_NAME = {0: "f32", 1: "bf16"}
 # reported while the sources of that kernel still hash to the value recorded with it.
 SKINNY_SRC = ("kernel_skinny.hip", "epilogue.hpp", "common.hpp")
 RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "epilogue.hpp", "common.hpp")
+RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
+RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp",
+             "common.hpp")
 TRAFFIC = {
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk4_cg2_nt1_split0"):
-        {"bytes": int((528467 * 2.0 + 4096 + 2106.13 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "d3d0d3646d1ca64d"},
+        {"bytes": int((528466 * 2.0 + 4096 + 2106.12 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "7f7a1e1e851312e7"},
+    ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
+        {"bytes": int((385324 * 2.0 + 65536) * 1024), "files": RINGF_SRC, "src": "d98b0e728176c0b1"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((791064 * 2.0 + 131072) * 1024), "files": RING_SRC, "src": "6d62aa854c8665b7"},
+        {"bytes": int((790157 * 2.0 + 131097) * 1024), "files": RING_SRC, "src": "b153061e39510446"},
+    ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
+        {"bytes": int((67454.8 * 2.0 + 262576) * 1024), "files": RINGP_SRC, "src": "9edbaa53f6a244ed"},
 }
 
 
