@@ -56,10 +56,28 @@ int validate(const Problem &p)
 
 bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 
-// Preference order: the streaming split-K kernels for at most 16 rows; then the MFMA tile
-// kernels in table order (direct-to-LDS kernels before staged ones, large C blocks before
-// small) - the first whose grid gives every CU a workgroup, else the one with most
-// workgroups; then the fallback.
+// The streaming kernels re-read B once per 16 rows of A.  For more than 16 rows that is worth it
+// while the re-reads (from L2, about 8 TB/s measured at 1024^3) take less time than an MFMA tile
+// kernel needs when its 128x128 tiles cover only part of the chip (140 TFLOP/s when every CU has
+// a tile).  Measured: 256^3 8 us against 37 us, 1024^3 29-37 us against more than 60 us,
+// 256 x 2048 x 2048 32 us against 250 us; from 2048^3 on the tile kernel wins.
+bool streaming_beats_tiles(const Problem &p)
+{
+    if (p.dtype != DT_F32 || p.layout != 0) return false;
+    const double blocks16 = (double)((p.M + 15) / 16), batch = (double)p.batch;
+    const double t_stream = batch * blocks16 * (double)p.K * (double)p.N * 4.0 / 8e12;
+    const double tm = (double)((p.M + 127) / 128), tn = (double)((p.N + 127) / 128);
+    const double tiles = tm * tn * batch;
+    const double share = tiles < 256.0 ? tiles / 256.0 : 1.0;
+    const double t_tiles = 2.0 * tiles * 128.0 * 128.0 * (double)p.K / (140e12 * share);   // whole tiles are computed
+    return t_stream < t_tiles;
+}
+
+// Preference order: the streaming split-K kernels for at most 16 rows, and for small fp32
+// problems of more rows (without the non-temporal hint: B is meant to stay in L2); then the MFMA
+// tile kernels - one that declares a measured preference for the shape, else in table order
+// (direct-to-LDS kernels before staged ones) the first whose grid gives every CU a workgroup,
+// else the one with most workgroups; then the fallback.
 int select(const Problem &p)
 {
     const Table &t = table();
@@ -68,6 +86,8 @@ int select(const Problem &p)
         if (p.M <= 16)
             for (int i = t.first_skinny; i < t.first_tile; ++i)
                 if (t.v[i]->supports(p)) return i;
+        if (streaming_beats_tiles(p) && t.first_skinny + 1 < t.first_tile && t.v[t.first_skinny + 1]->supports(p))
+            return t.first_skinny + 1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i)
             if (t.v[i]->prefers && t.v[i]->prefers(p) && t.v[i]->supports(p)) return i;
         int best = -1;

@@ -1,4 +1,4 @@
-// Streaming kernels for at most 16 rows of A (fp32, A and B row-major).
+// Streaming kernels for 16 rows of A at a time (fp32, A and B row-major).
 //
 // With M <= 16 the contraction reads every element of B once and uses it for 16
 // multiply-adds: HBM bandwidth is the bound, and the whole design serves one
@@ -26,6 +26,11 @@
 // accumulators in LDS and are summed in wave order; with SPLIT > 1 the per-workgroup
 // sums go to a workspace [SPLIT][batch][16][N] and a second kernel adds them in
 // split order, then applies bias and activation.  No atomics anywhere.
+//
+// More than 16 rows.  grid.z also counts blocks of 16 rows of A and C: every block streams B
+// again (from L2), which only pays while the whole problem is small - a few hundred rows of a
+// B that fits L2 - and the MFMA tile kernels would leave most CUs idle (256^3: 16 workgroups
+// of the 64x64 tile kernel take 17 us, this path spreads the same work over 128).
 #include "common.hpp"
 #include "epilogue.hpp"
 
@@ -40,8 +45,8 @@ struct SkinnyParams {
     const float *B; int64_t ldb, strideB;
     const float *bias; int64_t strideBias;
     float *C; int64_t ldc, strideC;
-    float *partial;        // [split][batch][16][N] when split > 1
-    int64_t batch;
+    float *partial;        // [split][batch * row_blocks][16][N] when split > 1
+    int64_t batch, row_blocks;
     int split, act;
 };
 
@@ -99,7 +104,8 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave % WN, wk = wave / WN;
     const int q = lane >> 4, c = lane & 15;
-    const int64_t batch = blockIdx.z;
+    const int64_t zb = blockIdx.z, batch = zb / p.row_blocks, rb = zb % p.row_blocks;
+    const int64_t rows = p.M - 16 * rb < 16 ? p.M - 16 * rb : 16;       // rows of this block
     const int64_t nblock0 = (int64_t)blockIdx.x * COLS;
     const int64_t n0 = nblock0 + (int64_t)wn * CG * 64 + 4 * c;   // this lane's first column in group 0
 
@@ -108,9 +114,9 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
     const int64_t parts = (int64_t)p.split * WK, part = (int64_t)blockIdx.y * WK + wk;
     const int64_t s_begin = steps * part / parts, s_end = steps * (part + 1) / parts;
 
-    const float *A = p.A + batch * p.strideA;
+    const float *A = p.A + batch * p.strideA + 16 * rb * p.lda;
     const float *B = p.B + batch * p.strideB;
-    const bool a_row_valid = c < p.M;
+    const bool a_row_valid = c < rows;
     bool col_valid[CG];
 #pragma unroll
     for (int g = 0; g < CG; ++g) col_valid[g] = n0 + 64 * g < p.N;     // N % 4 == 0: whole vectors
@@ -179,13 +185,13 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
         __syncthreads();
     }
 
-    float *out = p.split > 1 ? p.partial + ((int64_t)blockIdx.y * p.batch + batch) * 16 * p.N
-                             : p.C + batch * p.strideC;
+    float *out = p.split > 1 ? p.partial + ((int64_t)blockIdx.y * p.batch * p.row_blocks + zb) * 16 * p.N
+                             : p.C + batch * p.strideC + 16 * rb * p.ldc;
     const int64_t out_ld = p.split > 1 ? p.N : p.ldc;
     const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
 
     auto finish = [&](int row, int64_t col, floatx4 z) {
-        if (row >= p.M || col >= p.N) return;
+        if (row >= rows || col >= p.N) return;
         if (p.split == 1) {
             floatx4 bj = bias ? *reinterpret_cast<const floatx4 *>(bias + col) : floatx4{0, 0, 0, 0};
 #pragma unroll
@@ -222,9 +228,11 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyParams p)
     const int64_t batch = blockIdx.y;
     if (idx >= p.M * n4) return;
     const int64_t row = idx / n4, col = 4 * (idx % n4);
+    const int64_t zb = batch * p.row_blocks + row / 16;
     floatx4 z = floatx4{0, 0, 0, 0};
     for (int s = 0; s < p.split; ++s)
-        z += *reinterpret_cast<const floatx4 *>(p.partial + (((int64_t)s * p.batch + batch) * 16 + row) * p.N + col);
+        z += *reinterpret_cast<const floatx4 *>(
+            p.partial + (((int64_t)s * p.batch * p.row_blocks + zb) * 16 + row % 16) * p.N + col);
     const floatx4 bj = p.bias ? *reinterpret_cast<const floatx4 *>(p.bias + batch * p.strideBias + col)
                               : floatx4{0, 0, 0, 0};
 #pragma unroll
@@ -234,8 +242,8 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyParams p)
 
 bool skinny_supports(const Problem &p)
 {
-    return p.dtype == DT_F32 && p.layout == 0 && p.M >= 1 && p.M <= 16 && p.K >= 4 && p.K % 4 == 0 &&
-           p.N % 4 == 0 && p.batch <= 65535 && vector_friendly(p);
+    return p.dtype == DT_F32 && p.layout == 0 && p.M >= 1 && p.K >= 4 && p.K % 4 == 0 &&
+           p.N % 4 == 0 && p.batch * ((p.M + 15) / 16) <= 65535 && vector_friendly(p);
 }
 
 template <int WN, int WK, int CG, bool NT, int SPLIT>
@@ -249,10 +257,11 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     sp.bias = p.bias; sp.strideBias = p.strideBias;
     sp.C = static_cast<float *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
     sp.batch = p.batch; sp.act = p.act;
+    sp.row_blocks = (p.M + 15) / 16;
     // SPLIT == 0: enough workgroups for about two per CU, but never ranges shorter than 256 rows
     int split = SPLIT;
     if (SPLIT == 0) {
-        const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch;
+        const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
         const int64_t by_grid = (512 + col_blocks - 1) / col_blocks;
         const int64_t by_k = p.K / (256 * WK) > 0 ? p.K / (256 * WK) : 1;
         split = (int)(by_grid < by_k ? by_grid : by_k);
@@ -263,11 +272,11 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     sp.partial = nullptr;
     if (split > 1) {
         void *ws = nullptr;
-        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * 16 * p.N, &ws);
+        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws);
         if (e != hipSuccess) return e;
         sp.partial = static_cast<float *>(ws);
     }
-    dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)p.batch);
+    dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
     hipLaunchKernelGGL((skinny_kernel<WN, WK, CG, NT>), grid, dim3(64 * WN * WK), 0, stream, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
@@ -283,7 +292,9 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     {"skinny_f32_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT, skinny_supports, \
      skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0, reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT>)}
 
-// The first entry is the dispatcher's choice; the rest are there for the sweep.
+// The first entry is the dispatcher's choice for at most 16 rows, the second (same shape, B
+// loaded without the non-temporal hint) its choice for small problems of more rows; the rest
+// are there for the sweep.
 const Variant *skinny_variants()
 {
     static const Variant v[kNumSkinnyVariants] = {

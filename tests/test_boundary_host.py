@@ -98,7 +98,10 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 4096, 4096, 4096, layout=1).startswith("ring_f32_rc_128x128")
     assert sel(1, 8192, 8192, 8192, dtype=1).startswith("ring_bf16_rr_256x256")
     assert sel(32, 2048, 2048, 512, dtype=1).startswith("ringp_bf16_rr_256x256")   # many short tiles: persistent
-    assert sel(1, 256, 256, 256).startswith("tile_f32_rr_64x64")         # too few blocks for larger tiles
+    assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
+    assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
+    assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays
+    assert sel(1, 256, 256, 256, layout=2).startswith("tile_f32_cr_64x64")   # too few blocks for larger tiles
     assert sel(1, 1024, 1024, 64, layout=3, dtype=1).startswith("tile_bf16_cc_")
     # K = 0, misaligned base, odd leading dimension, ragged contiguous extent -> guarded fallback
     assert sel(1, 64, 64, 0).startswith("generic")

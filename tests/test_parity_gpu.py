@@ -142,13 +142,13 @@ def test_dispatch_random_shapes(t, M, N, K, layout, dtype, act, pad, use_bias):
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("layout", [0, 1, 2, 3])
 def test_dispatch_aligned_multi_tile_shapes(dtype, layout):
-    # shapes the MFMA kernels take (aligned, multiples of 8), several tiles in both directions,
-    # K not a multiple of the k-tile
+    # shapes the fast kernels take (aligned, multiples of 8), several tiles in both directions,
+    # K not a multiple of the k-tile; small fp32 row-major shapes go to the streaming kernels
     for (M, N, K) in [(520, 264, 72), (264, 776, 328), (1032, 1048, 40)]:
         A = synth.normal(500, "A", M, K); B = synth.normal(500, "B", K, N); bias = synth.normal(500, "bias", 1, N)[0]
         v = ob.optiml_select_variant(1, M, N, K, 0x1000, A.shape[0] if layout & 2 else K, 0, 0x1000,
                                      K if layout & 1 else N, 0, 0x1000, 0, 0x1000, N, 0, layout, dtype, 2)
-        assert ob.optiml_variant_name(v).startswith("tile_")
+        assert not ob.optiml_variant_name(v).startswith("generic")
         check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout,
                              entry="ex")
 
@@ -278,6 +278,21 @@ def test_row_permutation_equivariance():
     Y, _, _ = run_gpu(store(A, F32), store(B, F32), None, 1, M, N, K, F32, synth.ACT_SILU, 0)
     Yp, _, _ = run_gpu(store(A[perm], F32), store(B, F32), None, 1, M, N, K, F32, synth.ACT_SILU, 0)
     assert e1(Yp[0], Y[0][perm]) <= 1e-6
+
+
+@pytest.mark.parametrize("vid", variant_ids("skinny"))
+def test_skinny_variants_with_blocks_of_16_rows(vid):
+    """M > 16: grid.z counts blocks of 16 rows (the last one ragged) times batches; K long enough
+    for the automatic grid split, so the partial sums of every block go through the workspace."""
+    batch, M, N, K = 2, 45, 264, 4160
+    A = synth.normal(800 + vid, "A", M, K, batch=batch); B = synth.normal(800 + vid, "B", K, N, batch=batch)
+    bias = synth.normal(800 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_GELU_TANH, layout=0, variant=vid, ldc_pad=4)
+    Ai = synth.integers(810 + vid, "A", M, K, batch=batch); Bi = synth.integers(810 + vid, "B", K, N, batch=batch)
+    check_against_oracle(Ai, Bi, None, dtype=F32, act=synth.ACT_RELU, layout=0, variant=vid, exact=True)
+    # one batch, few columns, short K: no grid split
+    A = synth.uniform(820 + vid, "A", 100, 64); B = synth.uniform(820 + vid, "B", 64, 36)
+    check_against_oracle(A, B, synth.uniform(820 + vid, "bias", 1, 36)[0], dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
 
 
 @pytest.mark.parametrize("vid", variant_ids("skinny"))
