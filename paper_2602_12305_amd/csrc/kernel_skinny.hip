@@ -1,306 +1,23 @@
-// Streaming kernels for 16 rows of A at a time (fp32, A and B row-major).
-//
-// With M <= 16 the contraction reads every element of B once and uses it for 16
-// multiply-adds: HBM bandwidth is the bound, and the whole design serves one
-// goal - keep many 128-bit loads of B in flight on every CU and touch each byte
-// of B exactly once.  The paper's own matmul trajectory names the same levers for
-// its memory-side bottleneck (appendix "How OptiML-X improves the kernel":
-// vectorised loads to cut transactions, reuse from on-chip storage); what is
-// specific to gfx950 here is that the 16 multiply-adds per element go to the
-// matrix pipe (v_mfma_f32_16x16x4_f32: M = 16 is exactly one MFMA tile), which
-// leaves the vector ALUs to address generation.
-//
-// Work split.  A workgroup is WN x WK waves.  Along n a wave owns CG groups of 64
-// columns; along k the WK waves of a workgroup, times SPLIT workgroups (grid.y),
-// own contiguous ranges of 16-row "super-steps".  Lane (q = lane/16, c = lane%16)
-// loads, per super-step at k0:
-//     A[c][k0+4q .. k0+4q+3]                        one 128-bit load (L2 resident)
-//     B[k0+4q+t][n0 + 64g + 4c .. +3], t = 0..3     four 128-bit loads per group g
-// MFMA number (t, cc) multiplies A-register component t with component cc of B load
-// t: lane group q supplies k = k0+4q+t on both sides, and output column j = c stands
-// for n = n0 + 64g + 4c + cc.  Accumulator (g, cc) register r of lane (q, c) is then
-// Z[4q + r][n0 + 64g + 4c + cc]: four consecutive n per lane, stored as one 128-bit
-// vector.
-//
-// Reduction over k is deterministic: the WK waves of a workgroup leave their
-// accumulators in LDS and are summed in wave order; with SPLIT > 1 the per-workgroup
-// sums go to a workspace [SPLIT][batch][16][N] and a second kernel adds them in
-// split order, then applies bias and activation.  No atomics anywhere.
-//
-// More than 16 rows.  grid.z also counts blocks of 16 rows of A and C: every block streams B
-// again (from L2), which only pays while the whole problem is small - a few hundred rows of a
-// B that fits L2 - and the MFMA tile kernels would leave most CUs idle (256^3: 16 workgroups
-// of the 64x64 tile kernel take 17 us, this path spreads the same work over 128).
-#include "common.hpp"
-#include "epilogue.hpp"
+// Table of the streaming (skinny-M) kernel variants; the kernels are in kernel_skinny.hpp.
+#include "kernel_skinny.hpp"
 
 namespace optiml {
-namespace {
-
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-struct SkinnyParams {
-    int64_t M, N, K;
-    const float *A; int64_t lda, strideA;
-    const float *B; int64_t ldb, strideB;
-    const float *bias; int64_t strideBias;
-    float *C; int64_t ldc, strideC;
-    float *partial;        // [split][batch * row_blocks][16][N] when split > 1
-    int64_t batch, row_blocks;
-    int split, act;
-};
-
-// SS = super-steps (of 16 k) per pipelined batch of loads; two batches are live at a time
-
-template <int CG, int SS>
-struct Stage {
-    floatx4 a[SS];
-    floatx4 b[SS][CG][4];
-};
-
-template <int CG, int SS, bool NT>
-__device__ __forceinline__ void load_stage(Stage<CG, SS> &st, const float *a_ptr, const float *b_ptr, int64_t ldb,
-                                           bool a_valid, const bool (&col_valid)[CG])
-{
-#pragma unroll
-    for (int s = 0; s < SS; ++s) {
-        st.a[s] = a_valid ? *reinterpret_cast<const floatx4 *>(a_ptr + 16 * s) : floatx4{0, 0, 0, 0};
-#pragma unroll
-        for (int g = 0; g < CG; ++g)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const floatx4 *src = reinterpret_cast<const floatx4 *>(b_ptr + (16 * s + t) * ldb + 64 * g);
-                if (col_valid[g])
-                    st.b[s][g][t] = NT ? __builtin_nontemporal_load(src) : *src;
-                else
-                    st.b[s][g][t] = floatx4{0, 0, 0, 0};
-            }
-    }
-}
-
-template <int CG, int SS>
-__device__ __forceinline__ void mma_stage(const Stage<CG, SS> &st, floatx4 (&acc)[CG][4])
-{
-#pragma unroll
-    for (int s = 0; s < SS; ++s)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int g = 0; g < CG; ++g)
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-                    acc[g][cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.a[s][t], st.b[s][g][t][cc], acc[g][cc], 0, 0, 0);
-}
-
-template <int WN, int WK, int CG, bool NT>
-__global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
-{
-    // register budget: 128 per lane for 16 waves, 256 up to 8 waves
-    constexpr int SS = (WN * WK > 8) ? 1 : (CG > 1 ? 2 : 4);
-    constexpr int COLS = 64 * CG * WN;          // columns per workgroup
-    constexpr int THREADS = 64 * WN * WK;
-    __shared__ floatx4 red[WK > 1 ? WK * 16 * (COLS / 4) : 1];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave % WN, wk = wave / WN;
-    const int q = lane >> 4, c = lane & 15;
-    const int64_t zb = blockIdx.z, batch = zb / p.row_blocks, rb = zb % p.row_blocks;
-    const int64_t rows = p.M - 16 * rb < 16 ? p.M - 16 * rb : 16;       // rows of this block
-    const int64_t nblock0 = (int64_t)blockIdx.x * COLS;
-    const int64_t n0 = nblock0 + (int64_t)wn * CG * 64 + 4 * c;   // this lane's first column in group 0
-
-    // contiguous range of super-steps for this (split, wk)
-    const int64_t steps = (p.K + 15) / 16;
-    const int64_t parts = (int64_t)p.split * WK, part = (int64_t)blockIdx.y * WK + wk;
-    const int64_t s_begin = steps * part / parts, s_end = steps * (part + 1) / parts;
-
-    const float *A = p.A + batch * p.strideA + 16 * rb * p.lda;
-    const float *B = p.B + batch * p.strideB;
-    const bool a_row_valid = c < rows;
-    bool col_valid[CG];
-#pragma unroll
-    for (int g = 0; g < CG; ++g) col_valid[g] = n0 + 64 * g < p.N;     // N % 4 == 0: whole vectors
-
-    floatx4 acc[CG][4];
-#pragma unroll
-    for (int g = 0; g < CG; ++g)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) acc[g][cc] = floatx4{0, 0, 0, 0};
-
-    // full batches of SS super-steps whose last row is below K
-    int64_t s = s_begin;
-    const int64_t full_steps = p.K / 16;                        // super-steps with all 16 rows valid
-    const int64_t s_full_end = s_end < full_steps ? s_end : full_steps;
-    const int64_t nbatches = s_full_end > s ? (s_full_end - s) / SS : 0;
-    const float *a_ptr = A + (int64_t)c * p.lda + 16 * s + 4 * q;
-    const float *b_ptr = B + (16 * s + 4 * q) * p.ldb + n0;
-    if (nbatches > 0) {
-        Stage<CG, SS> cur, nxt;
-        load_stage<CG, SS, NT>(cur, a_ptr, b_ptr, p.ldb, a_row_valid, col_valid);
-        for (int64_t it = 1; it < nbatches; ++it) {
-            a_ptr += 16 * SS;
-            b_ptr += 16 * SS * p.ldb;
-            load_stage<CG, SS, NT>(nxt, a_ptr, b_ptr, p.ldb, a_row_valid, col_valid);
-            mma_stage<CG, SS>(cur, acc);
-            cur = nxt;
-        }
-        mma_stage<CG, SS>(cur, acc);
-        a_ptr += 16 * SS;
-        b_ptr += 16 * SS * p.ldb;
-        s += nbatches * SS;
-    }
-    // remaining super-steps one at a time, rows guarded against K (K % 4 == 0: a lane's four
-    // rows k0+4q..k0+4q+3 are valid together)
-    for (; s < s_end; ++s) {
-        const bool k_valid = 16 * s + 4 * q < p.K;
-        floatx4 a = floatx4{0, 0, 0, 0};
-        if (k_valid && a_row_valid) a = *reinterpret_cast<const floatx4 *>(a_ptr);
-#pragma unroll
-        for (int g = 0; g < CG; ++g) {
-            floatx4 b[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                b[t] = floatx4{0, 0, 0, 0};
-                if (k_valid && col_valid[g]) b[t] = *reinterpret_cast<const floatx4 *>(b_ptr + t * p.ldb + 64 * g);
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-                    acc[g][cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t][cc], acc[g][cc], 0, 0, 0);
-        }
-        a_ptr += 16;
-        b_ptr += 16 * p.ldb;
-    }
-
-    // accumulator (g, cc) register r of lane (q, c) is Z[4q + r][n0 + 64 g + cc]
-    if (WK > 1) {
-#pragma unroll
-        for (int g = 0; g < CG; ++g)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = 4 * q + r, col4 = (wn * CG + g) * 16 + c;
-                red[(wk * 16 + row) * (COLS / 4) + col4] = floatx4{acc[g][0][r], acc[g][1][r], acc[g][2][r], acc[g][3][r]};
-            }
-        __syncthreads();
-    }
-
-    float *out = p.split > 1 ? p.partial + ((int64_t)blockIdx.y * p.batch * p.row_blocks + zb) * 16 * p.N
-                             : p.C + batch * p.strideC + 16 * rb * p.ldc;
-    const int64_t out_ld = p.split > 1 ? p.N : p.ldc;
-    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
-
-    auto finish = [&](int row, int64_t col, floatx4 z) {
-        if (row >= rows || col >= p.N) return;
-        if (p.split == 1) {
-            floatx4 bj = bias ? *reinterpret_cast<const floatx4 *>(bias + col) : floatx4{0, 0, 0, 0};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) z[e] = apply_act(z[e] + bj[e], p.act);
-        }
-        *reinterpret_cast<floatx4 *>(out + (int64_t)row * out_ld + col) = z;
-    };
-
-    if (WK > 1) {
-        for (int e = tid; e < 16 * (COLS / 4); e += THREADS) {
-            const int row = e / (COLS / 4), col4 = e % (COLS / 4);
-            floatx4 z = red[row * (COLS / 4) + col4];
-#pragma unroll
-            for (int w = 1; w < WK; ++w) {
-                const floatx4 v = red[(w * 16 + row) * (COLS / 4) + col4];
-                z += v;
-            }
-            finish(row, nblock0 + 4 * col4, z);
-        }
-    } else {
-#pragma unroll
-        for (int g = 0; g < CG; ++g)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                finish(4 * q + r, n0 + 64 * g, floatx4{acc[g][0][r], acc[g][1][r], acc[g][2][r], acc[g][3][r]});
-    }
-}
-
-// C = act(bias + sum over splits of partial), splits added in ascending order
-__global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyParams p)
-{
-    const int64_t n4 = p.N / 4;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t batch = blockIdx.y;
-    if (idx >= p.M * n4) return;
-    const int64_t row = idx / n4, col = 4 * (idx % n4);
-    const int64_t zb = batch * p.row_blocks + row / 16;
-    floatx4 z = floatx4{0, 0, 0, 0};
-    for (int s = 0; s < p.split; ++s)
-        z += *reinterpret_cast<const floatx4 *>(
-            p.partial + (((int64_t)s * p.batch * p.row_blocks + zb) * 16 + row % 16) * p.N + col);
-    const floatx4 bj = p.bias ? *reinterpret_cast<const floatx4 *>(p.bias + batch * p.strideBias + col)
-                              : floatx4{0, 0, 0, 0};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) z[e] = apply_act(z[e] + bj[e], p.act);
-    *reinterpret_cast<floatx4 *>(p.C + batch * p.strideC + row * p.ldc + col) = z;
-}
-
-bool skinny_supports(const Problem &p)
-{
-    return p.dtype == DT_F32 && p.layout == 0 && p.M >= 1 && p.K >= 4 && p.K % 4 == 0 &&
-           p.N % 4 == 0 && p.batch * ((p.M + 15) / 16) <= 65535 && vector_friendly(p);
-}
-
-template <int WN, int WK, int CG, bool NT, int SPLIT>
-hipError_t skinny_launch(const Problem &p, hipStream_t stream)
-{
-    constexpr int COLS = 64 * CG * WN;
-    SkinnyParams sp;
-    sp.M = p.M; sp.N = p.N; sp.K = p.K;
-    sp.A = static_cast<const float *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
-    sp.B = static_cast<const float *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
-    sp.bias = p.bias; sp.strideBias = p.strideBias;
-    sp.C = static_cast<float *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
-    sp.batch = p.batch; sp.act = p.act;
-    sp.row_blocks = (p.M + 15) / 16;
-    // SPLIT == 0: enough workgroups for about two per CU, but never ranges shorter than 256 rows
-    int split = SPLIT;
-    if (SPLIT == 0) {
-        const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
-        const int64_t by_grid = (512 + col_blocks - 1) / col_blocks;
-        const int64_t by_k = p.K / (256 * WK) > 0 ? p.K / (256 * WK) : 1;
-        split = (int)(by_grid < by_k ? by_grid : by_k);
-        if (split < 1) split = 1;
-        if (split > 64) split = 64;
-    }
-    sp.split = split;
-    sp.partial = nullptr;
-    if (split > 1) {
-        void *ws = nullptr;
-        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws);
-        if (e != hipSuccess) return e;
-        sp.partial = static_cast<float *>(ws);
-    }
-    dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
-    hipLaunchKernelGGL((skinny_kernel<WN, WK, CG, NT>), grid, dim3(64 * WN * WK), 0, stream, sp);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || split == 1) return e;
-    const int64_t vecs = p.M * (p.N / 4);
-    hipLaunchKernelGGL(skinny_reduce_kernel, dim3((unsigned)((vecs + 255) / 256), (unsigned)p.batch), dim3(256), 0,
-                       stream, sp);
-    return hipGetLastError();
-}
-
-}  // namespace
+using namespace skinny;
 
 #define SKINNY(WN, WK, CG, NT, SPLIT)                                                     \
     {"skinny_f32_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT, skinny_supports, \
      skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0, reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT>)}
 
-// The first entry is the dispatcher's choice for at most 16 rows, the second (same shape, B
-// loaded without the non-temporal hint) its choice for small problems of more rows; the rest
-// are there for the sweep.
+// The first entry is the dispatcher's choice for at most 16 rows (found by the tree search of
+// paper_2602_12305_amd/search.py on the 16 x 16384 x 16384 case: eight waves deep in k, one
+// workgroup per CU), the second (B loaded without the non-temporal hint) its choice for small
+// problems of more rows; the rest are there for the sweep.
 const Variant *skinny_variants()
 {
     static const Variant v[kNumSkinnyVariants] = {
-        SKINNY(1, 4, 2, 1, 0),  SKINNY(1, 4, 2, 0, 0),  SKINNY(4, 1, 1, 1, 0),  SKINNY(2, 4, 1, 1, 0),
-        SKINNY(1, 8, 1, 1, 1),  SKINNY(1, 8, 1, 0, 1),  SKINNY(1, 16, 1, 1, 1), SKINNY(1, 4, 1, 1, 2),
-        SKINNY(4, 4, 1, 1, 0),  SKINNY(2, 2, 2, 1, 0),  SKINNY(8, 1, 1, 1, 0),  SKINNY(4, 1, 2, 1, 0),
+        SKINNY(1, 8, 2, 1, 0),  SKINNY(1, 4, 2, 0, 0),  SKINNY(1, 4, 2, 1, 0),  SKINNY(4, 1, 1, 1, 0),
+        SKINNY(2, 4, 1, 1, 0),  SKINNY(1, 8, 1, 1, 1),  SKINNY(1, 8, 1, 0, 1),  SKINNY(1, 16, 1, 1, 1),
+        SKINNY(1, 4, 1, 1, 2),  SKINNY(4, 4, 1, 1, 0),  SKINNY(2, 2, 2, 1, 0),  SKINNY(1, 8, 2, 1, 2),
     };
     return v;
 }
