@@ -1,4 +1,6 @@
-"""CPU oracle for C = act(A.B + bias): ctypes front end of oracle_gemm.c.
+"""CPU oracle for C = act(A.B + bias) and for its bandwidth-bound siblings (element-wise
+ReLU / sigmoid, sum, dot product, mean squared error): ctypes front end of oracle_gemm.c and
+oracle_streams.c.
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke entry point and by
 the benchmark's cpu_baseline leg; the product package never imports it, and it
@@ -16,6 +18,8 @@ from .build import build as _build
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
+EW_RELU, EW_SIGMOID = 0, 1
+RED_SUM, RED_DOT, RED_MSE = 0, 1, 2
 
 _lib = None
 
@@ -37,6 +41,10 @@ def lib():
         L.oracle_bf16_from_double.restype = C.c_uint16
         L.oracle_bf16_from_double.argtypes = [C.c_double]
         L.oracle_num_threads.restype = C.c_int
+        L.oracle_elementwise.restype = None
+        L.oracle_elementwise.argtypes = [i64, vp, C.c_int, vp]
+        L.oracle_reduce.restype = C.c_double
+        L.oracle_reduce.argtypes = [i64, vp, vp, C.c_int]
         _lib = L
     return _lib
 
@@ -120,6 +128,25 @@ def bf16_from_double(y):
     """uint16 bit patterns of the bf16 nearest (ties to even) to each fp64 value."""
     f = lib().oracle_bf16_from_double
     return np.vectorize(lambda v: f(float(v)), otypes=[np.uint16])(np.asarray(y, dtype=np.float64))
+
+
+def elementwise(x, op):
+    """fp64 array of op(x_i) for a contiguous fp32 array x (Table 4, tasks 10 and 1)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty(x.shape, dtype=np.float64)
+    lib().oracle_elementwise(x.size, _ptr(x), op, _ptr(y))
+    return y
+
+
+def reduce(x, y, op):
+    """fp64 value of sum(x), dot(x, y) or mean((x - y)^2) for contiguous fp32 arrays (Table 4,
+    tasks 14, 15, 7); y is ignored for the sum."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if op != RED_SUM:
+        y = np.ascontiguousarray(y, dtype=np.float32)
+        if y.size != x.size:
+            raise ValueError("operands of different length")
+    return float(lib().oracle_reduce(x.size, _ptr(x), None if op == RED_SUM else _ptr(y), op))
 
 
 def num_threads():

@@ -1,0 +1,131 @@
+"""Pins of the oracle for the streaming siblings (paper Table 4, tasks 1, 7, 10, 14, 15):
+closed forms, invariants and independent exact arithmetic, chosen so that a dropped element, a wrong
+sign, a missing 1/n or a swapped operand fails at least one of them."""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_12305_amd import synth
+
+SUM, DOT, MSE = oracle.RED_SUM, oracle.RED_DOT, oracle.RED_MSE
+
+
+def exact(terms):
+    """Exact rational sum of fp64 terms that are themselves exact."""
+    return sum((Fraction(float(t)) for t in terms), Fraction(0))
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 65535, 65536, 65537, 200003])
+def test_sum_of_consecutive_integers_is_gauss(n):
+    x = np.arange(1, n + 1, dtype=np.float32)          # exact in fp32 up to 2^24
+    assert oracle.reduce(x, None, SUM) == n * (n + 1) / 2
+
+
+def test_alternating_signs_catch_a_lost_or_doubled_element():
+    for n in (1, 2, 65536, 65537, 131073):
+        x = np.where(np.arange(n) % 2 == 0, 1.0, -1.0).astype(np.float32)
+        assert oracle.reduce(x, None, SUM) == float(n % 2)
+
+
+def test_dot_closed_forms_and_symmetry():
+    n = 70001
+    i = np.arange(n, dtype=np.float32)
+    ones = np.ones(n, dtype=np.float32)
+    assert oracle.reduce(i, ones, DOT) == n * (n - 1) / 2
+    assert oracle.reduce(i, i, DOT) == (n - 1) * n * (2 * n - 1) / 6        # sum of squares, < 2^53
+    a = synth.normal(11, "a", 1, n)[0]; b = synth.normal(11, "b", 1, n)[0]
+    assert oracle.reduce(a, b, DOT) == oracle.reduce(b, a, DOT)
+    assert oracle.reduce(a, -b, DOT) == -oracle.reduce(a, b, DOT)
+    e = np.zeros(n, dtype=np.float32); e[12345] = 1.0
+    assert oracle.reduce(a, e, DOT) == float(a[12345])                        # picks one element
+
+
+def test_mse_closed_forms():
+    n = 100000
+    x = synth.uniform(12, "x", 1, n)[0]
+    assert oracle.reduce(x, x, MSE) == 0.0
+    c = np.float32(0.5)
+    y = (x.astype(np.float64) + 0.5).astype(np.float32)
+    d = (x.astype(np.float64) - y.astype(np.float64))                         # exact differences
+    assert oracle.reduce(x, y, MSE) == pytest.approx(float(np.mean(d * d)), rel=1e-13)
+    z = np.zeros(n, dtype=np.float32)
+    const = np.full(n, 3.0, dtype=np.float32)
+    assert oracle.reduce(const, z, MSE) == 9.0                                 # the 1/n is there
+    assert oracle.reduce(z, const, MSE) == 9.0                                 # and the square
+    assert oracle.reduce(np.zeros(0, np.float32), np.zeros(0, np.float32), MSE) == 0.0
+    one = np.zeros(n, dtype=np.float32); one[-1] = 2.0                         # the last element counts
+    assert oracle.reduce(one, z, MSE) == 4.0 / n
+
+
+@pytest.mark.parametrize("n", [1, 17, 4097, 70000])
+def test_reductions_against_exact_rational_arithmetic(n):
+    a = synth.normal(20 + n, "a", 1, n)[0]; b = synth.normal(20 + n, "b", 1, n)[0]
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    ref = float(exact(a64))
+    assert oracle.reduce(a, None, SUM) == pytest.approx(ref, abs=1e-12 * float(np.sum(np.abs(a64))))
+    ref = float(exact(a64 * b64))                                              # products exact in fp64
+    assert oracle.reduce(a, b, DOT) == pytest.approx(ref, abs=1e-12 * float(np.sum(np.abs(a64 * b64))))
+    ref = float(sum((Fraction(float(p)) - Fraction(float(q))) ** 2 for p, q in zip(a64, b64)) / n)
+    assert oracle.reduce(a, b, MSE) == pytest.approx(ref, rel=1e-12)
+
+
+def test_sum_matches_math_fsum_on_a_large_array_with_cancellation():
+    n = 1 << 20
+    x = (synth.normal(30, "x", 1, n)[0].astype(np.float64) * 1e6).astype(np.float32)
+    x[::2] = -x[1::2]                                                          # exact sum 0, large terms
+    assert oracle.reduce(x, None, SUM) == 0.0
+    y = synth.uniform(31, "y", 1, n)[0]
+    ref = math.fsum(y.astype(np.float64).tolist())                             # exactly rounded sum
+    assert oracle.reduce(y, None, SUM) == pytest.approx(ref, abs=4e-12 * float(np.sum(np.abs(y))))
+
+
+def test_reduction_does_not_depend_on_the_thread_count_or_split():
+    n = 300001
+    x = synth.normal(32, "x", 1, n)[0]
+    whole = oracle.reduce(x, None, SUM)
+    assert whole == oracle.reduce(x.copy(), None, SUM)
+    # blocks of 65,536 in order: the same by hand
+    parts = [float(np.sum(x[i:i + 65536].astype(np.float64).cumsum()[-1:])) for i in range(0, n, 65536)]
+    acc = 0.0
+    for p in parts:
+        acc += p
+    assert whole == acc
+
+
+def test_relu_is_exact_and_sigmoid_values():
+    x = np.array([-3.5, -0.0, 0.0, 1e-30, 2.25, -1e30, 3e38, np.inf, -np.inf], dtype=np.float32)
+    y = oracle.elementwise(x, oracle.EW_RELU)
+    assert np.array_equal(y, np.maximum(x.astype(np.float64), 0.0))
+    assert y.dtype == np.float64 and y.shape == x.shape
+    s = oracle.elementwise(np.array([0.0, 1.0, -1.0, 2.0, -2.0, 20.0, -20.0, 100.0, -100.0, -800.0], np.float32),
+                           oracle.EW_SIGMOID)
+    # values computed by hand from exp(1) = 2.718281828459045, exp(2) = 7.38905609893065
+    assert s[0] == 0.5
+    assert s[1] == pytest.approx(1.0 / (1.0 + 1.0 / 2.718281828459045), rel=1e-15)      # 0.7310585786300049
+    assert s[1] == pytest.approx(0.7310585786300049, rel=1e-15)
+    assert s[3] == pytest.approx(0.8807970779778823, rel=1e-15)
+    assert s[5] == pytest.approx(1.0 - 2.0611536181902037e-09, rel=1e-15)
+    assert s[6] == pytest.approx(2.0611536181902037e-09, rel=1e-14)
+    assert s[7] == 1.0 and 0.0 < s[8] < 1e-43 and s[9] == 0.0
+    # sigma(x) + sigma(-x) = 1
+    assert s[1] + s[2] == pytest.approx(1.0, abs=2e-16) and s[3] + s[4] == pytest.approx(1.0, abs=2e-16)
+
+
+def test_sigmoid_against_60_digit_decimal_arithmetic():
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    x = synth.uniform(40, "x", 1, 200)[0] * np.float32(30.0)
+    s = oracle.elementwise(x, oracle.EW_SIGMOID)
+    for xi, si in zip(x, s):
+        ref = Decimal(1) / (Decimal(1) + (-Decimal(float(xi))).exp())
+        assert si == pytest.approx(float(ref), rel=4e-16)
+    assert np.all(np.diff(oracle.elementwise(np.sort(x), oracle.EW_SIGMOID)) >= 0)       # monotone
+
+
+def test_elementwise_keeps_shape_and_empty_input():
+    assert oracle.elementwise(np.zeros((0,), np.float32), oracle.EW_RELU).shape == (0,)
+    x = synth.normal(41, "x", 7, 13)
+    assert oracle.elementwise(x, oracle.EW_RELU).shape == (7, 13)

@@ -108,3 +108,18 @@ def test_a_candidate_compiles_and_exports_its_entry_points():
     assert path is not None and os.path.exists(path)
     syms = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
     assert " T cand_run" in syms and " T cand_resources" in syms
+
+
+@pytest.mark.gpu
+def test_search_runs_on_the_gpu_and_every_candidate_passes_its_check():
+    """Four kernels of the streaming family on the 256^3 workload: each is compiled (or found in the
+    cache), loaded next to the library, compared with the fallback kernel and timed."""
+    fam = S.FAMILIES["skinny"]
+    ev = S.Evaluator("c1_f32_256_relu", fam, steps=5, warmup=2)
+    root, nodes = S.search(fam, fam.root, ev, budget=3, seed=0)
+    assert len({S.key(n.params) for n in nodes}) == 4
+    for n in nodes:
+        assert n.alive and n.profile.correct and n.profile.extra["err"] <= 2e-5
+        assert 0 < n.profile.time < 1e-3 and n.profile.regs > 0 and n.profile.scratch_bytes == 0
+    best, path = S.best_keep_chain(root)
+    assert best.profile.time <= root.profile.time
