@@ -6,8 +6,10 @@
 A step is one call of the library on one seeded synthetic workload (inputs resident in
 HBM before the timed region; two rotating buffer sets so that consecutive steps do not
 re-read the same bytes from cache).  The default workload is the memory-bound skinny
-configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and adds
-them under "workloads".  One JSON line is printed.
+configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and the
+streaming siblings (element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats: --workload
+s_relu, s_sigmoid, s_sum, s_dot, s_mse) and adds them under "workloads".  One JSON line is
+printed.
 
 The "roofline" object prices the dominant kernel of the workload against the published
 MI355X peak (HBM 8 TB/s, dense bf16 MFMA 2516.6 TFLOP/s, fp32 MFMA 157.3 TFLOP/s) using
@@ -30,6 +32,10 @@ PEAK_TFLOPS = {0: 157.3, 1: 2516.6}          # fp32 MFMA, bf16 MFMA (dense)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma"}
 DTYPE_NAME = {0: "f32", 1: "bf16"}
+# streaming siblings: (entry point, op, arrays read, arrays written)
+STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
+           "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0)}
+STREAM_N = 1 << 28
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB per dispatch, scaled by what the same counters read for the library's 1 GiB copy
@@ -40,15 +46,20 @@ RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "e
 RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
 RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp",
              "common.hpp")
+STREAMS_SRC = ("kernel_streams.hip", "epilogue.hpp", "common.hpp")
 TRAFFIC = {
-    ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0"):
-        {"bytes": int((528467 * 2.0 + 2048 + 1083.62 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "e7a3c46449c9f7b5"},
+    ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
+        {"bytes": int((528469 * 2.0 + 2048 + 1081.5 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "877c25d5c39e2063"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((385324 * 2.0 + 65536) * 1024), "files": RINGF_SRC, "src": "d98b0e728176c0b1"},
+        {"bytes": int((384966 * 2.0 + 65536) * 1024), "files": RINGF_SRC, "src": "3eeb75c9ec4c2d7b"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((790157 * 2.0 + 131097) * 1024), "files": RING_SRC, "src": "b153061e39510446"},
+        {"bytes": int((792834 * 2.0 + 131073) * 1024), "files": RING_SRC, "src": "bddcc8d5838e99ea"},
     ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((67454.8 * 2.0 + 262576) * 1024), "files": RINGP_SRC, "src": "9edbaa53f6a244ed"},
+        {"bytes": int((67449.1 * 2.0 + 262866) * 1024), "files": RINGP_SRC, "src": "a856d6cc76f71e91"},
+    ("s_sigmoid", "s_sigmoid"):
+        {"bytes": int((524329 * 2.0 + 1048580) * 1024), "files": STREAMS_SRC, "src": "b7c0f379f99be1d5"},
+    ("s_dot", "s_dot"):
+        {"bytes": int(((1048650 + 33.08) * 2.0 + 256.55 + 0.03) * 1024), "files": STREAMS_SRC, "src": "b7c0f379f99be1d5"},
 }
 
 
@@ -163,6 +174,75 @@ def main():
                "dtype": DTYPE_NAME[w.dtype], "roofline": roof}
         return w, sets, res
 
+    def time_stream(name, steps, warmup, with_oracle):
+        """One streaming sibling on 2^28 seeded uniform floats (1 GiB per array)."""
+        kind, op, reads, writes = STREAMS[name]
+        n = STREAM_N
+        gen = lambda tag: synth.uniform(7, tag, n >> 16, 1 << 16, -2.0, 2.0).reshape(-1)
+        hx = gen("x")
+        hy = gen("y") if reads == 2 else None
+        xd = torch.from_numpy(hx).cuda()
+        yd = torch.from_numpy(hy).cuda() if hy is not None else None
+        od = torch.empty(n if kind == "ew" else 1, dtype=torch.float32, device="cuda")
+        if kind == "ew":
+            step = lambda: ob.optiml_elementwise(n, xd, od, op)
+        else:
+            step = lambda: ob.optiml_reduce(n, xd, yd, op, od)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+        ms, kernel_ms = max(wall_ms, dev_ms) / steps, dev_ms / steps
+        nbytes = 4 * n * (reads + writes) + (4 if kind == "red" else 0)
+        gbs = nbytes / (kernel_ms * 1e-3) / 1e9
+        tr = TRAFFIC.get((name, name))
+        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash(tr["files"]) else None
+        res = {"workload": name, "variant": name, "n": n, "ms_per_step": round(ms, 5),
+               "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 2), "hbm_frac": round(gbs / PEAK_HBM_GBS, 4), "dtype": "f32",
+               "roofline": {"bound": "hbm", "achieved": round(gbs, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "kernel": name,
+                            "kernel_ms": round(kernel_ms, 5)}}
+        if with_oracle:
+            import oracle
+            t0 = time.perf_counter()
+            if kind == "ew":
+                m = 1 << 24                                     # bounded sample: the first 2^24 elements
+                ref = oracle.elementwise(hx[:m], op)
+                secs = time.perf_counter() - t0
+                got = od[:m].cpu().numpy().astype(np.float64)
+                err = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)))
+                full, sample = secs * (n / m), f"first {m} of {n} elements"
+            else:
+                ref = oracle.reduce(hx, hy, op)
+                secs = time.perf_counter() - t0
+                err = abs(float(od.item()) - ref) / max(abs(ref), 1e-30)
+                full, sample = secs, "whole workload"
+            res["cpu_baseline"] = {"value": float(f"{nbytes / 1e9 / full:.4g}"), "unit": "GB/s",
+                                   "cores": oracle.num_threads(), "kind": "oracle", "sample": sample,
+                                   "seconds": round(secs, 3)}
+            res["parity_rel_err"] = float(f"{err:.3e}")
+        return res
+
+    if args.workload in STREAMS:
+        r = time_stream(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+        out = {"metric": "GB/s (algorithmic bytes) of " + args.workload[2:], "value": r["GB/s"], "unit": "GB/s",
+               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+               "config": {"workload": args.workload, "n": r["n"]}, "GB/s": r["GB/s"], "roofline": r["roofline"]}
+        for k in ("cpu_baseline", "parity_rel_err"):
+            if k in r:
+                out[k] = r[k]
+        print(json.dumps(out))
+        return
+
     w, sets, head = time_workload(args.workload, args.steps, args.warmup)
     bound = BOUND[args.workload]
     out = {
@@ -225,6 +305,9 @@ def main():
             del s
             torch.cuda.empty_cache()
             out["workloads"][name] = r
+        for name in STREAMS:
+            out["workloads"][name] = time_stream(name, args.steps, args.warmup, False)
+            torch.cuda.empty_cache()
 
     print(json.dumps(out))
 

@@ -176,6 +176,29 @@ int optiml_variant_resources(int variant_id, int *num_regs, int *scratch_bytes, 
  */
 int optiml_copy_bytes(void *dst, const void *src, int64_t nbytes, void *stream);
 
+/*
+ * Bandwidth-bound siblings of the contraction from the paper's Table 4, on float arrays of n
+ * elements (DEVICE pointers, any alignment; 16-byte aligned arrays take the 128-bit path).
+ *
+ * optiml_elementwise: y[i] = max(0, x[i]) (OPTIML_EW_RELU, task 10) or 1 / (1 + exp(-x[i]))
+ * (OPTIML_EW_SIGMOID, task 1; about 3 ulp).  y may be x itself; any other overlap is undefined.
+ * n == 0 writes nothing.
+ *
+ * optiml_reduce: *out (one float, DEVICE pointer) = sum_i x[i] (OPTIML_RED_SUM, task 14; y is
+ * ignored and may be NULL), sum_i x[i] * y[i] (OPTIML_RED_DOT, task 15) or
+ * (1/n) sum_i (x[i] - y[i])^2 (OPTIML_RED_MSE, task 7; 0 for n == 0).  Terms are formed and added
+ * in fp64 in a fixed order and the total is rounded once to float, so the result is the exact
+ * value's nearest float up to fp64 rounding of the sum, and repeating a call gives the same bits.
+ * Uses the per-device workspace (see Workspace above) and enqueues two kernels.  n == 0 writes 0.
+ *
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): n < 0, unknown op, NULL out, NULL x (or y where it
+ * is read) with n > 0.
+ */
+typedef enum { OPTIML_EW_RELU = 0, OPTIML_EW_SIGMOID = 1 } optiml_ew_t;
+typedef enum { OPTIML_RED_SUM = 0, OPTIML_RED_DOT = 1, OPTIML_RED_MSE = 2 } optiml_red_t;
+int optiml_elementwise(int64_t n, const float *x, float *y, int op, void *stream);
+int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out, void *stream);
+
 /* Human-readable text for a status code; static storage. */
 const char *optiml_status_string(int status);
 

@@ -32,6 +32,8 @@ SIGNATURES = {
     "optiml_gemm_epilogue_variant": (_int, _PROBLEM + [_vp, _int]),
     "optiml_variant_resources": (_int, [_int, C.POINTER(_int), C.POINTER(_int), C.POINTER(_int)]),
     "optiml_copy_bytes": (_int, [_vp, _vp, _i64, _vp]),
+    "optiml_elementwise": (_int, [_i64, _vp, _vp, _int, _vp]),
+    "optiml_reduce": (_int, [_i64, _vp, _vp, _int, _vp, _vp]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -147,6 +149,14 @@ def optiml_variant_resources(variant_id):
 
 def optiml_copy_bytes(dst, src, nbytes, stream=None):
     return _check(lib().optiml_copy_bytes(_addr(dst), _addr(src), nbytes, _stream(stream)))
+
+
+def optiml_elementwise(n, x, y, op, stream=None):
+    return _check(lib().optiml_elementwise(n, _addr(x), _addr(y), op, _stream(stream)))
+
+
+def optiml_reduce(n, x, y, op, out, stream=None):
+    return _check(lib().optiml_reduce(n, _addr(x), _addr(y), op, _addr(out), _stream(stream)))
 
 
 def optiml_status_string(status):

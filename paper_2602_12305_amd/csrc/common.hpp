@@ -43,9 +43,13 @@ int compute_units();
 // per-device scratch for split-K partial sums (grown on demand, never shrunk)
 hipError_t workspace(size_t bytes, void **ptr);
 
+// streaming siblings (kernel_streams.hip); arguments already validated
+hipError_t launch_elementwise(int64_t n, const float *x, float *y, int op, hipStream_t stream);
+hipError_t launch_reduce(int64_t n, const float *x, const float *y, int op, float *out, hipStream_t stream);
+
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
-const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 12;
+const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit

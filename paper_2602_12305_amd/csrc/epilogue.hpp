@@ -18,7 +18,8 @@ __device__ __forceinline__ float exp_neg(float x)
     const float l2e_hi = -1.44269502162933349609375f;     // -log2(e) rounded to fp32
     const float l2e_lo = -1.925963033500011e-08f;          // -(log2(e) - fp32(log2(e)))
     const float t = x * l2e_hi;
-    const float r = fmaf(x, l2e_hi, -t) + x * l2e_lo;      // what the rounded product lost
+    float r = fmaf(x, l2e_hi, -t) + x * l2e_lo;            // what the rounded product lost
+    r = __builtin_isinf(t) ? 0.0f : r;                     // infinite x (or product): inf - inf above
     const float p = __builtin_amdgcn_exp2f(t);
     return p * fmaf(r, 0.693147180559945f, 1.0f);          // 2^(t+r) = 2^t (1 + r ln 2 + ...); inf stays inf
 }

@@ -93,7 +93,10 @@ __device__ __forceinline__ void mma_stage(const Stage<CG, SS> &st, floatx4 (&acc
                     acc[g][cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(st.a[s][t], st.b[s][g][t][cc], acc[g][cc], 0, 0, 0);
 }
 
-template <int WN, int WK, int CG, bool NT>
+// IL: the WK waves of a workgroup take the batches of SS super-steps of the workgroup's k range in
+// turn (wave w: batches w, w + WK, ...) instead of one contiguous sub-range each, so that all
+// waves of all workgroups of a split read neighbouring rows of B at any moment.
+template <int WN, int WK, int CG, bool NT, bool IL = false>
 __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
 {
     // register budget: 128 per lane for 16 waves, 256 up to 8 waves
@@ -110,10 +113,28 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
     const int64_t nblock0 = (int64_t)blockIdx.x * COLS;
     const int64_t n0 = nblock0 + (int64_t)wn * CG * 64 + 4 * c;   // this lane's first column in group 0
 
-    // contiguous range of super-steps for this (split, wk)
-    const int64_t steps = (p.K + 15) / 16;
-    const int64_t parts = (int64_t)p.split * WK, part = (int64_t)blockIdx.y * WK + wk;
-    const int64_t s_begin = steps * part / parts, s_end = steps * (part + 1) / parts;
+    // super-steps of this (split, wk): first full batch (s), distance between batches, number of
+    // full batches, and the range [tail, s_end) of left-over steps taken one at a time
+    const int64_t steps = (p.K + 15) / 16, full_steps = p.K / 16;   // full: all 16 rows below K
+    int64_t s, batch_stride, nbatches, tail, s_end;
+    if (IL) {
+        const int64_t g0 = steps * blockIdx.y / p.split, g1 = steps * (blockIdx.y + 1) / p.split;
+        const int64_t g1f = g1 < full_steps ? g1 : full_steps;
+        const int64_t total = g1f > g0 ? (g1f - g0) / SS : 0;   // full batches of the workgroup
+        s = g0 + (int64_t)wk * SS;
+        batch_stride = (int64_t)SS * WK;
+        nbatches = total > wk ? (total - wk + WK - 1) / WK : 0;
+        tail = g0 + total * SS;
+        s_end = wk == 0 ? g1 : tail;                            // wave 0 takes what the batches leave
+    } else {
+        const int64_t parts = (int64_t)p.split * WK, part = (int64_t)blockIdx.y * WK + wk;
+        s = steps * part / parts;
+        s_end = steps * (part + 1) / parts;
+        const int64_t s_full_end = s_end < full_steps ? s_end : full_steps;
+        batch_stride = SS;
+        nbatches = s_full_end > s ? (s_full_end - s) / SS : 0;
+        tail = s + nbatches * SS;
+    }
 
     const float *A = p.A + batch * p.strideA + 16 * rb * p.lda;
     const float *B = p.B + batch * p.strideB;
@@ -129,27 +150,23 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
         for (int cc = 0; cc < 4; ++cc) acc[g][cc] = floatx4{0, 0, 0, 0};
 
     // full batches of SS super-steps whose last row is below K
-    int64_t s = s_begin;
-    const int64_t full_steps = p.K / 16;                        // super-steps with all 16 rows valid
-    const int64_t s_full_end = s_end < full_steps ? s_end : full_steps;
-    const int64_t nbatches = s_full_end > s ? (s_full_end - s) / SS : 0;
     const float *a_ptr = A + (int64_t)c * p.lda + 16 * s + 4 * q;
     const float *b_ptr = B + (16 * s + 4 * q) * p.ldb + n0;
     if (nbatches > 0) {
         Stage<CG, SS> cur, nxt;
         load_stage<CG, SS, NT>(cur, a_ptr, b_ptr, p.ldb, a_row_valid, col_valid);
         for (int64_t it = 1; it < nbatches; ++it) {
-            a_ptr += 16 * SS;
-            b_ptr += 16 * SS * p.ldb;
+            a_ptr += 16 * batch_stride;
+            b_ptr += 16 * batch_stride * p.ldb;
             load_stage<CG, SS, NT>(nxt, a_ptr, b_ptr, p.ldb, a_row_valid, col_valid);
             mma_stage<CG, SS>(cur, acc);
             cur = nxt;
         }
         mma_stage<CG, SS>(cur, acc);
-        a_ptr += 16 * SS;
-        b_ptr += 16 * SS * p.ldb;
-        s += nbatches * SS;
     }
+    s = tail;
+    a_ptr = A + (int64_t)c * p.lda + 16 * s + 4 * q;
+    b_ptr = B + (16 * s + 4 * q) * p.ldb + n0;
     // remaining super-steps one at a time, rows guarded against K (K % 4 == 0: a lane's four
     // rows k0+4q..k0+4q+3 are valid together)
     for (; s < s_end; ++s) {
@@ -247,7 +264,7 @@ inline bool skinny_supports(const Problem &p)
            p.N % 4 == 0 && p.batch * ((p.M + 15) / 16) <= 65535 && vector_friendly(p);
 }
 
-template <int WN, int WK, int CG, bool NT, int SPLIT>
+template <int WN, int WK, int CG, bool NT, int SPLIT, bool IL = false>
 hipError_t skinny_launch(const Problem &p, hipStream_t stream)
 {
     constexpr int COLS = 64 * CG * WN;
@@ -259,12 +276,12 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     sp.C = static_cast<float *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
     sp.batch = p.batch; sp.act = p.act;
     sp.row_blocks = (p.M + 15) / 16;
-    // SPLIT == 0: enough workgroups for one per CU when a workgroup has eight or more waves, else
-    // about two per CU, but never ranges shorter than 256 rows
+    // SPLIT == 0: enough workgroups for one per CU when a workgroup has eight or more waves or
+    // interleaves its waves in k, else about two per CU, but never ranges shorter than 256 rows
     int split = SPLIT;
     if (SPLIT == 0) {
         const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
-        const int64_t target = WN * WK >= 8 ? 256 : 512;
+        const int64_t target = (IL || WN * WK >= 8) ? 256 : 512;
         const int64_t by_grid = (target + col_blocks - 1) / col_blocks;
         const int64_t by_k = p.K / (256 * WK) > 0 ? p.K / (256 * WK) : 1;
         split = (int)(by_grid < by_k ? by_grid : by_k);
@@ -280,7 +297,7 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
         sp.partial = static_cast<float *>(ws);
     }
     dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
-    hipLaunchKernelGGL((skinny_kernel<WN, WK, CG, NT>), grid, dim3(64 * WN * WK), 0, stream, sp);
+    hipLaunchKernelGGL((skinny_kernel<WN, WK, CG, NT, IL>), grid, dim3(64 * WN * WK), 0, stream, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
     const int64_t vecs = p.M * (p.N / 4);

@@ -9,7 +9,7 @@ searches a tree whose nodes are kernels and whose edges are edits proposed by a 
 model; every node is compiled, tested, profiled and scored, the score is backed up the
 path, and the answer is the end of the best chain of KEEP verdicts.  Here the proposer is
 replaced by the finite set of single-parameter edits of a kernel template (tile shape, ring
-depth, prefetch, wave layout, split-K, non-temporal hint, persistence); everything else is
+depth, prefetch, wave layout, split-K, k interleaving, non-temporal hint, persistence); everything else is
 the paper's loop:
 
   * selection by UCT, Q + c sqrt(ln N_parent / N_child), c = 1.4, depth limit 6;
@@ -66,7 +66,9 @@ class Family:
 
 def _skinny_exprs(p, layout):
     t = f"{p['WN']}, {p['WK']}, {p['CG']}, {'true' if p['NT'] else 'false'}"
-    return ("skinny::skinny_supports", f"skinny::skinny_launch<{t}, {p['SPLIT']}>", f"skinny::skinny_kernel<{t}>")
+    il = "true" if p["IL"] else "false"
+    return ("skinny::skinny_supports", f"skinny::skinny_launch<{t}, {p['SPLIT']}, {il}>",
+            f"skinny::skinny_kernel<{t}, {il}>")
 
 
 def _ringf_exprs(p, layout):
@@ -84,9 +86,9 @@ def _ring_exprs(p, layout):
 FAMILIES = {
     "skinny": Family(
         "skinny", "kernel_skinny.hpp",
-        {"WN": [1, 2, 4, 8], "WK": [1, 2, 4, 8, 16], "CG": [1, 2], "NT": [0, 1], "SPLIT": [0, 1, 2, 4, 8]},
+        {"WN": [1, 2, 4, 8], "WK": [1, 2, 4, 8, 16], "CG": [1, 2], "NT": [0, 1], "SPLIT": [0, 1, 2, 4, 8], "IL": [0, 1]},
         lambda p: p["WN"] * p["WK"] <= 16 and not (p["WN"] * p["WK"] > 8 and p["CG"] > 1),
-        _skinny_exprs, {"WN": 1, "WK": 4, "CG": 2, "NT": 1, "SPLIT": 0}),
+        _skinny_exprs, {"WN": 1, "WK": 8, "CG": 2, "NT": 1, "SPLIT": 0, "IL": 1}),
     "ring_f32": Family(
         "ring_f32", "kernel_ring_f32.hpp",
         {"BM": [128, 256], "NS": [3, 4, 5, 6]},

@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 12
+    assert len(names) == 14
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -81,6 +81,21 @@ def test_plain_and_ex_entry_points_validate_too():
     assert L.optiml_gemm_epilogue_variant(1, 8, 8, 8, P, 8, 0, P, 8, 0, None, 0, P, 8, 0, 0, 0, 0, None, 9999) == ob.ERR_INVALID_ARG
     with pytest.raises(ob.OptimlError):
         ob.optiml_gemm_epilogue(8, 8, 8, P, 8, P, 8, None, 0, 8, 0, 0, stream=0)
+
+
+def test_streaming_entry_points_validate_on_the_host():
+    L = ob.lib()
+    assert L.optiml_elementwise(-1, P, P, 0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_elementwise(8, P, P, 2, None) == ob.ERR_INVALID_ARG          # unknown op
+    assert L.optiml_elementwise(8, None, P, 0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_elementwise(8, P, None, 1, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_elementwise(0, None, None, 0, None) == ob.OK                   # nothing to do
+    assert L.optiml_reduce(-1, P, P, 0, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_reduce(8, P, P, 3, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_reduce(8, P, P, 0, None, None) == ob.ERR_INVALID_ARG           # no place for the result
+    assert L.optiml_reduce(8, None, None, 0, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_reduce(8, P, None, 1, P, None) == ob.ERR_INVALID_ARG           # the dot product reads y
+    assert L.optiml_reduce(8, P, None, 2, P, None) == ob.ERR_INVALID_ARG
 
 
 def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bias=P):

@@ -45,9 +45,9 @@ def analytic(fam, optimum, dead=()):
 
 def test_search_reaches_the_optimum_through_keep_edges():
     fam = S.FAMILIES["skinny"]
-    opt = {"WN": 2, "WK": 4, "CG": 1, "NT": 0, "SPLIT": 1}                # four edits from the root
+    opt = {"WN": 1, "WK": 4, "CG": 1, "NT": 0, "SPLIT": 1, "IL": 1}       # four edits from the root
     assert fam.valid(opt)
-    root, nodes = S.search(fam, fam.root, analytic(fam, opt), budget=80, seed=1)
+    root, nodes = S.search(fam, fam.root, analytic(fam, opt), budget=120, seed=1)
     best, path = S.best_keep_chain(root)
     assert S.key(best.params) == S.key(opt)
     assert path[0] is root and path[-1] is best
@@ -56,7 +56,7 @@ def test_search_reaches_the_optimum_through_keep_edges():
     assert all(n.keep for n in path[1:])
     assert max(n.depth for n in nodes) <= S.MAX_DEPTH
     # the same seed gives the same tree
-    root2, nodes2 = S.search(fam, fam.root, analytic(fam, opt), budget=80, seed=1)
+    root2, nodes2 = S.search(fam, fam.root, analytic(fam, opt), budget=120, seed=1)
     assert [S.key(n.params) for n in nodes] == [S.key(n.params) for n in nodes2]
 
 
@@ -88,7 +88,7 @@ def test_dead_candidates_are_scored_as_failures_and_never_expanded():
 
 def test_depth_limit():
     fam = S.FAMILIES["skinny"]
-    root, nodes = S.search(fam, fam.root, analytic(fam, {"WN": 8, "WK": 2, "CG": 1, "NT": 0, "SPLIT": 8}), budget=300,
+    root, nodes = S.search(fam, fam.root, analytic(fam, {"WN": 8, "WK": 2, "CG": 1, "NT": 0, "SPLIT": 8, "IL": 0}), budget=300,
                            depth=2, seed=0)
     assert max(n.depth for n in nodes) == 2
     assert all(not n.untried for n in nodes if n.depth == 2)
@@ -98,13 +98,13 @@ def test_candidate_source_names_the_instantiation():
     fam = S.FAMILIES["ring_bf16"]
     src = S.source(fam, {"NS": 4, "PF": 0, "WN": 4, "PERSIST": 1}, 1)
     assert "ringp::launch<ring::Cfg<4, true, false, 4>>" in src and 'extern "C" int cand_run' in src
-    src = S.source(S.FAMILIES["skinny"], {"WN": 2, "WK": 4, "CG": 1, "NT": 1, "SPLIT": 0}, 0)
-    assert "skinny::skinny_launch<2, 4, 1, true, 0>" in src
+    src = S.source(S.FAMILIES["skinny"], {"WN": 2, "WK": 4, "CG": 1, "NT": 1, "SPLIT": 0, "IL": 1}, 0)
+    assert "skinny::skinny_launch<2, 4, 1, true, 0, true>" in src
 
 
 def test_a_candidate_compiles_and_exports_its_entry_points():
     fam = S.FAMILIES["skinny"]
-    path = S.build(fam, {"WN": 2, "WK": 4, "CG": 1, "NT": 1, "SPLIT": 0}, 0)
+    path = S.build(fam, {"WN": 2, "WK": 4, "CG": 1, "NT": 1, "SPLIT": 0, "IL": 0}, 0)
     assert path is not None and os.path.exists(path)
     syms = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
     assert " T cand_run" in syms and " T cand_resources" in syms
