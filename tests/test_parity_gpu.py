@@ -223,6 +223,25 @@ def test_large_pre_activations_stay_finite():
         assert np.all(Y[0, 1::2] == 480.0) and np.all(Y[0, ::2] == 0.0)
 
 
+def test_infinite_pre_activations_follow_the_limits():
+    # z = +inf (from an infinite bias) gives +inf for every activation; z = -inf gives -inf without
+    # an activation and zero for ReLU; SiLU / GELU of -inf are 0 * inf forms whose value nobody
+    # fixes and are not checked
+    M, N, K = 32, 64, 32
+    A = synth.uniform(1000, "A", M, K); B = synth.uniform(1000, "B", K, N)
+    bias = np.zeros(N, dtype=np.float32); bias[::2] = np.inf; bias[1::4] = -np.inf
+    for dtype in (F32, BF16):
+        As = store(A, dtype); Bs = store(B, dtype)
+        for act in ACTS:
+            Y, _, _ = run_gpu(As, Bs, bias, 1, M, N, K, dtype, act, 0)
+            assert np.all(Y[0, :, ::2] == np.inf), (dtype, act)
+            assert np.all(np.isfinite(Y[0, :, 3::4]))
+            if act == synth.ACT_NONE:
+                assert np.all(Y[0, :, 1::4] == -np.inf)
+            if act == synth.ACT_RELU:
+                assert np.all(Y[0, :, 1::4] == 0.0)
+
+
 def test_shared_operands_with_zero_strides():
     batch, M, N, K = 4, 40, 48, 56
     A = synth.uniform(900, "A", M, K, batch=batch); B = synth.uniform(900, "B", K, N); bias = synth.uniform(900, "bias", 1, N)[0]
