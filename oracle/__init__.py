@@ -1,5 +1,5 @@
 """CPU oracle for C = act(A.B + bias) and for its bandwidth-bound siblings (element-wise
-ReLU / sigmoid, sum, dot product, mean squared error): ctypes front end of oracle_gemm.c and
+ReLU / sigmoid, sum, dot product, mean squared error, cross-entropy, LayerNorm): ctypes front end of oracle_gemm.c and
 oracle_streams.c.
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke entry point and by
@@ -45,6 +45,10 @@ def lib():
         L.oracle_elementwise.argtypes = [i64, vp, C.c_int, vp]
         L.oracle_reduce.restype = C.c_double
         L.oracle_reduce.argtypes = [i64, vp, vp, C.c_int]
+        L.oracle_cross_entropy.restype = C.c_double
+        L.oracle_cross_entropy.argtypes = [i64, i64, vp, vp]
+        L.oracle_layernorm.restype = None
+        L.oracle_layernorm.argtypes = [i64, i64, vp, C.c_double, vp]
         _lib = L
     return _lib
 
@@ -147,6 +151,27 @@ def reduce(x, y, op):
         if y.size != x.size:
             raise ValueError("operands of different length")
     return float(lib().oracle_reduce(x.size, _ptr(x), None if op == RED_SUM else _ptr(y), op))
+
+
+def cross_entropy(z, labels):
+    """fp64 mean over rows of log(sum_k exp(z_jk)) - z_{j, label_j} for fp32 logits [N, C] and int32
+    labels [N] (Table 4, task 17)."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    if z.ndim != 2 or labels.shape != (z.shape[0],):
+        raise ValueError("logits [N, C] and labels [N] expected")
+    return float(lib().oracle_cross_entropy(z.shape[0], z.shape[1], _ptr(z), _ptr(labels)))
+
+
+def layernorm(x, eps=1e-5):
+    """fp64 array of (x - mean) / sqrt(var + eps) per row of the fp32 array x [rows, len] (Table 4,
+    task 4: every feature of one sample is one row)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim != 2:
+        raise ValueError("[rows, len] expected")
+    y = np.empty(x.shape, dtype=np.float64)
+    lib().oracle_layernorm(x.shape[0], x.shape[1], _ptr(x), float(eps), _ptr(y))
+    return y
 
 
 def num_threads():

@@ -5,6 +5,12 @@
  *   sum      (Table 4, task 14):        s = sum_i x_i
  *   dot      (Table 4, task 15):        s = sum_i x_i * y_i
  *   MSE      (Table 4, task 7):         s = (1/n) sum_i (x_i - y_i)^2
+ *   cross-entropy (Table 4, task 17):   L = (1/N) sum_j ( log(sum_k exp(z_jk)) - z_{j, y_j} )
+ *                                       for logits Z (N x C, row-major) and labels y_j in [0, C)
+ *   LayerNorm (Table 4, task 4):        y = (x - mean) / sqrt(var + eps) over all features of one
+ *                                       sample (rows of length L), mean and biased variance of
+ *                                       that row; the task states no eps and no scale / shift:
+ *                                       eps is an argument, there is no affine part
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the checker that the GPU library is compared
  * against; nothing on the product path may call it, and it shares no code, header, table
@@ -62,4 +68,59 @@ double oracle_reduce(int64_t n, const float *x, const float *y, int op)
     free(part);
     if (op == ORACLE_RED_MSE) total = n > 0 ? total / (double)n : 0.0;
     return total;
+}
+
+/*
+ * Cross-entropy.  Per row: the maximum m is found first, the sum of exp(z - m) runs over k
+ * ascending in fp64, the loss is log(sum) - (z_y - m): the stable form the task prescribes,
+ * with the exact difference z_y - m taken first so that large logits cost no accuracy.  Row
+ * losses are added in row order inside blocks of 4,096 rows, block sums in block order.  A label
+ * outside [0, C) makes the result NaN.  N == 0 gives 0.
+ */
+double oracle_cross_entropy(int64_t N, int64_t C, const float *z, const int32_t *labels)
+{
+    enum { BLOCK = 4096 };
+    const int64_t blocks = (N + BLOCK - 1) / BLOCK;
+    double *part = (double *)malloc(sizeof(double) * (size_t)(blocks > 0 ? blocks : 1));
+    if (!part) return NAN;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < blocks; ++b) {
+        const int64_t lo = b * BLOCK, hi = lo + BLOCK < N ? lo + BLOCK : N;
+        double s = 0.0;
+        for (int64_t j = lo; j < hi; ++j) {
+            const float *row = z + j * C;
+            if (labels[j] < 0 || labels[j] >= C) { s = NAN; continue; }
+            double m = (double)row[0];
+            for (int64_t k = 1; k < C; ++k) m = (double)row[k] > m ? (double)row[k] : m;
+            double e = 0.0;
+            for (int64_t k = 0; k < C; ++k) e += exp((double)row[k] - m);
+            s += log(e) - ((double)row[labels[j]] - m);
+        }
+        part[b] = s;
+    }
+    double total = 0.0;
+    for (int64_t b = 0; b < blocks; ++b) total += part[b];
+    free(part);
+    return N > 0 ? total / (double)N : 0.0;
+}
+
+/*
+ * LayerNorm of `rows` samples of `len` features each.  Two passes per row in fp64: the mean
+ * (sum in index order / len), then the biased variance as the mean of squared deviations from
+ * that mean (not E[x^2] - mean^2), then y = (x - mean) / sqrt(var + eps).  Results kept in fp64.
+ */
+void oracle_layernorm(int64_t rows, int64_t len, const float *x, double eps, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *xr = x + r * len;
+        double *yr = y + r * len;
+        double s = 0.0;
+        for (int64_t i = 0; i < len; ++i) s += (double)xr[i];
+        const double mean = s / (double)len;
+        double q = 0.0;
+        for (int64_t i = 0; i < len; ++i) q += ((double)xr[i] - mean) * ((double)xr[i] - mean);
+        const double rstd = 1.0 / sqrt(q / (double)len + eps);
+        for (int64_t i = 0; i < len; ++i) yr[i] = ((double)xr[i] - mean) * rstd;
+    }
 }

@@ -129,3 +129,90 @@ def test_elementwise_keeps_shape_and_empty_input():
     assert oracle.elementwise(np.zeros((0,), np.float32), oracle.EW_RELU).shape == (0,)
     x = synth.normal(41, "x", 7, 13)
     assert oracle.elementwise(x, oracle.EW_RELU).shape == (7, 13)
+
+
+# ---- cross-entropy (Table 4, task 17) and LayerNorm (task 4) -----------------------------------
+def test_cross_entropy_closed_forms():
+    N, C = 1000, 37
+    labels = (np.arange(N) * 7 % C).astype(np.int32)
+    z = np.zeros((N, C), dtype=np.float32)
+    assert oracle.cross_entropy(z, labels) == pytest.approx(math.log(C), rel=1e-15)          # uniform prediction
+    z = np.full((N, C), 5.25, dtype=np.float32)
+    assert oracle.cross_entropy(z, labels) == pytest.approx(math.log(C), rel=1e-14)          # shift invariance
+    # one-hot logits of height t on the true class: loss = log(1 + (C-1) e^-t)
+    for t in (1.0, 10.0, 50.0):
+        z = np.zeros((N, C), dtype=np.float32); z[np.arange(N), labels] = t
+        # (the stable form adds and subtracts t: absolute accuracy of a few ulp of t; the mean over
+        # 1000 rows adds a relative 1e-14)
+        assert oracle.cross_entropy(z, labels) == pytest.approx(math.log1p((C - 1) * math.exp(-t)), rel=1e-13, abs=1e-14)
+    # ... and on a wrong class: loss = t + log(1 + (C-1) e^-t)
+    z = np.zeros((N, C), dtype=np.float32); z[np.arange(N), (labels + 1) % C] = 10.0
+    assert oracle.cross_entropy(z, labels) == pytest.approx(10.0 + math.log1p((C - 1) * math.exp(-10.0)), rel=1e-14)
+    # huge logits do not overflow (the stable form)
+    z = np.full((N, C), 3e38, dtype=np.float32)
+    assert oracle.cross_entropy(z, labels) == pytest.approx(math.log(C), rel=1e-14)
+    assert oracle.cross_entropy(np.zeros((0, 5), np.float32), np.zeros(0, np.int32)) == 0.0
+    assert math.isnan(oracle.cross_entropy(np.zeros((3, 5), np.float32), np.array([0, 5, 1], np.int32)))
+
+
+def test_cross_entropy_against_60_digit_decimal_arithmetic_and_mean_over_rows():
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    N, C = 23, 11
+    z = synth.normal(50, "z", N, C) * np.float32(4.0)
+    labels = (np.arange(N) * 5 % C).astype(np.int32)
+    tot = Decimal(0)
+    for j in range(N):
+        tot += sum(Decimal(float(v)).exp() for v in z[j]).ln() - Decimal(float(z[j, labels[j]]))
+    assert oracle.cross_entropy(z, labels) == pytest.approx(float(tot / N), rel=1e-14)
+    # the mean: doubling the batch with the same rows changes nothing; a single row is its own loss
+    assert oracle.cross_entropy(np.vstack([z, z]), np.concatenate([labels, labels])) == pytest.approx(float(tot / N), rel=1e-14)
+    one = oracle.cross_entropy(z[3:4], labels[3:4])
+    assert one == pytest.approx(float(sum(Decimal(float(v)).exp() for v in z[3]).ln() - Decimal(float(z[3, labels[3]]))), rel=1e-14)
+    # the label picks the column: moving it changes the loss by the logit difference
+    l2 = labels.copy(); l2[0] = (l2[0] + 3) % C
+    d = oracle.cross_entropy(z, l2) - oracle.cross_entropy(z, labels)
+    assert d == pytest.approx((float(z[0, labels[0]]) - float(z[0, l2[0]])) / N, abs=1e-14)
+
+
+def test_layernorm_invariants_and_closed_forms():
+    rows, L = 5, 4099
+    x = synth.normal(60, "x", rows, L) * np.float32(3.0) + np.float32(7.0)
+    y = oracle.layernorm(x, eps=0.0)
+    assert y.shape == x.shape and y.dtype == np.float64
+    assert np.allclose(y.mean(axis=1), 0.0, atol=1e-13)
+    assert np.allclose((y * y).mean(axis=1), 1.0, rtol=1e-13)                     # biased variance: divide by L
+    # affine invariance: LayerNorm(a x + b) = sign(a) LayerNorm(x) when eps = 0 (powers of two keep x exact)
+    y2 = oracle.layernorm(x * np.float32(-4.0), eps=0.0)
+    assert np.allclose(y2, -y, rtol=1e-12, atol=1e-12)
+    # rows are independent
+    assert np.array_equal(oracle.layernorm(x[2:3], eps=0.0)[0], y[2])
+    # two-point row: (-1, +1) exactly, then with eps: 1 / sqrt(1 + eps)
+    t = np.array([[3.0, 5.0]], dtype=np.float32)
+    assert np.array_equal(oracle.layernorm(t, eps=0.0), [[-1.0, 1.0]])
+    assert oracle.layernorm(t, eps=3.0)[0, 1] == 0.5
+    assert oracle.layernorm(t)[0, 1] == pytest.approx(1.0 / math.sqrt(1.0 + 1e-5), rel=1e-15)   # default eps 1e-5
+    # constant row: zero deviations, finite because of eps
+    assert np.array_equal(oracle.layernorm(np.full((1, 9), 2.5, np.float32)), np.zeros((1, 9)))
+    # arithmetic progression 0..L-1: mean (L-1)/2, variance (L^2-1)/12
+    ap = np.arange(1001, dtype=np.float32)[None, :]
+    ya = oracle.layernorm(ap, eps=0.0)
+    assert ya[0, 0] == pytest.approx(-500.0 / math.sqrt((1001 ** 2 - 1) / 12.0), rel=1e-14)
+    assert ya[0, 500] == 0.0
+
+
+def test_layernorm_against_exact_rational_statistics():
+    L = 257
+    x = synth.uniform(61, "x", 1, L) * np.float32(100.0)
+    xs = [Fraction(float(v)) for v in x[0]]
+    mean = sum(xs) / L
+    var = sum((v - mean) ** 2 for v in xs) / L
+    y = oracle.layernorm(x, eps=0.0)[0]
+    for i in (0, 1, 100, 256):
+        assert y[i] == pytest.approx(float(xs[i] - mean) / math.sqrt(float(var)), rel=1e-13)
+    # large offset, small spread: the two-pass variance does not cancel
+    big = (np.float32(1e6) + synth.uniform(62, "x", 1, L)).astype(np.float32)
+    xb = [Fraction(float(v)) for v in big[0]]
+    mb = sum(xb) / L; vb = sum((v - mb) ** 2 for v in xb) / L
+    yb = oracle.layernorm(big, eps=0.0)[0]
+    assert yb[7] == pytest.approx(float(xb[7] - mb) / math.sqrt(float(vb)), rel=1e-10)
