@@ -199,6 +199,31 @@ typedef enum { OPTIML_RED_SUM = 0, OPTIML_RED_DOT = 1, OPTIML_RED_MSE = 2 } opti
 int optiml_elementwise(int64_t n, const float *x, float *y, int op, void *stream);
 int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out, void *stream);
 
+/*
+ * Row-wise siblings from the paper's Table 4, float arrays, DEVICE pointers.
+ *
+ * optiml_cross_entropy (task 17): *loss (one float, DEVICE pointer) = (1/N) sum_j
+ * ( log(sum_k exp(z[j][k])) - z[j][labels[j]] ) for logits z[j][k] at logits[j*ld + k], ld >= C,
+ * and labels[j] in [0, C) (32-bit integers).  Evaluated in the stable form with the row maximum;
+ * exponentials and the running sum in fp32 (about 2e-7 of absolute error on a row's loss), row
+ * losses and their mean in fp64 in a fixed order, one rounding to float.  A label outside
+ * [0, C) makes the result NaN.  N == 0 writes 0.  Uses the per-device workspace; two kernels.
+ *
+ * optiml_layernorm (task 4): every row of `len` values (one sample with all its features) is
+ * replaced by (x - mean) / sqrt(var + eps), mean and biased variance (divide by len) of that
+ * row; no scale or shift (the task names none; eps is the caller's, 1e-5 in common use).
+ * x[r*len + i] -> y[r*len + i]; y may be x itself.  Statistics and the normalisation are
+ * evaluated in fp64 and rounded once to float.  Rows longer than 8192 use the per-device
+ * workspace and two kernels per group of rows of about 64 MiB.  rows == 0 or len == 0 writes
+ * nothing.
+ *
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, C < 1, ld < C, NULL loss, NULL
+ * logits / labels / x / y with work to do, eps negative or NaN.
+ */
+int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, const int32_t *labels, float *loss,
+                         void *stream);
+int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream);
+
 /* Human-readable text for a status code; static storage. */
 const char *optiml_status_string(int status);
 

@@ -34,6 +34,8 @@ SIGNATURES = {
     "optiml_copy_bytes": (_int, [_vp, _vp, _i64, _vp]),
     "optiml_elementwise": (_int, [_i64, _vp, _vp, _int, _vp]),
     "optiml_reduce": (_int, [_i64, _vp, _vp, _int, _vp, _vp]),
+    "optiml_cross_entropy": (_int, [_i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "optiml_layernorm": (_int, [_i64, _i64, _vp, _vp, C.c_float, _vp]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -157,6 +159,14 @@ def optiml_elementwise(n, x, y, op, stream=None):
 
 def optiml_reduce(n, x, y, op, out, stream=None):
     return _check(lib().optiml_reduce(n, _addr(x), _addr(y), op, _addr(out), _stream(stream)))
+
+
+def optiml_cross_entropy(N, Cn, logits, ld, labels, loss, stream=None):
+    return _check(lib().optiml_cross_entropy(N, Cn, _addr(logits), ld, _addr(labels), _addr(loss), _stream(stream)))
+
+
+def optiml_layernorm(rows, length, x, y, eps, stream=None):
+    return _check(lib().optiml_layernorm(rows, length, _addr(x), _addr(y), eps, _stream(stream)))
 
 
 def optiml_status_string(status):

@@ -350,6 +350,32 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
     return OPTIML_OK;
 }
 
+int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, const int32_t *labels, float *loss,
+                         void *stream)
+{
+    if (N < 0 || C < 1 || ld < C || !loss) return OPTIML_ERR_INVALID_ARG;
+    if (N > 0 && (!logits || !labels)) return OPTIML_ERR_INVALID_ARG;
+    hipError_t e = optiml::launch_cross_entropy(N, C, logits, ld, labels, loss, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
+int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream)
+{
+    if (rows < 0 || len < 0 || !(eps >= 0.0f)) return OPTIML_ERR_INVALID_ARG;
+    if (rows == 0 || len == 0) return OPTIML_OK;
+    if (!x || !y) return OPTIML_ERR_INVALID_ARG;
+    hipError_t e = optiml::launch_layernorm(rows, len, x, y, eps, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
 const char *optiml_status_string(int status)
 {
     switch (status) {

@@ -46,6 +46,10 @@ hipError_t workspace(size_t bytes, void **ptr);
 // streaming siblings (kernel_streams.hip); arguments already validated
 hipError_t launch_elementwise(int64_t n, const float *x, float *y, int op, hipStream_t stream);
 hipError_t launch_reduce(int64_t n, const float *x, const float *y, int op, float *out, hipStream_t stream);
+// row-wise siblings (kernel_rows.hip)
+hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld, const int *labels, float *loss,
+                                hipStream_t stream);
+hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
 
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;

@@ -1,0 +1,409 @@
+// Row-wise bandwidth-bound siblings on fp32 arrays (paper Table 4): categorical cross-entropy
+// (task 17: mean over rows of log(sum_k exp(z_jk)) - z_{j, y_j}) and LayerNorm over all features
+// of a sample (task 4: (x - mean) / sqrt(var + eps) per row, biased variance, no scale / shift).
+//
+// Both read every input byte once when they can and walk memory in block order (see
+// kernel_streams.hip for why that matters on this board).
+//
+// Cross-entropy.  A wave owns a row at a time; a lane holds up to 32 logits of a 2048-column
+// slice in registers, takes the slice's maximum, and folds the slice into a running (max, sum)
+// pair: sum = sum * exp(max_old - max_new) + sum_k exp(z_k - max_new), one exponential per
+// logit.  Lanes are merged with the same rule by a butterfly; the row's loss is
+// log(sum) - (z_y - max) in fp64; row losses are added in fp64 in a fixed order (wave, then
+// workgroup, then a second small kernel over the per-workgroup partials).  For fewer than 64
+// classes a lane owns a whole row instead.
+//
+// LayerNorm.  Rows of at most 8192 features: one workgroup per row keeps the row in registers
+// (one read, one write).  Longer rows are cut into chunks of 32,768 features, one workgroup each:
+// a first kernel leaves per-chunk sums of d = x - x_row[0] and d^2 in fp64 (shifting by the
+// row's first element keeps the variance from cancelling when |mean| >> std), a second kernel
+// adds a row's chunk sums in chunk order and normalises its chunk.  The host runs the two
+// kernels over groups of rows of about 64 MiB, so that the second read of a group comes from
+// the 256 MiB Infinity Cache rather than from HBM.
+#include "common.hpp"
+#include "epilogue.hpp"
+
+namespace optiml {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kThreads = 256;
+
+bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+// ---- cross-entropy ---------------------------------------------------------------------------
+
+struct MaxSum {
+    float m, s;
+};
+
+__device__ __forceinline__ MaxSum merge(MaxSum a, MaxSum b)
+{
+    if (b.s == 0.0f) return a;               // a side that has seen nothing (a real side has s >= 1)
+    if (a.s == 0.0f) return b;
+    const float m = a.m > b.m ? a.m : b.m;
+    // exp_neg(x) = exp(-x)
+    return MaxSum{m, a.s * exp_neg(m - a.m) + b.s * exp_neg(m - b.m)};
+}
+
+// loss of one row from the merged (max, sum), in fp64; NaN for a label outside [0, C)
+__device__ __forceinline__ double row_loss(MaxSum r, const float *row, int64_t C, int label)
+{
+    if (label < 0 || label >= C) return __builtin_nan("");
+    return log((double)r.s) - ((double)row[label] - (double)r.m);
+}
+
+// WAVE_ROWS: a wave per row (C >= 64); rows_per_group rows per workgroup, taken by its 4 waves in turn.
+// VEC: rows are 16-byte aligned (base aligned, ld % 4 == 0).
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void ce_wave_rows_kernel(const float *__restrict__ z, int64_t ld,
+                                                                const int *__restrict__ labels, int64_t N, int64_t C,
+                                                                int rows_per_group, double *__restrict__ partial)
+{
+    __shared__ double wave_sum[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * rows_per_group;
+    double acc = 0.0;
+    for (int64_t j = row0 + wave; j < row0 + rows_per_group && j < N; j += kThreads / 64) {
+        const float *row = z + j * ld;
+        MaxSum r{-__builtin_inff(), 0.0f};
+        if (VEC) {
+            constexpr int U = 8;                          // 8 x 64 lanes x 4 = 2048 columns per slice
+            const int64_t c4 = C / 4;
+            const floatx4 *row4 = reinterpret_cast<const floatx4 *>(row);
+            for (int64_t base = lane; base < c4; base += U * 64) {
+                floatx4 v[U];
+                float mx = -__builtin_inff();
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool in = base + u * 64 < c4;
+                    v[u] = in ? __builtin_nontemporal_load(row4 + base + u * 64)
+                              : floatx4{-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff()};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) mx = v[u][e] > mx ? v[u][e] : mx;
+                }
+                if (mx == -__builtin_inff()) continue;     // nothing (or only -inf) in this lane's part
+                const float m = r.m > mx ? r.m : mx;
+                float s = r.s * exp_neg(m - r.m);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s += exp_neg(m - v[u][e]);
+                r = MaxSum{m, s};
+            }
+            for (int64_t k = 4 * c4 + lane; k < C; k += 64) r = merge(r, MaxSum{row[k], 1.0f});
+        } else {
+            for (int64_t k = lane; k < C; k += 64) r = merge(r, MaxSum{row[k], 1.0f});
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            MaxSum o{__shfl_xor(r.m, off, 64), __shfl_xor(r.s, off, 64)};
+            r = merge(r, o);
+        }
+        if (lane == 0) acc += row_loss(r, row, C, labels[j]);
+    }
+    if (lane == 0) wave_sum[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = wave_sum[0];
+        for (int w = 1; w < kThreads / 64; ++w) t += wave_sum[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
+// C < 64: a lane per row; workgroup b takes rows [256 b, 256 b + 256)
+__global__ __launch_bounds__(kThreads) void ce_lane_rows_kernel(const float *__restrict__ z, int64_t ld,
+                                                                const int *__restrict__ labels, int64_t N, int64_t C,
+                                                                double *__restrict__ partial)
+{
+    __shared__ double wave_sum[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    double loss = 0.0;
+    if (j < N) {
+        const float *row = z + j * ld;
+        float m = row[0];
+        for (int64_t k = 1; k < C; ++k) m = row[k] > m ? row[k] : m;
+        float s = 0.0f;
+        for (int64_t k = 0; k < C; ++k) s += exp_neg(m - row[k]);
+        loss = row_loss(MaxSum{m, s}, row, C, labels[j]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) loss += __shfl_xor(loss, off, 64);
+    if (lane == 0) wave_sum[wave] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = wave_sum[0];
+        for (int w = 1; w < kThreads / 64; ++w) t += wave_sum[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
+// out = (sum of the partials, thread t adding partials t, t + 1024, ... in order, then a fixed
+// tree) / N
+constexpr int kFinalThreads = 1024;
+__global__ __launch_bounds__(kFinalThreads) void mean_of_partials_kernel(const double *__restrict__ partial, int count,
+                                                                         int64_t N, float *__restrict__ out)
+{
+    __shared__ double tree[kFinalThreads];
+    double c = 0.0;
+    for (int i = threadIdx.x; i < count; i += kFinalThreads) c += partial[i];
+    tree[threadIdx.x] = c;
+    __syncthreads();
+    for (int half = kFinalThreads / 2; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) tree[threadIdx.x] += tree[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = (float)(N > 0 ? tree[0] / (double)N : 0.0);
+}
+
+// ---- LayerNorm -------------------------------------------------------------------------------
+
+// sum over the workgroup of two fp64 values, fixed order (butterfly in the wave, waves in order);
+// every thread gets the result
+__device__ __forceinline__ void block_sum2(double &a, double &b, double (*scratch)[2])
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        a += __shfl_xor(a, off, 64);
+        b += __shfl_xor(b, off, 64);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();                         // scratch may still be read from a previous call
+    if (lane == 0) { scratch[wave][0] = a; scratch[wave][1] = b; }
+    __syncthreads();
+    a = scratch[0][0]; b = scratch[0][1];
+    for (int w = 1; w < kThreads / 64; ++w) { a += scratch[w][0]; b += scratch[w][1]; }
+}
+
+// rows of at most 8192 features, one workgroup per row, row held in registers (VEC) or re-read (scalar)
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                   int64_t len, double eps)
+{
+    __shared__ double scratch[kThreads / 64][2];
+    const float *xr = x + (int64_t)blockIdx.x * len;
+    float *yr = y + (int64_t)blockIdx.x * len;
+    const double inv_len = 1.0 / (double)len;
+    if (VEC) {
+        constexpr int U = 8;
+        const int64_t n4 = len / 4;                      // len % 4 == 0 here
+        const floatx4 *x4 = reinterpret_cast<const floatx4 *>(xr);
+        floatx4 v[U];
+        double s = 0.0, unused = 0.0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = threadIdx.x + u * kThreads;
+            v[u] = i < n4 ? __builtin_nontemporal_load(x4 + i) : floatx4{0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s += (double)v[u][e];
+        }
+        block_sum2(s, unused, scratch);
+        const double mean = s * inv_len;
+        double q = 0.0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = threadIdx.x + u * kThreads;
+            if (i < n4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q += ((double)v[u][e] - mean) * ((double)v[u][e] - mean);
+            }
+        }
+        unused = 0.0;
+        block_sum2(q, unused, scratch);
+        const double rstd = 1.0 / sqrt(q * inv_len + eps);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = threadIdx.x + u * kThreads;
+            if (i < n4) {
+                floatx4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (float)(((double)v[u][e] - mean) * rstd);
+                __builtin_nontemporal_store(r, reinterpret_cast<floatx4 *>(yr) + i);
+            }
+        }
+    } else {
+        double s = 0.0, unused = 0.0;
+        for (int64_t i = threadIdx.x; i < len; i += kThreads) s += (double)xr[i];
+        block_sum2(s, unused, scratch);
+        const double mean = s * inv_len;
+        double q = 0.0;
+        for (int64_t i = threadIdx.x; i < len; i += kThreads) q += ((double)xr[i] - mean) * ((double)xr[i] - mean);
+        unused = 0.0;
+        block_sum2(q, unused, scratch);
+        const double rstd = 1.0 / sqrt(q * inv_len + eps);
+        for (int64_t i = threadIdx.x; i < len; i += kThreads) yr[i] = (float)(((double)xr[i] - mean) * rstd);
+    }
+}
+
+constexpr int64_t kChunk = 32768;                         // features per workgroup for long rows
+
+// long rows, first kernel: stats[(row * chunks + c) * 2 + {0, 1}] = sum of d, sum of d^2 over the
+// chunk, d = x - x_row[0].  Plain loads: the data is meant to stay in cache for the second kernel.
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *__restrict__ x, int64_t len, int64_t chunks,
+                                                                   double *__restrict__ stats)
+{
+    __shared__ double scratch[kThreads / 64][2];
+    const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
+    const float *xr = x + row * len;
+    const double pivot = (double)xr[0];
+    const int64_t lo = c * kChunk, hi = lo + kChunk < len ? lo + kChunk : len;
+    double s = 0.0, q = 0.0;
+    if (VEC) {
+        const floatx4 *x4 = reinterpret_cast<const floatx4 *>(xr);
+        for (int64_t base = lo / 4 + threadIdx.x; base < hi / 4; base += 8 * kThreads) {
+            floatx4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + u * kThreads;
+                v[u] = i < hi / 4 ? x4[i] : floatx4{(float)pivot, (float)pivot, (float)pivot, (float)pivot};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const double d = (double)v[u][e] - pivot;
+                    s += d;
+                    q += d * d;
+                }
+        }
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            const double d = (double)xr[i] - pivot;
+            s += d;
+            q += d * d;
+        }
+    }
+    block_sum2(s, q, scratch);
+    if (threadIdx.x == 0) {
+        stats[2 * blockIdx.x] = s;
+        stats[2 * blockIdx.x + 1] = q;
+    }
+}
+
+// long rows, second kernel: add the row's chunk sums in chunk order, normalise this chunk
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void layernorm_apply_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                   int64_t len, int64_t chunks,
+                                                                   const double *__restrict__ stats, double eps)
+{
+    const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
+    const float *xr = x + row * len;
+    float *yr = y + row * len;
+    double s = 0.0, q = 0.0;
+    for (int64_t i = 0; i < chunks; ++i) {
+        s += stats[2 * (row * chunks + i)];
+        q += stats[2 * (row * chunks + i) + 1];
+    }
+    const double inv_len = 1.0 / (double)len;
+    const double dm = s * inv_len;                        // mean - pivot
+    const double mean = (double)xr[0] + dm;
+    double var = q * inv_len - dm * dm;                   // shifted-data formula
+    var = var > 0.0 ? var : 0.0;
+    const double rstd = 1.0 / sqrt(var + eps);
+    const int64_t lo = c * kChunk, hi = lo + kChunk < len ? lo + kChunk : len;
+    if (VEC) {
+        const floatx4 *x4 = reinterpret_cast<const floatx4 *>(xr);
+        floatx4 *y4 = reinterpret_cast<floatx4 *>(yr);
+        for (int64_t base = lo / 4 + threadIdx.x; base < hi / 4; base += 8 * kThreads) {
+            floatx4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + u * kThreads;
+                v[u] = i < hi / 4 ? __builtin_nontemporal_load(x4 + i) : floatx4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + u * kThreads;
+                if (i < hi / 4) {
+                    floatx4 r;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[e] = (float)(((double)v[u][e] - mean) * rstd);
+                    __builtin_nontemporal_store(r, y4 + i);
+                }
+            }
+        }
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) yr[i] = (float)(((double)xr[i] - mean) * rstd);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld, const int *labels, float *loss,
+                                hipStream_t stream)
+{
+    int64_t grid = 0;
+    int rows_per_group = 0;
+    if (N > 0) {
+        if (C < 64) {
+            grid = (N + kThreads - 1) / kThreads;
+        } else {
+            // about 64 KiB of logits per workgroup, a multiple of its 4 waves
+            int64_t r = (16384 + C - 1) / C;
+            r = (r + 3) / 4 * 4;
+            rows_per_group = (int)(r < 4 ? 4 : (r > 1024 ? 1024 : r));
+            grid = (N + rows_per_group - 1) / rows_per_group;
+        }
+    }
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    void *ws = nullptr;
+    hipError_t e = workspace(sizeof(double) * (size_t)(grid > 0 ? grid : 1), &ws);
+    if (e != hipSuccess) return e;
+    double *partial = static_cast<double *>(ws);
+    if (grid > 0) {
+        if (C < 64) {
+            hipLaunchKernelGGL(ce_lane_rows_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, z, ld, labels, N, C,
+                               partial);
+        } else if (aligned16(z) && ld % 4 == 0) {
+            hipLaunchKernelGGL(ce_wave_rows_kernel<true>, dim3((unsigned)grid), dim3(kThreads), 0, stream, z, ld, labels, N,
+                               C, rows_per_group, partial);
+        } else {
+            hipLaunchKernelGGL(ce_wave_rows_kernel<false>, dim3((unsigned)grid), dim3(kThreads), 0, stream, z, ld, labels,
+                               N, C, rows_per_group, partial);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(mean_of_partials_kernel, dim3(1), dim3(kFinalThreads), 0, stream, partial, (int)grid, N, loss);
+    return hipGetLastError();
+}
+
+hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream)
+{
+    const bool vec = aligned16(x) && aligned16(y) && len % 4 == 0;
+    if (len <= 8192) {
+        if (rows > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (vec) hipLaunchKernelGGL(layernorm_short_kernel<true>, dim3((unsigned)rows), dim3(kThreads), 0, stream, x, y, len, (double)eps);
+        else hipLaunchKernelGGL(layernorm_short_kernel<false>, dim3((unsigned)rows), dim3(kThreads), 0, stream, x, y, len, (double)eps);
+        return hipGetLastError();
+    }
+    const int64_t chunks = (len + kChunk - 1) / kChunk;
+    // groups of rows of about 64 MiB: statistics, then normalisation while the group is still in cache
+    int64_t group = (int64_t(64) << 20) / (len * 4);
+    group = group < 1 ? 1 : group;
+    if (group * chunks > 0x7fffffffLL) return hipErrorInvalidValue;
+    void *ws = nullptr;
+    hipError_t e = workspace(sizeof(double) * 2 * (size_t)(group * chunks), &ws);
+    if (e != hipSuccess) return e;
+    double *stats = static_cast<double *>(ws);
+    for (int64_t r0 = 0; r0 < rows; r0 += group) {
+        const int64_t nr = rows - r0 < group ? rows - r0 : group;
+        const dim3 grid((unsigned)(nr * chunks)), block(kThreads);
+        const float *xg = x + r0 * len;
+        float *yg = y + r0 * len;
+        if (vec) {
+            hipLaunchKernelGGL(layernorm_stats_kernel<true>, grid, block, 0, stream, xg, len, chunks, stats);
+            hipLaunchKernelGGL(layernorm_apply_kernel<true>, grid, block, 0, stream, xg, yg, len, chunks, stats, (double)eps);
+        } else {
+            hipLaunchKernelGGL(layernorm_stats_kernel<false>, grid, block, 0, stream, xg, len, chunks, stats);
+            hipLaunchKernelGGL(layernorm_apply_kernel<false>, grid, block, 0, stream, xg, yg, len, chunks, stats, (double)eps);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace optiml

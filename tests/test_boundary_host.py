@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 14
+    assert len(names) == 16
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -96,6 +96,24 @@ def test_streaming_entry_points_validate_on_the_host():
     assert L.optiml_reduce(8, None, None, 0, P, None) == ob.ERR_INVALID_ARG
     assert L.optiml_reduce(8, P, None, 1, P, None) == ob.ERR_INVALID_ARG           # the dot product reads y
     assert L.optiml_reduce(8, P, None, 2, P, None) == ob.ERR_INVALID_ARG
+
+
+def test_row_wise_entry_points_validate_on_the_host():
+    L = ob.lib()
+    assert L.optiml_cross_entropy(-1, 8, P, 8, P, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_cross_entropy(4, 0, P, 8, P, P, None) == ob.ERR_INVALID_ARG       # no classes
+    assert L.optiml_cross_entropy(4, 8, P, 7, P, P, None) == ob.ERR_INVALID_ARG       # ld shorter than a row
+    assert L.optiml_cross_entropy(4, 8, P, 8, P, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_cross_entropy(4, 8, None, 8, P, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_cross_entropy(4, 8, P, 8, None, P, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(-1, 8, P, P, 1e-5, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(4, -8, P, P, 1e-5, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(4, 8, P, P, -1.0, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(4, 8, P, P, float("nan"), None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(4, 8, None, P, 1e-5, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(4, 8, P, None, 1e-5, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_layernorm(0, 8, None, None, 1e-5, None) == ob.OK
+    assert L.optiml_layernorm(4, 0, None, None, 1e-5, None) == ob.OK
 
 
 def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bias=P):
