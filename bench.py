@@ -8,7 +8,8 @@ HBM before the timed region; two rotating buffer sets so that consecutive steps 
 re-read the same bytes from cache).  The default workload is the memory-bound skinny
 configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and the
 streaming siblings (element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats: --workload
-s_relu, s_sigmoid, s_sum, s_dot, s_mse) and adds them under "workloads".  One JSON line is
+s_relu, s_sigmoid, s_sum, s_dot, s_mse; cross-entropy and LayerNorm: s_ce, s_ln_sample,
+s_ln_token) and adds them under "workloads".  One JSON line is
 printed.
 
 The "roofline" object prices the dominant kernel of the workload against the published
@@ -36,6 +37,9 @@ DTYPE_NAME = {0: "f32", 1: "bf16"}
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
            "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0)}
 STREAM_N = 1 << 28
+# row-wise siblings: cross-entropy on [8192, 32768] logits; LayerNorm on 64 samples of 64 x 256 x 256
+# features (the task's 4-D shape, every feature of a sample is one row) and on 32768 rows of 8192
+ROWS = {"s_ce": (8192, 32768), "s_ln_sample": (64, 64 * 256 * 256), "s_ln_token": (32768, 8192)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB per dispatch, scaled by what the same counters read for the library's 1 GiB copy
@@ -47,6 +51,7 @@ RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
 RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp",
              "common.hpp")
 STREAMS_SRC = ("kernel_streams.hip", "epilogue.hpp", "common.hpp")
+ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp", "common.hpp")
 TRAFFIC = {
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
         {"bytes": int((528469 * 2.0 + 2048 + 1081.5 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "877c25d5c39e2063"},
@@ -58,6 +63,12 @@ TRAFFIC = {
         {"bytes": int((67449.1 * 2.0 + 262866) * 1024), "files": RINGP_SRC, "src": "a856d6cc76f71e91"},
     ("s_sigmoid", "s_sigmoid"):
         {"bytes": int((524329 * 2.0 + 1048580) * 1024), "files": STREAMS_SRC, "src": "b7c0f379f99be1d5"},
+    ("s_ce", "s_ce"):
+        {"bytes": int(((524969 + 9.94) * 2.0 + 64.16 + 0.03) * 1024), "files": ROWS_SRC, "src": "5d15dc677cfbacc5"},
+    ("s_ln_sample", "s_ln_sample"):        # four groups of 256 MiB: statistics kernel + normalising kernel each
+        {"bytes": int(4 * ((131109 + 131373) * 2.0 + 128 + 262350) * 1024), "files": ROWS_SRC, "src": "5d15dc677cfbacc5"},
+    ("s_ln_token", "s_ln_token"):
+        {"bytes": int((524323 * 2.0 + 1048770) * 1024), "files": ROWS_SRC, "src": "5d15dc677cfbacc5"},
     ("s_dot", "s_dot"):
         {"bytes": int(((1048650 + 33.08) * 2.0 + 256.55 + 0.03) * 1024), "files": STREAMS_SRC, "src": "b7c0f379f99be1d5"},
 }
@@ -231,13 +242,73 @@ def main():
             res["parity_rel_err"] = float(f"{err:.3e}")
         return res
 
-    if args.workload in STREAMS:
-        r = time_stream(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    def time_rows(name, steps, warmup, with_oracle):
+        """Cross-entropy or LayerNorm on a seeded normal array of 1 GiB."""
+        rows, cols = ROWS[name]
+        hx = synth.normal(8, "x", rows, cols, 0.5, 2.0)
+        xd = torch.from_numpy(hx).cuda()
+        if name == "s_ce":
+            hl = (np.arange(rows, dtype=np.int64) * 7919 % cols).astype(np.int32)
+            ld_ = torch.from_numpy(hl).cuda()
+            od = torch.empty(1, dtype=torch.float32, device="cuda")
+            step = lambda: ob.optiml_cross_entropy(rows, cols, xd, cols, ld_, od)
+            nbytes = 4 * rows * cols + 4 * rows + 4
+        else:
+            od = torch.empty_like(xd)
+            step = lambda: ob.optiml_layernorm(rows, cols, xd, od, 1e-5)
+            nbytes = 8 * rows * cols
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+        ms, kernel_ms = max(wall_ms, dev_ms) / steps, dev_ms / steps
+        gbs = nbytes / (kernel_ms * 1e-3) / 1e9
+        tr = TRAFFIC.get((name, name))
+        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash(tr["files"]) else None
+        res = {"workload": name, "variant": name, "rows": rows, "cols": cols, "ms_per_step": round(ms, 5),
+               "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 2), "hbm_frac": round(gbs / PEAK_HBM_GBS, 4), "dtype": "f32",
+               "roofline": {"bound": "hbm", "achieved": round(gbs, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "kernel": name,
+                            "kernel_ms": round(kernel_ms, 5)}}
+        if with_oracle:
+            import oracle
+            t0 = time.perf_counter()
+            if name == "s_ce":
+                ref = oracle.cross_entropy(hx, hl)
+                secs = time.perf_counter() - t0
+                err = abs(float(od.item()) - ref)
+                full, sample = secs, "whole workload"
+            else:
+                m = max(1, rows // 16)                           # bounded sample: the first sixteenth of the rows
+                ref = oracle.layernorm(hx[:m], 1e-5)
+                secs = time.perf_counter() - t0
+                err = float(np.max(np.abs(od[:m].cpu().numpy().astype(np.float64) - ref)))
+                full, sample = secs * (rows / m), f"first {m} of {rows} rows"
+            res["cpu_baseline"] = {"value": float(f"{nbytes / 1e9 / full:.4g}"), "unit": "GB/s",
+                                   "cores": oracle.num_threads(), "kind": "oracle", "sample": sample,
+                                   "seconds": round(secs, 3)}
+            res["parity_abs_err"] = float(f"{err:.3e}")
+        return res
+
+    if args.workload in STREAMS or args.workload in ROWS:
+        if args.workload in ROWS:
+            r = time_rows(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+            r["n"] = r["rows"] * r["cols"]
+        else:
+            r = time_stream(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
         out = {"metric": "GB/s (algorithmic bytes) of " + args.workload[2:], "value": r["GB/s"], "unit": "GB/s",
                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
                "config": {"workload": args.workload, "n": r["n"]}, "GB/s": r["GB/s"], "roofline": r["roofline"]}
-        for k in ("cpu_baseline", "parity_rel_err"):
+        for k in ("cpu_baseline", "parity_rel_err", "parity_abs_err"):
             if k in r:
                 out[k] = r[k]
         print(json.dumps(out))
@@ -307,6 +378,9 @@ def main():
             out["workloads"][name] = r
         for name in STREAMS:
             out["workloads"][name] = time_stream(name, args.steps, args.warmup, False)
+            torch.cuda.empty_cache()
+        for name in ROWS:
+            out["workloads"][name] = time_rows(name, args.steps, args.warmup, False)
             torch.cuda.empty_cache()
 
     print(json.dumps(out))

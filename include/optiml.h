@@ -214,7 +214,7 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
  * row; no scale or shift (the task names none; eps is the caller's, 1e-5 in common use).
  * x[r*len + i] -> y[r*len + i]; y may be x itself.  Statistics and the normalisation are
  * evaluated in fp64 and rounded once to float.  Rows longer than 8192 use the per-device
- * workspace and two kernels per group of rows of about 64 MiB.  rows == 0 or len == 0 writes
+ * workspace and two kernels per group of rows of about 256 MiB (x is then read twice).  rows == 0 or len == 0 writes
  * nothing.
  *
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, C < 1, ld < C, NULL loss, NULL

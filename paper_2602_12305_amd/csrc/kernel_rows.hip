@@ -14,12 +14,13 @@
 // classes a lane owns a whole row instead.
 //
 // LayerNorm.  Rows of at most 8192 features: one workgroup per row keeps the row in registers
-// (one read, one write).  Longer rows are cut into chunks of 32,768 features, one workgroup each:
+// (one read, one write).  Longer rows are cut into chunks of 16,384 features, one workgroup each:
 // a first kernel leaves per-chunk sums of d = x - x_row[0] and d^2 in fp64 (shifting by the
 // row's first element keeps the variance from cancelling when |mean| >> std), a second kernel
-// adds a row's chunk sums in chunk order and normalises its chunk.  The host runs the two
-// kernels over groups of rows of about 64 MiB, so that the second read of a group comes from
-// the 256 MiB Infinity Cache rather than from HBM.
+// adds a row's chunk sums in a fixed order and normalises its chunk: x is read twice (12 bytes
+// per element against 8 algorithmic).  Running the two kernels over groups of rows small enough
+// for the 256 MiB Infinity Cache was measured and bought nothing (4.1 - 4.3 TB/s of algorithmic
+// bytes for any group size from 32 MiB up), so groups are 256 MiB only to bound the workspace.
 #include "common.hpp"
 #include "epilogue.hpp"
 
@@ -236,13 +237,12 @@ __global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *
     }
 }
 
-constexpr int64_t kChunk = 32768;                         // features per workgroup for long rows
 
 // long rows, first kernel: stats[(row * chunks + c) * 2 + {0, 1}] = sum of d, sum of d^2 over the
 // chunk, d = x - x_row[0].  Plain loads: the data is meant to stay in cache for the second kernel.
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *__restrict__ x, int64_t len, int64_t chunks,
-                                                                   double *__restrict__ stats)
+                                                                   int64_t kChunk, double *__restrict__ stats)
 {
     __shared__ double scratch[kThreads / 64][2];
     const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
@@ -282,20 +282,22 @@ __global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *
     }
 }
 
-// long rows, second kernel: add the row's chunk sums in chunk order, normalise this chunk
+// long rows, second kernel: add the row's chunk sums (fixed order), normalise this chunk
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_apply_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                                   int64_t len, int64_t chunks,
+                                                                   int64_t len, int64_t chunks, int64_t kChunk,
                                                                    const double *__restrict__ stats, double eps)
 {
     const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
     const float *xr = x + row * len;
     float *yr = y + row * len;
-    double s = 0.0, q = 0.0;
-    for (int64_t i = 0; i < chunks; ++i) {
+    __shared__ double scratch[kThreads / 64][2];
+    double s = 0.0, q = 0.0;                              // thread t: chunks t, t + 256, ... in order
+    for (int64_t i = threadIdx.x; i < chunks; i += kThreads) {
         s += stats[2 * (row * chunks + i)];
         q += stats[2 * (row * chunks + i) + 1];
     }
+    block_sum2(s, q, scratch);
     const double inv_len = 1.0 / (double)len;
     const double dm = s * inv_len;                        // mean - pivot
     const double mean = (double)xr[0] + dm;
@@ -379,9 +381,13 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
         else hipLaunchKernelGGL(layernorm_short_kernel<false>, dim3((unsigned)rows), dim3(kThreads), 0, stream, x, y, len, (double)eps);
         return hipGetLastError();
     }
+    // Chunk and group sizes from a sweep on 64 rows of 4 Mi features: 16 Ki features per workgroup and
+    // groups of 256 MiB gave 4.3 TB/s of algorithmic bytes; 8 - 32 Ki and 32 MiB - everything stayed
+    // within 8 % of that, 16 MiB groups (too few workgroups per launch) fell to 2.9 TB/s.
+    const int64_t kChunk = 16384, group_bytes = int64_t(256) << 20;
     const int64_t chunks = (len + kChunk - 1) / kChunk;
-    // groups of rows of about 64 MiB: statistics, then normalisation while the group is still in cache
-    int64_t group = (int64_t(64) << 20) / (len * 4);
+    // groups of rows: statistics, then normalisation, group by group
+    int64_t group = group_bytes / (len * 4);
     group = group < 1 ? 1 : group;
     if (group * chunks > 0x7fffffffLL) return hipErrorInvalidValue;
     void *ws = nullptr;
@@ -394,11 +400,11 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
         const float *xg = x + r0 * len;
         float *yg = y + r0 * len;
         if (vec) {
-            hipLaunchKernelGGL(layernorm_stats_kernel<true>, grid, block, 0, stream, xg, len, chunks, stats);
-            hipLaunchKernelGGL(layernorm_apply_kernel<true>, grid, block, 0, stream, xg, yg, len, chunks, stats, (double)eps);
+            hipLaunchKernelGGL(layernorm_stats_kernel<true>, grid, block, 0, stream, xg, len, chunks, kChunk, stats);
+            hipLaunchKernelGGL(layernorm_apply_kernel<true>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, (double)eps);
         } else {
-            hipLaunchKernelGGL(layernorm_stats_kernel<false>, grid, block, 0, stream, xg, len, chunks, stats);
-            hipLaunchKernelGGL(layernorm_apply_kernel<false>, grid, block, 0, stream, xg, yg, len, chunks, stats, (double)eps);
+            hipLaunchKernelGGL(layernorm_stats_kernel<false>, grid, block, 0, stream, xg, len, chunks, kChunk, stats);
+            hipLaunchKernelGGL(layernorm_apply_kernel<false>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, (double)eps);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
