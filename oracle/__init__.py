@@ -1,6 +1,7 @@
 """CPU oracle for C = act(A.B + bias) and for its bandwidth-bound siblings (element-wise
-ReLU / sigmoid, sum, dot product, mean squared error, cross-entropy, LayerNorm): ctypes front end of oracle_gemm.c and
-oracle_streams.c.
+ReLU / sigmoid, sum, dot product, mean squared error, cross-entropy, LayerNorm) and
+multi-head self-attention: ctypes front end of oracle_gemm.c, oracle_streams.c and
+oracle_attention.c.
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke entry point and by
 the benchmark's cpu_baseline leg; the product package never imports it, and it
@@ -49,6 +50,8 @@ def lib():
         L.oracle_cross_entropy.argtypes = [i64, i64, vp, vp]
         L.oracle_layernorm.restype = None
         L.oracle_layernorm.argtypes = [i64, i64, vp, C.c_double, vp]
+        L.oracle_mhsa.restype = C.c_int
+        L.oracle_mhsa.argtypes = [i64, i64, i64, i64, vp, vp, vp, C.c_int, vp]
         _lib = L
     return _lib
 
@@ -172,6 +175,22 @@ def layernorm(x, eps=1e-5):
     y = np.empty(x.shape, dtype=np.float64)
     lib().oracle_layernorm(x.shape[0], x.shape[1], _ptr(x), float(eps), _ptr(y))
     return y
+
+
+def mhsa(Q, K, V, heads, dtype=F32):
+    """fp64 multi-head self-attention Concat_i softmax(Q_i K_i^T / sqrt(d_k)) V_i for Q, K, V of shape
+    [batch, N, d_model] (or [N, d_model]) stored as fp32, or as bf16 bit patterns (uint16) with dtype=BF16
+    (Table 4, task 6)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    Q, K, V = (np.ascontiguousarray(a, dtype=want) for a in (Q, K, V))
+    if Q.shape != K.shape or Q.shape != V.shape or Q.ndim not in (2, 3):
+        raise ValueError("Q, K, V of one shape [batch,] N, d_model expected")
+    batch = Q.shape[0] if Q.ndim == 3 else 1
+    N, d_model = Q.shape[-2:]
+    out = np.empty(Q.shape, dtype=np.float64)
+    if lib().oracle_mhsa(batch, N, d_model, heads, _ptr(Q), _ptr(K), _ptr(V), dtype, _ptr(out)) != 0:
+        raise ValueError("oracle_mhsa rejected its arguments")
+    return out
 
 
 def num_threads():

@@ -8,7 +8,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, "oracle_gemm.c"), os.path.join(HERE, "oracle_streams.c")]
+SRCS = [os.path.join(HERE, f) for f in ("oracle_gemm.c", "oracle_streams.c", "oracle_attention.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
