@@ -36,6 +36,7 @@ SIGNATURES = {
     "optiml_reduce": (_int, [_i64, _vp, _vp, _int, _vp, _vp]),
     "optiml_cross_entropy": (_int, [_i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "optiml_layernorm": (_int, [_i64, _i64, _vp, _vp, C.c_float, _vp]),
+    "optiml_mhsa": (_int, [_i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -167,6 +168,11 @@ def optiml_cross_entropy(N, Cn, logits, ld, labels, loss, stream=None):
 
 def optiml_layernorm(rows, length, x, y, eps, stream=None):
     return _check(lib().optiml_layernorm(rows, length, _addr(x), _addr(y), eps, _stream(stream)))
+
+
+def optiml_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, stream=None):
+    return _check(lib().optiml_mhsa(batch, N, d_model, heads, _addr(Q), _addr(K), _addr(V), _addr(O), dtype,
+                                    _stream(stream)))
 
 
 def optiml_status_string(status):

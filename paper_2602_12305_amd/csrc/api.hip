@@ -376,6 +376,23 @@ int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float 
     return OPTIML_OK;
 }
 
+int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K, const void *V,
+                void *O, int dtype, void *stream)
+{
+    if (batch < 0 || N < 0 || d_model < 1 || heads < 1 || d_model % heads != 0) return OPTIML_ERR_INVALID_ARG;
+    if (dtype != OPTIML_F32 && dtype != OPTIML_BF16) return OPTIML_ERR_INVALID_ARG;
+    if (batch == 0 || N == 0) return OPTIML_OK;
+    if (!Q || !K || !V || !O) return OPTIML_ERR_INVALID_ARG;
+    const int path = optiml::mhsa_path(d_model, heads, dtype, Q, K, V, O);
+    if (path < 0) return OPTIML_ERR_UNSUPPORTED;
+    hipError_t e = optiml::launch_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, path, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
 const char *optiml_status_string(int status)
 {
     switch (status) {

@@ -51,6 +51,11 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
                                 hipStream_t stream);
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
 
+// attention (kernel_attention.hip): which kernel would serve (0 flash, 1 fallback, -1 none), launch
+int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const void *K, const void *V, const void *O);
+hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K,
+                       const void *V, void *O, int dtype, int path, hipStream_t stream);
+
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;

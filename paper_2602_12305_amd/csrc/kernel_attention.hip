@@ -1,0 +1,324 @@
+// Multi-head self-attention (paper Table 4, task 6):
+//     head_i = softmax(Q_i K_i^T / sqrt(d_k)) V_i,  output = Concat(head_1 .. head_h)
+// for Q, K, V of shape [batch][N][d_model] (row-major), heads of width d_k = d_model / h, no mask.
+//
+// Two kernels.
+//
+// mhsa_flash_kernel (bf16 storage, d_k = 64 or 128): the two chained contractions on the bf16
+// matrix pipe with an online softmax between them, never writing the N x N scores anywhere.
+// A workgroup of 4 waves owns 128 queries of one (batch, head); a wave owns 32 of them and
+// keeps their Q fragments, the running maximum / sum, and the output accumulators in
+// registers while the workgroup walks the keys 64 at a time through one LDS tile of K and one
+// of V.  Both products are computed TRANSPOSED:
+//     S^T (keys x queries) = K_blk . Q^T          O^T (d_k x queries) += V_blk^T . P^T
+// With v_mfma_f32_32x32x16_bf16 the accumulator lane l then holds column l%32 = one query, so
+//   * all 16 registers of a lane's S^T tile are scores of ONE query: its maximum and sum need
+//     one exchange with lane l^32 instead of a 32-lane reduction;
+//   * every register of a lane's O^T accumulators belongs to that same query: rescaling by
+//     exp(m_old - m_new) is a plain multiply;
+//   * registers 8s..8s+7 of a lane's P^T tile are exactly the 8 k-slots that lane must supply as
+//     the second MFMA operand of k-step s, up to a fixed permutation of the 16 keys of the step
+//     (lane half h owns keys 4h..4h+3 and 8+4h..8+4h+3 instead of 8h..8h+7).  A contraction does
+//     not care in which order its terms come, so the V^T operand is simply read with the same
+//     permutation (two transposing LDS reads at rows 16s+4h and 16s+8+4h) and P never passes
+//     through LDS or a shuffle.
+// LDS tiles are XOR-swizzled 16-byte chunks (K: chunk ^ row for 256-byte rows, chunk ^ (row/2)
+// for 128-byte rows; V: chunk ^ 4(row%4) or ^ 2(row%4)) so that the 128-bit fragment reads and
+// the transposing reads spread over the 64 banks.
+//
+// mhsa_rows_kernel (fp32 or bf16 storage, any d_k up to 256): one wave per query, a key per
+// lane, fp32 arithmetic throughout; the fallback for everything the flash kernel does not take.
+#include "common.hpp"
+#include "epilogue.hpp"
+
+namespace optiml {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+struct AttnParams {
+    int64_t batch, N, d_model, heads;
+    const char *Q, *K, *V;
+    char *O;
+    float scale2;        // log2(e) / sqrt(d_k)
+};
+
+constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
+
+template <int DK>
+__global__ __launch_bounds__(256) void mhsa_flash_kernel(AttnParams p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int ROWB = DK * 2;                 // bytes per row of a tile
+    constexpr int CHUNKS = DK / 8;               // 16-byte chunks per row
+    constexpr int KS = DK / 16;                  // k-steps of the first product
+    constexpr int TU = DK / 32;                  // 32-wide output tiles of the second product
+    constexpr int VKEY = DK == 128 ? 4 : 2;      // V swizzle: chunk ^ VKEY * (row % 4)
+    constexpr int PER_THREAD = kBK * CHUNKS / 256;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kBK * ROWB];
+    lds_char *const kt = (lds_char *)lds;
+    lds_char *const vt = kt + kBK * ROWB;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t qblocks = (p.N + kBQ - 1) / kBQ;
+    const int64_t qb = blockIdx.x % qblocks, bh = blockIdx.x / qblocks;
+    const int64_t b = bh / p.heads, head = bh % p.heads;
+    const int64_t ldb = p.d_model * 2;                                   // bytes per row of Q, K, V, O
+    const char *Qb = p.Q + (b * p.N * p.d_model + head * DK) * 2;
+    const char *Kb = p.K + (b * p.N * p.d_model + head * DK) * 2;
+    const char *Vb = p.V + (b * p.N * p.d_model + head * DK) * 2;
+    char *Ob = p.O + (b * p.N * p.d_model + head * DK) * 2;
+
+    // this lane's query (clamped at the end of the sequence: computed, not stored)
+    const int64_t q = qb * kBQ + wave * 32 + col;
+    const int64_t qc = q < p.N ? q : p.N - 1;
+    uintx4 qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const uintx4 *>(Qb + qc * ldb + (16 * s + 8 * half) * 2);
+
+    floatx16 acc_o[TU];
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[u][r] = 0.0f;
+    float m = -__builtin_inff(), l = 0.0f;
+
+    // staging: thread t copies chunks t, t + 256, ... of the 64 x CHUNKS chunk grid of K and of V
+    uintx4 sk[PER_THREAD], sv[PER_THREAD];
+    auto fetch = [&](int64_t key0) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int id = tid + i * 256, row = id / CHUNKS, c = id % CHUNKS;
+            int64_t n = key0 + row;
+            n = n < p.N ? n : p.N - 1;
+            sk[i] = *reinterpret_cast<const uintx4 *>(Kb + n * ldb + c * 16);
+            sv[i] = *reinterpret_cast<const uintx4 *>(Vb + n * ldb + c * 16);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int id = tid + i * 256, row = id / CHUNKS, c = id % CHUNKS;
+            const int kc = DK == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(kt + row * ROWB + kc * 16) = sk[i];
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(vt + row * ROWB + ((c ^ (VKEY * (row & 3))) << 4)) = sv[i];
+        }
+    };
+
+    // transposing read of V: a 16-lane group g reads rows r0 + (lane%16)/4, columns 16 (g%2) + 4 (lane%4) .. +3
+    const int g = lane >> 4, jj = lane & 15;
+    const int tr_row = 4 * (g >> 1) + (jj >> 2);          // + 16 s (+ 8 for the second half of the operand)
+    const int tr_col = 16 * (g & 1) + 4 * (jj & 3);       // + 32 u
+
+    fetch(0);
+    for (int64_t key0 = 0; key0 < p.N; key0 += kBK) {
+        __syncthreads();                                  // everybody is done with the previous tiles
+        stash();
+        __syncthreads();
+        if (key0 + kBK < p.N) fetch(key0 + kBK);          // in flight during the arithmetic below
+
+        // S^T = K_blk . Q^T : two 32-key tiles
+        floatx16 acc_s[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.0f;
+            const int row = 32 * t + col;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int c = 2 * s + half;
+                const int kc = DK == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+                const uintx4 kf = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(kt + row * ROWB + kc * 16);
+                acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf),
+                                                                   __builtin_bit_cast(bf16x8, qf[s]), acc_s[t], 0, 0, 0);
+            }
+        }
+
+        // online softmax for this lane's query over its 32 of the 64 keys (lane l^32 has the others)
+        float bm = -__builtin_inff();
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t n = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+                const float x = n < p.N ? acc_s[t][r] * p.scale2 : -__builtin_inff();
+                acc_s[t][r] = x;
+                bm = x > bm ? x : bm;
+            }
+        const float other = __shfl_xor(bm, 32, 64);
+        bm = other > bm ? other : bm;
+        const float m_new = m > bm ? m : bm;
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+        float rowsum = 0.0f;
+        uintx4 pf[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                float e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    e[i] = __builtin_amdgcn_exp2f(acc_s[t][8 * s + i] - m_new);
+                    rowsum += e[i];
+                }
+                pf[t][s] = uintx4{f32x2_to_bf16x2(e[0], e[1]), f32x2_to_bf16x2(e[2], e[3]),
+                                  f32x2_to_bf16x2(e[4], e[5]), f32x2_to_bf16x2(e[6], e[7])};
+            }
+        l = l * corr + rowsum;
+        m = m_new;
+#pragma unroll
+        for (int u = 0; u < TU; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[u][r] *= corr;
+
+        // O^T += V_blk^T . P^T : k-steps of 16 keys, lane half h supplying keys 4h..4h+3 and 8+4h..8+4h+3
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int r0 = 32 * t + 16 * s + tr_row;
+#pragma unroll
+                for (int u = 0; u < TU; ++u) {
+                    const int cb = (32 * u + tr_col) * 2;                 // byte column
+                    const int c = cb >> 4, within = cb & 15;
+                    const lds_char *a0 = vt + r0 * ROWB + ((c ^ (VKEY * (r0 & 3))) << 4) + within;
+                    const lds_char *a1 = vt + (r0 + 8) * ROWB + ((c ^ (VKEY * ((r0 + 8) & 3))) << 4) + within;
+                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(a0));
+                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(a1));
+                    const uintx2 l2 = __builtin_bit_cast(uintx2, lo), h2 = __builtin_bit_cast(uintx2, hi);
+                    const uintx4 vf = uintx4{l2[0], l2[1], h2[0], h2[1]};
+                    acc_o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                                       __builtin_bit_cast(bf16x8, pf[t][s]), acc_o[u], 0, 0, 0);
+                }
+            }
+    }
+
+    // normalise and store: register r of acc_o[u] is output column 32 u + 8 (r/4) + 4 half + r%4 of query q
+    const float total = l + __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / total;
+    if (q < p.N) {
+#pragma unroll
+        for (int u = 0; u < TU; ++u)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int dv = 32 * u + 8 * gq + 4 * half;
+                *reinterpret_cast<uintx2 *>(Ob + q * ldb + dv * 2) =
+                    uintx2{f32x2_to_bf16x2(acc_o[u][4 * gq] * inv, acc_o[u][4 * gq + 1] * inv),
+                           f32x2_to_bf16x2(acc_o[u][4 * gq + 2] * inv, acc_o[u][4 * gq + 3] * inv)};
+            }
+    }
+#endif
+}
+
+// ---- fallback: one wave per query, fp32 arithmetic ---------------------------------------------
+
+template <int DT>
+__device__ __forceinline__ float load_elem(const char *base, int64_t idx)
+{
+    if (DT == DT_F32) return reinterpret_cast<const float *>(base)[idx];
+    return bf16_to_f32(reinterpret_cast<const unsigned short *>(base)[idx]);
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void mhsa_rows_kernel(AttnParams p)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t dk = p.d_model / p.heads;
+    const int64_t rows = p.batch * p.heads * p.N;
+    const int64_t id = (int64_t)blockIdx.x * 4 + wave;
+    if (id >= rows) return;
+    const int64_t q = id % p.N, bh = id / p.N, b = bh / p.heads, head = bh % p.heads;
+    const int64_t base = b * p.N * p.d_model + head * dk;
+    const float scale = p.scale2;                       // scores are kept in base 2
+    float m = -__builtin_inff(), l = 0.0f, o[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // lane owns columns lane, lane+64, ...
+    for (int64_t key0 = 0; key0 < p.N; key0 += 64) {
+        const int64_t n = key0 + lane;
+        float s = -__builtin_inff();
+        if (n < p.N) {
+            float d = 0.0f;
+            for (int64_t c = 0; c < dk; ++c)
+                d = fmaf(load_elem<DT>(p.Q, base + q * p.d_model + c), load_elem<DT>(p.K, base + n * p.d_model + c), d);
+            s = d * scale;
+        }
+        float bm = s;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float t = __shfl_xor(bm, off, 64);
+            bm = t > bm ? t : bm;
+        }
+        const float m_new = m > bm ? m : bm;
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+        const float pw = __builtin_amdgcn_exp2f(s - m_new);     // 0 for keys past the end
+        float ps = pw;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off, 64);
+        l = l * corr + ps;
+        m = m_new;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] *= corr;
+        const int64_t nk = p.N - key0 < 64 ? p.N - key0 : 64;
+        for (int64_t j = 0; j < nk; ++j) {
+            const float w = __shfl(pw, (int)j, 64);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int64_t c = lane + 64 * t;
+                if (c < dk) o[t] = fmaf(w, load_elem<DT>(p.V, base + (key0 + j) * p.d_model + c), o[t]);
+            }
+        }
+    }
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int64_t c = lane + 64 * t;
+        if (c < dk) {
+            const float y = o[t] * inv;
+            if (DT == DT_F32) reinterpret_cast<float *>(p.O)[base + q * p.d_model + c] = y;
+            else reinterpret_cast<unsigned short *>(p.O)[base + q * p.d_model + c] = f32_to_bf16(y);
+        }
+    }
+}
+
+bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace
+
+// 0: flash kernel, 1: fallback, -1: not supported (d_k > 256 without a flash kernel)
+int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const void *K, const void *V, const void *O)
+{
+    const int64_t dk = d_model / heads;
+    if (dtype == DT_BF16 && (dk == 64 || dk == 128) && aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O))
+        return 0;
+    return dk <= 256 ? 1 : -1;
+}
+
+hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K,
+                       const void *V, void *O, int dtype, int path, hipStream_t stream)
+{
+    const int64_t dk = d_model / heads;
+    AttnParams p;
+    p.batch = batch; p.N = N; p.d_model = d_model; p.heads = heads;
+    p.Q = static_cast<const char *>(Q); p.K = static_cast<const char *>(K); p.V = static_cast<const char *>(V);
+    p.O = static_cast<char *>(O);
+    p.scale2 = (float)(1.4426950408889634 / sqrt((double)dk));
+    if (path == 0) {
+        const int64_t grid = batch * heads * ((N + kBQ - 1) / kBQ);
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (dk == 128) hipLaunchKernelGGL(mhsa_flash_kernel<128>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL(mhsa_flash_kernel<64>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+        return hipGetLastError();
+    }
+    const int64_t grid = (batch * heads * N + 3) / 4;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == DT_F32) hipLaunchKernelGGL(mhsa_rows_kernel<DT_F32>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(mhsa_rows_kernel<DT_BF16>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace optiml

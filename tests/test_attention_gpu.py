@@ -1,0 +1,99 @@
+"""Parity of multi-head self-attention (paper Table 4, task 6) with the CPU oracle, through the C-ABI.
+
+Bars (E1 = max |y - ref| / max(|ref|, rms(ref)), as for the contraction).  bf16 matrix-pipe kernel: the output is
+rounded to bf16 (2^-9 relative) and the softmax weights are rounded to bf16 before the second product (each
+weight 2^-9 relative, the weighted mean of values inherits at most that times the spread of the values): E1 <=
+2e-2.  fp32 kernel: fp32 dot products of d_k terms, hardware exp2 (1 ulp) of a score carrying 1e-7 * |score| of
+rounding, fp32 weighted sums: E1 <= 1e-5 for the score ranges tested (|score| < 30).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_12305_amd import binding as ob
+from paper_2602_12305_amd import synth
+
+pytestmark = pytest.mark.gpu
+F32, BF16 = 0, 1
+
+
+def e1(y, ref):
+    rho = float(np.sqrt(np.mean(ref * ref))) or 1.0
+    return float(np.max(np.abs(y - ref) / np.maximum(np.abs(ref), rho)))
+
+
+def run(Q, K, V, heads, dtype):
+    batch, N, d = Q.shape
+    if dtype == BF16:
+        conv = lambda a: torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).cuda()
+        O = torch.full((batch, N, d), 0x4640, dtype=torch.int16, device="cuda")
+    else:
+        conv = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        O = torch.full((batch, N, d), 12345.0, dtype=torch.float32, device="cuda")
+    ob.optiml_mhsa(batch, N, d, heads, conv(Q), conv(K), conv(V), O, dtype)
+    torch.cuda.synchronize()
+    o = O.cpu().numpy()
+    return synth.bf16_bits_to_f32(o.view(np.uint16)).astype(np.float64) if dtype == BF16 else o.astype(np.float64)
+
+
+def reference(Q, K, V, heads, dtype):
+    if dtype == BF16:
+        return oracle.mhsa(synth.f32_to_bf16_bits(Q), synth.f32_to_bf16_bits(K), synth.f32_to_bf16_bits(V), heads, dtype=oracle.BF16)
+    return oracle.mhsa(Q, K, V, heads)
+
+
+def inputs(seed, batch, N, d, qscale=1.0):
+    Q = synth.normal(seed, "q", N, d, batch=batch) * np.float32(qscale)
+    return Q, synth.normal(seed, "k", N, d, batch=batch), synth.normal(seed, "v", N, d, batch=batch)
+
+
+@pytest.mark.parametrize("batch,N,d,heads", [(1, 128, 128, 1), (2, 200, 256, 2), (1, 64, 128, 2), (1, 1, 128, 1),
+                                             (1, 333, 512, 4), (3, 130, 64, 1), (1, 1000, 256, 4), (1, 65, 384, 3)])
+def test_bf16_matrix_pipe_kernel_matches_the_oracle(batch, N, d, heads):
+    Q, K, V = inputs(2000 + N + d, batch, N, d)
+    got = run(Q, K, V, heads, BF16)
+    ref = reference(Q, K, V, heads, BF16)
+    assert np.all(np.isfinite(got))
+    assert e1(got, ref) <= 2e-2
+
+
+@pytest.mark.parametrize("batch,N,d,heads,dtype", [(1, 100, 96, 3, F32), (2, 77, 40, 5, F32), (1, 300, 128, 1, F32),
+                                                   (1, 64, 512, 2, F32), (1, 150, 96, 3, BF16), (1, 5, 7, 1, F32),
+                                                   (1, 1, 16, 2, F32), (2, 129, 200, 1, F32)])
+def test_fallback_kernel_matches_the_oracle(batch, N, d, heads, dtype):
+    Q, K, V = inputs(2100 + N + d, batch, N, d, qscale=0.5)
+    got = run(Q, K, V, heads, dtype)
+    ref = reference(Q, K, V, heads, dtype)
+    assert e1(got, ref) <= (1e-5 if dtype == F32 else 2e-2)
+
+
+@pytest.mark.parametrize("dtype,d,heads", [(BF16, 256, 2), (F32, 96, 2)])
+def test_closed_forms_on_the_gpu(dtype, d, heads):
+    N = 192
+    _, K, V = inputs(2200, 1, N, d)
+    # zero queries: every output row is the mean of the value rows (of the stored, rounded values)
+    got = run(np.zeros_like(K), K, V, heads, dtype)
+    Vs = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(V)).astype(np.float64) if dtype == BF16 else V.astype(np.float64)
+    mean = Vs.mean(axis=1, keepdims=True)
+    assert np.max(np.abs(got - mean)) <= (2e-2 if dtype == BF16 else 1e-5) * max(1.0, float(np.max(np.abs(mean))))
+    # sharp attention: one-hot keys scaled by 16, query i = key pi(i): output row i = value row pi(i)
+    dk = d // heads
+    n = min(N, dk)
+    Kh = np.zeros((1, n, d), dtype=np.float32)
+    for h in range(heads):
+        Kh[0, np.arange(n), h * dk + np.arange(n)] = 16.0
+    perm = (7 * np.arange(n) + 5) % n
+    Vh = synth.integers(2201, "v", n, d, -8, 8)[None]                    # exactly representable in bf16
+    got = run(Kh[:, perm], Kh, Vh, heads, dtype)
+    assert np.max(np.abs(got - Vh[0][perm])) <= 1e-3                       # other weights are e^(-256/sqrt(dk)) each
+
+
+def test_large_scores_stay_finite_and_repeat_bitwise():
+    Q, K, V = inputs(2300, 1, 256, 128, qscale=30.0)                       # scores of several hundred
+    a = run(Q, K, V, 1, BF16); b = run(Q, K, V, 1, BF16)
+    assert np.all(np.isfinite(a)) and np.array_equal(a, b)
+    ref = reference(Q, K, V, 1, BF16)
+    assert e1(a, ref) <= 2e-2
+    c = run(Q * np.float32(0.02), K, V, 4, F32); d = run(Q * np.float32(0.02), K, V, 4, F32)
+    assert np.array_equal(c, d)

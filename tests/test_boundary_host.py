@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 16
+    assert len(names) == 17
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -114,6 +114,21 @@ def test_row_wise_entry_points_validate_on_the_host():
     assert L.optiml_layernorm(4, 8, P, None, 1e-5, None) == ob.ERR_INVALID_ARG
     assert L.optiml_layernorm(0, 8, None, None, 1e-5, None) == ob.OK
     assert L.optiml_layernorm(4, 0, None, None, 1e-5, None) == ob.OK
+
+
+def test_attention_entry_point_validates_on_the_host():
+    L = ob.lib()
+    ok = (1, 64, 256, 4, P, P, P, P, 1, None)
+    bad = [(-1, 64, 256, 4, P, P, P, P, 1, None), (1, -64, 256, 4, P, P, P, P, 1, None), (1, 64, 0, 4, P, P, P, P, 1, None),
+           (1, 64, 256, 0, P, P, P, P, 1, None), (1, 64, 256, 3, P, P, P, P, 1, None),       # 256 columns, 3 heads
+           (1, 64, 256, 4, P, P, P, P, 2, None), (1, 64, 256, 4, None, P, P, P, 1, None),
+           (1, 64, 256, 4, P, None, P, P, 1, None), (1, 64, 256, 4, P, P, None, P, 1, None), (1, 64, 256, 4, P, P, P, None, 1, None)]
+    for args in bad:
+        assert L.optiml_mhsa(*args) == ob.ERR_INVALID_ARG, args
+    assert L.optiml_mhsa(0, 64, 256, 4, None, None, None, None, 1, None) == ob.OK
+    assert L.optiml_mhsa(1, 0, 256, 4, None, None, None, None, 0, None) == ob.OK
+    assert L.optiml_mhsa(1, 64, 1024, 2, P, P, P, P, 0, None) == ob.ERR_UNSUPPORTED           # d_k = 512
+    del ok
 
 
 def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bias=P):
