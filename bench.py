@@ -9,7 +9,7 @@ re-read the same bytes from cache).  The default workload is the memory-bound sk
 configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and the
 streaming siblings (element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats: --workload
 s_relu, s_sigmoid, s_sum, s_dot, s_mse; cross-entropy and LayerNorm: s_ce, s_ln_sample,
-s_ln_token) and adds them under "workloads".  One JSON line is
+s_ln_token; attention: s_mhsa) and adds them under "workloads".  One JSON line is
 printed.
 
 The "roofline" object prices the dominant kernel of the workload against the published
@@ -39,6 +39,8 @@ STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("r
 STREAM_N = 1 << 28
 # row-wise siblings: cross-entropy on [8192, 32768] logits; LayerNorm on 64 samples of 64 x 256 x 256
 # features (the task's 4-D shape, every feature of a sample is one row) and on 32768 rows of 8192
+# attention: bf16, 4 sequences of 4096 tokens, d_model 2048, 16 heads of 128
+MHSA = {"s_mhsa": (4, 4096, 2048, 16)}
 ROWS = {"s_ce": (8192, 32768), "s_ln_sample": (64, 64 * 256 * 256), "s_ln_token": (32768, 8192)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
@@ -298,6 +300,63 @@ def main():
             res["parity_abs_err"] = float(f"{err:.3e}")
         return res
 
+    def time_mhsa(name, steps, warmup, with_oracle):
+        """Multi-head self-attention, bf16 storage, seeded N(0, 1) inputs."""
+        batch, N, d, heads = MHSA[name]
+        host = [synth.f32_to_bf16_bits(synth.normal(9, tag, N, d, batch=batch)) for tag in ("q", "k", "v")]
+        Qd, Kd, Vd = (torch.from_numpy(h.view(np.int16)).cuda() for h in host)
+        Od = torch.empty_like(Qd)
+        step = lambda: ob.optiml_mhsa(batch, N, d, heads, Qd, Kd, Vd, Od, 1)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+        ms, kernel_ms = max(wall_ms, dev_ms) / steps, dev_ms / steps
+        flops = 4.0 * batch * N * N * d                    # two products of 2 N^2 d_k flops per head
+        tfl = flops / (kernel_ms * 1e-3) / 1e12
+        tr = TRAFFIC.get((name, name))
+        traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash(tr["files"]) else None
+        res = {"workload": name, "variant": "mhsa_flash_bf16_dk128", "batch": batch, "N": N, "d_model": d, "heads": heads,
+               "ms_per_step": round(ms, 5), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 3),
+               "mfma_frac": round(tfl / PEAK_TFLOPS[1], 4), "dtype": "bf16",
+               "roofline": {"bound": "mfma", "achieved": round(tfl, 3), "peak": PEAK_TFLOPS[1], "unit": "TFLOP/s",
+                            "frac": round(tfl / PEAK_TFLOPS[1], 4), "traffic": traffic, "kernel": "mhsa_flash_kernel<128>",
+                            "kernel_ms": round(kernel_ms, 5)}}
+        if with_oracle:
+            import oracle
+            t0 = time.perf_counter()
+            ref = oracle.mhsa(host[0][:1], host[1][:1], host[2][:1], heads, dtype=oracle.BF16)[0]   # bounded sample
+            secs = time.perf_counter() - t0
+            got = synth.bf16_bits_to_f32(Od[0].cpu().numpy().view(np.uint16)).astype(np.float64)
+            rho = float(np.sqrt(np.mean(ref * ref)))
+            err = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rho)))
+            res["cpu_baseline"] = {"value": float(f"{flops / batch / 1e12 / secs:.4g}"), "unit": "TFLOP/s",
+                                   "cores": oracle.num_threads(), "kind": "oracle",
+                                   "sample": f"sequence 0 of {batch} (all {heads} heads)", "seconds": round(secs, 3)}
+            res["parity_e1"] = float(f"{err:.3e}")
+        return res
+
+    if args.workload in MHSA:
+        r = time_mhsa(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+        out = {"metric": "TFLOP/s of multi-head self-attention", "value": r["TFLOP/s"], "unit": "TFLOP/s",
+               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": args.workload, "batch": r["batch"], "N": r["N"], "d_model": r["d_model"],
+                          "heads": r["heads"]}, "TFLOP/s": r["TFLOP/s"], "roofline": r["roofline"]}
+        for k in ("cpu_baseline", "parity_e1"):
+            if k in r:
+                out[k] = r[k]
+        print(json.dumps(out))
+        return
+
     if args.workload in STREAMS or args.workload in ROWS:
         if args.workload in ROWS:
             r = time_rows(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
@@ -381,6 +440,9 @@ def main():
             torch.cuda.empty_cache()
         for name in ROWS:
             out["workloads"][name] = time_rows(name, args.steps, args.warmup, False)
+            torch.cuda.empty_cache()
+        for name in MHSA:
+            out["workloads"][name] = time_mhsa(name, args.steps, args.warmup, False)
             torch.cuda.empty_cache()
 
     print(json.dumps(out))
