@@ -52,7 +52,7 @@ struct AttnParams {
 constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
 
 template <int DK>
-__global__ __launch_bounds__(256) void mhsa_flash_kernel(AttnParams p)
+__global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int ROWB = DK * 2;                 // bytes per row of a tile
@@ -173,10 +173,14 @@ __global__ __launch_bounds__(256) void mhsa_flash_kernel(AttnParams p)
             }
         l = l * corr + rowsum;
         m = m_new;
+        // after the first few blocks the running maximum rarely moves: skip the rescaling of the
+        // output accumulators when it moved for no query of this wave
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
 #pragma unroll
-        for (int u = 0; u < TU; ++u)
+            for (int u = 0; u < TU; ++u)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[u][r] *= corr;
+                for (int r = 0; r < 16; ++r) acc_o[u][r] *= corr;
+        }
 
         // O^T += V_blk^T . P^T : k-steps of 16 keys, lane half h supplying keys 4h..4h+3 and 8+4h..8+4h+3
 #pragma unroll
