@@ -124,37 +124,44 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
         __syncthreads();
         if (key0 + kBK < p.N) fetch(key0 + kBK);          // in flight during the arithmetic below
 
-        // S^T = K_blk . Q^T : two 32-key tiles
+        // S^T = K_blk . Q^T : two 32-key tiles, their two accumulation chains interleaved
         floatx16 acc_s[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.0f;
-            const int row = 32 * t + col;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int row = 32 * t + col;
                 const int c = 2 * s + half;
                 const int kc = DK == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
                 const uintx4 kf = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(kt + row * ROWB + kc * 16);
                 acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf),
                                                                    __builtin_bit_cast(bf16x8, qf[s]), acc_s[t], 0, 0, 0);
             }
+
+        // keys past the end of the sequence (last block only) drop out with a score of -inf
+        if (key0 + kBK > p.N) {
+            const int left = (int)(p.N - key0);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * t + 8 * (r >> 2) + 4 * half + (r & 3) >= left) acc_s[t][r] = -__builtin_inff();
         }
 
-        // online softmax for this lane's query over its 32 of the 64 keys (lane l^32 has the others)
-        float bm = -__builtin_inff();
+        // online softmax for this lane's query over its 32 of the 64 keys (lane l^32 has the others);
+        // the maximum is taken on the raw scores (the scale is positive) and the scale is folded
+        // into the exponent's multiply-add
+        float bm = acc_s[0][0];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t n = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-                const float x = n < p.N ? acc_s[t][r] * p.scale2 : -__builtin_inff();
-                acc_s[t][r] = x;
-                bm = x > bm ? x : bm;
-            }
-        const float other = __shfl_xor(bm, 32, 64);
-        bm = other > bm ? other : bm;
-        const float m_new = m > bm ? m : bm;
+            for (int r = 0; r < 16; ++r) bm = __builtin_fmaxf(bm, acc_s[t][r]);
+        bm = __builtin_fmaxf(bm, __shfl_xor(bm, 32, 64));
+        const float m_new = __builtin_fmaxf(m, bm * p.scale2);
         const float corr = __builtin_amdgcn_exp2f(m - m_new);
         float rowsum = 0.0f;
         uintx4 pf[2][2];
@@ -165,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                 float e[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    e[i] = __builtin_amdgcn_exp2f(acc_s[t][8 * s + i] - m_new);
+                    e[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[t][8 * s + i], p.scale2, -m_new));
                     rowsum += e[i];
                 }
                 pf[t][s] = uintx4{f32x2_to_bf16x2(e[0], e[1]), f32x2_to_bf16x2(e[2], e[3]),
