@@ -42,6 +42,36 @@ typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) char lds_char;
 
+// One wave-wide LDS-DMA load: lane l copies 16 bytes from base + off(l) to LDS byte lds_addr + 16 l
+// (base and lds_addr wave-uniform).  In assembly, so that the kernel keeps its own count of the
+// loads in flight (wait_all_loads_and_barrier below) instead of the compiler draining them
+// before unrelated LDS reads.
+__device__ __forceinline__ void dma_load16(const char *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(off), "s"(base), "s"(lds_addr)
+                 : "m0");
+}
+
+__device__ __forceinline__ const char *scalar_ptr(const char *q)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(q);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+
+// s_waitcnt vmcnt(0) lgkmcnt(0), then the workgroup barrier, without the fences of
+// __syncthreads(): every load of this wave has landed and its LDS reads have returned.
+__device__ __forceinline__ void wait_all_loads_and_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 struct AttnParams {
     int64_t batch, N, d_model, heads;
     const char *Q, *K, *V;
@@ -60,10 +90,10 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
     constexpr int KS = DK / 16;                  // k-steps of the first product
     constexpr int TU = DK / 32;                  // 32-wide output tiles of the second product
     constexpr int VKEY = DK == 128 ? 4 : 2;      // V swizzle: chunk ^ VKEY * (row % 4)
-    constexpr int PER_THREAD = kBK * CHUNKS / 256;
-    __shared__ __attribute__((aligned(1024))) char lds[2 * kBK * ROWB];
-    lds_char *const kt = (lds_char *)lds;
-    lds_char *const vt = kt + kBK * ROWB;
+    constexpr int TILE = kBK * ROWB;               // bytes of one K (or V) tile
+    constexpr int RPL = 1024 / ROWB;               // tile rows one wave-wide load covers
+    constexpr int LOADS = kBK / (4 * RPL);         // loads per wave per tile
+    __shared__ __attribute__((aligned(1024))) char lds[4 * TILE];     // two buffers of (K tile, V tile)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -90,25 +120,26 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
         for (int r = 0; r < 16; ++r) acc_o[u][r] = 0.0f;
     float m = -__builtin_inff(), l = 0.0f;
 
-    // staging: thread t copies chunks t, t + 256, ... of the 64 x CHUNKS chunk grid of K and of V
-    uintx4 sk[PER_THREAD], sv[PER_THREAD];
-    auto fetch = [&](int64_t key0) {
+    // Tile loads: wave w's load i fills the 1 KiB of LDS that holds rows RPL (w + 4 i) .. of the
+    // tile; a lane's slot there (row, position in the row) takes the chunk the swizzle assigns to
+    // it, so the swizzle is applied on the global side.  The swizzle terms depend on row % 16 or
+    // less and a load advances the row by a multiple of 16: one chunk offset per lane serves all.
+    const int ld_row = RPL * wave + lane / CHUNKS, ld_slot = lane % CHUNKS;
+    const uint32_t ld_kc = (DK == 128 ? (ld_slot ^ (ld_row & 15)) : (ld_slot ^ ((ld_row >> 1) & 7))) * 16;
+    const uint32_t ld_vc = (ld_slot ^ (VKEY * (ld_row & 3))) * 16;
+    const uint32_t ldb32 = (uint32_t)ldb;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>((lds_char *)lds) + wave * 1024);
+    auto issue = [&](int64_t key0, int buf) {
+        const char *kb = scalar_ptr(Kb + key0 * ldb), *vb = scalar_ptr(Vb + key0 * ldb);
+        const int64_t left64 = p.N - key0;
+        const int last = left64 < kBK ? (int)left64 - 1 : kBK - 1;       // rows past the end re-read the last key
+        const uint32_t dst = lds0 + buf * 2 * TILE;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int id = tid + i * 256, row = id / CHUNKS, c = id % CHUNKS;
-            int64_t n = key0 + row;
-            n = n < p.N ? n : p.N - 1;
-            sk[i] = *reinterpret_cast<const uintx4 *>(Kb + n * ldb + c * 16);
-            sv[i] = *reinterpret_cast<const uintx4 *>(Vb + n * ldb + c * 16);
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int id = tid + i * 256, row = id / CHUNKS, c = id % CHUNKS;
-            const int kc = DK == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
-            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(kt + row * ROWB + kc * 16) = sk[i];
-            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(vt + row * ROWB + ((c ^ (VKEY * (row & 3))) << 4)) = sv[i];
+        for (int i = 0; i < LOADS; ++i) {
+            const int row = ld_row + 4 * RPL * i;
+            const uint32_t ro = (uint32_t)(row < last ? row : last) * ldb32;
+            dma_load16(kb, ro + ld_kc, dst + i * 4096);
+            dma_load16(vb, ro + ld_vc, dst + TILE + i * 4096);
         }
     };
 
@@ -117,12 +148,14 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
     const int tr_row = 4 * (g >> 1) + (jj >> 2);          // + 16 s (+ 8 for the second half of the operand)
     const int tr_col = 16 * (g & 1) + 4 * (jj & 3);       // + 32 u
 
-    fetch(0);
-    for (int64_t key0 = 0; key0 < p.N; key0 += kBK) {
-        __syncthreads();                                  // everybody is done with the previous tiles
-        stash();
-        __syncthreads();
-        if (key0 + kBK < p.N) fetch(key0 + kBK);          // in flight during the arithmetic below
+    issue(0, 0);
+    int buf = 0;
+    for (int64_t key0 = 0; key0 < p.N; key0 += kBK, buf ^= 1) {
+        // this block's tiles have landed for every wave, and every wave is done with the other buffer
+        wait_all_loads_and_barrier();
+        if (key0 + kBK < p.N) issue(key0 + kBK, buf ^ 1);                // in flight during the arithmetic below
+        lds_char *const kt = (lds_char *)lds + buf * 2 * TILE;
+        lds_char *const vt = kt + TILE;
 
         // S^T = K_blk . Q^T : two 32-key tiles, their two accumulation chains interleaved
         floatx16 acc_s[2];
