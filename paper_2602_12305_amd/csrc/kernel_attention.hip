@@ -98,7 +98,19 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
     const int64_t qblocks = (p.N + kBQ - 1) / kBQ;
-    const int64_t qb = blockIdx.x % qblocks, bh = blockIdx.x / qblocks;
+    // Workgroups are dealt to the 8 XCDs round-robin by index.  When the (batch, head) pairs split
+    // evenly, XCD x takes the pairs = x (mod 8), so that the workgroups sharing one pair's K and V
+    // run behind the same L2.
+    const int64_t pairs = p.batch * p.heads;
+    int64_t qb, bh;
+    if (pairs % 8 == 0) {
+        const int64_t x = blockIdx.x % 8, j = blockIdx.x / 8;
+        bh = x + 8 * (j / qblocks);
+        qb = j % qblocks;
+    } else {
+        qb = blockIdx.x % qblocks;
+        bh = blockIdx.x / qblocks;
+    }
     const int64_t b = bh / p.heads, head = bh % p.heads;
     const int64_t ldb = p.d_model * 2;                                   // bytes per row of Q, K, V, O
     const char *Qb = p.Q + (b * p.N * p.d_model + head * DK) * 2;
