@@ -8,8 +8,11 @@
 // matrix pipe with an online softmax between them, never writing the N x N scores anywhere.
 // A workgroup of 4 waves owns 128 queries of one (batch, head); a wave owns 32 of them and
 // keeps their Q fragments, the running maximum / sum, and the output accumulators in
-// registers while the workgroup walks the keys 64 at a time through one LDS tile of K and one
-// of V.  Both products are computed TRANSPOSED:
+// registers while the workgroup walks the keys 64 at a time.  The K and V tiles of a key block
+// come in by LDS-DMA (no staging registers) into one of two LDS buffers while the arithmetic of
+// the block before runs from the other: one barrier per block.  Two workgroups share a compute
+// unit, so one's softmax arithmetic overlaps the other's matrix instructions.  Both products are
+// computed TRANSPOSED:
 //     S^T (keys x queries) = K_blk . Q^T          O^T (d_k x queries) += V_blk^T . P^T
 // With v_mfma_f32_32x32x16_bf16 the accumulator lane l then holds column l%32 = one query, so
 //   * all 16 registers of a lane's S^T tile are scores of ONE query: its maximum and sum need
@@ -80,6 +83,7 @@ struct AttnParams {
 };
 
 constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
+constexpr float kLazy = 8.0f;            // slack of the exponents' reference point below the running maximum
 
 template <int DK>
 __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
@@ -141,17 +145,27 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
     const uint32_t ld_vc = (ld_slot ^ (VKEY * (ld_row & 3))) * 16;
     const uint32_t ldb32 = (uint32_t)ldb;
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>((lds_char *)lds) + wave * 1024);
+    uint32_t ld_ro[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) ld_ro[i] = (uint32_t)(ld_row + 4 * RPL * i) * ldb32;
     auto issue = [&](int64_t key0, int buf) {
         const char *kb = scalar_ptr(Kb + key0 * ldb), *vb = scalar_ptr(Vb + key0 * ldb);
-        const int64_t left64 = p.N - key0;
-        const int last = left64 < kBK ? (int)left64 - 1 : kBK - 1;       // rows past the end re-read the last key
         const uint32_t dst = lds0 + buf * 2 * TILE;
+        if (key0 + kBK <= p.N) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int row = ld_row + 4 * RPL * i;
-            const uint32_t ro = (uint32_t)(row < last ? row : last) * ldb32;
-            dma_load16(kb, ro + ld_kc, dst + i * 4096);
-            dma_load16(vb, ro + ld_vc, dst + TILE + i * 4096);
+            for (int i = 0; i < LOADS; ++i) {
+                dma_load16(kb, ld_ro[i] + ld_kc, dst + i * 4096);
+                dma_load16(vb, ld_ro[i] + ld_vc, dst + TILE + i * 4096);
+            }
+        } else {
+            const int last = (int)(p.N - key0) - 1;                      // rows past the end re-read the last key
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                const int row = ld_row + 4 * RPL * i;
+                const uint32_t ro = (uint32_t)(row < last ? row : last) * ldb32;
+                dma_load16(kb, ro + ld_kc, dst + i * 4096);
+                dma_load16(vb, ro + ld_vc, dst + TILE + i * 4096);
+            }
         }
     };
 
@@ -160,13 +174,14 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
     const int tr_row = 4 * (g >> 1) + (jj >> 2);          // + 16 s (+ 8 for the second half of the operand)
     const int tr_col = 16 * (g & 1) + 4 * (jj & 3);       // + 32 u
 
-    issue(0, 0);
-    int buf = 0;
-    for (int64_t key0 = 0; key0 < p.N; key0 += kBK, buf ^= 1) {
+    // one key block from buffer BUF (a compile-time constant: every LDS address below is then a
+    // loop-invariant register plus an immediate)
+    auto block = [&](int64_t key0, auto bufc) {
+        constexpr int BUF = decltype(bufc)::value;
         // this block's tiles have landed for every wave, and every wave is done with the other buffer
         wait_all_loads_and_barrier();
-        if (key0 + kBK < p.N) issue(key0 + kBK, buf ^ 1);                // in flight during the arithmetic below
-        lds_char *const kt = (lds_char *)lds + buf * 2 * TILE;
+        if (key0 + kBK < p.N) issue(key0 + kBK, BUF ^ 1);                // in flight during the arithmetic below
+        lds_char *const kt = (lds_char *)lds + BUF * 2 * TILE;
         lds_char *const vt = kt + TILE;
 
         // S^T = K_blk . Q^T : two 32-key tiles, their two accumulation chains interleaved
@@ -206,7 +221,13 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) bm = __builtin_fmaxf(bm, acc_s[t][r]);
         bm = __builtin_fmaxf(bm, __shfl_xor(bm, 32, 64));
-        const float m_new = __builtin_fmaxf(m, bm * p.scale2);
+        // The reference point of the exponents only has to keep them in range, so it follows the
+        // maximum lazily: it moves when the block's maximum is more than kLazy (in base-2 units)
+        // above it, which after the first block is rare; until then the weights are at most
+        // 2^kLazy and the output accumulators need no rescaling.  The final division by the sum
+        // of the weights cancels the reference point exactly.
+        const float cand = bm * p.scale2;
+        const float m_new = cand > m + kLazy ? cand : m;
         const float corr = __builtin_amdgcn_exp2f(m - m_new);
         float rowsum = 0.0f;
         uintx4 pf[2][2];
@@ -225,8 +246,7 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
             }
         l = l * corr + rowsum;
         m = m_new;
-        // after the first few blocks the running maximum rarely moves: skip the rescaling of the
-        // output accumulators when it moved for no query of this wave
+        // skip the rescaling of the output accumulators when the reference moved for no query of this wave
         if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
 #pragma unroll
             for (int u = 0; u < TU; ++u)
@@ -254,6 +274,11 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                                                                        __builtin_bit_cast(bf16x8, pf[t][s]), acc_o[u], 0, 0, 0);
                 }
             }
+    };
+    issue(0, 0);
+    for (int64_t key0 = 0; key0 < p.N; key0 += 2 * kBK) {
+        block(key0, std::integral_constant<int, 0>{});
+        if (key0 + kBK < p.N) block(key0 + kBK, std::integral_constant<int, 1>{});
     }
 
     // normalise and store: register r of acc_o[u] is output column 32 u + 8 (r/4) + 4 half + r%4 of query q
