@@ -201,6 +201,15 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                 acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf),
                                                                    __builtin_bit_cast(bf16x8, qf[s]), acc_s[t], 0, 0, 0);
             }
+        // order for the scheduler: K fragment reads run kAhead k-steps ahead of the matrix
+        // instructions that consume them, so LDS latency is paid once, not per step
+        constexpr int kAhead = KS < 4 ? KS : 4;
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            if (s + kAhead < KS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
 
         // keys past the end of the sequence (last block only) drop out with a score of -inf
         if (key0 + kBK > p.N) {

@@ -49,7 +49,8 @@ def inputs(seed, batch, N, d, qscale=1.0):
 
 
 @pytest.mark.parametrize("batch,N,d,heads", [(1, 128, 128, 1), (2, 200, 256, 2), (1, 64, 128, 2), (1, 1, 128, 1),
-                                             (1, 333, 512, 4), (3, 130, 64, 1), (1, 1000, 256, 4), (1, 65, 384, 3)])
+                                             (1, 333, 512, 4), (3, 130, 64, 1), (1, 1000, 256, 4), (1, 65, 384, 3),
+                                             (2, 300, 512, 4), (1, 260, 1024, 16), (3, 129, 1024, 8)])
 def test_bf16_matrix_pipe_kernel_matches_the_oracle(batch, N, d, heads):
     Q, K, V = inputs(2000 + N + d, batch, N, d)
     got = run(Q, K, V, heads, BF16)
@@ -97,3 +98,16 @@ def test_large_scores_stay_finite_and_repeat_bitwise():
     assert e1(a, ref) <= 2e-2
     c = run(Q * np.float32(0.02), K, V, 4, F32); d = run(Q * np.float32(0.02), K, V, 4, F32)
     assert np.array_equal(c, d)
+
+
+@pytest.mark.parametrize("d,heads,ramp", [(128, 1, (0.05, 8.0)), (128, 1, (8.0, 0.05)), (128, 2, (0.05, 8.0))])
+def test_score_range_drifting_along_the_keys(d, heads, ramp):
+    """Key magnitudes ramp along the sequence, so the largest score seen so far keeps moving (up in small and large
+    steps, or not at all after the first block): the kernel's reference point for the exponents must follow."""
+    N = 700
+    Q, K, V = inputs(2400 + heads, 2, N, d, qscale=2.0)
+    K = K * np.linspace(ramp[0], ramp[1], N, dtype=np.float32)[None, :, None]
+    got = run(Q, K, V, heads, BF16)
+    ref = reference(Q, K, V, heads, BF16)
+    assert np.all(np.isfinite(got))
+    assert e1(got, ref) <= 2e-2
