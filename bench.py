@@ -53,6 +53,7 @@ RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "e
 RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
 RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 STREAMS_SRC = ("kernel_streams.hip", "epilogue.hpp")
+ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
@@ -71,6 +72,8 @@ TRAFFIC = {
         {"bytes": int(4 * ((131109 + 131373) * 2.0 + 128 + 262350) * 1024), "files": ROWS_SRC, "src": "7712a69450f82056"},
     ("s_ln_token", "s_ln_token"):
         {"bytes": int((524323 * 2.0 + 1048770) * 1024), "files": ROWS_SRC, "src": "7712a69450f82056"},
+    ("s_mhsa", "s_mhsa"):
+        {"bytes": int((98402.8 * 2.0 + 65536) * 1024), "files": ATTN_SRC, "src": "e8a988a024b40824"},
     ("s_dot", "s_dot"):
         {"bytes": int(((1048650 + 33.08) * 2.0 + 256.55 + 0.03) * 1024), "files": STREAMS_SRC, "src": "676666c89a415e62"},
 }
