@@ -16,7 +16,7 @@ import numpy as np
 
 from .build import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 EW_RELU, EW_SIGMOID = 0, 1
@@ -41,6 +41,10 @@ def lib():
         L.oracle_act.argtypes = [C.c_double, C.c_int]
         L.oracle_bf16_from_double.restype = C.c_uint16
         L.oracle_bf16_from_double.argtypes = [C.c_double]
+        L.oracle_f16_from_double.restype = C.c_uint16
+        L.oracle_f16_from_double.argtypes = [C.c_double]
+        L.oracle_f16_to_double.restype = C.c_double
+        L.oracle_f16_to_double.argtypes = [C.c_uint16]
         L.oracle_num_threads.restype = C.c_int
         L.oracle_elementwise.restype = None
         L.oracle_elementwise.argtypes = [i64, vp, C.c_int, vp]
@@ -135,6 +139,18 @@ def bf16_from_double(y):
     """uint16 bit patterns of the bf16 nearest (ties to even) to each fp64 value."""
     f = lib().oracle_bf16_from_double
     return np.vectorize(lambda v: f(float(v)), otypes=[np.uint16])(np.asarray(y, dtype=np.float64))
+
+
+def f16_from_double(y):
+    """uint16 bit patterns of the IEEE binary16 nearest (ties to even) to each fp64 value."""
+    f = lib().oracle_f16_from_double
+    return np.vectorize(lambda v: f(float(v)), otypes=[np.uint16])(np.asarray(y, dtype=np.float64))
+
+
+def f16_to_double(bits):
+    """fp64 value of each binary16 bit pattern."""
+    f = lib().oracle_f16_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(bits, dtype=np.uint16))
 
 
 def elementwise(x, op):

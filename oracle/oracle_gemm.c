@@ -17,7 +17,7 @@
  * Bias, SiLU, GELU, bf16 storage and batching are not in the paper; they are
  * the standard definitions named by this repository's benchmark configuration.
  *
- * Arithmetic: the stored fp32 / bf16 inputs are widened exactly to fp64; every
+ * Arithmetic: the stored fp32 / bf16 / fp16 inputs are widened exactly to fp64; every
  * product of two of them is exact in fp64 (at most 48 significant bits); the
  * sum runs over k ascending in one fp64 accumulator starting from +0.0; the
  * bias is added after the sum; activations use fp64 libm.  The result is kept
@@ -38,14 +38,31 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
 /* bit 0 of layout: B is column-major; bit 1: A is column-major */
+
+/* IEEE 754 binary16 (1 sign, 5 exponent bits with bias 15, 10 fraction bits) to double, exactly:
+ * exponent field 0 is a subnormal f * 2^-24, field 31 is infinity (f = 0) or NaN. */
+double oracle_f16_to_double(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp((double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
 
 static double widen(const void *base, int64_t idx, int dtype)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == ORACLE_F16)
+        return oracle_f16_to_double(((const uint16_t *)base)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -104,6 +121,35 @@ uint16_t oracle_bf16_from_double(double x)
     return sign | (uint16_t)(bits >> 16);
 }
 
+/* Round a double to the nearest binary16 (ties to even), straight from the fp64 value.
+ * 11 significant bits, smallest normal 2^-14, subnormal spacing 2^-24, largest finite 65504;
+ * a value that rounds to 2^16 or more gives infinity; NaN gives a quiet NaN. */
+uint16_t oracle_f16_from_double(double x)
+{
+    if (isnan(x))
+        return 0x7E00;
+    uint16_t sign = signbit(x) ? 0x8000 : 0;
+    double a = fabs(x);
+    if (a == 0.0)
+        return sign;
+    if (isinf(a))
+        return sign | 0x7C00;
+    int e;
+    (void)frexp(a, &e);
+    int exp_unb = e - 1;                               /* a in [2^exp_unb, 2^(exp_unb+1)) */
+    int q = exp_unb < -14 ? -24 : exp_unb - 10;        /* a is rounded to a multiple of 2^q */
+    double r = nearbyint(ldexp(a, -q));                /* default rounding mode: nearest even */
+    double v = ldexp(r, q);
+    if (v >= 65536.0)
+        return sign | 0x7C00;
+    if (v < ldexp(1.0, -14))                           /* subnormal (or zero): the count of 2^-24 steps */
+        return sign | (uint16_t)r;
+    (void)frexp(v, &e);                                /* rounding may have carried into the next binade */
+    int field = e - 1 + 15;
+    uint16_t frac = (uint16_t)(ldexp(v, 10 - (e - 1)) - 1024.0);
+    return sign | (uint16_t)(field << 10) | frac;
+}
+
 /*
  * Full evaluation.
  *   A      : A[i,k] at A[b*strideA + i*lda + k]   (A row-major)  or  [.. + k*lda + i] (column-major)
@@ -121,7 +167,7 @@ int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
                          int layout, int dtype, int act)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype != ORACLE_F32 && dtype != ORACLE_BF16) || act < 0 || act > 3)
+        (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) || act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
     const int64_t rows = batch * M;
@@ -186,7 +232,7 @@ int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t
                                  int layout, int dtype, int act)
 {
     if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype != ORACLE_F32 && dtype != ORACLE_BF16) || act < 0 || act > 3)
+        (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) || act < 0 || act > 3)
         return -1;
     for (int64_t t = 0; t < count; ++t)
         if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)

@@ -111,3 +111,22 @@ def test_score_range_drifting_along_the_keys(d, heads, ramp):
     ref = reference(Q, K, V, heads, BF16)
     assert np.all(np.isfinite(got))
     assert e1(got, ref) <= 2e-2
+
+
+def test_benchmark_shape_on_sampled_heads():
+    """The shape the benchmark times (batch 4, N 4096, d_model 2048, 16 heads): whole heads of sampled (sequence, head)
+    pairs against the oracle, which sees one head as a single-head problem of width d_k."""
+    batch, N, d, heads = 4, 4096, 2048, 16
+    dk = d // heads
+    q, k, v = (synth.f32_to_bf16_bits(synth.normal(9, tag, N, d, batch=batch)) for tag in ("q", "k", "v"))
+    dev = [torch.from_numpy(a.view(np.int16)).cuda() for a in (q, k, v)]
+    O = torch.full((batch, N, d), 0x4640, dtype=torch.int16, device="cuda")
+    ob.optiml_mhsa(batch, N, d, heads, dev[0], dev[1], dev[2], O, BF16)
+    torch.cuda.synchronize()
+    got = synth.bf16_bits_to_f32(O.cpu().numpy().view(np.uint16)).astype(np.float64)
+    assert np.all(np.isfinite(got))
+    for b, h in ((0, 0), (1, 7), (3, 15)):
+        cols = slice(h * dk, (h + 1) * dk)
+        part = lambda a: np.ascontiguousarray(a[b:b + 1, :, cols])
+        ref = oracle.mhsa(part(q), part(k), part(v), 1, dtype=oracle.BF16)[0]
+        assert e1(got[b, :, cols], ref) <= 2e-2, (b, h)

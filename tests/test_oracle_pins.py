@@ -277,6 +277,55 @@ def test_bf16_rounding_is_nearest_even():
     assert np.array_equal(oracle.bf16_from_double(x.astype(np.float64)), synth.f32_to_bf16_bits(x))
 
 
+# ---- IEEE binary16 storage: decode and rounding against numpy's float16 (an independent implementation) ----
+def test_f16_decode_and_rounding_agree_with_ieee_binary16():
+    bits = np.arange(0, 1 << 16, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = oracle.f16_to_double(bits)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # landmarks of the format, typed by hand: largest finite, smallest normal, smallest subnormal, one, -2
+    assert list(oracle.f16_to_double([0x7BFF, 0x0400, 0x0001, 0x3C00, 0xC000])) == [65504.0, 2.0 ** -14, 2.0 ** -24, 1.0, -2.0]
+    # every non-NaN value rounds to itself
+    assert np.array_equal(oracle.f16_from_double(got[~nan]), bits[~nan])
+    # midpoints between neighbours go to the even one, a hair to either side goes to that side
+    pos = bits[:0x7C00]
+    v = got[:0x7C00]
+    mids = (v[:-1] + v[1:]) / 2
+    assert np.array_equal(oracle.f16_from_double(mids), np.where(pos[:-1] % 2 == 0, pos[:-1], pos[1:]))
+    eps = (v[1:] - v[:-1]) * 2.0 ** -20
+    assert np.array_equal(oracle.f16_from_double(mids - eps), pos[:-1])
+    assert np.array_equal(oracle.f16_from_double(mids + eps), pos[1:])
+    # overflow threshold (65520 is the midpoint to 2^16: ties to even = infinity), specials
+    assert list(oracle.f16_from_double([65519.99, 65520.0, 1e9, -1e9, np.inf, -0.0, 2.0 ** -25, 2.0 ** -25 * 1.0001])) == \
+        [0x7BFF, 0x7C00, 0x7C00, 0xFC00, 0x7C00, 0x8000, 0x0000, 0x0001]
+    assert oracle.f16_from_double([np.nan])[0] & 0x7FFF > 0x7C00
+    # random doubles over the whole range, against numpy's double -> half conversion
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(20000) * np.exp2(rng.integers(-30, 17, 20000))
+    with np.errstate(over="ignore"):
+        assert np.array_equal(oracle.f16_from_double(x), x.astype(np.float16).view(np.uint16))
+
+
+def test_f16_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
+    rng = np.random.default_rng(6)
+    M, N, K = 7, 9, 33
+    A = rng.standard_normal((M, K)).astype(np.float16)
+    B = rng.standard_normal((K, N)).astype(np.float16)
+    bias = rng.standard_normal(N).astype(np.float32)
+    y = oracle.gemm_epilogue(A.view(np.uint16), B.view(np.uint16), bias, M, N, K, dtype=oracle.F16)[0]
+    ref = A.astype(np.float64) @ B.astype(np.float64) + bias.astype(np.float64)
+    assert np.allclose(y, ref, rtol=0, atol=1e-13)
+    # column-major B, batch of two, ReLU
+    Bt = np.ascontiguousarray(np.stack([B.T, 2 * B.T]))
+    A2 = np.ascontiguousarray(np.stack([A, A]))
+    y = oracle.gemm_epilogue(A2.view(np.uint16), Bt.view(np.uint16), None, M, N, K, dtype=oracle.F16, layout=synth.LAYOUT_RC,
+                             act=synth.ACT_RELU, batch=2)
+    ref = np.maximum(np.stack([A.astype(np.float64) @ B.astype(np.float64), 2 * (A.astype(np.float64) @ B.astype(np.float64))]), 0)
+    assert np.allclose(y, ref, rtol=0, atol=1e-13)
+
+
 def test_rejects_bad_arguments():
     A = np.zeros((2, 2), dtype=np.float32)
     with pytest.raises(ValueError):
