@@ -28,11 +28,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-PEAK_TFLOPS = {0: 157.3, 1: 2516.6}          # fp32 MFMA, bf16 MFMA (dense)
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6}          # fp32, bf16, fp16 MFMA (dense)
 # which roof bounds each workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
-         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma"}
-DTYPE_NAME = {0: "f32", 1: "bf16"}
+         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma"}
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}
 # streaming siblings: (entry point, op, arrays read, arrays written)
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
            "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0)}
@@ -414,8 +414,8 @@ def main():
             sample = f"{len(sb)} sampled output entries of {w.batch * w.M * w.N}"
             got = sets[(args.steps - 1) & 1][3].cpu().numpy()
             idx = (sb, si, sj)
-        if w.dtype == 1:
-            got = synth.bf16_bits_to_f32(got.view(np.uint16))
+        if w.dtype != 0:
+            got = synth.from_bits(got.view(np.uint16), w.dtype)
         got = got.astype(np.float64)
         if idx is not None:
             got = got[idx]
@@ -430,7 +430,7 @@ def main():
 
     if args.all:
         out["workloads"] = {}
-        for name in synth.WORKLOADS:
+        for name in synth.WORKLOADS + synth.BREADTH_WORKLOADS:
             if name == args.workload:
                 out["workloads"][name] = head
                 continue

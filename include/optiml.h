@@ -11,7 +11,7 @@
  * every row of the product, then an elementwise activation - ReLU max(0,x)
  * (Table 4, task 10), SiLU x*sigmoid(x) with sigmoid(x) = 1/(1+exp(-x))
  * (Table 4, task 1), or the tanh form of GELU
- * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).  Bias, SiLU, GELU, bf16
+ * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).  Bias, SiLU, GELU, 16-bit
  * storage, column-major operands and batching extend the paper's task; they
  * take their standard definitions.
  *
@@ -25,10 +25,13 @@
  *              A column-major: A[i,k] at A[k*lda + i], lda >= M.
  *              B row-major: B[k,j] at B[k*ldb + j], ldb >= N;
  *              B column-major: B[k,j] at B[j*ldb + k], ldb >= K.
- *   dtype      OPTIML_F32: A, B, C are float.  OPTIML_BF16: A, B, C are bfloat16
- *              (16-bit storage); products are accumulated in fp32, bias is added
- *              and the activation applied in fp32, and C is rounded once, to nearest
- *              even.  bias is always float; NULL means no bias.
+ *   dtype      OPTIML_F32: A, B, C are float.  OPTIML_BF16: A, B, C are bfloat16,
+ *              OPTIML_F16: IEEE binary16 (16-bit storage either way); products are
+ *              accumulated in fp32, bias is added and the activation applied in fp32,
+ *              and C is rounded once, to nearest even (binary16: beyond 65504 to
+ *              infinity).  bias is always float; NULL means no bias.  The
+ *              contraction entry points take all three; the other entry points say
+ *              which they take.
  *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
  *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
  *   Stream     `stream` is a hipStream_t passed as void* (NULL = the default
@@ -63,7 +66,7 @@
 extern "C" {
 #endif
 
-typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1 } optiml_dtype_t;
+typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2 } optiml_dtype_t;
 
 typedef enum {
     OPTIML_ACT_NONE = 0,

@@ -33,7 +33,7 @@ const Table &table()
 
 bool enum_ok(int layout, int dtype, int act)
 {
-    return layout >= 0 && layout <= 3 && (dtype == DT_F32 || dtype == DT_BF16) && act >= 0 && act <= 3;
+    return layout >= 0 && layout <= 3 && (dtype == DT_F32 || dtype == DT_BF16 || dtype == DT_F16) && act >= 0 && act <= 3;
 }
 
 // OPTIML_OK when the arguments describe a valid problem (possibly an empty one).

@@ -6,7 +6,7 @@
 
 namespace optiml {
 
-enum : int { DT_F32 = 0, DT_BF16 = 1 };
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
 
 // C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.

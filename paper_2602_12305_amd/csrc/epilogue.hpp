@@ -48,9 +48,9 @@ __device__ __forceinline__ float apply_act(float z, int act)
     }
 }
 
-// The same activations for results that are rounded to bf16 (relative step 2^-8): the
+// The same activations for results that are rounded to bf16 or fp16 (relative step 2^-8 / 2^-11): the
 // exponential is the bare v_exp_f32 of -x*log2(e), whose argument rounding costs at most
-// 6e-8*|x| of relative error, five orders below the output format's resolution.
+// 6e-8*|x| of relative error, orders below either output format's resolution.
 __device__ __forceinline__ float sigmoid_bf16out(float x)
 {
     return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.44269502162933349609375f));
@@ -108,6 +108,53 @@ __device__ __forceinline__ unsigned int f32x2_to_bf16x2(float lo, float hi)
 __device__ __forceinline__ float bf16_to_f32(unsigned short b)
 {
     return __uint_as_float(((unsigned int)b) << 16);
+}
+
+// IEEE binary16 storage: the hardware conversions round to nearest even (the default mode).
+__device__ __forceinline__ unsigned int f32x2_to_f16x2(float lo, float hi)
+{
+    typedef float floatx2_ __attribute__((ext_vector_type(2)));
+    typedef _Float16 halfx2_ __attribute__((ext_vector_type(2)));
+    const halfx2_ v = __builtin_convertvector(floatx2_{lo, hi}, halfx2_);
+    return __builtin_bit_cast(unsigned int, v);
+}
+
+__device__ __forceinline__ unsigned short f32_to_f16(float f)
+{
+    return __builtin_bit_cast(unsigned short, (_Float16)f);
+}
+
+__device__ __forceinline__ float f16_to_f32(unsigned short b)
+{
+    return (float)__builtin_bit_cast(_Float16, b);
+}
+
+// The two 16-bit storage types share every kernel; these pick the conversions and the matrix
+// instruction (same shape, same register layout) by the dtype code.
+template <int DT> __device__ __forceinline__ unsigned int pack2_16(float lo, float hi)
+{
+    return DT == DT_F16 ? f32x2_to_f16x2(lo, hi) : f32x2_to_bf16x2(lo, hi);
+}
+template <int DT> __device__ __forceinline__ unsigned short to_16(float f)
+{
+    return DT == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f);
+}
+template <int DT> __device__ __forceinline__ float from_16(unsigned short b)
+{
+    return DT == DT_F16 ? f16_to_f32(b) : bf16_to_f32(b);
+}
+template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x16(V4 a, V4 b, ACC c)
+{
+    typedef __bf16 bf16x8_ __attribute__((ext_vector_type(8)));
+    typedef _Float16 halfx8_ __attribute__((ext_vector_type(8)));
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (DT == DT_F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8_, a), __builtin_bit_cast(halfx8_, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_, a), __builtin_bit_cast(bf16x8_, b), c, 0, 0, 0);
+#else
+    return c;
+#endif
 }
 
 }  // namespace optiml

@@ -20,9 +20,11 @@ constexpr int PADDED = GT + 4;
 template <typename E> __device__ __forceinline__ float widen(E v);
 template <> __device__ __forceinline__ float widen<float>(float v) { return v; }
 template <> __device__ __forceinline__ float widen<unsigned short>(unsigned short v) { return bf16_to_f32(v); }
+template <> __device__ __forceinline__ float widen<_Float16>(_Float16 v) { return (float)v; }
 
 __device__ __forceinline__ void put(float *p, float y) { *p = y; }
 __device__ __forceinline__ void put(unsigned short *p, float y) { *p = f32_to_bf16(y); }
+__device__ __forceinline__ void put(_Float16 *p, float y) { *p = (_Float16)y; }
 
 template <typename E>
 __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_m, int64_t y0)
@@ -101,6 +103,8 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
         dim3 grid((unsigned)blocks_n, (unsigned)ny), block(256);
         if (p.dtype == DT_F32)
             hipLaunchKernelGGL(generic_kernel<float>, grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_F16)
+            hipLaunchKernelGGL(generic_kernel<_Float16>, grid, block, 0, s, p, blocks_m, y0);
         else
             hipLaunchKernelGGL(generic_kernel<unsigned short>, grid, block, 0, s, p, blocks_m, y0);
         hipError_t e = hipGetLastError();

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
                             y[e] = apply_act_bf16out(acc[jn][i][4 * gq + e] + (has_bias ? bv[e] : 0.0f), ACT);
                         *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                             slab + frag_row * PITCH + (((4 * jn + gq) ^ wkey) << 4) + 8 * half) =
-                            uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
+                            uintx2{pack2_16<C::DT>(y[0], y[1]), pack2_16<C::DT>(y[2], y[3])};
                     }
 #pragma unroll
                 for (int q = 0; q < READS; ++q) {

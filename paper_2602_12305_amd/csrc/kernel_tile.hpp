@@ -1,4 +1,4 @@
-// MFMA tile kernel for C = act(A.B + bias), fp32 and bf16 inputs, all four
+// MFMA tile kernel for C = act(A.B + bias), fp32 and 16-bit (bf16, fp16) inputs, all four
 // operand layouts, single and strided-batched.
 //
 // The paper's matmul case study arrives at a 16x16 shared-memory tile with one
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
         if (more) fetch(kt + 1);
 
         const char *a_base = cur + a_wave, *b_base = cur + C::A_BYTES + b_wave;
-        if constexpr (C::dt == DT_BF16) {
+        if constexpr (C::dt != DT_F32) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 uintx4 fa[TM], fb[TN];
@@ -270,9 +270,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[j]),
-                                                                            __builtin_bit_cast(bf16x8, fa[i]),
-                                                                            acc[j][i], 0, 0, 0);
+                        acc[j][i] = mfma_32x32x16<C::dt>(fb[j], fa[i], acc[j][i]);
             }
         } else {
             // fp32: k-tiles are summed into a second accumulator set that is added to the
@@ -373,7 +371,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
                 } else {
                     unsigned short h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16(y[e]);
+                    for (int e = 0; e < 4; ++e) h[e] = to_16<C::dt>(y[e]);
                     if (whole) {
                         *reinterpret_cast<uintx2 *>(dst) =
                             uintx2{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};

@@ -51,8 +51,9 @@ struct Params {
     int act;
 };
 
-template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4>
+template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16>
 struct Cfg {
+    static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
     static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier
@@ -168,8 +169,7 @@ __device__ __forceinline__ void mma_frags(const Frags<C> &f, floatx16 (&acc)[C::
     for (int j = J0; j < J1; ++j)
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
-            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.b[j]),
-                                                                __builtin_bit_cast(bf16x8, f.a[i]), acc[j][i], 0, 0, 0);
+            acc[j][i] = mfma_32x32x16<C::DT>(f.b[j], f.a[i], acc[j][i]);
 }
 
 // One k-tile of 32: see the file header for the order of events.  With C::PF the operands of
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
                 for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], ACT);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
-                    uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
+                    uintx2{pack2_16<C::DT>(y[0], y[1]), pack2_16<C::DT>(y[2], y[3])};
             }
 #pragma unroll
         for (int q = 0; q < READS; ++q) {
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
 template <class C>
 bool supports(const Problem &p)
 {
-    if (p.dtype != DT_BF16 || p.a_col() || p.b_col() != C::B_KC) return false;
+    if (p.dtype != C::DT || p.a_col() || p.b_col() != C::B_KC) return false;
     if (p.K < 32 * C::NS || p.K % 32 != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 8 != 0)) return false;
     const int64_t a_span = p.M * p.lda * 2, b_span = (C::B_KC ? p.N : 32) * p.ldb * 2 + p.N * 2;

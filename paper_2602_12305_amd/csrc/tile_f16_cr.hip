@@ -1,0 +1,8 @@
+// MFMA tile kernels, fp16 inputs, layout cr (A column-major, B row-major).
+#define TILE_DT optiml::DT_F16
+#define TILE_IS_F32 0
+#define TILE_A_KC false
+#define TILE_B_KC false
+#define TILE_TAG "f16_cr"
+#define TILE_SYMBOL kTile_f16_cr
+#include "tile_instances.inc"

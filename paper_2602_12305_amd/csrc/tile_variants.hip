@@ -5,33 +5,39 @@ namespace optiml {
 
 const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc();
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
+const Variant *kTile_f16_rr(), *kTile_f16_rc(), *kTile_f16_cr(), *kTile_f16_cc();
 const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc();
-const Variant *kRing_bf16_rr(), *kRing_bf16_rc();
+const Variant *kRing_bf16_rr(), *kRing_bf16_rc(), *kRing_f16_rr(), *kRing_f16_rc();
 const Variant *kRing_f32_rr(), *kRing_f32_rc();
 
 namespace {
+constexpr int kTotal = 12 * kTilesPerUnit + 2 * kDirectPerUnit + 4 * kRingPerUnit + 2 * kRingF32PerUnit;
 struct Gather {
-    Variant v[8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit + 2 * kRingF32PerUnit];
+    Variant v[kTotal];
     Gather()
     {
-        // the direct-to-LDS kernels come first: where they apply the dispatcher prefers them
-        constexpr int R = 2 * kRingPerUnit, F = R + 2 * kDirectPerUnit, D = F + 2 * kRingF32PerUnit;
-        for (int i = 0; i < kRingF32PerUnit; ++i) {
-            v[F + i] = kRing_f32_rr()[i];
-            v[F + kRingF32PerUnit + i] = kRing_f32_rc()[i];
-        }
-        for (int i = 0; i < kRingPerUnit; ++i) {
-            v[i] = kRing_bf16_rr()[i];
-            v[kRingPerUnit + i] = kRing_bf16_rc()[i];
-        }
-        for (int i = 0; i < kDirectPerUnit; ++i) {
-            v[R + i] = kDirect_bf16_rr()[i];
-            v[R + kDirectPerUnit + i] = kDirect_bf16_rc()[i];
-        }
+        // order = the dispatcher's preference where several apply: ring kernels, then the
+        // direct-to-LDS ones, then the staged tiles
+        int n = 0;
+        auto add = [&](const Variant *unit, int count) {
+            for (int i = 0; i < count; ++i) v[n++] = unit[i];
+        };
+        add(kRing_bf16_rr(), kRingPerUnit);
+        add(kRing_bf16_rc(), kRingPerUnit);
+        add(kDirect_bf16_rr(), kDirectPerUnit);
+        add(kDirect_bf16_rc(), kDirectPerUnit);
+        add(kRing_f32_rr(), kRingF32PerUnit);
+        add(kRing_f32_rc(), kRingF32PerUnit);
         const Variant *units[8] = {kTile_f32_rr(),  kTile_f32_rc(),  kTile_f32_cr(),  kTile_f32_cc(),
                                    kTile_bf16_rr(), kTile_bf16_rc(), kTile_bf16_cr(), kTile_bf16_cc()};
-        for (int u = 0; u < 8; ++u)
-            for (int i = 0; i < kTilesPerUnit; ++i) v[D + u * kTilesPerUnit + i] = units[u][i];
+        for (int u = 0; u < 8; ++u) add(units[u], kTilesPerUnit);
+        // fp16 after everything that existed before it, so that variant indices stay put
+        add(kRing_f16_rr(), kRingPerUnit);
+        add(kRing_f16_rc(), kRingPerUnit);
+        add(kTile_f16_rr(), kTilesPerUnit);
+        add(kTile_f16_rc(), kTilesPerUnit);
+        add(kTile_f16_cr(), kTilesPerUnit);
+        add(kTile_f16_cc(), kTilesPerUnit);
     }
 };
 }  // namespace
@@ -41,6 +47,6 @@ const Variant *tile_variants()
     static const Gather g;
     return g.v;
 }
-const int kNumTileVariants = 8 * kTilesPerUnit + 2 * kDirectPerUnit + 2 * kRingPerUnit + 2 * kRingF32PerUnit;
+const int kNumTileVariants = kTotal;
 
 }  // namespace optiml

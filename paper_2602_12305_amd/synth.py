@@ -131,6 +131,34 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to IEEE binary16 (nearest, ties to even; overflow to infinity); uint16 bit patterns."""
+    with np.errstate(over="ignore"):
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def to_bits(x, dtype):
+    """Storage of an fp32 array in the given dtype: fp32 itself, or the uint16 patterns of bf16 / fp16."""
+    if dtype == DTYPE_BF16:
+        return f32_to_bf16_bits(x)
+    if dtype == DTYPE_F16:
+        return f32_to_f16_bits(x)
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def from_bits(b, dtype):
+    """fp32 values of stored data (inverse of to_bits)."""
+    if dtype == DTYPE_BF16:
+        return bf16_bits_to_f32(b)
+    if dtype == DTYPE_F16:
+        return f16_bits_to_f32(b)
+    return np.asarray(b, dtype=np.float32)
+
+
 def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
     """(b, i, j) int64 triples to verify when the full output is too large to check:
     `count` iid uniform draws, plus the four corners of every batch's first and last
@@ -161,7 +189,7 @@ def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
 # ----------------------------------------------------------------------------------------------
 # The five workloads
 
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 
@@ -200,11 +228,12 @@ class Workload:
 def _store(x, dtype, transpose=False):
     if transpose:
         x = np.ascontiguousarray(np.swapaxes(x, -1, -2))
-    return f32_to_bf16_bits(x) if dtype == DTYPE_BF16 else np.ascontiguousarray(x)
+    return to_bits(x, dtype)
 
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
+BREADTH_WORKLOADS = ("c4_f16_8192_silu",)     # further dtypes on the same shapes
 
 
 def make_workload(name: str, scale: int = 1) -> Workload:
@@ -236,6 +265,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
         return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_RR, 3,
                         _store(normal(3, "A", M, K), DTYPE_BF16),
                         _store(normal(3, "B", K, N), DTYPE_BF16),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c4_f16_8192_silu":             # config 4's shape and distributions in binary16 storage
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_F16, ACT_SILU, LAYOUT_RR, 3,
+                        _store(normal(3, "A", M, K), DTYPE_F16),
+                        _store(normal(3, "B", K, N), DTYPE_F16),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c5_bf16_batched32_relu":
         nb, M, N, K = 32, 2048 // s, 2048 // s, 512 // s

@@ -24,13 +24,13 @@ def store(X, dtype, col_major=False, pad=0):
         P = np.full(shp, 777.0, dtype=np.float32)
         P[..., : X.shape[-1]] = X
         X = P
-    return synth.f32_to_bf16_bits(X) if dtype == synth.DTYPE_BF16 else X
+    return synth.to_bits(X, dtype)
 
 
 def as_real(X, dtype):
     """Stored operand -> the exact real values it holds, as fp64."""
-    if dtype == synth.DTYPE_BF16:
-        return synth.bf16_bits_to_f32(X).astype(np.float64)
+    if dtype != synth.DTYPE_F32:
+        return synth.from_bits(X, dtype).astype(np.float64)
     return np.asarray(X, dtype=np.float64)
 
 

@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=4), dict(layout=-1), dict(dtype=2), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=4), dict(layout=-1), dict(dtype=3), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])
@@ -146,6 +146,10 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 4096, 4096, 4096, layout=1).startswith("ring_f32_rc_128x128")
     assert sel(1, 8192, 8192, 8192, dtype=1).startswith("ring_bf16_rr_256x256")
     assert sel(32, 2048, 2048, 512, dtype=1).startswith("ringp_bf16_rr_256x256")   # many short tiles: persistent
+    assert sel(1, 8192, 8192, 8192, dtype=2).startswith("ring_f16_rr_256x256")      # binary16: the same kernels
+    assert sel(32, 2048, 2048, 512, dtype=2, layout=1).startswith("ringp_f16_rc_256x256")
+    assert sel(1, 1024, 1024, 64, layout=2, dtype=2).startswith("tile_f16_cr_")
+    assert sel(1, 1000, 1001, 64, dtype=2) == "generic_64x64"
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays

@@ -19,7 +19,8 @@ from helpers import e1, store
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16 = synth.DTYPE_F32, synth.DTYPE_BF16
+F32, BF16, F16 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16
+DT_OF = {"f32": F32, "bf16": BF16, "f16": F16}
 ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
 LAYOUT_OF = {"rr": 0, "rc": 1, "cr": 2, "cc": 3}
 
@@ -43,13 +44,13 @@ def problem_for(name):
             # two whole summation blocks, one partial block, and a tail shorter than the ring
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
-        return BF16, LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
+        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
         return BF16, LAYOUT_OF[lay], 300, 392, 320          # K a multiple of 64
     if name.startswith("tile"):
         _, dt, lay = name.split("_")[:3]
-        dtype = F32 if dt == "f32" else BF16
+        dtype = DT_OF[dt]
         ch = 4 if dtype == F32 else 8
         M, N, K = 300, 392, 200      # multiples of 8 where a contiguous extent needs it
         layout = LAYOUT_OF[lay]
@@ -104,6 +105,7 @@ def test_persistent_variants_walk_several_tiles(vid):
     bias on integer inputs (exact), where a tile computed from the wrong panel cannot hide."""
     name = ob.optiml_variant_name(vid)
     layout = LAYOUT_OF[name.split("_")[2]]
+    BF16 = DT_OF[name.split("_")[1]]          # the variant's own 16-bit storage type
     batch, M, N, K = 9, 1100, 1544, 224
     A = synth.normal(700 + vid, "A", M, K, batch=batch); B = synth.normal(700 + vid, "B", K, N, batch=batch)
     bias = synth.normal(700 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
@@ -139,7 +141,14 @@ def test_dispatch_random_shapes(t, M, N, K, layout, dtype, act, pad, use_bias):
     check_against_oracle(A, B, bias, dtype=dtype, act=act, layout=layout, pad=pad, ldc_pad=pad)
 
 
-@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("t,M,N,K,layout,dtype,act,pad,use_bias", [c for c in fuzz_cases() if c[0] % 2 == 0])
+def test_dispatch_random_shapes_in_binary16(t, M, N, K, layout, dtype, act, pad, use_bias):
+    A = synth.uniform(450 + t, "A", M, K); B = synth.uniform(450 + t, "B", K, N)
+    bias = synth.uniform(450 + t, "bias", 1, N)[0] if use_bias else None
+    check_against_oracle(A, B, bias, dtype=F16, act=act, layout=layout, pad=pad, ldc_pad=pad)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
 @pytest.mark.parametrize("layout", [0, 1, 2, 3])
 def test_dispatch_aligned_multi_tile_shapes(dtype, layout):
     # shapes the fast kernels take (aligned, multiples of 8), several tiles in both directions,
@@ -346,5 +355,30 @@ def test_bf16_output_rounding_ties_and_specials():
         from gpu_harness import to_host
         got = to_host(Cd)[0]
         want = oracle.bf16_from_double(bias.astype(np.float64))
+        bad = np.argwhere(got != np.broadcast_to(want, got.shape))
+        assert bad.size == 0, (name, [(float(bias[j]), hex(int(got[i, j])), hex(int(want[j]))) for i, j in bad[:6]])
+
+
+def test_f16_output_rounding_ties_overflow_and_subnormals():
+    # A = 0, so z = bias exactly: the stored binary16 must be the nearest-even rounding of the fp32 bias, including
+    # exact ties, values just off a tie, binary16 subnormals, and the overflow threshold (65520 and up: infinity)
+    rng = np.random.default_rng(10)
+    base = oracle.f16_to_double(rng.integers(0x0001, 0x7BFF, size=2048, dtype=np.uint16))
+    step = oracle.f16_to_double(oracle.f16_from_double(base) + np.uint16(1)) - base          # distance to the next value up
+    vals = np.concatenate([base + step / 2, base + step / 4, base + step * (0.5 + 2.0 ** -10), base + step * (0.5 - 2.0 ** -10),
+                           -(base + step / 2), [0.0, 2.0 ** -25, 2.0 ** -25 * (1 + 2.0 ** -10), -2.0 ** -24, 65504.0, 65519.0, 65520.0, -65520.0, 1e6]])
+    bias = vals.astype(np.float32)                         # every value above has at most 22 significant bits: exact in fp32
+    assert np.array_equal(bias.astype(np.float64), vals)
+    N = (bias.size + 7) // 8 * 8
+    bias = np.concatenate([bias, np.zeros(N - bias.size, dtype=np.float32)])
+    M, K = 40, 192
+    A = np.zeros((M, K), dtype=np.float32); B = np.zeros((K, N), dtype=np.float32)
+    from gpu_harness import to_host
+    for vid, name in all_variants():
+        if "f16_rr" not in name.replace("bf16", "") and not name.startswith("generic"):
+            continue
+        _, _, Cd = run_gpu(store(A, F16), store(B, F16), bias, 1, M, N, K, F16, synth.ACT_NONE, 0, variant=vid)
+        got = to_host(Cd)[0]
+        want = oracle.f16_from_double(bias.astype(np.float64))
         bad = np.argwhere(got != np.broadcast_to(want, got.shape))
         assert bad.size == 0, (name, [(float(bias[j]), hex(int(got[i, j])), hex(int(want[j]))) for i, j in bad[:6]])

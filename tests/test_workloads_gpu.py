@@ -46,10 +46,10 @@ def reference(w, Y):
 
 
 FULL_CHECK = {"c1_f32_256_relu": "full", "c2_f32_skinny16_silu": "full", "c3_f32_4096_rc_gelu": "full",
-              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full"}
+              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full", "c4_f16_8192_silu": "sampled"}
 
 
-@pytest.mark.parametrize("name", synth.WORKLOADS)
+@pytest.mark.parametrize("name", synth.WORKLOADS + synth.BREADTH_WORKLOADS)
 def test_workload_matches_oracle(name):
     w = synth.make_workload(name)
     w.check = FULL_CHECK[name]
@@ -58,16 +58,17 @@ def test_workload_matches_oracle(name):
     assert np.all(np.isfinite(Y))
     err = e1(got, ref)
     # componentwise forward error against |bias| + sum|a b| (fp32 accumulation), plus half a
-    # bf16 step of the value for the one rounding of a bf16 output; below 1e-36 (SiLU of
+    # step of the value for the one rounding of a bf16 / binary16 output; below 1e-36 (SiLU of
     # z < -88, where exp(-z) overflows fp32) the kernel may return -0
-    step = 2.0 ** -8 * 1.01 * np.abs(ref) if w.dtype == synth.DTYPE_BF16 else 0.0
+    half_step = {synth.DTYPE_F32: 0.0, synth.DTYPE_BF16: 2.0 ** -8, synth.DTYPE_F16: 2.0 ** -11}[w.dtype]
+    step = half_step * 1.01 * np.abs(ref)
     e2 = float(np.max((np.abs(got - ref) - step - 1e-36) / den))
     print(f"{name}: E1 = {err:.3e}, E2 = {e2:.3e} over {ref.size} entries ({w.check})")
     assert err <= TOL[w.dtype]
     assert e2 <= 16 * 2.0 ** -24
 
 
-@pytest.mark.parametrize("name", synth.WORKLOADS)
+@pytest.mark.parametrize("name", synth.WORKLOADS + synth.BREADTH_WORKLOADS)
 def test_workload_shape_is_exact_on_integers(name):
     w = synth.make_workload(name, scale=1 if name in ("c1_f32_256_relu", "c5_bf16_batched32_relu") else 1)
     lead = (w.batch,) if w.batch > 1 else ()
@@ -75,7 +76,7 @@ def test_workload_shape_is_exact_on_integers(name):
         x = synth.integers(w.seed + 77, tag, rows, cols, batch=w.batch if w.batch > 1 else None)
         if transpose:
             x = np.ascontiguousarray(np.swapaxes(x, -1, -2))
-        return synth.f32_to_bf16_bits(x) if w.dtype == synth.DTYPE_BF16 else x
+        return synth.to_bits(x, w.dtype)
     w.A = ints("A", w.M, w.K, bool(w.layout & 2))
     w.B = ints("B", w.K, w.N, bool(w.layout & 1))
     w.bias = synth.integers(w.seed + 77, "bias", 1, w.N, -5, 5, batch=w.batch).reshape(w.batch, w.N)
@@ -85,4 +86,6 @@ def test_workload_shape_is_exact_on_integers(name):
     got, ref, _ = reference(w, Y)
     if w.dtype == synth.DTYPE_BF16:
         ref = synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64)
+    elif w.dtype == synth.DTYPE_F16:
+        ref = oracle.f16_to_double(oracle.f16_from_double(ref))
     assert np.array_equal(got, ref)
