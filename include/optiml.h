@@ -44,11 +44,13 @@
  *   Results    Repeating a call with the same arguments gives bitwise the same C
  *              (no floating-point atomics; split-K partial sums are combined in a
  *              fixed order).
- *   Workspace  Split-K kernels keep partial sums in one per-device buffer that the
- *              library allocates on first need and grows when a larger one is
- *              needed (the only allocation the library ever makes); calls that use
- *              it are ordered by the stream they are enqueued on, and two streams
- *              must not run split-K calls on one device at the same time.
+ *   Workspace  Split-K kernels keep partial sums, and the fast path for a column-major
+ *              A keeps a row-major copy of A (batch x M x K elements), in one
+ *              per-device buffer that the library allocates on first need and grows
+ *              when a larger one is needed (the only allocation the library ever
+ *              makes); calls that use it are ordered by the stream they are enqueued
+ *              on, and two streams must not run such calls on one device at the
+ *              same time.
  *   Errors     The return value is an optiml_status_t; nothing is thrown or
  *              aborted.  OPTIML_ERR_INVALID_ARG: a NULL A/B (with K > 0) or C, a
  *              negative size or stride, an ld shorter than the row it spans, an

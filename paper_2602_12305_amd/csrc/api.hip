@@ -22,6 +22,7 @@ struct Table {
         for (int i = 0; i < kNumSkinnyVariants; ++i) v.push_back(&skinny_variants()[i]);
         first_tile = (int)v.size();
         for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
+        for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);
     }
 };
 

@@ -40,7 +40,8 @@ bool vector_friendly(const Problem &p);
 // number of compute units of the current device (256 if the query fails)
 int compute_units();
 
-// per-device scratch for split-K partial sums (grown on demand, never shrunk)
+// per-device scratch (split-K partial sums, reduction partials, the row-major copy of a
+// column-major A): grown on demand, never shrunk
 hipError_t workspace(size_t bytes, void **ptr);
 
 // streaming siblings (kernel_streams.hip); arguments already validated
@@ -61,6 +62,7 @@ const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
+const Variant *transpose_variants();       extern const int kNumTransposeVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
 constexpr int kRingPerUnit = 4;            // ring-of-stages bf16 kernels per B layout (three one-tile, one persistent)

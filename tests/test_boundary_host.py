@@ -150,6 +150,9 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(32, 2048, 2048, 512, dtype=2, layout=1).startswith("ringp_f16_rc_256x256")
     assert sel(1, 1024, 1024, 64, layout=2, dtype=2).startswith("tile_f16_cr_")
     assert sel(1, 1000, 1001, 64, dtype=2) == "generic_64x64"
+    assert sel(1, 8192, 8192, 8192, layout=2, dtype=1) == "xa_ring"       # column-major A: row-major copy, then a ring kernel
+    assert sel(1, 4096, 4096, 4096, layout=3) == "xa_ring"
+    assert sel(1, 2048, 512, 2048, layout=2, dtype=1).startswith("tile_bf16_cr_")   # too few columns to pay for the copy
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays

@@ -45,6 +45,8 @@ def problem_for(name):
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
         return DT_OF[dt], LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
+    if name.startswith("xa_"):
+        return BF16, 2, 304, 392, 480                      # A column-major, M and K whole 16-byte chunks
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
         return BF16, LAYOUT_OF[lay], 300, 392, 320          # K a multiple of 64
@@ -382,3 +384,26 @@ def test_f16_output_rounding_ties_overflow_and_subnormals():
         want = oracle.f16_from_double(bias.astype(np.float64))
         bad = np.argwhere(got != np.broadcast_to(want, got.shape))
         assert bad.size == 0, (name, [(float(bias[j]), hex(int(got[i, j])), hex(int(want[j]))) for i, j in bad[:6]])
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+@pytest.mark.parametrize("layout", [2, 3])
+def test_column_major_a_through_the_row_major_copy(dtype, layout):
+    """The fast path for a column-major A (copy to row-major in the workspace, then a ring kernel): ragged copy
+    tiles, a batch, shared A (stride 0) and padded leading dimensions, forced and as the dispatcher's own choice."""
+    vid = variant_ids("xa_ring")[0]
+    batch, M, N, K = 3, 328, 1032, 416
+    A = synth.normal(900 + layout, "A", M, K, batch=batch); B = synth.normal(900 + layout, "B", K, N, batch=batch)
+    bias = synth.normal(900 + layout, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid)
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, pad=8, ldc_pad=8)
+    Ai = synth.integers(910, "A", M, K, batch=batch); Bi = synth.integers(910, "B", K, N, batch=batch)
+    check_against_oracle(Ai, Bi, None, dtype=dtype, act=synth.ACT_RELU, layout=layout, variant=vid, exact=True)
+    # the dispatcher picks it by itself for a shape with enough columns and tiles
+    M, N, K = 2048, 2048, 256
+    lda = M
+    v = ob.optiml_select_variant(1, M, N, K, 0x1000, lda, 0, 0x1000, K if layout & 1 else N, 0, 0x1000, 0, 0x1000, N, 0,
+                                 layout, dtype, 0)
+    assert ob.optiml_variant_name(v) == "xa_ring"
+    A = synth.uniform(920, "A", M, K); B = synth.uniform(920, "B", K, N); bias = synth.uniform(920, "bias", 1, N)[0]
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout, entry="ex")
