@@ -52,6 +52,8 @@ def lib():
         L.oracle_reduce.argtypes = [i64, vp, vp, C.c_int]
         L.oracle_cross_entropy.restype = C.c_double
         L.oracle_cross_entropy.argtypes = [i64, i64, vp, vp]
+        L.oracle_cross_entropy_f64.restype = C.c_double
+        L.oracle_cross_entropy_f64.argtypes = [i64, i64, vp, vp]
         L.oracle_layernorm.restype = None
         L.oracle_layernorm.argtypes = [i64, i64, vp, C.c_double, vp]
         L.oracle_mhsa.restype = C.c_int
@@ -180,6 +182,17 @@ def cross_entropy(z, labels):
     if z.ndim != 2 or labels.shape != (z.shape[0],):
         raise ValueError("logits [N, C] and labels [N] expected")
     return float(lib().oracle_cross_entropy(z.shape[0], z.shape[1], _ptr(z), _ptr(labels)))
+
+
+def gemm_cross_entropy(A, B, bias, labels, M, N, K, *, dtype=F32, layout=LAYOUT_RR):
+    """Mean over the M rows of log(sum_j exp(z_ij)) - z_{i, label_i} for the logits z = A.B + bias of the
+    contraction (task 2 feeding task 17 of Table 4), every step in fp64: the logits are never rounded."""
+    z = gemm_epilogue(A, B, bias, M, N, K, dtype=dtype, act=ACT_NONE, layout=layout)[0]
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    if labels.shape != (M,):
+        raise ValueError("labels [M] expected")
+    return float(lib().oracle_cross_entropy_f64(M, N, _ptr(z), _ptr(labels)))
 
 
 def layernorm(x, eps=1e-5):

@@ -105,6 +105,37 @@ double oracle_cross_entropy(int64_t N, int64_t C, const float *z, const int32_t 
 }
 
 /*
+ * The same loss for logits that are already fp64 (the fused contraction + cross-entropy keeps its
+ * logits unrounded): identical steps, no conversion.
+ */
+double oracle_cross_entropy_f64(int64_t N, int64_t C, const double *z, const int32_t *labels)
+{
+    enum { BLOCK = 4096 };
+    const int64_t blocks = (N + BLOCK - 1) / BLOCK;
+    double *part = (double *)malloc(sizeof(double) * (size_t)(blocks > 0 ? blocks : 1));
+    if (!part) return NAN;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < blocks; ++b) {
+        const int64_t lo = b * BLOCK, hi = lo + BLOCK < N ? lo + BLOCK : N;
+        double s = 0.0;
+        for (int64_t j = lo; j < hi; ++j) {
+            const double *row = z + j * C;
+            if (labels[j] < 0 || labels[j] >= C) { s = NAN; continue; }
+            double m = row[0];
+            for (int64_t k = 1; k < C; ++k) m = row[k] > m ? row[k] : m;
+            double e = 0.0;
+            for (int64_t k = 0; k < C; ++k) e += exp(row[k] - m);
+            s += log(e) - (row[labels[j]] - m);
+        }
+        part[b] = s;
+    }
+    double total = 0.0;
+    for (int64_t b = 0; b < blocks; ++b) total += part[b];
+    free(part);
+    return N > 0 ? total / (double)N : 0.0;
+}
+
+/*
  * LayerNorm of `rows` samples of `len` features each.  Two passes per row in fp64: the mean
  * (sum in index order / len), then the biased variance as the mean of squared deviations from
  * that mean (not E[x^2] - mean^2), then y = (x - mean) / sqrt(var + eps).  Results kept in fp64.

@@ -216,3 +216,49 @@ def test_layernorm_against_exact_rational_statistics():
     mb = sum(xb) / L; vb = sum((v - mb) ** 2 for v in xb) / L
     yb = oracle.layernorm(big, eps=0.0)[0]
     assert yb[7] == pytest.approx(float(xb[7] - mb) / math.sqrt(float(vb)), rel=1e-10)
+
+
+# ---- the contraction feeding the cross-entropy (logits never rounded) -------------------------------------------
+@pytest.mark.parametrize("dtype,layout", [(oracle.F32, 0), (oracle.BF16, 1), (oracle.F16, 2), (oracle.F32, 3)])
+def test_fused_contraction_cross_entropy_against_library_routines(dtype, layout):
+    """numpy's fp64 matmul of the decoded operands and scipy's logsumexp, neither of which the oracle calls."""
+    from scipy.special import logsumexp
+    M, N, K = 37, 53, 29
+    A = synth.normal(70, "A", M, K); B = synth.normal(70, "B", K, N); bias = synth.normal(70, "bias", 1, N)[0]
+    labels = ((11 * np.arange(M) + 3) % N).astype(np.int32)
+    As = synth.to_bits(A.T if layout & 2 else A, dtype); Bs = synth.to_bits(B.T if layout & 1 else B, dtype)
+    got = oracle.gemm_cross_entropy(As, Bs, bias, labels, M, N, K, dtype=dtype, layout=layout)
+    Ad = synth.from_bits(synth.to_bits(A, dtype), dtype).astype(np.float64)
+    Bd = synth.from_bits(synth.to_bits(B, dtype), dtype).astype(np.float64)
+    z = Ad @ Bd + bias.astype(np.float64)
+    want = float(np.mean(logsumexp(z, axis=1) - z[np.arange(M), labels]))
+    assert got == pytest.approx(want, rel=1e-13)
+    # a wrong label, a dropped bias or a transposed operand all move the value
+    assert abs(oracle.gemm_cross_entropy(As, Bs, None, labels, M, N, K, dtype=dtype, layout=layout) - want) > 1e-5
+    assert abs(oracle.gemm_cross_entropy(As, Bs, bias, (labels + 1) % N, M, N, K, dtype=dtype, layout=layout) - want) > 1e-5
+
+
+def test_fused_contraction_cross_entropy_closed_forms():
+    M, N, K = 9, 16, 8
+    A = synth.normal(71, "A", M, K); Z = np.zeros((K, N), dtype=np.float32)
+    labels = (np.arange(M) % N).astype(np.int32)
+    # zero weights, no bias: uniform prediction, loss log N whatever the labels
+    assert oracle.gemm_cross_entropy(A, Z, None, labels, M, N, K) == pytest.approx(math.log(N), rel=1e-15)
+    # zero weights: the loss of the bias alone, the same for every row
+    bias = synth.normal(71, "bias", 1, N)[0]
+    b64 = bias.astype(np.float64)
+    lse = math.log(float(np.sum(np.exp(b64 - b64.max())))) + float(b64.max())
+    assert oracle.gemm_cross_entropy(A, Z, bias, labels, M, N, K) == pytest.approx(float(np.mean(lse - b64[labels])), rel=1e-13)
+    # integer operands: the logits are exact in fp32, so the fp32-logit cross-entropy of the product agrees
+    Ai = synth.integers(72, "A", M, K); Bi = synth.integers(72, "B", K, N); bi = synth.integers(72, "bias", 1, N)[0]
+    z = oracle.gemm_epilogue(Ai, Bi, bi, M, N, K)[0]
+    assert np.array_equal(z, z.astype(np.float32).astype(np.float64))
+    assert oracle.gemm_cross_entropy(Ai, Bi, bi, labels, M, N, K) == pytest.approx(oracle.cross_entropy(z.astype(np.float32), labels), rel=1e-14)
+    # identity weights scaled by t, one-hot rows: row i has logits t at i, 0 elsewhere; label = i
+    t = 5.0
+    E = np.eye(N, dtype=np.float32)
+    want = math.log(math.exp(t) + N - 1) - t
+    assert oracle.gemm_cross_entropy(E, (t * E).astype(np.float32), None, np.arange(N, dtype=np.int32), N, N, N) == pytest.approx(want, rel=1e-14)
+    # out-of-range label: NaN; no rows: 0
+    bad = labels.copy(); bad[3] = N
+    assert math.isnan(oracle.gemm_cross_entropy(A, Z, None, bad, M, N, K))
