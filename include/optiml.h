@@ -230,6 +230,31 @@ int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, 
 int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream);
 
 /*
+ * The contraction feeding the cross-entropy (the paper's Table 4, task 2 into task 17), fused:
+ *     *loss = (1/M) sum_i [ log sum_j exp(z[i][j]) - z[i][labels[i]] ],   z = A.B + bias
+ * for M rows (samples) and N classes, with A, B, bias, layouts, leading dimensions and dtype
+ * exactly as in optiml_gemm_epilogue_ex (no activation, no batch); labels are M 32-bit integers in
+ * [0, N), loss one float; all DEVICE pointers.  The logits are not written anywhere: products
+ * are accumulated in fp32, each row's maximum and sum of exponentials are formed in fp32 from
+ * the unrounded fp32 logits, the row losses and their mean in fp64 in a fixed order, rounded
+ * once to float; repeating a call gives the same bits.  16-bit storage with A row-major and a
+ * shape the ring kernel takes (K a multiple of 32 and at least 128, 16-byte aligned operands,
+ * N a multiple of 8 for a row-major B) runs on the matrix pipe; everything else runs a
+ * one-workgroup-per-row fp32 kernel.  Uses the per-device workspace (8 bytes per row and 64
+ * columns); three kernels.  A label outside [0, N) makes the result NaN; M == 0 writes 0.
+ * optiml_gemm_cross_entropy_path says which kernel a call would use (0 matrix pipe, 1 fallback;
+ * host only).
+ *
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): M < 0, N < 1, K < 0, unknown layout or dtype, NULL
+ * loss, NULL labels with M > 0, NULL A or B with M > 0 and K > 0, an ld shorter than the row it
+ * spans.
+ */
+int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                              const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream);
+int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                                   const float *bias, int layout, int dtype);
+
+/*
  * Multi-head self-attention (the paper's Table 4, task 6): for Q, K, V of shape [batch][N][d_model]
  * (row-major, contiguous, DEVICE pointers; float for OPTIML_F32, bfloat16 for OPTIML_BF16) and
  * `heads` heads of width d_k = d_model / heads,

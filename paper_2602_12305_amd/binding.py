@@ -37,6 +37,8 @@ SIGNATURES = {
     "optiml_cross_entropy": (_int, [_i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "optiml_layernorm": (_int, [_i64, _i64, _vp, _vp, C.c_float, _vp]),
     "optiml_mhsa": (_int, [_i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]),
+    "optiml_gemm_cross_entropy": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _int, _int, _vp]),
+    "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -173,6 +175,15 @@ def optiml_layernorm(rows, length, x, y, eps, stream=None):
 def optiml_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, stream=None):
     return _check(lib().optiml_mhsa(batch, N, d_model, heads, _addr(Q), _addr(K), _addr(V), _addr(O), dtype,
                                     _stream(stream)))
+
+
+def optiml_gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, layout, dtype, stream=None):
+    return _check(lib().optiml_gemm_cross_entropy(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(labels),
+                                                  _addr(loss), layout, dtype, _stream(stream)))
+
+
+def optiml_gemm_cross_entropy_path(M, N, K, A, lda, B, ldb, bias, layout, dtype):
+    return lib().optiml_gemm_cross_entropy_path(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), layout, dtype)
 
 
 def optiml_status_string(status):

@@ -377,6 +377,41 @@ int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float 
     return OPTIML_OK;
 }
 
+int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                              const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream)
+{
+    if (!enum_ok(layout, dtype, 0)) return OPTIML_ERR_INVALID_ARG;
+    if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0 || !loss) return OPTIML_ERR_INVALID_ARG;
+    Problem p{};
+    p.batch = 1; p.M = M; p.N = N; p.K = K;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.bias = bias;
+    p.layout = layout; p.dtype = dtype; p.act = ACT_NONE;
+    if (M > 0) {
+        if (!labels) return OPTIML_ERR_INVALID_ARG;
+        if (K > 0) {
+            if (!A || !B) return OPTIML_ERR_INVALID_ARG;
+            if (lda < (p.a_col() ? M : K) || ldb < (p.b_col() ? K : N)) return OPTIML_ERR_INVALID_ARG;
+        }
+    }
+    hipError_t e = optiml::launch_linear_ce(p, labels, loss, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
+int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                                   const float *bias, int layout, int dtype)
+{
+    if (!enum_ok(layout, dtype, 0) || M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0) return OPTIML_ERR_INVALID_ARG;
+    Problem p{};
+    p.batch = 1; p.M = M; p.N = N; p.K = K;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.bias = bias;
+    p.layout = layout; p.dtype = dtype; p.act = ACT_NONE;
+    return optiml::linear_ce_path(p);
+}
+
 int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K, const void *V,
                 void *O, int dtype, void *stream)
 {

@@ -57,6 +57,11 @@ int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const vo
 hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K,
                        const void *V, void *O, int dtype, int path, hipStream_t stream);
 
+// contraction + cross-entropy (kernel_linear_ce.hip): which path would serve (0 ring kernel with the
+// log-sum-exp epilogue, 1 row-per-workgroup fallback), launch; p.C, ldc, act and batch are ignored
+int linear_ce_path(const Problem &p);
+hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hipStream_t stream);
+
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;

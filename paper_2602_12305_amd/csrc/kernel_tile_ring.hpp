@@ -33,6 +33,7 @@
 namespace optiml {
 namespace ring {
 
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -49,11 +50,19 @@ struct Params {
     char *C; int64_t ldc, strideC;
     int64_t tiles_m, tiles_n;
     int act;
+    // EPI == 1 only: class labels of the M rows and where the label's logit of each row goes;
+    // C then points at the (max, sum) pairs [tiles_n * WN][M]
+    const int *labels;
+    float *picked;
 };
 
-template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16>
+template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0>
 struct Cfg {
     static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
+    // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 64 columns of A.B + bias
+    // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the
+    // cross-entropy over the N columns without the logits ever reaching memory.
+    static constexpr int EPI = EPI_;
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
     static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier
@@ -374,6 +383,47 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
                 for (int e = 0; e < 4; ++e) bj[j][gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
             }
         }
+    if constexpr (C::EPI == 1) {
+        float *part = reinterpret_cast<float *>(p.C);
+        const int64_t slice = tile_n * C::WN + wn;
+        const bool ragged = nw + C::WTN > p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = mw + 32 * i + frag_row;
+            const bool live = m < p.M;
+            // this lane holds columns nw + 32 j + 8 gq + 4 half + e of row m; `want` is the label's
+            // offset in those terms without the 4 half (or a value no offset takes)
+            const int64_t d = live ? (int64_t)p.labels[m] - nw : -1;
+            const int want = d >= 0 && d < C::WTN ? (int)d - 4 * half : -1000;
+            float mx = -__builtin_inff(), pick = 0.0f;
+            bool hit = false;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int cofs = 32 * j + 8 * gq + e;
+                        float v = acc[j][i][4 * gq + e] + bj[j][gq][e];
+                        if (ragged && nw + cofs + 4 * half >= p.N) v = -__builtin_inff();
+                        acc[j][i][4 * gq + e] = v;
+                        mx = __builtin_fmaxf(mx, v);
+                        if (want == cofs) { pick = v; hit = true; }
+                    }
+            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float ref = mx == -__builtin_inff() ? 0.0f : mx;       // a slice wholly past column N
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[j][i][r] - ref) * 1.44269504088896341f);
+            sum += __shfl_xor(sum, 32, 64);
+            if (live && half == 0)
+                *reinterpret_cast<floatx2 *>(part + 2 * (slice * p.M + m)) = floatx2{mx, sum};
+            if (live && hit) p.picked[m] = pick;
+        }
+        return;
+    }
     auto slab_key = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
     const int wkey = slab_key(frag_row);
     dispatch_act(p.act, [&](auto act_tag) {
@@ -439,6 +489,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = p.act;
+    q.labels = nullptr; q.picked = nullptr;
     const int64_t total = q.tiles_m * q.tiles_n * p.batch;
     hipLaunchKernelGGL(gemm_ring_kernel<C>, dim3((unsigned)total), dim3(C::THREADS), 0, stream, q);
     return hipGetLastError();

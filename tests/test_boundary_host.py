@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 17
+    assert len(names) == 19
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -180,3 +180,28 @@ def test_variant_supports_is_host_only_and_consistent():
     sk = next(i for i, n in enumerate(names) if n.startswith("skinny"))
     assert ob.optiml_variant_supports(sk, *bf16) == ob.ERR_UNSUPPORTED
     assert ob.lib().optiml_gemm_epilogue_variant(*bf16, None, sk) == ob.ERR_UNSUPPORTED
+
+
+def test_fused_cross_entropy_entry_point_validates_and_picks_its_kernel_on_the_host():
+    L = ob.lib()
+    #       M   N    K    A  lda  B  ldb bias labels loss layout dtype stream
+    bad = [(-1, 64, 128, P, 128, P, 64, P, P, P, 0, 1, None), (8, 0, 128, P, 128, P, 64, P, P, P, 0, 1, None),
+           (8, 64, -1, P, 128, P, 64, P, P, P, 0, 1, None), (8, 64, 128, P, 128, P, 64, P, P, None, 0, 1, None),
+           (8, 64, 128, P, 128, P, 64, P, None, P, 0, 1, None), (8, 64, 128, None, 128, P, 64, P, P, P, 0, 1, None),
+           (8, 64, 128, P, 128, None, 64, P, P, P, 0, 1, None), (8, 64, 128, P, 127, P, 64, P, P, P, 0, 1, None),
+           (8, 64, 128, P, 128, P, 63, P, P, P, 0, 1, None), (8, 64, 128, P, 128, P, 127, P, P, P, 1, 1, None),
+           (8, 64, 128, P, 7, P, 64, P, P, P, 2, 1, None), (8, 64, 128, P, 128, P, 64, P, P, P, 4, 1, None),
+           (8, 64, 128, P, 128, P, 64, P, P, P, 0, 3, None)]
+    for args in bad:
+        assert L.optiml_gemm_cross_entropy(*args) == ob.ERR_INVALID_ARG, args
+    path = lambda M, N, K, layout, dtype, A=P, lda=None, ldb=None: L.optiml_gemm_cross_entropy_path(
+        M, N, K, A, lda if lda is not None else (M if layout & 2 else K), P, ldb if ldb is not None else (K if layout & 1 else N),
+        P, layout, dtype)
+    assert path(8192, 32768, 4096, 0, 1) == 0 and path(8192, 32768, 4096, 1, 2) == 0     # 16-bit, A row-major: matrix pipe
+    assert path(300, 515, 160, 1, 1) == 0                                                  # ragged N with a column-major B
+    assert path(300, 516, 160, 0, 1) == 1                                                  # row-major B rows not whole chunks
+    assert path(8192, 32768, 4096, 0, 0) == 1                                              # fp32
+    assert path(8192, 32768, 4096, 2, 1) == 1                                              # A column-major
+    assert path(64, 64, 96, 0, 1) == 1 and path(64, 64, 0, 0, 1) == 1                     # K too short for the ring, K = 0
+    assert path(64, 64, 128, 0, 1, A=P + 2) == 1                                           # misaligned A
+    assert path(8, 64, 128, 0, 5) == ob.ERR_INVALID_ARG
