@@ -8,15 +8,15 @@
 // label's column hands out that logit.  What reaches memory is 8 bytes per row and 64 columns
 // instead of the logits.  Fallback (everything else): one workgroup per row forms the row's
 // logits one column per thread in fp32 and reduces them the same way.  Both are followed by
-// lce_rows_kernel (a thread per row merges the row's pairs in fp64, forms the row loss, and a
-// workgroup adds its rows in a fixed order) and lce_mean_kernel (adds the workgroups' sums in
+// lce_rows_kernel (16 threads per row merge the row's pairs in fp64 in a fixed order, form the
+// row loss, and a workgroup adds its 16 rows in row order) and lce_mean_kernel (adds the workgroups' sums in
 // order, divides by M, rounds once to float).
 #include "kernel_tile_ring.hpp"
 
 namespace optiml {
 namespace {
 
-constexpr int kRowsPerBlock = 256;
+constexpr int kRowsPerBlock = 16, kGroups = 16;     // rows per workgroup of lce_rows_kernel, threads per row
 
 template <typename E> __device__ __forceinline__ float widen_ce(E v);
 template <> __device__ __forceinline__ float widen_ce<float>(float v) { return v; }
@@ -66,41 +66,65 @@ __global__ __launch_bounds__(256) void lce_fallback_kernel(Problem p, const int 
     if (threadIdx.x == 0) { part[2 * i] = m; part[2 * i + 1] = s; }
 }
 
-// thread = row: merge the row's pairs (slice-major: pair of row i in slice q at part[2 (q M + i)]),
-// loss_i = log(S) + (max - z_label); a label outside [0, N) gives NaN
-__global__ __launch_bounds__(kRowsPerBlock) void lce_rows_kernel(const float *part, int64_t slices, int64_t M, int64_t N,
-                                                                 const int *labels, const float *picked, double *block_sums)
+// A workgroup owns kRowsPerBlock rows; thread (row r, group g) merges slices g, g + kGroups, ... of
+// its row in fp64 (pairs are slice-major: row i, slice q at part[2 (q M + i)], so the threads of
+// one group read consecutive rows), then the row's groups are merged in group order,
+// loss_i = log(S) + (max - z_label) (a label outside [0, N) gives NaN), and the rows are added in
+// row order.
+__global__ __launch_bounds__(kRowsPerBlock * kGroups) void lce_rows_kernel(const float *part, int64_t slices, int64_t M,
+                                                                          int64_t N, const int *labels, const float *picked,
+                                                                          double *block_sums)
 {
-    __shared__ double sh[kRowsPerBlock];
-    const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x;
-    double loss = 0.0;
-    if (i < M) {
-        float hi = -__builtin_inff();
-        for (int64_t q = 0; q < slices; ++q)
-            if (part[2 * (q * M + i) + 1] != 0.0f) hi = fmaxf(hi, part[2 * (q * M + i)]);
-        double S = 0.0;
-        for (int64_t q = 0; q < slices; ++q) {
-            const float s = part[2 * (q * M + i) + 1];
-            if (s != 0.0f) S += (double)s * exp((double)part[2 * (q * M + i)] - (double)hi);
+    __shared__ double sh_hi[kGroups][kRowsPerBlock], sh_s[kGroups][kRowsPerBlock], sh_loss[kRowsPerBlock];
+    const int r = threadIdx.x % kRowsPerBlock, g = threadIdx.x / kRowsPerBlock;
+    const int64_t i = (int64_t)blockIdx.x * kRowsPerBlock + r;
+    double hi = 0.0, S = 0.0;                       // S == 0: nothing merged yet
+    if (i < M)
+        for (int64_t q = g; q < slices; q += kGroups) {
+            const float2 pr = *reinterpret_cast<const float2 *>(part + 2 * (q * M + i));
+            if (pr.y == 0.0f) continue;                                  // a slice wholly past column N
+            const double m = (double)pr.x;
+            if (S == 0.0) { hi = m; S = (double)pr.y; }
+            else if (m > hi) { S = S * exp(hi - m) + (double)pr.y; hi = m; }
+            else S += (double)pr.y * exp(m - hi);
         }
-        const int label = labels[i];
-        loss = (label < 0 || label >= N) ? (double)__builtin_nanf("") : log(S) + ((double)hi - (double)picked[i]);
-    }
-    sh[threadIdx.x] = loss;
+    sh_hi[g][r] = hi; sh_s[g][r] = S;
     __syncthreads();
-    for (int step = kRowsPerBlock / 2; step > 0; step >>= 1) {
-        if ((int)threadIdx.x < step) sh[threadIdx.x] += sh[threadIdx.x + step];
-        __syncthreads();
+    if (g == 0) {
+        for (int k = 1; k < kGroups; ++k) {
+            const double m = sh_hi[k][r], s2 = sh_s[k][r];
+            if (s2 == 0.0) continue;
+            if (S == 0.0) { hi = m; S = s2; }
+            else if (m > hi) { S = S * exp(hi - m) + s2; hi = m; }
+            else S += s2 * exp(m - hi);
+        }
+        double loss = 0.0;
+        if (i < M) {
+            const int label = labels[i];
+            loss = (label < 0 || label >= N) ? (double)__builtin_nanf("") : log(S) + (hi - (double)picked[i]);
+        }
+        sh_loss[r] = loss;
     }
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = sh[0];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int k = 0; k < kRowsPerBlock; ++k) t += sh_loss[k];
+        block_sums[blockIdx.x] = t;
+    }
 }
 
+// lane t adds the workgroup sums t, t + 64, ... in that order, lane 0 the 64 lane sums in lane order
 __global__ __launch_bounds__(64) void lce_mean_kernel(const double *block_sums, int64_t blocks, int64_t M, float *loss)
 {
-    if (threadIdx.x != 0) return;
+    __shared__ double sh[64];
     double t = 0.0;
-    for (int64_t b = 0; b < blocks; ++b) t += block_sums[b];
-    *loss = (float)(M > 0 ? t / (double)M : 0.0);
+    for (int64_t b = threadIdx.x; b < blocks; b += 64) t += block_sums[b];
+    sh[threadIdx.x] = t;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    double total = 0.0;
+    for (int k = 0; k < 64; ++k) total += sh[k];
+    *loss = (float)(M > 0 ? total / (double)M : 0.0);
 }
 
 template <int DT, bool B_KC> using LseCfg = ring::Cfg<4, B_KC, true, 4, DT, 1>;
@@ -179,7 +203,8 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
         e = hipGetLastError();
     }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(lce_rows_kernel, dim3((unsigned)blocks), dim3(kRowsPerBlock), 0, stream, part, slices, p.M, p.N, labels,
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lce_rows_kernel, dim3((unsigned)blocks), dim3(kRowsPerBlock * kGroups), 0, stream, part, slices, p.M, p.N, labels,
                        picked, block_sums);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
