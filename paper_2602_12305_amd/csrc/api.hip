@@ -20,6 +20,7 @@ struct Table {
         for (int i = 0; i < kNumGenericVariants; ++i) v.push_back(&generic_variants()[i]);
         first_skinny = (int)v.size();
         for (int i = 0; i < kNumSkinnyVariants; ++i) v.push_back(&skinny_variants()[i]);
+        for (int i = 0; i < kNumSkinny16Variants; ++i) v.push_back(&skinny16_variants()[i]);
         first_tile = (int)v.size();
         for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
         for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);
@@ -74,6 +75,22 @@ bool streaming_beats_tiles(const Problem &p)
     return t_stream < t_tiles;
 }
 
+// The same question for 16-bit storage and up to 128 rows.  The 256 x 256 ring tiles waste most of
+// their rows there and, for one row of tiles, use N/256 CUs; the streaming kernel reads B once
+// per 16 rows, the blocks of rows running side by side and sharing much of B through the caches.
+// Calibrated on 16..64 x 16384 x 16384 (86, 121, 210 us streamed against 270 us) and
+// 16 x 32768 x 4096 (47 us against 80 us).
+bool streaming16_beats_tiles(const Problem &p)
+{
+    if (p.dtype == DT_F32 || p.layout != 0 || p.M > 128) return false;
+    const double rb = (double)((p.M + 15) / 16), batch = (double)p.batch;
+    const double t_stream = batch * (double)p.K * (double)p.N * 2.0 / 5.8e12 * (0.55 + 0.45 * rb);
+    const double tiles = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256) * batch;
+    const double rounds = (double)(int64_t)((tiles + 255.0) / 256.0);
+    const double t_tiles = rounds * 2.0 * 65536.0 * (double)p.K / 7e12;
+    return t_stream < t_tiles;
+}
+
 // Preference order: the streaming split-K kernels for at most 16 rows, and for small fp32
 // problems of more rows (without the non-temporal hint: B is meant to stay in L2); then the MFMA
 // tile kernels - one that declares a measured preference for the shape, else in table order
@@ -89,6 +106,9 @@ int select(const Problem &p)
                 if (t.v[i]->supports(p)) return i;
         if (streaming_beats_tiles(p) && t.first_skinny + 1 < t.first_tile && t.v[t.first_skinny + 1]->supports(p))
             return t.first_skinny + 1;
+        if (streaming16_beats_tiles(p))
+            for (int i = t.first_skinny + kNumSkinnyVariants; i < t.first_tile; ++i)
+                if (t.v[i]->supports(p)) return i;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i)
             if (t.v[i]->prefers && t.v[i]->prefers(p) && t.v[i]->supports(p)) return i;
         int best = -1;

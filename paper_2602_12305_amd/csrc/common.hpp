@@ -65,6 +65,7 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
+const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 16;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;

@@ -153,6 +153,11 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 8192, 8192, 8192, layout=2, dtype=1) == "xa_ring"       # column-major A: row-major copy, then a ring kernel
     assert sel(1, 4096, 4096, 4096, layout=3) == "xa_ring"
     assert sel(1, 2048, 512, 2048, layout=2, dtype=1).startswith("tile_bf16_cr_")   # too few columns to pay for the copy
+    assert sel(1, 16, 16384, 16384, dtype=1).startswith("skinny_bf16_wn1_wk4_cg2")     # 16-bit storage streams B the same way
+    assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_wn1_wk4_cg2")
+    assert sel(1, 64, 16384, 16384, dtype=1).startswith("skinny_bf16")                # four blocks of rows still beat one row of tiles
+    assert not sel(1, 64, 32768, 4096, dtype=1).startswith("skinny")                 # ... but not with a short K
+    assert not sel(1, 256, 16384, 16384, dtype=1).startswith("skinny")
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays
@@ -165,7 +170,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 512, 510, 512, ldb=512, ldc=512).startswith("generic")  # N % 4 != 0 with row-major B
     assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("tile_f32_rc")   # fine when k is contiguous
     assert sel(1, 16, 1024, 1022, lda=1024).startswith("generic")
-    assert "bf16_rr" in sel(1, 16, 1024, 1024, dtype=1)                  # skinny path is fp32 only
+    assert sel(1, 16, 1024, 1024, dtype=1).startswith("skinny_bf16")
     assert sel(1, 8, 8, 8, layout=7) == ob.ERR_INVALID_ARG
 
 

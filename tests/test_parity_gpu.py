@@ -36,7 +36,7 @@ def all_variants():
 def problem_for(name):
     """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
     if name.startswith("skinny"):
-        return F32, 0, 13, 1000, 1224
+        return DT_OF[name.split("_")[1]], 0, 13, 1000, 1224
     if name.startswith("ring"):
         _, dt, lay = name.split("_")[:3]
         ns = int(name.rsplit("ns", 1)[1][0])
@@ -314,22 +314,24 @@ def test_row_permutation_equivariance():
 def test_skinny_variants_with_blocks_of_16_rows(vid):
     """M > 16: grid.z counts blocks of 16 rows (the last one ragged) times batches; K long enough
     for the automatic grid split, so the partial sums of every block go through the workspace."""
+    F32 = DT_OF[ob.optiml_variant_name(vid).split("_")[1]]           # the variant's own storage type
     batch, M, N, K = 2, 45, 264, 4160
     A = synth.normal(800 + vid, "A", M, K, batch=batch); B = synth.normal(800 + vid, "B", K, N, batch=batch)
     bias = synth.normal(800 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
-    check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_GELU_TANH, layout=0, variant=vid, ldc_pad=4)
+    check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_GELU_TANH, layout=0, variant=vid, ldc_pad=8)
     Ai = synth.integers(810 + vid, "A", M, K, batch=batch); Bi = synth.integers(810 + vid, "B", K, N, batch=batch)
     check_against_oracle(Ai, Bi, None, dtype=F32, act=synth.ACT_RELU, layout=0, variant=vid, exact=True)
     # one batch, few columns, short K: no grid split
-    A = synth.uniform(820 + vid, "A", 100, 64); B = synth.uniform(820 + vid, "B", 64, 36)
-    check_against_oracle(A, B, synth.uniform(820 + vid, "bias", 1, 36)[0], dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
+    A = synth.uniform(820 + vid, "A", 100, 64); B = synth.uniform(820 + vid, "B", 64, 40)
+    check_against_oracle(A, B, synth.uniform(820 + vid, "bias", 1, 40)[0], dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
 
 
 @pytest.mark.parametrize("vid", variant_ids("skinny"))
 def test_skinny_variants_with_grid_split_k(vid):
     # K long enough that the automatic split uses several workgroups per column block, and
     # M = 16 rows exactly; a second shape has a ragged last column block and a k tail
-    for (M, N, K) in ((16, 512, 8192), (5, 328, 4100)):
+    F32 = DT_OF[ob.optiml_variant_name(vid).split("_")[1]]           # the variant's own storage type
+    for (M, N, K) in ((16, 512, 8192), (5, 328, 4104)):
         A = synth.normal(1400 + vid, "A", M, K, 0.0, K ** -0.5); B = synth.normal(1400 + vid, "B", K, N, 0.0, K ** -0.5)
         bias = synth.uniform(1400 + vid, "bias", 1, N, -0.1, 0.1)[0]
         check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
