@@ -233,7 +233,7 @@ def _store(x, dtype, transpose=False):
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
-BREADTH_WORKLOADS = ("c4_f16_8192_silu",)     # further dtypes on the same shapes
+BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu")     # further dtypes on the same shapes
 
 
 def make_workload(name: str, scale: int = 1) -> Workload:
@@ -266,6 +266,13 @@ def make_workload(name: str, scale: int = 1) -> Workload:
                         _store(normal(3, "A", M, K), DTYPE_BF16),
                         _store(normal(3, "B", K, N), DTYPE_BF16),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c2_bf16_skinny16_silu":        # config 2's shape and distributions in bf16 storage
+        M, N, K = 16, 16384 // s, 16384 // s
+        sd = K ** -0.5
+        return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_RR, 1,
+                        _store(normal(1, "A", M, K, 0.0, sd), DTYPE_BF16),
+                        _store(normal(1, "B", K, N, 0.0, sd), DTYPE_BF16),
+                        uniform(1, "bias", 1, N, -0.1, 0.1))
     if name == "c4_f16_8192_silu":             # config 4's shape and distributions in binary16 storage
         M = N = K = 8192 // s
         return Workload(name, 1, M, N, K, DTYPE_F16, ACT_SILU, LAYOUT_RR, 3,
