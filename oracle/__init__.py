@@ -208,7 +208,7 @@ def layernorm(x, eps=1e-5):
 
 def mhsa(Q, K, V, heads, dtype=F32):
     """fp64 multi-head self-attention Concat_i softmax(Q_i K_i^T / sqrt(d_k)) V_i for Q, K, V of shape
-    [batch, N, d_model] (or [N, d_model]) stored as fp32, or as bf16 bit patterns (uint16) with dtype=BF16
+    [batch, N, d_model] (or [N, d_model]) stored as fp32, or as bf16 / binary16 bit patterns (uint16) with dtype=BF16 / F16
     (Table 4, task 6)."""
     want = np.float32 if dtype == F32 else np.uint16
     Q, K, V = (np.ascontiguousarray(a, dtype=want) for a in (Q, K, V))

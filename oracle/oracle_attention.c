@@ -12,7 +12,7 @@
  * against; nothing on the product path may call it, and it shares no code, header, table
  * or constant with the HIP sources.
  *
- * Arithmetic: inputs (fp32, or bf16 widened exactly) in fp64.  Per (batch, head, query): the
+ * Arithmetic: inputs (fp32, or bf16 / binary16 widened exactly) in fp64.  Per (batch, head, query): the
  * scores s_n = (sum_c q_c k_nc) / sqrt(d_k) over keys n ascending, each dot product over c
  * ascending (products exact in fp64); the maximum score; weights exp(s_n - max); their sum;
  * then for every output column the sum over keys n ascending of weight_n * v_nc, divided by the
@@ -23,9 +23,13 @@
 #include <stdlib.h>
 #include <string.h>
 
+double oracle_f16_to_double(uint16_t h);      /* oracle_gemm.c */
+
+/* dtype 0: fp32; 1: bf16 bit patterns; 2: IEEE binary16 bit patterns */
 static double widen_a(const void *base, int64_t idx, int dtype)
 {
     if (dtype == 0) return (double)((const float *)base)[idx];
+    if (dtype == 2) return oracle_f16_to_double(((const uint16_t *)base)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -36,7 +40,7 @@ static double widen_a(const void *base, int64_t idx, int dtype)
 int oracle_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K, const void *V,
                 int dtype, double *out)
 {
-    if (batch < 0 || N < 0 || d_model < 1 || heads < 1 || d_model % heads != 0) return -1;
+    if (batch < 0 || N < 0 || d_model < 1 || heads < 1 || d_model % heads != 0 || dtype < 0 || dtype > 2) return -1;
     const int64_t dk = d_model / heads;
     const double scale = 1.0 / sqrt((double)dk);
     int failed = 0;

@@ -115,3 +115,15 @@ def test_bf16_inputs_are_widened_exactly_and_bad_arguments_rejected():
     with pytest.raises(ValueError):
         oracle.mhsa(Q, K[:, :5], V, heads=2)
     assert oracle.mhsa(Q[:, :0], K[:, :0], V[:, :0], heads=2).shape == (1, 0, 8)
+
+
+def test_sixteen_bit_storage_is_decoded_exactly():
+    """bf16 and binary16 inputs: the result is bit for bit that of the fp32 path on the decoded values (which numpy's
+    own float16 / shift decode supplies), so the storage type only chooses the decoder."""
+    Q = synth.normal(40, "q", 33, 48, batch=2); K = synth.normal(40, "k", 33, 48, batch=2); V = synth.normal(40, "v", 33, 48, batch=2)
+    for dtype in (oracle.BF16, oracle.F16):
+        bits = [synth.to_bits(a, dtype) for a in (Q, K, V)]
+        dec = [synth.from_bits(b, dtype) for b in bits]
+        assert np.array_equal(oracle.mhsa(*bits, 3, dtype=dtype), oracle.mhsa(*dec, 3))
+    with pytest.raises(ValueError):
+        oracle.mhsa(Q, K, V, 3, dtype=7)
