@@ -256,12 +256,12 @@ int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *
 
 /*
  * Multi-head self-attention (the paper's Table 4, task 6): for Q, K, V of shape [batch][N][d_model]
- * (row-major, contiguous, DEVICE pointers; float for OPTIML_F32, bfloat16 for OPTIML_BF16) and
+ * (row-major, contiguous, DEVICE pointers; float for OPTIML_F32, 16-bit for OPTIML_BF16 / OPTIML_F16) and
  * `heads` heads of width d_k = d_model / heads,
  *     O[b][:, i d_k : (i+1) d_k] = softmax( Q_i K_i^T / sqrt(d_k) ) V_i      (softmax over the keys of a query)
  * with no projections and no mask.  O has the shape and type of Q and must not overlap the inputs.
- * OPTIML_BF16 with d_k = 64 or 128 and 16-byte aligned pointers runs on the matrix pipe (bf16
- * products, fp32 accumulation, fp32 online softmax whose weights are rounded to bf16 before the
+ * 16-bit storage with d_k = 64 or 128 and 16-byte aligned pointers runs on the matrix pipe (16-bit
+ * products, fp32 accumulation, fp32 online softmax whose weights are rounded to the storage type before the
  * second product, one rounding of O); everything else with d_k <= 256 runs a one-wave-per-query
  * fp32 kernel; d_k > 256 is OPTIML_ERR_UNSUPPORTED.  batch == 0 or N == 0 writes nothing.
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, d_model < 1, heads < 1, d_model not

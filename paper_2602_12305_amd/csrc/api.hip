@@ -436,7 +436,7 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
                 void *O, int dtype, void *stream)
 {
     if (batch < 0 || N < 0 || d_model < 1 || heads < 1 || d_model % heads != 0) return OPTIML_ERR_INVALID_ARG;
-    if (dtype != OPTIML_F32 && dtype != OPTIML_BF16) return OPTIML_ERR_INVALID_ARG;
+    if (dtype != OPTIML_F32 && dtype != OPTIML_BF16 && dtype != OPTIML_F16) return OPTIML_ERR_INVALID_ARG;
     if (batch == 0 || N == 0) return OPTIML_OK;
     if (!Q || !K || !V || !O) return OPTIML_ERR_INVALID_ARG;
     const int path = optiml::mhsa_path(d_model, heads, dtype, Q, K, V, O);

@@ -4,8 +4,8 @@
 //
 // Two kernels.
 //
-// mhsa_flash_kernel (bf16 storage, d_k = 64 or 128): the two chained contractions on the bf16
-// matrix pipe with an online softmax between them, never writing the N x N scores anywhere.
+// mhsa_flash_kernel (bf16 or fp16 storage, d_k = 64 or 128): the two chained contractions on the
+// 16-bit matrix pipe with an online softmax between them, never writing the N x N scores anywhere.
 // A workgroup of 4 waves owns 128 queries of one (batch, head); a wave owns 32 of them and
 // keeps their Q fragments, the running maximum / sum, and the output accumulators in
 // registers while the workgroup walks the keys 64 at a time.  The K and V tiles of a key block
@@ -29,7 +29,7 @@
 // for 128-byte rows; V: chunk ^ 4(row%4) or ^ 2(row%4)) so that the 128-bit fragment reads and
 // the transposing reads spread over the 64 banks.
 //
-// mhsa_rows_kernel (fp32 or bf16 storage, any d_k up to 256): one wave per query, a key per
+// mhsa_rows_kernel (fp32, bf16 or fp16 storage, any d_k up to 256): one wave per query, a key per
 // lane, fp32 arithmetic throughout; the fallback for everything the flash kernel does not take.
 #include "common.hpp"
 #include "epilogue.hpp"
@@ -85,7 +85,7 @@ struct AttnParams {
 constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
 constexpr float kLazy = 8.0f;            // slack of the exponents' reference point below the running maximum
 
-template <int DK>
+template <int DK, int DT>
 __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -198,8 +198,7 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                 const int c = 2 * s + half;
                 const int kc = DK == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
                 const uintx4 kf = *reinterpret_cast<const __attribute__((address_space(3))) uintx4 *>(kt + row * ROWB + kc * 16);
-                acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf),
-                                                                   __builtin_bit_cast(bf16x8, qf[s]), acc_s[t], 0, 0, 0);
+                acc_s[t] = mfma_32x32x16<DT>(kf, qf[s], acc_s[t]);
             }
         // order for the scheduler: K fragment reads run kAhead k-steps ahead of the matrix
         // instructions that consume them, so LDS latency is paid once, not per step
@@ -250,8 +249,7 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                     e[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[t][8 * s + i], p.scale2, -m_new));
                     rowsum += e[i];
                 }
-                pf[t][s] = uintx4{f32x2_to_bf16x2(e[0], e[1]), f32x2_to_bf16x2(e[2], e[3]),
-                                  f32x2_to_bf16x2(e[4], e[5]), f32x2_to_bf16x2(e[6], e[7])};
+                pf[t][s] = uintx4{pack2_16<DT>(e[0], e[1]), pack2_16<DT>(e[2], e[3]), pack2_16<DT>(e[4], e[5]), pack2_16<DT>(e[6], e[7])};
             }
         l = l * corr + rowsum;
         m = m_new;
@@ -279,8 +277,7 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
                     const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4 *)(a1));
                     const uintx2 l2 = __builtin_bit_cast(uintx2, lo), h2 = __builtin_bit_cast(uintx2, hi);
                     const uintx4 vf = uintx4{l2[0], l2[1], h2[0], h2[1]};
-                    acc_o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf),
-                                                                       __builtin_bit_cast(bf16x8, pf[t][s]), acc_o[u], 0, 0, 0);
+                    acc_o[u] = mfma_32x32x16<DT>(vf, pf[t][s], acc_o[u]);
                 }
             }
     };
@@ -300,8 +297,8 @@ __global__ __launch_bounds__(256, 2) void mhsa_flash_kernel(AttnParams p)
             for (int gq = 0; gq < 4; ++gq) {
                 const int dv = 32 * u + 8 * gq + 4 * half;
                 *reinterpret_cast<uintx2 *>(Ob + q * ldb + dv * 2) =
-                    uintx2{f32x2_to_bf16x2(acc_o[u][4 * gq] * inv, acc_o[u][4 * gq + 1] * inv),
-                           f32x2_to_bf16x2(acc_o[u][4 * gq + 2] * inv, acc_o[u][4 * gq + 3] * inv)};
+                    uintx2{pack2_16<DT>(acc_o[u][4 * gq] * inv, acc_o[u][4 * gq + 1] * inv),
+                           pack2_16<DT>(acc_o[u][4 * gq + 2] * inv, acc_o[u][4 * gq + 3] * inv)};
             }
     }
 #endif
@@ -313,7 +310,7 @@ template <int DT>
 __device__ __forceinline__ float load_elem(const char *base, int64_t idx)
 {
     if (DT == DT_F32) return reinterpret_cast<const float *>(base)[idx];
-    return bf16_to_f32(reinterpret_cast<const unsigned short *>(base)[idx]);
+    return from_16<DT>(reinterpret_cast<const unsigned short *>(base)[idx]);
 }
 
 template <int DT>
@@ -370,7 +367,7 @@ __global__ __launch_bounds__(256) void mhsa_rows_kernel(AttnParams p)
         if (c < dk) {
             const float y = o[t] * inv;
             if (DT == DT_F32) reinterpret_cast<float *>(p.O)[base + q * p.d_model + c] = y;
-            else reinterpret_cast<unsigned short *>(p.O)[base + q * p.d_model + c] = f32_to_bf16(y);
+            else reinterpret_cast<unsigned short *>(p.O)[base + q * p.d_model + c] = to_16<DT>(y);
         }
     }
 }
@@ -383,7 +380,7 @@ bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) ==
 int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const void *K, const void *V, const void *O)
 {
     const int64_t dk = d_model / heads;
-    if (dtype == DT_BF16 && (dk == 64 || dk == 128) && aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O))
+    if (dtype != DT_F32 && (dk == 64 || dk == 128) && aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O))
         return 0;
     return dk <= 256 ? 1 : -1;
 }
@@ -400,13 +397,20 @@ hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads,
     if (path == 0) {
         const int64_t grid = batch * heads * ((N + kBQ - 1) / kBQ);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        if (dk == 128) hipLaunchKernelGGL(mhsa_flash_kernel<128>, dim3((unsigned)grid), dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL(mhsa_flash_kernel<64>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+        const dim3 g((unsigned)grid), b(256);
+        if (dtype == DT_F16) {
+            if (dk == 128) hipLaunchKernelGGL((mhsa_flash_kernel<128, DT_F16>), g, b, 0, stream, p);
+            else hipLaunchKernelGGL((mhsa_flash_kernel<64, DT_F16>), g, b, 0, stream, p);
+        } else {
+            if (dk == 128) hipLaunchKernelGGL((mhsa_flash_kernel<128, DT_BF16>), g, b, 0, stream, p);
+            else hipLaunchKernelGGL((mhsa_flash_kernel<64, DT_BF16>), g, b, 0, stream, p);
+        }
         return hipGetLastError();
     }
     const int64_t grid = (batch * heads * N + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_F32) hipLaunchKernelGGL(mhsa_rows_kernel<DT_F32>, dim3((unsigned)grid), dim3(256), 0, stream, p);
+    else if (dtype == DT_F16) hipLaunchKernelGGL(mhsa_rows_kernel<DT_F16>, dim3((unsigned)grid), dim3(256), 0, stream, p);
     else hipLaunchKernelGGL(mhsa_rows_kernel<DT_BF16>, dim3((unsigned)grid), dim3(256), 0, stream, p);
     return hipGetLastError();
 }

@@ -15,7 +15,7 @@ from paper_2602_12305_amd import binding as ob
 from paper_2602_12305_amd import synth
 
 pytestmark = pytest.mark.gpu
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def e1(y, ref):
@@ -25,8 +25,8 @@ def e1(y, ref):
 
 def run(Q, K, V, heads, dtype):
     batch, N, d = Q.shape
-    if dtype == BF16:
-        conv = lambda a: torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).cuda()
+    if dtype != F32:
+        conv = lambda a: torch.from_numpy(synth.to_bits(a, dtype).view(np.int16)).cuda()
         O = torch.full((batch, N, d), 0x4640, dtype=torch.int16, device="cuda")
     else:
         conv = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
@@ -34,12 +34,12 @@ def run(Q, K, V, heads, dtype):
     ob.optiml_mhsa(batch, N, d, heads, conv(Q), conv(K), conv(V), O, dtype)
     torch.cuda.synchronize()
     o = O.cpu().numpy()
-    return synth.bf16_bits_to_f32(o.view(np.uint16)).astype(np.float64) if dtype == BF16 else o.astype(np.float64)
+    return synth.from_bits(o.view(np.uint16), dtype).astype(np.float64) if dtype != F32 else o.astype(np.float64)
 
 
 def reference(Q, K, V, heads, dtype):
-    if dtype == BF16:
-        return oracle.mhsa(synth.f32_to_bf16_bits(Q), synth.f32_to_bf16_bits(K), synth.f32_to_bf16_bits(V), heads, dtype=oracle.BF16)
+    if dtype != F32:
+        return oracle.mhsa(synth.to_bits(Q, dtype), synth.to_bits(K, dtype), synth.to_bits(V, dtype), heads, dtype=dtype)
     return oracle.mhsa(Q, K, V, heads)
 
 
@@ -130,3 +130,15 @@ def test_benchmark_shape_on_sampled_heads():
         part = lambda a: np.ascontiguousarray(a[b:b + 1, :, cols])
         ref = oracle.mhsa(part(q), part(k), part(v), 1, dtype=oracle.BF16)[0]
         assert e1(got[b, :, cols], ref) <= 2e-2, (b, h)
+
+
+@pytest.mark.parametrize("batch,N,d,heads", [(2, 200, 256, 2), (1, 333, 512, 4), (3, 130, 64, 1), (1, 1000, 256, 4), (1, 150, 96, 3)])
+def test_binary16_storage_matches_the_oracle(batch, N, d, heads):
+    """fp16 storage: the same kernels with the f16 matrix instruction; weights and output carry 11 significant bits,
+    so the bar is the contraction's for this type (1e-3) plus the weights' rounding: E1 <= 2e-3.  The last case
+    (d_k = 32) runs the one-wave-per-query kernel."""
+    Q, K, V = inputs(2500 + N + d, batch, N, d)
+    got = run(Q, K, V, heads, F16)
+    ref = reference(Q, K, V, heads, F16)
+    assert np.all(np.isfinite(got))
+    assert e1(got, ref) <= 2e-3

@@ -121,7 +121,7 @@ def test_attention_entry_point_validates_on_the_host():
     ok = (1, 64, 256, 4, P, P, P, P, 1, None)
     bad = [(-1, 64, 256, 4, P, P, P, P, 1, None), (1, -64, 256, 4, P, P, P, P, 1, None), (1, 64, 0, 4, P, P, P, P, 1, None),
            (1, 64, 256, 0, P, P, P, P, 1, None), (1, 64, 256, 3, P, P, P, P, 1, None),       # 256 columns, 3 heads
-           (1, 64, 256, 4, P, P, P, P, 2, None), (1, 64, 256, 4, None, P, P, P, 1, None),
+           (1, 64, 256, 4, P, P, P, P, 3, None), (1, 64, 256, 4, None, P, P, P, 1, None),
            (1, 64, 256, 4, P, None, P, P, 1, None), (1, 64, 256, 4, P, P, None, P, 1, None), (1, 64, 256, 4, P, P, P, None, 1, None)]
     for args in bad:
         assert L.optiml_mhsa(*args) == ob.ERR_INVALID_ARG, args
