@@ -41,8 +41,9 @@ STREAM_N = 1 << 28
 # features (the task's 4-D shape, every feature of a sample is one row) and on 32768 rows of 8192
 # attention: bf16, 4 sequences of 4096 tokens, d_model 2048, 16 heads of 128
 MHSA = {"s_mhsa": (4, 4096, 2048, 16)}
-# contraction fused with the cross-entropy: 8192 rows (tokens), 32768 classes, K 4096, bf16, B row-major
-LCE = {"s_lce": (8192, 32768, 4096)}
+# contraction fused with the cross-entropy, B row-major: 8192 rows (tokens), 32768 classes, K 4096 in bf16;
+# 4096 rows, 32768 classes, K 2048 in fp32
+LCE = {"s_lce": (8192, 32768, 4096, 1), "s_lce_f32": (4096, 32768, 2048, 0)}     # (M, N, K, dtype)
 ROWS = {"s_ce": (8192, 32768), "s_ln_sample": (64, 64 * 256 * 256), "s_ln_token": (32768, 8192)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
@@ -351,16 +352,16 @@ def main():
 
     def time_lce(name, steps, warmup, with_oracle):
         """Contraction + cross-entropy, bf16 storage: A N(0, 1/K) (logits of unit variance), B N(0,1), bias N(0,1)."""
-        M, N, K = LCE[name]
-        A = synth.f32_to_bf16_bits(synth.normal(10, "A", M, K, 0.0, K ** -0.5))
-        B = synth.f32_to_bf16_bits(synth.normal(10, "B", K, N))
+        M, N, K, dt = LCE[name]
+        A = synth.to_bits(synth.normal(10, "A", M, K, 0.0, K ** -0.5), dt)
+        B = synth.to_bits(synth.normal(10, "B", K, N), dt)
         bias = synth.normal(10, "bias", 1, N)[0]
         labels = ((7919 * np.arange(M)) % N).astype(np.int32)
-        Ad, Bd = (torch.from_numpy(h.view(np.int16)).cuda() for h in (A, B))
+        Ad, Bd = (torch.from_numpy(h.view(np.int16) if dt else h).cuda() for h in (A, B))
         bd, ld = torch.from_numpy(bias).cuda(), torch.from_numpy(labels).cuda()
         out = torch.empty(2, dtype=torch.float32, device="cuda")
-        step = lambda rows=M, o=0: ob.optiml_gemm_cross_entropy(rows, N, K, Ad, K, Bd, N, bd, ld, out[o:], 0, 1)
-        assert ob.optiml_gemm_cross_entropy_path(M, N, K, Ad, K, Bd, N, bd, 0, 1) == 0
+        step = lambda rows=M, o=0: ob.optiml_gemm_cross_entropy(rows, N, K, Ad, K, Bd, N, bd, ld, out[o:], 0, dt)
+        assert ob.optiml_gemm_cross_entropy_path(M, N, K, Ad, K, Bd, N, bd, 0, dt) == 0
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
@@ -378,12 +379,14 @@ def main():
         tfl = flops / (kernel_ms * 1e-3) / 1e12
         tr = TRAFFIC.get((name, name))
         traffic = tr["bytes"] if tr and tr["src"] == kernel_source_hash(tr["files"]) else None
-        res = {"workload": name, "variant": "ring_bf16_rr_lse", "M": M, "N": N, "K": K, "ms_per_step": round(ms, 5),
-               "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 3), "mfma_frac": round(tfl / PEAK_TFLOPS[1], 4), "dtype": "bf16",
+        res = {"workload": name, "variant": f"ring_{DTYPE_NAME[dt]}_rr_lse", "M": M, "N": N, "K": K, "ms_per_step": round(ms, 5),
+               "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 3), "mfma_frac": round(tfl / PEAK_TFLOPS[dt], 4),
+               "dtype": DTYPE_NAME[dt],
                "loss": float(out[0].item()),
-               "roofline": {"bound": "mfma", "achieved": round(tfl, 3), "peak": PEAK_TFLOPS[1], "unit": "TFLOP/s",
-                            "frac": round(tfl / PEAK_TFLOPS[1], 4), "traffic": traffic,
-                            "kernel": "gemm_ring_kernel (log-sum-exp epilogue) + lce_rows_kernel + lce_mean_kernel",
+               "roofline": {"bound": "mfma", "achieved": round(tfl, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
+                            "frac": round(tfl / PEAK_TFLOPS[dt], 4), "traffic": traffic,
+                            "kernel": ("gemm_ring_kernel" if dt else "gemm_ring_f32_kernel") +
+                                      " (log-sum-exp epilogue) + lce_rows_kernel + lce_mean_kernel",
                             "kernel_ms": round(kernel_ms, 5)}}
         if with_oracle:
             import oracle
@@ -391,7 +394,7 @@ def main():
             step(m, 1)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            ref = oracle.gemm_cross_entropy(A[:m], B, bias, labels[:m], m, N, K, dtype=oracle.BF16)
+            ref = oracle.gemm_cross_entropy(A[:m], B, bias, labels[:m], m, N, K, dtype=dt)
             secs = time.perf_counter() - t0
             res["cpu_baseline"] = {"value": float(f"{flops * (m / M) / 1e12 / secs:.4g}"), "unit": "TFLOP/s",
                                    "cores": oracle.num_threads(), "kind": "oracle", "sample": f"first {m} of {M} rows",
@@ -403,7 +406,7 @@ def main():
         r = time_lce(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
         out = {"metric": "TFLOP/s of the contraction fused with the cross-entropy", "value": r["TFLOP/s"], "unit": "TFLOP/s",
                "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
-               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": r["dtype"], "data": "synthetic",
                "config": {"workload": args.workload, "M": r["M"], "N": r["N"], "K": r["K"]}, "TFLOP/s": r["TFLOP/s"],
                "loss": r["loss"], "roofline": r["roofline"]}
         for k in ("cpu_baseline", "parity_abs_err"):

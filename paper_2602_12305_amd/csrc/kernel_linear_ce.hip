@@ -2,16 +2,16 @@
 // logits ever reaching memory:
 //     loss = (1/M) sum_i [ log sum_j exp(z_ij) - z_{i, y_i} ],   z = A.B + bias  (M rows, N classes)
 //
-// Fast path (16-bit storage, A row-major, shapes the ring kernel takes): the bf16 / fp16 ring
-// kernel with its log-sum-exp epilogue - every wave reduces the 64 columns it holds of each of
-// its rows to a (maximum, sum of exponentials) pair, in registers, and the lane that holds the
-// label's column hands out that logit.  What reaches memory is 8 bytes per row and 64 columns
-// instead of the logits.  Fallback (everything else): one workgroup per row forms the row's
+// Fast path (A row-major, shapes the ring kernels take): the bf16 / fp16 or the fp32 ring kernel
+// with its log-sum-exp epilogue - every wave reduces the 64 (fp32: 32) columns it holds of each
+// of its rows to a (maximum, sum of exponentials) pair, in registers, and the lane that holds the
+// label's column hands out that logit.  What reaches memory is 8 bytes per row and 64 (32)
+// columns instead of the logits.  Fallback (everything else): one workgroup per row forms the row's
 // logits one column per thread in fp32 and reduces them the same way.  Both are followed by
 // lce_rows_kernel (16 threads per row merge the row's pairs in fp64 in a fixed order, form the
 // row loss, and a workgroup adds its 16 rows in row order) and lce_mean_kernel (adds the workgroups' sums in
 // order, divides by M, rounds once to float).
-#include "kernel_tile_ring.hpp"
+#include "kernel_ring_f32.hpp"
 
 namespace optiml {
 namespace {
@@ -129,6 +129,9 @@ __global__ __launch_bounds__(64) void lce_mean_kernel(const double *block_sums, 
 
 template <int DT, bool B_KC> using LseCfg = ring::Cfg<4, B_KC, true, 4, DT, 1>;
 
+using LseCfgF32Rr = ringf::Cfg<128, 4, false, 1>;
+using LseCfgF32Rc = ringf::Cfg<128, 4, true, 1>;
+
 template <class C>
 hipError_t launch_ring_lse(const Problem &p, const int *labels, float *part, float *picked, hipStream_t stream)
 {
@@ -142,7 +145,11 @@ hipError_t launch_ring_lse(const Problem &p, const int *labels, float *part, flo
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = ACT_NONE;
     q.labels = labels; q.picked = picked;
-    hipLaunchKernelGGL(ring::gemm_ring_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
+    if constexpr (std::is_same<C, LseCfgF32Rr>::value || std::is_same<C, LseCfgF32Rc>::value) {
+        hipLaunchKernelGGL(ringf::gemm_ring_f32_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
+    } else {
+        hipLaunchKernelGGL(ring::gemm_ring_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
+    }
     return hipGetLastError();
 }
 
@@ -151,14 +158,14 @@ bool ring_takes(const Problem &p)
 {
     if (p.dtype == DT_BF16) return p.b_col() ? ring::supports<LseCfg<DT_BF16, true>>(p) : ring::supports<LseCfg<DT_BF16, false>>(p);
     if (p.dtype == DT_F16) return p.b_col() ? ring::supports<LseCfg<DT_F16, true>>(p) : ring::supports<LseCfg<DT_F16, false>>(p);
-    return false;
+    return p.b_col() ? ringf::supports<LseCfgF32Rc>(p) : ringf::supports<LseCfgF32Rr>(p);
 }
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 }  // namespace
 
-// 0: ring kernel with the log-sum-exp epilogue, 1: row-per-workgroup fallback
+// 0: a ring kernel with the log-sum-exp epilogue, 1: row-per-workgroup fallback
 int linear_ce_path(const Problem &p)
 {
     Problem q = p;
@@ -170,7 +177,8 @@ int linear_ce_path(const Problem &p)
 hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hipStream_t stream)
 {
     const int path = linear_ce_path(p);
-    const int64_t slices = path == 0 ? ((p.N + 255) / 256) * 4 : 1;
+    // a pair per row and wave-wide slice of columns: 4 slices per 256-column (fp32: 128-column) tile
+    const int64_t slices = path != 0 ? 1 : p.dtype == DT_F32 ? ((p.N + 127) / 128) * 4 : ((p.N + 255) / 256) * 4;
     const int64_t blocks = (p.M + kRowsPerBlock - 1) / kRowsPerBlock;
     const size_t part_bytes = align256(sizeof(float) * 2 * (size_t)slices * p.M);
     const size_t pick_bytes = align256(sizeof(float) * (size_t)p.M);
@@ -188,9 +196,12 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
         if (p.dtype == DT_BF16)
             e = p.b_col() ? launch_ring_lse<LseCfg<DT_BF16, true>>(p, labels, part, picked, stream)
                           : launch_ring_lse<LseCfg<DT_BF16, false>>(p, labels, part, picked, stream);
-        else
+        else if (p.dtype == DT_F16)
             e = p.b_col() ? launch_ring_lse<LseCfg<DT_F16, true>>(p, labels, part, picked, stream)
                           : launch_ring_lse<LseCfg<DT_F16, false>>(p, labels, part, picked, stream);
+        else
+            e = p.b_col() ? launch_ring_lse<LseCfgF32Rc>(p, labels, part, picked, stream)
+                          : launch_ring_lse<LseCfgF32Rr>(p, labels, part, picked, stream);
     } else {
         if (p.M > 0x7fffffffLL) return hipErrorInvalidValue;
         const dim3 grid((unsigned)p.M);

@@ -37,8 +37,12 @@ using ring::lds_char;
 using ring::Params;
 using ring::uintx4;
 
-template <int BM_, int NS_, bool B_KC_>
+template <int BM_, int NS_, bool B_KC_, int EPI_ = 0>
 struct Cfg {
+    // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 32 columns of A.B + bias
+    // to a (maximum, sum of exponentials) pair per row and hands out the label's logit (see the
+    // same switch of the 16-bit ring kernel).
+    static constexpr int EPI = EPI_;
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
     static constexpr int BM = BM_, BN = 128, BK = 16, WM = 2, WN = 4, NW = WM * WN, THREADS = 64 * NW;
@@ -254,6 +258,43 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
             for (int e = 0; e < 4; ++e) bj[gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
         }
     }
+    if constexpr (C::EPI == 1) {
+        float *pairs = reinterpret_cast<float *>(p.C);
+        const int64_t slice = tile_n * C::WN + wn;
+        const bool ragged = nw + C::WTN > p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = mw + 32 * i + frag_row;
+            const bool live = m < p.M;
+            // this lane holds columns nw + 8 gq + 4 half + e of row m; `want` is the label's offset
+            // in those terms without the 4 half (or a value no offset takes)
+            const int64_t d = live ? (int64_t)p.labels[m] - nw : -1;
+            const int want = d >= 0 && d < C::WTN ? (int)d - 4 * half : -1000;
+            float mx = -__builtin_inff(), pick = 0.0f;
+            bool hit = false;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int cofs = 8 * gq + e;
+                    float v = acc[i][4 * gq + e] + bj[gq][e];
+                    if (ragged && nw + cofs + 4 * half >= p.N) v = -__builtin_inff();
+                    acc[i][4 * gq + e] = v;
+                    mx = __builtin_fmaxf(mx, v);
+                    if (want == cofs) { pick = v; hit = true; }
+                }
+            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float ref = mx == -__builtin_inff() ? 0.0f : mx;       // a slice wholly past column N
+            float sum = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[i][r] - ref) * 1.44269504088896341f);
+            sum += __shfl_xor(sum, 32, 64);
+            if (live && half == 0)
+                *reinterpret_cast<ring::floatx2 *>(pairs + 2 * (slice * p.M + m)) = ring::floatx2{mx, sum};
+            if (live && hit) p.picked[m] = pick;
+        }
+        return;
+    }
     const int wkey = (frag_row >> 1) & 7;
     dispatch_act(p.act, [&](auto act_tag) {
     constexpr int ACT = decltype(act_tag)::value;
@@ -315,6 +356,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = p.act;
+    q.labels = nullptr; q.picked = nullptr;
     const int64_t total = q.tiles_m * q.tiles_n * p.batch;
     hipLaunchKernelGGL(gemm_ring_f32_kernel<C>, dim3((unsigned)total), dim3(C::THREADS), 0, stream, q);
     return hipGetLastError();

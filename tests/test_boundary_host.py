@@ -205,7 +205,8 @@ def test_fused_cross_entropy_entry_point_validates_and_picks_its_kernel_on_the_h
     assert path(8192, 32768, 4096, 0, 1) == 0 and path(8192, 32768, 4096, 1, 2) == 0     # 16-bit, A row-major: matrix pipe
     assert path(300, 515, 160, 1, 1) == 0                                                  # ragged N with a column-major B
     assert path(300, 516, 160, 0, 1) == 1                                                  # row-major B rows not whole chunks
-    assert path(8192, 32768, 4096, 0, 0) == 1                                              # fp32
+    assert path(8192, 32768, 4096, 0, 0) == 0 and path(100, 130, 64, 1, 0) == 0            # fp32: its own ring kernel
+    assert path(100, 130, 48, 1, 0) == 1 and path(100, 130, 64, 0, 0) == 1                 # K < 64; row-major B rows not whole chunks
     assert path(8192, 32768, 4096, 2, 1) == 1                                              # A column-major
     assert path(64, 64, 96, 0, 1) == 1 and path(64, 64, 0, 0, 1) == 1                     # K too short for the ring, K = 0
     assert path(64, 64, 128, 0, 1, A=P + 2) == 1                                           # misaligned A

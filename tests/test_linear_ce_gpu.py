@@ -59,7 +59,14 @@ def test_matrix_pipe_path_matches_the_oracle(dtype, layout, M, N, K):
     check(M, N, K, layout, dtype, 3100 + N, 0, use_bias=False, scale=0.25)
 
 
-@pytest.mark.parametrize("dtype,layout,M,N,K,pad", [(F32, 0, 37, 53, 29, 0), (F32, 1, 40, 300, 64, 4), (F32, 2, 33, 257, 100, 0),
+@pytest.mark.parametrize("layout,M,N,K", [(0, 300, 520, 160), (1, 300, 515, 160), (0, 1024, 2048, 512), (1, 77, 64, 64),
+                                          (0, 513, 264, 1008), (1, 130, 1000, 2048)])
+def test_fp32_matrix_pipe_path_matches_the_oracle(layout, M, N, K):
+    check(M, N, K, layout, F32, 3500 + N, 0)
+    check(M, N, K, layout, F32, 3600 + N, 0, use_bias=False, scale=0.25)
+
+
+@pytest.mark.parametrize("dtype,layout,M,N,K,pad", [(F32, 0, 37, 53, 29, 0), (F32, 1, 40, 300, 48, 4), (F32, 2, 33, 257, 100, 0),
                                                     (F32, 3, 5, 1000, 7, 1), (BF16, 2, 64, 512, 128, 0), (F16, 0, 50, 77, 45, 0),
                                                     (BF16, 0, 20, 516, 160, 0), (F32, 0, 3, 1, 16, 0), (F16, 3, 130, 130, 130, 2)])
 def test_fallback_path_matches_the_oracle(dtype, layout, M, N, K, pad):
@@ -73,7 +80,7 @@ def test_closed_forms_and_degenerate_cases_on_the_gpu():
     labels = (np.arange(M) % N).astype(np.int32)
     for dtype in (BF16, F32):
         got, path = run(store(A, dtype), store(Z, dtype), None, labels, M, N, K, 0, dtype)
-        assert path == (0 if dtype == BF16 else 1)
+        assert path == 0
         assert got == pytest.approx(math.log(N), abs=2e-6)                # zero weights: uniform prediction
         # K = 0: the loss of the bias alone
         bias = synth.normal(3300, "bias", 1, N)[0]
