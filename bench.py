@@ -47,7 +47,7 @@ LCE = {"s_lce": (8192, 32768, 4096, 1), "s_lce_f32": (4096, 32768, 2048, 0)}    
 ROWS = {"s_ce": (8192, 32768), "s_ln_sample": (64, 64 * 256 * 256), "s_ln_token": (32768, 8192)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# passes (KiB per dispatch, scaled by what the same counters read for the library's 1 GiB copy
+# passes (KiB summed over the kernels of one step, scaled by what the same counters read for the library's 1 GiB copy
 # kernel: FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000; summaries under profiles/).  An entry is only
 # reported while the sources of that kernel (its own files and the shared epilogue arithmetic) still hash to
 # the value recorded with it.
@@ -56,29 +56,41 @@ RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "e
 RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
 RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 STREAMS_SRC = ("kernel_streams.hip", "epilogue.hpp")
+SKINNY16_SRC = ('kernel_skinny16.hpp', 'kernel_skinny16.hip', 'epilogue.hpp')
+LCE_SRC = ('kernel_linear_ce.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
+LCE_F32_SRC = ('kernel_linear_ce.hip', 'kernel_ring_f32.hpp', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
+    # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
-        {"bytes": int((528469 * 2.0 + 2048 + 1081.5 * 2.0 + 1024) * 1024), "files": SKINNY_SRC, "src": "c9b23ea574ddc4b8"},
+        {"bytes": int((529550.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "c552b7023eddf7be"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((384966 * 2.0 + 65536) * 1024), "files": RINGF_SRC, "src": "ed30a56b5411eddf"},
+        {"bytes": int((384928.0 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "cbc84d18131bb72d"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((792834 * 2.0 + 131073) * 1024), "files": RING_SRC, "src": "7492004065ec089f"},
+        {"bytes": int((791041.6 * 2.0 + 131088.9) * 1024), "files": RING_SRC, "src": "2345bd5346290519"},
+    ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
+        {"bytes": int((793805.8 * 2.0 + 131091.7) * 1024), "files": RING_SRC, "src": "2345bd5346290519"},
     ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((67449.1 * 2.0 + 262866) * 1024), "files": RINGP_SRC, "src": "c02f95aa26f68638"},
+        {"bytes": int((67500.6 * 2.0 + 262735.4) * 1024), "files": RINGP_SRC, "src": "1326f112e3c54462"},
+    ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
+        {"bytes": int((266405.4 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "94bbd1015fd43913"},
     ("s_sigmoid", "s_sigmoid"):
-        {"bytes": int((524329 * 2.0 + 1048580) * 1024), "files": STREAMS_SRC, "src": "676666c89a415e62"},
-    ("s_ce", "s_ce"):
-        {"bytes": int(((524969 + 9.94) * 2.0 + 64.16 + 0.03) * 1024), "files": ROWS_SRC, "src": "7712a69450f82056"},
-    ("s_ln_sample", "s_ln_sample"):        # four groups of 256 MiB: statistics kernel + normalising kernel each
-        {"bytes": int(4 * ((131109 + 131373) * 2.0 + 128 + 262350) * 1024), "files": ROWS_SRC, "src": "7712a69450f82056"},
-    ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524323 * 2.0 + 1048770) * 1024), "files": ROWS_SRC, "src": "7712a69450f82056"},
-    ("s_mhsa", "s_mhsa"):
-        {"bytes": int((98402.8 * 2.0 + 65536) * 1024), "files": ATTN_SRC, "src": "e8a988a024b40824"},
+        {"bytes": int((524327.4 * 2.0 + 1048577.4) * 1024), "files": STREAMS_SRC, "src": "02250798199cd25e"},
     ("s_dot", "s_dot"):
-        {"bytes": int(((1048650 + 33.08) * 2.0 + 256.55 + 0.03) * 1024), "files": STREAMS_SRC, "src": "676666c89a415e62"},
+        {"bytes": int((1048631.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "02250798199cd25e"},
+    ("s_ce", "s_ce"):
+        {"bytes": int((524980.1 * 2.0 + 64.3) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+    ("s_ln_sample", "s_ln_sample"):
+        {"bytes": int((1049927.7 * 2.0 + 1049906.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+    ("s_ln_token", "s_ln_token"):
+        {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+    ("s_mhsa", "s_mhsa"):
+        {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "0b50637145a1936e"},
+    ("s_lce", "s_lce"):
+        {"bytes": int((1590396.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "a728f331d9580d2d"},
+    ("s_lce_f32", "s_lce_f32"):
+        {"bytes": int((1584475.5 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "f7657cf71d7ba4ff"},
 }
 
 
