@@ -54,6 +54,8 @@ def lib():
         L.oracle_cross_entropy.argtypes = [i64, i64, vp, vp]
         L.oracle_cross_entropy_f64.restype = C.c_double
         L.oracle_cross_entropy_f64.argtypes = [i64, i64, vp, vp]
+        L.oracle_transpose.restype = None
+        L.oracle_transpose.argtypes = [i64, i64, vp, vp, i64]
         L.oracle_layernorm.restype = None
         L.oracle_layernorm.argtypes = [i64, i64, vp, C.c_double, vp]
         L.oracle_mhsa.restype = C.c_int
@@ -193,6 +195,16 @@ def gemm_cross_entropy(A, B, bias, labels, M, N, K, *, dtype=F32, layout=LAYOUT_
     if labels.shape != (M,):
         raise ValueError("labels [M] expected")
     return float(lib().oracle_cross_entropy_f64(M, N, _ptr(z), _ptr(labels)))
+
+
+def transpose(x):
+    """The transposed copy of a 2-D array of 2- or 4-byte elements (Table 4, task 8), same dtype."""
+    x = np.ascontiguousarray(x)
+    if x.ndim != 2 or x.dtype.itemsize not in (2, 4):
+        raise ValueError("a 2-D array of 2- or 4-byte elements expected")
+    out = np.empty((x.shape[1], x.shape[0]), dtype=x.dtype)
+    lib().oracle_transpose(x.shape[0], x.shape[1], _ptr(x), _ptr(out), x.dtype.itemsize)
+    return out
 
 
 def layernorm(x, eps=1e-5):

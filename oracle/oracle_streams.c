@@ -28,6 +28,7 @@
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <string.h>
 
 enum { ORACLE_EW_RELU = 0, ORACLE_EW_SIGMOID = 1 };
 enum { ORACLE_RED_SUM = 0, ORACLE_RED_DOT = 1, ORACLE_RED_MSE = 2 };
@@ -154,4 +155,17 @@ void oracle_layernorm(int64_t rows, int64_t len, const float *x, double eps, dou
         const double rstd = 1.0 / sqrt(q / (double)len + eps);
         for (int64_t i = 0; i < len; ++i) yr[i] = ((double)xr[i] - mean) * rstd;
     }
+}
+
+/*
+ * Transpose (Table 4, task 8): dst[j][i] = src[i][j] for a rows x cols row-major matrix of
+ * elements of `esize` bytes; dst is cols x rows row-major.  Bytes are moved, never interpreted.
+ */
+void oracle_transpose(int64_t rows, int64_t cols, const void *src, void *dst, int64_t esize)
+{
+    const char *s = (const char *)src;
+    char *d = (char *)dst;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j)
+            memcpy(d + (j * rows + i) * esize, s + (i * cols + j) * esize, (size_t)esize);
 }

@@ -262,3 +262,22 @@ def test_fused_contraction_cross_entropy_closed_forms():
     # out-of-range label: NaN; no rows: 0
     bad = labels.copy(); bad[3] = N
     assert math.isnan(oracle.gemm_cross_entropy(A, Z, None, bad, M, N, K))
+
+
+def test_transpose_moves_every_element_to_its_mirror_position():
+    # a matrix whose entries encode their own position: entry (i, j) = 1000 i + j
+    rows, cols = 7, 13
+    x = (1000 * np.arange(rows)[:, None] + np.arange(cols)[None, :]).astype(np.float32)
+    t = oracle.transpose(x)
+    assert t.shape == (cols, rows) and t.dtype == np.float32
+    for i, j in ((0, 0), (0, 12), (6, 0), (6, 12), (3, 5)):
+        assert t[j, i] == 1000 * i + j
+    assert np.array_equal(t, x.T)                                  # numpy's view of the same thing
+    assert np.array_equal(oracle.transpose(t), x)                  # an involution
+    # 16-bit elements, bit patterns that are NaNs or denormals as floats: bytes are moved, not interpreted
+    b = np.arange(5 * 9, dtype=np.uint16).reshape(5, 9) * np.uint16(1499) + np.uint16(0x7F80)
+    assert np.array_equal(oracle.transpose(b), b.T)
+    assert oracle.transpose(np.zeros((0, 4), np.float32)).shape == (4, 0)
+    # a row and a column
+    v = np.arange(11, dtype=np.int32).reshape(1, 11)
+    assert np.array_equal(oracle.transpose(v), v.reshape(11, 1))
