@@ -9,7 +9,7 @@ re-read the same bytes from cache).  The default workload is the memory-bound sk
 configuration (M=16, N=K=16384, fp32, SiLU); --all also times the other four and the
 streaming siblings (element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats: --workload
 s_relu, s_sigmoid, s_sum, s_dot, s_mse; cross-entropy and LayerNorm: s_ce, s_ln_sample,
-s_ln_token; attention: s_mhsa; contraction + cross-entropy: s_lce) and adds them under "workloads".  One JSON line is
+s_ln_token; transpose: s_transpose; attention: s_mhsa; contraction + cross-entropy: s_lce) and adds them under "workloads".  One JSON line is
 printed.
 
 The "roofline" object prices the dominant kernel of the workload against the published
@@ -35,7 +35,7 @@ BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_r
 DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}
 # streaming siblings: (entry point, op, arrays read, arrays written)
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
-           "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0)}
+           "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0), "s_transpose": ("tr", 0, 1, 1)}
 STREAM_N = 1 << 28
 # row-wise siblings: cross-entropy on [8192, 32768] logits; LayerNorm on 64 samples of 64 x 256 x 256
 # features (the task's 4-D shape, every feature of a sample is one row) and on 32768 rows of 8192
@@ -214,9 +214,12 @@ def main():
         hy = gen("y") if reads == 2 else None
         xd = torch.from_numpy(hx).cuda()
         yd = torch.from_numpy(hy).cuda() if hy is not None else None
-        od = torch.empty(n if kind == "ew" else 1, dtype=torch.float32, device="cuda")
+        od = torch.empty(1 if kind == "red" else n, dtype=torch.float32, device="cuda")
+        side = 1 << 14                                          # the transpose sees the array as 16384 x 16384
         if kind == "ew":
             step = lambda: ob.optiml_elementwise(n, xd, od, op)
+        elif kind == "tr":
+            step = lambda: ob.optiml_transpose(side, side, xd, side, od, side, 4)
         else:
             step = lambda: ob.optiml_reduce(n, xd, yd, op, od)
         for _ in range(warmup):
@@ -251,6 +254,11 @@ def main():
                 got = od[:m].cpu().numpy().astype(np.float64)
                 err = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)))
                 full, sample = secs * (n / m), f"first {m} of {n} elements"
+            elif kind == "tr":
+                ref = oracle.transpose(hx.reshape(side, side))
+                secs = time.perf_counter() - t0
+                err = 0.0 if np.array_equal(od.cpu().numpy().reshape(side, side), ref) else 1.0
+                full, sample = secs, "whole workload"
             else:
                 ref = oracle.reduce(hx, hy, op)
                 secs = time.perf_counter() - t0

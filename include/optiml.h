@@ -230,6 +230,19 @@ int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, 
 int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream);
 
 /*
+ * Transpose (the paper's Table 4, task 8): dst[j * ld_dst + i] = src[i * ld_src + j] for a
+ * rows x cols row-major matrix of elements of elem_bytes (2 or 4) bytes; dst is cols x rows.
+ * DEVICE pointers, src and dst must not overlap; pitches in elements, ld_src >= cols,
+ * ld_dst >= rows; padding is neither read nor written.  Bytes are moved, never interpreted.
+ * 16-byte aligned bases with extents and pitches that are whole 16-byte chunks take the
+ * vectorised kernel, everything else an element-wise one.  rows == 0 or cols == 0 writes nothing.
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, elem_bytes not 2 or 4, a pitch
+ * shorter than its row, NULL src or dst with work to do.
+ */
+int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int elem_bytes,
+                     void *stream);
+
+/*
  * The contraction feeding the cross-entropy (the paper's Table 4, task 2 into task 17), fused:
  *     *loss = (1/M) sum_i [ log sum_j exp(z[i][j]) - z[i][labels[i]] ],   z = A.B + bias
  * for M rows (samples) and N classes, with A, B, bias, layouts, leading dimensions and dtype

@@ -37,6 +37,7 @@ SIGNATURES = {
     "optiml_cross_entropy": (_int, [_i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "optiml_layernorm": (_int, [_i64, _i64, _vp, _vp, C.c_float, _vp]),
     "optiml_mhsa": (_int, [_i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]),
+    "optiml_transpose": (_int, [_i64, _i64, _vp, _i64, _vp, _i64, _int, _vp]),
     "optiml_gemm_cross_entropy": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _int, _int, _vp]),
     "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
     "optiml_status_string": (C.c_char_p, [_int]),
@@ -175,6 +176,10 @@ def optiml_layernorm(rows, length, x, y, eps, stream=None):
 def optiml_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, stream=None):
     return _check(lib().optiml_mhsa(batch, N, d_model, heads, _addr(Q), _addr(K), _addr(V), _addr(O), dtype,
                                     _stream(stream)))
+
+
+def optiml_transpose(rows, cols, src, ld_src, dst, ld_dst, elem_bytes, stream=None):
+    return _check(lib().optiml_transpose(rows, cols, _addr(src), ld_src, _addr(dst), ld_dst, elem_bytes, _stream(stream)))
 
 
 def optiml_gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, layout, dtype, stream=None):

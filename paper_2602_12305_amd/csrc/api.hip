@@ -397,6 +397,21 @@ int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float 
     return OPTIML_OK;
 }
 
+int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int elem_bytes,
+                     void *stream)
+{
+    if (rows < 0 || cols < 0 || (elem_bytes != 2 && elem_bytes != 4) || ld_src < cols || ld_dst < rows)
+        return OPTIML_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return OPTIML_OK;
+    if (!src || !dst) return OPTIML_ERR_INVALID_ARG;
+    hipError_t e = optiml::launch_transpose(rows, cols, src, ld_src, dst, ld_dst, elem_bytes, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    return OPTIML_OK;
+}
+
 int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                               const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream)
 {

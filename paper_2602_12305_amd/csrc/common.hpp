@@ -62,6 +62,10 @@ hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads,
 int linear_ce_path(const Problem &p);
 hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hipStream_t stream);
 
+// transpose (kernel_transpose.hip), arguments already validated
+hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int esize,
+                            hipStream_t s);
+
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;

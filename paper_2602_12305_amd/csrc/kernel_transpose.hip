@@ -5,9 +5,9 @@
 // time and the ring kernel is about twice as fast as the staged tile kernel that otherwise
 // serves this layout.
 //
-// transpose_kernel: a workgroup owns a 64 x 64 element tile; 16-byte reads along the source's
-// contiguous direction, element-wise writes into a padded LDS tile, 16-byte reads of LDS along
-// the other direction, 16-byte writes.  Both extents must be whole 16-byte chunks.
+// transpose_kernel: a workgroup owns a tile of 256 bytes x 256 bytes; 16-byte accesses on both
+// sides of memory and an XOR-swizzled LDS tile in between.  Both extents must be whole 16-byte
+// chunks.
 #include "common.hpp"
 
 namespace optiml {
@@ -15,35 +15,65 @@ namespace {
 
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
-// dst[b][c][r] = src[b][r * ld + c] for r < rows, c < cols; E = element type (2 or 4 bytes)
+// dst[b][c * ld_dst + r] = src[b][r * ld + c] for r < rows, c < cols (batches of the destination are
+// cols * ld_dst apart); E = element type (2 or 4 bytes).  A tile is T x T elements with T = 256
+// bytes / element size, so both sides move 256-byte row segments.  The tile sits in LDS
+// untransposed, 16 chunks of 16 bytes per row, chunk ch of row r at position ch ^ ((r / CH) % 16):
+// the 128-bit writes of a row are a permutation of its chunks, and in the read phase thread
+// (c, k) gathers element c of rows CH k .. CH k + CH - 1, which for the 16 values of k lie in 16
+// different chunk positions - no bank conflicts on either side.
 template <typename E>
 __global__ __launch_bounds__(256) void transpose_kernel(const E *__restrict__ src, E *__restrict__ dst, int64_t rows,
                                                         int64_t cols, int64_t ld, int64_t stride_src, int64_t tiles_c,
-                                                        int64_t tiles_r)
+                                                        int64_t tiles_r, int64_t ld_dst)
 {
-    constexpr int T = 64, CH = 16 / sizeof(E), CPR = T / CH;        // chunks per tile row
-    __shared__ E tile[T][T + CH];                                   // [c][r], rows kept 16-byte aligned
+    constexpr int CH = 16 / sizeof(E), T = 16 * CH;                  // elements per chunk, tile edge
+    __shared__ __attribute__((aligned(16))) E tile[T][T];
     const int64_t b = blockIdx.x / (tiles_c * tiles_r), t = blockIdx.x % (tiles_c * tiles_r);
-    const int64_t r0 = (t / tiles_c) * T, c0 = (t % tiles_c) * T;
+    // Diagonal walk: workgroup t takes column tile t % tiles_c of row band (t / tiles_c + that) %
+    // tiles_r, so the workgroups that run together read, and write, at different offsets within a
+    // row.  With a power-of-two pitch a row-major walk has them all at the same offset, i.e. on
+    // the same few memory channels (measured 4.3 against 5.0 TB/s for an odd pitch).
+    const int64_t tc = t % tiles_c, tr = (t / tiles_c + tc) % tiles_r;
+    const int64_t r0 = tr * T, c0 = tc * T;
     const E *s = src + b * stride_src;
-    E *d = dst + b * rows * cols;
-    for (int id = threadIdx.x; id < T * CPR; id += 256) {
-        const int r = id / CPR, ch = id % CPR;
-        if (r0 + r < rows && c0 + ch * CH < cols) {
-            const uintx4 v = *reinterpret_cast<const uintx4 *>(s + (r0 + r) * ld + c0 + ch * CH);
-            E e[CH];
-            __builtin_memcpy(e, &v, 16);
-#pragma unroll
-            for (int i = 0; i < CH; ++i) tile[ch * CH + i][r] = e[i];
-        }
+    E *d = dst + b * cols * ld_dst;
+    for (int id = threadIdx.x; id < T * 16; id += 256) {
+        const int r = id >> 4, ch = id & 15;
+        if (r0 + r < rows && c0 + ch * CH < cols)
+            *reinterpret_cast<uintx4 *>(&tile[r][(ch ^ ((r / CH) & 15)) * CH]) =
+                *reinterpret_cast<const uintx4 *>(s + (r0 + r) * ld + c0 + ch * CH);
     }
     __syncthreads();
-    for (int id = threadIdx.x; id < T * CPR; id += 256) {
-        const int c = id / CPR, ch = id % CPR;
-        if (c0 + c < cols && r0 + ch * CH < rows)
-            *reinterpret_cast<uintx4 *>(d + (c0 + c) * rows + r0 + ch * CH) =
-                *reinterpret_cast<const uintx4 *>(&tile[c][ch * CH]);
+    for (int id = threadIdx.x; id < T * 16; id += 256) {
+        const int c = id >> 4, k = id & 15;
+        if (c0 + c < cols && r0 + k * CH < rows) {
+            E e[CH];
+            const int pos = (((c / CH) ^ k) * CH) + c % CH;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) e[i] = tile[k * CH + i][pos];
+            uintx4 v;
+            __builtin_memcpy(&v, e, 16);
+            __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(d + (c0 + c) * ld_dst + r0 + k * CH));
+        }
     }
+}
+
+// Any shape, pitch and alignment: a 64 x 64 tile through a padded LDS tile, one element per access,
+// consecutive threads on consecutive addresses on both sides.
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_any_kernel(const E *__restrict__ src, E *__restrict__ dst, int64_t rows,
+                                                            int64_t cols, int64_t ld, int64_t ld_dst, int64_t tiles_c)
+{
+    constexpr int T = 64;
+    __shared__ E tile[T][T + 1];
+    const int64_t r0 = (blockIdx.x / tiles_c) * T, c0 = (blockIdx.x % tiles_c) * T;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < T; r += 4)
+        if (r0 + r < rows && c0 + tx < cols) tile[r][tx] = src[(r0 + r) * ld + c0 + tx];
+    __syncthreads();
+    for (int c = ty; c < T; c += 4)
+        if (c0 + c < cols && r0 + tx < rows) dst[(c0 + c) * ld_dst + r0 + tx] = tile[tx][c];
 }
 
 // the problem the ring kernel sees: A row-major in the workspace
@@ -74,7 +104,8 @@ bool xa_supports(const Problem &p)
     if (!p.a_col() || p.K < 1 || !vector_friendly(p)) return false;
     const int ch = 16 / p.esize();
     if (p.M % ch != 0 || p.K % ch != 0) return false;
-    if (p.batch * ((p.M + 63) / 64) * ((p.K + 63) / 64) > 0x7fffffffLL) return false;
+    const int64_t T = 256 / p.esize();
+    if (p.batch * ((p.M + T - 1) / T) * ((p.K + T - 1) / T) > 0x7fffffffLL) return false;
     return ring_for(with_row_major_a(p, reinterpret_cast<const void *>(uintptr_t(256)))) != nullptr;
 }
 
@@ -92,20 +123,52 @@ hipError_t xa_launch(const Problem &p, hipStream_t s)
     const Problem q = with_row_major_a(p, ws);
     const Variant *ring = ring_for(q);
     if (!ring) return hipErrorInvalidValue;
-    const int64_t tiles_c = (p.M + 63) / 64, tiles_r = (p.K + 63) / 64;
+    const int64_t T = 256 / p.esize();
+    const int64_t tiles_c = (p.M + T - 1) / T, tiles_r = (p.K + T - 1) / T;
     const dim3 grid((unsigned)(p.batch * tiles_c * tiles_r));
     if (p.esize() == 4)
         hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t *>(p.A),
-                           static_cast<uint32_t *>(ws), p.K, p.M, p.lda, p.strideA, tiles_c, tiles_r);
+                           static_cast<uint32_t *>(ws), p.K, p.M, p.lda, p.strideA, tiles_c, tiles_r, p.K);
     else
         hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(p.A),
-                           static_cast<uint16_t *>(ws), p.K, p.M, p.lda, p.strideA, tiles_c, tiles_r);
+                           static_cast<uint16_t *>(ws), p.K, p.M, p.lda, p.strideA, tiles_c, tiles_r, p.K);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return ring->launch(q, s);
 }
 
 }  // namespace
+
+// Table 4 task 8 as an operation of its own: dst (cols x rows, pitch ld_dst) = transpose of src
+// (rows x cols, pitch ld_src), elements of 2 or 4 bytes.  Arguments already validated.
+hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int esize,
+                            hipStream_t s)
+{
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t ch = 16 / esize;
+    auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    const bool fast = aligned(src) && aligned(dst) && rows % ch == 0 && cols % ch == 0 && ld_src % ch == 0 && ld_dst % ch == 0;
+    const int64_t T = fast ? 256 / esize : 64;                       // tile edge of the kernel that will run
+    const int64_t tiles_c = (cols + T - 1) / T, tiles_r = (rows + T - 1) / T;
+    if (tiles_c * tiles_r > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(tiles_c * tiles_r));
+    if (esize == 4) {
+        if (fast)
+            hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t *>(src),
+                               static_cast<uint32_t *>(dst), rows, cols, ld_src, 0, tiles_c, tiles_r, ld_dst);
+        else
+            hipLaunchKernelGGL(transpose_any_kernel<uint32_t>, grid, dim3(256), 0, s, static_cast<const uint32_t *>(src),
+                               static_cast<uint32_t *>(dst), rows, cols, ld_src, ld_dst, tiles_c);
+    } else {
+        if (fast)
+            hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(src),
+                               static_cast<uint16_t *>(dst), rows, cols, ld_src, 0, tiles_c, tiles_r, ld_dst);
+        else
+            hipLaunchKernelGGL(transpose_any_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(src),
+                               static_cast<uint16_t *>(dst), rows, cols, ld_src, ld_dst, tiles_c);
+    }
+    return hipGetLastError();
+}
 
 const Variant *transpose_variants()
 {

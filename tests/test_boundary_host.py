@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 19
+    assert len(names) == 20
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -211,3 +211,13 @@ def test_fused_cross_entropy_entry_point_validates_and_picks_its_kernel_on_the_h
     assert path(64, 64, 96, 0, 1) == 1 and path(64, 64, 0, 0, 1) == 1                     # K too short for the ring, K = 0
     assert path(64, 64, 128, 0, 1, A=P + 2) == 1                                           # misaligned A
     assert path(8, 64, 128, 0, 5) == ob.ERR_INVALID_ARG
+
+
+def test_transpose_entry_point_validates_on_the_host():
+    L = ob.lib()
+    bad = [(-1, 8, P, 8, P, 8, 4, None), (8, -1, P, 8, P, 8, 4, None), (8, 8, P, 7, P, 8, 4, None), (8, 8, P, 8, P, 7, 4, None),
+           (8, 8, P, 8, P, 8, 3, None), (8, 8, P, 8, P, 8, 8, None), (8, 8, None, 8, P, 8, 4, None), (8, 8, P, 8, None, 8, 2, None)]
+    for args in bad:
+        assert L.optiml_transpose(*args) == ob.ERR_INVALID_ARG, args
+    assert L.optiml_transpose(0, 8, None, 8, None, 0, 4, None) == ob.OK
+    assert L.optiml_transpose(8, 0, None, 0, None, 8, 2, None) == ob.OK

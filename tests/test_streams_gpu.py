@@ -161,3 +161,26 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     ref = np.float32(oracle.reduce(x, None, oracle.RED_SUM))
     assert abs(out.item() - float(ref)) <= float(np.spacing(np.abs(ref)))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+@pytest.mark.parametrize("rows,cols,pad_src,pad_dst", [(1, 1, 0, 0), (64, 64, 0, 0), (200, 136, 0, 0), (77, 131, 0, 0), (1000, 8, 8, 16),
+                                                      (5, 3000, 3, 1), (1, 4096, 0, 0), (4096, 1, 0, 0), (520, 1032, 8, 8),
+                                                      (2104, 4208, 0, 8)])
+def test_transpose_is_bit_exact(dtype, rows, cols, pad_src, pad_dst):
+    """Table 4 task 8: every element at its mirror position, bit for bit (16-bit patterns include NaNs), padding untouched;
+    aligned shapes take the vectorised kernel, the others the element-wise one."""
+    rng = np.random.default_rng(rows * 7 + cols)
+    if dtype == np.float32:
+        x = rng.standard_normal((rows, cols + pad_src)).astype(np.float32)
+        src = torch.from_numpy(x).cuda(); dst = torch.full((cols, rows + pad_dst), 777.0, dtype=torch.float32, device="cuda")
+    else:
+        x = rng.integers(0, 1 << 16, size=(rows, cols + pad_src), dtype=np.uint16)
+        src = torch.from_numpy(x.view(np.int16)).cuda(); dst = torch.full((cols, rows + pad_dst), 777, dtype=torch.int16, device="cuda")
+    ob.optiml_transpose(rows, cols, src, cols + pad_src, dst, rows + pad_dst, x.dtype.itemsize)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy().view(x.dtype)
+    want = oracle.transpose(np.ascontiguousarray(x[:, :cols]))
+    assert np.array_equal(got[:, :rows].view(np.uint8), want.view(np.uint8))
+    pad = got[:, rows:]
+    assert np.all(pad == (np.float32(777.0) if dtype == np.float32 else np.uint16(777)))
