@@ -60,6 +60,7 @@ SKINNY16_SRC = ('kernel_skinny16.hpp', 'kernel_skinny16.hip', 'epilogue.hpp')
 LCE_SRC = ('kernel_linear_ce.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 LCE_F32_SRC = ('kernel_linear_ce.hip', 'kernel_ring_f32.hpp', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
+TRANSPOSE_SRC = ("kernel_transpose.hip",)
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
@@ -85,6 +86,8 @@ TRAFFIC = {
         {"bytes": int((1049927.7 * 2.0 + 1049906.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
     ("s_ln_token", "s_ln_token"):
         {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+    ("s_transpose", "s_transpose"):
+        {"bytes": int((524327.0 * 2.0 + 1048890.0) * 1024), "files": TRANSPOSE_SRC, "src": "7550a1f1381dfe3e"},
     ("s_mhsa", "s_mhsa"):
         {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "0b50637145a1936e"},
     ("s_lce", "s_lce"):
