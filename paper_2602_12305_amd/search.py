@@ -71,6 +71,15 @@ def _skinny_exprs(p, layout):
             f"skinny::skinny_kernel<{t}, {il}>")
 
 
+def _skinny16_exprs(dt):
+    def exprs(p, layout):
+        t = f"{p['WN']}, {p['WK']}, {p['CG']}, {'true' if p['NT'] else 'false'}"
+        il = "true" if p["IL"] else "false"
+        return (f"skinny16::supports<{dt}>", f"skinny16::launch<{dt}, {t}, {p['SPLIT']}, {il}>",
+                f"skinny16::skinny16_kernel<{dt}, {t}, {il}>")
+    return exprs
+
+
 def _ringf_exprs(p, layout):
     c = f"ringf::Cfg<{p['BM']}, {p['NS']}, {'true' if layout & 1 else 'false'}>"
     return (f"ringf::supports<{c}>", f"ringf::launch<{c}>", f"ringf::gemm_ring_f32_kernel<{c}>")
@@ -89,6 +98,14 @@ FAMILIES = {
         {"WN": [1, 2, 4, 8], "WK": [1, 2, 4, 8, 16], "CG": [1, 2], "NT": [0, 1], "SPLIT": [0, 1, 2, 4, 8], "IL": [0, 1]},
         lambda p: p["WN"] * p["WK"] <= 16 and not (p["WN"] * p["WK"] > 8 and p["CG"] > 1),
         _skinny_exprs, {"WN": 1, "WK": 8, "CG": 2, "NT": 1, "SPLIT": 0, "IL": 1}),
+    # 16-bit streaming kernels: the cross-wave reduction buffer (WK x 16 rows x 128 CG WN columns of
+    # fp32) must fit 64 KiB of static LDS
+    "skinny16_bf16": Family(
+        "skinny16_bf16", "kernel_skinny16.hpp",
+        {"WN": [1, 2, 4, 8], "WK": [1, 2, 4, 8, 16], "CG": [1, 2], "NT": [0, 1], "SPLIT": [0, 1, 2, 4, 8], "IL": [0, 1]},
+        lambda p: p["WN"] * p["WK"] <= 16 and not (p["WN"] * p["WK"] > 8 and p["CG"] > 1)
+        and (p["WK"] == 1 or p["WK"] * p["CG"] * p["WN"] <= 8),
+        _skinny16_exprs("DT_BF16"), {"WN": 1, "WK": 4, "CG": 2, "NT": 1, "SPLIT": 0, "IL": 1}),
     "ring_f32": Family(
         "ring_f32", "kernel_ring_f32.hpp",
         {"BM": [128, 256], "NS": [3, 4, 5, 6]},
