@@ -20,7 +20,11 @@
  *              keeps no reference after the call's work has run, never frees or
  *              reallocates them.  C must not overlap A, B or bias (not checked).
  *   Units      lda, ldb, ldc and all strides are in ELEMENTS of the operand's type.
- *   Layouts    C is always row-major: C[i,j] at C[i*ldc + j], ldc >= N.
+ *   Layouts    C is row-major, C[i,j] at C[i*ldc + j], ldc >= N, unless the layout code has
+ *              OPTIML_LAYOUT_C_COLUMN_MAJOR added: then C[i,j] at C[j*ldc + i], ldc >= M,
+ *              and a batch's C spans (N-1)*ldc + M elements.  (Served as the transposed
+ *              problem C^T = B^T A^T with the bias running down the rows; the streaming
+ *              and persistent kernels do not take that form, the others do.)
  *              A row-major: A[i,k] at A[i*lda + k], lda >= K;
  *              A column-major: A[i,k] at A[k*lda + i], lda >= M.
  *              B row-major: B[k,j] at B[k*ldb + j], ldb >= N;
@@ -82,7 +86,8 @@ typedef enum {
     OPTIML_LAYOUT_RR = 0,
     OPTIML_LAYOUT_RC = 1,
     OPTIML_LAYOUT_CR = 2,
-    OPTIML_LAYOUT_CC = 3
+    OPTIML_LAYOUT_CC = 3,
+    OPTIML_LAYOUT_C_COLUMN_MAJOR = 4   /* added to any of the four: C[i,j] at C[j*ldc + i] */
 } optiml_layout_t;
 
 typedef enum {

@@ -14,6 +14,7 @@ import os
 F32, BF16, F16 = 0, 1, 2
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
+LAYOUT_C_COLUMN_MAJOR = 4        # added to any of the four
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "liboptiml.so")

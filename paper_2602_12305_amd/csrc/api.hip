@@ -56,6 +56,12 @@ int validate(const Problem &p)
     return OPTIML_OK;
 }
 
+// a variant can run p: its own shape / alignment test, and the row-wise bias if p carries one
+bool can_run(const Variant *v, const Problem &p)
+{
+    return (!(p.bias_row && p.bias) || v->row_bias) && v->supports(p);
+}
+
 bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 
 // The streaming kernels re-read B once per 16 rows of A.  For more than 16 rows that is worth it
@@ -103,18 +109,18 @@ int select(const Problem &p)
     if (p.K > 0 && vector_friendly(p)) {
         if (p.M <= 16)
             for (int i = t.first_skinny; i < t.first_tile; ++i)
-                if (t.v[i]->supports(p)) return i;
-        if (streaming_beats_tiles(p) && t.first_skinny + 1 < t.first_tile && t.v[t.first_skinny + 1]->supports(p))
+                if (can_run(t.v[i], p)) return i;
+        if (streaming_beats_tiles(p) && t.first_skinny + 1 < t.first_tile && can_run(t.v[t.first_skinny + 1], p))
             return t.first_skinny + 1;
         if (streaming16_beats_tiles(p))
             for (int i = t.first_skinny + kNumSkinnyVariants; i < t.first_tile; ++i)
-                if (t.v[i]->supports(p)) return i;
+                if (can_run(t.v[i], p)) return i;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i)
-            if (t.v[i]->prefers && t.v[i]->prefers(p) && t.v[i]->supports(p)) return i;
+            if (t.v[i]->prefers && t.v[i]->prefers(p) && can_run(t.v[i], p)) return i;
         int best = -1;
         int64_t best_blocks = -1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
-            if (!t.v[i]->supports(p)) continue;
+            if (!can_run(t.v[i], p)) continue;
             const int64_t blocks = ((p.M + t.v[i]->bm - 1) / t.v[i]->bm) * ((p.N + t.v[i]->bn - 1) / t.v[i]->bn) * p.batch;
             if (blocks >= kComputeUnits) return i;
             if (blocks > best_blocks) { best = i; best_blocks = blocks; }
@@ -122,7 +128,7 @@ int select(const Problem &p)
         if (best >= 0) return best;
     }
     for (int i = 0; i < t.first_skinny; ++i)
-        if (t.v[i]->supports(p)) return i;
+        if (can_run(t.v[i], p)) return i;
     return OPTIML_ERR_UNSUPPORTED;
 }
 
@@ -130,7 +136,7 @@ int run(const Problem &p, int variant_id, void *stream)
 {
     const Table &t = table();
     if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
-    if (!t.v[variant_id]->supports(p)) return OPTIML_ERR_UNSUPPORTED;
+    if (!can_run(t.v[variant_id], p)) return OPTIML_ERR_UNSUPPORTED;
     hipError_t e = t.v[variant_id]->launch(p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
         tls_last_hip_error = (int)e;
@@ -150,6 +156,16 @@ Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int6
     p.bias = bias; p.strideBias = strideBias;
     p.C = C; p.ldc = ldc; p.strideC = strideC;
     p.layout = layout; p.dtype = dtype; p.act = act;
+    if (layout >= 4 && layout <= 7) {
+        // Column-major C (bit 2): C^T = B^T . A^T is the same problem with a row-major result.
+        // B^T takes A's place - it is row-major exactly when B was column-major - and A^T takes
+        // B's; the bias, one value per column of C, runs down the rows of C^T.
+        p.M = N; p.N = M;
+        p.A = B; p.lda = ldb; p.strideA = strideB;
+        p.B = A; p.ldb = lda; p.strideB = strideA;
+        p.layout = ((layout & 1) ? 0 : 2) | ((layout & 2) ? 0 : 1);
+        p.bias_row = true;
+    }
     return p;
 }
 
@@ -273,7 +289,7 @@ int optiml_variant_supports(int variant_id, int64_t batch, int64_t M, int64_t N,
     if (st != OPTIML_OK) return st;
     const Table &t = table();
     if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
-    return t.v[variant_id]->supports(p) ? OPTIML_OK : OPTIML_ERR_UNSUPPORTED;
+    return can_run(t.v[variant_id], p) ? OPTIML_OK : OPTIML_ERR_UNSUPPORTED;
 }
 
 int optiml_gemm_epilogue_variant(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,

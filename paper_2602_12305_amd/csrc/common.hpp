@@ -18,6 +18,9 @@ struct Problem {
     void *C; int64_t ldc, strideC;
     int layout;   // bit 0: B column-major, bit 1: A column-major
     int dtype, act;
+    // the bias is indexed by the ROW of C instead of the column: how a column-major C is served
+    // (C^T = B^T A^T is a row-major problem whose bias runs down the rows)
+    bool bias_row = false;
     bool a_col() const { return (layout & 2) != 0; }
     bool b_col() const { return (layout & 1) != 0; }
     int esize() const { return dtype == DT_F32 ? 4 : 2; }
@@ -32,6 +35,7 @@ struct Variant {
     // optional: true for problems on which this variant was measured faster than the ones
     // before it in the table; the dispatcher asks these first
     bool (*prefers)(const Problem &) = nullptr;
+    bool row_bias = false;   // handles Problem::bias_row
 };
 
 // every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks

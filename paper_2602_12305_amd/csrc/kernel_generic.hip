@@ -78,12 +78,14 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
     for (int j = 0; j < 4; ++j) {
         const int64_t col = col0 + tx * 4 + j;
         if (col >= p.N) continue;
-        const float bj = p.bias ? p.bias[b * p.strideBias + col] : 0.0f;
+        const float bj = (p.bias && !p.bias_row) ? p.bias[b * p.strideBias + col] : 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t row = row0 + ty * 4 + i;
-            if (row < p.M)
-                put(&C[row * p.ldc + col], apply_act(acc[i][j] + bj, p.act));
+            if (row < p.M) {
+                const float bi = (p.bias && p.bias_row) ? p.bias[b * p.strideBias + row] : bj;
+                put(&C[row * p.ldc + col], apply_act(acc[i][j] + bi, p.act));
+            }
         }
     }
 }
@@ -118,7 +120,7 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
 const Variant *generic_variants()
 {
     static const Variant v[] = {{"generic_64x64", generic_supports, generic_launch, 0, 0,
-                                 reinterpret_cast<const void *>(&generic_kernel<float>)}};
+                                 reinterpret_cast<const void *>(&generic_kernel<float>), nullptr, true}};
     return v;
 }
 const int kNumGenericVariants = 1;

@@ -144,7 +144,7 @@ hipError_t launch_ring_lse(const Problem &p, const int *labels, float *part, flo
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = ACT_NONE;
-    q.labels = labels; q.picked = picked;
+    q.labels = labels; q.picked = picked; q.bias_row = 0;
     if constexpr (std::is_same<C, LseCfgF32Rr>::value || std::is_same<C, LseCfgF32Rc>::value) {
         hipLaunchKernelGGL(ringf::gemm_ring_f32_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
     } else {

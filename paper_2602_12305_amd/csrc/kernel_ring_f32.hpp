@@ -249,13 +249,13 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
 #pragma unroll
     for (int gq = 0; gq < 4; ++gq) {
         const int64_t n = nw + 8 * gq + 4 * half;
-        if (bias && n + 3 < p.N) {
+        if (bias && !(C::EPI == 0 && p.bias_row) && n + 3 < p.N) {
             const floatx4 v = *reinterpret_cast<const floatx4 *>(bias + n);
 #pragma unroll
             for (int e = 0; e < 4; ++e) bj[gq][e] = v[e];
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) bj[gq][e] = (bias && n + e < p.N) ? bias[n + e] : 0.0f;
+            for (int e = 0; e < 4; ++e) bj[gq][e] = (bias && !(C::EPI == 0 && p.bias_row) && n + e < p.N) ? bias[n + e] : 0.0f;
         }
     }
     if constexpr (C::EPI == 1) {
@@ -300,11 +300,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
     constexpr int ACT = decltype(act_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        // a bias that runs down the rows: this lane's row of the 32-row group
+        const int64_t mb = mw + 32 * i + frag_row;
+        const float bi = (bias && p.bias_row && mb < p.M) ? bias[mb] : 0.0f;
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             floatx4 y;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[i][4 * gq + e] + bj[gq][e], ACT);
+            for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[i][4 * gq + e] + (bj[gq][e] + bi), ACT);
             *reinterpret_cast<__attribute__((address_space(3))) floatx4 *>(
                 slab + frag_row * 128 + (((2 * gq + half) ^ wkey) << 4)) = y;
         }
@@ -356,7 +359,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = p.act;
-    q.labels = nullptr; q.picked = nullptr;
+    q.labels = nullptr; q.picked = nullptr; q.bias_row = p.bias_row ? 1 : 0;
     const int64_t total = q.tiles_m * q.tiles_n * p.batch;
     hipLaunchKernelGGL(gemm_ring_f32_kernel<C>, dim3((unsigned)total), dim3(C::THREADS), 0, stream, q);
     return hipGetLastError();

@@ -316,7 +316,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = p.act;
-    q.labels = nullptr; q.picked = nullptr;
+    q.labels = nullptr; q.picked = nullptr; q.bias_row = 0;
     const int64_t total = q.tiles_m * q.tiles_n * p.batch;
     const int64_t grid = total < cus ? total : cus;
     hipLaunchKernelGGL(gemm_ring_persistent_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS), 0, stream, q);

@@ -54,6 +54,7 @@ struct Params {
     char *C; int64_t ldc, strideC;
     int64_t tiles_m, tiles_n;
     int act;
+    int bias_row;        // bias[m] instead of bias[n]
 };
 
 template <int DT, int BM_, int BN_, int WM_, int WN_, bool A_KC_, bool B_KC_>
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
             if (n >= p.N) continue;
             const bool whole = n + 3 < p.N;
             float bj[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (bias) {
+            if (bias && !p.bias_row) {
                 if (whole) {
                     const floatx4 v = *reinterpret_cast<const floatx4 *>(bias + n);
                     bj[0] = v[0]; bj[1] = v[1]; bj[2] = v[2]; bj[3] = v[3];
@@ -356,9 +357,10 @@ __global__ __launch_bounds__(C::THREADS) void gemm_tile_kernel(Params p)
             for (int i = 0; i < TM; ++i) {
                 const int64_t m = mw + 32 * i + frag_row;
                 if (m >= p.M) continue;
+                const float bi = (bias && p.bias_row) ? bias[m] : 0.0f;
                 float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * g + e] + bj[e], ACT);
+                for (int e = 0; e < 4; ++e) y[e] = apply_act(acc[j][i][4 * g + e] + (bj[e] + bi), ACT);
                 char *dst = Cb + (m * p.ldc + n) * ES;
                 if constexpr (C::dt == DT_F32) {
                     if (whole) {
@@ -421,7 +423,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     q.M = p.M; q.N = p.N; q.K = p.K; q.batch = p.batch;
     q.A = static_cast<const char *>(p.A); q.lda = p.lda; q.strideA = p.strideA;
     q.B = static_cast<const char *>(p.B); q.ldb = p.ldb; q.strideB = p.strideB;
-    q.bias = p.bias; q.strideBias = p.strideBias;
+    q.bias = p.bias; q.strideBias = p.strideBias; q.bias_row = p.bias_row ? 1 : 0;
     q.C = static_cast<char *>(p.C); q.ldc = p.ldc; q.strideC = p.strideC;
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;

@@ -93,6 +93,7 @@ const Variant *ring_for(const Problem &q)
     const Variant *first = nullptr;
     for (int i = 0; i < kNumTileVariants; ++i) {
         if (t[i].name[0] != 'r' || !t[i].supports(q)) continue;        // "ring..." / "ringp..."
+        if (q.bias_row && q.bias && !t[i].row_bias) continue;
         if (t[i].prefers && t[i].prefers(q)) return &t[i];
         if (!first) first = &t[i];
     }
@@ -173,7 +174,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *transpose_variants()
 {
     static const Variant v[] = {{"xa_ring", xa_supports, xa_launch, 256, 256,
-                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), xa_prefers}};
+                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), xa_prefers, true}};
     return v;
 }
 const int kNumTransposeVariants = 1;

@@ -46,7 +46,9 @@ def run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, *, ldc=None, varia
             strideA=None, strideB=None, strideBias=None, entry="batched"):
     """As/Bs: storage arrays ([batch,] rows, ld).  Returns (Y fp64 [batch,M,N], pad region, device C)."""
     lda, ldb = As.shape[-1], Bs.shape[-1]
-    ldc = N if ldc is None else ldc
+    c_col = bool(layout & 4)                       # column-major C: storage [batch, N, ldc >= M]
+    crows, ccols = (N, M) if c_col else (M, N)
+    ldc = ccols if ldc is None else ldc
     if strideA is None:
         strideA = As.shape[-2] * lda if batch > 1 else 0
     if strideB is None:
@@ -54,8 +56,8 @@ def run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, *, ldc=None, varia
     if strideBias is None:
         strideBias = N if (bias is not None and batch > 1 and bias.size >= batch * N) else 0
     Ad, Bd, bd = to_dev(As), to_dev(Bs), to_dev(None if bias is None else np.ascontiguousarray(bias, dtype=np.float32))
-    Cd = alloc_c(batch, M, ldc, dtype)
-    strideC = M * ldc
+    Cd = alloc_c(batch, crows, ldc, dtype)
+    strideC = crows * ldc
     if variant is not None:
         binding.optiml_gemm_epilogue_variant(batch, M, N, K, Ad, lda, strideA, Bd, ldb, strideB, bd, strideBias,
                                              Cd, ldc, strideC, layout, dtype, act, variant)
@@ -69,7 +71,9 @@ def run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, *, ldc=None, varia
         binding.optiml_gemm_epilogue_strided_batched(batch, M, N, K, Ad, lda, strideA, Bd, ldb, strideB, bd,
                                                      strideBias, Cd, ldc, strideC, layout, dtype, act)
     torch.cuda.synchronize()
-    Y, pad = c_values(Cd, dtype, N)
+    Y, pad = c_values(Cd, dtype, ccols)
+    if c_col:
+        Y = np.ascontiguousarray(np.swapaxes(Y, -1, -2))
     return Y, pad, Cd
 
 
@@ -81,9 +85,9 @@ def check_against_oracle(A, B, bias, *, dtype, act, layout, pad=0, ldc_pad=0, va
     batch = A.shape[0] if A.ndim == 3 else 1
     M, K = A.shape[-2:]; N = B.shape[-1]
     As = store(A, dtype, (layout >> 1) & 1, pad); Bs = store(B, dtype, layout & 1, pad)
-    Y, padregion, _ = run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, ldc=N + ldc_pad,
+    Y, padregion, _ = run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, ldc=(M if layout & 4 else N) + ldc_pad,
                               variant=variant, entry=entry)
-    ref = oracle.gemm_epilogue(As, Bs, bias, M, N, K, dtype=dtype, act=act, layout=layout, batch=batch)
+    ref = oracle.gemm_epilogue(As, Bs, bias, M, N, K, dtype=dtype, act=act, layout=layout & 3, batch=batch)
     assert Y.shape == ref.shape
     if padregion.size:
         assert np.all(padregion == np.float32(POISON) if dtype == synth.DTYPE_F32 else

@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=4), dict(layout=-1), dict(dtype=3), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=3), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])
@@ -135,8 +135,8 @@ def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bi
     a_col, b_col = (layout >> 1) & 1, layout & 1
     lda = lda if lda is not None else (M if a_col else K)
     ldb = ldb if ldb is not None else (K if b_col else N)
-    ldc = ldc if ldc is not None else N
-    v = ob.optiml_select_variant(batch, M, N, K, A, lda, M * K, P, ldb, K * N, bias, N, P, ldc, M * ldc, layout, dtype, 0)
+    ldc = ldc if ldc is not None else (M if layout & 4 else N)
+    v = ob.optiml_select_variant(batch, M, N, K, A, lda, M * K, P, ldb, K * N, bias, N, P, ldc, M * N, layout, dtype, 0)
     return ob.optiml_variant_name(v) if v >= 0 else v
 
 
@@ -158,6 +158,12 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 64, 16384, 16384, dtype=1).startswith("skinny_bf16")                # four blocks of rows still beat one row of tiles
     assert not sel(1, 64, 32768, 4096, dtype=1).startswith("skinny")                 # ... but not with a short K
     assert not sel(1, 256, 16384, 16384, dtype=1).startswith("skinny")
+    # column-major C (layout + 4): the transposed problem, served by kernels that take a bias down the rows
+    assert sel(1, 8192, 8192, 8192, layout=4 + 1, dtype=1).startswith("ring_bf16_rc_256x256")   # B^T row-major, A^T column-major
+    assert sel(1, 8192, 8192, 8192, layout=4 + 0, dtype=1) == "xa_ring"                          # B^T column-major: copied
+    assert sel(1, 4096, 4096, 4096, layout=4 + 3).startswith("ring_f32_rr")
+    assert sel(32, 2048, 2048, 512, layout=4 + 1, dtype=1).startswith("ring_bf16_rc")            # not the persistent kernel
+    assert sel(1, 16, 16384, 16384, layout=4 + 3).startswith("ring_f32_rr") or sel(1, 16, 16384, 16384, layout=4 + 3).startswith("tile_")
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays
@@ -171,7 +177,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("tile_f32_rc")   # fine when k is contiguous
     assert sel(1, 16, 1024, 1022, lda=1024).startswith("generic")
     assert sel(1, 16, 1024, 1024, dtype=1).startswith("skinny_bf16")
-    assert sel(1, 8, 8, 8, layout=7) == ob.ERR_INVALID_ARG
+    assert sel(1, 8, 8, 8, layout=8) == ob.ERR_INVALID_ARG
 
 
 def test_variant_supports_is_host_only_and_consistent():

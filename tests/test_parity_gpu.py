@@ -409,3 +409,32 @@ def test_column_major_a_through_the_row_major_copy(dtype, layout):
     assert ob.optiml_variant_name(v) == "xa_ring"
     A = synth.uniform(920, "A", M, K); B = synth.uniform(920, "B", K, N); bias = synth.uniform(920, "bias", 1, N)[0]
     check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout, entry="ex")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+def test_column_major_c(dtype, layout):
+    """Layout + 4: C stored column-major (C[i,j] at C[j ldc + i]); the library runs the transposed problem with the
+    bias down the rows.  Aligned multi-tile shapes (ring / staged / copy paths), a batch with padded ldc, ragged and
+    unaligned shapes (fallback), integers exactly."""
+    for (M, N, K) in [(520, 264, 160), (264, 1032, 328)]:
+        A = synth.normal(950 + layout, "A", M, K); B = synth.normal(950 + layout, "B", K, N); bias = synth.normal(950, "bias", 1, N)[0]
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout + 4, entry="ex")
+    batch, M, N, K = 3, 136, 200, 96
+    A = synth.normal(960, "A", M, K, batch=batch); B = synth.normal(960, "B", K, N, batch=batch)
+    bias = synth.normal(960, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout + 4, ldc_pad=8)
+    Ai = synth.integers(961, "A", M, K, batch=batch); Bi = synth.integers(961, "B", K, N, batch=batch)
+    bi = synth.integers(961, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
+    check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_RELU, layout=layout + 4, exact=True)
+    A = synth.uniform(962, "A", 37, 29); B = synth.uniform(962, "B", 29, 53); bias = synth.uniform(962, "bias", 1, 53)[0]
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_NONE, layout=layout + 4, pad=1, ldc_pad=3)
+    check_against_oracle(A, B, None, dtype=dtype, act=synth.ACT_RELU, layout=layout + 4)
+
+
+def test_column_major_c_is_refused_by_kernels_without_a_row_bias():
+    A = synth.uniform(963, "A", 16, 256); B = synth.uniform(963, "B", 256, 512); bias = synth.uniform(963, "bias", 1, 512)[0]
+    vid = variant_ids("skinny_f32")[0]
+    with pytest.raises(ob.OptimlError) as e:
+        check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_NONE, layout=4 + 3, variant=vid)
+    assert e.value.status == ob.ERR_UNSUPPORTED
