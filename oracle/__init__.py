@@ -16,7 +16,7 @@ import numpy as np
 
 from .build import build as _build
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 EW_RELU, EW_SIGMOID = 0, 1
@@ -45,6 +45,8 @@ def lib():
         L.oracle_f16_from_double.argtypes = [C.c_double]
         L.oracle_f16_to_double.restype = C.c_double
         L.oracle_f16_to_double.argtypes = [C.c_uint16]
+        L.oracle_f8e4m3_to_double.restype = C.c_double
+        L.oracle_f8e4m3_to_double.argtypes = [C.c_uint8]
         L.oracle_num_threads.restype = C.c_int
         L.oracle_elementwise.restype = None
         L.oracle_elementwise.argtypes = [i64, vp, C.c_int, vp]
@@ -69,7 +71,7 @@ def _ptr(a):
 
 
 def _check_operand(x, dtype, what):
-    want = np.float32 if dtype == F32 else np.uint16
+    want = {F32: np.float32, F8E4M3: np.uint8}.get(dtype, np.uint16)
     if x.dtype != want or not x.flags.c_contiguous:
         raise TypeError(f"{what}: need C-contiguous {want.__name__} storage, got {x.dtype}")
 
@@ -149,6 +151,12 @@ def f16_from_double(y):
     """uint16 bit patterns of the IEEE binary16 nearest (ties to even) to each fp64 value."""
     f = lib().oracle_f16_from_double
     return np.vectorize(lambda v: f(float(v)), otypes=[np.uint16])(np.asarray(y, dtype=np.float64))
+
+
+def f8e4m3_to_double(bits):
+    """fp64 value of each OCP E4M3 bit pattern (uint8)."""
+    f = lib().oracle_f8e4m3_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(bits, dtype=np.uint8))
 
 
 def f16_to_double(bits):

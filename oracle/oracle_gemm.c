@@ -17,7 +17,7 @@
  * Bias, SiLU, GELU, bf16 storage and batching are not in the paper; they are
  * the standard definitions named by this repository's benchmark configuration.
  *
- * Arithmetic: the stored fp32 / bf16 / fp16 inputs are widened exactly to fp64; every
+ * Arithmetic: the stored fp32 / bf16 / fp16 / 8-bit E4M3 inputs are widened exactly to fp64; every
  * product of two of them is exact in fp64 (at most 48 significant bits); the
  * sum runs over k ascending in one fp64 accumulator starting from +0.0; the
  * bias is added after the sum; activations use fp64 libm.  The result is kept
@@ -38,7 +38,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3 };
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
 /* bit 0 of layout: B is column-major; bit 1: A is column-major */
 
@@ -57,12 +57,30 @@ double oracle_f16_to_double(uint16_t h)
     return sign ? -v : v;
 }
 
+/* OCP 8-bit floating point E4M3 (1 sign, 4 exponent bits with bias 7, 3 fraction bits; the "FN"
+ * variant: no infinities, the single NaN pattern S.1111.111, largest finite 448) to double,
+ * exactly: exponent field 0 is a subnormal f * 2^-9. */
+double oracle_f8e4m3_to_double(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 3) & 15, f = b & 7;
+    double v;
+    if (e == 15 && f == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)f, -9);
+    else
+        v = ldexp((double)(8 + f), e - 10);
+    return sign ? -v : v;
+}
+
 static double widen(const void *base, int64_t idx, int dtype)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
     if (dtype == ORACLE_F16)
         return oracle_f16_to_double(((const uint16_t *)base)[idx]);
+    if (dtype == ORACLE_F8E4M3)
+        return oracle_f8e4m3_to_double(((const uint8_t *)base)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -167,7 +185,7 @@ int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
                          int layout, int dtype, int act)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F8E4M3) || act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
     const int64_t rows = batch * M;
@@ -232,7 +250,7 @@ int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t
                                  int layout, int dtype, int act)
 {
     if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F8E4M3) || act < 0 || act > 3)
         return -1;
     for (int64_t t = 0; t < count; ++t)
         if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)

@@ -141,12 +141,41 @@ def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
 
 
+def f32_to_f8e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to OCP E4M3 (nearest, ties to even; magnitudes beyond 448 saturate to 448, NaN -> 0x7F); uint8."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.minimum(np.abs(np.nan_to_num(x.astype(np.float64), nan=0.0)), 448.0)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -20)))
+    e = np.maximum(e, -6.0)                              # below 2^-6 the spacing stays 2^-9 (subnormals)
+    q = np.exp2(e - 3.0)                                 # spacing: 3 fraction bits
+    r = np.rint(a / q) * q                               # numpy rounds half to even
+    r = np.minimum(r, 448.0)
+    ee = np.floor(np.log2(np.maximum(r, 2.0 ** -20)))
+    normal = r >= 2.0 ** -6
+    field = np.where(normal, ee + 7.0, 0.0)
+    frac = np.where(normal, r / np.exp2(ee) * 8.0 - 8.0, r * 512.0)
+    bits = (field.astype(np.int64) << 3 | frac.astype(np.int64)).astype(np.uint8)
+    bits = np.where(np.isnan(x), np.uint8(0x7F), bits)
+    return (bits | (np.signbit(x).astype(np.uint8) << 7)).astype(np.uint8)
+
+
+def f8e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    b = np.ascontiguousarray(b, dtype=np.uint8).astype(np.int64)
+    e, f = (b >> 3) & 15, b & 7
+    v = np.where(e == 0, f * 2.0 ** -9, (8 + f) * np.exp2(e - 10.0))
+    v = np.where((e == 15) & (f == 7), np.nan, v)
+    return np.where(b >> 7 == 1, -v, v).astype(np.float32)
+
+
 def to_bits(x, dtype):
-    """Storage of an fp32 array in the given dtype: fp32 itself, or the uint16 patterns of bf16 / fp16."""
+    """Storage of an fp32 array in the given dtype: fp32 itself, the uint16 patterns of bf16 / fp16, or the uint8
+    patterns of E4M3."""
     if dtype == DTYPE_BF16:
         return f32_to_bf16_bits(x)
     if dtype == DTYPE_F16:
         return f32_to_f16_bits(x)
+    if dtype == DTYPE_F8E4M3:
+        return f32_to_f8e4m3_bits(x)
     return np.ascontiguousarray(x, dtype=np.float32)
 
 
@@ -156,6 +185,8 @@ def from_bits(b, dtype):
         return bf16_bits_to_f32(b)
     if dtype == DTYPE_F16:
         return f16_bits_to_f32(b)
+    if dtype == DTYPE_F8E4M3:
+        return f8e4m3_bits_to_f32(b)
     return np.asarray(b, dtype=np.float32)
 
 
@@ -189,7 +220,7 @@ def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
 # ----------------------------------------------------------------------------------------------
 # The five workloads
 
-DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3 = 0, 1, 2, 3
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 

@@ -308,6 +308,37 @@ def test_f16_decode_and_rounding_agree_with_ieee_binary16():
         assert np.array_equal(oracle.f16_from_double(x), x.astype(np.float16).view(np.uint16))
 
 
+def test_f8e4m3_decode_and_the_generator_encoding_agree_with_the_ocp_format():
+    import torch
+    bits = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(bits.copy()).view(torch.float8_e4m3fn).float().numpy().astype(np.float64)   # an independent decoder
+    got = oracle.f8e4m3_to_double(bits)
+    nan = np.isnan(want)
+    assert list(np.flatnonzero(nan)) == [0x7F, 0xFF]
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # landmarks typed by hand: largest finite 448, smallest normal 2^-6, smallest subnormal 2^-9, one, -1.5
+    assert list(oracle.f8e4m3_to_double([0x7E, 0x08, 0x01, 0x38, 0xBC])) == [448.0, 2.0 ** -6, 2.0 ** -9, 1.0, -1.5]
+    # the input generator's own decoder and encoder (numpy, no code shared with the oracle)
+    assert np.array_equal(synth.f8e4m3_bits_to_f32(bits)[~nan].astype(np.float64), want[~nan])
+    assert np.array_equal(synth.f32_to_f8e4m3_bits(got[~nan].astype(np.float32)), bits[~nan])          # every value to itself
+    x = synth.normal(93, "x", 64, 1024, 0.0, 3.0)
+    enc = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(synth.f32_to_f8e4m3_bits(x), enc)                                           # in range: torch's rounding
+    mids = (got[:0x7E] + got[1:0x7F]) / 2                                                             # ties go to the even neighbour
+    assert np.array_equal(synth.f32_to_f8e4m3_bits(mids.astype(np.float32)), np.where(bits[:0x7E] % 2 == 0, bits[:0x7E], bits[1:0x7F]))
+    assert list(synth.f32_to_f8e4m3_bits(np.array([1e9, -1e9, 464.0, np.nan, -0.0], np.float32))) == [0x7E, 0xFE, 0x7E, 0x7F, 0x80]
+
+
+def test_f8e4m3_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
+    M, N, K = 7, 9, 33
+    A = synth.to_bits(synth.normal(94, "A", M, K), oracle.F8E4M3); B = synth.to_bits(synth.normal(94, "B", N, K), oracle.F8E4M3)
+    bias = synth.normal(94, "bias", 1, N)[0]
+    y = oracle.gemm_epilogue(A, B, bias, M, N, K, dtype=oracle.F8E4M3, layout=synth.LAYOUT_RC)[0]
+    ref = synth.f8e4m3_bits_to_f32(A).astype(np.float64) @ synth.f8e4m3_bits_to_f32(B).astype(np.float64).T + bias.astype(np.float64)
+    assert np.allclose(y, ref, rtol=0, atol=1e-13)
+
+
 def test_f16_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
     rng = np.random.default_rng(6)
     M, N, K = 7, 9, 33
