@@ -33,8 +33,11 @@
  *              OPTIML_F16: IEEE binary16 (16-bit storage either way); products are
  *              accumulated in fp32, bias is added and the activation applied in fp32,
  *              and C is rounded once, to nearest even (binary16: beyond 65504 to
- *              infinity).  bias is always float; NULL means no bias.  The
- *              contraction entry points take all three; the other entry points say
+ *              infinity).  OPTIML_F8E4M3: A and B are 8-bit OCP E4M3 (1 sign, 4 exponent
+ *              bits with bias 7, 3 fraction bits; no infinities, largest finite 448), one
+ *              byte per element, decoded exactly; C is bfloat16; no scale factors.
+ *              bias is always float; NULL means no bias.  The
+ *              contraction entry points take all four; the other entry points say
  *              which they take.
  *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
  *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
@@ -72,7 +75,7 @@
 extern "C" {
 #endif
 
-typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2 } optiml_dtype_t;
+typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3 } optiml_dtype_t;
 
 typedef enum {
     OPTIML_ACT_NONE = 0,
@@ -251,7 +254,7 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
  * The contraction feeding the cross-entropy (the paper's Table 4, task 2 into task 17), fused:
  *     *loss = (1/M) sum_i [ log sum_j exp(z[i][j]) - z[i][labels[i]] ],   z = A.B + bias
  * for M rows (samples) and N classes, with A, B, bias, layouts, leading dimensions and dtype
- * exactly as in optiml_gemm_epilogue_ex (no activation, no batch); labels are M 32-bit integers in
+ * exactly as in optiml_gemm_epilogue_ex (no activation, no batch, not OPTIML_F8E4M3); labels are M 32-bit integers in
  * [0, N), loss one float; all DEVICE pointers.  The logits are not written anywhere: products
  * are accumulated in fp32, each row's maximum and sum of exponentials are formed in fp32 from
  * the unrounded fp32 logits, the row losses and their mean in fp64 in a fixed order, rounded

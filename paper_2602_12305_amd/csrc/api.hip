@@ -35,7 +35,7 @@ const Table &table()
 
 bool enum_ok(int layout, int dtype, int act)
 {
-    return layout >= 0 && layout <= 3 && (dtype == DT_F32 || dtype == DT_BF16 || dtype == DT_F16) && act >= 0 && act <= 3;
+    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_F8 && act >= 0 && act <= 3;
 }
 
 // OPTIML_OK when the arguments describe a valid problem (possibly an empty one).
@@ -177,11 +177,11 @@ DeviceScratch g_scratch[64];
 
 bool vector_friendly(const Problem &p)
 {
-    const int64_t chunk = 16 / p.esize();
+    const int64_t chunk = 16 / p.esize(), cchunk = 16 / p.csize();
     auto aligned = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     if (!aligned(p.A) || !aligned(p.B) || !aligned(p.C)) return false;
-    if (p.lda % chunk || p.ldb % chunk || p.ldc % chunk) return false;
-    if (p.batch > 1 && (p.strideA % chunk || p.strideB % chunk || p.strideC % chunk)) return false;
+    if (p.lda % chunk || p.ldb % chunk || p.ldc % cchunk) return false;
+    if (p.batch > 1 && (p.strideA % chunk || p.strideB % chunk || p.strideC % cchunk)) return false;
     if (p.bias && (!aligned(p.bias) || (p.batch > 1 && p.strideBias % 4))) return false;
     return true;
 }
@@ -431,7 +431,7 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
 int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                               const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream)
 {
-    if (!enum_ok(layout, dtype, 0)) return OPTIML_ERR_INVALID_ARG;
+    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
     if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0 || !loss) return OPTIML_ERR_INVALID_ARG;
     Problem p{};
     p.batch = 1; p.M = M; p.N = N; p.K = K;
@@ -455,7 +455,8 @@ int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, in
 int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                                    const float *bias, int layout, int dtype)
 {
-    if (!enum_ok(layout, dtype, 0) || M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0) return OPTIML_ERR_INVALID_ARG;
+    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8 || M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0)
+        return OPTIML_ERR_INVALID_ARG;
     Problem p{};
     p.batch = 1; p.M = M; p.N = N; p.K = K;
     p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.bias = bias;

@@ -6,7 +6,7 @@
 
 namespace optiml {
 
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3 };   // DT_F8: A, B in OCP E4M3, C in bf16
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
 
 // C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.
@@ -23,7 +23,8 @@ struct Problem {
     bool bias_row = false;
     bool a_col() const { return (layout & 2) != 0; }
     bool b_col() const { return (layout & 1) != 0; }
-    int esize() const { return dtype == DT_F32 ? 4 : 2; }
+    int esize() const { return dtype == DT_F32 ? 4 : dtype == DT_F8 ? 1 : 2; }   // bytes per element of A and B
+    int csize() const { return dtype == DT_F32 ? 4 : 2; }                        // ... of C
 };
 
 struct Variant {

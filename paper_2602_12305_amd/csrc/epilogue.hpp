@@ -129,6 +129,17 @@ __device__ __forceinline__ float f16_to_f32(unsigned short b)
     return (float)__builtin_bit_cast(_Float16, b);
 }
 
+// OCP 8-bit E4M3 (bias 7, no infinities, NaN = S.1111.111, subnormals f * 2^-9) to fp32, exactly
+__device__ __forceinline__ float f8e4m3_to_f32(unsigned char b)
+{
+    const unsigned e = (b >> 3) & 15u, f = b & 7u;
+    float v;
+    if (e == 15u && f == 7u) v = __builtin_nanf("");
+    else if (e == 0u) v = (float)f * 0.001953125f;                                   // f * 2^-9
+    else v = __uint_as_float(((e + 120u) << 23) | (f << 20));                        // 1.f * 2^(e-7)
+    return (b & 0x80u) ? -v : v;
+}
+
 // The two 16-bit storage types share every kernel; these pick the conversions and the matrix
 // instruction (same shape, same register layout) by the dtype code.
 template <int DT> __device__ __forceinline__ unsigned int pack2_16(float lo, float hi)

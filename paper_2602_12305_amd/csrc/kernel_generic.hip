@@ -21,12 +21,14 @@ template <typename E> __device__ __forceinline__ float widen(E v);
 template <> __device__ __forceinline__ float widen<float>(float v) { return v; }
 template <> __device__ __forceinline__ float widen<unsigned short>(unsigned short v) { return bf16_to_f32(v); }
 template <> __device__ __forceinline__ float widen<_Float16>(_Float16 v) { return (float)v; }
+template <> __device__ __forceinline__ float widen<unsigned char>(unsigned char v) { return f8e4m3_to_f32(v); }
 
 __device__ __forceinline__ void put(float *p, float y) { *p = y; }
 __device__ __forceinline__ void put(unsigned short *p, float y) { *p = f32_to_bf16(y); }
 __device__ __forceinline__ void put(_Float16 *p, float y) { *p = (_Float16)y; }
 
-template <typename E>
+// E: storage type of A and B, CE: of C (the same, except 8-bit operands with a bf16 result)
+template <typename E, typename CE = E>
 __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_m, int64_t y0)
 {
     __shared__ float As[GK][PADDED];   // As[k][row]
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
         }
         __syncthreads();
     }
-    E *C = static_cast<E *>(p.C) + b * p.strideC;
+    CE *C = static_cast<CE *>(p.C) + b * p.strideC;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int64_t col = col0 + tx * 4 + j;
@@ -107,6 +109,8 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
             hipLaunchKernelGGL(generic_kernel<float>, grid, block, 0, s, p, blocks_m, y0);
         else if (p.dtype == DT_F16)
             hipLaunchKernelGGL(generic_kernel<_Float16>, grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_F8)
+            hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short>), grid, block, 0, s, p, blocks_m, y0);
         else
             hipLaunchKernelGGL(generic_kernel<unsigned short>, grid, block, 0, s, p, blocks_m, y0);
         hipError_t e = hipGetLastError();

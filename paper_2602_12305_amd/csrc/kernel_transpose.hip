@@ -102,7 +102,7 @@ const Variant *ring_for(const Problem &q)
 
 bool xa_supports(const Problem &p)
 {
-    if (!p.a_col() || p.K < 1 || !vector_friendly(p)) return false;
+    if (!p.a_col() || p.K < 1 || p.dtype == DT_F8 || !vector_friendly(p)) return false;
     const int ch = 16 / p.esize();
     if (p.M % ch != 0 || p.K % ch != 0) return false;
     const int64_t T = 256 / p.esize();

@@ -10,7 +10,12 @@ from helpers import e1, store
 
 # binary16: one rounding of the output, half a step = 2^-12 .. 2^-11 relative across a binade (4.9e-4 at most),
 # plus fp32 accumulation: bar 1e-3
-TOL = {synth.DTYPE_F32: 1e-5, synth.DTYPE_BF16: 2e-2, synth.DTYPE_F16: 1e-3}
+TOL = {synth.DTYPE_F32: 1e-5, synth.DTYPE_BF16: 2e-2, synth.DTYPE_F16: 1e-3, synth.DTYPE_F8E4M3: 2e-2}     # E4M3 operands: bf16 result
+
+
+def c_dtype(dtype):
+    """Storage type of C for a contraction dtype (8-bit operands give a bf16 result)."""
+    return synth.DTYPE_BF16 if dtype == synth.DTYPE_F8E4M3 else dtype
 POISON = 12345.0
 
 
@@ -29,6 +34,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 def alloc_c(batch, M, ldc, dtype, fill=POISON):
     """C storage [batch, M, ldc], pre-filled so that untouched entries (padding) can be checked."""
+    dtype = c_dtype(dtype)
     if dtype == synth.DTYPE_F32:
         return torch.full((batch, M, ldc), fill, dtype=torch.float32, device="cuda")
     bits = int(synth.to_bits(np.array([fill], dtype=np.float32), dtype)[0])
@@ -38,7 +44,7 @@ def alloc_c(batch, M, ldc, dtype, fill=POISON):
 def c_values(Cd, dtype, N):
     """Device C storage -> (fp64 values [batch, M, N], padding region as fp32)."""
     h = to_host(Cd)
-    f = synth.from_bits(h, dtype)
+    f = synth.from_bits(h, c_dtype(dtype))
     return f[..., :N].astype(np.float64), f[..., N:]
 
 
@@ -91,9 +97,9 @@ def check_against_oracle(A, B, bias, *, dtype, act, layout, pad=0, ldc_pad=0, va
     assert Y.shape == ref.shape
     if padregion.size:
         assert np.all(padregion == np.float32(POISON) if dtype == synth.DTYPE_F32 else
-                      np.all(synth.to_bits(padregion, dtype) == synth.to_bits(np.array([POISON], dtype=np.float32), dtype)[0]))
+                      np.all(synth.to_bits(padregion, c_dtype(dtype)) == synth.to_bits(np.array([POISON], dtype=np.float32), c_dtype(dtype))[0]))
     if exact:
-        if dtype == synth.DTYPE_BF16:
+        if c_dtype(dtype) == synth.DTYPE_BF16:
             want = synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64)
         elif dtype == synth.DTYPE_F16:
             want = oracle.f16_to_double(oracle.f16_from_double(ref))

@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=3), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=4), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])

@@ -19,8 +19,8 @@ from helpers import e1, store
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16, F16 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16
-DT_OF = {"f32": F32, "bf16": BF16, "f16": F16}
+F32, BF16, F16, F8 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3
+DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8}
 ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
 LAYOUT_OF = {"rr": 0, "rc": 1, "cr": 2, "cc": 3}
 
@@ -438,3 +438,33 @@ def test_column_major_c_is_refused_by_kernels_without_a_row_bias():
     with pytest.raises(ob.OptimlError) as e:
         check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_NONE, layout=4 + 3, variant=vid)
     assert e.value.status == ob.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("t,M,N,K,layout,dtype,act,pad,use_bias", [c for c in fuzz_cases() if c[0] % 2 == 1])
+def test_dispatch_random_shapes_in_e4m3(t, M, N, K, layout, dtype, act, pad, use_bias):
+    A = synth.uniform(470 + t, "A", M, K, -4.0, 4.0); B = synth.uniform(470 + t, "B", K, N)
+    bias = synth.uniform(470 + t, "bias", 1, N)[0] if use_bias else None
+    check_against_oracle(A, B, bias, dtype=F8, act=act, layout=layout, pad=pad, ldc_pad=pad)
+
+
+@pytest.mark.parametrize("layout", [0, 1, 2, 3, 5])
+def test_e4m3_storage_multi_tile_shapes_and_specials(layout):
+    """8-bit E4M3 operands, bf16 result: several tiles with a batch, exact on integers, and every one of the 256 bit
+    patterns (subnormals, +-448, the two NaN patterns) decoded as the format says."""
+    batch, M, N, K = 2, 264, 520, 192
+    A = synth.normal(975, "A", M, K, batch=batch); B = synth.normal(975, "B", K, N, batch=batch)
+    bias = synth.normal(975, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout)
+    Ai = synth.integers(976, "A", M, K, batch=batch); Bi = synth.integers(976, "B", K, N, batch=batch)
+    check_against_oracle(Ai, Bi, None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True)
+    if layout == 1:
+        # row i of A holds pattern i in column 0 (other columns zero), B is the identity's first row scaled by 1:
+        # C[i, 0] = value of pattern i; NaN patterns give NaN
+        pats = np.arange(256, dtype=np.uint8)
+        As = np.zeros((256, 16), dtype=np.uint8); As[:, 0] = pats
+        Bs = np.zeros((8, 16), dtype=np.uint8); Bs[0, 0] = 0x38                       # 1.0
+        Y, _, _ = run_gpu(As, Bs, None, 1, 256, 8, 16, F8, synth.ACT_NONE, 1)
+        want = oracle.f8e4m3_to_double(pats)
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(Y[0, :, 0]), nan)
+        assert np.array_equal(Y[0, ~nan, 0], want[~nan])                              # every E4M3 value is exact in bf16
