@@ -28,11 +28,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6}          # fp32, bf16, fp16 MFMA (dense)
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2}          # fp32, bf16, fp16, fp8 MFMA (dense)
 # which roof bounds each workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
-         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm"}
-DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}
+         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma"}
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3"}
 # streaming siblings: (entry point, op, arrays read, arrays written)
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
            "s_dot": ("red", 1, 2, 0), "s_mse": ("red", 2, 2, 0), "s_transpose": ("tr", 0, 1, 1)}
@@ -506,7 +506,7 @@ def main():
             got = sets[(args.steps - 1) & 1][3].cpu().numpy()
             idx = (sb, si, sj)
         if w.dtype != 0:
-            got = synth.from_bits(got.view(np.uint16), w.dtype)
+            got = synth.from_bits(got.view(np.uint16), 1 if w.dtype == 3 else w.dtype)      # E4M3 operands: bf16 result
         got = got.astype(np.float64)
         if idx is not None:
             got = got[idx]

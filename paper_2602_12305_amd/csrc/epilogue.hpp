@@ -144,7 +144,7 @@ __device__ __forceinline__ float f8e4m3_to_f32(unsigned char b)
 // instruction (same shape, same register layout) by the dtype code.
 template <int DT> __device__ __forceinline__ unsigned int pack2_16(float lo, float hi)
 {
-    return DT == DT_F16 ? f32x2_to_f16x2(lo, hi) : f32x2_to_bf16x2(lo, hi);
+    return DT == DT_F16 ? f32x2_to_f16x2(lo, hi) : f32x2_to_bf16x2(lo, hi);      // DT_F8 stores bf16
 }
 template <int DT> __device__ __forceinline__ unsigned short to_16(float f)
 {
@@ -159,7 +159,15 @@ template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32
     typedef __bf16 bf16x8_ __attribute__((ext_vector_type(8)));
     typedef _Float16 halfx8_ __attribute__((ext_vector_type(8)));
 #if defined(__HIP_DEVICE_COMPILE__)
-    if constexpr (DT == DT_F16)
+    if constexpr (DT == DT_F8) {
+        // 16 bytes per lane = 16 E4M3 values of k: two instructions of 8 each.  Which k a lane's
+        // byte stands for only has to agree between the two operands, and it does: both come from
+        // the same chunk and byte of their rows.
+        typedef long longx2_ __attribute__((ext_vector_type(2)));
+        const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
+    } else if constexpr (DT == DT_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8_, a), __builtin_bit_cast(halfx8_, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_, a), __builtin_bit_cast(bf16x8_, b), c, 0, 0, 0);

@@ -64,6 +64,13 @@ struct Cfg {
     // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the
     // cross-entropy over the N columns without the logits ever reaching memory.
     static constexpr int EPI = EPI_;
+    // DT_F8: A and B in 8-bit E4M3 (column-major B only), C in bf16.  The tile geometry is in
+    // bytes, so a k-tile is 64 elements instead of 32 and each 16-byte fragment feeds two matrix
+    // instructions.
+    static constexpr int ES = DT_ == DT_F8 ? 1 : 2;          // bytes per element of A and B
+    static constexpr int BKE = 64 / ES;                      // k elements per tile
+    static constexpr int ODT = DT_ == DT_F8 ? DT_BF16 : DT_; // storage type of C
+    static_assert(DT_ != DT_F8 || B_KC_, "8-bit operands: k must be contiguous in both");
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
     static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier
@@ -273,8 +280,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     const int64_t tile_m = first + t % rows_in_band, tile_n = t / rows_in_band;
     const int64_t m0 = tile_m * C::BM, n0 = tile_n * C::BN;
 
-    const char *A = p.A + batch * p.strideA * 2;
-    const char *B = p.B + batch * p.strideB * 2;
+    const char *A = p.A + batch * p.strideA * C::ES;
+    const char *B = p.B + batch * p.strideB * C::ES;
 
     Ctx<C> ctx;
     ctx.wave = wave;
@@ -285,7 +292,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
         const int c = (lane & 3) ^ ((r >> 2) & 3);
         int64_t row = m0 + r;
         row = row < p.M ? row : p.M - 1;
-        ctx.a_off[i] = (uint32_t)(row * p.lda * 2 + c * 16);
+        ctx.a_off[i] = (uint32_t)(row * p.lda * C::ES + c * 16);
     }
 #pragma unroll
     for (int i = 0; i < C::B_INSTR; ++i) {
@@ -295,7 +302,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             const int c = (lane & 3) ^ ((r >> 2) & 3);
             int64_t row = n0 + r;
             row = row < p.N ? row : p.N - 1;
-            ctx.b_off[i] = (uint32_t)(row * p.ldb * 2 + c * 16);
+            ctx.b_off[i] = (uint32_t)(row * p.ldb * C::ES + c * 16);
         } else {
             const int pidx = q * 64 + lane, k = pidx >> 5;          // 32 chunks per k-row
             const int c = (pidx & 31) ^ (4 * (k & 3));
@@ -330,7 +337,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     }
 
     lds_char *stage[5] = {(lds_char *)st0, (lds_char *)st1, (lds_char *)st2, (lds_char *)st3, (lds_char *)st4};
-    const int64_t nk = p.K / 32, last = nk - 1;            // nk >= NS - 1
+    const int64_t nk = p.K / C::BKE, last = nk - 1;        // nk >= NS - 1
     auto ga = [&](int64_t kt) { return A + (kt < last ? kt : last) * 64; };
     auto gb = [&](int64_t kt) { return B + (kt < last ? kt : last) * b_step; };
 
@@ -444,7 +451,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
                 for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + (bj[j][gq][e] + bi), ACT);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (((4 * j + gq) ^ wkey) << 4) + 8 * half) =
-                    uintx2{pack2_16<C::DT>(y[0], y[1]), pack2_16<C::DT>(y[2], y[3])};
+                    uintx2{pack2_16<C::ODT>(y[0], y[1]), pack2_16<C::ODT>(y[2], y[3])};
             }
 #pragma unroll
         for (int q = 0; q < READS; ++q) {
@@ -473,9 +480,9 @@ template <class C>
 bool supports(const Problem &p)
 {
     if (p.dtype != C::DT || p.a_col() || p.b_col() != C::B_KC) return false;
-    if (p.K < 32 * C::NS || p.K % 32 != 0 || !vector_friendly(p)) return false;
+    if (p.K < C::BKE * C::NS || p.K % C::BKE != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 8 != 0)) return false;
-    const int64_t a_span = p.M * p.lda * 2, b_span = (C::B_KC ? p.N : 32) * p.ldb * 2 + p.N * 2;
+    const int64_t a_span = p.M * p.lda * C::ES, b_span = (C::B_KC ? p.N : 32) * p.ldb * C::ES + p.N * C::ES;
     if (a_span >= (int64_t(1) << 31) || b_span >= (int64_t(1) << 31)) return false;
     const int64_t tiles = ((p.M + C::BM - 1) / C::BM) * ((p.N + C::BN - 1) / C::BN);
     if (tiles <= 0 || p.batch > 0x7fffffffLL / tiles) return false;

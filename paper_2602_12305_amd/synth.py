@@ -251,8 +251,9 @@ class Workload:
     @property
     def algorithmic_bytes(self):
         """One read of A, B and bias, one write of C."""
-        es = 4 if self.dtype == DTYPE_F32 else 2
-        per = (self.M * self.K + self.K * self.N + self.M * self.N) * es + 4 * self.N
+        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1}.get(self.dtype, 2)      # A and B
+        cs = 4 if self.dtype == DTYPE_F32 else 2                      # C
+        per = (self.M * self.K + self.K * self.N) * es + self.M * self.N * cs + 4 * self.N
         return self.batch * per
 
 
@@ -264,7 +265,7 @@ def _store(x, dtype, transpose=False):
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
-BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu")     # further dtypes on the same shapes
+BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu")     # further dtypes on the same shapes
 
 
 def make_workload(name: str, scale: int = 1) -> Workload:
@@ -304,6 +305,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
                         _store(normal(1, "A", M, K, 0.0, sd), DTYPE_BF16),
                         _store(normal(1, "B", K, N, 0.0, sd), DTYPE_BF16),
                         uniform(1, "bias", 1, N, -0.1, 0.1))
+    if name == "c4_f8_8192_rc_silu":           # config 4's shape in 8-bit E4M3 operands (bf16 result), B column-major
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_F8E4M3, ACT_SILU, LAYOUT_RC, 3,
+                        _store(normal(3, "A", M, K), DTYPE_F8E4M3),
+                        _store(normal(3, "B", K, N), DTYPE_F8E4M3, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c4_f16_8192_silu":             # config 4's shape and distributions in binary16 storage
         M = N = K = 8192 // s
         return Workload(name, 1, M, N, K, DTYPE_F16, ACT_SILU, LAYOUT_RR, 3,

@@ -44,7 +44,7 @@ def problem_for(name):
             # two whole summation blocks, one partial block, and a tail shorter than the ring
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
-        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, 32 * (4 * ns - 1)   # tile count not a multiple of the ring depth
+        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, (64 if dt == "f8" else 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("xa_"):
         return BF16, 2, 304, 392, 480                      # A column-major, M and K whole 16-byte chunks
     if name.startswith("direct"):
@@ -445,6 +445,19 @@ def test_dispatch_random_shapes_in_e4m3(t, M, N, K, layout, dtype, act, pad, use
     A = synth.uniform(470 + t, "A", M, K, -4.0, 4.0); B = synth.uniform(470 + t, "B", K, N)
     bias = synth.uniform(470 + t, "bias", 1, N)[0] if use_bias else None
     check_against_oracle(A, B, bias, dtype=F8, act=act, layout=layout, pad=pad, ldc_pad=pad)
+
+
+def test_e4m3_matrix_pipe_kernel_is_the_dispatchers_choice_and_sees_every_k():
+    """A row-major, B column-major, K a multiple of 64: the ring kernel.  One-hot rows of A pick single k positions,
+    so a fragment byte fed to the wrong k slot of the matrix instruction cannot hide."""
+    M, N, K = 256, 256, 256
+    v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, K, 0, 0x1000, 0, 0x1000, N, 0, 1, F8, 0)
+    assert ob.optiml_variant_name(v).startswith("ring_f8_rc")
+    A = np.zeros((M, K), dtype=np.float32); A[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
+    B = synth.integers(977, "B", K, N, -8, 8)
+    check_against_oracle(A, B, None, dtype=F8, act=synth.ACT_NONE, layout=1, exact=True, entry="ex")
+    A = synth.normal(978, "A", 520, 1024); B = synth.normal(978, "B", 1024, 776); bias = synth.normal(978, "bias", 1, 776)[0]
+    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_GELU_TANH, layout=1, entry="ex")
 
 
 @pytest.mark.parametrize("layout", [0, 1, 2, 3, 5])
