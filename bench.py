@@ -61,6 +61,7 @@ LCE_SRC = ('kernel_linear_ce.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 LCE_F32_SRC = ('kernel_linear_ce.hip', 'kernel_ring_f32.hpp', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
 TRANSPOSE_SRC = ("kernel_transpose.hip",)
+RING_F8_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f8_rc.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
@@ -86,6 +87,8 @@ TRAFFIC = {
         {"bytes": int((1049927.7 * 2.0 + 1049906.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
     ("s_ln_token", "s_ln_token"):
         {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+    ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
+        {"bytes": int((393506.0 * 2.0 + 131209.0) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
     ("s_transpose", "s_transpose"):
         {"bytes": int((524327.0 * 2.0 + 1048890.0) * 1024), "files": TRANSPOSE_SRC, "src": "7550a1f1381dfe3e"},
     ("s_mhsa", "s_mhsa"):

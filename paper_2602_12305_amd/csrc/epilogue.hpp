@@ -85,6 +85,20 @@ __device__ __forceinline__ void dispatch_act(int act, F &&f)
     }
 }
 
+// One 32x32x64 matrix instruction on E4M3 operands given as two 16-byte halves each (the scale
+// operands of the builtin are zero: the unscaled instruction)
+template <class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x64_f8(V4 a_lo, V4 a_hi, V4 b_lo, V4 b_hi, ACC c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef int intx8_ __attribute__((ext_vector_type(8)));
+    const intx8_ a = intx8_{(int)a_lo[0], (int)a_lo[1], (int)a_lo[2], (int)a_lo[3], (int)a_hi[0], (int)a_hi[1], (int)a_hi[2], (int)a_hi[3]};
+    const intx8_ b = intx8_{(int)b_lo[0], (int)b_lo[1], (int)b_lo[2], (int)b_lo[3], (int)b_hi[0], (int)b_hi[1], (int)b_hi[2], (int)b_hi[3]};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+#else
+    return c;
+#endif
+}
+
 // fp32 -> bf16 bits, round to nearest even; NaN stays a (quiet) NaN
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
 {

@@ -57,8 +57,12 @@ struct Params {
     int bias_row;        // EPI == 0: bias[m] instead of bias[n]
 };
 
-template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0>
+template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0, bool K64_ = false>
 struct Cfg {
+    // 8-bit operands only: one v_mfma_f32_32x32x64_f8f6f4 per k-tile and pair of fragments instead
+    // of four v_mfma_f32_32x32x16_fp8_fp8
+    static constexpr bool K64 = K64_;
+    static_assert(!K64_ || (DT_ == DT_F8 && !PF_), "the 64-deep instruction: 8-bit operands, no fragment prefetch");
     static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
     // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 64 columns of A.B + bias
     // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the
@@ -241,8 +245,18 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
     {
         load_frags<C>(c, rd, 0, f0);
         load_frags<C>(c, rd, 1, f1);
-        mma_frags<C>(f0, acc);
-        mma_frags<C>(f1, acc);
+        if constexpr (C::K64) {
+            // both 16-byte fragments of a row are one 32-byte operand: 64 values of k (which value
+            // sits in which byte only has to agree between the two operands)
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i)
+                    acc[j][i] = mfma_32x32x64_f8(f0.b[j], f1.b[j], f0.a[i], f1.a[i], acc[j][i]);
+        } else {
+            mma_frags<C>(f0, acc);
+            mma_frags<C>(f1, acc);
+        }
     }
 }
 #endif
