@@ -138,6 +138,68 @@ hipError_t xa_launch(const Problem &p, hipStream_t s)
     return ring->launch(q, s);
 }
 
+// ---- 8-bit operands: the matrix-pipe kernel wants k contiguous in BOTH operands -----------------
+// Whichever operand has k as its slow direction (A column-major: stored [K][M]; B row-major:
+// stored [K][N]) is copied into the workspace with k contiguous, then the E4M3 ring kernel runs on
+// the copies as an A-row-major, B-column-major problem.
+
+template <typename E>
+hipError_t copy_transposed(const void *src, void *dst, int64_t batch, int64_t rows, int64_t cols, int64_t ld, int64_t stride,
+                           hipStream_t s)
+{
+    const int64_t T = 256 / (int64_t)sizeof(E);
+    const int64_t tiles_c = (cols + T - 1) / T, tiles_r = (rows + T - 1) / T;
+    if (batch * tiles_c * tiles_r > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_kernel<E>, dim3((unsigned)(batch * tiles_c * tiles_r)), dim3(256), 0, s,
+                       static_cast<const E *>(src), static_cast<E *>(dst), rows, cols, ld, stride, tiles_c, tiles_r, rows);
+    return hipGetLastError();
+}
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+Problem with_k_contiguous(const Problem &p, const void *a, const void *b)
+{
+    Problem q = p;
+    if (p.a_col()) { q.A = a; q.lda = p.K; q.strideA = p.M * p.K; }
+    if (!p.b_col()) { q.B = b; q.ldb = p.K; q.strideB = p.N * p.K; }
+    q.layout = 1;
+    return q;
+}
+
+bool x8_supports(const Problem &p)
+{
+    if (p.dtype != DT_F8 || (!p.a_col() && p.b_col()) || p.K < 1 || !vector_friendly(p)) return false;
+    if (p.K % 16 != 0 || (p.a_col() && p.M % 16 != 0) || (!p.b_col() && p.N % 16 != 0)) return false;
+    if (p.batch * ((p.M + 255) / 256 + (p.N + 255) / 256) * ((p.K + 255) / 256) > 0x7fffffffLL) return false;
+    const void *fake = reinterpret_cast<const void *>(uintptr_t(256));
+    return ring_for(with_k_contiguous(p, fake, fake)) != nullptr;
+}
+
+// the alternative is the element-wise fallback: worth it as soon as there is a tile's worth of work
+bool x8_prefers(const Problem &p) { return p.M * p.N >= 65536 && p.K >= 256; }
+
+hipError_t x8_launch(const Problem &p, hipStream_t s)
+{
+    const size_t a_bytes = p.a_col() ? align256((size_t)p.batch * p.M * p.K) : 0;
+    const size_t b_bytes = !p.b_col() ? align256((size_t)p.batch * p.N * p.K) : 0;
+    void *ws = nullptr;
+    hipError_t e = workspace(a_bytes + b_bytes, &ws);
+    if (e != hipSuccess) return e;
+    void *wa = ws, *wb = static_cast<char *>(ws) + a_bytes;
+    const Problem q = with_k_contiguous(p, wa, wb);
+    const Variant *ring = ring_for(q);
+    if (!ring) return hipErrorInvalidValue;
+    if (p.a_col()) {
+        e = copy_transposed<uint8_t>(p.A, wa, p.batch, p.K, p.M, p.lda, p.strideA, s);
+        if (e != hipSuccess) return e;
+    }
+    if (!p.b_col()) {
+        e = copy_transposed<uint8_t>(p.B, wb, p.batch, p.K, p.N, p.ldb, p.strideB, s);
+        if (e != hipSuccess) return e;
+    }
+    return ring->launch(q, s);
+}
+
 }  // namespace
 
 // Table 4 task 8 as an operation of its own: dst (cols x rows, pitch ld_dst) = transpose of src
@@ -174,9 +236,11 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *transpose_variants()
 {
     static const Variant v[] = {{"xa_ring", xa_supports, xa_launch, 256, 256,
-                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), xa_prefers, true}};
+                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), xa_prefers, true},
+                                {"xk_ring_f8", x8_supports, x8_launch, 256, 256,
+                                 reinterpret_cast<const void *>(&transpose_kernel<uint8_t>), x8_prefers, true}};
     return v;
 }
-const int kNumTransposeVariants = 1;
+const int kNumTransposeVariants = 2;
 
 }  // namespace optiml

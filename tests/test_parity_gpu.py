@@ -45,6 +45,8 @@ def problem_for(name):
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
         return DT_OF[dt], LAYOUT_OF[lay], 300, 392, (64 if dt == "f8" else 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
+    if name.startswith("xk_"):
+        return F8, 0, 304, 400, 448                        # 8-bit operands, B row-major: copied with k contiguous
     if name.startswith("xa_"):
         return BF16, 2, 304, 392, 480                      # A column-major, M and K whole 16-byte chunks
     if name.startswith("direct"):
@@ -481,3 +483,24 @@ def test_e4m3_storage_multi_tile_shapes_and_specials(layout):
         nan = np.isnan(want)
         assert np.array_equal(np.isnan(Y[0, :, 0]), nan)
         assert np.array_equal(Y[0, ~nan, 0], want[~nan])                              # every E4M3 value is exact in bf16
+
+
+@pytest.mark.parametrize("layout", [0, 2, 3, 4, 6])
+def test_e4m3_operands_copied_with_k_contiguous(layout):
+    """8-bit operands whose k is not contiguous (A column-major and / or B row-major, also under a column-major C):
+    copied into the workspace, then the matrix-pipe kernel.  The dispatcher's own choice, a batch, one-hot rows."""
+    M, N, K = 528, 784, 448
+    a_col, b_col = (layout >> 1) & 1, layout & 1
+    if layout & 4:
+        a_col, b_col = 1 - b_col, 1 - a_col               # what the transposed problem looks like
+    v = ob.optiml_select_variant(1, M, N, K, 0x1000, M if layout & 2 else K, 0, 0x1000, K if layout & 1 else N, 0, 0x1000, 0,
+                                 0x1000, M if layout & 4 else N, 0, layout, F8, 0)
+    assert ob.optiml_variant_name(v) == ("ring_f8_rc_256x256_w2x4_ns5_k64" if (not a_col and b_col) else "xk_ring_f8")
+    A = synth.normal(980 + layout, "A", M, K); B = synth.normal(980 + layout, "B", K, N); bias = synth.normal(980, "bias", 1, N)[0]
+    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout, entry="ex")
+    batch = 3
+    Ai = synth.integers(981, "A", M, K, batch=batch); Bi = synth.integers(981, "B", K, N, batch=batch)
+    bi = synth.integers(981, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
+    check_against_oracle(Ai, Bi, bi, dtype=F8, act=synth.ACT_RELU, layout=layout, exact=True)
+    A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
+    check_against_oracle(A1, synth.integers(982, "B", K, N, -8, 8), None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True, entry="ex")
