@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2}          # fp32, bf16, fp16, fp8 MFMA (dense)
 # which roof bounds each workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
-         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma"}
+         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma"}
 DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3"}
 # streaming siblings: (entry point, op, arrays read, arrays written)
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),

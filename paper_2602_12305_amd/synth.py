@@ -265,7 +265,7 @@ def _store(x, dtype, transpose=False):
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
-BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu")     # further dtypes on the same shapes
+BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu")     # further dtypes on the same shapes
 
 
 def make_workload(name: str, scale: int = 1) -> Workload:
@@ -310,6 +310,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
         return Workload(name, 1, M, N, K, DTYPE_F8E4M3, ACT_SILU, LAYOUT_RC, 3,
                         _store(normal(3, "A", M, K), DTYPE_F8E4M3),
                         _store(normal(3, "B", K, N), DTYPE_F8E4M3, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c4_bf16_8192_cr_silu":         # config 4 with A stored column-major ([K][M])
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_CR, 3,
+                        _store(normal(3, "A", M, K), DTYPE_BF16, transpose=True),
+                        _store(normal(3, "B", K, N), DTYPE_BF16),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c4_f16_8192_silu":             # config 4's shape and distributions in binary16 storage
         M = N = K = 8192 // s
