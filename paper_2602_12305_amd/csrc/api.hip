@@ -21,6 +21,7 @@ struct Table {
         first_skinny = (int)v.size();
         for (int i = 0; i < kNumSkinnyVariants; ++i) v.push_back(&skinny_variants()[i]);
         for (int i = 0; i < kNumSkinny16Variants; ++i) v.push_back(&skinny16_variants()[i]);
+        for (int i = 0; i < kNumSkinnyRcVariants; ++i) v.push_back(&skinny_rc_variants()[i]);
         first_tile = (int)v.size();
         for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
         for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);

@@ -75,6 +75,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
 const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 16;
+const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 16;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;

@@ -1,0 +1,276 @@
+// Streaming kernels for 16 rows of A at a time when B is column-major (stored [N][K]: every column
+// of B, i.e. every output feature, is one contiguous K-vector - the usual layout of weights), for
+// all four storage types: fp32, bf16, fp16 and 8-bit E4M3 (bf16 result).
+//
+// As in kernel_skinny.hpp the bound is HBM: every byte of B is read once and used for 16
+// multiply-adds on the matrix pipe.  With k contiguous in B nothing has to be rearranged: a lane's
+// 128-bit load IS a run of consecutive k of one column, which is what the 16x16 matrix
+// instructions want per lane.  Lane (q = lane/16, c = lane%16) of a wave, per step of 256 bytes
+// of k and per group g of 16 columns, loads
+//     B[n0 + 16g + c][kb + 64t + 16q .. +15]   and   A[c][kb + 64t + 16q .. +15]   (bytes), t = 0..3
+// and feeds each 16-byte pair to the matrix pipe in operand-sized pieces: E4M3 two
+// v_mfma_f32_16x16x32_fp8_fp8 (8 bytes = 8 k per lane), bf16 / fp16 two v_mfma_f32_16x16x16 (4 k),
+// fp32 four v_mfma_f32_16x16x4_f32 (1 k).  Which k a lane's piece stands for only has to agree
+// between the two operands.  Accumulator g register r of lane (q, c) is Z[4q + r][n0 + 16g + c].
+//
+// Memory walk: a workgroup owns COLS = 16 CG WN consecutive columns = one contiguous block of B,
+// and its WK waves take the 256-byte steps of k in turn, so the workgroup streams its block front
+// to back.  With N / COLS >= the number of CUs no split of k over workgroups is needed; smaller N
+// splits k over grid.y with fp32 partial sums in the workspace, added in split order by a second
+// kernel.  The WK waves' sums are added in wave order through LDS.  No atomics; repeatable.
+#pragma once
+#include "common.hpp"
+#include "epilogue.hpp"
+
+namespace optiml {
+namespace skinny_rc {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+
+struct Params {
+    int64_t M, N, K;
+    const char *A; int64_t lda, strideA;       // leading dimensions and strides in elements
+    const char *B; int64_t ldb, strideB;
+    const float *bias; int64_t strideBias;
+    char *C; int64_t ldc, strideC;
+    float *partial;        // [split][batch * row_blocks][16][N] when split > 1
+    int64_t batch, row_blocks;
+    int split, act;
+};
+
+template <int DT> struct Type {
+    static constexpr int ES = DT == DT_F32 ? 4 : DT == DT_F8 ? 1 : 2;     // bytes per element of A and B
+    static constexpr int CS = DT == DT_F32 ? 4 : 2;                       // ... of C
+    static constexpr int ODT = DT == DT_F8 ? DT_BF16 : DT;                // storage type of a 16-bit C
+};
+
+// the multiply-adds of one 16-byte piece of k: a from A's row c, b from B's column c
+template <int DT>
+__device__ __forceinline__ floatx4 mma16(uintx4 a, uintx4 b, floatx4 acc)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (DT == DT_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[i]), __uint_as_float(b[i]), acc, 0, 0, 0);
+    } else if constexpr (DT == DT_F8) {
+        typedef long longx2_ __attribute__((ext_vector_type(2)));
+        const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a2[0], b2[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a2[1], b2[1], acc, 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uintx2 ai = uintx2{a[2 * i], a[2 * i + 1]}, bi = uintx2{b[2 * i], b[2 * i + 1]};
+            if constexpr (DT == DT_F16)
+                acc = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(halfx4, ai), __builtin_bit_cast(halfx4, bi), acc, 0, 0, 0);
+            else
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, ai), __builtin_bit_cast(shortx4, bi), acc, 0, 0, 0);
+        }
+    }
+#endif
+    return acc;
+}
+
+template <int CG>
+struct Stage {
+    uintx4 a[4];
+    uintx4 b[CG][4];
+};
+
+// one whole step (256 bytes of k below the end): a_ptr / b_ptr point at this lane's first vector
+template <int CG>
+__device__ __forceinline__ void load_stage(Stage<CG> &st, const char *a_ptr, const char *const (&b_ptr)[CG], int64_t off,
+                                           bool a_valid, const bool (&col_valid)[CG])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        st.a[t] = a_valid ? *reinterpret_cast<const uintx4 *>(a_ptr + off + 64 * t) : uintx4{0, 0, 0, 0};
+#pragma unroll
+        for (int g = 0; g < CG; ++g)
+            st.b[g][t] = col_valid[g] ? __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(b_ptr[g] + off + 64 * t))
+                                      : uintx4{0, 0, 0, 0};
+    }
+}
+
+template <int DT, int CG>
+__device__ __forceinline__ void mma_stage(const Stage<CG> &st, floatx4 (&acc)[CG])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int g = 0; g < CG; ++g) acc[g] = mma16<DT>(st.a[t], st.b[g][t], acc[g]);
+}
+
+template <int DT, int WN, int WK, int CG>
+__global__ __launch_bounds__(64 * WN * WK) void skinny_rc_kernel(Params p)
+{
+    constexpr int ES = Type<DT>::ES, CS = Type<DT>::CS;
+    constexpr int COLS = 16 * CG * WN;
+    constexpr int THREADS = 64 * WN * WK;
+    __shared__ floatx4 red[WK > 1 ? WK * 4 * COLS : 1];          // [wk][row group q][column]: rows 4q..4q+3
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave % WN, wk = wave / WN;
+    const int q = lane >> 4, c = lane & 15;
+    const int64_t zb = blockIdx.z, batch = zb / p.row_blocks, rb = zb % p.row_blocks;
+    const int64_t rows = p.M - 16 * rb < 16 ? p.M - 16 * rb : 16;
+    const int64_t nblock0 = (int64_t)blockIdx.x * COLS;
+    const int64_t n0 = nblock0 + (int64_t)wn * CG * 16 + c;       // this lane's column in group 0
+
+    // steps of 256 bytes of k: this workgroup's range [g0, g1) of the grid split, its waves in turn
+    const int64_t kbytes = p.K * ES, steps = (kbytes + 255) / 256, full_steps = kbytes / 256;
+    const int64_t g0 = steps * blockIdx.y / p.split, g1 = steps * (blockIdx.y + 1) / p.split;
+    const int64_t g1f = g1 < full_steps ? g1 : full_steps;
+
+    const bool a_valid = c < rows;
+    const char *a_ptr = p.A + (batch * p.strideA + (16 * rb + (a_valid ? c : 0)) * p.lda) * ES + 16 * q;
+    bool col_valid[CG];
+    const char *b_ptr[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+        col_valid[g] = n0 + 16 * g < p.N;
+        b_ptr[g] = p.B + (batch * p.strideB + (col_valid[g] ? n0 + 16 * g : 0) * p.ldb) * ES + 16 * q;
+    }
+
+    floatx4 acc[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[g] = floatx4{0, 0, 0, 0};
+
+    // whole steps, two register stages
+    int64_t s = g0 + wk;
+    if (s < g1f) {
+        Stage<CG> cur, nxt;
+        load_stage<CG>(cur, a_ptr, b_ptr, s * 256, a_valid, col_valid);
+        for (s += WK; s < g1f; s += WK) {
+            load_stage<CG>(nxt, a_ptr, b_ptr, s * 256, a_valid, col_valid);
+            mma_stage<DT, CG>(cur, acc);
+            cur = nxt;
+        }
+        mma_stage<DT, CG>(cur, acc);
+    }
+    // the ragged last step (K * ES is a multiple of 16: whole vectors), taken by wave 0 of the last split
+    if (wk == 0 && g1 > g1f) {
+        const int64_t kb = full_steps * 256;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const bool k_valid = kb + 64 * t + 16 * q + 16 <= kbytes;
+            const uintx4 a = (k_valid && a_valid) ? *reinterpret_cast<const uintx4 *>(a_ptr + kb + 64 * t) : uintx4{0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < CG; ++g) {
+                const uintx4 b = (k_valid && col_valid[g]) ? *reinterpret_cast<const uintx4 *>(b_ptr[g] + kb + 64 * t)
+                                                           : uintx4{0, 0, 0, 0};
+                acc[g] = mma16<DT>(a, b, acc[g]);
+            }
+        }
+    }
+
+    // sum the WK waves in wave order
+    if (WK > 1) {
+#pragma unroll
+        for (int g = 0; g < CG; ++g) red[(wk * 4 + q) * COLS + (wn * CG + g) * 16 + c] = acc[g];
+        __syncthreads();
+    }
+    float *part = p.split > 1 ? p.partial + ((int64_t)blockIdx.y * p.batch * p.row_blocks + zb) * 16 * p.N : nullptr;
+    char *out = p.C + (batch * p.strideC + 16 * rb * p.ldc) * CS;
+    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
+
+    // four rows (4 qq .. 4 qq + 3) of one column
+    auto finish = [&](int qq, int64_t col, floatx4 z) {
+        if (col >= p.N) return;
+        const float bj = (bias && p.split == 1) ? bias[col] : 0.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * qq + r;
+            if (row >= rows) continue;
+            if (p.split > 1) { part[(int64_t)row * p.N + col] = z[r]; continue; }
+            const float y = apply_act(z[r] + bj, p.act);
+            if constexpr (DT == DT_F32) reinterpret_cast<float *>(out)[(int64_t)row * p.ldc + col] = y;
+            else reinterpret_cast<unsigned short *>(out)[(int64_t)row * p.ldc + col] = to_16<Type<DT>::ODT>(y);
+        }
+    };
+    if (WK > 1) {
+        for (int e = tid; e < 4 * COLS; e += THREADS) {
+            const int qq = e / COLS, col = e % COLS;
+            floatx4 z = red[qq * COLS + col];
+#pragma unroll
+            for (int w = 1; w < WK; ++w) z += red[(w * 4 + qq) * COLS + col];
+            finish(qq, nblock0 + col, z);
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < CG; ++g) finish(q, n0 + 16 * g, acc[g]);
+    }
+}
+
+// C = act(bias + sum over splits of partial), splits added in ascending order, one rounding
+template <int DT>
+__global__ __launch_bounds__(256) void skinny_rc_reduce_kernel(Params p)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t batch = blockIdx.y;
+    if (idx >= p.M * p.N) return;
+    const int64_t row = idx / p.N, col = idx % p.N;
+    const int64_t zb = batch * p.row_blocks + row / 16;
+    float z = 0.0f;
+    for (int s = 0; s < p.split; ++s) z += p.partial[(((int64_t)s * p.batch * p.row_blocks + zb) * 16 + row % 16) * p.N + col];
+    const float y = apply_act(z + (p.bias ? p.bias[batch * p.strideBias + col] : 0.0f), p.act);
+    char *out = p.C + (batch * p.strideC + row * p.ldc + col) * Type<DT>::CS;
+    if constexpr (DT == DT_F32) *reinterpret_cast<float *>(out) = y;
+    else *reinterpret_cast<unsigned short *>(out) = to_16<Type<DT>::ODT>(y);
+}
+
+template <int DT>
+bool supports(const Problem &p)
+{
+    // A row-major, B column-major; whole 16-byte vectors of k; 32-bit friendly sizes
+    return p.dtype == DT && p.layout == 1 && p.M >= 1 && p.K >= 1 && (p.K * Type<DT>::ES) % 16 == 0 &&
+           p.batch * ((p.M + 15) / 16) <= 65535 && vector_friendly(p);
+}
+
+template <int DT, int WN, int WK, int CG>
+hipError_t launch(const Problem &p, hipStream_t stream)
+{
+    constexpr int COLS = 16 * CG * WN;
+    Params sp;
+    sp.M = p.M; sp.N = p.N; sp.K = p.K;
+    sp.A = static_cast<const char *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
+    sp.B = static_cast<const char *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
+    sp.bias = p.bias; sp.strideBias = p.strideBias;
+    sp.C = static_cast<char *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
+    sp.batch = p.batch; sp.act = p.act;
+    sp.row_blocks = (p.M + 15) / 16;
+    // split k over the grid only as far as needed for one workgroup per CU, and never into ranges
+    // shorter than WK * 8 steps (2 KiB of k per wave)
+    const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
+    const int64_t steps = (p.K * Type<DT>::ES + 255) / 256;
+    int64_t split = (compute_units() + col_blocks - 1) / col_blocks;
+    const int64_t by_k = steps / (WK * 8) > 0 ? steps / (WK * 8) : 1;
+    if (split > by_k) split = by_k;
+    if (split < 1) split = 1;
+    if (split > 64) split = 64;
+    sp.split = (int)split;
+    sp.partial = nullptr;
+    if (split > 1) {
+        void *ws = nullptr;
+        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws);
+        if (e != hipSuccess) return e;
+        sp.partial = static_cast<float *>(ws);
+    }
+    const int64_t gx = (p.N + COLS - 1) / COLS;
+    if (gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)gx, (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
+    hipLaunchKernelGGL((skinny_rc_kernel<DT, WN, WK, CG>), grid, dim3(64 * WN * WK), 0, stream, sp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split == 1) return e;
+    const int64_t elems = p.M * p.N;
+    hipLaunchKernelGGL(skinny_rc_reduce_kernel<DT>, dim3((unsigned)((elems + 255) / 256), (unsigned)p.batch), dim3(256), 0, stream, sp);
+    return hipGetLastError();
+}
+
+}  // namespace skinny_rc
+}  // namespace optiml

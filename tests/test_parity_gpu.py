@@ -35,6 +35,8 @@ def all_variants():
 
 def problem_for(name):
     """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
+    if name.startswith("skinnyrc"):
+        return DT_OF[name.split("_")[1]], 1, 13, 1000, 1232    # B column-major, K a whole number of 16-byte vectors
     if name.startswith("skinny"):
         return DT_OF[name.split("_")[1]], 0, 13, 1000, 1224
     if name.startswith("ring"):
@@ -312,7 +314,7 @@ def test_row_permutation_equivariance():
     assert e1(Yp[0], Y[0][perm]) <= 1e-6
 
 
-@pytest.mark.parametrize("vid", variant_ids("skinny"))
+@pytest.mark.parametrize("vid", variant_ids("skinny_"))
 def test_skinny_variants_with_blocks_of_16_rows(vid):
     """M > 16: grid.z counts blocks of 16 rows (the last one ragged) times batches; K long enough
     for the automatic grid split, so the partial sums of every block go through the workspace."""
@@ -328,7 +330,7 @@ def test_skinny_variants_with_blocks_of_16_rows(vid):
     check_against_oracle(A, B, synth.uniform(820 + vid, "bias", 1, 40)[0], dtype=F32, act=synth.ACT_SILU, layout=0, variant=vid)
 
 
-@pytest.mark.parametrize("vid", variant_ids("skinny"))
+@pytest.mark.parametrize("vid", variant_ids("skinny_"))
 def test_skinny_variants_with_grid_split_k(vid):
     # K long enough that the automatic split uses several workgroups per column block, and
     # M = 16 rows exactly; a second shape has a ragged last column block and a k tail
@@ -504,3 +506,25 @@ def test_e4m3_operands_copied_with_k_contiguous(layout):
     check_against_oracle(Ai, Bi, bi, dtype=F8, act=synth.ACT_RELU, layout=layout, exact=True)
     A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
     check_against_oracle(A1, synth.integers(982, "B", K, N, -8, 8), None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True, entry="ex")
+
+
+@pytest.mark.parametrize("vid", variant_ids("skinnyrc"))
+def test_column_major_b_streaming_variants(vid):
+    """B stored [N][K]: blocks of 16 rows (the last ragged) times batches, a grid split of k through the workspace,
+    a ragged last step of k, few columns, padded leading dimensions; integers exactly."""
+    dtype = DT_OF[ob.optiml_variant_name(vid).split("_")[1]]
+    batch, M, N, K = 2, 45, 264, 4240                              # long k, few columns: grid split
+    A = synth.normal(1500 + vid, "A", M, K, batch=batch); B = synth.normal(1500 + vid, "B", K, N, batch=batch)
+    bias = synth.normal(1500 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=1, variant=vid, ldc_pad=8)
+    Ai = synth.integers(1510 + vid, "A", M, K, batch=batch); Bi = synth.integers(1510 + vid, "B", K, N, batch=batch)
+    check_against_oracle(Ai, Bi, None, dtype=dtype, act=synth.ACT_RELU, layout=1, variant=vid, exact=True)
+    for (M, N, K) in ((16, 4104, 512), (5, 37, 48), (1, 1, 16), (16, 64, 272)):   # no split; tiny; one vector; ragged step only
+        A = synth.uniform(1520 + vid, "A", M, K); B = synth.uniform(1520 + vid, "B", K, N)
+        check_against_oracle(A, B, synth.uniform(1520 + vid, "bias", 1, N)[0], dtype=dtype, act=synth.ACT_SILU, layout=1,
+                             variant=vid, pad=16, ldc_pad=(-N) % 8)        # rows of C stay 16-byte aligned
+    # one-hot rows of A pick single k positions: a piece of a vector in the wrong k slot cannot hide
+    M, N, K = 16, 128, 1024
+    A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (61 * np.arange(M) + 7) % K] = 2.0
+    check_against_oracle(A1, synth.integers(1530, "B", K, N, -8, 8), None, dtype=dtype, act=synth.ACT_NONE, layout=1,
+                         variant=vid, exact=True)
