@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2}          # fp32, bf16, fp16, fp8 MFMA (dense)
 # which roof bounds each workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
-         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma"}
+         "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma", "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma", "c2_f32_skinny16_rc_silu": "hbm"}
 DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3"}
 # streaming siblings: (entry point, op, arrays read, arrays written)
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
@@ -61,6 +61,7 @@ LCE_SRC = ('kernel_linear_ce.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 LCE_F32_SRC = ('kernel_linear_ce.hip', 'kernel_ring_f32.hpp', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
 TRANSPOSE_SRC = ("kernel_transpose.hip",)
+SKINNY_RC_SRC = ("kernel_skinny_rc.hpp", "kernel_skinny_rc.hip", "epilogue.hpp")
 RING_F8_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f8_rc.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
@@ -89,6 +90,8 @@ TRAFFIC = {
         {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393506.0 * 2.0 + 131209.0) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
+    ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_wn1_wk4_cg4_t4"):
+        {"bytes": int((542219.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "ae947796a68b87c8"},
     ("s_transpose", "s_transpose"):
         {"bytes": int((524327.0 * 2.0 + 1048890.0) * 1024), "files": TRANSPOSE_SRC, "src": "7550a1f1381dfe3e"},
     ("s_mhsa", "s_mhsa"):

@@ -4,10 +4,10 @@
 namespace optiml {
 using namespace skinny_rc;
 
-#define SKRC(DT, TAG, WN, WK, CG)                                                                       \
-    {"skinnyrc_" TAG "_wn" #WN "_wk" #WK "_cg" #CG, supports<DT>, launch<DT, WN, WK, CG>, 0, 0,         \
-     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG>)}
-#define SKRC_SET(DT, TAG) SKRC(DT, TAG, 1, 8, 4), SKRC(DT, TAG, 1, 4, 4), SKRC(DT, TAG, 2, 4, 2), SKRC(DT, TAG, 1, 8, 2)
+#define SKRC(DT, TAG, WN, WK, CG, T)                                                                      \
+    {"skinnyrc_" TAG "_wn" #WN "_wk" #WK "_cg" #CG "_t" #T, supports<DT>, launch<DT, WN, WK, CG, T>, 0, 0,  \
+     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>)}
+#define SKRC_SET(DT, TAG) SKRC(DT, TAG, 1, 4, 4, 4), SKRC(DT, TAG, 2, 2, 2, 8), SKRC(DT, TAG, 4, 1, 1, 16), SKRC(DT, TAG, 2, 4, 1, 16)
 
 // per dtype the first entry is the dispatcher's choice
 const Variant *skinny_rc_variants()

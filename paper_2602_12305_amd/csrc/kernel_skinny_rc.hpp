@@ -5,17 +5,17 @@
 // As in kernel_skinny.hpp the bound is HBM: every byte of B is read once and used for 16
 // multiply-adds on the matrix pipe.  With k contiguous in B nothing has to be rearranged: a lane's
 // 128-bit load IS a run of consecutive k of one column, which is what the 16x16 matrix
-// instructions want per lane.  Lane (q = lane/16, c = lane%16) of a wave, per step of 256 bytes
+// instructions want per lane.  Lane (q = lane/16, c = lane%16) of a wave, per step of 64 T bytes
 // of k and per group g of 16 columns, loads
-//     B[n0 + 16g + c][kb + 64t + 16q .. +15]   and   A[c][kb + 64t + 16q .. +15]   (bytes), t = 0..3
+//     B[n0 + 16g + c][kb + 64t + 16q .. +15]   and   A[c][kb + 64t + 16q .. +15]   (bytes), t = 0..T-1
 // and feeds each 16-byte pair to the matrix pipe in operand-sized pieces: E4M3 two
 // v_mfma_f32_16x16x32_fp8_fp8 (8 bytes = 8 k per lane), bf16 / fp16 two v_mfma_f32_16x16x16 (4 k),
 // fp32 four v_mfma_f32_16x16x4_f32 (1 k).  Which k a lane's piece stands for only has to agree
 // between the two operands.  Accumulator g register r of lane (q, c) is Z[4q + r][n0 + 16g + c].
 //
 // Memory walk: a workgroup owns COLS = 16 CG WN consecutive columns = one contiguous block of B,
-// and its WK waves take the 256-byte steps of k in turn, so the workgroup streams its block front
-// to back.  With N / COLS >= the number of CUs no split of k over workgroups is needed; smaller N
+// and its WK waves take the steps of k in turn, so the workgroup streams its block front
+// to back (starting at a per-workgroup offset and wrapping).  With N / COLS >= the number of CUs no split of k over workgroups is needed; smaller N
 // splits k over grid.y with fp32 partial sums in the workspace, added in split order by a second
 // kernel.  The WK waves' sums are added in wave order through LDS.  No atomics; repeatable.
 #pragma once
@@ -76,19 +76,20 @@ __device__ __forceinline__ floatx4 mma16(uintx4 a, uintx4 b, floatx4 acc)
     return acc;
 }
 
-template <int CG>
+// T = 16-byte vectors per lane, column group and step: a step covers 64 T bytes of k
+template <int CG, int T>
 struct Stage {
-    uintx4 a[4];
-    uintx4 b[CG][4];
+    uintx4 a[T];
+    uintx4 b[CG][T];
 };
 
 // one whole step (256 bytes of k below the end): a_ptr / b_ptr point at this lane's first vector
-template <int CG>
-__device__ __forceinline__ void load_stage(Stage<CG> &st, const char *a_ptr, const char *const (&b_ptr)[CG], int64_t off,
+template <int CG, int T>
+__device__ __forceinline__ void load_stage(Stage<CG, T> &st, const char *a_ptr, const char *const (&b_ptr)[CG], int64_t off,
                                            bool a_valid, const bool (&col_valid)[CG])
 {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < T; ++t) {
         st.a[t] = a_valid ? *reinterpret_cast<const uintx4 *>(a_ptr + off + 64 * t) : uintx4{0, 0, 0, 0};
 #pragma unroll
         for (int g = 0; g < CG; ++g)
@@ -97,19 +98,20 @@ __device__ __forceinline__ void load_stage(Stage<CG> &st, const char *a_ptr, con
     }
 }
 
-template <int DT, int CG>
-__device__ __forceinline__ void mma_stage(const Stage<CG> &st, floatx4 (&acc)[CG])
+template <int DT, int CG, int T>
+__device__ __forceinline__ void mma_stage(const Stage<CG, T> &st, floatx4 (&acc)[CG])
 {
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < T; ++t)
 #pragma unroll
         for (int g = 0; g < CG; ++g) acc[g] = mma16<DT>(st.a[t], st.b[g][t], acc[g]);
 }
 
-template <int DT, int WN, int WK, int CG>
+template <int DT, int WN, int WK, int CG, int T>
 __global__ __launch_bounds__(64 * WN * WK) void skinny_rc_kernel(Params p)
 {
     constexpr int ES = Type<DT>::ES, CS = Type<DT>::CS;
+    constexpr int STEP = 64 * T;                                   // bytes of k per step
     constexpr int COLS = 16 * CG * WN;
     constexpr int THREADS = 64 * WN * WK;
     __shared__ floatx4 red[WK > 1 ? WK * 4 * COLS : 1];          // [wk][row group q][column]: rows 4q..4q+3
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_rc_kernel(Params p)
     const int64_t n0 = nblock0 + (int64_t)wn * CG * 16 + c;       // this lane's column in group 0
 
     // steps of 256 bytes of k: this workgroup's range [g0, g1) of the grid split, its waves in turn
-    const int64_t kbytes = p.K * ES, steps = (kbytes + 255) / 256, full_steps = kbytes / 256;
+    const int64_t kbytes = p.K * ES, steps = (kbytes + STEP - 1) / STEP, full_steps = kbytes / STEP;
     const int64_t g0 = steps * blockIdx.y / p.split, g1 = steps * (blockIdx.y + 1) / p.split;
     const int64_t g1f = g1 < full_steps ? g1 : full_steps;
 
@@ -141,23 +143,29 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_rc_kernel(Params p)
 #pragma unroll
     for (int g = 0; g < CG; ++g) acc[g] = floatx4{0, 0, 0, 0};
 
-    // whole steps, two register stages
-    int64_t s = g0 + wk;
-    if (s < g1f) {
-        Stage<CG> cur, nxt;
-        load_stage<CG>(cur, a_ptr, b_ptr, s * 256, a_valid, col_valid);
-        for (s += WK; s < g1f; s += WK) {
-            load_stage<CG>(nxt, a_ptr, b_ptr, s * 256, a_valid, col_valid);
-            mma_stage<DT, CG>(cur, acc);
+    // whole steps, two register stages.  The workgroups do not all start at the front of their
+    // columns: workgroup x starts 17 x steps in and wraps around, so that the workgroups in flight
+    // sit at different offsets within their columns.  With a power-of-two column pitch a common
+    // offset means a common set of memory channels (the transpose kernel's finding).
+    const int64_t nfull = g1f - g0;
+    if (wk < nfull) {
+        const int64_t rot = ((int64_t)blockIdx.x * 17) % nfull;
+        auto step_of = [&](int64_t j) { const int64_t u = j + rot; return g0 + (u < nfull ? u : u - nfull); };
+        Stage<CG, T> cur, nxt;
+        int64_t j = wk;
+        load_stage<CG, T>(cur, a_ptr, b_ptr, step_of(j) * STEP, a_valid, col_valid);
+        for (j += WK; j < nfull; j += WK) {
+            load_stage<CG, T>(nxt, a_ptr, b_ptr, step_of(j) * STEP, a_valid, col_valid);
+            mma_stage<DT, CG, T>(cur, acc);
             cur = nxt;
         }
-        mma_stage<DT, CG>(cur, acc);
+        mma_stage<DT, CG, T>(cur, acc);
     }
     // the ragged last step (K * ES is a multiple of 16: whole vectors), taken by wave 0 of the last split
     if (wk == 0 && g1 > g1f) {
-        const int64_t kb = full_steps * 256;
+        const int64_t kb = full_steps * STEP;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < T; ++t) {
             const bool k_valid = kb + 64 * t + 16 * q + 16 <= kbytes;
             const uintx4 a = (k_valid && a_valid) ? *reinterpret_cast<const uintx4 *>(a_ptr + kb + 64 * t) : uintx4{0, 0, 0, 0};
 #pragma unroll
@@ -232,7 +240,7 @@ bool supports(const Problem &p)
            p.batch * ((p.M + 15) / 16) <= 65535 && vector_friendly(p);
 }
 
-template <int DT, int WN, int WK, int CG>
+template <int DT, int WN, int WK, int CG, int T>
 hipError_t launch(const Problem &p, hipStream_t stream)
 {
     constexpr int COLS = 16 * CG * WN;
@@ -247,9 +255,9 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     // split k over the grid only as far as needed for one workgroup per CU, and never into ranges
     // shorter than WK * 8 steps (2 KiB of k per wave)
     const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
-    const int64_t steps = (p.K * Type<DT>::ES + 255) / 256;
+    const int64_t steps = (p.K * Type<DT>::ES + 64 * T - 1) / (64 * T);
     int64_t split = (compute_units() + col_blocks - 1) / col_blocks;
-    const int64_t by_k = steps / (WK * 8) > 0 ? steps / (WK * 8) : 1;
+    const int64_t by_k = steps * T / (WK * 32) > 0 ? steps * T / (WK * 32) : 1;
     if (split > by_k) split = by_k;
     if (split < 1) split = 1;
     if (split > 64) split = 64;
@@ -264,7 +272,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     const int64_t gx = (p.N + COLS - 1) / COLS;
     if (gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)gx, (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
-    hipLaunchKernelGGL((skinny_rc_kernel<DT, WN, WK, CG>), grid, dim3(64 * WN * WK), 0, stream, sp);
+    hipLaunchKernelGGL((skinny_rc_kernel<DT, WN, WK, CG, T>), grid, dim3(64 * WN * WK), 0, stream, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
     const int64_t elems = p.M * p.N;

@@ -265,7 +265,8 @@ def _store(x, dtype, transpose=False):
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
-BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu")     # further dtypes on the same shapes
+BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu",
+                     "c2_f32_skinny16_rc_silu")     # further dtypes on the same shapes
 
 
 def make_workload(name: str, scale: int = 1) -> Workload:
@@ -298,6 +299,13 @@ def make_workload(name: str, scale: int = 1) -> Workload:
                         _store(normal(3, "A", M, K), DTYPE_BF16),
                         _store(normal(3, "B", K, N), DTYPE_BF16),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c2_f32_skinny16_rc_silu":      # config 2 with B stored column-major ([N][K]: one contiguous K-vector per output)
+        M, N, K = 16, 16384 // s, 16384 // s
+        sd = K ** -0.5
+        return Workload(name, 1, M, N, K, DTYPE_F32, ACT_SILU, LAYOUT_RC, 1,
+                        _store(normal(1, "A", M, K, 0.0, sd), DTYPE_F32),
+                        _store(normal(1, "B", K, N, 0.0, sd), DTYPE_F32, transpose=True),
+                        uniform(1, "bias", 1, N, -0.1, 0.1))
     if name == "c2_bf16_skinny16_silu":        # config 2's shape and distributions in bf16 storage
         M, N, K = 16, 16384 // s, 16384 // s
         sd = K ** -0.5
