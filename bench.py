@@ -90,8 +90,8 @@ TRAFFIC = {
         {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393506.0 * 2.0 + 131209.0) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
-    ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_wn1_wk4_cg4_t4"):
-        {"bytes": int((542219.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "ae947796a68b87c8"},
+    ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
+        {"bytes": int((610078.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "10ec44f15caf0a01"},
     ("s_transpose", "s_transpose"):
         {"bytes": int((524327.0 * 2.0 + 1048890.0) * 1024), "files": TRANSPOSE_SRC, "src": "7550a1f1381dfe3e"},
     ("s_mhsa", "s_mhsa"):

@@ -7,9 +7,14 @@ using namespace skinny_rc;
 #define SKRC(DT, TAG, WN, WK, CG, T)                                                                      \
     {"skinnyrc_" TAG "_wn" #WN "_wk" #WK "_cg" #CG "_t" #T, supports<DT>, launch<DT, WN, WK, CG, T>, 0, 0,  \
      reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>)}
-#define SKRC_SET(DT, TAG) SKRC(DT, TAG, 1, 4, 4, 4), SKRC(DT, TAG, 2, 2, 2, 8), SKRC(DT, TAG, 4, 1, 1, 16), SKRC(DT, TAG, 2, 4, 1, 16)
+#define SKRC_DMA(DT, TAG, WK, CG, NS)                                                                     \
+    {"skinnyrc_" TAG "_dma_wk" #WK "_cg" #CG "_ns" #NS, supports_dma<DT>, launch_dma<DT, WK, CG, NS>, 0, 0,  \
+     reinterpret_cast<const void *>(&skinny_rc_dma_kernel<DT, WK, CG, NS>)}
+#define SKRC_SET(DT, TAG) SKRC_DMA(DT, TAG, 4, 4, 2), SKRC(DT, TAG, 1, 4, 4, 4), SKRC_DMA(DT, TAG, 4, 2, 3), SKRC_DMA(DT, TAG, 2, 4, 4)
 
-// per dtype the first entry is the dispatcher's choice
+// per dtype the first entry is the dispatcher's choice: staged through LDS by DMA, four waves, four column groups,
+// two stages (160 KiB of LDS); the second is the register-only kernel (also the fallback when the 32-bit lane
+// offsets of the DMA kernel do not reach)
 const Variant *skinny_rc_variants()
 {
     static const Variant v[kNumSkinnyRcVariants] = {SKRC_SET(DT_F32, "f32"), SKRC_SET(DT_BF16, "bf16"), SKRC_SET(DT_F16, "f16"),

@@ -167,7 +167,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 8192, 8192, 8192, layout=1, dtype=3).startswith("ring_f8_rc_256x256")          # E4M3, k contiguous in both
     assert sel(1, 8192, 8192, 8192, layout=0, dtype=3) == "xk_ring_f8"                            # ... otherwise copied that way
     assert sel(1, 100, 100, 100, layout=0, dtype=3) == "generic_64x64"
-    assert sel(1, 16, 16384, 16384, layout=1).startswith("skinnyrc_f32_wn1_wk4_cg4")                # column-major B: streamed too
+    assert sel(1, 16, 16384, 16384, layout=1).startswith("skinnyrc_f32_dma_wk4_cg4_ns2")                # column-major B: streamed too
     assert sel(1, 32, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and not sel(1, 48, 16384, 16384, layout=1, dtype=1).startswith("skinny")
     assert sel(1, 16, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and sel(1, 3, 4096, 4096, layout=1, dtype=3).startswith("skinnyrc_f8")
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
