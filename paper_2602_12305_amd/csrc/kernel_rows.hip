@@ -72,7 +72,14 @@ __global__ __launch_bounds__(kThreads) void ce_wave_rows_kernel(const float *__r
             constexpr int U = 8;                          // 8 x 64 lanes x 4 = 2048 columns per slice
             const int64_t c4 = C / 4;
             const floatx4 *row4 = reinterpret_cast<const floatx4 *>(row);
-            for (int64_t base = lane; base < c4; base += U * 64) {
+            // Rows are walked in slices of 2048 columns, row j starting 5 j slices in and wrapping:
+            // with a power-of-two row pitch the waves in flight would otherwise all sit at the same
+            // offset within their rows, i.e. on the same few memory channels.
+            const int64_t slices = (c4 + U * 64 - 1) / (U * 64);
+            const int64_t start = slices > 0 ? (j * 5) % slices : 0;
+            for (int64_t it = 0; it < slices; ++it) {
+                const int64_t sl = it + start < slices ? it + start : it + start - slices;
+                const int64_t base = lane + sl * (U * 64);
                 floatx4 v[U];
                 float mx = -__builtin_inff();
 #pragma unroll
