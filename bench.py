@@ -67,39 +67,39 @@ ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
-        {"bytes": int((529550.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "c552b7023eddf7be"},
+        {"bytes": int((529550.6 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "688c123f3902d3da"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((384928.0 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "cbc84d18131bb72d"},
+        {"bytes": int((385049.6 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "1eb1b7785df05428"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((791041.6 * 2.0 + 131088.9) * 1024), "files": RING_SRC, "src": "2345bd5346290519"},
+        {"bytes": int((793541.1 * 2.0 + 131075.0) * 1024), "files": RING_SRC, "src": "ebc12004cda035e0"},
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((793805.8 * 2.0 + 131091.7) * 1024), "files": RING_SRC, "src": "2345bd5346290519"},
+        {"bytes": int((795204.7 * 2.0 + 131077.1) * 1024), "files": RING_SRC, "src": "ebc12004cda035e0"},
     ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((67500.6 * 2.0 + 262735.4) * 1024), "files": RINGP_SRC, "src": "1326f112e3c54462"},
+        {"bytes": int((67359.9 * 2.0 + 263116.7) * 1024), "files": RINGP_SRC, "src": "5eadfb81ea491bc6"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
-        {"bytes": int((266405.4 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "94bbd1015fd43913"},
+        {"bytes": int((266405.3 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "126c6c257aab597c"},
     ("s_sigmoid", "s_sigmoid"):
-        {"bytes": int((524327.4 * 2.0 + 1048577.4) * 1024), "files": STREAMS_SRC, "src": "02250798199cd25e"},
+        {"bytes": int((524327.4 * 2.0 + 1048576.7) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
     ("s_dot", "s_dot"):
-        {"bytes": int((1048631.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "02250798199cd25e"},
+        {"bytes": int((1048631.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
     ("s_ce", "s_ce"):
-        {"bytes": int((524980.1 * 2.0 + 64.3) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+        {"bytes": int((524987.1 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((1049927.7 * 2.0 + 1049906.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+        {"bytes": int((1049945.8 * 2.0 + 1049879.3) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
     ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524323.1 * 2.0 + 1048788.2) * 1024), "files": ROWS_SRC, "src": "c3dccb553bd4fcc8"},
+        {"bytes": int((524315.1 * 2.0 + 1048753.0) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393506.0 * 2.0 + 131209.0) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
+        {"bytes": int((393484.6 * 2.0 + 131255.3) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((610078.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "10ec44f15caf0a01"},
+        {"bytes": int((609902.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "10ec44f15caf0a01"},
     ("s_transpose", "s_transpose"):
-        {"bytes": int((524327.0 * 2.0 + 1048890.0) * 1024), "files": TRANSPOSE_SRC, "src": "7550a1f1381dfe3e"},
+        {"bytes": int((524326.7 * 2.0 + 1048853.8) * 1024), "files": TRANSPOSE_SRC, "src": "e58e62a4e32315d6"},
     ("s_mhsa", "s_mhsa"):
-        {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "0b50637145a1936e"},
+        {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "a4876881c0272702"},
     ("s_lce", "s_lce"):
-        {"bytes": int((1590396.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "a728f331d9580d2d"},
+        {"bytes": int((1590401.9 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "f47b3d42dbf7e43a"},
     ("s_lce_f32", "s_lce_f32"):
-        {"bytes": int((1584475.5 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "f7657cf71d7ba4ff"},
+        {"bytes": int((1584548.7 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "b9faa7bb22c86a4d"},
 }
 
 
