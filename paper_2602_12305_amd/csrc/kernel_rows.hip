@@ -169,6 +169,7 @@ __global__ __launch_bounds__(kFinalThreads) void mean_of_partials_kernel(const d
 
 // sum over the workgroup of two fp64 values, fixed order (butterfly in the wave, waves in order);
 // every thread gets the result
+template <int THREADS = kThreads>
 __device__ __forceinline__ void block_sum2(double &a, double &b, double (*scratch)[2])
 {
 #pragma unroll
@@ -181,20 +182,21 @@ __device__ __forceinline__ void block_sum2(double &a, double &b, double (*scratc
     if (lane == 0) { scratch[wave][0] = a; scratch[wave][1] = b; }
     __syncthreads();
     a = scratch[0][0]; b = scratch[0][1];
-    for (int w = 1; w < kThreads / 64; ++w) { a += scratch[w][0]; b += scratch[w][1]; }
+    for (int w = 1; w < THREADS / 64; ++w) { a += scratch[w][0]; b += scratch[w][1]; }
 }
 
-// rows of at most 8192 features, one workgroup per row, row held in registers (VEC) or re-read (scalar)
-template <bool VEC>
-__global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                                   int64_t len, double eps)
+// One workgroup of THREADS per row.  VEC: the row, at most THREADS * U * 4 features, is read once
+// and held in registers (8 bytes of traffic per feature); scalar: it is read three times.
+template <bool VEC, int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void layernorm_short_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                  int64_t len, double eps)
 {
+    constexpr int kThreads = THREADS;
     __shared__ double scratch[kThreads / 64][2];
     const float *xr = x + (int64_t)blockIdx.x * len;
     float *yr = y + (int64_t)blockIdx.x * len;
     const double inv_len = 1.0 / (double)len;
     if (VEC) {
-        constexpr int U = 8;
         const int64_t n4 = len / 4;                      // len % 4 == 0 here
         const floatx4 *x4 = reinterpret_cast<const floatx4 *>(xr);
         floatx4 v[U];
@@ -206,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *
 #pragma unroll
             for (int e = 0; e < 4; ++e) s += (double)v[u][e];
         }
-        block_sum2(s, unused, scratch);
+        block_sum2<THREADS>(s, unused, scratch);
         const double mean = s * inv_len;
         double q = 0.0;
 #pragma unroll
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *
             }
         }
         unused = 0.0;
-        block_sum2(q, unused, scratch);
+        block_sum2<THREADS>(q, unused, scratch);
         const double rstd = 1.0 / sqrt(q * inv_len + eps);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -233,12 +235,12 @@ __global__ __launch_bounds__(kThreads) void layernorm_short_kernel(const float *
     } else {
         double s = 0.0, unused = 0.0;
         for (int64_t i = threadIdx.x; i < len; i += kThreads) s += (double)xr[i];
-        block_sum2(s, unused, scratch);
+        block_sum2<THREADS>(s, unused, scratch);
         const double mean = s * inv_len;
         double q = 0.0;
         for (int64_t i = threadIdx.x; i < len; i += kThreads) q += ((double)xr[i] - mean) * ((double)xr[i] - mean);
         unused = 0.0;
-        block_sum2(q, unused, scratch);
+        block_sum2<THREADS>(q, unused, scratch);
         const double rstd = 1.0 / sqrt(q * inv_len + eps);
         for (int64_t i = threadIdx.x; i < len; i += kThreads) yr[i] = (float)(((double)xr[i] - mean) * rstd);
     }
@@ -382,10 +384,17 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream)
 {
     const bool vec = aligned16(x) && aligned16(y) && len % 4 == 0;
-    if (len <= 8192) {
+    if (len <= 8192 || (vec && len <= 32768)) {
         if (rows > 0x7fffffffLL) return hipErrorInvalidValue;
-        if (vec) hipLaunchKernelGGL(layernorm_short_kernel<true>, dim3((unsigned)rows), dim3(kThreads), 0, stream, x, y, len, (double)eps);
-        else hipLaunchKernelGGL(layernorm_short_kernel<false>, dim3((unsigned)rows), dim3(kThreads), 0, stream, x, y, len, (double)eps);
+        const dim3 grid((unsigned)rows);
+        const double e64 = (double)eps;
+        if (!vec) hipLaunchKernelGGL((layernorm_short_kernel<false, kThreads, 8>), grid, dim3(kThreads), 0, stream, x, y, len, e64);
+        else if (len <= 8192) hipLaunchKernelGGL((layernorm_short_kernel<true, kThreads, 8>), grid, dim3(kThreads), 0, stream, x, y, len, e64);
+        // rows that a 1024-thread workgroup still holds in registers: one pass instead of the
+        // two kernels below
+        // (16 vectors a thread would spill)
+        else if (len <= 16384) hipLaunchKernelGGL((layernorm_short_kernel<true, 512, 8>), grid, dim3(512), 0, stream, x, y, len, e64);
+        else hipLaunchKernelGGL((layernorm_short_kernel<true, 1024, 8>), grid, dim3(1024), 0, stream, x, y, len, e64);
         return hipGetLastError();
     }
     // Chunk and group sizes from a sweep on 64 rows of 4 Mi features: 16 Ki features per workgroup and
