@@ -10,16 +10,21 @@
 //
 // Wait counts.  A wave's vector-memory operations complete in issue order, and the ring's
 // loads are counted by hand (see kernel_tile_ring.hpp).  The epilogue of a whole tile issues a
-// fixed number of stores per wave (TM * READS) plus one load of the next tile's bias slice;
-// the first AHEAD+1 steps of the next tile wait for loads that are older than those, so they
-// allow that many more operations to be outstanding (ring_step<C, EXTRA>).  A tile that
+// fixed number of stores per wave (TM * READS); the first AHEAD+1 steps of the next tile wait
+// for loads that are older than those, so they allow that many more operations to be
+// outstanding (ring_step<C, EXTRA>).  A tile that
 // touches the edge of C stores a data-dependent number of times: after it the wave simply
 // waits for everything (s_waitcnt vmcnt(0)) and the next tile starts with the plain counts.
 //
-// LDS: NS ring stages, then 1 KiB per wave for the tile's 256 bias values (fetched by LDS-DMA
-// too, so that no compiler-tracked load sits between the hand-counted ones).  The epilogue's
-// staging slabs live in the stage of the k-tile multiplied last, the only one no load in
-// flight is aimed at.
+// Bias.  The accumulators of a tile start from its bias values instead of zero, which takes the
+// addition (a quarter of the vector instructions of a ReLU epilogue) out of the part of the tile
+// during which the matrix pipe idles.  The 256 values come by LDS-DMA too (no compiler-tracked
+// load sits between the hand-counted ones), into one of two KiB slices per wave, requested
+// before the first k-tiles of the tile they belong to: a load older than the ones a step waits
+// for can only make that wait stricter.
+//
+// LDS: NS ring stages, then the bias slices.  The epilogue's staging slabs live in the stage of
+// the k-tile multiplied last, the only one no load in flight is aimed at.
 #pragma once
 #include <type_traits>
 
@@ -40,10 +45,10 @@ struct PCfg {
     static constexpr int CPR = C::WTN / 8, PITCH = C::WTN * 2;      // 16-byte chunks and bytes per slab row
     static constexpr int READS = 32 * CPR / 64;                      // 16-byte stores per lane per 32 rows
     static constexpr int STORES = C::TM * READS;                     // per wave per whole tile
-    static constexpr int EXTRA = STORES + 1;                         // + the bias load
+    static constexpr int EXTRA = STORES;
     static constexpr int HEAD = C::AHEAD + 1;                        // steps that may still see them
     static constexpr int MIN_NK = HEAD + C::NS - 1;
-    static constexpr int BIAS_BYTES = C::NW * 1024;
+    static constexpr int BIAS_BYTES = 2 * C::NW * 1024;              // per wave: this tile's slice and the next one's
     static constexpr int LDS_BYTES = C::NS * C::STAGE_BYTES + BIAS_BYTES;
     static_assert(C::NW * 32 * PITCH <= C::STAGE_BYTES, "slabs fit one stage");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
@@ -62,8 +67,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WM, wn = wave / C::WM;
     lds_char *const base = (lds_char *)lds;
-    const lds_char *const bias_rd = base + NS * STAGE + wave * 1024;
-    const uint32_t bias_lds = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(bias_rd));
+    // bias slice `slot` (0 or 1) of this wave
+    auto bias_slice = [&](int slot) { return base + NS * STAGE + (slot * NW + wave) * 1024; };
 
     // Tile list of this workgroup.  Workgroup ids go round-robin over the 8 XCDs; XCD x owns a
     // contiguous range of tiles (in band order, see below) and its workgroups take them in turn,
@@ -137,20 +142,16 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
         }
     }
 
-    // one wave-wide load of the tile's bias slice (lane l: four values from column n0 + 4l,
-    // clamped at the edge) into this wave's KiB; without a bias an in-bounds dummy of the same cost
-    auto issue_bias = [&](const Tile &t, const char *b_of_tile) {
-        const char *src;
-        uint32_t off;
-        if (p.bias) {
-            src = reinterpret_cast<const char *>(p.bias + t.batch * p.strideBias + t.n0);
-            const int64_t col = t.n0 + 4 * lane;
-            off = (uint32_t)(((col + 4 <= p.N ? col : p.N - 4) - t.n0) * 4);
-        } else {
-            src = b_of_tile;
-            off = 0;
-        }
-        ring::dma_load16(ring::scalar_ptr(src), off, bias_lds);
+    // One wave-wide load of a tile's bias slice (lane l: four values from column n0 + 4l, clamped
+    // at the edge) into slice `slot` of this wave.  The accumulators of the tile start from these
+    // values, so the epilogue has no bias to add.
+    const bool has_bias = p.bias != nullptr;
+    auto issue_bias = [&](const Tile &t, int slot) {
+        const char *src = reinterpret_cast<const char *>(p.bias + t.batch * p.strideBias + t.n0);
+        const int64_t col = t.n0 + 4 * lane;
+        const uint32_t off = (uint32_t)(((col + 4 <= p.N ? col : p.N - 4) - t.n0) * 4);
+        ring::dma_load16(ring::scalar_ptr(src), off,
+                         __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(bias_slice(slot))));
     };
 
     const int64_t nk = p.K / 32;                   // >= MIN_NK
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
     Tile cur = decode(start + j);
     set_offsets(cur);
     const char *ldA = p.A + cur.batch * p.strideA * 2, *ldB = p.B + cur.batch * p.strideB * 2;
-    issue_bias(cur, ldB);
+    int slot = 0;                                  // bias slice of the current tile
+    if (has_bias) issue_bias(cur, slot);
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) ring::issue_stage<C>(ctx, ldA + s * 64, ldB + s * b_step, base + s * STAGE);
     if constexpr (C::PF) {
@@ -182,31 +184,55 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
 
     bool pending = false;                          // stores of the previous tile may be outstanding
     for (;;) {
+        if (has_bias) {
+            // The slice was requested before the NS-1 k-tiles in flight (and before the previous
+            // tile's stores): once at most those are outstanding it has landed.  It is this
+            // wave's own, so no barrier.
+            if (pending) ring::wait_vmcnt<(NS - 1) * C::LOADS + P::STORES>();
+            else ring::wait_vmcnt<(NS - 1) * C::LOADS>();
+            asm volatile("" ::: "memory");
+            const lds_char *const bias_rd = bias_slice(slot);
 #pragma unroll
-        for (int jn = 0; jn < TN; ++jn)
+            for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int gq = 0; gq < 4; ++gq) {
+                    const floatx4 bv = *reinterpret_cast<const __attribute__((address_space(3))) floatx4 *>(
+                        bias_rd + (wn * C::WTN + 32 * jn + 8 * gq + 4 * half) * 4);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[jn][i][r] = 0.0f;
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[jn][i][4 * gq + e] = bv[e];
+                }
+        } else {
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[jn][i][r] = 0.0f;
+        }
 
+        const int64_t jnext = j + nwg;
+        const bool has_next = jnext < count;
+        Tile nxt = cur;
+        // The last NS-1 steps fetch the first k-tiles of the next tile (or, after the last tile,
+        // re-fetch those of this one: in bounds, never read).
+        auto turn_to_next = [&]() {
+            if (has_next) {
+                nxt = decode(start + jnext);
+                set_offsets(nxt);
+                ldA = p.A + nxt.batch * p.strideA * 2;
+                ldB = p.B + nxt.batch * p.strideB * 2;
+                if (has_bias) issue_bias(nxt, slot ^ 1);
+            }
+        };
         if (pending) {
             for (int kt = 0; kt < P::HEAD; ++kt) step(AfterStores{}, ldA + (kt + NS - 1) * 64, ldB + (kt + NS - 1) * b_step);
         } else {
             for (int kt = 0; kt < P::HEAD; ++kt) step(Plain{}, ldA + (kt + NS - 1) * 64, ldB + (kt + NS - 1) * b_step);
         }
         for (int64_t kt = P::HEAD; kt + NS <= nk; ++kt) step(Plain{}, ldA + (kt + NS - 1) * 64, ldB + (kt + NS - 1) * b_step);
-
-        // the last NS-1 steps fetch the first k-tiles of the next tile (or, after the last tile,
-        // re-fetch those of this one: in bounds, never read)
-        const int64_t jnext = j + nwg;
-        const bool has_next = jnext < count;
-        Tile nxt = cur;
-        if (has_next) {
-            nxt = decode(start + jnext);
-            set_offsets(nxt);
-            ldA = p.A + nxt.batch * p.strideA * 2;
-            ldB = p.B + nxt.batch * p.strideB * 2;
-        }
+        turn_to_next();
         for (int s = 0; s < NS - 1; ++s) step(Plain{}, ldA + s * 64, ldB + s * b_step);
 
         // ---- epilogue of `cur`: bias, activation, bf16 conversion in registers; 32 rows at a time
@@ -219,7 +245,6 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
             char *const Cw = p.C + (cur.batch * p.strideC + mw * p.ldc + nw) * 2;
             constexpr int CPR = P::CPR, PITCH = P::PITCH, READS = P::READS;
             lds_char *slab = base + ((st + NS - 1) % NS) * STAGE + wave * (32 * PITCH);
-            const bool has_bias = p.bias != nullptr;
             const bool whole = cur.m0 + C::BM <= p.M && cur.n0 + C::BN <= p.N;
             auto slab_key = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
             const int wkey = slab_key(frag_row);
@@ -230,13 +255,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
                 for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
                     for (int gq = 0; gq < 4; ++gq) {
-                        // the bias values are re-read from LDS for every 32 rows: registers are scarce here
-                        const floatx4 bv = *reinterpret_cast<const __attribute__((address_space(3))) floatx4 *>(
-                            bias_rd + (wn * C::WTN + 32 * jn + 8 * gq + 4 * half) * 4);
                         float y[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            y[e] = apply_act_bf16out(acc[jn][i][4 * gq + e] + (has_bias ? bv[e] : 0.0f), ACT);
+                        for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[jn][i][4 * gq + e], ACT);
                         *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                             slab + frag_row * PITCH + (((4 * jn + gq) ^ wkey) << 4) + 8 * half) =
                             uintx2{pack2_16<C::DT>(y[0], y[1]), pack2_16<C::DT>(y[2], y[3])};
@@ -272,8 +293,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_persistent_kernel(Params
                 }
             });
             if (!has_next) break;
-            asm volatile("" ::: "memory");         // the bias slice has been read before it is overwritten
-            issue_bias(nxt, ldB);
+            slot ^= 1;
             if (!whole) ring::wait_vmcnt<0>();     // unknown number of stores: start the next tile drained
             pending = whole;
         }
