@@ -75,7 +75,7 @@ TRAFFIC = {
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
         {"bytes": int((795204.7 * 2.0 + 131077.1) * 1024), "files": RING_SRC, "src": "ebc12004cda035e0"},
     ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((67359.9 * 2.0 + 263116.7) * 1024), "files": RINGP_SRC, "src": "5eadfb81ea491bc6"},
+        {"bytes": int((70059.5 * 2.0 + 266801.0) * 1024), "files": RINGP_SRC, "src": "fe2b4a4cb3c298cb"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
         {"bytes": int((266405.3 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "126c6c257aab597c"},
     ("s_sigmoid", "s_sigmoid"):
@@ -83,11 +83,11 @@ TRAFFIC = {
     ("s_dot", "s_dot"):
         {"bytes": int((1048631.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
     ("s_ce", "s_ce"):
-        {"bytes": int((524987.1 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
+        {"bytes": int((524983.2 * 2.0 + 64.2) * 1024), "files": ROWS_SRC, "src": "ba5a7445e9a0b7d4"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((1049945.8 * 2.0 + 1049879.3) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
+        {"bytes": int((1049946.4 * 2.0 + 1049979.6) * 1024), "files": ROWS_SRC, "src": "ba5a7445e9a0b7d4"},
     ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524315.1 * 2.0 + 1048753.0) * 1024), "files": ROWS_SRC, "src": "6520e22171ec46c9"},
+        {"bytes": int((524317.2 * 2.0 + 1048741.1) * 1024), "files": ROWS_SRC, "src": "ba5a7445e9a0b7d4"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393484.6 * 2.0 + 131255.3) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
