@@ -65,66 +65,183 @@ bool can_run(const Variant *v, const Problem &p)
 
 bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 
-// The streaming kernels re-read B once per 16 rows of A.  For more than 16 rows that is worth it
-// while the re-reads (from L2, about 8 TB/s measured at 1024^3) take less time than an MFMA tile
-// kernel needs when its 128x128 tiles cover only part of the chip (140 TFLOP/s when every CU has
-// a tile).  Measured: 256^3 8 us against 37 us, 1024^3 29-37 us against more than 60 us,
-// 256 x 2048 x 2048 32 us against 250 us; from 2048^3 on the tile kernel wins.
-bool streaming_beats_tiles(const Problem &p)
+// ---- Variant selection: a small cost model, calibrated on this chip -------------------------
+//
+// Tile kernels.  Time = rounds x (fixed + flop per tile / rate of one workgroup).  `fixed` is the
+// part of a tile that is not its k loop (first loads in flight, epilogue), `rate` what one
+// workgroup sustains when the whole chip runs the kernel, `share` how many workgroups' worth of
+// that rate a CU delivers when it holds several (1: rounds are whole, a 257th tile costs a second
+// round).  `boost`: the 16-bit direct-to-LDS kernels are bounded by the board's power, and a
+// partly filled chip clocks up to 1.5 x higher (64 tiles of 256 x 256 at K = 2048: 43.6 us, where
+// the full-chip rate would give 63).  Numbers from 4096^3 (full chip) and from 64 x 4096 x 4096,
+// 128 x 8192 x 8192, 1024^3, 2048^3 (part of the chip), in us and TFLOP/s:
+//   ring 256x256 (16-bit) 8 + f / 4.9      ring 256x256 (8-bit, 64-deep) 8 + f / 9.0, else f / 6.6
+//   persistent ring       4.3 + f / 4.56   (more tiles than CUs only)
+//   direct 256x256 5 + f / 4.3             direct 256x128 3 + f / 3.5
+//   direct 128x128 2.7 + f / 2.56, 1.45 workgroups' worth per CU
+//   staged 16-bit 256x256 5 + f / 2.0, 256x128 4 + f / 1.8, 128x128 3 + f / 1.17 (1.8 per CU)
+//   fp32 ring 128x128 3 + f / 0.548, 256x128 3 + f / 0.53
+//   staged fp32 256x128 4 + f / 0.41, 128x128 3 + f / 0.33, 64x64 3 + f / 0.151 (2.3 per CU)
+// A CU reaches its `share` only gradually: with n workgroups per CU it delivers min(share,
+// 1 + 0.45 (n - 1)) (64x64 fp32 tiles at 1536^3, 2.25 per CU: 124 us, not the 86 us of n = share).
+// The staged 128- and 256-row kernels lose about a fifth on a K with a partial last k-tile
+// (3000^3: 878 us estimated 633 without it).
+struct Cost {
+    float fixed_us = 0, tf_wg = 0, share = 1;
+    bool boost = false, many_tiles_only = false;
+};
+
+bool starts_with(const char *s, const char *prefix)
 {
-    if (p.dtype != DT_F32 || p.layout != 0) return false;
-    const double blocks16 = (double)((p.M + 15) / 16), batch = (double)p.batch;
-    const double t_stream = batch * blocks16 * (double)p.K * (double)p.N * 4.0 / 8e12;
-    const double tm = (double)((p.M + 127) / 128), tn = (double)((p.N + 127) / 128);
-    const double tiles = tm * tn * batch;
-    const double share = tiles < 256.0 ? tiles / 256.0 : 1.0;
-    const double t_tiles = 2.0 * tiles * 128.0 * 128.0 * (double)p.K / (140e12 * share);   // whole tiles are computed
-    return t_stream < t_tiles;
+    while (*prefix)
+        if (*s++ != *prefix++) return false;
+    return true;
 }
 
-// The same question for 16-bit storage and up to 128 rows.  The 256 x 256 ring tiles waste most of
-// their rows there and, for one row of tiles, use N/256 CUs; the streaming kernel reads B once
-// per 16 rows, the blocks of rows running side by side and sharing much of B through the caches.
-// Calibrated on 16..64 x 16384 x 16384 (86, 121, 210 us streamed against 270 us) and
-// 16 x 32768 x 4096 (47 us against 80 us).
-bool streaming16_beats_tiles(const Problem &p)
+bool contains(const char *s, const char *what)
 {
-    if (p.dtype == DT_F32 || p.layout != 0 || p.M > 128) return false;
-    const double rb = (double)((p.M + 15) / 16), batch = (double)p.batch;
-    const double t_stream = batch * (double)p.K * (double)p.N * 2.0 / 5.8e12 * (0.55 + 0.45 * rb);
-    const double tiles = (double)((p.M + 255) / 256) * (double)((p.N + 255) / 256) * batch;
-    const double rounds = (double)(int64_t)((tiles + 255.0) / 256.0);
-    const double t_tiles = rounds * 2.0 * 65536.0 * (double)p.K / 7e12;
-    return t_stream < t_tiles;
+    for (; *s; ++s)
+        if (starts_with(s, what)) return true;
+    return false;
 }
 
-// Preference order: the streaming split-K kernels for at most 16 rows, and for small fp32
-// problems of more rows (without the non-temporal hint: B is meant to stay in L2); then the MFMA
-// tile kernels - one that declares a measured preference for the shape, else in table order
-// (direct-to-LDS kernels before staged ones) the first whose grid gives every CU a workgroup,
-// else the one with most workgroups; then the fallback.
+Cost cost_of(const Variant *v)
+{
+    const char *n = v->name;
+    Cost c;
+    const bool f32 = contains(n, "_f32_");
+    if (starts_with(n, "ringp_")) { c.fixed_us = 4.3f; c.tf_wg = 4.56f; c.boost = true; c.many_tiles_only = true; }
+    else if (starts_with(n, "ring_f32_")) { c.fixed_us = 3.0f; c.tf_wg = v->bm == 128 ? 0.548f : 0.53f; }
+    else if (starts_with(n, "ring_f8_")) { c.fixed_us = 8.0f; c.tf_wg = contains(n, "_k64") ? 9.0f : 6.6f; c.boost = true; }
+    else if (starts_with(n, "ring_")) { c.fixed_us = 8.0f; c.tf_wg = 4.9f; c.boost = true; }
+    else if (starts_with(n, "direct_")) {
+        c.boost = true;
+        if (v->bm == 256 && v->bn == 256) { c.fixed_us = 5.0f; c.tf_wg = 4.3f; }
+        else if (v->bm == 256) { c.fixed_us = 3.0f; c.tf_wg = 3.5f; }
+        else { c.fixed_us = 2.7f; c.tf_wg = 2.56f; c.share = 1.45f; }
+    } else if (starts_with(n, "tile_") && f32) {
+        if (v->bm == 256) { c.fixed_us = 4.0f; c.tf_wg = 0.41f; }
+        else if (v->bm == 128) { c.fixed_us = 3.0f; c.tf_wg = 0.33f; c.share = 1.07f; }
+        else { c.fixed_us = 3.0f; c.tf_wg = 0.151f; c.share = 2.3f; }
+    } else if (starts_with(n, "tile_")) {
+        if (v->bm == 256 && v->bn == 256) { c.fixed_us = 5.0f; c.tf_wg = 2.0f; }
+        else if (v->bm == 256) { c.fixed_us = 4.0f; c.tf_wg = 1.8f; }
+        else { c.fixed_us = 3.0f; c.tf_wg = 1.17f; c.share = 1.8f; }
+    }
+    return c;
+}
+
+double tile_estimate_us(const Variant *v, const Cost &c, const Problem &p)
+{
+    constexpr double kCUs = 256.0;
+    const double tiles = (double)((p.M + v->bm - 1) / v->bm) * (double)((p.N + v->bn - 1) / v->bn) * (double)p.batch;
+    if (c.many_tiles_only && tiles <= kCUs) return 1e30;
+    const double fill = tiles < kCUs ? tiles / kCUs : 1.0;
+    double rate = c.tf_wg * (c.boost ? 1.5 - 0.5 * fill : 1.0);                // TFLOP/s = flop per us / 1e6
+    if (starts_with(v->name, "tile_") && v->bm >= 128 && p.K % (p.dtype == DT_F32 ? 16 : 32) != 0) rate *= 0.8;
+    const double tile_us = c.fixed_us + 2.0 * v->bm * v->bn * (double)p.K / (rate * 1e6);
+    if (c.share == 1.0f) return tile_us * (double)(int64_t)((tiles + kCUs - 1.0) / kCUs);
+    const double n = tiles / kCUs;                                             // workgroups per CU
+    if (n <= 1.0) return tile_us;
+    const double grown = 1.0 + 0.45 * (n - 1.0);
+    return tile_us * n / (grown < c.share ? grown : c.share);
+}
+
+// Streaming kernels (B read once per 16 rows of A, the blocks of rows side by side): the first
+// pass comes from memory at about 6 TB/s, the others largely from the caches, at a rate that
+// grows with the length of a workgroup's k range: row-major B 14 TB/s (8- and 16-bit) and
+// 11 K / (K + 120) TB/s (fp32, where the matrix instruction is the slower side); column-major B
+// 16 K / (K + 900) and 12 K / (K + 600).  Measured from 8 x 512^3 and 64 x 4096 x 4096 to 4096^3,
+// within 20 %; 4 us for the two launches.
+double stream_estimate_us(const Problem &p)
+{
+    const double rb = (double)((p.M + 15) / 16), K = (double)p.K;
+    const double bytes = (double)p.batch * K * (double)p.N * (double)p.esize();
+    double again;                                                              // bytes per us
+    if (p.layout == 1) again = p.dtype == DT_F32 ? 12e6 * K / (K + 600.0) : 16e6 * K / (K + 900.0);
+    else again = p.dtype == DT_F32 ? 11e6 * K / (K + 120.0) : 14e6;
+    return 4.0 + bytes / 6.0e6 + bytes * (rb - 1.0) / again;
+}
+
+// workgroups the streaming kernels launch: column blocks x row blocks x batch x the split along k
+// they choose (never ranges shorter than `k_min` per workgroup)
+int64_t stream_workgroups(const Problem &p, int64_t cols, int64_t k_min)
+{
+    const int64_t blocks = (p.N + cols - 1) / cols * p.batch * ((p.M + 15) / 16);
+    int64_t split = (256 + blocks - 1) / blocks;
+    const int64_t by_k = p.K / k_min > 0 ? p.K / k_min : 1;
+    split = split < by_k ? split : by_k;
+    return blocks * (split > 64 ? 64 : split);
+}
+
+// The streaming variant for p, or -1.  Within a family the first entry is the one tuned on 16 rows
+// x 16384 x 16384; problems on which it would launch fewer than 192 workgroups take the entry
+// with half the columns per workgroup (8 x 4096 x 4096: 13.5 against 20.6 us in bf16, 19 against
+// 38 us in fp32, 8.0 against 10.5 us with B column-major), and more than one block of rows takes
+// the entries that leave B in the caches (32 x 16384 x 1024 in bf16: 9.5 against 18.5 us) or,
+// for a short K and few columns, the four-wave entry (768 x 3072 x 768: 23 against 31 us).
+int stream_variant(const Table &t, const Problem &p)
+{
+    const int f32 = t.first_skinny, b16 = f32 + kNumSkinnyVariants, rc = b16 + kNumSkinny16Variants;
+    int want[3] = {-1, -1, -1};
+    if (p.layout == 0 && p.dtype == DT_F32) {
+        const bool starved = stream_workgroups(p, 128, 2048) < 192 && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 2048);
+        // a few blocks of rows over a long K whose 64-column groups already give every CU a workgroup:
+        // eight waves and no split along k (64 x 4096 x 4096: 31 against 39 us)
+        const bool unsplit = p.M <= 128 && p.K >= 2048 && (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= 192;
+        want[0] = p.M > 16 ? (unsplit ? f32 + 7 : f32 + 1) : starved ? f32 + 14 : f32;
+        want[1] = p.M > 16 ? f32 + 1 : f32;
+    } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {
+        const int base = b16 + (p.dtype == DT_F16 ? kNumSkinny16Variants / 2 : 0);
+        const bool starved = stream_workgroups(p, 256, 1024) < 192 && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
+        want[0] = p.M > 16 ? (p.K <= 2048 && p.N <= 8192 ? base + 3 : base + 1) : starved ? base + 3 : base;
+        want[1] = base;
+    } else if (p.layout == 1) {
+        const int per = kNumSkinnyRcVariants / 4;
+        const int base = rc + per * (p.dtype == DT_F32 ? 0 : p.dtype == DT_BF16 ? 1 : p.dtype == DT_F16 ? 2 : 3);
+        const int64_t k_min = 32 * 256 / p.esize();               // 32 steps of 256 bytes
+        const bool starved = stream_workgroups(p, 64, k_min) < 192 && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min);
+        want[0] = starved ? base + 2 : base;
+        want[1] = base;
+    }
+    for (int i : want)
+        if (i >= 0 && i < t.first_tile && can_run(t.v[i], p)) return i;
+    // any other entry of the family that takes the problem
+    const int lo = p.layout == 1 ? rc : p.dtype == DT_F32 ? f32 : b16;
+    const int hi = p.layout == 1 ? t.first_tile : p.dtype == DT_F32 ? b16 : rc;
+    if (p.layout <= 1)
+        for (int i = lo; i < hi; ++i)
+            if (can_run(t.v[i], p)) return i;
+    return -1;
+}
+
+// Up to 16 rows: the streaming kernels.  Else a variant that copies an operand into the layout
+// a faster kernel wants and declares the problem worth it; else the smaller estimate of the
+// streaming variant and the best tile kernel; then tile kernels without an estimate (the first
+// whose grid gives every CU a workgroup, else the one with most workgroups); then the fallback.
 int select(const Problem &p)
 {
     const Table &t = table();
     constexpr int64_t kComputeUnits = 256;
     if (p.K > 0 && vector_friendly(p)) {
-        if (p.M <= 16)
-            for (int i = t.first_skinny; i < t.first_tile; ++i)
-                if (can_run(t.v[i], p)) return i;
-        if (streaming_beats_tiles(p) && t.first_skinny + 1 < t.first_tile && can_run(t.v[t.first_skinny + 1], p))
-            return t.first_skinny + 1;
-        // column-major B, up to 32 rows, and one row of ring tiles would not fill the chip: two passes
-        // over B still beat it (measured at 16 x 16384 x 16384: fp32 225 against 920 us, bf16 112
-        // against 235, E4M3 57 against 157)
-        if (p.layout == 1 && p.M <= 32 && (p.N + 127) / 128 * p.batch < 2 * kComputeUnits)
-            for (int i = t.first_skinny + kNumSkinnyVariants + kNumSkinny16Variants; i < t.first_tile; ++i)
-                if (can_run(t.v[i], p)) return i;
-        if (streaming16_beats_tiles(p))
-            for (int i = t.first_skinny + kNumSkinnyVariants; i < t.first_tile; ++i)
-                if (can_run(t.v[i], p)) return i;
+        const int sv = stream_variant(t, p);
+        if (sv >= 0 && p.M <= 16) return sv;
+        static const std::vector<Cost> costs = [&t] {
+            std::vector<Cost> c;
+            for (const Variant *v : t.v) c.push_back(cost_of(v));
+            return c;
+        }();
         for (int i = t.first_tile; i < (int)t.v.size(); ++i)
-            if (t.v[i]->prefers && t.v[i]->prefers(p) && can_run(t.v[i], p)) return i;
+            if (costs[i].tf_wg == 0 && t.v[i]->prefers && t.v[i]->prefers(p) && can_run(t.v[i], p)) return i;
         int best = -1;
+        double best_us = 1e30;
+        for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
+            if (costs[i].tf_wg == 0 || !can_run(t.v[i], p)) continue;
+            const double us = tile_estimate_us(t.v[i], costs[i], p);
+            if (us < best_us) { best = i; best_us = us; }
+        }
+        if (sv >= 0 && (best < 0 || stream_estimate_us(p) < best_us)) return sv;
+        if (best >= 0) return best;
         int64_t best_blocks = -1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
             if (!can_run(t.v[i], p)) continue;

@@ -154,8 +154,10 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 4096, 4096, 4096, layout=3) == "xa_ring"
     assert sel(1, 2048, 512, 2048, layout=2, dtype=1).startswith("tile_bf16_cr_")   # too few columns to pay for the copy
     assert sel(1, 16, 16384, 16384, dtype=1).startswith("skinny_bf16_wn1_wk4_cg2")     # 16-bit storage streams B the same way
-    assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_wn1_wk4_cg2")
-    assert sel(1, 64, 16384, 16384, dtype=1).startswith("skinny_bf16")                # four blocks of rows still beat one row of tiles
+    assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_wn1_wk4_cg1")        # too few workgroups with 256 columns each
+    assert sel(1, 8, 4096, 4096).startswith("skinny_f32_wn1_wk4_cg1") and sel(1, 8, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16_dma_wk4_cg2")
+    assert "nt0" in sel(1, 32, 16384, 1024, dtype=1)                                   # two blocks of rows: B is left in the caches
+    assert sel(1, 32, 16384, 16384, dtype=1).startswith("skinny_bf16")                # two blocks of rows still beat one row of tiles
     assert not sel(1, 64, 32768, 4096, dtype=1).startswith("skinny")                 # ... but not with a short K
     assert not sel(1, 256, 16384, 16384, dtype=1).startswith("skinny")
     # column-major C (layout + 4): the transposed problem, served by kernels that take a bias down the rows
@@ -168,7 +170,12 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 8192, 8192, 8192, layout=0, dtype=3) == "xk_ring_f8"                            # ... otherwise copied that way
     assert sel(1, 100, 100, 100, layout=0, dtype=3) == "generic_64x64"
     assert sel(1, 16, 16384, 16384, layout=1).startswith("skinnyrc_f32_dma_wk4_cg4_ns2")                # column-major B: streamed too
-    assert sel(1, 32, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and not sel(1, 48, 16384, 16384, layout=1, dtype=1).startswith("skinny")
+    assert sel(1, 32, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and not sel(1, 512, 16384, 16384, layout=1, dtype=1).startswith("skinny")
+    # by estimated time: a few blocks of rows streamed, then the smallest tiles that waste no rows
+    assert sel(1, 64, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16") and sel(1, 64, 4096, 4096, layout=1).startswith("skinnyrc_f32")
+    assert sel(1, 128, 8192, 8192, layout=1, dtype=1).startswith("direct_bf16_rc_128x128")
+    assert sel(1, 2048, 2048, 2048, dtype=1).startswith("direct_bf16_rr_128x128") and sel(1, 4096, 4096, 4096, dtype=1).startswith("ring_bf16_rr_256x256")
+    assert sel(1, 4096, 512, 4096).startswith("skinny_f32") and sel(1, 512, 8192, 256).startswith("ring_f32_rr_128x128")
     assert sel(1, 16, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and sel(1, 3, 4096, 4096, layout=1, dtype=3).startswith("skinnyrc_f8")
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
@@ -180,7 +187,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 512, 512, 512, A=P + 4).startswith("generic")
     assert sel(1, 512, 512, 512, lda=513).startswith("generic")
     assert sel(1, 512, 510, 512, ldb=512, ldc=512).startswith("generic")  # N % 4 != 0 with row-major B
-    assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("tile_f32_rc")   # fine when k is contiguous
+    assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("skinnyrc_f32")  # fine when k is contiguous
     assert sel(1, 16, 1024, 1022, lda=1024).startswith("generic")
     assert sel(1, 16, 1024, 1024, dtype=1).startswith("skinny_bf16")
     assert sel(1, 8, 8, 8, layout=8) == ob.ERR_INVALID_ARG

@@ -454,12 +454,13 @@ def test_dispatch_random_shapes_in_e4m3(t, M, N, K, layout, dtype, act, pad, use
 def test_e4m3_matrix_pipe_kernel_is_the_dispatchers_choice_and_sees_every_k():
     """A row-major, B column-major, K a multiple of 64: the ring kernel.  One-hot rows of A pick single k positions,
     so a fragment byte fed to the wrong k slot of the matrix instruction cannot hide."""
-    M, N, K = 256, 256, 256
+    M, N, K = 4096, 4096, 4096
     v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, K, 0, 0x1000, 0, 0x1000, N, 0, 1, F8, 0)
     assert ob.optiml_variant_name(v).startswith("ring_f8_rc")
+    M, N, K = 256, 256, 512                   # (a problem this small is streamed by the dispatcher: forced here)
     A = np.zeros((M, K), dtype=np.float32); A[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
     B = synth.integers(977, "B", K, N, -8, 8)
-    check_against_oracle(A, B, None, dtype=F8, act=synth.ACT_NONE, layout=1, exact=True, entry="ex")
+    check_against_oracle(A, B, None, dtype=F8, act=synth.ACT_NONE, layout=1, exact=True, variant=v)
     A = synth.normal(978, "A", 520, 1024); B = synth.normal(978, "B", 1024, 776); bias = synth.normal(978, "bias", 1, 776)[0]
     check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_GELU_TANH, layout=1, entry="ex")
 
