@@ -11,6 +11,7 @@ namespace optiml {
 namespace {
 
 thread_local int tls_last_hip_error = 0;
+thread_local size_t tls_workspace_head = 0;      // see WorkspaceHead
 
 struct Table {
     std::vector<const Variant *> v;
@@ -216,32 +217,38 @@ int stream_variant(const Table &t, const Problem &p)
 }
 
 // Up to 16 rows: the streaming kernels.  Else a variant that copies an operand into the layout
-// a faster kernel wants and declares the problem worth it; else the smaller estimate of the
-// streaming variant and the best tile kernel; then tile kernels without an estimate (the first
-// whose grid gives every CU a workgroup, else the one with most workgroups); then the fallback.
-int select(const Problem &p)
+// a faster kernel wants and declares the problem worth it; else the smallest estimate among the
+// streaming variant, the tile kernels and the variants that bring their own estimate; then tile
+// kernels without an estimate (the first whose grid gives every CU a workgroup, else the one with
+// most workgroups); then the fallback.
+int select(const Problem &p, double *estimate_us = nullptr, bool allow_streaming = true)
 {
     const Table &t = table();
     constexpr int64_t kComputeUnits = 256;
+    double unused;
+    double &us_out = estimate_us ? *estimate_us : unused;
+    us_out = 1e30;
     if (p.K > 0 && vector_friendly(p)) {
-        const int sv = stream_variant(t, p);
-        if (sv >= 0 && p.M <= 16) return sv;
+        const int sv = allow_streaming ? stream_variant(t, p) : -1;
+        const double stream_us = sv >= 0 ? stream_estimate_us(p) : 1e30;
+        if (sv >= 0 && p.M <= 16) { us_out = stream_us; return sv; }
         static const std::vector<Cost> costs = [&t] {
             std::vector<Cost> c;
             for (const Variant *v : t.v) c.push_back(cost_of(v));
             return c;
         }();
         for (int i = t.first_tile; i < (int)t.v.size(); ++i)
-            if (costs[i].tf_wg == 0 && t.v[i]->prefers && t.v[i]->prefers(p) && can_run(t.v[i], p)) return i;
+            if (costs[i].tf_wg == 0 && !t.v[i]->estimate_us && t.v[i]->prefers && t.v[i]->prefers(p) && can_run(t.v[i], p))
+                return i;
         int best = -1;
         double best_us = 1e30;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
-            if (costs[i].tf_wg == 0 || !can_run(t.v[i], p)) continue;
-            const double us = tile_estimate_us(t.v[i], costs[i], p);
+            if ((costs[i].tf_wg == 0 && !t.v[i]->estimate_us) || !can_run(t.v[i], p)) continue;
+            const double us = t.v[i]->estimate_us ? t.v[i]->estimate_us(p) : tile_estimate_us(t.v[i], costs[i], p);
             if (us < best_us) { best = i; best_us = us; }
         }
-        if (sv >= 0 && (best < 0 || stream_estimate_us(p) < best_us)) return sv;
-        if (best >= 0) return best;
+        if (sv >= 0 && (best < 0 || stream_us < best_us)) { us_out = stream_us; return sv; }
+        if (best >= 0) { us_out = best_us; return best; }
         int64_t best_blocks = -1;
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
             if (!can_run(t.v[i], p)) continue;
@@ -310,6 +317,17 @@ bool vector_friendly(const Problem &p)
     return true;
 }
 
+int select_variant(const Problem &p, double *estimate_us, bool allow_streaming) { return select(p, estimate_us, allow_streaming); }
+
+const Variant *variant_at(int id)
+{
+    const Table &t = table();
+    return id >= 0 && id < (int)t.v.size() ? t.v[id] : nullptr;
+}
+
+WorkspaceHead::WorkspaceHead(size_t bytes) { tls_workspace_head = (bytes + 255) & ~size_t(255); }
+WorkspaceHead::~WorkspaceHead() { tls_workspace_head = 0; }
+
 int compute_units()
 {
     static int cus[64] = {};
@@ -331,7 +349,10 @@ hipError_t workspace(size_t bytes, void **ptr)
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
     DeviceScratch &s = g_scratch[dev];
+    const size_t head = tls_workspace_head;
+    bytes += head;
     if (s.bytes < bytes) {
+        if (head) return hipErrorOutOfMemory;     // the holder of the head did not size the buffer: refuse to drop its copy
         if (s.ptr) {
             e = hipFree(s.ptr);      // waits for work that may still read the old buffer
             s.ptr = nullptr; s.bytes = 0;
@@ -342,7 +363,7 @@ hipError_t workspace(size_t bytes, void **ptr)
         if (e != hipSuccess) { s.ptr = nullptr; return e; }
         s.bytes = want;
     }
-    *ptr = s.ptr;
+    *ptr = static_cast<char *>(s.ptr) + head;
     return hipSuccess;
 }
 

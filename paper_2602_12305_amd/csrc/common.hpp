@@ -37,7 +37,16 @@ struct Variant {
     // before it in the table; the dispatcher asks these first
     bool (*prefers)(const Problem &) = nullptr;
     bool row_bias = false;   // handles Problem::bias_row
+    // optional: the variant's own estimate of its time on p in microseconds (the dispatcher compares
+    // it with its estimates for the other kernels)
+    double (*estimate_us)(const Problem &) = nullptr;
 };
+
+// The dispatcher's choice for p: index into the variant table (or a negative OPTIML_ERR_*) and,
+// if asked, the time it expects in microseconds.  allow_streaming = false leaves out the kernels
+// that take a second buffer in the workspace.
+int select_variant(const Problem &p, double *estimate_us, bool allow_streaming = true);
+const Variant *variant_at(int id);
 
 // every pointer 16-byte aligned, every ld / batch stride a whole number of 16-byte chunks
 bool vector_friendly(const Problem &p);
@@ -48,6 +57,16 @@ int compute_units();
 // per-device scratch (split-K partial sums, reduction partials, the row-major copy of a
 // column-major A): grown on demand, never shrunk
 hipError_t workspace(size_t bytes, void **ptr);
+// While one of these lives, workspace() on this thread hands out the memory behind the first
+// `bytes` of the buffer: a launcher that keeps a copy of an operand there can call kernels that
+// ask for scratch of their own.  It must have sized the buffer for both beforehand (one
+// workspace(bytes + the callee's need) call): growing the buffer would drop the copy.
+struct WorkspaceHead {
+    explicit WorkspaceHead(size_t bytes);
+    ~WorkspaceHead();
+    WorkspaceHead(const WorkspaceHead &) = delete;
+    WorkspaceHead &operator=(const WorkspaceHead &) = delete;
+};
 
 // streaming siblings (kernel_streams.hip); arguments already validated
 hipError_t launch_elementwise(int64_t n, const float *x, float *y, int op, hipStream_t stream);

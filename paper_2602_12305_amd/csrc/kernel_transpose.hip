@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void transpose_any_kernel(const E *__restrict_
         if (c0 + c < cols && r0 + tx < rows) dst[(c0 + c) * ld_dst + r0 + tx] = tile[tx][c];
 }
 
-// the problem the ring kernel sees: A row-major in the workspace
+// the problem the second kernel sees: A row-major in the workspace
 Problem with_row_major_a(const Problem &p, const void *a)
 {
     Problem q = p;
@@ -87,17 +87,24 @@ Problem with_row_major_a(const Problem &p, const void *a)
     return q;
 }
 
-const Variant *ring_for(const Problem &q)
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// The streaming kernels keep split-k partial sums in the workspace, behind the copy of A: at most
+// 64 splits of [batch][blocks of 16 rows][16][N] floats.  Beyond this bound the copy is followed
+// by a kernel that needs no scratch.
+constexpr size_t kMaxPartialBytes = size_t(1) << 30;
+size_t partial_bound(const Problem &p)
 {
-    const Variant *t = tile_variants();
-    const Variant *first = nullptr;
-    for (int i = 0; i < kNumTileVariants; ++i) {
-        if (t[i].name[0] != 'r' || !t[i].supports(q)) continue;        // "ring..." / "ringp..."
-        if (q.bias_row && q.bias && !t[i].row_bias) continue;
-        if (t[i].prefers && t[i].prefers(q)) return &t[i];
-        if (!first) first = &t[i];
-    }
-    return first;
+    return sizeof(float) * 64 * (size_t)p.batch * (size_t)((p.M + 15) / 16) * 16 * (size_t)p.N;
+}
+
+// the kernel that follows the copy: the dispatcher's choice for the row-major problem
+int second_kernel(const Problem &p, double *us)
+{
+    const Problem q = with_row_major_a(p, reinterpret_cast<const void *>(uintptr_t(256)));
+    const int id = select_variant(q, us, partial_bound(p) <= kMaxPartialBytes);
+    const Variant *v = variant_at(id);
+    return v && v->name[0] != 'g' ? id : -1;                   // not the guarded fallback: no gain in copying for it
 }
 
 bool xa_supports(const Problem &p)
@@ -107,23 +114,27 @@ bool xa_supports(const Problem &p)
     if (p.M % ch != 0 || p.K % ch != 0) return false;
     const int64_t T = 256 / p.esize();
     if (p.batch * ((p.M + T - 1) / T) * ((p.K + T - 1) / T) > 0x7fffffffLL) return false;
-    return ring_for(with_row_major_a(p, reinterpret_cast<const void *>(uintptr_t(256)))) != nullptr;
+    return second_kernel(p, nullptr) >= 0;
 }
 
-// worth the copy: enough columns to amortise it, and enough work to fill the chip with ring tiles
-bool xa_prefers(const Problem &p)
+// the copy (read and write of A at about 5 TB/s, one launch) plus the second kernel
+double xa_estimate(const Problem &p)
 {
-    return p.N >= 1024 && p.batch * ((p.M + 127) / 128) * ((p.N + 127) / 128) >= 256;
+    double us = 1e30;
+    if (second_kernel(p, &us) < 0) return 1e30;
+    return us + 3.0 + 2.0 * (double)p.batch * (double)p.M * (double)p.K * p.esize() / 5.0e6;
 }
 
 hipError_t xa_launch(const Problem &p, hipStream_t s)
 {
+    const Variant *second = variant_at(second_kernel(p, nullptr));
+    if (!second) return hipErrorInvalidValue;
+    const size_t copy = align256((size_t)p.batch * p.M * p.K * p.esize());
+    const size_t more = second->name[0] == 's' ? partial_bound(p) : 0;        // "skinny...": split-k partials
     void *ws = nullptr;
-    hipError_t e = workspace((size_t)p.batch * p.M * p.K * p.esize(), &ws);
+    hipError_t e = workspace(copy + more, &ws);
     if (e != hipSuccess) return e;
     const Problem q = with_row_major_a(p, ws);
-    const Variant *ring = ring_for(q);
-    if (!ring) return hipErrorInvalidValue;
     const int64_t T = 256 / p.esize();
     const int64_t tiles_c = (p.M + T - 1) / T, tiles_r = (p.K + T - 1) / T;
     const dim3 grid((unsigned)(p.batch * tiles_c * tiles_r));
@@ -135,7 +146,8 @@ hipError_t xa_launch(const Problem &p, hipStream_t s)
                            static_cast<uint16_t *>(ws), p.K, p.M, p.lda, p.strideA, tiles_c, tiles_r, p.K);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return ring->launch(q, s);
+    const WorkspaceHead keep(copy);          // the second kernel's scratch, if any, goes behind the copy
+    return second->launch(q, s);
 }
 
 // ---- 8-bit operands: the matrix-pipe kernel wants k contiguous in BOTH operands -----------------
@@ -155,7 +167,18 @@ hipError_t copy_transposed(const void *src, void *dst, int64_t batch, int64_t ro
     return hipGetLastError();
 }
 
-size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+const Variant *ring_for(const Problem &q)
+{
+    const Variant *t = tile_variants();
+    const Variant *first = nullptr;
+    for (int i = 0; i < kNumTileVariants; ++i) {
+        if (t[i].name[0] != 'r' || !t[i].supports(q)) continue;        // "ring..." / "ringp..."
+        if (q.bias_row && q.bias && !t[i].row_bias) continue;
+        if (t[i].prefers && t[i].prefers(q)) return &t[i];
+        if (!first) first = &t[i];
+    }
+    return first;
+}
 
 Problem with_k_contiguous(const Problem &p, const void *a, const void *b)
 {
@@ -236,7 +259,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *transpose_variants()
 {
     static const Variant v[] = {{"xa_ring", xa_supports, xa_launch, 256, 256,
-                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), xa_prefers, true},
+                                 reinterpret_cast<const void *>(&transpose_kernel<uint16_t>), nullptr, true, xa_estimate},
                                 {"xk_ring_f8", x8_supports, x8_launch, 256, 256,
                                  reinterpret_cast<const void *>(&transpose_kernel<uint8_t>), x8_prefers, true}};
     return v;

@@ -152,7 +152,8 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 1000, 1001, 64, dtype=2) == "generic_64x64"
     assert sel(1, 8192, 8192, 8192, layout=2, dtype=1) == "xa_ring"       # column-major A: row-major copy, then a ring kernel
     assert sel(1, 4096, 4096, 4096, layout=3) == "xa_ring"
-    assert sel(1, 2048, 512, 2048, layout=2, dtype=1).startswith("tile_bf16_cr_")   # too few columns to pay for the copy
+    assert sel(1, 64, 64, 64, layout=2, dtype=1).startswith("tile_bf16_cr_")        # too little work to pay for the copy
+    assert sel(1, 64, 4096, 4096, layout=2, dtype=1) == "xa_ring"                   # ... a few rows: copied, then streamed
     assert sel(1, 16, 16384, 16384, dtype=1).startswith("skinny_bf16_wn1_wk4_cg2")     # 16-bit storage streams B the same way
     assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_wn1_wk4_cg1")        # too few workgroups with 256 columns each
     assert sel(1, 8, 4096, 4096).startswith("skinny_f32_wn1_wk4_cg1") and sel(1, 8, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16_dma_wk4_cg2")
@@ -180,7 +181,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays
-    assert sel(1, 256, 256, 256, layout=2).startswith("tile_f32_cr_64x64")   # too few blocks for larger tiles
+    assert sel(1, 256, 256, 256, layout=2) == "xa_ring"                       # copied, then streamed like the row-major problem
     assert sel(1, 1024, 1024, 64, layout=3, dtype=1).startswith("tile_bf16_cc_")
     # K = 0, misaligned base, odd leading dimension, ragged contiguous extent -> guarded fallback
     assert sel(1, 64, 64, 0).startswith("generic")
