@@ -167,19 +167,6 @@ hipError_t copy_transposed(const void *src, void *dst, int64_t batch, int64_t ro
     return hipGetLastError();
 }
 
-const Variant *ring_for(const Problem &q)
-{
-    const Variant *t = tile_variants();
-    const Variant *first = nullptr;
-    for (int i = 0; i < kNumTileVariants; ++i) {
-        if (t[i].name[0] != 'r' || !t[i].supports(q)) continue;        // "ring..." / "ringp..."
-        if (q.bias_row && q.bias && !t[i].row_bias) continue;
-        if (t[i].prefers && t[i].prefers(q)) return &t[i];
-        if (!first) first = &t[i];
-    }
-    return first;
-}
-
 Problem with_k_contiguous(const Problem &p, const void *a, const void *b)
 {
     Problem q = p;
@@ -189,13 +176,20 @@ Problem with_k_contiguous(const Problem &p, const void *a, const void *b)
     return q;
 }
 
+// the kernel that follows the copies: the dispatcher's choice for the k-contiguous problem
+const Variant *second_kernel_f8(const Problem &p)
+{
+    const void *fake = reinterpret_cast<const void *>(uintptr_t(256));
+    const Variant *v = variant_at(select_variant(with_k_contiguous(p, fake, fake), nullptr, partial_bound(p) <= kMaxPartialBytes));
+    return v && v->name[0] != 'g' ? v : nullptr;
+}
+
 bool x8_supports(const Problem &p)
 {
     if (p.dtype != DT_F8 || (!p.a_col() && p.b_col()) || p.K < 1 || !vector_friendly(p)) return false;
     if (p.K % 16 != 0 || (p.a_col() && p.M % 16 != 0) || (!p.b_col() && p.N % 16 != 0)) return false;
     if (p.batch * ((p.M + 255) / 256 + (p.N + 255) / 256) * ((p.K + 255) / 256) > 0x7fffffffLL) return false;
-    const void *fake = reinterpret_cast<const void *>(uintptr_t(256));
-    return ring_for(with_k_contiguous(p, fake, fake)) != nullptr;
+    return second_kernel_f8(p) != nullptr;
 }
 
 // the alternative is the element-wise fallback: worth it as soon as there is a tile's worth of work
@@ -203,15 +197,16 @@ bool x8_prefers(const Problem &p) { return p.M * p.N >= 65536 && p.K >= 256; }
 
 hipError_t x8_launch(const Problem &p, hipStream_t s)
 {
+    const Variant *second = second_kernel_f8(p);
+    if (!second) return hipErrorInvalidValue;
     const size_t a_bytes = p.a_col() ? align256((size_t)p.batch * p.M * p.K) : 0;
     const size_t b_bytes = !p.b_col() ? align256((size_t)p.batch * p.N * p.K) : 0;
+    const size_t more = second->name[0] == 's' ? partial_bound(p) : 0;        // "skinny...": split-k partials
     void *ws = nullptr;
-    hipError_t e = workspace(a_bytes + b_bytes, &ws);
+    hipError_t e = workspace(a_bytes + b_bytes + more, &ws);
     if (e != hipSuccess) return e;
     void *wa = ws, *wb = static_cast<char *>(ws) + a_bytes;
     const Problem q = with_k_contiguous(p, wa, wb);
-    const Variant *ring = ring_for(q);
-    if (!ring) return hipErrorInvalidValue;
     if (p.a_col()) {
         e = copy_transposed<uint8_t>(p.A, wa, p.batch, p.K, p.M, p.lda, p.strideA, s);
         if (e != hipSuccess) return e;
@@ -220,7 +215,8 @@ hipError_t x8_launch(const Problem &p, hipStream_t s)
         e = copy_transposed<uint8_t>(p.B, wb, p.batch, p.K, p.N, p.ldb, p.strideB, s);
         if (e != hipSuccess) return e;
     }
-    return ring->launch(q, s);
+    const WorkspaceHead keep(a_bytes + b_bytes);     // the second kernel's scratch, if any, goes behind the copies
+    return second->launch(q, s);
 }
 
 }  // namespace

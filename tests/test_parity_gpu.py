@@ -484,6 +484,18 @@ def test_e4m3_matrix_pipe_kernel_is_the_dispatchers_choice_and_sees_every_k():
     check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_GELU_TANH, layout=1, entry="ex")
 
 
+@pytest.mark.parametrize("layout", [0, 2, 3])
+def test_e4m3_copies_followed_by_a_streaming_kernel(layout):
+    """8-bit operands whose k is not contiguous, a few rows, a long K: after the copies the dispatcher's choice is the
+    streaming kernel, whose split-k partial sums go behind the copies in the workspace."""
+    for t, (batch, M, N, K) in enumerate([(1, 48, 1024, 4096), (2, 80, 2048, 2048), (1, 48, 1024, 4096)]):
+        A = synth.normal(985 + t, "A", M, K, batch=batch); B = synth.normal(985 + t, "B", K, N, batch=batch)
+        bias = synth.normal(985 + t, "bias", 1, N, batch=batch).reshape(batch, N)
+        check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout)
+        Ai = synth.integers(990 + t, "A", M, K, batch=batch); Bi = synth.integers(990 + t, "B", K, N, batch=batch)
+        check_against_oracle(Ai, Bi, None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True)
+
+
 @pytest.mark.parametrize("layout", [0, 1, 2, 3, 5])
 def test_e4m3_storage_multi_tile_shapes_and_specials(layout):
     """8-bit E4M3 operands, bf16 result: several tiles with a batch, exact on integers, and every one of the 256 bit
