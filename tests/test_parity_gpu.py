@@ -126,6 +126,23 @@ def test_persistent_variants_walk_several_tiles(vid):
     check_against_oracle(Ai, Bi, bi, dtype=BF16, act=synth.ACT_NONE, layout=layout, variant=vid, exact=True)
 
 
+# ---- L1: many blocks of 16 rows through the streaming kernels (the dispatcher's choice by estimated time) ----
+@pytest.mark.parametrize("dtype,layout", [(F32, 0), (F32, 1), (BF16, 1), (F16, 0)])
+def test_streaming_kernels_with_many_row_blocks(dtype, layout):
+    """More than a hundred blocks of 16 rows (grid.z), a ragged last block, ragged N and a k tail: every block
+    must read its own rows of A and write its own rows of C."""
+    M, N, K = 2100, 520, 776
+    ldb = K if layout & 1 else N
+    v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, ldb, 0, 0x1000, 0, 0x1000, N, 0, layout, dtype, 0)
+    forced = None
+    if not ob.optiml_variant_name(v).startswith("skinny"):            # 16-bit row-major: tiles win at this size
+        forced = [i for i, n in enumerate(ob.variant_names()) if n.startswith("skinny_f16")][1]
+    A = synth.normal(1500, "A", M, K); B = synth.normal(1500, "B", K, N); bias = synth.normal(1500, "bias", 1, N)[0]
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=forced)
+    Ai = synth.integers(1501, "A", M, K); Bi = synth.integers(1501, "B", K, N)
+    check_against_oracle(Ai, Bi, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=forced, exact=True)
+
+
 # ---- L1: dispatcher over seeded random shapes, all layouts / dtypes / acts / paddings --------
 def fuzz_cases():
     rng = np.random.default_rng(2602)
