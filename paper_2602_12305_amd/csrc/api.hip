@@ -78,7 +78,7 @@ bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 // 128 x 8192 x 8192, 1024^3, 2048^3 (part of the chip), in us and TFLOP/s:
 //   ring 256x256 (16-bit) 8 + f / 4.9      ring 256x256 (8-bit, 64-deep) 8 + f / 9.0, else f / 6.6
 //   persistent ring       4.3 + f / 4.56   (more tiles than CUs only)
-//   direct 256x256 5 + f / 4.3             direct 256x128 3 + f / 3.5
+//   direct 256x256 8.5 + f / 4.4           direct 256x128 7.5 + f / 3.86
 //   direct 128x128 2.7 + f / 2.56, 1.45 workgroups' worth per CU
 //   staged 16-bit 256x256 5 + f / 2.0, 256x128 4 + f / 1.8, 128x128 3 + f / 1.17 (1.8 per CU)
 //   fp32 ring 128x128 3 + f / 0.548, 256x128 3 + f / 0.53
@@ -117,8 +117,8 @@ Cost cost_of(const Variant *v)
     else if (starts_with(n, "ring_")) { c.fixed_us = 8.0f; c.tf_wg = 4.9f; c.boost = true; }
     else if (starts_with(n, "direct_")) {
         c.boost = true;
-        if (v->bm == 256 && v->bn == 256) { c.fixed_us = 5.0f; c.tf_wg = 4.3f; }
-        else if (v->bm == 256) { c.fixed_us = 3.0f; c.tf_wg = 3.5f; }
+        if (v->bm == 256 && v->bn == 256) { c.fixed_us = 8.5f; c.tf_wg = 4.4f; }
+        else if (v->bm == 256) { c.fixed_us = 7.5f; c.tf_wg = 3.86f; }
         else { c.fixed_us = 2.7f; c.tf_wg = 2.56f; c.share = 1.45f; }
     } else if (starts_with(n, "tile_") && f32) {
         if (v->bm == 256) { c.fixed_us = 4.0f; c.tf_wg = 0.41f; }
@@ -188,8 +188,10 @@ int stream_variant(const Table &t, const Problem &p)
     if (p.layout == 0 && p.dtype == DT_F32) {
         const bool starved = stream_workgroups(p, 128, 2048) < 192 && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 2048);
         // a few blocks of rows over a long K whose 64-column groups already give every CU a workgroup:
-        // eight waves and no split along k (64 x 4096 x 4096: 31 against 39 us)
-        const bool unsplit = p.M <= 128 && p.K >= 2048 && (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= 192;
+        // eight waves and no split along k (64 x 4096 x 4096: 31 against 39 us; not beyond 8192 x 8192, where
+        // 64 x 16384 x 16384 takes 744 against 524 us)
+        const bool unsplit = p.M <= 128 && p.K >= 2048 && (double)p.K * (double)p.N <= 67108864.0 &&
+                             (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= 192;
         want[0] = p.M > 16 ? (unsplit ? f32 + 7 : f32 + 1) : starved ? f32 + 14 : f32;
         want[1] = p.M > 16 ? f32 + 1 : f32;
     } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {

@@ -99,7 +99,7 @@ const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
-constexpr int kDirectPerUnit = 4;          // direct-to-LDS bf16 kernels per B layout
+constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
 constexpr int kRingPerUnit = 4;            // ring-of-stages bf16 kernels per B layout (three one-tile, one persistent)
 constexpr int kRingF32PerUnit = 3;         // ring-of-stages fp32 kernels per B layout
 

@@ -45,8 +45,9 @@ struct Params {
     int act;
 };
 
-template <int BM_, int BN_, int WM_, int WN_, bool B_KC_>
+template <int BM_, int BN_, int WM_, int WN_, bool B_KC_, int DT_ = DT_BF16>
 struct Cfg {
+    static constexpr int DT = DT_;       // DT_BF16 or DT_F16: another matrix instruction and rounding, nothing else
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, BK = 64;
     static constexpr bool B_KC = B_KC_;
     static constexpr int NW = WM * WN, THREADS = 64 * NW;
@@ -141,9 +142,7 @@ __device__ __forceinline__ void tile_step(const StepCtx<C> &c, const char *__res
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[s & 1][j]),
-                                                                    __builtin_bit_cast(bf16x8, fa[s & 1][i]),
-                                                                    acc[j][i], 0, 0, 0);
+                acc[j][i] = mfma_32x32x16<C::DT>(fb[s & 1][j], fa[s & 1][i], acc[j][i]);
     }
     wait_vmem();
     __syncthreads();
@@ -312,7 +311,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
                 for (int e = 0; e < 4; ++e) y[e] = apply_act_bf16out(acc[j][i][4 * gq + e] + bj[j][gq][e], ACT);
                 *reinterpret_cast<__attribute__((address_space(3))) uintx2 *>(
                     slab + frag_row * PITCH + (32 * j + 8 * gq + 4 * half) * 2) =
-                    uintx2{f32x2_to_bf16x2(y[0], y[1]), f32x2_to_bf16x2(y[2], y[3])};
+                    uintx2{pack2_16<C::DT>(y[0], y[1]), pack2_16<C::DT>(y[2], y[3])};
             }
 #pragma unroll
         for (int q = 0; q < READS; ++q) {
@@ -339,7 +338,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
 template <class C>
 bool supports(const Problem &p)
 {
-    if (p.dtype != DT_BF16 || p.a_col() || p.b_col() != C::B_KC) return false;
+    if (p.dtype != C::DT || p.a_col() || p.b_col() != C::B_KC) return false;
     if (p.K < 64 || p.K % 64 != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 8 != 0)) return false;
     // per-lane source offsets are 32-bit

@@ -6,12 +6,12 @@ namespace optiml {
 const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc();
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
 const Variant *kTile_f16_rr(), *kTile_f16_rc(), *kTile_f16_cr(), *kTile_f16_cc();
-const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc();
+const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc(), *kDirect_f16_rr(), *kDirect_f16_rc();
 const Variant *kRing_bf16_rr(), *kRing_bf16_rc(), *kRing_f16_rr(), *kRing_f16_rc(), *kRing_f8_rc();
 const Variant *kRing_f32_rr(), *kRing_f32_rc();
 
 namespace {
-constexpr int kTotal = 12 * kTilesPerUnit + 2 * kDirectPerUnit + 5 * kRingPerUnit + 2 * kRingF32PerUnit;
+constexpr int kTotal = 12 * kTilesPerUnit + 4 * kDirectPerUnit + 5 * kRingPerUnit + 2 * kRingF32PerUnit;
 struct Gather {
     Variant v[kTotal];
     Gather()
@@ -34,6 +34,8 @@ struct Gather {
         // fp16 after everything that existed before it, so that variant indices stay put
         add(kRing_f16_rr(), kRingPerUnit);
         add(kRing_f16_rc(), kRingPerUnit);
+        add(kDirect_f16_rr(), kDirectPerUnit);
+        add(kDirect_f16_rc(), kDirectPerUnit);
         add(kTile_f16_rr(), kTilesPerUnit);
         add(kTile_f16_rc(), kTilesPerUnit);
         add(kTile_f16_cr(), kTilesPerUnit);

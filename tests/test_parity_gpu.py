@@ -53,7 +53,7 @@ def problem_for(name):
         return BF16, 2, 304, 392, 480                      # A column-major, M and K whole 16-byte chunks
     if name.startswith("direct"):
         _, dt, lay = name.split("_")[:3]
-        return BF16, LAYOUT_OF[lay], 300, 392, 320          # K a multiple of 64
+        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, 320      # K a multiple of 64
     if name.startswith("tile"):
         _, dt, lay = name.split("_")[:3]
         dtype = DT_OF[dt]
