@@ -93,7 +93,7 @@ TRAFFIC = {
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
         {"bytes": int((609902.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "10ec44f15caf0a01"},
     ("s_transpose", "s_transpose"):
-        {"bytes": int((524326.7 * 2.0 + 1048853.8) * 1024), "files": TRANSPOSE_SRC, "src": "e58e62a4e32315d6"},
+        {"bytes": int((524327.0 * 2.0 + 1048910.0) * 1024), "files": TRANSPOSE_SRC, "src": "00f7350d0ac9d4a0"},
     ("s_mhsa", "s_mhsa"):
         {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "a4876881c0272702"},
     ("s_lce", "s_lce"):
