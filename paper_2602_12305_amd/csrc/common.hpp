@@ -34,7 +34,7 @@ struct Variant {
     int bm, bn;   // C block computed by one workgroup (0, 0 where that does not apply)
     const void *kernel;   // host handle of the variant's main kernel, for hipFuncGetAttributes
     // optional: true for problems on which this variant was measured faster than the ones
-    // before it in the table; the dispatcher asks these first
+    // before it in the table; the dispatcher asks it of variants it has no time estimate for
     bool (*prefers)(const Problem &) = nullptr;
     bool row_bias = false;   // handles Problem::bias_row
     // optional: the variant's own estimate of its time on p in microseconds (the dispatcher compares
