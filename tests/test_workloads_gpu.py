@@ -90,3 +90,13 @@ def test_workload_shape_is_exact_on_integers(name):
     elif w.dtype == synth.DTYPE_F16:
         ref = oracle.f16_to_double(oracle.f16_from_double(ref))
     assert np.array_equal(got, ref)
+
+
+def test_dispatcher_choice_is_near_the_fastest_variant_on_a_few_clear_cases():
+    """Shapes on which the right family wins by 3x or more (streaming against tiles for a few rows, tiles against
+    streaming for thousands): the dispatcher's choice must be within 2.5x of the fastest variant that takes the
+    shape.  A coarse guard against a mis-calibrated estimate; the full comparison is `dispatch_check`."""
+    from paper_2602_12305_amd import dispatch_check
+    for case in dispatch_check.SETS["quick"]:
+        pn, pt, bn, bt = dispatch_check.check(*case, steps=10)
+        assert pt <= 2.5 * bt, (case, pn, pt, bn, bt)
