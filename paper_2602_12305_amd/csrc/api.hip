@@ -192,12 +192,15 @@ int stream_variant(const Table &t, const Problem &p)
         // 64 x 16384 x 16384 takes 744 against 524 us)
         const bool unsplit = p.M <= 128 && p.K >= 2048 && (double)p.K * (double)p.N <= 67108864.0 &&
                              (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= 192;
-        want[0] = p.M > 16 ? (unsplit ? f32 + 7 : f32 + 1) : starved ? f32 + 14 : f32;
+        want[0] = p.M > 16 ? (unsplit ? f32 + 7 : starved && p.K >= 4096 ? f32 + 14 : f32 + 1) : starved ? f32 + 14 : f32;
         want[1] = p.M > 16 ? f32 + 1 : f32;
     } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {
         const int base = b16 + (p.dtype == DT_F16 ? kNumSkinny16Variants / 2 : 0);
         const bool starved = stream_workgroups(p, 256, 1024) < 192 && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
-        want[0] = p.M > 16 ? (p.K <= 2048 && p.N <= 8192 ? base + 3 : base + 1) : starved ? base + 3 : base;
+        // more than 16 rows: the eight-wave entry (128 columns, k ranges of 2048 or more) unless it is starved too
+        const bool starved8 = stream_workgroups(p, 128, 2048) < 192 && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 128, 2048);
+        if (p.M > 16) want[0] = starved8 || (p.K <= 2048 && p.N <= 8192) ? base + 3 : base + 1;
+        else want[0] = starved ? base + 3 : base;
         want[1] = base;
     } else if (p.layout == 1) {
         const int per = kNumSkinnyRcVariants / 4;
