@@ -51,8 +51,9 @@
  *   Results    Repeating a call with the same arguments gives bitwise the same C
  *              (no floating-point atomics; split-K partial sums are combined in a
  *              fixed order).
- *   Workspace  Split-K kernels keep partial sums, and the fast path for a column-major
- *              A keeps a row-major copy of A (batch x M x K elements), in one
+ *   Workspace  Split-K kernels keep partial sums, and the fast paths for a column-major
+ *              A and for 8-bit operands whose k is not contiguous keep a copy of that
+ *              operand (batch x M x K or batch x N x K elements), in one
  *              per-device buffer that the library allocates on first need and grows
  *              when a larger one is needed (the only allocation the library ever
  *              makes); calls that use it are ordered by the stream they are enqueued
@@ -226,9 +227,9 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
  * replaced by (x - mean) / sqrt(var + eps), mean and biased variance (divide by len) of that
  * row; no scale or shift (the task names none; eps is the caller's, 1e-5 in common use).
  * x[r*len + i] -> y[r*len + i]; y may be x itself.  Statistics and the normalisation are
- * evaluated in fp64 and rounded once to float.  Rows longer than 8192 use the per-device
- * workspace and two kernels per group of rows of about 256 MiB (x is then read twice).  rows == 0 or len == 0 writes
- * nothing.
+ * evaluated in fp64 and rounded once to float.  Rows longer than 32768 (8192 unless x, y are
+ * 16-byte aligned and len % 4 == 0) use the per-device workspace and two kernels per group of
+ * rows of about 256 MiB (x is then read twice).  rows == 0 or len == 0 writes nothing.
  *
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, C < 1, ld < C, NULL loss, NULL
  * logits / labels / x / y with work to do, eps negative or NaN.
