@@ -7,10 +7,10 @@ using namespace skinny;
 #define SKINNY_IL(WN, WK, CG, NT, SPLIT)                                                       \
     {"skinny_f32_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT "_il", skinny_supports,     \
      skinny_launch<WN, WK, CG, NT, SPLIT, true>, 0, 0,                                             \
-     reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT, true>)}
+     reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT, true>), nullptr, true}
 #define SKINNY(WN, WK, CG, NT, SPLIT)                                                     \
     {"skinny_f32_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT, skinny_supports, \
-     skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0, reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT>)}
+     skinny_launch<WN, WK, CG, NT, SPLIT>, 0, 0, reinterpret_cast<const void *>(&skinny_kernel<WN, WK, CG, NT>), nullptr, true}
 
 // The first entry is the dispatcher's choice for at most 16 rows (eight waves deep in k, one
 // workgroup per CU: the point the tree search of paper_2602_12305_amd/search.py found on the

@@ -45,6 +45,7 @@ struct SkinnyParams {
     const float *A; int64_t lda, strideA;
     const float *B; int64_t ldb, strideB;
     const float *bias; int64_t strideBias;
+    int bias_row;          // bias[m] (the row of C) instead of bias[n]
     float *C; int64_t ldc, strideC;
     float *partial;        // [split][batch * row_blocks][16][N] when split > 1
     int64_t batch, row_blocks;
@@ -211,7 +212,9 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
     auto finish = [&](int row, int64_t col, floatx4 z) {
         if (row >= rows || col >= p.N) return;
         if (p.split == 1) {
-            floatx4 bj = bias ? *reinterpret_cast<const floatx4 *>(bias + col) : floatx4{0, 0, 0, 0};
+            floatx4 bj = floatx4{0, 0, 0, 0};
+            if (bias && p.bias_row) { const float b = bias[16 * rb + row]; bj = floatx4{b, b, b, b}; }
+            else if (bias) bj = *reinterpret_cast<const floatx4 *>(bias + col);
 #pragma unroll
             for (int e = 0; e < 4; ++e) z[e] = apply_act(z[e] + bj[e], p.act);
         }
@@ -251,8 +254,9 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyParams p)
     for (int s = 0; s < p.split; ++s)
         z += *reinterpret_cast<const floatx4 *>(
             p.partial + (((int64_t)s * p.batch * p.row_blocks + zb) * 16 + row % 16) * p.N + col);
-    const floatx4 bj = p.bias ? *reinterpret_cast<const floatx4 *>(p.bias + batch * p.strideBias + col)
-                              : floatx4{0, 0, 0, 0};
+    floatx4 bj = floatx4{0, 0, 0, 0};
+    if (p.bias && p.bias_row) { const float b = p.bias[batch * p.strideBias + row]; bj = floatx4{b, b, b, b}; }
+    else if (p.bias) bj = *reinterpret_cast<const floatx4 *>(p.bias + batch * p.strideBias + col);
 #pragma unroll
     for (int e = 0; e < 4; ++e) z[e] = apply_act(z[e] + bj[e], p.act);
     *reinterpret_cast<floatx4 *>(p.C + batch * p.strideC + row * p.ldc + col) = z;
@@ -272,7 +276,7 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     sp.M = p.M; sp.N = p.N; sp.K = p.K;
     sp.A = static_cast<const float *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
     sp.B = static_cast<const float *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
-    sp.bias = p.bias; sp.strideBias = p.strideBias;
+    sp.bias = p.bias; sp.strideBias = p.strideBias; sp.bias_row = p.bias_row ? 1 : 0;
     sp.C = static_cast<float *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
     sp.batch = p.batch; sp.act = p.act;
     sp.row_blocks = (p.M + 15) / 16;

@@ -7,7 +7,7 @@ using namespace skinny16;
 #define SK16(DT, TAG, WN, WK, CG, NT, SPLIT, IL, ILTAG)                                                       \
     {"skinny_" TAG "_wn" #WN "_wk" #WK "_cg" #CG "_nt" #NT "_split" #SPLIT ILTAG, supports<DT>,              \
      launch<DT, WN, WK, CG, NT, SPLIT, IL>, 0, 0,                                                             \
-     reinterpret_cast<const void *>(&skinny16_kernel<DT, WN, WK, CG, NT, IL>)}
+     reinterpret_cast<const void *>(&skinny16_kernel<DT, WN, WK, CG, NT, IL>), nullptr, true}
 #define SK16_SET(DT, TAG)                                                                                     \
     SK16(DT, TAG, 1, 4, 2, 1, 0, true, "_il"), SK16(DT, TAG, 1, 8, 1, 0, 0, true, "_il"),                      \
     SK16(DT, TAG, 1, 8, 1, 1, 0, true, "_il"), SK16(DT, TAG, 1, 4, 1, 1, 0, true, "_il"),                      \

@@ -6,10 +6,10 @@ using namespace skinny_rc;
 
 #define SKRC(DT, TAG, WN, WK, CG, T)                                                                      \
     {"skinnyrc_" TAG "_wn" #WN "_wk" #WK "_cg" #CG "_t" #T, supports<DT>, launch<DT, WN, WK, CG, T>, 0, 0,  \
-     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>)}
+     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>), nullptr, true}
 #define SKRC_DMA(DT, TAG, WK, CG, NS)                                                                     \
     {"skinnyrc_" TAG "_dma_wk" #WK "_cg" #CG "_ns" #NS, supports_dma<DT>, launch_dma<DT, WK, CG, NS>, 0, 0,  \
-     reinterpret_cast<const void *>(&skinny_rc_dma_kernel<DT, WK, CG, NS>)}
+     reinterpret_cast<const void *>(&skinny_rc_dma_kernel<DT, WK, CG, NS>), nullptr, true}
 #define SKRC_SET(DT, TAG) SKRC_DMA(DT, TAG, 4, 4, 2), SKRC(DT, TAG, 1, 4, 4, 4), SKRC_DMA(DT, TAG, 4, 2, 3), SKRC_DMA(DT, TAG, 2, 4, 4)
 
 // per dtype the first entry is the dispatcher's choice: staged through LDS by DMA, four waves, four column groups,

@@ -35,6 +35,7 @@ struct Params {
     const char *A; int64_t lda, strideA;       // leading dimensions and strides in elements
     const char *B; int64_t ldb, strideB;
     const float *bias; int64_t strideBias;
+    int bias_row;          // bias[m] (the row of C) instead of bias[n]
     char *C; int64_t ldc, strideC;
     float *partial;        // [split][batch * row_blocks][16][N] when split > 1
     int64_t batch, row_blocks;
@@ -189,13 +190,13 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_rc_kernel(Params p)
     // four rows (4 qq .. 4 qq + 3) of one column
     auto finish = [&](int qq, int64_t col, floatx4 z) {
         if (col >= p.N) return;
-        const float bj = (bias && p.split == 1) ? bias[col] : 0.0f;
+        const float bj = (bias && p.split == 1 && !p.bias_row) ? bias[col] : 0.0f;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = 4 * qq + r;
             if (row >= rows) continue;
             if (p.split > 1) { part[(int64_t)row * p.N + col] = z[r]; continue; }
-            const float y = apply_act(z[r] + bj, p.act);
+            const float y = apply_act(z[r] + (bias && p.bias_row ? bias[16 * rb + row] : bj), p.act);
             if constexpr (DT == DT_F32) reinterpret_cast<float *>(out)[(int64_t)row * p.ldc + col] = y;
             else reinterpret_cast<unsigned short *>(out)[(int64_t)row * p.ldc + col] = to_16<Type<DT>::ODT>(y);
         }
@@ -352,13 +353,13 @@ __global__ __launch_bounds__(64 * WK) void skinny_rc_dma_kernel(Params p)
     const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
     auto finish = [&](int qq, int64_t col, floatx4 z) {
         if (col >= p.N) return;
-        const float bj = (bias && p.split == 1) ? bias[col] : 0.0f;
+        const float bj = (bias && p.split == 1 && !p.bias_row) ? bias[col] : 0.0f;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = 4 * qq + r;
             if (row >= rows) continue;
             if (p.split > 1) { part[(int64_t)row * p.N + col] = z[r]; continue; }
-            const float y = apply_act(z[r] + bj, p.act);
+            const float y = apply_act(z[r] + (bias && p.bias_row ? bias[16 * rb + row] : bj), p.act);
             if constexpr (DT == DT_F32) reinterpret_cast<float *>(out)[(int64_t)row * p.ldc + col] = y;
             else reinterpret_cast<unsigned short *>(out)[(int64_t)row * p.ldc + col] = to_16<Type<DT>::ODT>(y);
         }
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(256) void skinny_rc_reduce_kernel(Params p)
     const int64_t zb = batch * p.row_blocks + row / 16;
     float z = 0.0f;
     for (int s = 0; s < p.split; ++s) z += p.partial[(((int64_t)s * p.batch * p.row_blocks + zb) * 16 + row % 16) * p.N + col];
-    const float y = apply_act(z + (p.bias ? p.bias[batch * p.strideBias + col] : 0.0f), p.act);
+    const float y = apply_act(z + (p.bias ? p.bias[batch * p.strideBias + (p.bias_row ? row : col)] : 0.0f), p.act);
     char *out = p.C + (batch * p.strideC + row * p.ldc + col) * Type<DT>::CS;
     if constexpr (DT == DT_F32) *reinterpret_cast<float *>(out) = y;
     else *reinterpret_cast<unsigned short *>(out) = to_16<Type<DT>::ODT>(y);
@@ -411,7 +412,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     sp.M = p.M; sp.N = p.N; sp.K = p.K;
     sp.A = static_cast<const char *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
     sp.B = static_cast<const char *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
-    sp.bias = p.bias; sp.strideBias = p.strideBias;
+    sp.bias = p.bias; sp.strideBias = p.strideBias; sp.bias_row = p.bias_row ? 1 : 0;
     sp.C = static_cast<char *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
     sp.batch = p.batch; sp.act = p.act;
     sp.row_blocks = (p.M + 15) / 16;
@@ -462,7 +463,7 @@ hipError_t launch_dma(const Problem &p, hipStream_t stream)
     sp.M = p.M; sp.N = p.N; sp.K = p.K;
     sp.A = static_cast<const char *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
     sp.B = static_cast<const char *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
-    sp.bias = p.bias; sp.strideBias = p.strideBias;
+    sp.bias = p.bias; sp.strideBias = p.strideBias; sp.bias_row = p.bias_row ? 1 : 0;
     sp.C = static_cast<char *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
     sp.batch = p.batch; sp.act = p.act;
     sp.row_blocks = (p.M + 15) / 16;

@@ -166,7 +166,8 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 8192, 8192, 8192, layout=4 + 0, dtype=1) == "xa_ring"                          # B^T column-major: copied
     assert sel(1, 4096, 4096, 4096, layout=4 + 3).startswith("ring_f32_rr")
     assert sel(32, 2048, 2048, 512, layout=4 + 1, dtype=1).startswith("ring_bf16_rc")            # not the persistent kernel
-    assert sel(1, 16, 16384, 16384, layout=4 + 3).startswith("ring_f32_rr") or sel(1, 16, 16384, 16384, layout=4 + 3).startswith("tile_")
+    assert sel(1, 16, 16384, 16384, layout=4 + 3).startswith("skinny_f32")                       # 16 columns of C^T: streamed, bias down the rows
+    assert sel(1, 16384, 16, 16384, layout=4 + 3).startswith("skinny_f32") and sel(1, 4096, 8, 4096, layout=4 + 1, dtype=1).startswith("skinnyrc_bf16")
     assert sel(1, 8192, 8192, 8192, layout=1, dtype=3).startswith("ring_f8_rc_256x256")          # E4M3, k contiguous in both
     assert sel(1, 8192, 8192, 8192, layout=0, dtype=3) == "xk_ring_f8"                            # ... otherwise copied that way
     assert sel(1, 100, 100, 100, layout=0, dtype=3) == "generic_64x64"

@@ -473,11 +473,37 @@ def test_column_major_c(dtype, layout):
 
 
 def test_column_major_c_is_refused_by_kernels_without_a_row_bias():
-    A = synth.uniform(963, "A", 16, 256); B = synth.uniform(963, "B", 256, 512); bias = synth.uniform(963, "bias", 1, 512)[0]
-    vid = variant_ids("skinny_f32")[0]
+    A = synth.uniform(963, "A", 512, 256); B = synth.uniform(963, "B", 256, 512); bias = synth.uniform(963, "bias", 1, 512)[0]
+    vid = variant_ids("ringp_bf16_rr")[0]                    # the persistent kernel takes its bias along the columns only
     with pytest.raises(ob.OptimlError) as e:
-        check_against_oracle(A, B, bias, dtype=F32, act=synth.ACT_NONE, layout=4 + 3, variant=vid)
+        check_against_oracle(A, B, bias, dtype=BF16, act=synth.ACT_NONE, layout=4 + 3, variant=vid)
     assert e.value.status == ob.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16])
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+def test_column_major_c_with_few_columns_is_streamed(dtype, layout):
+    """C^T has as many rows as C has columns: with a handful of columns the transposed problem goes to the streaming
+    kernels, which then take the bias down their rows - in the kernel itself and, with a split along k, in the
+    kernel that adds the partial sums."""
+    for t, (batch, M, N, K) in enumerate([(1, 1024, 8, 4096), (2, 520, 24, 1024), (1, 136, 40, 256)]):
+        A = synth.normal(965 + t, "A", M, K, batch=batch); B = synth.normal(965 + t, "B", K, N, batch=batch)
+        bias = synth.normal(965 + t, "bias", 1, N, batch=batch).reshape(batch, N)
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout + 4)
+        Ai = synth.integers(968 + t, "A", M, K, batch=batch); Bi = synth.integers(968 + t, "B", K, N, batch=batch)
+        bi = synth.integers(968 + t, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
+        check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_NONE, layout=layout + 4, exact=True)
+    if layout == 3:      # C^T = B^T.A^T is then a row-major problem: forced through every streaming variant of the dtype
+        fam = {F32: "skinny_f32", BF16: "skinny_bf16", F16: "skinny_f16"}[dtype]
+        A = synth.normal(971, "A", 264, 512); B = synth.normal(971, "B", 512, 24); bias = synth.normal(971, "bias", 1, 24)[0]
+        for vid in variant_ids(fam):
+            if ob.optiml_variant_name(vid).startswith(fam + "_"):
+                check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=7, variant=vid)
+    if layout == 1:      # ... and A row-major, B column-major gives a problem of the same layout: its streaming kernels
+        fam = {F32: "skinnyrc_f32", BF16: "skinnyrc_bf16", F16: "skinnyrc_f16"}[dtype]
+        A = synth.normal(972, "A", 264, 512); B = synth.normal(972, "B", 512, 24); bias = synth.normal(972, "bias", 1, 24)[0]
+        for vid in variant_ids(fam):
+            check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=5, variant=vid)
 
 
 @pytest.mark.parametrize("t,M,N,K,layout,dtype,act,pad,use_bias", [c for c in fuzz_cases() if c[0] % 2 == 1])
