@@ -308,7 +308,7 @@ template <class C>
 bool supports(const Problem &p)
 {
     if (!ring::supports<C>(p)) return false;
-    if (p.K / 32 < PCfg<C>::MIN_NK || p.N % 4 != 0) return false;
+    if (p.K % 32 != 0 || p.K / 32 < PCfg<C>::MIN_NK || p.N % 4 != 0) return false;     // whole k-tiles only
     if (p.ldc >= (int64_t(1) << 22)) return false;      // 32 rows of C within a 32-bit byte offset
     return true;
 }

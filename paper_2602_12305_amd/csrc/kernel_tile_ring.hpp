@@ -381,6 +381,52 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     wait_vmcnt<0>();
     __syncthreads();                         // every load has landed, every wave is done with the stages
 
+    // A K that ends inside a k-tile: the last, partial k-tile goes through stage 0 by ordinary
+    // loads, 16-byte chunks at or beyond K written as zeros (K is a whole number of chunks), in
+    // the places the DMA loads of a full tile would have filled.
+    if (p.K % C::BKE != 0) {
+        constexpr int CHE = 16 / C::ES;                          // elements per chunk
+        const int64_t k0 = nk * C::BKE;
+        lds_char *const t0 = (lds_char *)st0;
+#pragma unroll
+        for (int i = 0; i < C::A_INSTR; ++i) {
+            const int q = wave + i * NW, r = 16 * q + (lane >> 2);
+            const int c = (lane & 3) ^ ((r >> 2) & 3);
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if (k0 + c * CHE < p.K) v = *reinterpret_cast<const uintx4 *>(A + ctx.a_off[i] + k0 * C::ES);
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(t0 + q * 1024 + lane * 16) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_INSTR; ++i) {
+            const int q = wave + i * NW;
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if constexpr (C::B_KC) {
+                const int r = 16 * q + (lane >> 2);
+                const int c = (lane & 3) ^ ((r >> 2) & 3);
+                if (k0 + c * CHE < p.K) v = *reinterpret_cast<const uintx4 *>(B + ctx.b_off[i] + k0 * C::ES);
+            } else {
+                const int k = (q * 64 + lane) >> 5;
+                if (k0 + k < p.K) v = *reinterpret_cast<const uintx4 *>(B + ctx.b_off[i] + k0 * p.ldb * 2);
+            }
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(t0 + C::A_BYTES + q * 1024 + lane * 16) = v;
+        }
+        __syncthreads();
+        Frags<C> g0, g1;
+        load_frags<C>(ctx, t0, 0, g0);
+        load_frags<C>(ctx, t0, 1, g1);
+        if constexpr (C::K64) {
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i)
+                    acc[j][i] = mfma_32x32x64_f8(g0.b[j], g1.b[j], g0.a[i], g1.a[i], acc[j][i]);
+        } else {
+            mma_frags<C>(g0, acc);
+            mma_frags<C>(g1, acc);
+        }
+        __syncthreads();                     // stage 0 is the epilogue's slab next
+    }
+
     // Epilogue: bias, activation, bf16 conversion in registers; then each wave passes its tile
     // through a private 32-row slab (WTN*2 bytes per row, 16-byte chunks XOR-swizzled by the row)
     // in stage 0 and stores whole 128-byte lines.  See kernel_tile_direct.hpp.
@@ -494,7 +540,7 @@ template <class C>
 bool supports(const Problem &p)
 {
     if (p.dtype != C::DT || p.a_col() || p.b_col() != C::B_KC) return false;
-    if (p.K < C::BKE * C::NS || p.K % C::BKE != 0 || !vector_friendly(p)) return false;
+    if (p.K < C::BKE * C::NS || p.K % (16 / C::ES) != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 8 != 0)) return false;
     const int64_t a_span = p.M * p.lda * C::ES, b_span = (C::B_KC ? p.N : 32) * p.ldb * C::ES + p.N * C::ES;
     if (a_span >= (int64_t(1) << 31) || b_span >= (int64_t(1) << 31)) return false;
