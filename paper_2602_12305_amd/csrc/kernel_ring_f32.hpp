@@ -81,6 +81,9 @@ __device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *ga, con
 
 // One k-tile of 16 held in stage `rd`, added into the block sums.
 template <class C>
+__device__ __forceinline__ void multiply_stage(const Ctx<C> &c, const lds_char *rd, floatx16 (&part)[C::TM]);
+
+template <class C>
 __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *ga, const char *gb, lds_char *dma,
                                           const lds_char *rd, floatx16 (&part)[C::TM])
 {
@@ -88,7 +91,13 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *ga, const
     ring::block_barrier();
     issue_stage<C>(c, ga, gb, dma);
     __builtin_amdgcn_sched_barrier(0);      // the loads go out before the tile is multiplied
+    multiply_stage<C>(c, rd, part);
+}
 
+// part += the k-tile held in stage `rd`
+template <class C>
+__device__ __forceinline__ void multiply_stage(const Ctx<C> &c, const lds_char *rd, floatx16 (&part)[C::TM])
+{
     const lds_char *sa = rd + c.a_wave;
     const lds_char *sb = rd + C::A_BYTES + c.b_base;
     uintx4 fa[2][C::TM];
@@ -237,6 +246,44 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
     ring::wait_vmcnt<0>();
     __syncthreads();                         // every load has landed, every wave is done with the stages
 
+    // A K that ends inside a k-tile: the last, partial k-tile goes through stage 0 by ordinary
+    // loads, 16-byte chunks at or beyond K written as zeros (K is a whole number of chunks), in
+    // the places the DMA loads of a full tile would have filled.
+    if (p.K % 16 != 0) {
+        const int64_t k0 = nk * 16;
+#pragma unroll
+        for (int i = 0; i < C::A_INSTR; ++i) {
+            const int q = wave + i * NW, r = 16 * q + (lane >> 2);
+            const int c = (lane & 3) ^ ((r >> 2) & 3);
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if (k0 + c * 4 < p.K) v = *reinterpret_cast<const uintx4 *>(A + ctx.a_off[i] + k0 * 4);
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(base + q * 1024 + lane * 16) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_INSTR; ++i) {
+            const int q = wave + i * NW;
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if constexpr (C::B_KC) {
+                const int r = 16 * q + (lane >> 2);
+                const int c = (lane & 3) ^ ((r >> 2) & 3);
+                if (k0 + c * 4 < p.K) v = *reinterpret_cast<const uintx4 *>(B + ctx.b_off[i] + k0 * 4);
+            } else {
+                const int k = (q * 64 + lane) >> 5;
+                if (k0 + k < p.K) v = *reinterpret_cast<const uintx4 *>(B + ctx.b_off[i] + k0 * p.ldb * 4);
+            }
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(base + C::A_BYTES + q * 1024 + lane * 16) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[i][r] = 0.0f;
+        multiply_stage<C>(ctx, base, part);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) acc[i] += part[i];
+        __syncthreads();                     // stage 0 is the epilogue's slab next
+    }
+
     // Epilogue: bias and activation in registers; then each wave passes 32 rows at a time through
     // a private slab (32 rows x 128 bytes, 16-byte chunks XOR-swizzled by the row pair) and
     // stores whole 128-byte lines.  Register r of acc[i] is Z[m][n] with m = mw + 32 i + lane%32,
@@ -337,7 +384,7 @@ template <class C>
 bool supports(const Problem &p)
 {
     if (p.dtype != DT_F32 || p.a_col() || p.b_col() != C::B_KC) return false;
-    if (p.K < 16 * C::NS || p.K % 16 != 0 || !vector_friendly(p)) return false;
+    if (p.K < 16 * C::NS || p.K % 4 != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 4 != 0)) return false;
     // lane offsets are 32-bit byte offsets from the tile's first k
     const int64_t a_span = p.M * p.lda * 4, b_span = (C::B_KC ? p.N : 16) * p.ldb * 4 + p.N * 4;

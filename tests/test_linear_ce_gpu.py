@@ -53,14 +53,14 @@ def check(M, N, K, layout, dtype, seed, want_path, *, use_bias=True, pad=0, scal
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
 @pytest.mark.parametrize("layout,M,N,K", [(0, 300, 520, 160), (1, 300, 515, 160), (0, 1024, 4096, 512), (1, 77, 64, 128),
-                                          (0, 513, 264, 992), (1, 256, 1000, 1024)])
+                                          (0, 513, 264, 992), (1, 256, 1000, 1024), (0, 300, 520, 344), (1, 300, 515, 376)])
 def test_matrix_pipe_path_matches_the_oracle(dtype, layout, M, N, K):
     check(M, N, K, layout, dtype, 3000 + N, 0)
     check(M, N, K, layout, dtype, 3100 + N, 0, use_bias=False, scale=0.25)
 
 
 @pytest.mark.parametrize("layout,M,N,K", [(0, 300, 520, 160), (1, 300, 515, 160), (0, 1024, 2048, 512), (1, 77, 64, 64),
-                                          (0, 513, 264, 1008), (1, 130, 1000, 2048)])
+                                          (0, 513, 264, 1008), (1, 130, 1000, 2048), (0, 300, 520, 172), (1, 300, 515, 184)])
 def test_fp32_matrix_pipe_path_matches_the_oracle(layout, M, N, K):
     check(M, N, K, layout, F32, 3500 + N, 0)
     check(M, N, K, layout, F32, 3600 + N, 0, use_bias=False, scale=0.25)

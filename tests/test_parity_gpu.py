@@ -104,7 +104,7 @@ def test_every_variant_batched_and_repeatable(vid, name):
 
 
 # ---- L1: ring kernels on a K that ends inside a k-tile ----------------------------------------
-@pytest.mark.parametrize("vid", [i for i, n in enumerate(ob.variant_names()) if n.startswith("ring_") and "_f32_" not in n])
+@pytest.mark.parametrize("vid", [i for i, n in enumerate(ob.variant_names()) if n.startswith("ring_")])
 def test_ring_kernels_take_a_partial_last_k_tile(vid):
     """K = whole k-tiles + 1, 2 or 3 chunks of 16 bytes: the chunks beyond K must count as zeros, whatever lies
     behind the end of a row (the next row, or for the last rows of B the end of the buffer).  Exact on integers,
@@ -112,7 +112,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
     name = ob.optiml_variant_name(vid)
     dt = name.split("_")[1]
     dtype, layout = DT_OF[dt], LAYOUT_OF[name.split("_")[2]]
-    tile, chunk = (64, 16) if dt == "f8" else (32, 8)
+    tile, chunk = {"f8": (64, 16), "f32": (16, 4)}.get(dt, (32, 8))
     for extra in (1, 2, 3):
         M, N, K = 300, 392, tile * 9 + chunk * extra
         Ai = synth.integers(1600 + extra, "A", M, K); Bi = synth.integers(1600 + extra, "B", K, N)
@@ -120,7 +120,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
         check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, exact=True)
     A = synth.normal(1610, "A", 300, tile * 7 + chunk, batch=2); B = synth.normal(1610, "B", tile * 7 + chunk, 392, batch=2)
     bias = synth.normal(1610, "bias", 1, 392, batch=2).reshape(2, 392)
-    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad=8 if dt != "f8" else 16)
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad={"f8": 16, "f32": 4}.get(dt, 8))
 
 
 # ---- L1: persistent kernels: more C tiles than CUs, so workgroups walk several tiles ----------
