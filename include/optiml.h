@@ -260,8 +260,8 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
  * are accumulated in fp32, each row's maximum and sum of exponentials are formed in fp32 from
  * the unrounded fp32 logits, the row losses and their mean in fp64 in a fixed order, rounded
  * once to float; repeating a call gives the same bits.  A row-major with a shape the ring kernels
- * take (16-byte aligned operands; 16-bit storage: K a multiple of 32 and at least 128, N a
- * multiple of 8 for a row-major B; fp32: K a multiple of 16 and at least 64, N a multiple of 4 for
+ * take (16-byte aligned operands; 16-bit storage: K a multiple of 8 and at least 128, N a
+ * multiple of 8 for a row-major B; fp32: K a multiple of 4 and at least 64, N a multiple of 4 for
  * a row-major B) runs on the matrix pipe; everything else runs a one-workgroup-per-row fp32
  * kernel.  Uses the per-device workspace (8 bytes per row and 64 columns, 32 for fp32); three
  * kernels.  A label outside [0, N) makes the result NaN; M == 0 writes 0.
