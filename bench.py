@@ -69,13 +69,13 @@ TRAFFIC = {
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
         {"bytes": int((529551.0 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "d4ff8d1267cf9162"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((385049.6 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "1eb1b7785df05428"},
+        {"bytes": int((385145.3 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "3d144bf02577476c"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((793541.1 * 2.0 + 131075.0) * 1024), "files": RING_SRC, "src": "ebc12004cda035e0"},
+        {"bytes": int((806644.5 * 2.0 + 131072.1) * 1024), "files": RING_SRC, "src": "7a5f3f964118548f"},
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((795204.7 * 2.0 + 131077.1) * 1024), "files": RING_SRC, "src": "ebc12004cda035e0"},
+        {"bytes": int((813173.6 * 2.0 + 131072.0) * 1024), "files": RING_SRC, "src": "7a5f3f964118548f"},
     ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((70059.5 * 2.0 + 266801.0) * 1024), "files": RINGP_SRC, "src": "fe2b4a4cb3c298cb"},
+        {"bytes": int((69975.3 * 2.0 + 266658.2) * 1024), "files": RINGP_SRC, "src": "b23f7957bb0ba2b5"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
         {"bytes": int((266407.9 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "52329cc04db85d01"},
     ("s_sigmoid", "s_sigmoid"):
@@ -89,7 +89,7 @@ TRAFFIC = {
     ("s_ln_token", "s_ln_token"):
         {"bytes": int((524317.2 * 2.0 + 1048741.1) * 1024), "files": ROWS_SRC, "src": "ba5a7445e9a0b7d4"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393484.6 * 2.0 + 131255.3) * 1024), "files": RING_F8_SRC, "src": "620f43b18e62716d"},
+        {"bytes": int((393480.9 * 2.0 + 131206.4) * 1024), "files": RING_F8_SRC, "src": "1b37960b6cd1073e"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
         {"bytes": int((609659.9 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "7ff6f414fc2ebc17"},
     ("s_transpose", "s_transpose"):
@@ -97,9 +97,9 @@ TRAFFIC = {
     ("s_mhsa", "s_mhsa"):
         {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "a4876881c0272702"},
     ("s_lce", "s_lce"):
-        {"bytes": int((1590401.9 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "f47b3d42dbf7e43a"},
+        {"bytes": int((1590396.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "6afe4dac2e72a9c6"},
     ("s_lce_f32", "s_lce_f32"):
-        {"bytes": int((1584548.7 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "b9faa7bb22c86a4d"},
+        {"bytes": int((1583509.3 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "b2d898c0c56d34de"},
 }
 
 
