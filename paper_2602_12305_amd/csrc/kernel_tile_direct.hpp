@@ -98,6 +98,10 @@ __device__ __forceinline__ void issue_tile(const StepCtx<C> &c, const char *__re
         __builtin_amdgcn_global_load_lds(gb + c.b_off[i], dst + C::A_BYTES + (c.wave + i * C::NW) * 1024, 16, 0, 0);
 }
 
+template <class C>
+__device__ __forceinline__ void multiply_tile(const StepCtx<C> &c, const lds_char *__restrict__ rd,
+                                              floatx16 (&acc)[C::TN][C::TM]);
+
 // One k-tile: start the loads of the next tile into `dma`, multiply the tile held in
 // `rd`, then wait for the loads and meet the other waves.  `dma` and `rd` are the two LDS
 // stages; restrict tells the compiler that the in-flight DMA cannot touch what is being read,
@@ -107,10 +111,19 @@ __device__ __forceinline__ void tile_step(const StepCtx<C> &c, const char *__res
                                           lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
                                           floatx16 (&acc)[C::TN][C::TM])
 {
-    constexpr int TM = C::TM, TN = C::TN;
     issue_tile<C>(c, ga, gb, dma);
     __builtin_amdgcn_sched_barrier(0);      // the loads must be in flight while the tile is multiplied
+    multiply_tile<C>(c, rd, acc);
+    wait_vmem();
+    __syncthreads();
+}
 
+// acc += the k-tile (64 values of k) held in stage `rd`
+template <class C>
+__device__ __forceinline__ void multiply_tile(const StepCtx<C> &c, const lds_char *__restrict__ rd,
+                                              floatx16 (&acc)[C::TN][C::TM])
+{
+    constexpr int TM = C::TM, TN = C::TN;
     const lds_char *sa = rd + c.a_wave;
     const lds_char *sb = rd + C::A_BYTES;
     uintx4 fa[2][TM], fb[2][TN];
@@ -144,8 +157,6 @@ __device__ __forceinline__ void tile_step(const StepCtx<C> &c, const char *__res
             for (int i = 0; i < TM; ++i)
                 acc[j][i] = mfma_32x32x16<C::DT>(fb[s & 1][j], fa[s & 1][i], acc[j][i]);
     }
-    wait_vmem();
-    __syncthreads();
 }
 #endif
 
@@ -268,6 +279,40 @@ __global__ __launch_bounds__(C::THREADS) void gemm_direct_kernel(Params p)
     }
     if (kt < nk) tile_step<C>(ctx, A + last * 128, B + last * b_step, stage1, stage0, acc);
 
+    // A K that ends inside a k-tile: the partial last k-tile goes through stage 0 by ordinary loads,
+    // 16-byte chunks at or beyond K written as zeros (K is a whole number of chunks), in the places
+    // the DMA loads of a full tile would have filled.  Every step above ended with a barrier, so
+    // both stages are free.
+    if (p.K % 64 != 0) {
+        const int64_t k0 = nk * 64;
+#pragma unroll
+        for (int i = 0; i < C::A_INSTR; ++i) {
+            const int q = wave + i * NW, r = 8 * q + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if (k0 + c * 8 < p.K) v = *reinterpret_cast<const uintx4 *>(A + a_off[i] + k0 * 2);
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(stage0 + q * 1024 + lane * 16) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_INSTR; ++i) {
+            const int q = wave + i * NW;
+            uintx4 v = uintx4{0, 0, 0, 0};
+            if constexpr (C::B_KC) {
+                const int r = 8 * q + (lane >> 3);
+                const int c = (lane & 7) ^ ((r >> 1) & 7);
+                if (k0 + c * 8 < p.K) v = *reinterpret_cast<const uintx4 *>(B + b_off[i] + k0 * 2);
+            } else {
+                constexpr int CR = C::BN / 8;
+                const int k = (q * 64 + lane) / CR;
+                if (k0 + k < p.K) v = *reinterpret_cast<const uintx4 *>(B + b_off[i] + k0 * p.ldb * 2);
+            }
+            *reinterpret_cast<__attribute__((address_space(3))) uintx4 *>(stage0 + C::A_BYTES + q * 1024 + lane * 16) = v;
+        }
+        __syncthreads();
+        multiply_tile<C>(ctx, stage0, acc);
+        __syncthreads();                     // the epilogue's slabs reuse the stages
+    }
+
     // Epilogue.  Register r of acc[j][i] is Z[m][n] with m = mw + 32 i + lane%32 and
     // n = nw + 32 j + 8 (r/4) + 4 (lane/32) + r%4: a lane owns short runs of one row, which
     // would make 8-byte stores scattered over 32 rows.  Each wave therefore passes its tile
@@ -339,7 +384,7 @@ template <class C>
 bool supports(const Problem &p)
 {
     if (p.dtype != C::DT || p.a_col() || p.b_col() != C::B_KC) return false;
-    if (p.K < 64 || p.K % 64 != 0 || !vector_friendly(p)) return false;
+    if (p.K < 64 || p.K % 8 != 0 || !vector_friendly(p)) return false;
     if (!C::B_KC && (p.N % 8 != 0)) return false;
     // per-lane source offsets are 32-bit
     const int64_t a_span = p.M * p.lda * 2, b_span = (C::B_KC ? p.N : 64) * p.ldb * 2 + p.N * 2;

@@ -104,7 +104,7 @@ def test_every_variant_batched_and_repeatable(vid, name):
 
 
 # ---- L1: ring kernels on a K that ends inside a k-tile ----------------------------------------
-@pytest.mark.parametrize("vid", [i for i, n in enumerate(ob.variant_names()) if n.startswith("ring_")])
+@pytest.mark.parametrize("vid", [i for i, n in enumerate(ob.variant_names()) if n.startswith("ring_") or n.startswith("direct_")])
 def test_ring_kernels_take_a_partial_last_k_tile(vid):
     """K = whole k-tiles + 1, 2 or 3 chunks of 16 bytes: the chunks beyond K must count as zeros, whatever lies
     behind the end of a row (the next row, or for the last rows of B the end of the buffer).  Exact on integers,
@@ -113,7 +113,10 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
     dt = name.split("_")[1]
     dtype, layout = DT_OF[dt], LAYOUT_OF[name.split("_")[2]]
     tile, chunk = {"f8": (64, 16), "f32": (16, 4)}.get(dt, (32, 8))
-    for extra in (1, 2, 3):
+    if name.startswith("direct_"):
+        tile = 64                                                       # their k-tile: 1 .. 7 chunks beyond it
+    extras = (1, 2, 3) if not name.startswith("direct_") else (1, 4, 7)
+    for extra in extras:
         M, N, K = 300, 392, tile * 9 + chunk * extra
         Ai = synth.integers(1600 + extra, "A", M, K); Bi = synth.integers(1600 + extra, "B", K, N)
         bi = synth.integers(1600 + extra, "bias", 1, N, -5, 5)[0]
