@@ -158,8 +158,9 @@ def test_streaming_kernels_with_many_row_blocks(dtype, layout):
     ldb = K if layout & 1 else N
     v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, ldb, 0, 0x1000, 0, 0x1000, N, 0, layout, dtype, 0)
     forced = None
-    if not ob.optiml_variant_name(v).startswith("skinny"):            # 16-bit row-major: tiles win at this size
-        forced = [i for i, n in enumerate(ob.variant_names()) if n.startswith("skinny_f16")][1]
+    if not ob.optiml_variant_name(v).startswith("skinny"):            # 16-bit: tiles win at this size
+        fam = ("skinnyrc_" if layout & 1 else "skinny_") + {F32: "f32", BF16: "bf16", F16: "f16"}[dtype]
+        forced = [i for i, n in enumerate(ob.variant_names()) if n.startswith(fam + "_")][0]
     A = synth.normal(1500, "A", M, K); B = synth.normal(1500, "B", K, N); bias = synth.normal(1500, "bias", 1, N)[0]
     check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=forced)
     Ai = synth.integers(1501, "A", M, K); Bi = synth.integers(1501, "B", K, N)
