@@ -1,7 +1,7 @@
 """Dispatcher check: for a list of shapes, time every kernel variant that takes the shape and compare the
 dispatcher's choice with the fastest one.
 
-    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|quick] [--steps N]
+    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|quick] [--steps N]
 
 Prints one line per case (shape, the dispatcher's variant and its time, the fastest variant and its time, the
 ratio) and a summary.  Inputs are N(0,1) (8-bit operands: random bytes below 120); nothing is checked for
@@ -32,6 +32,9 @@ SETS = {
     "mid": [(dt, lay) + s for dt in (1, 0) for lay in (0, 1) for s in MID],
     "other": [(dt, lay) + s for dt, lay in ((3, 1), (3, 0), (1, 2), (1, 3), (0, 2), (0, 3)) for s in OTHER],
     "batched": [(dt, lay) + s for dt, lay in ((1, 0), (1, 1), (0, 0), (0, 1), (2, 0)) for s in BATCHED],
+    # K (and the row pitch) not a whole number of k-tiles
+    "ragged": [(dt, lay, 1, n, n, n) for dt in (1, 2, 0) for lay in (0, 1) for n in (1000, 1496, 3000)] +
+              [(3, 1, 1, 1008, 1008, 1008), (3, 1, 1, 3024, 3024, 3024), (1, 0, 1, 64, 4096, 4104), (0, 1, 1, 48, 8192, 8196)],
     "quick": [(1, 1, 1, 64, 4096, 4096), (0, 1, 1, 64, 4096, 4096), (1, 2, 1, 64, 4096, 4096), (0, 0, 1, 8, 4096, 4096),
               (1, 0, 1, 2048, 2048, 2048), (0, 0, 1, 4096, 512, 4096)],
 }
