@@ -46,14 +46,17 @@
  *              host; buffers must stay valid until the stream has run the work.
  *   Alignment  Any alignment and any ld is accepted.  The fast kernels need
  *              16-byte aligned bases and ld (and batch strides) that keep rows
- *              16-byte aligned; other arguments are served by a guarded
- *              element-wise kernel with the same results to rounding.
+ *              16-byte aligned; other arguments are first copied into that form in
+ *              the workspace when the problem is large enough to pay for it, else
+ *              served by a guarded element-wise kernel, with the same results to
+ *              rounding either way.
  *   Results    Repeating a call with the same arguments gives bitwise the same C
  *              (no floating-point atomics; split-K partial sums are combined in a
  *              fixed order).
  *   Workspace  Split-K kernels keep partial sums, and the fast paths for a column-major
- *              A and for 8-bit operands whose k is not contiguous keep a copy of that
- *              operand (batch x M x K or batch x N x K elements), in one
+ *              A, for 8-bit operands whose k is not contiguous and for unaligned or
+ *              odd-sized problems keep copies of operands (batch x M x K, batch x N x K
+ *              elements; the last also a temporary C), in one
  *              per-device buffer that the library allocates on first need and grows
  *              when a larger one is needed (the only allocation the library ever
  *              makes); calls that use it are ordered by the stream they are enqueued

@@ -26,6 +26,7 @@ struct Table {
         first_tile = (int)v.size();
         for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
         for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);
+        for (int i = 0; i < kNumPadVariants; ++i) v.push_back(&pad_variants()[i]);
     }
 };
 
@@ -239,6 +240,10 @@ int select(const Problem &p, double *estimate_us = nullptr, bool allow_streaming
     double unused;
     double &us_out = estimate_us ? *estimate_us : unused;
     us_out = 1e30;
+    // the element-wise fallback: a launch, then 64 x 64 blocks at 0.047 TFLOP/s each, four of them to a CU (48
+    // TFLOP/s with the chip full, in every storage type; 1025 x 1031 x 2051: 405 us, 4097^3: 2.9 ms)
+    const double fallback_tiles = (double)((p.M + 63) / 64) * (double)((p.N + 63) / 64) * (double)p.batch;
+    const double fallback_us = 5.0 + (fallback_tiles < 1024.0 ? 1.0 : fallback_tiles / 1024.0) * 2.0 * 4096.0 * (double)p.K / 0.047e6;
     if (p.K > 0 && vector_friendly(p)) {
         const int sv = allow_streaming ? stream_variant(t, p) : -1;
         const double stream_us = sv >= 0 ? stream_estimate_us(p) : 1e30;
@@ -256,6 +261,7 @@ int select(const Problem &p, double *estimate_us = nullptr, bool allow_streaming
         for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
             if ((costs[i].tf_wg == 0 && !t.v[i]->estimate_us) || !can_run(t.v[i], p)) continue;
             const double us = t.v[i]->estimate_us ? t.v[i]->estimate_us(p) : tile_estimate_us(t.v[i], costs[i], p);
+            if (t.v[i]->estimate_us && us >= 0.7 * fallback_us) continue;    // a copy path that the one-launch fallback matches
             if (us < best_us) { best = i; best_us = us; }
         }
         if (sv >= 0 && (best < 0 || stream_us < best_us)) { us_out = stream_us; return sv; }
@@ -268,6 +274,18 @@ int select(const Problem &p, double *estimate_us = nullptr, bool allow_streaming
             if (blocks > best_blocks) { best = i; best_blocks = blocks; }
         }
         if (best >= 0) return best;
+    }
+    // nothing above takes the problem as it is: a variant that first copies it into a form they take, if it
+    // expects to beat the element-wise fallback (about 50 TFLOP/s in every storage type)
+    if (p.K > 0) {
+        int best = -1;
+        double best_us = 0.7 * fallback_us;          // several launches against one: only for a clear gain
+        for (int i = t.first_tile; i < (int)t.v.size(); ++i) {
+            if (!t.v[i]->estimate_us || !can_run(t.v[i], p)) continue;
+            const double us = t.v[i]->estimate_us(p);
+            if (us < best_us) { best = i; best_us = us; }
+        }
+        if (best >= 0) { us_out = best_us; return best; }
     }
     for (int i = 0; i < t.first_skinny; ++i)
         if (can_run(t.v[i], p)) return i;

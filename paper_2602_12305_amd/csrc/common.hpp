@@ -98,6 +98,7 @@ const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;
+const Variant *pad_variants();             extern const int kNumPadVariants;      // kernel_pad.hip
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
 constexpr int kRingPerUnit = 4;            // ring-of-stages bf16 kernels per B layout (three one-tile, one persistent)

@@ -186,11 +186,14 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 1024, 1024, 64, layout=3, dtype=1).startswith("tile_bf16_cc_")
     # K = 0, misaligned base, odd leading dimension, ragged contiguous extent -> guarded fallback
     assert sel(1, 64, 64, 0).startswith("generic")
-    assert sel(1, 512, 512, 512, A=P + 4).startswith("generic")
-    assert sel(1, 512, 512, 512, lda=513).startswith("generic")
-    assert sel(1, 512, 510, 512, ldb=512, ldc=512).startswith("generic")  # N % 4 != 0 with row-major B
+    assert sel(1, 64, 64, 64, A=P + 4).startswith("generic") and sel(1, 100, 100, 52, lda=53).startswith("generic")
+    assert sel(1, 512, 512, 512, A=P + 4) == "xpad" and sel(1, 512, 512, 512, lda=513) == "xpad"   # worth the copies already
+    assert sel(1, 512, 510, 512, ldb=512, ldc=512) in ("generic_64x64", "xpad")  # N % 4 != 0 with row-major B
+    # ... and when the problem is large enough to pay for copies into an aligned, padded form: those, then a fast kernel
+    assert sel(1, 4096, 4096, 4096, A=P + 4, dtype=1) == "xpad" and sel(1, 4097, 4097, 4097, dtype=1) == "xpad"
+    assert sel(1, 2048, 2050, 2048, dtype=2) == "xpad" and sel(1, 3001, 3001, 3001, layout=3) == "xpad"
     assert sel(1, 512, 510, 512, layout=1, ldc=512).startswith("skinnyrc_f32")  # fine when k is contiguous
-    assert sel(1, 16, 1024, 1022, lda=1024).startswith("generic")
+    assert sel(1, 16, 1024, 1022, lda=1024) in ("generic_64x64", "xpad")
     assert sel(1, 16, 1024, 1024, dtype=1).startswith("skinny_bf16")
     assert sel(1, 8, 8, 8, layout=8) == ob.ERR_INVALID_ARG
 

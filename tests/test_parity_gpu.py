@@ -167,6 +167,36 @@ def test_streaming_kernels_with_many_row_blocks(dtype, layout):
     check_against_oracle(Ai, Bi, None, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=forced, exact=True)
 
 
+# ---- L1: problems no fast kernel takes as they are: copied into an aligned, padded form first ------------
+@pytest.mark.parametrize("dtype", [F32, BF16, F16, F8])
+@pytest.mark.parametrize("layout", [0, 1, 2, 3, 4, 7])
+def test_copy_into_padded_form_then_a_fast_kernel(dtype, layout):
+    """Odd K, odd N, odd M, leading dimensions that are no whole number of 16-byte chunks (pad = 1 or 3 elements), a
+    batch, a bias: the variant that copies A, B and the bias into the workspace (k contiguous, zeros behind K), runs a
+    fast kernel into an aligned temporary C and copies that back - forced, against the oracle, exact on integers,
+    with the padding columns of C left alone."""
+    vid = variant_ids("xpad")[0]
+    for t, (batch, M, N, K, pad) in enumerate([(1, 301, 395, 203, 1), (2, 67, 130, 515, 3), (1, 17, 1031, 1037, 1)]):
+        A = synth.normal(1700 + t, "A", M, K, batch=batch); B = synth.normal(1700 + t, "B", K, N, batch=batch)
+        bias = synth.normal(1700 + t, "bias", 1, N, batch=batch).reshape(batch, N)
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad=pad, ldc_pad=pad)
+        Ai = synth.integers(1710 + t, "A", M, K, batch=batch); Bi = synth.integers(1710 + t, "B", K, N, batch=batch)
+        bi = synth.integers(1710 + t, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
+        check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, pad=pad, ldc_pad=pad,
+                             exact=True)
+
+
+def test_copy_into_padded_form_is_the_dispatchers_choice_for_large_odd_shapes():
+    M, N, K = 1025, 1031, 2051
+    for dtype, layout in ((BF16, 0), (F32, 1), (F16, 3), (F8, 2)):
+        lda = M if layout & 2 else K
+        ldb = K if layout & 1 else N
+        v = ob.optiml_select_variant(1, M, N, K, 0x1000, lda, 0, 0x1000, ldb, 0, 0x1000, 0, 0x1000, N, 0, layout, dtype, 0)
+        assert ob.optiml_variant_name(v) == "xpad", (dtype, layout, ob.optiml_variant_name(v))
+        A = synth.normal(1720, "A", M, K); B = synth.normal(1720, "B", K, N); bias = synth.normal(1720, "bias", 1, N)[0]
+        check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=layout)
+
+
 # ---- L1: dispatcher over seeded random shapes, all layouts / dtypes / acts / paddings --------
 def fuzz_cases():
     rng = np.random.default_rng(2602)
