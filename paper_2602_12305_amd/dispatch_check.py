@@ -1,7 +1,7 @@
 """Dispatcher check: for a list of shapes, time every kernel variant that takes the shape and compare the
 dispatcher's choice with the fastest one.
 
-    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|quick] [--steps N]
+    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|odd|quick] [--steps N]
 
 Prints one line per case (shape, the dispatcher's variant and its time, the fastest variant and its time, the
 ratio) and a summary.  Inputs are N(0,1) (8-bit operands: random bytes below 120); nothing is checked for
@@ -35,6 +35,9 @@ SETS = {
     # K (and the row pitch) not a whole number of k-tiles
     "ragged": [(dt, lay, 1, n, n, n) for dt in (1, 2, 0) for lay in (0, 1) for n in (1000, 1496, 3000)] +
               [(3, 1, 1, 1008, 1008, 1008), (3, 1, 1, 3024, 3024, 3024), (1, 0, 1, 64, 4096, 4104), (0, 1, 1, 48, 8192, 8196)],
+    # odd sizes and pitches: nothing but the copy path (xpad) and the fallback takes these
+    "odd": [(dt, lay, 1) + s for dt in (1, 0) for lay in (0, 1, 3)
+            for s in ((1025, 1031, 2051), (4097, 4097, 4097), (301, 395, 203), (17, 4099, 4099), (513, 515, 517))],
     "quick": [(1, 1, 1, 64, 4096, 4096), (0, 1, 1, 64, 4096, 4096), (1, 2, 1, 64, 4096, 4096), (0, 0, 1, 8, 4096, 4096),
               (1, 0, 1, 2048, 2048, 2048), (0, 0, 1, 4096, 512, 4096)],
 }
@@ -78,8 +81,9 @@ def check(dt, lay, b, M, N, K, steps=0, names=None):
     steps = steps or max(3, min(50, int(2e11 / max(flops, 1e9))))
     best = None
     t_pick = None
+    only_fallback_left = names[pick] in ("xpad", "generic_64x64")
     for i, n in enumerate(names):
-        if n.startswith("generic") and flops > 5e10 and i != pick:
+        if n.startswith("generic") and flops > 5e10 and i != pick and not only_fallback_left:
             continue
         if ob.optiml_variant_supports(i, *prob) != 0:
             continue
