@@ -46,7 +46,8 @@ def check_ce(z, labels, **kw):
 
 
 @pytest.mark.parametrize("N,C", [(1, 1), (5, 2), (1000, 10), (257, 63), (300, 64), (77, 100), (33, 1000), (9, 2048),
-                                 (7, 2052), (5, 5000), (3, 50257), (4100, 128)])
+                                 (7, 2052), (5, 5000), (3, 50257), (4100, 128), (531, 68), (400, 130), (263, 256), (129, 260),
+                                 (77, 512), (65, 514), (50, 1024), (41, 1022), (35, 1028)])
 def test_cross_entropy_matches_the_oracle(N, C):
     z = synth.normal(1100 + N + C, "z", N, C) * np.float32(3.0)
     labels = (np.arange(N, dtype=np.int64) * 7919 % C).astype(np.int32)
