@@ -87,11 +87,11 @@ TRAFFIC = {
     ("s_dot", "s_dot"):
         {"bytes": int((1048631.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
     ("s_ce", "s_ce"):
-        {"bytes": int((524987.6 * 2.0 + 64.2) * 1024), "files": ROWS_SRC, "src": "31a0c444ecf70f6b"},
+        {"bytes": int((524988.0 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((1049946.1 * 2.0 + 1050044.3) * 1024), "files": ROWS_SRC, "src": "31a0c444ecf70f6b"},
+        {"bytes": int((1049946.3 * 2.0 + 1049990.3) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
     ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524319.3 * 2.0 + 1048586.6) * 1024), "files": ROWS_SRC, "src": "31a0c444ecf70f6b"},
+        {"bytes": int((524321.3 * 2.0 + 1048587.4) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393480.9 * 2.0 + 131206.4) * 1024), "files": RING_F8_SRC, "src": "1b37960b6cd1073e"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):

@@ -305,10 +305,10 @@ __global__ __launch_bounds__(THREADS) void layernorm_short_kernel(const float *_
 // rows of at most 2048 features (len % 4 == 0, 16-byte aligned): one wave per row, four rows per workgroup, the row
 // in registers, sums by butterfly across the wave only - no LDS, no barrier.  A workgroup per row leaves such rows
 // at 4.2 TB/s (8 KiB of work per workgroup).
+template <int U>                 // vectors of four per lane: len <= 256 U
 __global__ __launch_bounds__(kThreads) void layernorm_wave_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                                   int64_t rows, int64_t len, double eps)
 {
-    constexpr int U = 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + wave;
     if (row >= rows) return;
@@ -498,10 +498,13 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
         if (rows > 0x7fffffffLL) return hipErrorInvalidValue;
         const dim3 grid((unsigned)rows);
         const double e64 = (double)eps;
-        if (vec && len <= 2048)
-            hipLaunchKernelGGL(layernorm_wave_kernel, dim3((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64))), dim3(kThreads), 0,
-                               stream, x, y, rows, len, e64);
-        else if (!vec) hipLaunchKernelGGL((layernorm_short_kernel<false, kThreads, 8>), grid, dim3(kThreads), 0, stream, x, y, len, e64);
+        if (vec && len <= 2048) {
+            const dim3 g((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64))), b(kThreads);
+            if (len <= 256) hipLaunchKernelGGL(layernorm_wave_kernel<1>, g, b, 0, stream, x, y, rows, len, e64);
+            else if (len <= 512) hipLaunchKernelGGL(layernorm_wave_kernel<2>, g, b, 0, stream, x, y, rows, len, e64);
+            else if (len <= 1024) hipLaunchKernelGGL(layernorm_wave_kernel<4>, g, b, 0, stream, x, y, rows, len, e64);
+            else hipLaunchKernelGGL(layernorm_wave_kernel<8>, g, b, 0, stream, x, y, rows, len, e64);
+        } else if (!vec) hipLaunchKernelGGL((layernorm_short_kernel<false, kThreads, 8>), grid, dim3(kThreads), 0, stream, x, y, len, e64);
         else if (len <= 4096) hipLaunchKernelGGL((layernorm_short_kernel<true, kThreads, 8>), grid, dim3(kThreads), 0, stream, x, y, len, e64);
         // rows that a 1024-thread workgroup still holds in registers: one pass instead of the
         // two kernels below
