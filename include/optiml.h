@@ -56,18 +56,26 @@
  *   Workspace  Split-K kernels keep partial sums, and the fast paths for a column-major
  *              A, for 8-bit operands whose k is not contiguous and for unaligned or
  *              odd-sized problems keep copies of operands (batch x M x K, batch x N x K
- *              elements; the last also a temporary C), in one
- *              per-device buffer that the library allocates on first need and grows
- *              when a larger one is needed (the only allocation the library ever
- *              makes); calls that use it are ordered by the stream they are enqueued
- *              on, and two streams must not run such calls on one device at the
- *              same time.
+ *              elements; the last also a temporary C), in one per-device buffer.
+ *              By default the library allocates it on first need and, when a call needs
+ *              more, allocates a larger one (at least double) and keeps the old one
+ *              allocated until the process ends, because enqueued work and HIP graphs
+ *              captured earlier may still hold its address; these are the only
+ *              allocations the library makes.  It is never grown while `stream` is being
+ *              captured: such a call returns OPTIML_ERR_UNSUPPORTED, so run every call
+ *              of a graph once before capturing it (or hand over a buffer).  With
+ *              optiml_set_workspace the caller supplies the buffer instead; the library
+ *              then never allocates, and a call that needs more than the buffer holds
+ *              returns OPTIML_ERR_UNSUPPORTED.  Calls that use the workspace are ordered
+ *              by the stream they are enqueued on; two streams must not run such calls
+ *              on one device at the same time (not checked).
  *   Errors     The return value is an optiml_status_t; nothing is thrown or
  *              aborted.  OPTIML_ERR_INVALID_ARG: a NULL A/B (with K > 0) or C, a
  *              negative size or stride, an ld shorter than the row it spans, an
  *              unknown enum - decided on the host BEFORE any GPU call, so it is
  *              reportable on a machine without a GPU.  OPTIML_ERR_UNSUPPORTED: a
- *              forced variant cannot run this shape / alignment.  OPTIML_ERR_HIP:
+ *              forced variant cannot run this shape / alignment, or the workspace is
+ *              too small and may not grow (see Workspace).  OPTIML_ERR_HIP:
  *              the runtime refused a launch; optiml_last_hip_error() has the code.
  */
 #ifndef OPTIML_H
@@ -295,6 +303,20 @@ int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *
  */
 int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const void *Q, const void *K, const void *V,
                 void *O, int dtype, void *stream);
+
+/*
+ * Hands the library a workspace for the current device (see Workspace above): `bytes` bytes of
+ * DEVICE memory at `ptr`, 256-byte aligned, owned by the caller, which keeps it valid and
+ * otherwise untouched until every call that may use it has run and another buffer (or none) has
+ * been set.  ptr == NULL with bytes == 0 returns to the library's own buffer.  The split-K
+ * partial sums of the contraction need split x batch x 16 ceil(M/16) x N floats (split <= 64;
+ * 8 MiB for M = 16, N = K = 16384), the copy paths the operand sizes given above.
+ * optiml_workspace_bytes() is the capacity of the buffer in use on the current device (0 before
+ * the first allocation).  OPTIML_ERR_INVALID_ARG (before any GPU call): bytes < 0, ptr not
+ * 256-byte aligned, exactly one of ptr and bytes zero.
+ */
+int optiml_set_workspace(void *ptr, int64_t bytes);
+int64_t optiml_workspace_bytes(void);
 
 /* Human-readable text for a status code; static storage. */
 const char *optiml_status_string(int status);

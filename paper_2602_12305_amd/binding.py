@@ -41,6 +41,8 @@ SIGNATURES = {
     "optiml_transpose": (_int, [_i64, _i64, _vp, _i64, _vp, _i64, _int, _vp]),
     "optiml_gemm_cross_entropy": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _int, _int, _vp]),
     "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
+    "optiml_set_workspace": (_int, [_vp, _i64]),
+    "optiml_workspace_bytes": (_i64, []),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -190,6 +192,15 @@ def optiml_gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, layou
 
 def optiml_gemm_cross_entropy_path(M, N, K, A, lda, B, ldb, bias, layout, dtype):
     return lib().optiml_gemm_cross_entropy_path(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), layout, dtype)
+
+
+def optiml_set_workspace(ptr, nbytes):
+    """Caller-supplied workspace for the current device (None, 0: back to the library's own)."""
+    return _check(lib().optiml_set_workspace(_addr(ptr), nbytes))
+
+
+def optiml_workspace_bytes():
+    return lib().optiml_workspace_bytes()
 
 
 def optiml_status_string(status):

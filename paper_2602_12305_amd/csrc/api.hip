@@ -12,6 +12,21 @@ namespace {
 
 thread_local int tls_last_hip_error = 0;
 thread_local size_t tls_workspace_head = 0;      // see WorkspaceHead
+// workspace() refused (too small and not allowed to grow): the entry points report
+// OPTIML_ERR_UNSUPPORTED instead of a HIP error
+thread_local bool tls_workspace_refused = false;
+
+int status_of(hipError_t e)
+{
+    if (e == hipSuccess) return OPTIML_OK;
+    if (tls_workspace_refused) {
+        tls_workspace_refused = false;
+        return OPTIML_ERR_UNSUPPORTED;
+    }
+    tls_last_hip_error = (int)e;
+    return OPTIML_ERR_HIP;
+}
+
 
 struct Table {
     std::vector<const Variant *> v;
@@ -48,6 +63,17 @@ int validate(const Problem &p)
     if (p.batch < 0 || p.M < 0 || p.N < 0 || p.K < 0) return OPTIML_ERR_INVALID_ARG;
     if (p.strideA < 0 || p.strideB < 0 || p.strideBias < 0 || p.strideC < 0) return OPTIML_ERR_INVALID_ARG;
     if (p.lda < 0 || p.ldb < 0 || p.ldc < 0) return OPTIML_ERR_INVALID_ARG;
+    // Every operand must span fewer than 2^47 elements (batch stride and leading dimension
+    // included), so that no index or byte offset formed from these numbers can leave int64.
+    constexpr int64_t kMaxSpan = int64_t(1) << 47;
+    auto span_ok = [](int64_t batch, int64_t stride, int64_t rows, int64_t ld, int64_t cols) {
+        const __int128 span = (__int128)(batch > 0 ? batch - 1 : 0) * stride + (__int128)(rows > 0 ? rows - 1 : 0) * ld + cols;
+        return span < kMaxSpan;
+    };
+    if (!span_ok(p.batch, p.strideC, p.M, p.ldc, p.N) || !span_ok(p.batch, p.strideBias, 1, 0, p.bias_row ? p.M : p.N) ||
+        !span_ok(p.batch, p.strideA, p.a_col() ? p.K : p.M, p.lda, p.a_col() ? p.M : p.K) ||
+        !span_ok(p.batch, p.strideB, p.b_col() ? p.N : p.K, p.ldb, p.b_col() ? p.K : p.N))
+        return OPTIML_ERR_INVALID_ARG;
     if (p.batch == 0 || p.M == 0 || p.N == 0) return OPTIML_OK;
     if (!p.C || p.ldc < p.N) return OPTIML_ERR_INVALID_ARG;
     if (p.batch > 1 && p.strideC < (p.M - 1) * p.ldc + p.N) return OPTIML_ERR_INVALID_ARG;
@@ -298,11 +324,7 @@ int run(const Problem &p, int variant_id, void *stream)
     if (variant_id < 0 || variant_id >= (int)t.v.size()) return OPTIML_ERR_INVALID_ARG;
     if (!can_run(t.v[variant_id], p)) return OPTIML_ERR_UNSUPPORTED;
     hipError_t e = t.v[variant_id]->launch(p, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, int64_t strideA,
@@ -329,10 +351,24 @@ Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int6
     return p;
 }
 
-struct DeviceScratch { void *ptr = nullptr; size_t bytes = 0; };
+// The per-device workspace: either the library's own buffer (allocated on first need; a larger
+// need allocates a new one and RETIRES the old one, which stays allocated until the process ends:
+// work already enqueued, and HIP graphs captured earlier, may still hold its address) or a buffer
+// the caller handed over with optiml_set_workspace (never grown, never freed here).
+struct DeviceScratch {
+    void *own = nullptr;           // the library's buffer
+    size_t own_bytes = 0;
+    std::vector<void *> retired;
+    void *callers = nullptr;       // optiml_set_workspace's, used instead while set
+    size_t callers_bytes = 0;
+};
 std::mutex g_scratch_mutex;
 DeviceScratch g_scratch[64];
 
+// Set while an entry point that must not allocate runs on this thread: workspace() then hands out
+// this fixed buffer and refuses anything larger.
+struct FixedWorkspace { void *ptr = nullptr; size_t bytes = 0; };
+thread_local FixedWorkspace tls_fixed_workspace;
 }  // namespace
 
 bool vector_friendly(const Problem &p)
@@ -370,29 +406,52 @@ int compute_units()
     return cus[dev];
 }
 
-hipError_t workspace(size_t bytes, void **ptr)
+hipError_t workspace(size_t bytes, void **ptr, hipStream_t stream)
 {
+    const size_t head = tls_workspace_head;
+    bytes += head;
+    if (tls_fixed_workspace.ptr) {
+        if (tls_fixed_workspace.bytes < bytes) {
+            tls_workspace_refused = true;
+            return hipErrorOutOfMemory;
+        }
+        *ptr = static_cast<char *>(tls_fixed_workspace.ptr) + head;
+        return hipSuccess;
+    }
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
     DeviceScratch &s = g_scratch[dev];
-    const size_t head = tls_workspace_head;
-    bytes += head;
-    if (s.bytes < bytes) {
-        if (head) return hipErrorOutOfMemory;     // the holder of the head did not size the buffer: refuse to drop its copy
-        if (s.ptr) {
-            e = hipFree(s.ptr);      // waits for work that may still read the old buffer
-            s.ptr = nullptr; s.bytes = 0;
-            if (e != hipSuccess) return e;
+    if (s.callers) {
+        if (s.callers_bytes < bytes) {
+            tls_workspace_refused = true;
+            return hipErrorOutOfMemory;
         }
-        const size_t want = (bytes + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
-        e = hipMalloc(&s.ptr, want);
-        if (e != hipSuccess) { s.ptr = nullptr; return e; }
-        s.bytes = want;
+        *ptr = static_cast<char *>(s.callers) + head;
+        return hipSuccess;
     }
-    *ptr = static_cast<char *>(s.ptr) + head;
+    if (s.own_bytes < bytes) {
+        // not grown when the holder of the head did not size the buffer (a new one would not hold
+        // its copy) or while the stream is being captured (an allocation would end the capture, and
+        // the graph would keep the address of a buffer that the next growth retires)
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (head || (hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)) {
+            tls_workspace_refused = true;
+            return hipErrorOutOfMemory;
+        }
+        // at least double, so that all retired buffers together stay below the live one
+        size_t want = bytes > 2 * s.own_bytes ? bytes : 2 * s.own_bytes;
+        want = (want + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+        void *fresh = nullptr;
+        e = hipMalloc(&fresh, want);
+        if (e != hipSuccess) return e;
+        if (s.own) s.retired.push_back(s.own);
+        s.own = fresh;
+        s.own_bytes = want;
+    }
+    *ptr = static_cast<char *>(s.own) + head;
     return hipSuccess;
 }
 
@@ -528,11 +587,7 @@ int optiml_copy_bytes(void *dst, const void *src, int64_t nbytes, void *stream)
     hipLaunchKernelGGL(optiml::copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const optiml::copy_vec *>(src), static_cast<optiml::copy_vec *>(dst), n16);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_elementwise(int64_t n, const float *x, float *y, int op, void *stream)
@@ -541,11 +596,7 @@ int optiml_elementwise(int64_t n, const float *x, float *y, int op, void *stream
     if (n == 0) return OPTIML_OK;
     if (!x || !y) return OPTIML_ERR_INVALID_ARG;
     hipError_t e = optiml::launch_elementwise(n, x, y, op, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out, void *stream)
@@ -554,11 +605,7 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
         return OPTIML_ERR_INVALID_ARG;
     if (n > 0 && (!x || (op != OPTIML_RED_SUM && !y))) return OPTIML_ERR_INVALID_ARG;
     hipError_t e = optiml::launch_reduce(n, x, y, op, out, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, const int32_t *labels, float *loss,
@@ -567,11 +614,7 @@ int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, 
     if (N < 0 || C < 1 || ld < C || !loss) return OPTIML_ERR_INVALID_ARG;
     if (N > 0 && (!logits || !labels)) return OPTIML_ERR_INVALID_ARG;
     hipError_t e = optiml::launch_cross_entropy(N, C, logits, ld, labels, loss, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream)
@@ -580,11 +623,7 @@ int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float 
     if (rows == 0 || len == 0) return OPTIML_OK;
     if (!x || !y) return OPTIML_ERR_INVALID_ARG;
     hipError_t e = optiml::launch_layernorm(rows, len, x, y, eps, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int elem_bytes,
@@ -595,11 +634,7 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
     if (rows == 0 || cols == 0) return OPTIML_OK;
     if (!src || !dst) return OPTIML_ERR_INVALID_ARG;
     hipError_t e = optiml::launch_transpose(rows, cols, src, ld_src, dst, ld_dst, elem_bytes, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
@@ -607,6 +642,14 @@ int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, in
 {
     if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
     if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0 || !loss) return OPTIML_ERR_INVALID_ARG;
+    {
+        // operand spans below 2^47 elements, as in validate()
+        constexpr int64_t kMaxSpan = int64_t(1) << 47;
+        const bool ac = (layout & 2) != 0, bc = (layout & 1) != 0;
+        const __int128 a_span = (__int128)((ac ? K : M) > 0 ? (ac ? K : M) - 1 : 0) * lda + (ac ? M : K);
+        const __int128 b_span = (__int128)((bc ? N : K) > 0 ? (bc ? N : K) - 1 : 0) * ldb + (bc ? K : N);
+        if (a_span >= kMaxSpan || b_span >= kMaxSpan) return OPTIML_ERR_INVALID_ARG;
+    }
     Problem p{};
     p.batch = 1; p.M = M; p.N = N; p.K = K;
     p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.bias = bias;
@@ -619,11 +662,7 @@ int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, in
         }
     }
     hipError_t e = optiml::launch_linear_ce(p, labels, loss, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) {
-        tls_last_hip_error = (int)e;
-        return OPTIML_ERR_HIP;
-    }
-    return OPTIML_OK;
+    return status_of(e);
 }
 
 int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
@@ -648,11 +687,31 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
     const int path = optiml::mhsa_path(d_model, heads, dtype, Q, K, V, O);
     if (path < 0) return OPTIML_ERR_UNSUPPORTED;
     hipError_t e = optiml::launch_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, path, static_cast<hipStream_t>(stream));
+    return status_of(e);
+}
+
+int optiml_set_workspace(void *ptr, int64_t bytes)
+{
+    if (bytes < 0 || (ptr == nullptr) != (bytes == 0) || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return OPTIML_ERR_INVALID_ARG;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= 64)) e = hipErrorInvalidDevice;
     if (e != hipSuccess) {
         tls_last_hip_error = (int)e;
         return OPTIML_ERR_HIP;
     }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    g_scratch[dev].callers = ptr;
+    g_scratch[dev].callers_bytes = (size_t)bytes;
     return OPTIML_OK;
+}
+
+int64_t optiml_workspace_bytes(void)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return (int64_t)(g_scratch[dev].callers ? g_scratch[dev].callers_bytes : g_scratch[dev].own_bytes);
 }
 
 const char *optiml_status_string(int status)
@@ -660,7 +719,7 @@ const char *optiml_status_string(int status)
     switch (status) {
     case OPTIML_OK: return "ok";
     case OPTIML_ERR_INVALID_ARG: return "invalid argument";
-    case OPTIML_ERR_UNSUPPORTED: return "variant does not support these arguments";
+    case OPTIML_ERR_UNSUPPORTED: return "variant does not support these arguments, or the workspace is too small and may not grow";
     case OPTIML_ERR_HIP: return "HIP runtime error (see optiml_last_hip_error)";
     default: return "unknown status";
     }

@@ -55,8 +55,11 @@ bool vector_friendly(const Problem &p);
 int compute_units();
 
 // per-device scratch (split-K partial sums, reduction partials, the row-major copy of a
-// column-major A): grown on demand, never shrunk
-hipError_t workspace(size_t bytes, void **ptr);
+// column-major A): the caller's buffer if one was set, else the library's own, which is replaced
+// by a larger one on demand (the old one stays allocated) unless `stream` is being captured.
+// When the buffer is too small and may not grow, the error is reported to the caller of the
+// entry point as OPTIML_ERR_UNSUPPORTED.
+hipError_t workspace(size_t bytes, void **ptr, hipStream_t stream);
 // While one of these lives, workspace() on this thread hands out the memory behind the first
 // `bytes` of the buffer: a launcher that keeps a copy of an operand there can call kernels that
 // ask for scratch of their own.  It must have sized the buffer for both beforehand (one

@@ -145,6 +145,7 @@ hipError_t launch_ring_lse(const Problem &p, const int *labels, float *part, flo
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = ACT_NONE;
     q.labels = labels; q.picked = picked; q.bias_row = 0;
+    if (q.tiles_m * q.tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;     // the grid is 32-bit
     if constexpr (std::is_same<C, LseCfgF32Rr>::value || std::is_same<C, LseCfgF32Rc>::value) {
         hipLaunchKernelGGL(ringf::gemm_ring_f32_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
     } else {
@@ -183,7 +184,7 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
     const size_t part_bytes = align256(sizeof(float) * 2 * (size_t)slices * p.M);
     const size_t pick_bytes = align256(sizeof(float) * (size_t)p.M);
     void *ws = nullptr;
-    hipError_t e = workspace(part_bytes + pick_bytes + sizeof(double) * (size_t)blocks, &ws);
+    hipError_t e = workspace(part_bytes + pick_bytes + sizeof(double) * (size_t)blocks, &ws, stream);
     if (e != hipSuccess) return e;
     float *part = static_cast<float *>(ws);
     float *picked = reinterpret_cast<float *>(static_cast<char *>(ws) + part_bytes);

@@ -156,7 +156,7 @@ hipError_t pad_launch(const Problem &p, hipStream_t s)
     const Plan pl = plan_for(p);
     const size_t more = second->name[0] == 's' ? partial_bound(p) : 0;        // "skinny...": split-k partials
     void *ws = nullptr;
-    hipError_t e = workspace(pl.total() + more, &ws);
+    hipError_t e = workspace(pl.total() + more, &ws, s);
     if (e != hipSuccess) return e;
     const Problem q = padded(p, pl, ws);
     const int es = p.esize();

@@ -463,7 +463,7 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
     }
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     void *ws = nullptr;
-    hipError_t e = workspace(sizeof(double) * (size_t)(grid > 0 ? grid : 1), &ws);
+    hipError_t e = workspace(sizeof(double) * (size_t)(grid > 0 ? grid : 1), &ws, stream);
     if (e != hipSuccess) return e;
     double *partial = static_cast<double *>(ws);
     if (grid > 0) {
@@ -523,7 +523,7 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
     group = group < 1 ? 1 : group;
     if (group * chunks > 0x7fffffffLL) return hipErrorInvalidValue;
     void *ws = nullptr;
-    hipError_t e = workspace(sizeof(double) * 2 * (size_t)(group * chunks), &ws);
+    hipError_t e = workspace(sizeof(double) * 2 * (size_t)(group * chunks), &ws, stream);
     if (e != hipSuccess) return e;
     double *stats = static_cast<double *>(ws);
     for (int64_t r0 = 0; r0 < rows; r0 += group) {

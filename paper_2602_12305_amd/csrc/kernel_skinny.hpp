@@ -296,7 +296,7 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     sp.partial = nullptr;
     if (split > 1) {
         void *ws = nullptr;
-        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws);
+        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws, stream);
         if (e != hipSuccess) return e;
         sp.partial = static_cast<float *>(ws);
     }

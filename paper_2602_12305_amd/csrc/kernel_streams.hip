@@ -222,7 +222,7 @@ hipError_t launch_reduce(int64_t n, const float *x, const float *y, int op, floa
     const bool vec = aligned16(x) && (op == OPTIML_RED_SUM || aligned16(y));
     const int grid = n > 0 ? (int)grid_for(n, vec, (int64_t)kBlock * kRedIter) : 0;
     void *ws = nullptr;
-    hipError_t e = workspace(sizeof(double) * (size_t)(grid > 0 ? grid : 1), &ws);
+    hipError_t e = workspace(sizeof(double) * (size_t)(grid > 0 ? grid : 1), &ws, stream);
     if (e != hipSuccess) return e;
     double *partial = static_cast<double *>(ws);
     if (grid > 0) {

@@ -132,7 +132,7 @@ hipError_t xa_launch(const Problem &p, hipStream_t s)
     const size_t copy = align256((size_t)p.batch * p.M * p.K * p.esize());
     const size_t more = second->name[0] == 's' ? partial_bound(p) : 0;        // "skinny...": split-k partials
     void *ws = nullptr;
-    hipError_t e = workspace(copy + more, &ws);
+    hipError_t e = workspace(copy + more, &ws, s);
     if (e != hipSuccess) return e;
     const Problem q = with_row_major_a(p, ws);
     const int64_t T = 256 / p.esize();
@@ -203,7 +203,7 @@ hipError_t x8_launch(const Problem &p, hipStream_t s)
     const size_t b_bytes = !p.b_col() ? align256((size_t)p.batch * p.N * p.K) : 0;
     const size_t more = second->name[0] == 's' ? partial_bound(p) : 0;        // "skinny...": split-k partials
     void *ws = nullptr;
-    hipError_t e = workspace(a_bytes + b_bytes + more, &ws);
+    hipError_t e = workspace(a_bytes + b_bytes + more, &ws, s);
     if (e != hipSuccess) return e;
     void *wa = ws, *wb = static_cast<char *>(ws) + a_bytes;
     const Problem q = with_k_contiguous(p, wa, wb);

@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 20
+    assert len(names) == 22
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -245,3 +245,23 @@ def test_transpose_entry_point_validates_on_the_host():
         assert L.optiml_transpose(*args) == ob.ERR_INVALID_ARG, args
     assert L.optiml_transpose(0, 8, None, 8, None, 0, 4, None) == ob.OK
     assert L.optiml_transpose(8, 0, None, 0, None, 8, 2, None) == ob.OK
+
+
+def test_operand_spans_that_would_overflow_are_rejected_on_the_host():
+    big = 1 << 46
+    # (M - 1) * ldc + N, (batch - 1) * stride and the operands' own spans all stay below 2^47 elements
+    assert call(M=4, ldc=big, sC=0) == ob.ERR_INVALID_ARG
+    assert call(M=1 << 40, lda=1 << 40, K=8) == ob.ERR_INVALID_ARG
+    assert call(batch=4, sA=big, sC=64) == ob.ERR_INVALID_ARG
+    assert call(batch=1 << 62, sC=1 << 62) == ob.ERR_INVALID_ARG
+    assert call(K=1 << 50, lda=1 << 50, ldb=8) == ob.ERR_INVALID_ARG
+    L = ob.lib()
+    assert L.optiml_gemm_cross_entropy(1 << 30, 8, 1 << 30, P, 1 << 30, P, 8, None, P, P, 0, 0, None) == ob.ERR_INVALID_ARG
+
+
+def test_set_workspace_validates_on_the_host():
+    L = ob.lib()
+    assert L.optiml_set_workspace(P, -1) == ob.ERR_INVALID_ARG
+    assert L.optiml_set_workspace(None, 4096) == ob.ERR_INVALID_ARG
+    assert L.optiml_set_workspace(P, 0) == ob.ERR_INVALID_ARG
+    assert L.optiml_set_workspace(P + 16, 4096) == ob.ERR_INVALID_ARG      # not 256-byte aligned
