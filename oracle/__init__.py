@@ -56,6 +56,10 @@ def lib():
         L.oracle_cross_entropy.argtypes = [i64, i64, vp, vp]
         L.oracle_cross_entropy_f64.restype = C.c_double
         L.oracle_cross_entropy_f64.argtypes = [i64, i64, vp, vp]
+        L.oracle_cross_entropy_rows_f64.restype = None
+        L.oracle_cross_entropy_rows_f64.argtypes = [i64, i64, vp, vp, vp]
+        L.oracle_layernorm_f64.restype = None
+        L.oracle_layernorm_f64.argtypes = [i64, i64, vp, C.c_double, vp]
         L.oracle_transpose.restype = None
         L.oracle_transpose.argtypes = [i64, i64, vp, vp, i64]
         L.oracle_layernorm.restype = None
@@ -203,6 +207,29 @@ def gemm_cross_entropy(A, B, bias, labels, M, N, K, *, dtype=F32, layout=LAYOUT_
     if labels.shape != (M,):
         raise ValueError("labels [M] expected")
     return float(lib().oracle_cross_entropy_f64(M, N, _ptr(z), _ptr(labels)))
+
+
+def gemm_cross_entropy_rows(A, B, bias, labels, M, N, K, *, dtype=F32, layout=LAYOUT_RR):
+    """The M per-row losses log(sum_j exp(z_ij)) - z_{i, label_i} of the same fused operation (fp64 array [M]); their
+    mean in row order is what gemm_cross_entropy returns up to the order of the additions."""
+    z = gemm_epilogue(A, B, bias, M, N, K, dtype=dtype, act=ACT_NONE, layout=layout)[0]
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    if labels.shape != (M,):
+        raise ValueError("labels [M] expected")
+    out = np.empty(M, dtype=np.float64)
+    lib().oracle_cross_entropy_rows_f64(M, N, _ptr(z), _ptr(labels), _ptr(out))
+    return out
+
+
+def gemm_layernorm(A, B, bias, M, N, K, *, dtype=F32, layout=LAYOUT_RR, eps=1e-5):
+    """LayerNorm (Table 4, task 4: mean and biased variance of a row, no scale or shift) of every row of
+    z = A.B + bias (task 2), every step in fp64: the product is never rounded before it is normalised.  fp64 [M, N]."""
+    z = gemm_epilogue(A, B, bias, M, N, K, dtype=dtype, act=ACT_NONE, layout=layout)[0]
+    z = np.ascontiguousarray(z, dtype=np.float64).reshape(M, N)
+    y = np.empty((M, N), dtype=np.float64)
+    lib().oracle_layernorm_f64(M, N, _ptr(z), float(eps), _ptr(y))
+    return y
 
 
 def transpose(x):

@@ -137,6 +137,26 @@ double oracle_cross_entropy_f64(int64_t N, int64_t C, const double *z, const int
 }
 
 /*
+ * The per-row losses of the same cross-entropy on fp64 logits, loss_j = log(sum_k exp(z_jk)) -
+ * z_{j, y_j} with the row maximum taken out first (same steps as above, nothing summed over rows):
+ * what the fused contraction + cross-entropy is compared with row by row.  A label outside [0, C)
+ * gives NaN for that row.
+ */
+void oracle_cross_entropy_rows_f64(int64_t N, int64_t C, const double *z, const int32_t *labels, double *loss)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        const double *row = z + j * C;
+        if (labels[j] < 0 || labels[j] >= C) { loss[j] = NAN; continue; }
+        double m = row[0];
+        for (int64_t k = 1; k < C; ++k) m = row[k] > m ? row[k] : m;
+        double e = 0.0;
+        for (int64_t k = 0; k < C; ++k) e += exp(row[k] - m);
+        loss[j] = log(e) - (row[labels[j]] - m);
+    }
+}
+
+/*
  * LayerNorm of `rows` samples of `len` features each.  Two passes per row in fp64: the mean
  * (sum in index order / len), then the biased variance as the mean of squared deviations from
  * that mean (not E[x^2] - mean^2), then y = (x - mean) / sqrt(var + eps).  Results kept in fp64.
@@ -154,6 +174,26 @@ void oracle_layernorm(int64_t rows, int64_t len, const float *x, double eps, dou
         for (int64_t i = 0; i < len; ++i) q += ((double)xr[i] - mean) * ((double)xr[i] - mean);
         const double rstd = 1.0 / sqrt(q / (double)len + eps);
         for (int64_t i = 0; i < len; ++i) yr[i] = ((double)xr[i] - mean) * rstd;
+    }
+}
+
+/*
+ * The same LayerNorm for rows that are already fp64 (the contraction fused with LayerNorm keeps
+ * its products unrounded): identical steps, no conversion.
+ */
+void oracle_layernorm_f64(int64_t rows, int64_t len, const double *x, double eps, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * len;
+        double *yr = y + r * len;
+        double s = 0.0;
+        for (int64_t i = 0; i < len; ++i) s += xr[i];
+        const double mean = s / (double)len;
+        double q = 0.0;
+        for (int64_t i = 0; i < len; ++i) q += (xr[i] - mean) * (xr[i] - mean);
+        const double rstd = 1.0 / sqrt(q / (double)len + eps);
+        for (int64_t i = 0; i < len; ++i) yr[i] = (xr[i] - mean) * rstd;
     }
 }
 

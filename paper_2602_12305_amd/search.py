@@ -321,7 +321,7 @@ def best_keep_chain(root: Node):
 class Evaluator:
     def __init__(self, workload: str, fam: Family, steps: int, warmup: int):
         from .sweep import Runner
-        from . import synth
+        from inputs import synth
         self.r = Runner(workload)
         self.fam, self.steps, self.warmup = fam, steps, warmup
         w, np = self.r.w, self.r.np

@@ -60,7 +60,7 @@ class Runner:
         import numpy as np
         import torch
         from . import binding as ob
-        from . import synth
+        from inputs import synth
         self.np, self.torch, self.ob, self.synth = np, torch, ob, synth
         w = synth.make_workload(name)
         self.w = w
@@ -167,7 +167,7 @@ def main():
                 pass
 
     # shape-only support query needs device pointers for alignment: use aligned fakes (host logic only)
-    from . import synth
+    from inputs import synth
     shapes = {"c1_f32_256_relu": (1, 256, 256, 256, 0, 0), "c2_f32_skinny16_silu": (1, 16, 16384, 16384, 0, 0),
               "c3_f32_4096_rc_gelu": (1, 4096, 4096, 4096, 1, 0), "c4_bf16_8192_silu": (1, 8192, 8192, 8192, 0, 1),
               "c5_bf16_batched32_relu": (32, 2048, 2048, 512, 0, 1)}

@@ -5,7 +5,8 @@ import numpy as np
 import torch
 
 import oracle
-from paper_2602_12305_amd import binding, synth
+from inputs import synth
+from paper_2602_12305_amd import binding
 from helpers import e1, store
 
 # binary16: one rounding of the output, half a step = 2^-12 .. 2^-11 relative across a binade (4.9e-4 at most),

@@ -7,7 +7,7 @@ from fractions import Fraction
 
 import numpy as np
 
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 getcontext().prec = 60
 

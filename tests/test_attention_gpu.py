@@ -12,7 +12,7 @@ import torch
 
 import oracle
 from paper_2602_12305_amd import binding as ob
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 pytestmark = pytest.mark.gpu
 F32, BF16, F16 = 0, 1, 2

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2602_12305_amd import binding as ob
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 pytestmark = pytest.mark.gpu
 

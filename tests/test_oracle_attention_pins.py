@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 
 def rand(seed, batch, N, d):

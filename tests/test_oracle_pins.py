@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2602_12305_amd import synth
+from inputs import synth
 from helpers import act_decimal, as_real, exact_z, store
 
 F32, BF16 = synth.DTYPE_F32, synth.DTYPE_BF16

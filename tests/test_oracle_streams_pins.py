@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 SUM, DOT, MSE = oracle.RED_SUM, oracle.RED_DOT, oracle.RED_MSE
 
@@ -262,6 +262,86 @@ def test_fused_contraction_cross_entropy_closed_forms():
     # out-of-range label: NaN; no rows: 0
     bad = labels.copy(); bad[3] = N
     assert math.isnan(oracle.gemm_cross_entropy(A, Z, None, bad, M, N, K))
+
+
+@pytest.mark.parametrize("dtype,layout", [(oracle.F32, 0), (oracle.BF16, 1), (oracle.F16, 3)])
+def test_fused_contraction_cross_entropy_row_losses(dtype, layout):
+    from scipy.special import logsumexp
+    M, N, K = 19, 37, 23
+    A = synth.normal(73, "A", M, K); B = synth.normal(73, "B", K, N); bias = synth.normal(73, "bias", 1, N)[0]
+    labels = ((5 * np.arange(M) + 36) % N).astype(np.int32)          # row 0 takes the last class
+    As = synth.to_bits(A.T if layout & 2 else A, dtype); Bs = synth.to_bits(B.T if layout & 1 else B, dtype)
+    rows = oracle.gemm_cross_entropy_rows(As, Bs, bias, labels, M, N, K, dtype=dtype, layout=layout)
+    assert rows.shape == (M,) and rows.dtype == np.float64
+    Ad = synth.from_bits(synth.to_bits(A, dtype), dtype).astype(np.float64)
+    Bd = synth.from_bits(synth.to_bits(B, dtype), dtype).astype(np.float64)
+    z = Ad @ Bd + bias.astype(np.float64)
+    want = logsumexp(z, axis=1) - z[np.arange(M), labels]             # a library routine the oracle does not call
+    assert np.allclose(rows, want, rtol=1e-13, atol=1e-14)
+    # the mean of the rows is the scalar the other oracle function returns
+    assert float(np.mean(rows)) == pytest.approx(oracle.gemm_cross_entropy(As, Bs, bias, labels, M, N, K, dtype=dtype, layout=layout), rel=1e-14)
+    # a row's loss depends on its own label only; a wrong label in one row moves that row alone
+    other = labels.copy(); other[4] = (other[4] + 1) % N
+    rows2 = oracle.gemm_cross_entropy_rows(As, Bs, bias, other, M, N, K, dtype=dtype, layout=layout)
+    assert abs(rows2[4] - rows[4]) > 1e-9 and np.array_equal(np.delete(rows2, 4), np.delete(rows, 4))
+    # closed forms: zero weights -> log-sum-exp of the bias minus the label's bias, whatever the row
+    Z = np.zeros_like(Bs)
+    b64 = bias.astype(np.float64)
+    rz = oracle.gemm_cross_entropy_rows(As, Z, bias, labels, M, N, K, dtype=dtype, layout=layout)
+    assert np.allclose(rz, logsumexp(b64) - b64[labels], rtol=1e-14)
+    bad = labels.copy(); bad[2] = -1
+    rb = oracle.gemm_cross_entropy_rows(As, Bs, bias, bad, M, N, K, dtype=dtype, layout=layout)
+    assert math.isnan(rb[2]) and np.array_equal(np.delete(rb, 2), np.delete(rows, 2))
+
+
+# ---- the contraction followed by LayerNorm over each row of the product (task 2 into task 4) ------------------
+@pytest.mark.parametrize("dtype,layout", [(oracle.F32, 0), (oracle.BF16, 1), (oracle.F16, 2), (oracle.F32, 3)])
+def test_fused_contraction_layernorm_against_library_routines(dtype, layout):
+    M, N, K = 11, 53, 29
+    A = synth.normal(74, "A", M, K); B = synth.normal(74, "B", K, N); bias = synth.normal(74, "bias", 1, N)[0]
+    As = synth.to_bits(A.T if layout & 2 else A, dtype); Bs = synth.to_bits(B.T if layout & 1 else B, dtype)
+    eps = 1e-3
+    got = oracle.gemm_layernorm(As, Bs, bias, M, N, K, dtype=dtype, layout=layout, eps=eps)
+    assert got.shape == (M, N) and got.dtype == np.float64
+    Ad = synth.from_bits(synth.to_bits(A, dtype), dtype).astype(np.float64)
+    Bd = synth.from_bits(synth.to_bits(B, dtype), dtype).astype(np.float64)
+    z = Ad @ Bd + bias.astype(np.float64)                             # numpy's matmul, mean and var: not the oracle's loops
+    want = (z - z.mean(axis=1, keepdims=True)) / np.sqrt(z.var(axis=1, keepdims=True) + eps)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
+    # a dropped bias, a transposed operand or eps in the wrong place all move the values
+    assert np.max(np.abs(oracle.gemm_layernorm(As, Bs, None, M, N, K, dtype=dtype, layout=layout, eps=eps) - want)) > 1e-3
+    assert np.max(np.abs(oracle.gemm_layernorm(As, Bs, bias, M, N, K, dtype=dtype, layout=layout, eps=10 * eps) - want)) > 1e-4
+    unbiased = (z - z.mean(axis=1, keepdims=True)) / np.sqrt(z.var(axis=1, ddof=1, keepdims=True) + eps)
+    assert np.max(np.abs(got - unbiased)) > 1e-3                      # the variance divides by N, not N - 1
+
+
+def test_fused_contraction_layernorm_closed_forms():
+    M, N, K = 7, 24, 8
+    A = synth.normal(75, "A", M, K); Z = np.zeros((K, N), dtype=np.float32)
+    bias = synth.normal(75, "bias", 1, N)[0]
+    # zero weights: every row is LayerNorm of the bias
+    got = oracle.gemm_layernorm(A, Z, bias, M, N, K, eps=1e-5)
+    one = oracle.layernorm(bias[None, :], eps=1e-5)[0]
+    assert all(np.array_equal(got[i], one) for i in range(M))
+    # integer operands: the product is exact in fp32, so LayerNorm of the rounded product agrees
+    Ai = synth.integers(76, "A", M, K); Bi = synth.integers(76, "B", K, N); bi = synth.integers(76, "bias", 1, N)[0]
+    z = oracle.gemm_epilogue(Ai, Bi, bi, M, N, K)[0]
+    assert np.array_equal(z, z.astype(np.float32).astype(np.float64))
+    assert np.array_equal(oracle.gemm_layernorm(Ai, Bi, bi, M, N, K, eps=0.5), oracle.layernorm(z.astype(np.float32), eps=0.5))
+    # rank one, eps = 0: z_ij = u_i v_j, so a row is sign(u_i) LayerNorm(v) whatever |u_i| (powers of two: exact)
+    u = np.array([[1.0], [-2.0], [0.25]], dtype=np.float32); v = synth.normal(77, "v", 1, N)
+    r1 = oracle.gemm_layernorm(u, v, None, 3, N, 1, eps=0.0)
+    lv = oracle.layernorm(v, eps=0.0)[0]
+    assert np.allclose(r1[0], lv, rtol=1e-13) and np.allclose(r1[1], -lv, rtol=1e-13) and np.allclose(r1[2], lv, rtol=1e-13)
+    # exact rational statistics of one row (brute force, k descending)
+    Ab = synth.integers(78, "A", 1, 5, -7, 7); Bb = synth.uniform(78, "B", 5, 6); bb = synth.uniform(78, "bias", 1, 6)[0]
+    zr = [sum((Fraction(float(Ab[0, k])) * Fraction(float(Bb[k, j])) for k in reversed(range(5))), Fraction(float(bb[j])))
+          for j in range(6)]
+    mean = sum(zr) / 6
+    var = sum((t - mean) ** 2 for t in zr) / 6
+    yb = oracle.gemm_layernorm(Ab, Bb, bb, 1, 6, 5, eps=0.0)[0]
+    for j in range(6):
+        assert yb[j] == pytest.approx(float(zr[j] - mean) / math.sqrt(float(var)), rel=1e-12)
 
 
 def test_transpose_moves_every_element_to_its_mirror_position():

@@ -13,7 +13,7 @@ import torch
 
 import oracle
 from paper_2602_12305_amd import binding as ob
-from paper_2602_12305_amd import synth
+from inputs import synth
 from gpu_harness import TOL, check_against_oracle, run_gpu, to_dev
 from helpers import e1, store
 

@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from paper_2602_12305_amd import synth
+from inputs import synth
 
 
 def test_deterministic_and_tag_seed_dependent():

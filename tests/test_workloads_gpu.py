@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from paper_2602_12305_amd import binding as ob
-from paper_2602_12305_amd import synth
+from inputs import synth
 from gpu_harness import TOL, c_values, alloc_c, to_dev
 from helpers import e1
 
