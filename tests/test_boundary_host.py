@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 22
+    assert len(names) == 23
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -265,3 +265,11 @@ def test_set_workspace_validates_on_the_host():
     assert L.optiml_set_workspace(None, 4096) == ob.ERR_INVALID_ARG
     assert L.optiml_set_workspace(P, 0) == ob.ERR_INVALID_ARG
     assert L.optiml_set_workspace(P + 16, 4096) == ob.ERR_INVALID_ARG      # not 256-byte aligned
+
+
+def test_mfma_probe_validates_on_the_host():
+    L = ob.lib()
+    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, -1, 1, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, 10, 0, None, None) == ob.ERR_INVALID_ARG     # fp32: not offered
+    assert L.optiml_mfma_probe(None, 1 << 30, P, 1 << 30, 10, 1, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_mfma_probe(P + 8, 1 << 30, P, 1 << 30, 10, 1, None, None) == ob.ERR_INVALID_ARG
