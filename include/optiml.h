@@ -335,6 +335,28 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
 int optiml_set_workspace(void *ptr, int64_t bytes);
 int64_t optiml_workspace_bytes(void);
 
+/*
+ * optiml_gemm_epilogue_strided_batched for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bitwise the same C; what the kernels need beyond A, B, bias and C (split-K partial
+ * sums, operand copies) lives in a static array of OPTIML_NOALLOC_SCRATCH_BYTES in the library's
+ * device image - one copy per GPU, held until the process ends - instead of the workspace, so the
+ * call never allocates or frees, on the first call or any other, and never touches the buffer of
+ * optiml_set_workspace.  A problem whose kernels need more than that returns OPTIML_ERR_UNSUPPORTED
+ * and enqueues nothing (the split-K partial sums of M <= 16 fit for every N x split <= 262144; the
+ * copy paths for column-major A, 8-bit operands in other layouts and unaligned problems fit while
+ * their copies do).  The array keeps the last call's contents; nothing in it has to start at zero.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or graphs replayed concurrently) race; calls ordered on one stream do not.
+ */
+#define OPTIML_NOALLOC_SCRATCH_BYTES (16u << 20)
+int optiml_gemm_epilogue_noalloc(int64_t batch, int64_t M, int64_t N, int64_t K,
+                                 const void *A, int64_t lda, int64_t strideA,
+                                 const void *B, int64_t ldb, int64_t strideB,
+                                 const float *bias, int64_t strideBias,
+                                 void *C, int64_t ldc, int64_t strideC,
+                                 int layout, int dtype, int act, void *stream);
+
 /* Human-readable text for a status code; static storage. */
 const char *optiml_status_string(int status);
 

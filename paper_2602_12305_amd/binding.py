@@ -26,6 +26,7 @@ SIGNATURES = {
     "optiml_gemm_epilogue": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int, _vp]),
     "optiml_gemm_epilogue_ex": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int, _int, _vp]),
     "optiml_gemm_epilogue_strided_batched": (_int, _PROBLEM + [_vp]),
+    "optiml_gemm_epilogue_noalloc": (_int, _PROBLEM + [_vp]),
     "optiml_variant_count": (_int, []),
     "optiml_variant_name": (C.c_char_p, [_int]),
     "optiml_select_variant": (_int, _PROBLEM),
@@ -117,6 +118,13 @@ def optiml_gemm_epilogue_ex(M, N, K, A, lda, B, ldb, bias, Cout, ldc, layout, dt
 def optiml_gemm_epilogue_strided_batched(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
                                          Cout, ldc, strideC, layout, dtype, act, stream=None):
     return _check(lib().optiml_gemm_epilogue_strided_batched(
+        batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB, _addr(bias), strideBias,
+        _addr(Cout), ldc, strideC, layout, dtype, act, _stream(stream)))
+
+
+def optiml_gemm_epilogue_noalloc(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias,
+                                 Cout, ldc, strideC, layout, dtype, act, stream=None):
+    return _check(lib().optiml_gemm_epilogue_noalloc(
         batch, M, N, K, _addr(A), lda, strideA, _addr(B), ldb, strideB, _addr(bias), strideBias,
         _addr(Cout), ldc, strideC, layout, dtype, act, _stream(stream)))
 

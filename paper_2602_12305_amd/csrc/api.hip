@@ -6,6 +6,11 @@
 #include <mutex>
 #include <vector>
 
+// Device memory for optiml_gemm_epilogue_noalloc: one copy per GPU the library runs on, held until
+// the process ends.  In host code this name is a stand-in, not a device address: the address comes
+// from hipGetSymbolAddress (static_scratch() below) and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[OPTIML_NOALLOC_SCRATCH_BYTES];
+
 namespace optiml {
 
 namespace {
@@ -688,6 +693,59 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
     if (path < 0) return OPTIML_ERR_UNSUPPORTED;
     hipError_t e = optiml::launch_mhsa(batch, N, d_model, heads, Q, K, V, O, dtype, path, static_cast<hipStream_t>(stream));
     return status_of(e);
+}
+
+namespace {
+std::mutex g_static_mutex;
+void *g_static_ptr[64] = {};
+
+// device address of this GPU's copy of `scratch` (looked up once per device, with it current)
+hipError_t static_scratch(void **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!q) return hipErrorInvalidSymbol;
+        g_static_ptr[dev] = q;
+    }
+    *ptr = g_static_ptr[dev];
+    return hipSuccess;
+}
+
+struct FixedWorkspaceScope {
+    FixedWorkspaceScope(void *p, size_t bytes) { tls_fixed_workspace.ptr = p; tls_fixed_workspace.bytes = bytes; }
+    ~FixedWorkspaceScope() { tls_fixed_workspace = FixedWorkspace(); }
+};
+}  // namespace
+
+int optiml_gemm_epilogue_noalloc(int64_t batch, int64_t M, int64_t N, int64_t K,
+                                 const void *A, int64_t lda, int64_t strideA,
+                                 const void *B, int64_t ldb, int64_t strideB,
+                                 const float *bias, int64_t strideBias,
+                                 void *C, int64_t ldc, int64_t strideC,
+                                 int layout, int dtype, int act, void *stream)
+{
+    const Problem p = make(batch, M, N, K, A, lda, strideA, B, ldb, strideB, bias, strideBias, C, ldc, strideC,
+                           layout, dtype, act);
+    const int st = validate(p);
+    if (st != OPTIML_OK || is_empty(p)) return st;
+    void *fixed = nullptr;
+    const hipError_t e = static_scratch(&fixed);
+    if (e != hipSuccess) {
+        tls_last_hip_error = (int)e;
+        return OPTIML_ERR_HIP;
+    }
+    const int id = select(p);
+    if (id < 0) return id;
+    // while this lives, workspace() hands out the static array and refuses what does not fit
+    const FixedWorkspaceScope scope(fixed, OPTIML_NOALLOC_SCRATCH_BYTES);
+    return run(p, id, stream);
 }
 
 int optiml_set_workspace(void *ptr, int64_t bytes)
