@@ -306,6 +306,17 @@ int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *
                                    const float *bias, int layout, int dtype);
 
 /*
+ * The same fused operation with the per-row losses handed out (the "no reduction" form of task 17):
+ * row_loss[i] = log sum_j exp(z[i][j]) - z[i][labels[i]] for every row i, M floats, DEVICE pointer,
+ * each rounded once from the fp64 value the mean is formed from (NaN for a label outside [0, N)).
+ * loss (one float, DEVICE pointer) receives the mean as above and may be NULL.  Same kernels, same
+ * workspace use, same argument rules; OPTIML_ERR_INVALID_ARG also for a NULL row_loss with M > 0.
+ */
+int optiml_gemm_cross_entropy_rows(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                                   const float *bias, const int32_t *labels, float *row_loss, float *loss, int layout,
+                                   int dtype, void *stream);
+
+/*
  * Multi-head self-attention (the paper's Table 4, task 6): for Q, K, V of shape [batch][N][d_model]
  * (row-major, contiguous, DEVICE pointers; float for OPTIML_F32, 16-bit for OPTIML_BF16 / OPTIML_F16) and
  * `heads` heads of width d_k = d_model / heads,

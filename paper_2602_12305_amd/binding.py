@@ -42,6 +42,7 @@ SIGNATURES = {
     "optiml_mhsa": (_int, [_i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _int, _vp]),
     "optiml_transpose": (_int, [_i64, _i64, _vp, _i64, _vp, _i64, _int, _vp]),
     "optiml_gemm_cross_entropy": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _int, _int, _vp]),
+    "optiml_gemm_cross_entropy_rows": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _int, _int, _vp]),
     "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
     "optiml_set_workspace": (_int, [_vp, _i64]),
     "optiml_workspace_bytes": (_i64, []),
@@ -205,6 +206,11 @@ def optiml_transpose(rows, cols, src, ld_src, dst, ld_dst, elem_bytes, stream=No
 def optiml_gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, layout, dtype, stream=None):
     return _check(lib().optiml_gemm_cross_entropy(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(labels),
                                                   _addr(loss), layout, dtype, _stream(stream)))
+
+
+def optiml_gemm_cross_entropy_rows(M, N, K, A, lda, B, ldb, bias, labels, row_loss, loss, layout, dtype, stream=None):
+    return _check(lib().optiml_gemm_cross_entropy_rows(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(labels),
+                                                       _addr(row_loss), _addr(loss), layout, dtype, _stream(stream)))
 
 
 def optiml_gemm_cross_entropy_path(M, N, K, A, lda, B, ldb, bias, layout, dtype):

@@ -642,11 +642,13 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
     return status_of(e);
 }
 
-int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
-                              const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream)
+namespace {
+int gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                       const float *bias, const int32_t *labels, float *loss, float *row_loss, int layout, int dtype,
+                       void *stream)
 {
     if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
-    if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0 || !loss) return OPTIML_ERR_INVALID_ARG;
+    if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0) return OPTIML_ERR_INVALID_ARG;
     {
         // operand spans below 2^47 elements, as in validate()
         constexpr int64_t kMaxSpan = int64_t(1) << 47;
@@ -666,8 +668,23 @@ int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, in
             if (lda < (p.a_col() ? M : K) || ldb < (p.b_col() ? K : N)) return OPTIML_ERR_INVALID_ARG;
         }
     }
-    hipError_t e = optiml::launch_linear_ce(p, labels, loss, static_cast<hipStream_t>(stream));
-    return status_of(e);
+    return status_of(optiml::launch_linear_ce(p, labels, loss, row_loss, static_cast<hipStream_t>(stream)));
+}
+}  // namespace
+
+int optiml_gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                              const float *bias, const int32_t *labels, float *loss, int layout, int dtype, void *stream)
+{
+    if (!loss) return OPTIML_ERR_INVALID_ARG;
+    return gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, nullptr, layout, dtype, stream);
+}
+
+int optiml_gemm_cross_entropy_rows(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                                   const float *bias, const int32_t *labels, float *row_loss, float *loss, int layout,
+                                   int dtype, void *stream)
+{
+    if (!row_loss && M > 0) return OPTIML_ERR_INVALID_ARG;
+    return gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, row_loss, layout, dtype, stream);
 }
 
 int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,

@@ -87,7 +87,8 @@ hipError_t launch_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads,
 // contraction + cross-entropy (kernel_linear_ce.hip): which path would serve (0 ring kernel with the
 // log-sum-exp epilogue, 1 row-per-workgroup fallback), launch; p.C, ldc, act and batch are ignored
 int linear_ce_path(const Problem &p);
-hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hipStream_t stream);
+// loss: the mean over rows (may be null); row_loss: every row's loss (may be null)
+hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, float *row_loss, hipStream_t stream);
 
 // transpose (kernel_transpose.hip), arguments already validated
 hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int esize,

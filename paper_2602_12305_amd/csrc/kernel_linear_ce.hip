@@ -70,10 +70,10 @@ __global__ __launch_bounds__(256) void lce_fallback_kernel(Problem p, const int 
 // its row in fp64 (pairs are slice-major: row i, slice q at part[2 (q M + i)], so the threads of
 // one group read consecutive rows), then the row's groups are merged in group order,
 // loss_i = log(S) + (max - z_label) (a label outside [0, N) gives NaN), and the rows are added in
-// row order.
+// row order.  row_loss, if given, receives every row's loss rounded once to float.
 __global__ __launch_bounds__(kRowsPerBlock * kGroups) void lce_rows_kernel(const float *part, int64_t slices, int64_t M,
                                                                           int64_t N, const int *labels, const float *picked,
-                                                                          double *block_sums)
+                                                                          double *block_sums, float *row_loss)
 {
     __shared__ double sh_hi[kGroups][kRowsPerBlock], sh_s[kGroups][kRowsPerBlock], sh_loss[kRowsPerBlock];
     const int r = threadIdx.x % kRowsPerBlock, g = threadIdx.x / kRowsPerBlock;
@@ -102,6 +102,7 @@ __global__ __launch_bounds__(kRowsPerBlock * kGroups) void lce_rows_kernel(const
         if (i < M) {
             const int label = labels[i];
             loss = (label < 0 || label >= N) ? (double)__builtin_nanf("") : log(S) + (hi - (double)picked[i]);
+            if (row_loss) row_loss[i] = (float)loss;
         }
         sh_loss[r] = loss;
     }
@@ -175,7 +176,7 @@ int linear_ce_path(const Problem &p)
     return p.K > 0 && !p.a_col() && ring_takes(q) ? 0 : 1;
 }
 
-hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hipStream_t stream)
+hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, float *row_loss, hipStream_t stream)
 {
     const int path = linear_ce_path(p);
     // a pair per row and wave-wide slice of columns: 4 slices per 256-column (fp32: 128-column) tile
@@ -190,6 +191,7 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
     float *picked = reinterpret_cast<float *>(static_cast<char *>(ws) + part_bytes);
     double *block_sums = reinterpret_cast<double *>(static_cast<char *>(ws) + part_bytes + pick_bytes);
     if (p.M == 0) {                                   // no rows: the mean of nothing is 0
+        if (!loss) return hipSuccess;
         hipLaunchKernelGGL(lce_mean_kernel, dim3(1), dim3(64), 0, stream, block_sums, 0, 0, loss);
         return hipGetLastError();
     }
@@ -217,9 +219,10 @@ hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, hi
     if (e != hipSuccess) return e;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(lce_rows_kernel, dim3((unsigned)blocks), dim3(kRowsPerBlock * kGroups), 0, stream, part, slices, p.M, p.N, labels,
-                       picked, block_sums);
+                       picked, block_sums, row_loss);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (!loss) return hipSuccess;
     hipLaunchKernelGGL(lce_mean_kernel, dim3(1), dim3(64), 0, stream, block_sums, blocks, p.M, loss);
     return hipGetLastError();
 }

@@ -23,7 +23,7 @@ pytestmark = pytest.mark.gpu
 F32, BF16, F16 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16
 
 
-def run(As, Bs, bias, labels, M, N, K, layout, dtype):
+def run(As, Bs, bias, labels, M, N, K, layout, dtype, rows=False):
     Ad, Bd = to_dev(As), to_dev(Bs)
     bd = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
     ld = torch.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)).cuda()
@@ -31,21 +31,36 @@ def run(As, Bs, bias, labels, M, N, K, layout, dtype):
     ob.optiml_gemm_cross_entropy(M, N, K, Ad, As.shape[-1], Bd, Bs.shape[-1], bd, ld, out, layout, dtype)
     torch.cuda.synchronize()
     path = ob.optiml_gemm_cross_entropy_path(M, N, K, Ad, As.shape[-1], Bd, Bs.shape[-1], bd, layout, dtype)
-    return float(out.item()), path
+    if not rows:
+        return float(out.item()), path
+    per_row = torch.full((M + 1,), 54321.0, dtype=torch.float32, device="cuda")
+    out2 = torch.full((1,), 12345.0, dtype=torch.float32, device="cuda")
+    ob.optiml_gemm_cross_entropy_rows(M, N, K, Ad, As.shape[-1], Bd, Bs.shape[-1], bd, ld, per_row, out2, layout, dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) or (math.isnan(out.item()) and math.isnan(out2.item()))     # the same mean, bit for bit
+    per_row = per_row.cpu().numpy()
+    assert per_row[M] == 54321.0                                         # nothing written past the M rows
+    return float(out.item()), path, per_row[:M].astype(np.float64)
 
 
-def check(M, N, K, layout, dtype, seed, want_path, *, use_bias=True, pad=0, scale=1.0):
+def check(M, N, K, layout, dtype, seed, want_path, *, use_bias=True, pad=0, scale=1.0, labels=None):
     A = synth.normal(seed, "A", M, K) * np.float32(scale); B = synth.normal(seed, "B", K, N)
     bias = synth.normal(seed, "bias", 1, N)[0] if use_bias else None
-    labels = ((7919 * np.arange(M) + 3) % N).astype(np.int32)
+    if labels is None:
+        labels = ((7919 * np.arange(M) + 3) % N).astype(np.int32)
     As = store(A, dtype, (layout >> 1) & 1, pad); Bs = store(B, dtype, layout & 1, pad)
-    got, path = run(As, Bs, bias, labels, M, N, K, layout, dtype)
+    got, path, got_rows = run(As, Bs, bias, labels, M, N, K, layout, dtype, rows=True)
     assert path == want_path
     _, den = oracle.gemm_epilogue(As, Bs, bias, M, N, K, dtype=dtype, layout=layout, want_absden=True)
+    ref_rows = oracle.gemm_cross_entropy_rows(As, Bs, bias, labels, M, N, K, dtype=dtype, layout=layout)
     ref = oracle.gemm_cross_entropy(As, Bs, bias, labels, M, N, K, dtype=dtype, layout=layout)
     tol = 2 * 16 * 2.0 ** -24 * float(den.max()) + 2e-6 + float(np.spacing(np.float32(abs(ref))))
     assert math.isfinite(got)
     assert abs(got - ref) <= tol, (got, ref, tol)
+    # every row on its own: its logits' error bound, the exponentials, one rounding to float
+    row_tol = 2 * 16 * 2.0 ** -24 * den.reshape(M, N).max(axis=1) + 2e-6 + np.spacing(np.abs(ref_rows).astype(np.float32)).astype(np.float64)
+    worst = int(np.argmax(np.abs(got_rows - ref_rows) - row_tol))
+    assert np.all(np.abs(got_rows - ref_rows) <= row_tol), (worst, got_rows[worst], ref_rows[worst], row_tol[worst], int(labels[worst]))
     again, _ = run(As, Bs, bias, labels, M, N, K, layout, dtype)
     assert again == got                                                  # bitwise repeatable
     return got, ref
@@ -71,6 +86,20 @@ def test_fp32_matrix_pipe_path_matches_the_oracle(layout, M, N, K):
                                                     (BF16, 0, 20, 516, 160, 0), (F32, 0, 3, 1, 16, 0), (F16, 3, 130, 130, 130, 2)])
 def test_fallback_path_matches_the_oracle(dtype, layout, M, N, K, pad):
     check(M, N, K, layout, dtype, 3200 + N, 1, pad=pad)
+
+
+@pytest.mark.parametrize("dtype,layout,M,N,K,path", [(BF16, 0, 300, 520, 160, 0), (F16, 1, 300, 515, 160, 0), (F32, 0, 300, 516, 160, 0),
+                                                     (F32, 1, 130, 1003, 256, 0), (BF16, 0, 600, 2120, 256, 0), (F32, 3, 37, 263, 29, 1)])
+def test_every_row_with_its_label_in_the_ragged_last_slice_of_columns(dtype, layout, M, N, K, path):
+    """Labels in the last, partly filled wave-wide slice of columns (64 for 16-bit storage, 32 for fp32) and in the
+    last column of every full slice before it, rows in several 256-row tiles with a ragged last tile."""
+    width = 32 if dtype == F32 else 64
+    tail = list(range((N - 1) // width * width, N))                       # the columns of the ragged slice
+    ends = list(range(width - 1, N, width)) + [0, N - 1]
+    pool = np.array(tail * 3 + ends, dtype=np.int64)
+    labels = pool[(5 * np.arange(M)) % len(pool)].astype(np.int32)
+    assert (labels >= (N - 1) // width * width).sum() >= M // 3
+    check(M, N, K, layout, dtype, 3700 + N, path, labels=labels)
 
 
 def test_closed_forms_and_degenerate_cases_on_the_gpu():
