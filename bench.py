@@ -481,19 +481,22 @@ def main():
         out["copy_GBs"] = round(2 * nbytes / (ms * 1e-3) / 1e9, 1)
         del src, dst
         cus = torch.cuda.get_device_properties(0).multi_processor_count
-        n16 = cus * 256 * 64                                        # 16-bit operand values the probe reads
+        n16 = cus * 32768                                           # 16-bit operand values the probe may read
         sink = torch.empty(cus * 256, dtype=torch.float32, device="cuda")
         normal = synth.f32_to_bf16_bits(synth.normal(12, "probe", n16 >> 10, 1 << 10)).view(np.int16).reshape(-1)
-        for tag, host in (("zeros", np.zeros(n16, dtype=np.int16)), ("normal", normal)):
+        for tag, host, reads in (("zeros", np.zeros(n16, dtype=np.int16), 0), ("normal", normal, 0),
+                                 ("normal_lds8", normal, 8), ("normal_lds12", normal, 12)):
             ops = torch.from_numpy(host).cuda()
             flops = [0.0]
 
             def probe(i):
-                flops[0] = ob.optiml_mfma_probe(ops, n16 * 2, sink, cus * 256, 4000, 1)
+                flops[0] = ob.optiml_mfma_probe(ops, n16 * 2, sink, cus * 256, 4000, 1, reads)
             ms, _ = run_timed(probe, 20, 3, 300.0)
             out[f"mfma_bf16_{tag}_TFLOPs"] = round(flops[0] / (ms * 1e-3) / 1e12, 1)
-        out["note"] = ("plain 1 GiB copy (read + write); register-only loop of 32x32x16 bf16 matrix instructions on "
-                       "all-zero and on N(0,1) operands, no memory traffic: the board's own ceilings under its power limit")
+        out["note"] = ("plain 1 GiB copy (read + write); loop of 32x32x16 bf16 matrix instructions with no global-memory "
+                       "traffic on all-zero and on N(0,1) operands held in registers, and on N(0,1) operands read from "
+                       "LDS at 8 or 12 fragment reads per 16 instructions (128x128 / 128x64 wave tiles): the board's "
+                       "own ceilings under its power limit")
         return out
 
     if args.copy_gib > 0:

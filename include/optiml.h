@@ -204,19 +204,22 @@ int optiml_copy_bytes(void *dst, const void *src, int64_t nbytes, void *stream);
 /*
  * Matrix-pipe rate probe, the companion of optiml_copy_bytes for the other roof: one workgroup per
  * compute unit runs `iters` rounds of sixteen 32x32x16 matrix instructions (OPTIML_BF16 or
- * OPTIML_F16) on operand fragments read ONCE from `operands` - no memory traffic in the loop - so
- * the time of a launch gives the rate the board sustains on operands of that value distribution
- * (the paper's reward prices kernels in percent of a speed of light, section 3.2; on a
- * power-limited board that light is slower for operands whose bits toggle more).  `operands`:
- * DEVICE pointer, 16-byte aligned, at least 32768 bytes per compute unit of 16-bit values, read
- * only; `sink`: DEVICE pointer to at least 256 floats per compute unit, overwritten (checksums, so
- * that the loop is not optimised away).  *flops (HOST pointer, may be NULL) receives the number of
- * floating-point operations the launch performs.  Enqueued on `stream`.
- * OPTIML_ERR_INVALID_ARG: iters < 0, another dtype, a NULL or misaligned pointer, buffers too
- * small.  The size checks need the device's compute-unit count and so a GPU.
+ * OPTIML_F16) with no global-memory traffic in the loop, so the time of a launch gives the rate
+ * the board sustains on operands of that value distribution (the paper's reward prices kernels in
+ * percent of a speed of light, section 3.2; on a power-limited board that light is slower for
+ * operands whose bits toggle more, and slower again when the operands have to come from LDS).
+ * lds_reads: 0 - operand fragments are read once and stay in registers; 8, 12 or 16 - every
+ * k-step's operands are read from LDS (filled once from `operands`), that many 16-byte-per-lane
+ * reads per sixteen instructions: the ratio of a 128x128, 128x64 or 64x64 wave tile.
+ * `operands`: DEVICE pointer, 16-byte aligned, at least 65536 bytes per compute unit of 16-bit
+ * values, read only; `sink`: DEVICE pointer to at least 256 floats per compute unit, overwritten
+ * (checksums, so that the loop is not optimised away).  *flops (HOST pointer, may be NULL) receives
+ * the number of floating-point operations the launch performs.  Enqueued on `stream`.
+ * OPTIML_ERR_INVALID_ARG: iters < 0, another dtype or lds_reads, a NULL or misaligned pointer,
+ * buffers too small.  The size checks need the device's compute-unit count and so a GPU.
  */
 int optiml_mfma_probe(const void *operands, int64_t operand_bytes, float *sink, int64_t sink_floats,
-                      int64_t iters, int dtype, double *flops, void *stream);
+                      int64_t iters, int dtype, int lds_reads, double *flops, void *stream);
 
 /*
  * Bandwidth-bound siblings of the contraction from the paper's Table 4, on float arrays of n

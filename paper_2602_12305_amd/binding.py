@@ -34,7 +34,7 @@ SIGNATURES = {
     "optiml_gemm_epilogue_variant": (_int, _PROBLEM + [_vp, _int]),
     "optiml_variant_resources": (_int, [_int, C.POINTER(_int), C.POINTER(_int), C.POINTER(_int)]),
     "optiml_copy_bytes": (_int, [_vp, _vp, _i64, _vp]),
-    "optiml_mfma_probe": (_int, [_vp, _i64, _vp, _i64, _i64, _int, C.POINTER(C.c_double), _vp]),
+    "optiml_mfma_probe": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _int, C.POINTER(C.c_double), _vp]),
     "optiml_elementwise": (_int, [_i64, _vp, _vp, _int, _vp]),
     "optiml_reduce": (_int, [_i64, _vp, _vp, _int, _vp, _vp]),
     "optiml_cross_entropy": (_int, [_i64, _i64, _vp, _i64, _vp, _vp, _vp]),
@@ -170,10 +170,10 @@ def optiml_copy_bytes(dst, src, nbytes, stream=None):
     return _check(lib().optiml_copy_bytes(_addr(dst), _addr(src), nbytes, _stream(stream)))
 
 
-def optiml_mfma_probe(operands, operand_bytes, sink, sink_floats, iters, dtype, stream=None):
+def optiml_mfma_probe(operands, operand_bytes, sink, sink_floats, iters, dtype, lds_reads=0, stream=None):
     """Enqueue the matrix-pipe rate probe; returns the number of flops the launch performs."""
     flops = C.c_double(0.0)
-    _check(lib().optiml_mfma_probe(_addr(operands), operand_bytes, _addr(sink), sink_floats, iters, dtype,
+    _check(lib().optiml_mfma_probe(_addr(operands), operand_bytes, _addr(sink), sink_floats, iters, dtype, lds_reads,
                                    C.byref(flops), _stream(stream)))
     return flops.value
 

@@ -269,7 +269,8 @@ def test_set_workspace_validates_on_the_host():
 
 def test_mfma_probe_validates_on_the_host():
     L = ob.lib()
-    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, -1, 1, None, None) == ob.ERR_INVALID_ARG
-    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, 10, 0, None, None) == ob.ERR_INVALID_ARG     # fp32: not offered
-    assert L.optiml_mfma_probe(None, 1 << 30, P, 1 << 30, 10, 1, None, None) == ob.ERR_INVALID_ARG
-    assert L.optiml_mfma_probe(P + 8, 1 << 30, P, 1 << 30, 10, 1, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, -1, 1, 0, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, 10, 0, 0, None, None) == ob.ERR_INVALID_ARG     # fp32: not offered
+    assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, 10, 1, 7, None, None) == ob.ERR_INVALID_ARG     # 0, 8, 12 or 16
+    assert L.optiml_mfma_probe(None, 1 << 30, P, 1 << 30, 10, 1, 0, None, None) == ob.ERR_INVALID_ARG
+    assert L.optiml_mfma_probe(P + 8, 1 << 30, P, 1 << 30, 10, 1, 0, None, None) == ob.ERR_INVALID_ARG
