@@ -12,8 +12,8 @@ with its own roofline, CPU baseline and parity figure (--only: the headline alon
 the breadth workloads (other storage types and layouts on the same shapes) and the siblings:
 element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats (s_relu, s_sigmoid, s_sum, s_dot,
 s_mse), transpose (s_transpose), cross-entropy and LayerNorm (s_ce, s_ln_sample, s_ln_token),
-attention (s_mhsa), the contraction fused with the cross-entropy (s_lce, s_lce_f32).  Any of
-these names can be the headline.  One JSON line is printed.
+attention (s_mhsa), the contraction fused with the cross-entropy (s_lce, s_lce_f32) and with
+LayerNorm (s_gln, s_gln_f32).  Any of these names can be the headline.  One JSON line is printed.
 
 The "roofline" object prices the dominant kernel of a workload against the published MI355X peak
 (HBM 8 TB/s, dense bf16 / fp16 MFMA 2516.6 TFLOP/s, fp8 5033.2, fp32 MFMA 157.3) using algorithmic
@@ -57,6 +57,8 @@ ROWS = {"s_ce": (8192, 32768), "s_ln_sample": (64, 64 * 256 * 256), "s_ln_token"
 MHSA = {"s_mhsa": (4, 4096, 2048, 16)}
 # contraction fused with the cross-entropy, B row-major: (M rows, N classes, K, dtype)
 LCE = {"s_lce": (8192, 32768, 4096, 1), "s_lce_f32": (4096, 32768, 2048, 0)}
+# contraction fused with LayerNorm over each row of the product, B row-major: (M, N, K, dtype)
+GLN = {"s_gln": (8192, 8192, 4096, 1), "s_gln_f32": (4096, 4096, 4096, 0)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB summed over the kernels of one step, scaled by what the same counters read for the
@@ -462,10 +464,46 @@ def main():
             return (self.baseline(oracle, secs, m / M, f"first {m} of {M} rows"), "parity_abs_err",
                     abs(float(self.out[1].item()) - ref))
 
+    class Gln(Case):
+        """Contraction + LayerNorm over the rows of the product: A N(0, 1/K), B N(0,1), bias N(1.5, 3^2)."""
+        bound = "mfma"
+
+        def __init__(self, name):
+            self.name = name
+            M, N, K, dt = self.shape = GLN[name]
+            self.dtype = dt
+            self.kernel = f"ring_{DTYPE_NAME[dt]}_rr_ln"
+            self.A = synth.to_bits(synth.normal(13, "A", M, K, 0.0, K ** -0.5), dt)
+            self.B = synth.to_bits(synth.normal(13, "B", K, N), dt)
+            self.bias = synth.normal(13, "bias", 1, N, 1.5, 3.0)[0]
+            self.Ad, self.Bd = (torch.from_numpy(h.view(np.int16) if dt else h).cuda() for h in (self.A, self.B))
+            self.bd = torch.from_numpy(self.bias).cuda()
+            self.Y = torch.empty((M, N), dtype=torch.int16 if dt else torch.float32, device="cuda")
+            assert ob.optiml_gemm_layernorm_path(M, N, K, self.Ad, K, self.Bd, N, self.bd, self.Y, N, 0, dt) == 0
+            self.flops = 2.0 * M * N * K
+            self.nbytes = float((M * K + K * N + M * N) * (2 if dt else 4) + 4 * N)
+            self.config = {"M": M, "N": N, "K": K}
+
+        def step(self, i):
+            M, N, K, dt = self.shape
+            ob.optiml_gemm_layernorm(M, N, K, self.Ad, K, self.Bd, N, self.bd, self.Y, N, 1e-5, 0, dt)
+
+        def check(self):
+            import oracle
+            M, N, K, dt = self.shape
+            m = 256                                                 # bounded sample: the first 256 rows, whole rows
+            t0 = time.perf_counter()
+            ref = oracle.gemm_layernorm(self.A[:m], self.B, self.bias, m, N, K, dtype=dt, eps=1e-5)
+            secs = time.perf_counter() - t0
+            got = self.Y[:m].cpu().numpy()
+            got = (synth.from_bits(got.view(np.uint16), dt) if dt else got).astype(np.float64)
+            return (self.baseline(oracle, secs, m / M, f"first {m} of {M} rows"), "parity_abs_err",
+                    float(np.max(np.abs(got - ref))))
+
     def make_case(name, variant=-1):
         if name in BOUND:
             return Gemm(name, variant)
-        for table, cls in ((STREAMS, Stream), (ROWS, Rows), (MHSA, Mhsa), (LCE, Lce)):
+        for table, cls in ((STREAMS, Stream), (ROWS, Rows), (MHSA, Mhsa), (LCE, Lce), (GLN, Gln)):
             if name in table:
                 return cls(name)
         raise SystemExit(f"bench.py: unknown workload {name}")
@@ -532,7 +570,7 @@ def main():
     if not args.only:
         others += [n for n in synth.WORKLOADS if n != args.workload]
     if args.all:
-        others += [n for n in list(synth.BREADTH_WORKLOADS) + list(STREAMS) + list(ROWS) + list(MHSA) + list(LCE)
+        others += [n for n in list(synth.BREADTH_WORKLOADS) + list(STREAMS) + list(ROWS) + list(MHSA) + list(LCE) + list(GLN)
                    if n != args.workload and n not in others]
     if others:
         out["workloads"] = {args.workload: head}

@@ -320,6 +320,31 @@ int optiml_gemm_cross_entropy_rows(int64_t M, int64_t N, int64_t K, const void *
                                    int dtype, void *stream);
 
 /*
+ * The contraction followed by LayerNorm over each row of the product (the paper's Table 4, task 2
+ * into task 4), fused:
+ *     Y[i][j] = (z[i][j] - mean_i) / sqrt(var_i + eps),   z = A.B + bias,
+ * mean_i and var_i the mean and the biased variance (divide by N) of the N entries of row i; no
+ * scale or shift, eps is the caller's (as in optiml_layernorm).  A, B, bias, layouts, leading
+ * dimensions and dtype exactly as in optiml_gemm_epilogue_ex (no activation, no batch, not
+ * OPTIML_F8E4M3); Y is M x N row-major with pitch ldy >= N in the storage type of dtype; all DEVICE
+ * pointers.  The product is accumulated in fp32 and is NOT rounded to the storage type before it
+ * is normalised: the contraction's epilogue keeps z in fp32 (in Y itself for OPTIML_F32, in the
+ * per-device workspace - 4 bytes per entry - for 16-bit storage) and takes, in registers, each
+ * row's mean and sum of squared deviations per wave-wide slice of columns; a second kernel merges
+ * them per row (fp64, fixed order), subtracts, scales and rounds once.  Repeating a call gives the
+ * same bits.  A row-major with a shape the ring kernels take (as for optiml_gemm_cross_entropy;
+ * fp32 also needs Y 16-byte aligned and ldy % 4 == 0) runs on the matrix pipe, everything else a
+ * one-workgroup-per-row fp32 kernel; optiml_gemm_layernorm_path says which (0 matrix pipe,
+ * 1 fallback; host only).  K == 0: LayerNorm of the bias in every row.  M == 0 or N == 0 writes
+ * nothing.  OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, ldy < N, unknown layout
+ * or dtype, eps negative or NaN, NULL Y, NULL A or B with K > 0, an ld shorter than the row it spans.
+ */
+int optiml_gemm_layernorm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                          const float *bias, void *Y, int64_t ldy, float eps, int layout, int dtype, void *stream);
+int optiml_gemm_layernorm_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                               const float *bias, void *Y, int64_t ldy, int layout, int dtype);
+
+/*
  * Multi-head self-attention (the paper's Table 4, task 6): for Q, K, V of shape [batch][N][d_model]
  * (row-major, contiguous, DEVICE pointers; float for OPTIML_F32, 16-bit for OPTIML_BF16 / OPTIML_F16) and
  * `heads` heads of width d_k = d_model / heads,

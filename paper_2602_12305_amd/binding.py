@@ -43,6 +43,8 @@ SIGNATURES = {
     "optiml_transpose": (_int, [_i64, _i64, _vp, _i64, _vp, _i64, _int, _vp]),
     "optiml_gemm_cross_entropy": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _int, _int, _vp]),
     "optiml_gemm_cross_entropy_rows": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _int, _int, _vp]),
+    "optiml_gemm_layernorm": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, C.c_float, _int, _int, _vp]),
+    "optiml_gemm_layernorm_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int]),
     "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
     "optiml_set_workspace": (_int, [_vp, _i64]),
     "optiml_workspace_bytes": (_i64, []),
@@ -211,6 +213,15 @@ def optiml_gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, layou
 def optiml_gemm_cross_entropy_rows(M, N, K, A, lda, B, ldb, bias, labels, row_loss, loss, layout, dtype, stream=None):
     return _check(lib().optiml_gemm_cross_entropy_rows(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(labels),
                                                        _addr(row_loss), _addr(loss), layout, dtype, _stream(stream)))
+
+
+def optiml_gemm_layernorm(M, N, K, A, lda, B, ldb, bias, Y, ldy, eps, layout, dtype, stream=None):
+    return _check(lib().optiml_gemm_layernorm(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(Y), ldy, eps,
+                                              layout, dtype, _stream(stream)))
+
+
+def optiml_gemm_layernorm_path(M, N, K, A, lda, B, ldb, bias, Y, ldy, layout, dtype):
+    return lib().optiml_gemm_layernorm_path(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(bias), _addr(Y), ldy, layout, dtype)
 
 
 def optiml_gemm_cross_entropy_path(M, N, K, A, lda, B, ldb, bias, layout, dtype):

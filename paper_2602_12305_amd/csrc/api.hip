@@ -687,6 +687,40 @@ int optiml_gemm_cross_entropy_rows(int64_t M, int64_t N, int64_t K, const void *
     return gemm_cross_entropy(M, N, K, A, lda, B, ldb, bias, labels, loss, row_loss, layout, dtype, stream);
 }
 
+namespace {
+// shared argument checks of the contraction + LayerNorm entry points; fills p
+int gemm_layernorm_problem(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           const float *bias, void *Y, int64_t ldy, int layout, int dtype, Problem &p)
+{
+    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || lda < 0 || ldb < 0 || ldy < N) return OPTIML_ERR_INVALID_ARG;
+    p = Problem{};
+    p.batch = 1; p.M = M; p.N = N; p.K = K;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.bias = bias; p.C = Y; p.ldc = ldy;
+    p.layout = layout; p.dtype = dtype; p.act = ACT_NONE;
+    return validate(p);
+}
+}  // namespace
+
+int optiml_gemm_layernorm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                          const float *bias, void *Y, int64_t ldy, float eps, int layout, int dtype, void *stream)
+{
+    if (!(eps >= 0.0f)) return OPTIML_ERR_INVALID_ARG;
+    Problem p;
+    const int st = gemm_layernorm_problem(M, N, K, A, lda, B, ldb, bias, Y, ldy, layout, dtype, p);
+    if (st != OPTIML_OK || M == 0 || N == 0) return st;
+    return status_of(optiml::launch_linear_ln(p, (double)eps, static_cast<hipStream_t>(stream)));
+}
+
+int optiml_gemm_layernorm_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                               const float *bias, void *Y, int64_t ldy, int layout, int dtype)
+{
+    Problem p;
+    const int st = gemm_layernorm_problem(M, N, K, A, lda, B, ldb, bias, Y, ldy, layout, dtype, p);
+    if (st != OPTIML_OK) return st;
+    return optiml::linear_ln_path(p);
+}
+
 int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                                    const float *bias, int layout, int dtype)
 {

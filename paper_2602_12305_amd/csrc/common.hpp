@@ -90,6 +90,12 @@ int linear_ce_path(const Problem &p);
 // loss: the mean over rows (may be null); row_loss: every row's loss (may be null)
 hipError_t launch_linear_ce(const Problem &p, const int *labels, float *loss, float *row_loss, hipStream_t stream);
 
+// contraction + LayerNorm over the rows of the product (kernel_linear_ln.hip): which path would serve (0 ring
+// kernel with the statistics epilogue, 1 row-per-workgroup fallback), launch; p.C, p.ldc are Y; act and batch
+// are ignored
+int linear_ln_path(const Problem &p);
+hipError_t launch_linear_ln(const Problem &p, double eps, hipStream_t stream);
+
 // transpose (kernel_transpose.hip), arguments already validated
 hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src, void *dst, int64_t ld_dst, int esize,
                             hipStream_t s);

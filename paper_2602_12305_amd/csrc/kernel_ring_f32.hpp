@@ -342,6 +342,55 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_f32_kernel(Params p)
         }
         return;
     }
+    if constexpr (C::EPI == 2) {
+        // Z = A.B + bias stays where C is (fp32 already); each wave leaves the mean of its 32 columns
+        // of every row and the sum of squared deviations from it (see ring::Cfg::EPI)
+        float *Z = reinterpret_cast<float *>(p.C);
+        ring::floatx2 *pairs = reinterpret_cast<ring::floatx2 *>(p.picked);
+        const int64_t slice = tile_n * C::WN + wn;
+        const int64_t left = p.N - nw;
+        const float count = (float)(left >= C::WTN ? C::WTN : left > 0 ? left : 0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = mw + 32 * i + frag_row;
+            const bool live = m < p.M;
+            float sum = 0.0f;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float v = acc[i][4 * gq + e] + bj[gq][e];
+                    acc[i][4 * gq + e] = v;
+                    sum += (8 * gq + 4 * half + e < left) ? v : 0.0f;
+                }
+            sum += __shfl_xor(sum, 32, 64);
+            const float mean = count > 0.0f ? sum / count : 0.0f;
+            float dev = 0.0f;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float d = (8 * gq + 4 * half + e < left) ? acc[i][4 * gq + e] - mean : 0.0f;
+                    dev += d * d;
+                }
+            dev += __shfl_xor(dev, 32, 64);
+            if (live && half == 0) pairs[slice * p.M + m] = ring::floatx2{mean, dev};
+            if (!live) continue;
+            float *zr = Z + m * p.ldc + nw;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int c0 = 8 * gq + 4 * half;
+                if (c0 + 4 <= left) {
+                    *reinterpret_cast<floatx4 *>(zr + c0) = floatx4{acc[i][4 * gq], acc[i][4 * gq + 1], acc[i][4 * gq + 2], acc[i][4 * gq + 3]};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c0 + e < left) zr[c0 + e] = acc[i][4 * gq + e];
+                }
+            }
+        }
+        return;
+    }
     const int wkey = (frag_row >> 1) & 7;
     dispatch_act(p.act, [&](auto act_tag) {
     constexpr int ACT = decltype(act_tag)::value;

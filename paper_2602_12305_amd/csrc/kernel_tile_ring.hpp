@@ -52,6 +52,8 @@ struct Params {
     int act;
     // EPI == 1 only: class labels of the M rows and where the label's logit of each row goes;
     // C then points at the (max, sum) pairs [tiles_n * WN][M]
+    // EPI == 2: C points at fp32 Z (pitch ldc floats) and `picked` at the (mean, sum of squared
+    // deviations) pairs [tiles_n * WN][M]
     const int *labels;
     float *picked;
     int bias_row;        // EPI == 0: bias[m] instead of bias[n]
@@ -66,7 +68,10 @@ struct Cfg {
     static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
     // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 64 columns of A.B + bias
     // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the
-    // cross-entropy over the N columns without the logits ever reaching memory.
+    // cross-entropy over the N columns without the logits ever reaching memory.  2: Z = A.B + bias
+    // is written unrounded, as fp32, and each wave leaves the mean of its 64 columns of every row and
+    // the sum of squared deviations from that mean: the row statistics of a LayerNorm over the N
+    // columns come out of the registers that hold the product.
     static constexpr int EPI = EPI_;
     // DT_F8: A and B in 8-bit E4M3 (column-major B only), C in bf16.  The tile geometry is in
     // bytes, so a k-tile is 64 elements instead of 32 and each 16-byte fragment feeds two matrix
@@ -490,6 +495,75 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             if (live && half == 0)
                 *reinterpret_cast<floatx2 *>(part + 2 * (slice * p.M + m)) = floatx2{mx, sum};
             if (live && hit) p.picked[m] = pick;
+        }
+        return;
+    }
+    if constexpr (C::EPI == 2) {
+        float *Z = reinterpret_cast<float *>(p.C);
+        ring::floatx2 *pairs = reinterpret_cast<ring::floatx2 *>(p.picked);
+        const int64_t slice = tile_n * C::WN + wn;
+        const int64_t left = p.N - nw;                                   // columns of this slice inside the matrix
+        const float count = (float)(left >= C::WTN ? C::WTN : left > 0 ? left : 0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = mw + 32 * i + frag_row;
+            const bool live = m < p.M;
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float v = acc[j][i][4 * gq + e] + bj[j][gq][e];
+                        acc[j][i][4 * gq + e] = v;
+                        sum += (32 * j + 8 * gq + 4 * half + e < left) ? v : 0.0f;
+                    }
+            sum += __shfl_xor(sum, 32, 64);
+            const float mean = count > 0.0f ? sum / count : 0.0f;
+            float dev = 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float d = (32 * j + 8 * gq + 4 * half + e < left) ? acc[j][i][4 * gq + e] - mean : 0.0f;
+                        dev += d * d;
+                    }
+            dev += __shfl_xor(dev, 32, 64);
+            if (live && half == 0) pairs[slice * p.M + m] = ring::floatx2{mean, dev};
+            // the 32 x WTN fp32 sub-tile goes through the wave's slab (16-byte chunks XOR-swizzled by the
+            // row) so that every store instruction writes whole rows of WTN * 4 contiguous bytes; plain
+            // stores: the finishing kernel reads z back next, partly from the caches
+            constexpr int ZCH = C::WTN / 4;                              // 16-byte chunks per slab row
+            static_assert(4 * 32 * C::WTN * 4 <= C::STAGE_BYTES && C::NW <= 8, "four slabs per stage, two stages");
+            lds_char *zslab = (wave < 4 ? (lds_char *)st0 : (lds_char *)st1) + (wave & 3) * (32 * C::WTN * 4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+                    *reinterpret_cast<__attribute__((address_space(3))) floatx4 *>(
+                        zslab + frag_row * (C::WTN * 4) + (((8 * j + 2 * gq + half) ^ (frag_row & (ZCH - 1))) << 4)) =
+                        floatx4{acc[j][i][4 * gq], acc[j][i][4 * gq + 1], acc[j][i][4 * gq + 2], acc[j][i][4 * gq + 3]};
+#pragma unroll
+            for (int q = 0; q < 32 * ZCH / 64; ++q) {
+                const int id = q * 64 + lane, row = id / ZCH, chunk = id % ZCH;
+                const floatx4 v = *reinterpret_cast<const __attribute__((address_space(3))) floatx4 *>(
+                    zslab + row * (C::WTN * 4) + ((chunk ^ (row & (ZCH - 1))) << 4));
+                const int64_t mr = mw + 32 * i + row;
+                const int c0 = 4 * chunk;
+                if (mr < p.M && c0 < left) {
+                    float *dst = Z + mr * p.ldc + nw + c0;
+                    if (c0 + 4 <= left) {
+                        *reinterpret_cast<floatx4 *>(dst) = v;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c0 + e < left) dst[e] = v[e];
+                    }
+                }
+            }
         }
         return;
     }

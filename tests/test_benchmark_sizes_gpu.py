@@ -100,3 +100,26 @@ def test_contraction_fused_with_cross_entropy(name):
     err = np.abs(rows.cpu().numpy().astype(np.float64) - ref_rows)
     assert float(err.max()) <= 1.2e-4, (int(err.argmax()), float(err.max()))
     print(f"{name}: worst row {float(err.max()):.3e}, mean {abs(out.item() - ref):.3e}")
+
+
+@pytest.mark.parametrize("name", list(bench.GLN))
+def test_contraction_fused_with_layernorm(name):
+    """Whole rows, sampled over the row tiles (first, last and every 37th row): the oracle normalises a row only when it
+    has all of it.  Unit-variance products on a bias of spread 3: |bias| + sum |a b| stays below 80, s is about 3.2, so
+    the bound of tests/test_linear_ln_gpu.py stays below 2e-4 (1 + |y|); one rounding to the storage type on top."""
+    M, N, K, dt = bench.GLN[name]
+    A = synth.to_bits(synth.normal(13, "A", M, K, 0.0, K ** -0.5), dt)
+    B = synth.to_bits(synth.normal(13, "B", K, N), dt)
+    bias = synth.normal(13, "bias", 1, N, 1.5, 3.0)[0]
+    conv = lambda h: torch.from_numpy(h.view(np.int16) if dt else h).cuda()
+    Y = torch.empty((M, N), dtype=torch.int16 if dt else torch.float32, device="cuda")
+    ob.optiml_gemm_layernorm(M, N, K, conv(A), K, conv(B), N, torch.from_numpy(bias).cuda(), Y, N, 1e-5, 0, dt)
+    torch.cuda.synchronize()
+    rows = sorted(set(range(0, M, 37)) | {M - 1, 255, 256})
+    ref = oracle.gemm_layernorm(np.ascontiguousarray(A[rows]), B, bias, len(rows), N, K, dtype=dt, eps=1e-5)
+    got = Y[rows].cpu().numpy()
+    got = (synth.from_bits(got.view(np.uint16), dt) if dt else got).astype(np.float64)
+    half = 2.0 ** -8 if dt else 2.0 ** -24
+    err = np.abs(got - ref) - half * np.abs(ref)
+    assert np.all(np.isfinite(got)) and float(np.max(err - 2e-4 * (1 + np.abs(ref)))) <= 0.0, float(err.max())
+    print(f"{name}: worst entry beyond its rounding step {float(err.max()):.3e} over {len(rows)} rows")

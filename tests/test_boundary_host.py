@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 25
+    assert len(names) == 27
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -274,3 +274,29 @@ def test_mfma_probe_validates_on_the_host():
     assert L.optiml_mfma_probe(P, 1 << 30, P, 1 << 30, 10, 1, 7, None, None) == ob.ERR_INVALID_ARG     # 0, 8, 12 or 16
     assert L.optiml_mfma_probe(None, 1 << 30, P, 1 << 30, 10, 1, 0, None, None) == ob.ERR_INVALID_ARG
     assert L.optiml_mfma_probe(P + 8, 1 << 30, P, 1 << 30, 10, 1, 0, None, None) == ob.ERR_INVALID_ARG
+
+
+def test_fused_layernorm_entry_point_validates_and_picks_its_kernel_on_the_host():
+    L = ob.lib()
+    ok = dict(M=512, N=768, K=256, A=P, lda=256, B=P, ldb=768, bias=P, Y=P, ldy=768, eps=1e-5, layout=0, dtype=1)
+
+    def call_ln(**kw):
+        a = dict(ok, **kw)
+        return L.optiml_gemm_layernorm(a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"], a["bias"], a["Y"], a["ldy"],
+                                       a["eps"], a["layout"], a["dtype"], None)
+
+    def path(**kw):
+        a = dict(ok, **kw)
+        return L.optiml_gemm_layernorm_path(a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"], a["bias"], a["Y"],
+                                            a["ldy"], a["layout"], a["dtype"])
+
+    for bad in (dict(M=-1), dict(N=-1), dict(K=-1), dict(ldy=767), dict(lda=255), dict(ldb=767), dict(Y=None), dict(A=None),
+                dict(B=None), dict(eps=-1.0), dict(eps=float("nan")), dict(layout=4), dict(dtype=3), dict(dtype=9)):
+        assert call_ln(**bad) == ob.ERR_INVALID_ARG, bad
+    assert call_ln(M=0) == ob.OK and call_ln(N=0, ldb=0, ldy=0) == ob.OK           # nothing to write
+    assert path() == 0 and path(dtype=0) == 0 and path(dtype=2, layout=1, ldb=256) == 0
+    assert path(layout=2, lda=512) == 1                         # column-major A
+    assert path(K=0) == 1 and path(K=40, lda=40) == 1           # nothing to contract / too short for the ring
+    assert path(A=P + 2) == 1                                   # misaligned operand
+    assert path(dtype=0, Y=P + 4) == 1 and path(dtype=0, ldy=770) == 1   # fp32: z is written into Y with 16-byte stores
+    assert path(dtype=1, Y=P + 2, ldy=771) == 0                 # 16-bit: z goes to the workspace, Y may sit anywhere
