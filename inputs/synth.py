@@ -269,6 +269,21 @@ BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc
                      "c2_f32_skinny16_rc_silu")     # further dtypes on the same shapes
 
 
+# shape of every workload without its data: (batch, M, N, K, layout, dtype, act)
+SPECS = {
+    "c1_f32_256_relu": (1, 256, 256, 256, LAYOUT_RR, DTYPE_F32, ACT_RELU),
+    "c2_f32_skinny16_silu": (1, 16, 16384, 16384, LAYOUT_RR, DTYPE_F32, ACT_SILU),
+    "c3_f32_4096_rc_gelu": (1, 4096, 4096, 4096, LAYOUT_RC, DTYPE_F32, ACT_GELU_TANH),
+    "c4_bf16_8192_silu": (1, 8192, 8192, 8192, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
+    "c5_bf16_batched32_relu": (32, 2048, 2048, 512, LAYOUT_RR, DTYPE_BF16, ACT_RELU),
+    "c4_f16_8192_silu": (1, 8192, 8192, 8192, LAYOUT_RR, DTYPE_F16, ACT_SILU),
+    "c2_bf16_skinny16_silu": (1, 16, 16384, 16384, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
+    "c4_f8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E4M3, ACT_SILU),
+    "c4_bf16_8192_cr_silu": (1, 8192, 8192, 8192, LAYOUT_CR, DTYPE_BF16, ACT_SILU),
+    "c2_f32_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F32, ACT_SILU),
+}
+
+
 def make_workload(name: str, scale: int = 1) -> Workload:
     """Build one of the five workloads.  `scale` > 1 divides every dimension (for
     quick functional runs at the same distributions); the distributions' parameters that

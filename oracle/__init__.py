@@ -16,7 +16,7 @@ import numpy as np
 
 from .build import build as _build
 
-F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
+F32, BF16, F16, F8E4M3, F4E2M1 = 0, 1, 2, 3, 4
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 EW_RELU, EW_SIGMOID = 0, 1
@@ -47,6 +47,12 @@ def lib():
         L.oracle_f16_to_double.argtypes = [C.c_uint16]
         L.oracle_f8e4m3_to_double.restype = C.c_double
         L.oracle_f8e4m3_to_double.argtypes = [C.c_uint8]
+        L.oracle_f4e2m1_to_double.restype = C.c_double
+        L.oracle_f4e2m1_to_double.argtypes = [C.c_uint8]
+        L.oracle_e8m0_to_double.restype = C.c_double
+        L.oracle_e8m0_to_double.argtypes = [C.c_uint8]
+        L.oracle_gemm_epilogue_mx.restype = C.c_int
+        L.oracle_gemm_epilogue_mx.argtypes = [i64, i64, i64, vp, i64, vp, vp, i64, vp, vp, vp, C.c_int, C.c_int, C.c_int]
         L.oracle_num_threads.restype = C.c_int
         L.oracle_elementwise.restype = None
         L.oracle_elementwise.argtypes = [i64, vp, C.c_int, vp]
@@ -75,18 +81,19 @@ def _ptr(a):
 
 
 def _check_operand(x, dtype, what):
-    want = {F32: np.float32, F8E4M3: np.uint8}.get(dtype, np.uint16)
+    want = {F32: np.float32, F8E4M3: np.uint8, F4E2M1: np.uint8}.get(dtype, np.uint16)
     if x.dtype != want or not x.flags.c_contiguous:
         raise TypeError(f"{what}: need C-contiguous {want.__name__} storage, got {x.dtype}")
 
 
-def _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB):
+def _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB, dtype=F32):
     """Leading dimensions / strides default to those of dense [batch, rows, ld] arrays."""
     a_col, b_col = (layout >> 1) & 1, layout & 1
+    per_byte = 2 if dtype == F4E2M1 else 1          # E2M1: two elements to a byte, leading dimensions in elements
     if lda is None:
-        lda = A.shape[-1]
+        lda = A.shape[-1] * per_byte
     if ldb is None:
-        ldb = B.shape[-1]
+        ldb = B.shape[-1] * per_byte
     if strideA is None:
         strideA = (K if a_col else M) * lda if batch > 1 else 0
     if strideB is None:
@@ -99,7 +106,7 @@ def gemm_epilogue(A, B, bias, M, N, K, *, dtype=F32, act=ACT_NONE, layout=LAYOUT
                   want_absden=False):
     """Y[batch, M, N] (fp64) = act(A.B + bias); optionally also |bias| + sum|a b|."""
     _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
-    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB)
+    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB, dtype)
     if bias is not None:
         bias = np.ascontiguousarray(bias, dtype=np.float32)
         if strideBias is None:
@@ -120,7 +127,7 @@ def gemm_epilogue_sampled(sb, si, sj, A, B, bias, M, N, K, *, dtype=F32, act=ACT
                           strideB=None, strideBias=None, want_absden=False):
     """The same definition evaluated only at entries (sb[t], si[t], sj[t])."""
     _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
-    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB)
+    lda, ldb, strideA, strideB = _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB, dtype)
     if bias is not None:
         bias = np.ascontiguousarray(bias, dtype=np.float32)
         if strideBias is None:
@@ -161,6 +168,37 @@ def f8e4m3_to_double(bits):
     """fp64 value of each OCP E4M3 bit pattern (uint8)."""
     f = lib().oracle_f8e4m3_to_double
     return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(bits, dtype=np.uint8))
+
+
+def f4e2m1_to_double(nibbles):
+    """fp64 value of each OCP E2M1 code (low four bits of each uint8)."""
+    f = lib().oracle_f4e2m1_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(nibbles, dtype=np.uint8))
+
+
+def e8m0_to_double(codes):
+    """fp64 value 2^(e - 127) of each OCP E8M0 scale code (255: NaN)."""
+    f = lib().oracle_e8m0_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(codes, dtype=np.uint8))
+
+
+def gemm_epilogue_mx(A, scaleA, B, scaleB, bias, M, N, K, *, dtype=F4E2M1, act=ACT_NONE, layout=LAYOUT_RC, lda=None, ldb=None):
+    """Y[M, N] (fp64) = act((sA * A).(sB * B) + bias) for block-scaled operands: E4M3 or E2M1 elements (uint8 storage, E2M1
+    two to a byte) with one E8M0 scale per 32 consecutive k of every row of A (scaleA [M, ceil(K/32)]) and every column of
+    B (scaleB [N, ceil(K/32)])."""
+    _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
+    lda, ldb, _, _ = _geometry(A, B, layout, 1, M, N, K, lda, ldb, 0, 0, dtype)
+    scaleA = np.ascontiguousarray(scaleA, dtype=np.uint8); scaleB = np.ascontiguousarray(scaleB, dtype=np.uint8)
+    blocks = (K + 31) // 32
+    if scaleA.shape != (M, blocks) or scaleB.shape != (N, blocks):
+        raise ValueError("scales [M, ceil(K/32)] and [N, ceil(K/32)] expected")
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    Y = np.empty((M, N), dtype=np.float64)
+    if lib().oracle_gemm_epilogue_mx(M, N, K, _ptr(A), lda, _ptr(scaleA), _ptr(B), ldb, _ptr(scaleB), _ptr(bias), _ptr(Y),
+                                     layout, dtype, act) != 0:
+        raise ValueError("oracle_gemm_epilogue_mx rejected its arguments")
+    return Y
 
 
 def f16_to_double(bits):

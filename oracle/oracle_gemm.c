@@ -38,7 +38,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3, ORACLE_F4E2M1 = 4 };
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
 /* bit 0 of layout: B is column-major; bit 1: A is column-major */
 
@@ -73,8 +73,27 @@ double oracle_f8e4m3_to_double(uint8_t b)
     return sign ? -v : v;
 }
 
+/* OCP 4-bit floating point E2M1 (1 sign, 2 exponent bits with bias 1, 1 fraction bit; no infinities, no NaN)
+ * to double, exactly: exponent field 0 is a subnormal f * 2^-1, else (2 + f) * 2^(e - 2).  The sixteen codes
+ * are 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives.  Only the low four bits of `nibble` are read. */
+double oracle_f4e2m1_to_double(uint8_t nibble)
+{
+    const int sign = (nibble >> 3) & 1, e = (nibble >> 1) & 3, f = nibble & 1;
+    const double v = e == 0 ? ldexp((double)f, -1) : ldexp((double)(2 + f), e - 2);
+    return sign ? -v : v;
+}
+
+/* OCP E8M0 block scale (8 exponent bits with bias 127, no sign, no fraction): 2^(e - 127); 255 is NaN. */
+double oracle_e8m0_to_double(uint8_t e)
+{
+    return e == 255 ? NAN : ldexp(1.0, (int)e - 127);
+}
+
 static double widen(const void *base, int64_t idx, int dtype)
 {
+    /* E2M1: two elements to a byte, element idx in the low (idx even) or high (idx odd) four bits */
+    if (dtype == ORACLE_F4E2M1)
+        return oracle_f4e2m1_to_double((uint8_t)(((const uint8_t *)base)[idx >> 1] >> ((idx & 1) * 4)));
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
     if (dtype == ORACLE_F16)
@@ -185,7 +204,7 @@ int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
                          int layout, int dtype, int act)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F8E4M3) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F4E2M1) || act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
     const int64_t rows = batch * M;
@@ -250,7 +269,7 @@ int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t
                                  int layout, int dtype, int act)
 {
     if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F8E4M3) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F4E2M1) || act < 0 || act > 3)
         return -1;
     for (int64_t t = 0; t < count; ++t)
         if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)
@@ -284,4 +303,37 @@ int oracle_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/*
+ * Block-scaled operands (the OCP microscaling formats): every 32 consecutive k of a row of A and of a column
+ * of B share one E8M0 scale,
+ *     z_ij = bias_j + sum_k (sA[i][k / 32] a_ik) (sB[j][k / 32] b_kj),   y_ij = act(z_ij),
+ * with a, b in E4M3 or E2M1 storage (dtype), decoded exactly; a scaled element is a power of two times a
+ * short significand, exact in fp64, and so is every product; one fp64 accumulator per output, k ascending,
+ * bias after the sum.  scaleA is [M][ceil(K / 32)], scaleB [N][ceil(K / 32)] (row-major bytes); A and B in
+ * the layouts of oracle_gemm_epilogue, leading dimensions in elements.  Y fp64 [M][N].
+ * Returns 0, or -1 on a bad enum / negative size.
+ */
+int oracle_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const uint8_t *scaleA,
+                            const void *B, int64_t ldb, const uint8_t *scaleB, const float *bias, double *Y,
+                            int layout, int dtype, int act)
+{
+    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 || (dtype != ORACLE_F8E4M3 && dtype != ORACLE_F4E2M1) ||
+        act < 0 || act > 3)
+        return -1;
+    const int a_col = (layout >> 1) & 1, b_col = layout & 1;
+    const int64_t blocks = (K + 31) / 32;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = oracle_e8m0_to_double(scaleA[i * blocks + k / 32]) * widen(A, a_col ? k * lda + i : i * lda + k, dtype);
+                const double b = oracle_e8m0_to_double(scaleB[j * blocks + k / 32]) * widen(B, b_col ? j * ldb + k : k * ldb + j, dtype);
+                s += a * b;
+            }
+            Y[i * N + j] = oracle_act(s + (bias ? (double)bias[j] : 0.0), act);
+        }
+    return 0;
 }

@@ -109,7 +109,10 @@ bool is_empty(const Problem &p) { return p.batch == 0 || p.M == 0 || p.N == 0; }
 // the full-chip rate would give 63).  Numbers from 4096^3 (full chip) and from 64 x 4096 x 4096,
 // 128 x 8192 x 8192, 1024^3, 2048^3 (part of the chip), in us and TFLOP/s:
 //   ring 256x256 (16-bit) 8 + f / 4.9      ring 256x256 (8-bit, 64-deep) 8 + f / 9.0, else f / 6.6
-//   persistent ring       4.3 + f / 4.56   (more tiles than CUs only)
+//   ring 128x256 (four waves, two workgroups to a CU) 6.9 + f / 2.53 per workgroup, both running:
+//     32 x 2048 x 2048 x K: 0.106 / 0.161 ms at K = 256 / 512 (0.123 / 0.170 for 256x256), 8 x 4096 x 4096 x 1024
+//     0.267 (0.2585), so 7 % are taken off its rate from K = 1024
+//   persistent ring       6.5 + f / 4.59   (more tiles than CUs only; 0.096 / 0.169 ms at K = 192 / 512)
 //   direct 256x256 8.5 + f / 4.4           direct 256x128 7.5 + f / 3.86
 //   direct 128x128 2.7 + f / 2.56, 1.45 workgroups' worth per CU
 //   staged 16-bit 256x256 5 + f / 2.0, 256x128 4 + f / 1.8, 128x128 3 + f / 1.17 (1.8 per CU)
@@ -124,57 +127,54 @@ struct Cost {
     bool boost = false, many_tiles_only = false;
 };
 
-bool starts_with(const char *s, const char *prefix)
-{
-    while (*prefix)
-        if (*s++ != *prefix++) return false;
-    return true;
-}
-
-bool contains(const char *s, const char *what)
-{
-    for (; *s; ++s)
-        if (starts_with(s, what)) return true;
-    return false;
-}
-
 Cost cost_of(const Variant *v)
 {
-    const char *n = v->name;
     Cost c;
-    const bool f32 = contains(n, "_f32_");
-    if (starts_with(n, "ringp_")) { c.fixed_us = 4.3f; c.tf_wg = 4.56f; c.boost = true; c.many_tiles_only = true; }
-    else if (starts_with(n, "ring_f32_")) { c.fixed_us = 3.0f; c.tf_wg = v->bm == 128 ? 0.548f : 0.53f; }
-    else if (starts_with(n, "ring_f8_")) { c.fixed_us = 8.0f; c.tf_wg = contains(n, "_k64") ? 9.0f : 6.6f; c.boost = true; }
-    else if (starts_with(n, "ring_")) { c.fixed_us = 8.0f; c.tf_wg = 4.9f; c.boost = true; }
-    else if (starts_with(n, "direct_")) {
+    switch (v->family) {
+    case FAM_RINGP: c.fixed_us = 6.5f; c.tf_wg = 4.59f; c.boost = true; c.many_tiles_only = true; break;
+    case FAM_RINGF: c.fixed_us = 3.0f; c.tf_wg = v->bm == 128 ? 0.548f : 0.53f; break;
+    case FAM_RING8_K64: c.fixed_us = 8.0f; c.tf_wg = 9.0f; c.boost = true; break;
+    case FAM_RING8:
+        if (v->bm == 128) { c.fixed_us = 6.9f; c.tf_wg = 3.4f; c.share = 2.0f; c.boost = true; }
+        else { c.fixed_us = 8.0f; c.tf_wg = 6.6f; c.boost = true; }
+        break;
+    case FAM_RING16:
+        if (v->bm == 128) { c.fixed_us = 6.9f; c.tf_wg = 2.53f; c.share = 2.0f; c.boost = true; }     // two workgroups to a CU
+        else { c.fixed_us = 8.0f; c.tf_wg = 4.9f; c.boost = true; }
+        break;
+    case FAM_DIRECT:
         c.boost = true;
         if (v->bm == 256 && v->bn == 256) { c.fixed_us = 8.5f; c.tf_wg = 4.4f; }
         else if (v->bm == 256) { c.fixed_us = 7.5f; c.tf_wg = 3.86f; }
         else { c.fixed_us = 2.7f; c.tf_wg = 2.56f; c.share = 1.45f; }
-    } else if (starts_with(n, "tile_") && f32) {
+        break;
+    case FAM_TILEF:
         if (v->bm == 256) { c.fixed_us = 4.0f; c.tf_wg = 0.41f; }
         else if (v->bm == 128) { c.fixed_us = 3.0f; c.tf_wg = 0.33f; c.share = 1.07f; }
         else { c.fixed_us = 3.0f; c.tf_wg = 0.151f; c.share = 2.3f; }
-    } else if (starts_with(n, "tile_")) {
+        break;
+    case FAM_TILE16:
         if (v->bm == 256 && v->bn == 256) { c.fixed_us = 5.0f; c.tf_wg = 2.0f; }
         else if (v->bm == 256) { c.fixed_us = 4.0f; c.tf_wg = 1.8f; }
         else { c.fixed_us = 3.0f; c.tf_wg = 1.17f; c.share = 1.8f; }
+        break;
+    default: break;                    // no model: the variant brings its own estimate or none
     }
     return c;
 }
 
 double tile_estimate_us(const Variant *v, const Cost &c, const Problem &p)
 {
-    constexpr double kCUs = 256.0;
+    const double kCUs = (double)compute_units();
     const double tiles = (double)((p.M + v->bm - 1) / v->bm) * (double)((p.N + v->bn - 1) / v->bn) * (double)p.batch;
     if (c.many_tiles_only && tiles <= kCUs) return 1e30;
     const double fill = tiles < kCUs ? tiles / kCUs : 1.0;
     double rate = c.tf_wg * (c.boost ? 1.5 - 0.5 * fill : 1.0);                // TFLOP/s = flop per us / 1e6
-    if (starts_with(v->name, "tile_") && v->bm >= 128 && p.K % (p.dtype == DT_F32 ? 16 : 32) != 0) rate *= 0.8;
+    if ((v->family == FAM_TILE16 || v->family == FAM_TILEF) && v->bm >= 128 && p.K % (p.dtype == DT_F32 ? 16 : 32) != 0) rate *= 0.8;
     // the direct kernels fetch 128-byte row segments: with a row pitch that is not a multiple of 128 bytes each
     // straddles two cache lines (3000^3 bf16: 101 us where the estimate without this says 64)
-    if (starts_with(v->name, "direct_") && ((p.lda * 2) % 128 != 0 || (p.ldb * 2) % 128 != 0)) rate *= 0.65;
+    if (v->family == FAM_DIRECT && ((p.lda * 2) % 128 != 0 || (p.ldb * 2) % 128 != 0)) rate *= 0.65;
+    if ((v->family == FAM_RING16 || v->family == FAM_RING8) && v->bm == 128 && p.K >= 1024) rate *= 0.93;
     const double tile_us = c.fixed_us + 2.0 * v->bm * v->bn * (double)p.K / (rate * 1e6);
     if (c.share == 1.0f) return tile_us * (double)(int64_t)((tiles + kCUs - 1.0) / kCUs);
     const double n = tiles / kCUs;                                             // workgroups per CU
@@ -204,7 +204,8 @@ double stream_estimate_us(const Problem &p)
 int64_t stream_workgroups(const Problem &p, int64_t cols, int64_t k_min)
 {
     const int64_t blocks = (p.N + cols - 1) / cols * p.batch * ((p.M + 15) / 16);
-    int64_t split = (256 + blocks - 1) / blocks;
+    const int64_t cus = compute_units();
+    int64_t split = (cus + blocks - 1) / blocks;
     const int64_t by_k = p.K / k_min > 0 ? p.K / k_min : 1;
     split = split < by_k ? split : by_k;
     return blocks * (split > 64 ? 64 : split);
@@ -218,44 +219,48 @@ int64_t stream_workgroups(const Problem &p, int64_t cols, int64_t k_min)
 // for a short K and few columns, the four-wave entry (768 x 3072 x 768: 23 against 31 us).
 int stream_variant(const Table &t, const Problem &p)
 {
-    const int f32 = t.first_skinny, b16 = f32 + kNumSkinnyVariants, rc = b16 + kNumSkinny16Variants;
-    int want[3] = {-1, -1, -1};
+    // entries are found by the role their table gives them; a variant's own support test keeps to its
+    // storage type and layouts, so the first entry of a role that can run p is the one of p's family
+    auto by_role = [&](int role) {
+        for (int i = t.first_skinny; i < t.first_tile; ++i)
+            if (t.v[i]->role == role && can_run(t.v[i], p)) return i;
+        return -1;
+    };
+    if (p.layout > 1) return -1;
+    int want = ROLE_STREAM_DEFAULT;
+    const int64_t enough = compute_units() * 3 / 4;               // workgroups below which the chip is starved
     if (p.layout == 0 && p.dtype == DT_F32) {
-        const bool starved = stream_workgroups(p, 128, 2048) < 192 && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 2048);
+        const bool starved = stream_workgroups(p, 128, 2048) < enough && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 2048);
         // a few blocks of rows over a long K whose 64-column groups already give every CU a workgroup:
         // eight waves and no split along k (64 x 4096 x 4096: 31 against 39 us; not beyond 8192 x 8192, where
         // 64 x 16384 x 16384 takes 744 against 524 us)
         const bool unsplit = p.M <= 128 && p.K >= 2048 && (double)p.K * (double)p.N <= 67108864.0 &&
-                             (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= 192;
-        want[0] = p.M > 16 ? (unsplit ? f32 + 7 : starved && p.K >= 4096 ? f32 + 14 : f32 + 1) : starved ? f32 + 14 : f32;
-        want[1] = p.M > 16 ? f32 + 1 : f32;
+                             (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= enough;
+        if (p.M > 16) want = unsplit ? ROLE_STREAM_UNSPLIT : starved && p.K >= 4096 ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
+        else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
     } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {
-        const int base = b16 + (p.dtype == DT_F16 ? kNumSkinny16Variants / 2 : 0);
-        const bool starved = stream_workgroups(p, 256, 1024) < 192 && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
+        const bool starved = stream_workgroups(p, 256, 1024) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
         // more than 16 rows: the eight-wave entry (128 columns, k ranges of 2048 or more) unless it is starved too
-        const bool starved8 = stream_workgroups(p, 128, 2048) < 192 && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 128, 2048);
-        if (p.M > 16) want[0] = starved8 || (p.K <= 2048 && p.N <= 8192) ? base + 3 : base + 1;
-        else want[0] = starved ? base + 3 : base;
-        want[1] = base;
+        const bool starved8 = stream_workgroups(p, 128, 2048) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 128, 2048);
+        if (p.M > 16) want = starved8 || (p.K <= 2048 && p.N <= 8192) ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
+        else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
     } else if (p.layout == 1) {
-        const int per = kNumSkinnyRcVariants / 4;
-        const int base = rc + per * (p.dtype == DT_F32 ? 0 : p.dtype == DT_BF16 ? 1 : p.dtype == DT_F16 ? 2 : 3);
         const int64_t k_min = 32 * 256 / p.esize();               // 32 steps of 256 bytes
-        const bool starved = stream_workgroups(p, 64, k_min) < 192 && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min);
-        want[0] = starved ? base + 2 : base;
+        const bool starved = stream_workgroups(p, 64, k_min) < enough && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min);
+        want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
         // 8-bit operands over a short K: the register-only kernel (1024^3: 14.8 against 17.2 us, 1008^3: 15.5
         // against 25.8 us)
-        if (p.dtype == DT_F8 && p.K <= 2048 && p.M > 16) want[0] = base + 1;
-        want[1] = base;
+        if (p.dtype == DT_F8 && p.K <= 2048 && p.M > 16) want = ROLE_STREAM_REGS;
+    } else {
+        return -1;
     }
-    for (int i : want)
-        if (i >= 0 && i < t.first_tile && can_run(t.v[i], p)) return i;
-    // any other entry of the family that takes the problem
-    const int lo = p.layout == 1 ? rc : p.dtype == DT_F32 ? f32 : b16;
-    const int hi = p.layout == 1 ? t.first_tile : p.dtype == DT_F32 ? b16 : rc;
-    if (p.layout <= 1)
-        for (int i = lo; i < hi; ++i)
-            if (can_run(t.v[i], p)) return i;
+    int id = by_role(want);
+    if (id < 0 && want != ROLE_STREAM_DEFAULT) id = by_role(p.M > 16 && want != ROLE_STREAM_ROWS ? ROLE_STREAM_ROWS : ROLE_STREAM_DEFAULT);
+    if (id < 0) id = by_role(ROLE_STREAM_DEFAULT);
+    if (id >= 0) return id;
+    // any other streaming entry that takes the problem
+    for (int i = t.first_skinny; i < t.first_tile; ++i)
+        if (can_run(t.v[i], p)) return i;
     return -1;
 }
 
@@ -267,7 +272,7 @@ int stream_variant(const Table &t, const Problem &p)
 int select(const Problem &p, double *estimate_us = nullptr, bool allow_streaming = true)
 {
     const Table &t = table();
-    constexpr int64_t kComputeUnits = 256;
+    const int64_t kComputeUnits = compute_units();
     double unused;
     double &us_out = estimate_us ? *estimate_us : unused;
     us_out = 1e30;

@@ -27,6 +27,15 @@ struct Problem {
     int csize() const { return dtype == DT_F32 ? 4 : 2; }                        // ... of C
 };
 
+// Kernel family of a variant: what the dispatcher's cost model is keyed on (with the tile shape).
+enum : int { FAM_NONE = 0, FAM_RING16, FAM_RING8, FAM_RING8_K64, FAM_RINGP, FAM_RINGF, FAM_DIRECT, FAM_TILE16, FAM_TILEF };
+// What the dispatcher uses a streaming variant for (at most one variant per role and storage type):
+//   DEFAULT  the entry tuned on 16 rows x 16384 x 16384;  ROWS  more than one block of 16 rows;
+//   UNSPLIT  a few blocks of rows over a long K, eight waves and no split along k;
+//   NARROW   half the columns per workgroup, for problems that would otherwise launch too few workgroups
+//            (and, 16-bit, for a short K); REGS  the register-only kernel (8-bit operands over a short K).
+enum : int { ROLE_NONE = 0, ROLE_STREAM_DEFAULT, ROLE_STREAM_ROWS, ROLE_STREAM_UNSPLIT, ROLE_STREAM_NARROW, ROLE_STREAM_REGS };
+
 struct Variant {
     const char *name;
     bool (*supports)(const Problem &);
@@ -40,6 +49,8 @@ struct Variant {
     // optional: the variant's own estimate of its time on p in microseconds (the dispatcher compares
     // it with its estimates for the other kernels)
     double (*estimate_us)(const Problem &) = nullptr;
+    int family = FAM_NONE;   // cost-model key of the tile kernels
+    int role = ROLE_NONE;    // streaming kernels: what the dispatcher picks this entry for
 };
 
 // The dispatcher's choice for p: index into the variant table (or a negative OPTIML_ERR_*) and,
@@ -111,7 +122,7 @@ const Variant *transpose_variants();       extern const int kNumTransposeVariant
 const Variant *pad_variants();             extern const int kNumPadVariants;      // kernel_pad.hip
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
-constexpr int kRingPerUnit = 4;            // ring-of-stages bf16 kernels per B layout (three one-tile, one persistent)
+constexpr int kRingPerUnit = 5;            // ring-of-stages 16-bit kernels per B layout (three one-tile, one persistent, one 128 x 256)
 constexpr int kRingF32PerUnit = 3;         // ring-of-stages fp32 kernels per B layout
 
 }  // namespace optiml

@@ -4,13 +4,15 @@
 namespace optiml {
 using namespace skinny_rc;
 
-#define SKRC(DT, TAG, WN, WK, CG, T)                                                                      \
+#define SKRC(DT, TAG, WN, WK, CG, T, ROLE)                                                                    \
     {"skinnyrc_" TAG "_wn" #WN "_wk" #WK "_cg" #CG "_t" #T, supports<DT>, launch<DT, WN, WK, CG, T>, 0, 0,  \
-     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>), nullptr, true}
-#define SKRC_DMA(DT, TAG, WK, CG, NS)                                                                     \
+     reinterpret_cast<const void *>(&skinny_rc_kernel<DT, WN, WK, CG, T>), nullptr, true, nullptr, FAM_NONE, ROLE}
+#define SKRC_DMA(DT, TAG, WK, CG, NS, ROLE)                                                                   \
     {"skinnyrc_" TAG "_dma_wk" #WK "_cg" #CG "_ns" #NS, supports_dma<DT>, launch_dma<DT, WK, CG, NS>, 0, 0,  \
-     reinterpret_cast<const void *>(&skinny_rc_dma_kernel<DT, WK, CG, NS>), nullptr, true}
-#define SKRC_SET(DT, TAG) SKRC_DMA(DT, TAG, 4, 4, 2), SKRC(DT, TAG, 1, 4, 4, 4), SKRC_DMA(DT, TAG, 4, 2, 3), SKRC_DMA(DT, TAG, 2, 4, 4)
+     reinterpret_cast<const void *>(&skinny_rc_dma_kernel<DT, WK, CG, NS>), nullptr, true, nullptr, FAM_NONE, ROLE}
+#define SKRC_SET(DT, TAG)                                                                                 \
+    SKRC_DMA(DT, TAG, 4, 4, 2, ROLE_STREAM_DEFAULT), SKRC(DT, TAG, 1, 4, 4, 4, ROLE_STREAM_REGS),         \
+    SKRC_DMA(DT, TAG, 4, 2, 3, ROLE_STREAM_NARROW), SKRC_DMA(DT, TAG, 2, 4, 4, ROLE_NONE)
 
 // per dtype the first entry is the dispatcher's choice: staged through LDS by DMA, four waves, four column groups,
 // two stages (160 KiB of LDS); the second is the register-only kernel (also the fallback when the 32-bit lane

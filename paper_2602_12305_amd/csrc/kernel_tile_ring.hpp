@@ -59,8 +59,19 @@ struct Params {
     int bias_row;        // EPI == 0: bias[m] instead of bias[n]
 };
 
-template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0, bool K64_ = false>
+template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0, bool K64_ = false, int BAND_ = 8,
+          int SWZ_ = 4, int WM_ = 2>
 struct Cfg {
+    // WM = 1: a 128 x 256 block computed by four waves (1 x 4, the same 128 x 64 wave tile) with 24 KiB
+    // stages; with NS = 3 two such workgroups share a CU (144 KiB of LDS, at most 256 registers a lane),
+    // so that one's first loads and epilogue run under the other's k loop: for many short tiles.
+    static constexpr int MIN_WAVES_PER_SIMD = WM_ == 1 ? 2 : 1;
+    // Tile walk: a band is BAND tile rows, walked column by column, so that the workgroups in flight on
+    // an XCD share few panels of A and B.  SWZ: XOR key step of the row-major B tile in LDS, chunk c
+    // of k-row k at (c ^ SWZ (k & 3)) - 4 measured best (165 B/clk against 128 B/clk for 2).  Both are
+    // edit classes of the tree search.
+    static constexpr int BAND = BAND_, SWZ = SWZ_;
+    static_assert(BAND_ >= 1 && (SWZ_ == 2 || SWZ_ == 4 || SWZ_ == 8), "tile walk and swizzle key");
     // 8-bit operands only: one v_mfma_f32_32x32x64_f8f6f4 per k-tile and pair of fragments instead
     // of four v_mfma_f32_32x32x16_fp8_fp8
     static constexpr bool K64 = K64_;
@@ -84,13 +95,13 @@ struct Cfg {
     static constexpr bool B_KC = B_KC_;
     static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier
     static constexpr int AHEAD = PF_ ? NS_ - 3 : NS_ - 2;   // stages allowed in flight at the barrier
-    static constexpr int BM = 256, BN = 256, BK = 32, WM = 2, WN = WN_, NW = WM * WN, THREADS = 64 * NW;
+    static constexpr int BM = 128 * WM_, BN = 256, BK = 32, WM = WM_, WN = WN_, NW = WM * WN, THREADS = 64 * NW;
     static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     static constexpr int A_BYTES = BM * 64, B_BYTES = BN * 64, STAGE_BYTES = A_BYTES + B_BYTES;   // 32 KiB
     static constexpr int A_INSTR = A_BYTES / 1024 / NW, B_INSTR = B_BYTES / 1024 / NW;
     static constexpr int LOADS = A_INSTR + B_INSTR;                                               // per wave per stage
     static_assert(NS >= 3 && NS <= 5 && (!PF_ || NS_ >= 4), "ring depth");
-    static_assert(WN == 2 || WN == 4, "2 x 2 or 2 x 4 waves");
+    static_assert((WN == 2 || WN == 4) && (WM_ == 2 || (WM_ == 1 && WN_ == 4)), "2 x 2, 2 x 4 or 1 x 4 waves");
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -267,7 +278,7 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
 #endif
 
 template <class C>
-__global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
+__global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_kernel(Params p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     // one array per ring stage (distinct objects: see the file header); unused ones cost nothing
@@ -292,7 +303,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     const int64_t per_batch = p.tiles_m * p.tiles_n;
     const int64_t batch = tile_id / per_batch;
     int64_t t = tile_id % per_batch;
-    constexpr int BAND = 8;
+    constexpr int BAND = C::BAND;
     const int64_t band = t / (BAND * p.tiles_n), first = band * BAND;
     const int64_t rows_in_band = p.tiles_m - first < BAND ? p.tiles_m - first : BAND;
     t -= band * BAND * p.tiles_n;
@@ -324,7 +335,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
             ctx.b_off[i] = (uint32_t)(row * p.ldb * C::ES + c * 16);
         } else {
             const int pidx = q * 64 + lane, k = pidx >> 5;          // 32 chunks per k-row
-            const int c = (pidx & 31) ^ (4 * (k & 3));
+            const int c = (pidx & 31) ^ (C::SWZ * (k & 3));
             int64_t col = n0 + c * 8;
             col = col + 8 <= p.N ? col : p.N - 8;
             ctx.b_off[i] = (uint32_t)((k * p.ldb + col) * 2);
@@ -348,7 +359,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_ring_kernel(Params p)
     const int g = lane >> 4, jj = lane & 15;
     ctx.tr_row = 8 * (g >> 1) + (jj >> 2);
     const int tr_col = wn * C::WTN + 16 * (g & 1) + 4 * (jj & 3);
-    const int tr_key = 4 * (jj >> 2);                        // 4 * (row & 3)
+    const int tr_key = C::SWZ * (jj >> 2);                   // SWZ * (row & 3)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = tr_col + 32 * j;

@@ -26,6 +26,17 @@ the paper's loop:
     node reachable from the root through KEEP edges only.
 
 Nodes with equal parameters reached along different paths share one measurement.
+
+With --pmc every correct candidate is also PROFILED, as the paper profiles every node (its node
+state is (T, m) with m the profiler's metric vector): three rocprofv3 counter passes per distinct
+kernel, each a child process of its own (separate from timing, as the paper runs its profiler),
+give HBM bytes, L1 requests, executed instructions and matrix-pipe busy cycles; from them the
+node's SOL percentages are MEASURED (matrix pipe busy share of the launch, HBM bytes over time
+against 8 TB/s), so the bottleneck regime and the proxy terms of the reward come from counters and
+the traffic / instruction inflation guardrail can fire.  In that mode this process never touches
+the GPU: a worker child times and checks the candidates, the counter passes are further children.
+Without --pmc the SOL terms are left out (the proxy reward is then 0 rather than a second function
+of the time).
 """
 from __future__ import annotations
 
@@ -86,7 +97,8 @@ def _ringf_exprs(p, layout):
 
 
 def _ring_exprs(p, layout):
-    c = f"ring::Cfg<{p['NS']}, {'true' if layout & 1 else 'false'}, {'true' if p['PF'] else 'false'}, {p['WN']}>"
+    c = (f"ring::Cfg<{p['NS']}, {'true' if layout & 1 else 'false'}, {'true' if p['PF'] else 'false'}, {p['WN']}, DT_BF16, 0, false, "
+         f"{p['BAND']}, {p['SWZ']}>")
     if p["PERSIST"]:
         return (f"ringp::supports<{c}>", f"ringp::launch<{c}>", f"ringp::gemm_ring_persistent_kernel<{c}>")
     return (f"ring::supports<{c}>", f"ring::launch<{c}>", f"ring::gemm_ring_kernel<{c}>")
@@ -113,10 +125,12 @@ FAMILIES = {
         _ringf_exprs, {"BM": 128, "NS": 4}),
     "ring_bf16": Family(
         "ring_bf16", "kernel_ring_persistent.hpp",
-        {"NS": [3, 4, 5], "PF": [0, 1], "WN": [2, 4], "PERSIST": [0, 1]},
+        # BAND: tile rows per band of the workgroup -> tile walk (which panels an XCD's L2 shares);
+        # SWZ: XOR key step of the row-major B tile in LDS (which banks a transposing read touches)
+        {"NS": [3, 4, 5], "PF": [0, 1], "WN": [2, 4], "PERSIST": [0, 1], "BAND": [2, 4, 8, 16], "SWZ": [2, 4]},
         lambda p: (not p["PF"] or p["NS"] >= 4)
-        and (not p["PERSIST"] or p["NS"] * 32768 + 2 * p["WN"] * 1024 <= 160 * 1024),
-        _ring_exprs, {"NS": 4, "PF": 1, "WN": 4, "PERSIST": 0}),
+        and (not p["PERSIST"] or (p["NS"] * 32768 + 2 * p["WN"] * 1024 <= 160 * 1024 and p["BAND"] == 8 and p["SWZ"] == 4)),
+        _ring_exprs, {"NS": 4, "PF": 1, "WN": 4, "PERSIST": 0, "BAND": 8, "SWZ": 4}),
 }
 
 
@@ -319,12 +333,14 @@ def best_keep_chain(root: Node):
 # GPU evaluation
 
 class Evaluator:
-    def __init__(self, workload: str, fam: Family, steps: int, warmup: int):
+    def __init__(self, workload: str, fam: Family, steps: int, warmup: int, with_reference: bool = True):
         from .sweep import Runner
         from inputs import synth
         self.r = Runner(workload)
         self.fam, self.steps, self.warmup = fam, steps, warmup
         w, np = self.r.w, self.r.np
+        if not with_reference:          # a counter pass: nothing but the candidate's own kernels may run
+            return
         self.idx = synth.sample_entries(w.seed, 65536, w.batch, w.M, w.N)
         Cref = self.r.new_c()
         self.r.run(0, Cref)                                  # guarded fallback kernel
@@ -370,10 +386,146 @@ class Evaluator:
         regs, scr, lds = ci(), ci(), ci()
         lib.cand_resources(ctypes.byref(regs), ctypes.byref(scr), ctypes.byref(lds))
         tfl, gbs = w.flops / t / 1e12, w.algorithmic_bytes / t / 1e9
-        peak = 157.3 if w.dtype == 0 else 2516.6
-        return R.Profile(time=t, sol_sm=100.0 * tfl / peak, sol_dram=100.0 * gbs / 8000.0, regs=regs.value,
-                         scratch_bytes=scr.value, correct=correct,
+        # the SOL fields stay empty here: they are the profiler's (see ProfiledEvaluator), and filling them from the
+        # time alone would make the proxy reward a second function of the time
+        return R.Profile(time=t, regs=regs.value, scratch_bytes=scr.value, correct=correct,
                          extra={"err": err, "lds": lds.value, "TFLOP/s": tfl, "GB/s": gbs})
+
+    def launch_only(self, params, times=3):
+        """A few launches of one candidate and nothing else: what a counter pass profiles."""
+        path = build(self.fam, params, self.r.w.layout)
+        lib = ctypes.CDLL(path)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.cand_run.argtypes = [i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, ci, ci, ci, vp]
+        lib.cand_run.restype = ci
+        C = self.r.new_c()
+        for _ in range(times):
+            self._call(lib.cand_run, C)
+        self.r.torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------------
+# profiled evaluation: timing in a worker child, counters in rocprofv3 children
+
+# One rocprofv3 run cannot split counters over passes: each group stays within the per-block limits
+# (TCC: FETCH_SIZE takes 3 of 4, WRITE_SIZE 2; SQ: 8; TCP: 4; GRBM: 2).
+PMC_GROUPS = (
+    ("FETCH_SIZE",),
+    ("WRITE_SIZE", "TCP_TOTAL_CACHE_ACCESSES_sum", "TCP_TCC_READ_REQ_sum"),
+    ("SQ_INSTS_VALU", "SQ_INSTS_SALU", "SQ_INSTS_LDS", "SQ_INSTS_VMEM_RD", "SQ_INSTS_VMEM_WR", "SQ_VALU_MFMA_BUSY_CYCLES",
+     "GRBM_GUI_ACTIVE"),
+)
+# what the byte counters read for a plain copy of known size on this chip (KiB -> bytes)
+FETCH_SCALE, WRITE_SCALE = 2.0 * 1024.0, 1.0 * 1024.0
+PEAK_HBM_BYTES_PER_S = 8.0e12
+SIMDS, XCDS = 1024, 8
+
+
+def signals(counters: dict, seconds: float) -> dict:
+    """Profiler signals of the reward from raw per-dispatch counter sums and the kernel's time: SOL of the
+    matrix pipe (busy cycles per SIMD over the launch's cycles per XCD), SOL of HBM (bytes over time against
+    the peak), HBM bytes, L1 requests, executed instructions.  Missing counters give None."""
+    out = {"sol_sm": None, "sol_dram": None, "l1": None, "dram_bytes": None, "inst": None}
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in counters and counters.get("GRBM_GUI_ACTIVE", 0) > 0:
+        out["sol_sm"] = 100.0 * (counters["SQ_VALU_MFMA_BUSY_CYCLES"] / SIMDS) / (counters["GRBM_GUI_ACTIVE"] / XCDS)
+    if "FETCH_SIZE" in counters and "WRITE_SIZE" in counters:
+        out["dram_bytes"] = counters["FETCH_SIZE"] * FETCH_SCALE + counters["WRITE_SIZE"] * WRITE_SCALE
+        if seconds > 0 and math.isfinite(seconds):
+            out["sol_dram"] = 100.0 * out["dram_bytes"] / seconds / PEAK_HBM_BYTES_PER_S
+    if "TCP_TOTAL_CACHE_ACCESSES_sum" in counters:
+        out["l1"] = counters["TCP_TOTAL_CACHE_ACCESSES_sum"]
+    inst = [counters[k] for k in ("SQ_INSTS_VALU", "SQ_INSTS_SALU", "SQ_INSTS_LDS", "SQ_INSTS_VMEM_RD", "SQ_INSTS_VMEM_WR")
+            if k in counters]
+    if len(inst) == 5:
+        out["inst"] = float(sum(inst))
+    return out
+
+
+def main_kernel_counters(csv_paths, wanted) -> dict:
+    """Mean per dispatch of each wanted counter for the library kernel that dominates the run: per kernel name
+    the mean over its dispatches, then per counter the largest of those means (the copy kernel and
+    framework kernels are left out)."""
+    import csv
+    per_kernel = {}
+    for f in csv_paths:
+        for row in csv.DictReader(open(f)):
+            k = row["Kernel_Name"]
+            if "optiml" not in k or "copy_kernel" in k:
+                continue
+            per_kernel.setdefault(k, {}).setdefault(row["Counter_Name"], []).append(float(row["Counter_Value"]))
+    vals = {}
+    for c in wanted:
+        best = max((sum(v[c]) / len(v[c]) for v in per_kernel.values() if c in v), default=None)
+        if best is not None:
+            vals[c] = best
+    return vals
+
+
+def collect_counters(workload: str, fam: Family, params: dict, timeout: int = 180) -> dict:
+    """The counter passes of one candidate, each `rocprofv3 --pmc <group> -- python -m ...search --pmc-child`."""
+    import glob
+    import tempfile
+    vals = {}
+    root = os.path.dirname(HERE)
+    for group in PMC_GROUPS:
+        with tempfile.TemporaryDirectory(dir="/tmp") as d:
+            cmd = ["rocprofv3", "--pmc", *group, "--output-format", "csv", "-d", d, "-o", "r", "--", sys.executable, "-m",
+                   "paper_2602_12305_amd.search", "--workload", workload, "--family", fam.name, "--pmc-child", json.dumps(params)]
+            try:
+                subprocess.run(cmd, cwd=root, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL, timeout=timeout, check=False,
+                               env={**os.environ, "TMPDIR": "/tmp"})
+            except (subprocess.TimeoutExpired, OSError):
+                continue
+            vals.update(main_kernel_counters(glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True), group))
+    return vals
+
+
+class ProfiledEvaluator:
+    """evaluate(params) for search(): time and correctness from a worker child (one per search, fed one JSON line per
+    candidate), counters from collect_counters() for every correct candidate.  The process that owns this object
+    never touches the GPU."""
+
+    def __init__(self, workload: str, fam: Family, steps: int, warmup: int, counters=collect_counters):
+        self.workload, self.fam, self.counters = workload, fam, counters
+        self.worker = subprocess.Popen([sys.executable, "-m", "paper_2602_12305_amd.search", "--workload", workload, "--family",
+                                        fam.name, "--steps", str(steps), "--warmup", str(warmup), "--worker"],
+                                       cwd=os.path.dirname(HERE), stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True)
+
+    def __call__(self, params) -> R.Profile:
+        self.worker.stdin.write(json.dumps(params) + "\n")
+        self.worker.stdin.flush()
+        line = self.worker.stdout.readline()
+        while line and not line.startswith("{"):               # anything a library printed on stdout
+            line = self.worker.stdout.readline()
+        if not line:
+            return R.Profile(time=math.inf, correct=False, extra={"why": "worker ended"})
+        j = json.loads(line)
+        p = R.Profile(time=j["time"] if j["time"] is not None else math.inf, regs=j.get("regs"),
+                      scratch_bytes=j.get("scratch_bytes"), correct=j["correct"], extra=j.get("extra", {}))
+        if p.correct:
+            c = self.counters(self.workload, self.fam, params)
+            for k, v in signals(c, p.time).items():
+                setattr(p, k, v)
+            p.extra["counters"] = c
+        return p
+
+    def close(self):
+        try:
+            self.worker.stdin.close()
+            self.worker.wait(timeout=60)
+        except Exception:
+            self.worker.kill()
+
+
+def worker_loop(ev: "Evaluator"):
+    """Child of ProfiledEvaluator: one candidate per input line, one JSON profile per output line."""
+    for line in sys.stdin:
+        line = line.strip()
+        if not line:
+            continue
+        p = ev(json.loads(line))
+        print(json.dumps({"time": p.time if math.isfinite(p.time) else None, "regs": p.regs, "scratch_bytes": p.scratch_bytes,
+                          "correct": bool(p.correct), "extra": p.extra}), flush=True)
 
 
 def main():
@@ -391,8 +543,18 @@ def main():
     ap.add_argument("--prebuild", type=int, default=-1,
                     help="only compile every candidate within this many edits of the root (no GPU needed)")
     ap.add_argument("--jobs", type=int, default=8)
+    ap.add_argument("--pmc", action="store_true", help="profile every correct candidate with rocprofv3 counter passes")
+    ap.add_argument("--worker", action="store_true", help=argparse.SUPPRESS)        # child: time candidates read from stdin
+    ap.add_argument("--pmc-child", default="", help=argparse.SUPPRESS)              # child under rocprofv3: launch one candidate
     a = ap.parse_args()
     fam = FAMILIES[a.family]
+
+    if a.worker:
+        worker_loop(Evaluator(a.workload, fam, a.steps, a.warmup))
+        return
+    if a.pmc_child:
+        Evaluator(a.workload, fam, 1, 0, with_reference=False).launch_only(json.loads(a.pmc_child))
+        return
 
     if a.prebuild >= 0:
         layout = a.layout if a.layout >= 0 else (1 if a.workload.startswith("c3_") else 0)   # only config 3 has B column-major
@@ -402,7 +564,7 @@ def main():
         print(f"{sum(x is not None for x in res)} of {len(pts)} candidates of {fam.name} built under {CAND}")
         return
 
-    ev = Evaluator(a.workload, fam, a.steps, a.warmup)
+    ev = ProfiledEvaluator(a.workload, fam, a.steps, a.warmup) if a.pmc else Evaluator(a.workload, fam, a.steps, a.warmup)
     out = open(a.out, "a") if a.out else None
 
     def log(n: Node):
@@ -412,14 +574,24 @@ def main():
                "correct": n.alive, "reward": None if n.reward == -math.inf else round(n.reward, 4), "keep": n.keep,
                "regs": p.regs, "scratch": p.scratch_bytes, **{k: (round(v, 3) if isinstance(v, float) else v)
                                                                for k, v in p.extra.items()}}
+        if n.alive and p.sol_sm is not None:
+            rec.update({"sol_sm": round(p.sol_sm, 2), "sol_dram": None if p.sol_dram is None else round(p.sol_dram, 2),
+                        "dram_bytes": p.dram_bytes, "l1": p.l1, "inst": p.inst, "regime": R.regime(p)})
+            if n.parent is not None:
+                rec["r_time"] = round(R.time_reward(n.parent.profile.time, p.time), 4)
+                rec["r_proxy"] = round(R.proxy_reward(n.parent.profile, p), 4)
+                rec["p_guard"] = round(R.guard_penalty(n.parent.profile, p), 4)
         if out:
             out.write(json.dumps(rec) + "\n")
             out.flush()
         ms = f"{p.time * 1e3:9.4f} ms" if n.alive else f"   dead ({p.extra.get('why', 'wrong result')})"
         rw = "   -inf" if n.reward == -math.inf else f"{n.reward:+7.3f}"
-        print(f"d{n.depth} {n.edit:16s} {key(n.params):40s} {ms}  R {rw} {'KEEP' if n.keep else ''}", flush=True)
+        sol = f"  sm {p.sol_sm:5.1f}% dram {p.sol_dram:5.1f}% proxy {rec.get('r_proxy', 0.0):+.3f}" if "sol_sm" in rec and p.sol_dram is not None else ""
+        print(f"d{n.depth} {n.edit:16s} {key(n.params):52s} {ms}  R {rw} {'KEEP' if n.keep else '    '}{sol}", flush=True)
 
     root, nodes = search(fam, fam.root, ev, a.budget, a.depth, a.c, a.seed, log)
+    if a.pmc:
+        ev.close()
     best, path = best_keep_chain(root)
     print(f"evaluated {len(nodes)} nodes ({len({key(n.params) for n in nodes})} distinct kernels)")
     print("best KEEP chain: " + " -> ".join(f"{key(n.params)} ({n.profile.time * 1e3:.4f} ms)" for n in path))

@@ -145,9 +145,9 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 8, 4096, 4096).startswith("skinny_f32")
     assert sel(1, 4096, 4096, 4096, layout=1).startswith("ring_f32_rc_128x128")
     assert sel(1, 8192, 8192, 8192, dtype=1).startswith("ring_bf16_rr_256x256")
-    assert sel(32, 2048, 2048, 512, dtype=1).startswith("ringp_bf16_rr_256x256")   # many short tiles: persistent
+    assert sel(32, 2048, 2048, 512, dtype=1).startswith("ring_bf16_rr_128x256_w1x4")   # many short tiles: two workgroups to a CU
     assert sel(1, 8192, 8192, 8192, dtype=2).startswith("ring_f16_rr_256x256")      # binary16: the same kernels
-    assert sel(32, 2048, 2048, 512, dtype=2, layout=1).startswith("ringp_f16_rc_256x256")
+    assert sel(32, 2048, 2048, 512, dtype=2, layout=1).startswith("ring_f16_rc_128x256_w1x4")
     assert sel(1, 1024, 1024, 64, layout=2, dtype=2).startswith("tile_f16_cr_")
     assert sel(1, 1000, 1001, 64, dtype=2) == "generic_64x64"
     assert sel(1, 8192, 8192, 8192, layout=2, dtype=1) == "xa_ring"       # column-major A: row-major copy, then a ring kernel

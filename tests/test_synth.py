@@ -97,3 +97,12 @@ def test_full_size_workload_accounting():
     assert bytes_(32, 2048, 2048, 512, 2) == 402915328
     w = synth.make_workload("c1_f32_256_relu")
     assert w.algorithmic_bytes == 787456 and w.flops == 2 * 256 ** 3
+
+
+def test_workload_specs_match_the_workloads_they_describe():
+    assert sorted(synth.SPECS) == sorted(synth.WORKLOADS + synth.BREADTH_WORKLOADS)
+    for name, (batch, M, N, K, layout, dtype, act) in synth.SPECS.items():
+        s = 64 if M >= 4096 or N >= 4096 else 1
+        w = synth.make_workload(name, scale=s)
+        assert (w.batch, w.layout, w.dtype, w.act) == (batch, layout, dtype, act), name
+        assert (w.M * (s if M > 16 else 1), w.N * s, w.K * s) == (M, N, K), name
