@@ -167,9 +167,70 @@ def f8e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.where(b >> 7 == 1, -v, v).astype(np.float32)
 
 
+# the eight magnitudes of OCP E2M1, by code
+_F4_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
+
+
+def f32_to_f4e2m1_codes(x: np.ndarray) -> np.ndarray:
+    """Nearest OCP E2M1 code of each fp32 value (ties to the even code, magnitudes beyond 6 saturate, NaN -> +0): uint8
+    in 0..15, one code per element (not yet packed)."""
+    x = np.nan_to_num(np.ascontiguousarray(x, dtype=np.float32), nan=0.0)
+    a = np.minimum(np.abs(x), np.float32(6.0))
+    # midpoints between neighbouring magnitudes; a tie goes to the even code (0, 1.0, 2.0, 4.0 have even codes)
+    mids = (_F4_VALUES[:-1] + _F4_VALUES[1:]) / np.float32(2.0)
+    code = np.searchsorted(mids, a, side="left").astype(np.int64)            # a == mid -> the lower code
+    tie = np.isin(a, mids) & (code % 2 == 1)                                  # lower code odd -> take the upper, even one
+    code = code + tie.astype(np.int64)
+    return (code | (np.signbit(x).astype(np.int64) << 3)).astype(np.uint8)
+
+
+def pack_f4(codes: np.ndarray) -> np.ndarray:
+    """Two 4-bit codes to a byte along the last axis (even index in the low four bits); the last axis must be even."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    if c.shape[-1] % 2:
+        raise ValueError("an even number of 4-bit elements per row expected")
+    return (c[..., 0::2] | (c[..., 1::2] << np.uint8(4))).astype(np.uint8)
+
+
+def unpack_f4(packed: np.ndarray) -> np.ndarray:
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    out = np.empty(p.shape[:-1] + (2 * p.shape[-1],), dtype=np.uint8)
+    out[..., 0::2] = p & np.uint8(15)
+    out[..., 1::2] = p >> np.uint8(4)
+    return out
+
+
+def f4e2m1_codes_to_f32(codes: np.ndarray) -> np.ndarray:
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    v = _F4_VALUES[c & np.uint8(7)]
+    return np.where((c >> np.uint8(3)) & np.uint8(1) == 1, -v, v).astype(np.float32)
+
+
+def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
+    """Block-scaled storage of an fp32 matrix [rows, K] in the way of the OCP microscaling formats: every `block`
+    consecutive elements of a row share an E8M0 scale 2^(floor(log2(max |x|)) - emax) with emax the largest exponent of
+    the element type (2 for E2M1, 8 for E4M3), and the elements are x / scale rounded to that type.  Returns (stored
+    elements as to_bits would give them, scale codes uint8 [rows, ceil(K / block)]).  An all-zero block gets scale code 127."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, K = x.shape
+    nb = (K + block - 1) // block
+    pad = np.zeros((rows, nb * block), dtype=np.float32)
+    pad[:, :K] = x
+    amax = np.abs(pad.reshape(rows, nb, block)).max(axis=2)
+    emax = 2 if dtype == DTYPE_F4E2M1 else 8
+    with np.errstate(divide="ignore"):
+        e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - emax, 0.0)
+    e = np.clip(e, -127, 127)
+    scale = np.exp2(e).astype(np.float32)
+    q = (pad.reshape(rows, nb, block) / scale[:, :, None]).reshape(rows, nb * block)[:, :K]
+    return to_bits(q, dtype), (e + 127).astype(np.uint8)
+
+
 def to_bits(x, dtype):
-    """Storage of an fp32 array in the given dtype: fp32 itself, the uint16 patterns of bf16 / fp16, or the uint8
-    patterns of E4M3."""
+    """Storage of an fp32 array in the given dtype: fp32 itself, the uint16 patterns of bf16 / fp16, the uint8
+    patterns of E4M3, or E2M1 codes packed two to a byte (last axis halved)."""
+    if dtype == DTYPE_F4E2M1:
+        return pack_f4(f32_to_f4e2m1_codes(x))
     if dtype == DTYPE_BF16:
         return f32_to_bf16_bits(x)
     if dtype == DTYPE_F16:
@@ -181,6 +242,8 @@ def to_bits(x, dtype):
 
 def from_bits(b, dtype):
     """fp32 values of stored data (inverse of to_bits)."""
+    if dtype == DTYPE_F4E2M1:
+        return f4e2m1_codes_to_f32(unpack_f4(b))
     if dtype == DTYPE_BF16:
         return bf16_bits_to_f32(b)
     if dtype == DTYPE_F16:
@@ -220,7 +283,7 @@ def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
 # ----------------------------------------------------------------------------------------------
 # The five workloads
 
-DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3 = 0, 1, 2, 3
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3, DTYPE_F4E2M1 = 0, 1, 2, 3, 4
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 
