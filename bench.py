@@ -108,7 +108,7 @@ TRAFFIC = {
         {"bytes": int((609659.9 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "7ff6f414fc2ebc17"},
     ("s_transpose", "s_transpose"):
         {"bytes": int((524327.0 * 2.0 + 1048910.0) * 1024), "files": TRANSPOSE_SRC, "src": "00f7350d0ac9d4a0"},
-    ("s_mhsa", "mhsa_flash_bf16_dk128"):
+    ("s_mhsa", "mhsa_pingpong_bf16_dk128"):
         {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "a4876881c0272702"},
     ("s_lce", "ring_bf16_rr_lse"):
         {"bytes": int((1590396.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "6afe4dac2e72a9c6"},
@@ -400,7 +400,7 @@ def main():
 
     class Mhsa(Case):
         """Multi-head self-attention, bf16 storage, seeded N(0, 1) inputs."""
-        bound, dtype, kernel = "mfma", 1, "mhsa_flash_bf16_dk128"
+        bound, dtype, kernel = "mfma", 1, "mhsa_pingpong_bf16_dk128"
 
         def __init__(self, name):
             self.name = name

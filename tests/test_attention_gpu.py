@@ -59,6 +59,21 @@ def test_bf16_matrix_pipe_kernel_matches_the_oracle(batch, N, d, heads):
     assert e1(got, ref) <= 2e-2
 
 
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("batch,N,d,heads", [(1, 256, 128, 1), (2, 257, 256, 2), (1, 319, 128, 1), (1, 320, 128, 1), (3, 511, 128, 1),
+                                             (1, 513, 384, 3), (1, 1217, 128, 1)])
+def test_eight_wave_kernel_at_the_edges_of_its_blocks(batch, N, d, heads, dtype):
+    """d_k = 128 and N >= 256 run the kernel whose workgroup holds 256 queries in two groups of waves a phase apart:
+    one full block exactly, a last query block of 1 .. 255 rows, a last key block of 1 .. 63 keys, an odd and an even
+    number of key blocks."""
+    Q, K, V = inputs(2700 + N + d, batch, N, d)
+    got = run(Q, K, V, heads, dtype)
+    ref = reference(Q, K, V, heads, dtype)
+    assert np.all(np.isfinite(got))
+    assert e1(got, ref) <= (2e-2 if dtype == BF16 else 2e-3)
+    assert np.array_equal(got, run(Q, K, V, heads, dtype))                 # bitwise repeatable
+
+
 @pytest.mark.parametrize("batch,N,d,heads,dtype", [(1, 100, 96, 3, F32), (2, 77, 40, 5, F32), (1, 300, 128, 1, F32),
                                                    (1, 64, 512, 2, F32), (1, 150, 96, 3, BF16), (1, 5, 7, 1, F32),
                                                    (1, 1, 16, 2, F32), (2, 129, 200, 1, F32)])
