@@ -99,7 +99,7 @@ TRAFFIC = {
     ("s_ce", "s_ce"):
         {"bytes": int((524988.0 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((1049946.3 * 2.0 + 1049990.3) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
+        {"bytes": int((527793.0 * 2.0 + 1053600.0) * 1024), "files": ROWS_SRC, "src": "c83f66083110762a"},
     ("s_ln_token", "s_ln_token"):
         {"bytes": int((524321.3 * 2.0 + 1048587.4) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):

@@ -259,8 +259,13 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
  * row; no scale or shift (the task names none; eps is the caller's, 1e-5 in common use).
  * x[r*len + i] -> y[r*len + i]; y may be x itself.  Statistics and the normalisation are
  * evaluated in fp64 and rounded once to float.  Rows longer than 32768 (8192 unless x, y are
- * 16-byte aligned and len % 4 == 0) use the per-device workspace and two kernels per group of
- * rows of about 256 MiB (x is then read twice).  rows == 0 or len == 0 writes nothing.
+ * 16-byte aligned and len % 4 == 0) use the per-device workspace.  Aligned rows of up to 4 Mi
+ * values are still read once: the workgroups that share a row exchange their partial sums
+ * through the workspace inside one kernel and wait for each other, for at most the number of
+ * shader clocks set by optiml_set_wait_limit (default 2^22, about 2 ms; 0 = no waiting); a
+ * workgroup whose wait runs out leaves its part of the row to a second kernel, which reads x
+ * again, so the result does not depend on the limit.  Other long rows take two kernels per
+ * group of rows of about 256 MiB (x is then read twice).  rows == 0 or len == 0 writes nothing.
  *
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, C < 1, ld < C, NULL loss, NULL
  * logits / labels / x / y with work to do, eps negative or NaN.
@@ -268,6 +273,8 @@ int optiml_reduce(int64_t n, const float *x, const float *y, int op, float *out,
 int optiml_cross_entropy(int64_t N, int64_t C, const float *logits, int64_t ld, const int32_t *labels, float *loss,
                          void *stream);
 int optiml_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, void *stream);
+/* Process-wide bound, in shader clocks, of the wait described under optiml_layernorm; negative values count as 0. */
+void optiml_set_wait_limit(int64_t clocks);
 
 /*
  * Transpose (the paper's Table 4, task 8): dst[j * ld_dst + i] = src[i * ld_src + j] for a

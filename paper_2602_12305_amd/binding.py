@@ -48,6 +48,7 @@ SIGNATURES = {
     "optiml_gemm_cross_entropy_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _int, _int]),
     "optiml_set_workspace": (_int, [_vp, _i64]),
     "optiml_workspace_bytes": (_i64, []),
+    "optiml_set_wait_limit": (None, [_i64]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -235,6 +236,11 @@ def optiml_set_workspace(ptr, nbytes):
 
 def optiml_workspace_bytes():
     return lib().optiml_workspace_bytes()
+
+
+def optiml_set_wait_limit(clocks):
+    """Bound, in shader clocks, of the wait between the workgroups of one long LayerNorm row."""
+    lib().optiml_set_wait_limit(int(clocks))
 
 
 def optiml_status_string(status):

@@ -820,6 +820,8 @@ int optiml_set_workspace(void *ptr, int64_t bytes)
     return OPTIML_OK;
 }
 
+void optiml_set_wait_limit(int64_t clocks) { optiml::set_wait_limit((long long)clocks); }
+
 int64_t optiml_workspace_bytes(void)
 {
     int dev = 0;

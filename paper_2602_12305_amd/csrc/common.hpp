@@ -89,6 +89,7 @@ hipError_t launch_reduce(int64_t n, const float *x, const float *y, int op, floa
 hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld, const int *labels, float *loss,
                                 hipStream_t stream);
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
+void set_wait_limit(long long clocks);
 
 // attention (kernel_attention.hip): which kernel would serve (0 flash, 1 fallback, -1 none), launch
 int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const void *K, const void *V, const void *O);

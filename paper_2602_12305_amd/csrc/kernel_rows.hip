@@ -351,10 +351,11 @@ __global__ __launch_bounds__(kThreads) void layernorm_wave_kernel(const float *_
 }
 
 // long rows, first kernel: stats[(row * chunks + c) * 2 + {0, 1}] = sum of d, sum of d^2 over the
-// chunk, d = x - x_row[0].  Plain loads: the data is meant to stay in cache for the second kernel.
+// chunk, d = x - x_row[0]; pivots[row] = x_row[0] (y may be x: the second kernel must not read it there).  Plain loads: the data is meant to stay in cache for the second kernel.
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *__restrict__ x, int64_t len, int64_t chunks,
-                                                                   int64_t kChunk, double *__restrict__ stats)
+                                                                   int64_t kChunk, double *__restrict__ stats,
+                                                                   double *__restrict__ pivots)
 {
     __shared__ double scratch[kThreads / 64][2];
     const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
@@ -391,6 +392,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *
     if (threadIdx.x == 0) {
         stats[2 * blockIdx.x] = s;
         stats[2 * blockIdx.x + 1] = q;
+        if (c == 0) pivots[row] = pivot;
     }
 }
 
@@ -398,8 +400,11 @@ __global__ __launch_bounds__(kThreads) void layernorm_stats_kernel(const float *
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void layernorm_apply_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                                    int64_t len, int64_t chunks, int64_t kChunk,
-                                                                   const double *__restrict__ stats, double eps)
+                                                                   const double *__restrict__ stats,
+                                                                   const double *__restrict__ pivots, double eps,
+                                                                   const unsigned *__restrict__ done)
 {
+    if (done != nullptr && done[blockIdx.x] != 0u) return;      // normalised by the one-pass kernel already
     const int64_t row = blockIdx.x / chunks, c = blockIdx.x % chunks;
     const float *xr = x + row * len;
     float *yr = y + row * len;
@@ -412,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_apply_kernel(const float *
     block_sum2(s, q, scratch);
     const double inv_len = 1.0 / (double)len;
     const double dm = s * inv_len;                        // mean - pivot
-    const double mean = (double)xr[0] + dm;
+    const double mean = pivots[row] + dm;
     double var = q * inv_len - dm * dm;                   // shifted-data formula
     var = var > 0.0 ? var : 0.0;
     const double rstd = 1.0 / sqrt(var + eps);
@@ -443,7 +448,159 @@ __global__ __launch_bounds__(kThreads) void layernorm_apply_kernel(const float *
     }
 }
 
+// Long rows in ONE pass over x.  A workgroup keeps a chunk of 8 Ki features in registers (8 vectors a thread),
+// publishes the chunk's (sum of d, sum of d^2), announces itself on the row's counter and waits until all the
+// row's chunks have done so; then every workgroup adds the row's chunk sums in the same fixed order and normalises
+// from registers: 8 bytes of traffic per feature instead of 12.
+//   * The grid is persistent: no larger than what the device holds at once, a multiple of the chunks per row where
+//     that fits, each workgroup taking chunk after chunk (index += grid size), so that the workgroups of a row
+//     reach it together whatever order the hardware starts workgroups in.
+//   * Signalling through a memory system that is saturated with the rows themselves takes microseconds per round
+//     trip, so a workgroup has TWO chunks in flight: it loads and publishes its next chunk before it waits for the
+//     row of the current one, and the wait is hidden behind that load.
+//   * Other work on the device can still keep part of the grid from running, so the wait is bounded (`wait_clocks`
+//     shader clocks): a workgroup that gives up leaves its chunk to layernorm_apply_kernel, which runs afterwards
+//     over all chunks and skips those marked done.  `arrived` and `done` start at zero.
+constexpr int64_t kOnePassChunk = 8192, kOnePassMaxChunks = 512;     // rows of up to 4 Mi features; beyond, two kernels are faster
+
+__global__ __launch_bounds__(kThreads, 4) void layernorm_onepass_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t len,
+                                                                        int64_t chunks, int64_t tasks, double *stats, double *pivots,
+                                                                        unsigned long long *arrived, unsigned *done, double eps,
+                                                                        long long wait_clocks)
+{
+    __shared__ double scratch[kThreads / 64][2];
+    __shared__ int ready;
+    constexpr int U = (int)(kOnePassChunk / 4 / kThreads);      // vectors a thread holds of one chunk
+    auto count_of = [&](int64_t task) __attribute__((always_inline)) {                   // vectors in the chunk
+        const int64_t lo = (task % chunks) * kOnePassChunk;
+        return ((lo + kOnePassChunk < len ? lo + kOnePassChunk : len) - lo) / 4;        // len % 4 == 0 here
+    };
+    // the chunk into registers, its sums published, its arrival counted
+    auto take = [&](floatx4 (&v)[U], float &pivot, int64_t task) __attribute__((always_inline)) {
+        const int64_t row = task / chunks, c = task % chunks;
+        const float *xr = x + row * len;
+        pivot = xr[0];
+        const int64_t n4 = count_of(task);
+        const floatx4 *x4 = reinterpret_cast<const floatx4 *>(xr + c * kOnePassChunk);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = threadIdx.x + u * kThreads;
+            v[u] = i < n4 ? __builtin_nontemporal_load(x4 + i) : floatx4{pivot, pivot, pivot, pivot};
+        }
+        double s = 0.0, q = 0.0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double d = (double)v[u][e] - (double)pivot;
+                s += d;
+                q += d * d;
+            }
+            __builtin_amdgcn_sched_barrier(0);           // one vector at a time: the doubles are not kept
+        }
+        block_sum2(s, q, scratch);
+        if (threadIdx.x == 0) {
+            // Only relaxed device-scope atomics cross between workgroups here: they are performed at the memory
+            // side, past the per-XCD L2s, and cost nothing else (an acquire or release at device scope would
+            // invalidate or write back a whole L2 for every workgroup and poll).  Order comes from completion:
+            // the two exchanges have returned their old values, so they are done, before the counter is bumped,
+            // and a reader loads the sums only after it has seen the full count.  Such atomics on ONE address
+            // take about 0.1 us each, one after the other, so a row counts its arrivals in 32 places (16 words of
+            // 64 bits, a count in each half), which one 16-lane load reads back.
+            const double old_s = __hip_atomic_exchange(stats + 2 * task, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double old_q = __hip_atomic_exchange(stats + 2 * task + 1, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (c == 0) pivots[row] = (double)pivot;     // for the second kernel: y may be x, and x[row][0] gone by then
+            asm volatile("" :: "v"(old_s), "v"(old_q) : "memory");       // both have returned
+            const unsigned long long old_n = __hip_atomic_fetch_add(arrived + row * 16 + ((c & 31) >> 1), (c & 1) ? 1ull << 32 : 1ull,
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("" :: "v"(old_n) : "memory");
+        }
+    };
+    // wait for the chunk's row, normalise from registers
+    auto finish = [&](floatx4 (&v)[U], float pivot, int64_t task) __attribute__((always_inline)) {
+        const int64_t row = task / chunks, c = task % chunks;
+        if (threadIdx.x < 64) {
+            const unsigned long long *row_count = arrived + row * 16;
+            const long long t0 = (long long)__builtin_amdgcn_s_memtime();
+            int ok = 0;
+            for (;;) {
+                const unsigned long long w = threadIdx.x < 16 ? __hip_atomic_load(row_count + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                unsigned seen = (unsigned)(w & 0xffffffffull) + (unsigned)(w >> 32);
+#pragma unroll
+                for (int off = 8; off >= 1; off >>= 1) seen += __shfl_xor(seen, off, 64);
+                seen = __builtin_amdgcn_readfirstlane(seen);
+                if (seen >= (unsigned)chunks) { ok = 1; break; }
+                if ((long long)__builtin_amdgcn_s_memtime() - t0 >= wait_clocks) break;
+                // every poll of a row goes to the same two lines in memory: sleep longer while many are missing
+                for (unsigned k = 0; k <= ((unsigned)chunks - seen) / 32u; ++k) __builtin_amdgcn_s_sleep(4);
+            }
+            asm volatile("" ::: "memory");
+            if (threadIdx.x == 0) ready = ok;
+        }
+        __syncthreads();
+        const bool go = ready != 0;
+        __syncthreads();                                  // `ready` is free again
+        if (!go) return;                                  // the second kernel normalises this chunk
+        double s = 0.0, q = 0.0;                          // thread t: chunks t, t + 256, ... in order, as the apply kernel
+        for (int64_t i = threadIdx.x; i < chunks; i += kThreads) {
+            s += __hip_atomic_load(stats + 2 * (row * chunks + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            q += __hip_atomic_load(stats + 2 * (row * chunks + i) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        block_sum2(s, q, scratch);
+        const double inv_len = 1.0 / (double)len;
+        const double dm = s * inv_len;                    // mean - pivot
+        const double mean = (double)pivot + dm;
+        double var = q * inv_len - dm * dm;               // shifted-data formula
+        var = var > 0.0 ? var : 0.0;
+        const double rstd = 1.0 / sqrt(var + eps);
+        const int64_t n4 = count_of(task);
+        floatx4 *y4 = reinterpret_cast<floatx4 *>(y + row * len + c * kOnePassChunk);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = threadIdx.x + u * kThreads;
+            if (i < n4) {
+                floatx4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float f = v[u][e];
+                    asm volatile("" : "+v"(f));          // convert again here rather than keep 64 doubles from the first pass
+                    r[e] = (float)(((double)f - mean) * rstd);
+                }
+                __builtin_nontemporal_store(r, y4 + i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (threadIdx.x == 0) done[task] = 1u;
+    };
+
+    floatx4 va[U], vb[U];
+    float pa = 0.0f, pb = 0.0f;
+    int64_t t = blockIdx.x;
+    if (t < tasks) take(va, pa, t);
+    while (t < tasks) {
+        int64_t tn = t + gridDim.x;
+        if (tn < tasks) take(vb, pb, tn);
+        finish(va, pa, t);
+        t = tn;
+        if (t >= tasks) break;
+        tn = t + gridDim.x;
+        if (tn < tasks) take(va, pa, tn);
+        finish(vb, pb, t);
+        t = tn;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void zero_words_kernel(unsigned *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+long long g_wait_clocks = 1ll << 22;       // about 2 ms: a row's loads take microseconds
+
 }  // namespace
+
+void set_wait_limit(long long clocks) { g_wait_clocks = clocks < 0 ? 0 : clocks; }
 
 hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld, const int *labels, float *loss,
                                 hipStream_t stream)
@@ -513,6 +670,33 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
         else hipLaunchKernelGGL((layernorm_short_kernel<true, 1024, 8>), grid, dim3(1024), 0, stream, x, y, len, e64);
         return hipGetLastError();
     }
+    if (vec && (len + kOnePassChunk - 1) / kOnePassChunk <= kOnePassMaxChunks) {
+        const int64_t chunks = (len + kOnePassChunk - 1) / kOnePassChunk, blocks = rows * chunks;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        // workspace: 2 doubles per chunk, a pivot per row, 16 words of 64 bits of arrival counts per row, a flag per chunk
+        const size_t words = (size_t)(32 * rows + blocks);
+        void *ws = nullptr;
+        hipError_t e = workspace(sizeof(double) * (2 * (size_t)blocks + (size_t)rows) + sizeof(unsigned) * words, &ws, stream);
+        if (e != hipSuccess) return e;
+        double *stats = static_cast<double *>(ws), *pivots = stats + 2 * blocks;
+        unsigned long long *arrived = reinterpret_cast<unsigned long long *>(pivots + rows);
+        unsigned *done = reinterpret_cast<unsigned *>(arrived + 16 * rows);
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                           reinterpret_cast<unsigned *>(arrived), (int64_t)words);
+        // persistent grid: what the device holds at once, rounded down to whole rows
+        static const int per_cu = [] {
+            int n = 0;
+            return hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, layernorm_onepass_kernel, kThreads, 0) == hipSuccess && n > 0 ? n : 1;
+        }();
+        int64_t grid = (int64_t)per_cu * compute_units();
+        if (grid > chunks) grid -= grid % chunks;
+        if (grid > blocks) grid = blocks;
+        hipLaunchKernelGGL(layernorm_onepass_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, x, y, len, chunks, blocks,
+                           stats, pivots, arrived, done, (double)eps, g_wait_clocks);
+        hipLaunchKernelGGL(layernorm_apply_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, y, len, chunks,
+                           kOnePassChunk, stats, pivots, (double)eps, done);
+        return hipGetLastError();
+    }
     // Chunk and group sizes from a sweep on 64 rows of 4 Mi features: 16 Ki features per workgroup and
     // groups of 256 MiB gave 4.3 TB/s of algorithmic bytes; 8 - 32 Ki and 32 MiB - everything stayed
     // within 8 % of that, 16 MiB groups (too few workgroups per launch) fell to 2.9 TB/s.
@@ -523,20 +707,20 @@ hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y,
     group = group < 1 ? 1 : group;
     if (group * chunks > 0x7fffffffLL) return hipErrorInvalidValue;
     void *ws = nullptr;
-    hipError_t e = workspace(sizeof(double) * 2 * (size_t)(group * chunks), &ws, stream);
+    hipError_t e = workspace(sizeof(double) * (2 * (size_t)(group * chunks) + (size_t)group), &ws, stream);
     if (e != hipSuccess) return e;
-    double *stats = static_cast<double *>(ws);
+    double *stats = static_cast<double *>(ws), *pivots = stats + 2 * group * chunks;
     for (int64_t r0 = 0; r0 < rows; r0 += group) {
         const int64_t nr = rows - r0 < group ? rows - r0 : group;
         const dim3 grid((unsigned)(nr * chunks)), block(kThreads);
         const float *xg = x + r0 * len;
         float *yg = y + r0 * len;
         if (vec) {
-            hipLaunchKernelGGL(layernorm_stats_kernel<true>, grid, block, 0, stream, xg, len, chunks, kChunk, stats);
-            hipLaunchKernelGGL(layernorm_apply_kernel<true>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, (double)eps);
+            hipLaunchKernelGGL(layernorm_stats_kernel<true>, grid, block, 0, stream, xg, len, chunks, kChunk, stats, pivots);
+            hipLaunchKernelGGL(layernorm_apply_kernel<true>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, pivots, (double)eps, nullptr);
         } else {
-            hipLaunchKernelGGL(layernorm_stats_kernel<false>, grid, block, 0, stream, xg, len, chunks, kChunk, stats);
-            hipLaunchKernelGGL(layernorm_apply_kernel<false>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, (double)eps);
+            hipLaunchKernelGGL(layernorm_stats_kernel<false>, grid, block, 0, stream, xg, len, chunks, kChunk, stats, pivots);
+            hipLaunchKernelGGL(layernorm_apply_kernel<false>, grid, block, 0, stream, xg, yg, len, chunks, kChunk, stats, pivots, (double)eps, nullptr);
         }
         e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -123,3 +123,27 @@ def test_layernorm_offset_data_constant_rows_and_in_place():
     # many rows: more rows than one 64 MiB group of the long-row path holds
     many = synth.normal(1403, "x", 300, 70000)
     check_ln(many)
+
+
+def test_layernorm_long_rows_do_not_depend_on_the_wait_between_workgroups():
+    """Aligned long rows are normalised in one pass by workgroups that wait for each other's partial sums; a wait that
+    runs out hands the chunk to the second kernel.  With the limit at 0 every workgroup that is not the last of its
+    row gives up, so the second kernel does nearly all the work: same bits, same parity."""
+    cases = [synth.normal(1500, "x", 3, 40000) * np.float32(2.5) + np.float32(1.25), synth.normal(1501, "x", 2, (1 << 20) + 8),
+             synth.normal(1502, "x", 70, 70000)]
+    try:
+        for x in cases:
+            ob.optiml_set_wait_limit(1 << 22)
+            waited = run_ln(x, 1e-5)
+            ob.optiml_set_wait_limit(0)
+            gave_up = run_ln(x, 1e-5)
+            assert np.array_equal(waited, gave_up)
+            check_ln(x)                                 # against the oracle, still with no waiting
+            ob.optiml_set_wait_limit(-5)                # counts as 0
+            assert np.array_equal(run_ln(x, 1e-5, inplace=True), waited)
+        # rows that take two kernels per group (not a multiple of 4 long): in place, x[row][0] is overwritten while
+        # other workgroups still need it as the pivot of the row's sums
+        odd = synth.normal(1503, "x", 3, 100003) + np.float32(3.0)
+        assert np.array_equal(run_ln(odd, 1e-5, inplace=True), run_ln(odd, 1e-5))
+    finally:
+        ob.optiml_set_wait_limit(1 << 22)
