@@ -105,7 +105,7 @@ TRAFFIC = {
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393480.9 * 2.0 + 131206.4) * 1024), "files": RING_F8_SRC, "src": "1b37960b6cd1073e"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((609659.9 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "7ff6f414fc2ebc17"},
+        {"bytes": int((534597.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "6f4eda0d8690b915"},
     ("s_transpose", "s_transpose"):
         {"bytes": int((524327.0 * 2.0 + 1048910.0) * 1024), "files": TRANSPOSE_SRC, "src": "00f7350d0ac9d4a0"},
     ("s_mhsa", "mhsa_pingpong_bf16_dk128"):

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64 * WK) void skinny_rc_dma_kernel(Params p)
 #pragma unroll
         for (int g = 0; g < CG; ++g)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ring::dma_load16(gb, b_off[g][i], d + (g + 1) * BLOCK + i * 1024);
+            for (int i = 0; i < 4; ++i) ring::dma_load16_once(gb, b_off[g][i], d + (g + 1) * BLOCK + i * 1024);   // B: read once
     };
     // LDS side: this lane's reads of a block: chunk 4t + q of row / column c
     int rd[4];

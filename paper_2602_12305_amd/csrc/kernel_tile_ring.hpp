@@ -156,6 +156,16 @@ __device__ __forceinline__ void dma_load16(const char *base, uint32_t off, uint3
                  : "m0");
 }
 
+// The same load with the non-temporal hint: for data that is read once, so that it does not push
+// operands that many workgroups share out of the L2.
+__device__ __forceinline__ void dma_load16_once(const char *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(off), "s"(base), "s"(lds_addr)
+                 : "m0");
+}
+
 template <class C>
 __device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
                                             lds_char *__restrict__ dst)
