@@ -39,12 +39,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2}          # fp32, bf16, fp16, fp8 MFMA (dense)
-DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3"}
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2, 4: 10066.3}          # fp32, bf16, fp16, fp8, fp4 MFMA (dense)
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1"}
 # which roof bounds each contraction workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma",
-         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
+         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
          "c2_f32_skinny16_rc_silu": "hbm"}
 # streaming siblings: (entry point, op, arrays read, arrays written) on 2^28 floats
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
@@ -264,7 +264,8 @@ def main():
             w = self.w = synth.make_workload(name)
             self.name, self.bound, self.dtype = name, BOUND[name], w.dtype
             self.flops, self.nbytes = float(w.flops), float(w.algorithmic_bytes)
-            self.lda, self.ldb = w.A.shape[-1], w.B.shape[-1]
+            pack = 2 if w.dtype == 4 else 1                          # E2M1: two elements a byte
+            self.lda, self.ldb = w.A.shape[-1] * pack, w.B.shape[-1] * pack
             self.sA = w.A.shape[-2] * self.lda if w.batch > 1 else 0
             self.sB = w.B.shape[-2] * self.ldb if w.batch > 1 else 0
             self.sBias = w.N if w.batch > 1 else 0
@@ -307,7 +308,7 @@ def main():
                 sample = f"{len(idx[0])} sampled output entries of {w.batch * w.M * w.N}"
             got = self.sets[self.last][3].cpu().numpy()
             if w.dtype != 0:
-                got = synth.from_bits(got.view(np.uint16), 1 if w.dtype == 3 else w.dtype)      # E4M3 operands: bf16 result
+                got = synth.from_bits(got.view(np.uint16), 1 if w.dtype in (3, 4) else w.dtype)      # E4M3 / E2M1 operands: bf16 result
             got = got.astype(np.float64)
             if idx is not None:
                 got = got[idx]

@@ -36,8 +36,17 @@
  *              infinity).  OPTIML_F8E4M3: A and B are 8-bit OCP E4M3 (1 sign, 4 exponent
  *              bits with bias 7, 3 fraction bits; no infinities, largest finite 448), one
  *              byte per element, decoded exactly; C is bfloat16; no scale factors.
+ *              OPTIML_F4E2M1: A and B are 4-bit OCP E2M1 (1 sign, 2 exponent bits with bias
+ *              1, 1 fraction bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), two
+ *              elements per byte along k, the element with the even k in the low half;
+ *              decoded exactly, no scale factors; C is bfloat16.  K, lda, ldb and the
+ *              operand strides still count ELEMENTS and must be even
+ *              (OPTIML_ERR_INVALID_ARG otherwise), and k must be contiguous in both
+ *              operands: A row-major and B column-major, i.e. OPTIML_LAYOUT_RC, or its
+ *              mirror image with a column-major C; other layouts return
+ *              OPTIML_ERR_UNSUPPORTED.
  *              bias is always float; NULL means no bias.  The
- *              contraction entry points take all four; the other entry points say
+ *              contraction entry points take all five; the other entry points say
  *              which they take.
  *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
  *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
@@ -87,7 +96,7 @@
 extern "C" {
 #endif
 
-typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3 } optiml_dtype_t;
+typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3, OPTIML_F4E2M1 = 4 } optiml_dtype_t;
 
 typedef enum {
     OPTIML_ACT_NONE = 0,
@@ -293,7 +302,7 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
  * The contraction feeding the cross-entropy (the paper's Table 4, task 2 into task 17), fused:
  *     *loss = (1/M) sum_i [ log sum_j exp(z[i][j]) - z[i][labels[i]] ],   z = A.B + bias
  * for M rows (samples) and N classes, with A, B, bias, layouts, leading dimensions and dtype
- * exactly as in optiml_gemm_epilogue_ex (no activation, no batch, not OPTIML_F8E4M3); labels are M 32-bit integers in
+ * exactly as in optiml_gemm_epilogue_ex (no activation, no batch, not OPTIML_F8E4M3 or OPTIML_F4E2M1); labels are M 32-bit integers in
  * [0, N), loss one float; all DEVICE pointers.  The logits are not written anywhere: products
  * are accumulated in fp32, each row's maximum and sum of exponentials are formed in fp32 from
  * the unrounded fp32 logits, the row losses and their mean in fp64 in a fixed order, rounded

@@ -314,9 +314,9 @@ class Workload:
     @property
     def algorithmic_bytes(self):
         """One read of A, B and bias, one write of C."""
-        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1}.get(self.dtype, 2)      # A and B
+        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1, DTYPE_F4E2M1: 0.5}.get(self.dtype, 2)      # A and B
         cs = 4 if self.dtype == DTYPE_F32 else 2                      # C
-        per = (self.M * self.K + self.K * self.N) * es + self.M * self.N * cs + 4 * self.N
+        per = int((self.M * self.K + self.K * self.N) * es) + self.M * self.N * cs + 4 * self.N
         return self.batch * per
 
 
@@ -329,7 +329,7 @@ def _store(x, dtype, transpose=False):
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
 BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu",
-                     "c2_f32_skinny16_rc_silu")     # further dtypes on the same shapes
+                     "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu")     # further dtypes on the same shapes
 
 
 # shape of every workload without its data: (batch, M, N, K, layout, dtype, act)
@@ -343,6 +343,7 @@ SPECS = {
     "c2_bf16_skinny16_silu": (1, 16, 16384, 16384, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
     "c4_f8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E4M3, ACT_SILU),
     "c4_bf16_8192_cr_silu": (1, 8192, 8192, 8192, LAYOUT_CR, DTYPE_BF16, ACT_SILU),
+    "c4_f4_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F4E2M1, ACT_SILU),
     "c2_f32_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F32, ACT_SILU),
 }
 
@@ -397,6 +398,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
                         _store(normal(3, "A", M, K), DTYPE_F8E4M3),
                         _store(normal(3, "B", K, N), DTYPE_F8E4M3, transpose=True),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c4_f4_8192_rc_silu":           # config 4's shape in 4-bit E2M1 operands (bf16 result), k contiguous in both
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_F4E2M1, ACT_SILU, LAYOUT_RC, 3,
+                        _store(normal(3, "A", M, K), DTYPE_F4E2M1),                  # N(0, 1) rounded to 0, 0.5 .. 6
+                        _store(normal(3, "B", K, N), DTYPE_F4E2M1, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 16 else "sampled")
     if name == "c4_bf16_8192_cr_silu":         # config 4 with A stored column-major ([K][M])
         M = N = K = 8192 // s
         return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_CR, 3,

@@ -58,13 +58,14 @@ const Table &table()
 
 bool enum_ok(int layout, int dtype, int act)
 {
-    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_F8 && act >= 0 && act <= 3;
+    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_F4 && act >= 0 && act <= 3;
 }
 
 // OPTIML_OK when the arguments describe a valid problem (possibly an empty one).
 int validate(const Problem &p)
 {
     if (!enum_ok(p.layout, p.dtype, p.act)) return OPTIML_ERR_INVALID_ARG;
+    if (p.pre_status != OPTIML_OK) return p.pre_status;
     if (p.batch < 0 || p.M < 0 || p.N < 0 || p.K < 0) return OPTIML_ERR_INVALID_ARG;
     if (p.strideA < 0 || p.strideB < 0 || p.strideBias < 0 || p.strideC < 0) return OPTIML_ERR_INVALID_ARG;
     if (p.lda < 0 || p.ldb < 0 || p.ldc < 0) return OPTIML_ERR_INVALID_ARG;
@@ -357,6 +358,13 @@ Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int6
         p.B = A; p.ldb = lda; p.strideB = strideA;
         p.layout = ((layout & 1) ? 0 : 2) | ((layout & 2) ? 0 : 1);
         p.bias_row = true;
+    }
+    if (dtype == DT_F4) {
+        // Two E2M1 values to a byte along k: from here on the problem is described in bytes of k.  That needs k
+        // contiguous in both operands and whole bytes in every row.
+        if (K < 0 || (K & 1) || (p.lda & 1) || (p.ldb & 1) || (p.strideA & 1) || (p.strideB & 1)) p.pre_status = OPTIML_ERR_INVALID_ARG;
+        else if (p.layout != 1) p.pre_status = OPTIML_ERR_UNSUPPORTED;
+        p.K = K / 2; p.lda /= 2; p.ldb /= 2; p.strideA /= 2; p.strideB /= 2;
     }
     return p;
 }
@@ -652,7 +660,7 @@ int gemm_cross_entropy(int64_t M, int64_t N, int64_t K, const void *A, int64_t l
                        const float *bias, const int32_t *labels, float *loss, float *row_loss, int layout, int dtype,
                        void *stream)
 {
-    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
+    if (!enum_ok(layout, dtype, 0) || is_8bit(dtype)) return OPTIML_ERR_INVALID_ARG;
     if (M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0) return OPTIML_ERR_INVALID_ARG;
     {
         // operand spans below 2^47 elements, as in validate()
@@ -697,7 +705,7 @@ namespace {
 int gemm_layernorm_problem(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                            const float *bias, void *Y, int64_t ldy, int layout, int dtype, Problem &p)
 {
-    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8) return OPTIML_ERR_INVALID_ARG;
+    if (!enum_ok(layout, dtype, 0) || is_8bit(dtype)) return OPTIML_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0 || lda < 0 || ldb < 0 || ldy < N) return OPTIML_ERR_INVALID_ARG;
     p = Problem{};
     p.batch = 1; p.M = M; p.N = N; p.K = K;
@@ -729,7 +737,7 @@ int optiml_gemm_layernorm_path(int64_t M, int64_t N, int64_t K, const void *A, i
 int optiml_gemm_cross_entropy_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                                    const float *bias, int layout, int dtype)
 {
-    if (!enum_ok(layout, dtype, 0) || dtype == DT_F8 || M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0)
+    if (!enum_ok(layout, dtype, 0) || is_8bit(dtype) || M < 0 || N < 1 || K < 0 || lda < 0 || ldb < 0)
         return OPTIML_ERR_INVALID_ARG;
     Problem p{};
     p.batch = 1; p.M = M; p.N = N; p.K = K;

@@ -6,7 +6,11 @@
 
 namespace optiml {
 
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3 };   // DT_F8: A, B in OCP E4M3, C in bf16
+// DT_F8: A, B in OCP E4M3, C in bf16.  DT_F4: A, B in OCP E2M1, two values to a byte along k (the even k in the
+// low half), C in bf16; inside the library such a problem is described in BYTES of k: K, lda, ldb and the operand
+// strides are halved on entry, an "element" of A or B is a byte holding two values.
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3, DT_F4 = 4 };
+constexpr bool is_8bit(int dt) { return dt == DT_F8 || dt == DT_F4; }   // one byte per stored element of A and B
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
 
 // C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.
@@ -21,9 +25,10 @@ struct Problem {
     // the bias is indexed by the ROW of C instead of the column: how a column-major C is served
     // (C^T = B^T A^T is a row-major problem whose bias runs down the rows)
     bool bias_row = false;
+    int pre_status = 0;     // a status the construction of the problem found (an OPTIML_ERR_* for validate() to return)
     bool a_col() const { return (layout & 2) != 0; }
     bool b_col() const { return (layout & 1) != 0; }
-    int esize() const { return dtype == DT_F32 ? 4 : dtype == DT_F8 ? 1 : 2; }   // bytes per element of A and B
+    int esize() const { return dtype == DT_F32 ? 4 : is_8bit(dtype) ? 1 : 2; }   // bytes per element of A and B
     int csize() const { return dtype == DT_F32 ? 4 : 2; }                        // ... of C
 };
 
@@ -116,7 +121,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
 const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 16;
-const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 16;
+const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 20;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;

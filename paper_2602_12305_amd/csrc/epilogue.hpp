@@ -154,6 +154,14 @@ __device__ __forceinline__ float f8e4m3_to_f32(unsigned char b)
     return (b & 0x80u) ? -v : v;
 }
 
+// OCP 4-bit E2M1 (bias 1, no infinities or NaN): sign, then 0, 0.5, 1, 1.5, 2, 3, 4, 6
+__device__ __forceinline__ float f4e2m1_to_f32(unsigned int code)
+{
+    const unsigned e = (code >> 1) & 3u, f = code & 1u;
+    const float v = e == 0u ? 0.5f * (float)f : __uint_as_float(((e + 126u) << 23) | (f << 22));   // 1.f * 2^(e-1)
+    return (code & 8u) ? -v : v;
+}
+
 // The two 16-bit storage types share every kernel; these pick the conversions and the matrix
 // instruction (same shape, same register layout) by the dtype code.
 template <int DT> __device__ __forceinline__ unsigned int pack2_16(float lo, float hi)
@@ -170,10 +178,19 @@ template <int DT> __device__ __forceinline__ float from_16(unsigned short b)
 }
 template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x16(V4 a, V4 b, ACC c)
 {
-    typedef __bf16 bf16x8_ __attribute__((ext_vector_type(8)));
-    typedef _Float16 halfx8_ __attribute__((ext_vector_type(8)));
+    typedef __bf16 bf16x8_ __attribute__((ext_vector_type(8), unused));
+    typedef _Float16 halfx8_ __attribute__((ext_vector_type(8), unused));
 #if defined(__HIP_DEVICE_COMPILE__)
-    if constexpr (DT == DT_F8) {
+    if constexpr (DT == DT_F4) {
+        // 16 bytes per lane = 32 E2M1 values of k = this lane's half of one 64-deep instruction, with both
+        // block scales at 2^0 (E8M0 127).  Format code 4 = E2M1 for either operand; only the low four
+        // registers of the eight-register operands are read for it.
+        typedef int intx8_ __attribute__((ext_vector_type(8)));
+        typedef int intx4_ __attribute__((ext_vector_type(4)));
+        const intx4_ a4 = __builtin_bit_cast(intx4_, a), b4 = __builtin_bit_cast(intx4_, b);
+        const intx8_ a8 = {a4[0], a4[1], a4[2], a4[3], 0, 0, 0, 0}, b8 = {b4[0], b4[1], b4[2], b4[3], 0, 0, 0, 0};
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+    } else if constexpr (DT == DT_F8) {
         // 16 bytes per lane = 16 E4M3 values of k: two instructions of 8 each.  Which k a lane's
         // byte stands for only has to agree between the two operands, and it does: both come from
         // the same chunk and byte of their rows.

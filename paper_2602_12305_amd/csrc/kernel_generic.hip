@@ -27,12 +27,13 @@ __device__ __forceinline__ void put(float *p, float y) { *p = y; }
 __device__ __forceinline__ void put(unsigned short *p, float y) { *p = f32_to_bf16(y); }
 __device__ __forceinline__ void put(_Float16 *p, float y) { *p = (_Float16)y; }
 
-// E: storage type of A and B, CE: of C (the same, except 8-bit operands with a bf16 result)
-template <typename E, typename CE = E>
+// E: storage type of A and B, CE: of C (the same, except 8-bit operands with a bf16 result).  PACK = 2: every
+// stored byte holds two E2M1 values of consecutive k (the even one in the low half) and p.K counts bytes.
+template <typename E, typename CE = E, int PACK = 1>
 __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_m, int64_t y0)
 {
-    __shared__ float As[GK][PADDED];   // As[k][row]
-    __shared__ float Bs[GK][PADDED];   // Bs[k][col]
+    __shared__ float As[GK * PACK][PADDED];   // As[k][row]
+    __shared__ float Bs[GK * PACK][PADDED];   // Bs[k][col]
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;
     const int64_t by = y0 + blockIdx.y;
@@ -50,20 +51,32 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
             // consecutive threads walk the operand's contiguous storage direction
             const int ar = a_col ? (e & 63) : (e >> 4), ak = a_col ? (e >> 6) : (e & 15);
             const int64_t gr = row0 + ar, gk = k0 + ak;
-            float v = 0.0f;
-            if (gr < p.M && gk < p.K)
-                v = widen<E>(a_col ? A[gk * p.lda + gr] : A[gr * p.lda + gk]);
-            As[ak][ar] = v;
+            if constexpr (PACK == 2) {
+                const unsigned byte = (gr < p.M && gk < p.K) ? (unsigned)(a_col ? A[gk * p.lda + gr] : A[gr * p.lda + gk]) : 0u;
+                As[2 * ak][ar] = f4e2m1_to_f32(byte & 15u);
+                As[2 * ak + 1][ar] = f4e2m1_to_f32(byte >> 4);
+            } else {
+                float v = 0.0f;
+                if (gr < p.M && gk < p.K)
+                    v = widen<E>(a_col ? A[gk * p.lda + gr] : A[gr * p.lda + gk]);
+                As[ak][ar] = v;
+            }
             const int bc = b_col ? (e >> 4) : (e & 63), bk = b_col ? (e & 15) : (e >> 6);
             const int64_t gc = col0 + bc, gkb = k0 + bk;
-            float w = 0.0f;
-            if (gc < p.N && gkb < p.K)
-                w = widen<E>(b_col ? B[gc * p.ldb + gkb] : B[gkb * p.ldb + gc]);
-            Bs[bk][bc] = w;
+            if constexpr (PACK == 2) {
+                const unsigned byte = (gc < p.N && gkb < p.K) ? (unsigned)(b_col ? B[gc * p.ldb + gkb] : B[gkb * p.ldb + gc]) : 0u;
+                Bs[2 * bk][bc] = f4e2m1_to_f32(byte & 15u);
+                Bs[2 * bk + 1][bc] = f4e2m1_to_f32(byte >> 4);
+            } else {
+                float w = 0.0f;
+                if (gc < p.N && gkb < p.K)
+                    w = widen<E>(b_col ? B[gc * p.ldb + gkb] : B[gkb * p.ldb + gc]);
+                Bs[bk][bc] = w;
+            }
         }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < GK; ++k) {
+        for (int k = 0; k < GK * PACK; ++k) {
             float a[4], c[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; c[i] = Bs[k][tx * 4 + i]; }
@@ -111,6 +124,8 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
             hipLaunchKernelGGL(generic_kernel<_Float16>, grid, block, 0, s, p, blocks_m, y0);
         else if (p.dtype == DT_F8)
             hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short>), grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_F4)
+            hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short, 2>), grid, block, 0, s, p, blocks_m, y0);
         else
             hipLaunchKernelGGL(generic_kernel<unsigned short>, grid, block, 0, s, p, blocks_m, y0);
         hipError_t e = hipGetLastError();

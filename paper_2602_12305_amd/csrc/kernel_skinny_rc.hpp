@@ -43,9 +43,9 @@ struct Params {
 };
 
 template <int DT> struct Type {
-    static constexpr int ES = DT == DT_F32 ? 4 : DT == DT_F8 ? 1 : 2;     // bytes per element of A and B
+    static constexpr int ES = DT == DT_F32 ? 4 : is_8bit(DT) ? 1 : 2;     // bytes per element of A and B (E2M1: per pair)
     static constexpr int CS = DT == DT_F32 ? 4 : 2;                       // ... of C
-    static constexpr int ODT = DT == DT_F8 ? DT_BF16 : DT;                // storage type of a 16-bit C
+    static constexpr int ODT = is_8bit(DT) ? DT_BF16 : DT;                // storage type of a 16-bit C
 };
 
 // the multiply-adds of one 16-byte piece of k: a from A's row c, b from B's column c
@@ -57,6 +57,11 @@ __device__ __forceinline__ floatx4 mma16(uintx4 a, uintx4 b, floatx4 acc)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[i]), __uint_as_float(b[i]), acc, 0, 0, 0);
+    } else if constexpr (DT == DT_F4) {
+        // 16 bytes = 32 E2M1 values: this lane's quarter of one 128-deep scaled instruction, both scales 2^0
+        typedef int intx8_ __attribute__((ext_vector_type(8)));
+        const intx8_ a8 = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], 0, 0, 0, 0}, b8 = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], 0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b8, acc, 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
     } else if constexpr (DT == DT_F8) {
         typedef long longx2_ __attribute__((ext_vector_type(2)));
         const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);

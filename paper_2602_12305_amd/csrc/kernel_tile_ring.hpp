@@ -86,11 +86,12 @@ struct Cfg {
     static constexpr int EPI = EPI_;
     // DT_F8: A and B in 8-bit E4M3 (column-major B only), C in bf16.  The tile geometry is in
     // bytes, so a k-tile is 64 elements instead of 32 and each 16-byte fragment feeds two matrix
-    // instructions.
-    static constexpr int ES = DT_ == DT_F8 ? 1 : 2;          // bytes per element of A and B
+    // instructions.  DT_F4: the same with two E2M1 values in every byte (the problem arrives with K
+    // counted in bytes) and one 64-deep scaled matrix instruction per pair of 16-byte fragments.
+    static constexpr int ES = is_8bit(DT_) ? 1 : 2;          // bytes per element of A and B
     static constexpr int BKE = 64 / ES;                      // k elements per tile
-    static constexpr int ODT = DT_ == DT_F8 ? DT_BF16 : DT_; // storage type of C
-    static_assert(DT_ != DT_F8 || B_KC_, "8-bit operands: k must be contiguous in both");
+    static constexpr int ODT = is_8bit(DT_) ? DT_BF16 : DT_; // storage type of C
+    static_assert(!is_8bit(DT_) || B_KC_, "8-bit and 4-bit operands: k must be contiguous in both");
     static constexpr int NS = NS_;
     static constexpr bool B_KC = B_KC_;
     static constexpr bool PF = PF_;      // fetch the next tile's first fragments before the barrier

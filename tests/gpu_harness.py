@@ -11,12 +11,18 @@ from helpers import e1, store
 
 # binary16: one rounding of the output, half a step = 2^-12 .. 2^-11 relative across a binade (4.9e-4 at most),
 # plus fp32 accumulation: bar 1e-3
-TOL = {synth.DTYPE_F32: 1e-5, synth.DTYPE_BF16: 2e-2, synth.DTYPE_F16: 1e-3, synth.DTYPE_F8E4M3: 2e-2}     # E4M3 operands: bf16 result
+TOL = {synth.DTYPE_F32: 1e-5, synth.DTYPE_BF16: 2e-2, synth.DTYPE_F16: 1e-3, synth.DTYPE_F8E4M3: 2e-2,
+       synth.DTYPE_F4E2M1: 2e-2}     # E4M3 and E2M1 operands: bf16 result
 
 
 def c_dtype(dtype):
-    """Storage type of C for a contraction dtype (8-bit operands give a bf16 result)."""
-    return synth.DTYPE_BF16 if dtype == synth.DTYPE_F8E4M3 else dtype
+    """Storage type of C for a contraction dtype (8-bit and 4-bit operands give a bf16 result)."""
+    return synth.DTYPE_BF16 if dtype in (synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1) else dtype
+
+
+def ld_elements(X, dtype):
+    """Leading dimension, in elements, of a storage array (E2M1 arrays hold two elements a byte)."""
+    return X.shape[-1] * (2 if dtype == synth.DTYPE_F4E2M1 else 1)
 POISON = 12345.0
 
 
@@ -52,7 +58,7 @@ def c_values(Cd, dtype, N):
 def run_gpu(As, Bs, bias, batch, M, N, K, dtype, act, layout, *, ldc=None, variant=None,
             strideA=None, strideB=None, strideBias=None, entry="batched"):
     """As/Bs: storage arrays ([batch,] rows, ld).  Returns (Y fp64 [batch,M,N], pad region, device C)."""
-    lda, ldb = As.shape[-1], Bs.shape[-1]
+    lda, ldb = ld_elements(As, dtype), ld_elements(Bs, dtype)
     c_col = bool(layout & 4)                       # column-major C: storage [batch, N, ldc >= M]
     crows, ccols = (N, M) if c_col else (M, N)
     ldc = ccols if ldc is None else ldc

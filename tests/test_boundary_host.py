@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=4), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=5), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])
@@ -300,3 +300,20 @@ def test_fused_layernorm_entry_point_validates_and_picks_its_kernel_on_the_host(
     assert path(A=P + 2) == 1                                   # misaligned operand
     assert path(dtype=0, Y=P + 4) == 1 and path(dtype=0, ldy=770) == 1   # fp32: z is written into Y with 16-byte stores
     assert path(dtype=1, Y=P + 2, ldy=771) == 0                 # 16-bit: z goes to the workspace, Y may sit anywhere
+
+
+def test_e2m1_operands_are_validated_and_dispatched_before_any_gpu_call():
+    """4-bit operands: two elements a byte along k, so K, lda, ldb (in elements) must be even and k contiguous in both."""
+    ERR_INVALID, ERR_UNSUPPORTED = -1, -2
+    assert ob.optiml_status_string(ERR_INVALID) and ob.optiml_status_string(ERR_UNSUPPORTED)
+    assert sel(1, 8192, 8192, 8192, layout=1, dtype=4).startswith("ring_f4_rc_256x256")
+    assert sel(1, 16, 16384, 16384, layout=1, dtype=4).startswith("skinnyrc_f4")
+    assert sel(1, 100, 100, 70, layout=1, dtype=4) == "generic_64x64"                   # 35 bytes of k a row
+    assert sel(1, 512, 512, 512, layout=5, dtype=4) != ERR_UNSUPPORTED                   # column-major C of an RC problem: its mirror image
+    for layout in (0, 2, 3, 4, 6, 7):
+        assert sel(1, 512, 512, 512, layout=layout, dtype=4) == ERR_UNSUPPORTED
+    assert sel(1, 512, 512, 511, layout=1, dtype=4) == ERR_INVALID                       # odd K
+    assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=513) == ERR_INVALID              # odd pitch
+    assert sel(1, 512, 512, 512, layout=1, dtype=4, ldb=515) == ERR_INVALID
+    assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=510) == ERR_INVALID              # pitch shorter than a row
+    assert sel(1, 512, 512, 512, layout=1, dtype=5) == ERR_INVALID                       # no such storage type

@@ -19,8 +19,8 @@ from helpers import e1, store
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16, F16, F8 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3
-DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8}
+F32, BF16, F16, F8, F4 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1
+DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8, "f4": F4}
 ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
 LAYOUT_OF = {"rr": 0, "rc": 1, "cr": 2, "cc": 3}
 
@@ -36,7 +36,8 @@ def all_variants():
 def problem_for(name):
     """(dtype, layout, M, N, K) that a variant accepts: a few tiles, ragged M, a k tail."""
     if name.startswith("skinnyrc"):
-        return DT_OF[name.split("_")[1]], 1, 13, 1000, 1232    # B column-major, K a whole number of 16-byte vectors
+        dt = name.split("_")[1]
+        return DT_OF[dt], 1, 13, 1000, 1248 if dt == "f4" else 1232    # B column-major, K a whole number of 16-byte vectors
     if name.startswith("skinny"):
         return DT_OF[name.split("_")[1]], 0, 13, 1000, 1224
     if name.startswith("ring"):
@@ -46,7 +47,7 @@ def problem_for(name):
             # two whole summation blocks, one partial block, and a tail shorter than the ring
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
-        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, (64 if dt == "f8" else 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
+        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, {"f8": 64, "f4": 128}.get(dt, 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("xk_"):
         return F8, 0, 304, 400, 448                        # 8-bit operands, B row-major: copied with k contiguous
     if name.startswith("xa_"):
@@ -112,7 +113,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
     name = ob.optiml_variant_name(vid)
     dt = name.split("_")[1]
     dtype, layout = DT_OF[dt], LAYOUT_OF[name.split("_")[2]]
-    tile, chunk = {"f8": (64, 16), "f32": (16, 4)}.get(dt, (32, 8))
+    tile, chunk = {"f8": (64, 16), "f4": (128, 32), "f32": (16, 4)}.get(dt, (32, 8))
     if name.startswith("direct_"):
         tile = 64                                                       # their k-tile: 1 .. 7 chunks beyond it
     extras = (1, 2, 3) if not name.startswith("direct_") else (1, 4, 7)
@@ -123,7 +124,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
         check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, exact=True)
     A = synth.normal(1610, "A", 300, tile * 7 + chunk, batch=2); B = synth.normal(1610, "B", tile * 7 + chunk, 392, batch=2)
     bias = synth.normal(1610, "bias", 1, 392, batch=2).reshape(2, 392)
-    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad={"f8": 16, "f32": 4}.get(dt, 8))
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad={"f8": 16, "f4": 32, "f32": 4}.get(dt, 8))
 
 
 # ---- L1: persistent kernels: more C tiles than CUs, so workgroups walk several tiles ----------
