@@ -62,7 +62,8 @@
  *   Results    Repeating a call with the same arguments gives bitwise the same C
  *              (no floating-point atomics; split-K partial sums are combined in a
  *              fixed order).
- *   Workspace  Split-K kernels keep partial sums, and the fast paths for a column-major
+ *   Workspace  Split-K kernels (the streaming kernels for few rows, and the split of a tiled
+ *              contraction's nearly empty last round of tiles) keep partial sums, and the fast paths for a column-major
  *              A, for 8-bit operands whose k is not contiguous and for unaligned or
  *              odd-sized problems keep copies of operands (batch x M x K, batch x N x K
  *              elements; the last also a temporary C), in one per-device buffer.

@@ -47,6 +47,7 @@ struct Table {
         for (int i = 0; i < kNumTileVariants; ++i) v.push_back(&tile_variants()[i]);
         for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);
         for (int i = 0; i < kNumPadVariants; ++i) v.push_back(&pad_variants()[i]);
+        for (int i = 0; i < kNumTailVariants; ++i) v.push_back(&tail_variants()[i]);
     }
 };
 

@@ -95,6 +95,10 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
                                 hipStream_t stream);
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
 void set_wait_limit(long long clocks);
+// kernel_linear_ln.hip: unrounded fp32 products of p.batch 16-bit problems by the ring kernel (used to split a
+// contraction along k); `pairs` needs 2 * 4 * ceil(N / 256) * M floats per batch
+bool unrounded_products_supported(const Problem &p);
+hipError_t launch_unrounded_products(const Problem &p, float *Z, int64_t ldz, float *pairs, hipStream_t stream);
 
 // attention (kernel_attention.hip): which kernel would serve (0 flash, 1 fallback, -1 none), launch
 int mhsa_path(int64_t d_model, int64_t heads, int dtype, const void *Q, const void *K, const void *V, const void *O);
@@ -126,6 +130,7 @@ const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;
 const Variant *pad_variants();             extern const int kNumPadVariants;      // kernel_pad.hip
+const Variant *tail_variants();            constexpr int kNumTailVariants = 1;    // kernel_tail.hip
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
 constexpr int kRingPerUnit = 5;            // ring-of-stages 16-bit kernels per B layout (three one-tile, one persistent, one 128 x 256)

@@ -139,15 +139,20 @@ hipError_t launch_ring_ln(const Problem &p, float *Z, int64_t ldz, float *pairs,
     q.B = static_cast<const char *>(p.B); q.ldb = p.ldb; q.strideB = 0;
     q.bias = p.bias; q.strideBias = 0;
     q.C = reinterpret_cast<char *>(Z); q.ldc = ldz; q.strideC = 0;
+    if constexpr (!std::is_same<C, LnCfgF32Rr>::value && !std::is_same<C, LnCfgF32Rc>::value) {
+        // the 16-bit kernels also take batches (Z slabs p.strideC floats apart): how the k-split partial
+        // products of launch_unrounded_products are formed
+        q.batch = p.batch; q.strideA = p.strideA; q.strideB = p.strideB; q.strideBias = p.strideBias; q.strideC = p.strideC;
+    }
     q.tiles_m = (p.M + C::BM - 1) / C::BM;
     q.tiles_n = (p.N + C::BN - 1) / C::BN;
     q.act = ACT_NONE;
     q.labels = nullptr; q.picked = pairs; q.bias_row = 0;
-    if (q.tiles_m * q.tiles_n > 0x7fffffffLL) return hipErrorInvalidValue;     // the grid is 32-bit
+    if (q.tiles_m * q.tiles_n * q.batch > 0x7fffffffLL) return hipErrorInvalidValue;     // the grid is 32-bit
     if constexpr (std::is_same<C, LnCfgF32Rr>::value || std::is_same<C, LnCfgF32Rc>::value) {
         hipLaunchKernelGGL(ringf::gemm_ring_f32_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
     } else {
-        hipLaunchKernelGGL(ring::gemm_ring_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n)), dim3(C::THREADS), 0, stream, q);
+        hipLaunchKernelGGL(ring::gemm_ring_kernel<C>, dim3((unsigned)(q.tiles_m * q.tiles_n * q.batch)), dim3(C::THREADS), 0, stream, q);
     }
     return hipGetLastError();
 }
@@ -162,6 +167,26 @@ bool ring_takes_ln(const Problem &p)
 size_t align256_ln(size_t x) { return (x + 255) & ~size_t(255); }
 
 }  // namespace
+
+// The unrounded fp32 products A.B (+ bias) of p.batch problems of 16-bit operands, A row-major, that the ring kernel
+// takes: slab b of Z (pitch ldz, p.strideC floats apart) = A_b . B_b.  `pairs` receives the row statistics the kernel
+// also forms, 2 * 4 * ceil(N / 256) * M floats per batch; a caller that splits a contraction along k ignores them.
+bool unrounded_products_supported(const Problem &p)
+{
+    Problem q = p;
+    q.batch = 1; q.strideA = q.strideB = q.strideBias = q.strideC = 0;
+    q.C = const_cast<void *>(p.A); q.ldc = 0;
+    return (p.dtype == DT_BF16 || p.dtype == DT_F16) && p.K > 0 && !p.a_col() && ring_takes_ln(q);
+}
+
+hipError_t launch_unrounded_products(const Problem &p, float *Z, int64_t ldz, float *pairs, hipStream_t stream)
+{
+    if (p.dtype == DT_BF16)
+        return p.b_col() ? launch_ring_ln<LnCfg<DT_BF16, true>>(p, Z, ldz, pairs, stream)
+                         : launch_ring_ln<LnCfg<DT_BF16, false>>(p, Z, ldz, pairs, stream);
+    return p.b_col() ? launch_ring_ln<LnCfg<DT_F16, true>>(p, Z, ldz, pairs, stream)
+                     : launch_ring_ln<LnCfg<DT_F16, false>>(p, Z, ldz, pairs, stream);
+}
 
 // 0: a ring kernel with the statistics epilogue, 1: row-per-workgroup fallback.  p.C / p.ldc are Y.
 int linear_ln_path(const Problem &p)

@@ -521,8 +521,9 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
         return;
     }
     if constexpr (C::EPI == 2) {
-        float *Z = reinterpret_cast<float *>(p.C);
-        ring::floatx2 *pairs = reinterpret_cast<ring::floatx2 *>(p.picked);
+        // batches: Z slabs strideC floats apart, each batch its own tiles_n * WN slices of pairs
+        float *Z = reinterpret_cast<float *>(p.C) + batch * p.strideC;
+        ring::floatx2 *pairs = reinterpret_cast<ring::floatx2 *>(p.picked) + batch * (p.tiles_n * C::WN) * p.M;
         const int64_t slice = tile_n * C::WN + wn;
         const int64_t left = p.N - nw;                                   // columns of this slice inside the matrix
         const float count = (float)(left >= C::WTN ? C::WTN : left > 0 ? left : 0);

@@ -30,7 +30,9 @@ def variant_ids(prefix):
 
 
 def all_variants():
-    return list(enumerate(ob.variant_names()))
+    # every variant but the one that splits the last round of a problem with more tiles than CUs along k: too large
+    # for a whole-output comparison, it has tests of its own on sampled entries
+    return [(i, n) for i, n in enumerate(ob.variant_names()) if n != "xtail_split"]
 
 
 def problem_for(name):
