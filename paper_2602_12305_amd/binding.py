@@ -49,6 +49,8 @@ SIGNATURES = {
     "optiml_set_workspace": (_int, [_vp, _i64]),
     "optiml_workspace_bytes": (_i64, []),
     "optiml_set_wait_limit": (None, [_i64]),
+    "optiml_gemm_epilogue_mx": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int, _int, _vp]),
+    "optiml_gemm_epilogue_mx_path": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _int]),
     "optiml_status_string": (C.c_char_p, [_int]),
     "optiml_last_hip_error": (_int, []),
 }
@@ -236,6 +238,17 @@ def optiml_set_workspace(ptr, nbytes):
 
 def optiml_workspace_bytes():
     return lib().optiml_workspace_bytes()
+
+
+def optiml_gemm_epilogue_mx(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc, dtype=4, act=0, stream=None):
+    """Block-scaled E2M1 contraction (A [M][K], B [N][K], one E8M0 scale per 32 elements of k), bf16 result."""
+    return _check(lib().optiml_gemm_epilogue_mx(M, N, K, _addr(A), lda, _addr(scaleA), lds_a, _addr(B), ldb, _addr(scaleB), lds_b,
+                                                _addr(bias), _addr(C), ldc, dtype, act, _stream(stream)))
+
+
+def optiml_gemm_epilogue_mx_path(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc, dtype=4):
+    return lib().optiml_gemm_epilogue_mx_path(M, N, K, _addr(A), lda, _addr(scaleA), lds_a, _addr(B), ldb, _addr(scaleB), lds_b,
+                                              _addr(bias), _addr(C), ldc, dtype)
 
 
 def optiml_set_wait_limit(clocks):

@@ -57,11 +57,21 @@ struct Params {
     const int *labels;
     float *picked;
     int bias_row;        // EPI == 0: bias[m] instead of bias[n]
+    // block-scaled operands (Cfg::MX): one E8M0 byte per row of A (column of B) and 32 elements of k,
+    // scaleA[i * lds_a + k / 32], scaleB[j * lds_b + k / 32]
+    const char *scaleA = nullptr, *scaleB = nullptr;
+    int64_t lds_a = 0, lds_b = 0;
 };
 
 template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0, bool K64_ = false, int BAND_ = 8,
-          int SWZ_ = 4, int WM_ = 2>
+          int SWZ_ = 4, int WM_ = 2, bool MX_ = false>
 struct Cfg {
+    // Block-scaled E2M1 operands: every 32 consecutive k of a row of A (column of B) share an E8M0 scale.  A lane's
+    // 16-byte fragment is exactly one such block, and the matrix instruction takes the block's scale from a byte of a
+    // register of that lane.  The scales of a k-tile (four blocks = one dword per row) travel with the tile: one more
+    // LDS-DMA load per wave and stage (4 bytes a lane) into 2 KiB behind the B tile.
+    static constexpr bool MX = MX_;
+    static_assert(!MX_ || (DT_ == DT_F4 && B_KC_ && !PF_ && !K64_ && EPI_ == 0 && WM_ == 2 && WN_ == 4), "block scales: the plain 2 x 4 E2M1 kernel");
     // WM = 1: a 128 x 256 block computed by four waves (1 x 4, the same 128 x 64 wave tile) with 24 KiB
     // stages; with NS = 3 two such workgroups share a CU (144 KiB of LDS, at most 256 registers a lane),
     // so that one's first loads and epilogue run under the other's k loop: for many short tiles.
@@ -98,9 +108,11 @@ struct Cfg {
     static constexpr int AHEAD = PF_ ? NS_ - 3 : NS_ - 2;   // stages allowed in flight at the barrier
     static constexpr int BM = 128 * WM_, BN = 256, BK = 32, WM = WM_, WN = WN_, NW = WM * WN, THREADS = 64 * NW;
     static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
-    static constexpr int A_BYTES = BM * 64, B_BYTES = BN * 64, STAGE_BYTES = A_BYTES + B_BYTES;   // 32 KiB
+    static constexpr int A_BYTES = BM * 64, B_BYTES = BN * 64;
+    static constexpr int SCALE_BYTES = MX_ ? (BM + BN) * 4 : 0;                                   // a dword per row and column
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SCALE_BYTES;                           // 32 KiB (34 with scales)
     static constexpr int A_INSTR = A_BYTES / 1024 / NW, B_INSTR = B_BYTES / 1024 / NW;
-    static constexpr int LOADS = A_INSTR + B_INSTR;                                               // per wave per stage
+    static constexpr int LOADS = A_INSTR + B_INSTR + (MX_ ? 1 : 0);                               // per wave per stage
     static_assert(NS >= 3 && NS <= 5 && (!PF_ || NS_ >= 4), "ring depth");
     static_assert((WN == 2 || WN == 4) && (WM_ == 2 || (WM_ == 1 && WN_ == 4)), "2 x 2, 2 x 4 or 1 x 4 waves");
 };
@@ -142,6 +154,8 @@ struct Ctx {
     uint32_t a_off[C::A_INSTR], b_off[C::B_INSTR];
     int a_frag[2], tr_cb[C::TN];
     int wave, a_wave, b_wave_kc, tr_row;
+    uint32_t s_off;              // MX: this lane's row (waves 0-3: of A, 4-7: of B) times the pitch of the scales
+    int sa_frag, sb_frag;        // MX: LDS offsets of this lane's first scale dwords within the stage
 };
 
 // One wave-wide LDS-DMA load: lane l copies 16 bytes from base + off(l) to LDS byte lds_addr + 16 l.
@@ -167,9 +181,19 @@ __device__ __forceinline__ void dma_load16_once(const char *base, uint32_t off, 
                  : "m0");
 }
 
+// ... and with 4 bytes a lane: lane l copies base + off(l) .. +3 to LDS byte lds_addr + 4 l
+__device__ __forceinline__ void dma_load4(const char *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(off), "s"(base), "s"(lds_addr)
+                 : "m0");
+}
+
+// gs (MX only): the scales of this wave's operand (A for waves 0-3, B for 4-7) at the tile's first block of k
 template <class C>
 __device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
-                                            lds_char *__restrict__ dst)
+                                            lds_char *__restrict__ dst, const char *__restrict__ gs = nullptr)
 {
     ga = scalar_ptr(ga);
     gb = scalar_ptr(gb);
@@ -178,6 +202,11 @@ __device__ __forceinline__ void issue_stage(const Ctx<C> &c, const char *__restr
     for (int i = 0; i < C::A_INSTR; ++i) dma_load16(ga, c.a_off[i], d + i * C::NW * 1024);
 #pragma unroll
     for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
+    if constexpr (C::MX) {
+        // wave w fills dwords 64 w .. 64 w + 63 of the scale area: rows 0-255 of A, then columns 0-255 of B
+        const uint32_t ds = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dst) + C::A_BYTES + C::B_BYTES + c.wave * 256);
+        dma_load4(scalar_ptr(gs), c.s_off, ds);
+    }
 }
 
 template <class C>
@@ -232,7 +261,7 @@ template <class C, int EXTRA = 0>
 __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
                                           lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
                                           const lds_char *__restrict__ nxt, Frags<C> &f0,
-                                          floatx16 (&acc)[C::TN][C::TM])
+                                          floatx16 (&acc)[C::TN][C::TM], const char *__restrict__ gs = nullptr)
 {
     static_assert(C::AHEAD * C::LOADS + EXTRA <= 63, "vmcnt is a 6-bit counter");
     wait_vmcnt<C::AHEAD * C::LOADS + EXTRA>();
@@ -267,12 +296,45 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
         }
         return;
     }
-    issue_stage<C>(c, ga, gb, dma);
+    issue_stage<C>(c, ga, gb, dma, gs);
     __builtin_amdgcn_sched_barrier(0);      // the loads go out before the tile is multiplied
     {
         load_frags<C>(c, rd, 0, f0);
         load_frags<C>(c, rd, 1, f1);
-        if constexpr (C::K64) {
+        if constexpr (C::MX) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            // This lane's fragment of k-step s is block 2 s + half of the tile: byte 2 s + half of its row's scale
+            // dword, shifted down to byte 0 (the byte the instruction reads with a zero selector).  The
+            // instruction's first operand is the B fragment (the tile is computed transposed), so its scale is the
+            // column's.
+            typedef int intx8_ __attribute__((ext_vector_type(8)));
+            const int shift = (threadIdx.x & 32) ? 8 : 0;
+            unsigned int sa[C::TM], sb[C::TN];
+#pragma unroll
+            for (int i = 0; i < C::TM; ++i)
+                sa[i] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sa_frag + i * 128) >> shift;
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+                sb[j] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sb_frag + j * 128) >> shift;
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i) {
+                    const intx8_ b0 = {(int)f0.b[j][0], (int)f0.b[j][1], (int)f0.b[j][2], (int)f0.b[j][3], 0, 0, 0, 0};
+                    const intx8_ a0 = {(int)f0.a[i][0], (int)f0.a[i][1], (int)f0.a[i][2], (int)f0.a[i][3], 0, 0, 0, 0};
+                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a0, acc[j][i], 4, 4, 0, (int)sb[j], 0, (int)sa[i]);
+                }
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i) {
+                    const intx8_ b1 = {(int)f1.b[j][0], (int)f1.b[j][1], (int)f1.b[j][2], (int)f1.b[j][3], 0, 0, 0, 0};
+                    const intx8_ a1 = {(int)f1.a[i][0], (int)f1.a[i][1], (int)f1.a[i][2], (int)f1.a[i][3], 0, 0, 0, 0};
+                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a1, acc[j][i], 4, 4, 0, (int)(sb[j] >> 16), 0,
+                                                                                (int)(sa[i] >> 16));
+                }
+#endif
+        } else if constexpr (C::K64) {
             // both 16-byte fragments of a row are one 32-byte operand: 64 values of k (which value
             // sits in which byte only has to agree between the two operands)
 #pragma unroll
@@ -381,10 +443,25 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
     const int64_t nk = p.K / C::BKE, last = nk - 1;        // nk >= NS - 1
     auto ga = [&](int64_t kt) { return A + (kt < last ? kt : last) * 64; };
     auto gb = [&](int64_t kt) { return B + (kt < last ? kt : last) * b_step; };
+    // block scales: waves 0-3 fetch those of the tile's 256 rows of A, waves 4-7 those of its 256 columns of B
+    // (rows and columns past the end re-read the last valid one), four bytes = four blocks of k per k-tile
+    const char *S = nullptr;
+    ctx.s_off = 0; ctx.sa_frag = 0; ctx.sb_frag = 0;
+    if constexpr (C::MX) {
+        const bool of_a = wave < 4;
+        int64_t row = (of_a ? m0 : n0) + 64 * (wave & 3) + lane;
+        const int64_t limit = of_a ? p.M : p.N;
+        row = row < limit ? row : limit - 1;
+        ctx.s_off = (uint32_t)(row * (of_a ? p.lds_a : p.lds_b));
+        S = of_a ? p.scaleA : p.scaleB;                         // one problem per call
+        ctx.sa_frag = C::A_BYTES + C::B_BYTES + (wm * C::WTM + frag_row) * 4;
+        ctx.sb_frag = C::A_BYTES + C::B_BYTES + C::BM * 4 + (wn * C::WTN + frag_row) * 4;
+    }
+    auto gs = [&](int64_t kt) { return C::MX ? S + (kt < last ? kt : last) * 4 : nullptr; };
 
     // prologue: tiles 0 .. NS-2
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue_stage<C>(ctx, ga(s), gb(s), stage[s]);
+    for (int s = 0; s < NS - 1; ++s) issue_stage<C>(ctx, ga(s), gb(s), stage[s], gs(s));
     Frags<C> f0;
     if constexpr (C::PF) {
         wait_vmcnt<(NS - 2) * C::LOADS>();   // tile 0 has landed
@@ -397,14 +474,14 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
 #pragma unroll
         for (int s = 0; s < NS; ++s)
             ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
-                         stage[(s + 1) % NS], f0, acc);
+                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1));
     }
     // the last nk % NS tiles, same stage order
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (kt + s < nk)
             ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
-                         stage[(s + 1) % NS], f0, acc);
+                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1));
     wait_vmcnt<0>();
     __syncthreads();                         // every load has landed, every wave is done with the stages
 

@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(ob.LIB_PATH)
     names = declared_symbols()
-    assert len(names) == 28
+    assert len(names) == 30
     for n in names:
         assert hasattr(L, n), n
     assert sorted(ob.SIGNATURES) == names
@@ -317,3 +317,21 @@ def test_e2m1_operands_are_validated_and_dispatched_before_any_gpu_call():
     assert sel(1, 512, 512, 512, layout=1, dtype=4, ldb=515) == ERR_INVALID
     assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=510) == ERR_INVALID              # pitch shorter than a row
     assert sel(1, 512, 512, 512, layout=1, dtype=5) == ERR_INVALID                       # no such storage type
+
+
+def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
+    L = ob.lib()
+    def call(M=512, N=512, K=512, A=P, lda=None, sA=P, lds_a=None, B=P, ldb=None, sB=P, lds_b=None, bias=P, C=P, ldc=None, dtype=4, act=0):
+        lda = K if lda is None else lda; ldb = K if ldb is None else ldb; ldc = N if ldc is None else ldc
+        lds_a = K // 32 if lds_a is None else lds_a; lds_b = K // 32 if lds_b is None else lds_b
+        return (L.optiml_gemm_epilogue_mx(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype, act, None),
+                L.optiml_gemm_epilogue_mx_path(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype))
+    for kw in (dict(M=-1), dict(K=-32), dict(K=48), dict(lda=510), dict(lda=513), dict(ldb=511), dict(lds_a=15), dict(lds_b=3), dict(ldc=511),
+               dict(dtype=3), dict(dtype=1), dict(A=None), dict(B=None), dict(sA=None), dict(sB=None), dict(C=None)):
+        assert call(**kw)[1] == ob.ERR_INVALID_ARG, kw
+    assert call(act=7)[0] == ob.ERR_INVALID_ARG
+    assert call(M=0, A=None, C=None)[0] == ob.OK and call(N=0)[0] == ob.OK                # nothing to do
+    assert call()[1] == 0 and call(M=4096, N=4096, K=4096)[1] == 0                        # the matrix-pipe tile kernel
+    assert call(K=480)[1] == 1 and call(M=100, N=100)[1] == 1                             # K not whole k-tiles; a small C
+    assert call(A=P + 2)[1] == 1 and call(sA=P + 1)[1] == 1 and call(lds_a=18)[1] == 1    # addresses or pitches the wide loads cannot take
+    assert call(lda=514)[1] == 1

@@ -645,18 +645,20 @@ def test_column_major_b_streaming_variants(vid):
     """B stored [N][K]: blocks of 16 rows (the last ragged) times batches, a grid split of k through the workspace,
     a ragged last step of k, few columns, padded leading dimensions; integers exactly."""
     dtype = DT_OF[ob.optiml_variant_name(vid).split("_")[1]]
-    batch, M, N, K = 2, 45, 264, 4240                              # long k, few columns: grid split
+    kx = 2 if dtype == F4 else 1                                   # E2M1: two elements a byte, the same bytes of k
+    batch, M, N, K = 2, 45, 264, 4240 * kx                         # long k, few columns: grid split
     A = synth.normal(1500 + vid, "A", M, K, batch=batch); B = synth.normal(1500 + vid, "B", K, N, batch=batch)
     bias = synth.normal(1500 + vid, "bias", 1, N, batch=batch).reshape(batch, N)
     check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=1, variant=vid, ldc_pad=8)
     Ai = synth.integers(1510 + vid, "A", M, K, batch=batch); Bi = synth.integers(1510 + vid, "B", K, N, batch=batch)
     check_against_oracle(Ai, Bi, None, dtype=dtype, act=synth.ACT_RELU, layout=1, variant=vid, exact=True)
     for (M, N, K) in ((16, 4104, 512), (5, 37, 48), (1, 1, 16), (16, 64, 272)):   # no split; tiny; one vector; ragged step only
+        K *= kx
         A = synth.uniform(1520 + vid, "A", M, K); B = synth.uniform(1520 + vid, "B", K, N)
         check_against_oracle(A, B, synth.uniform(1520 + vid, "bias", 1, N)[0], dtype=dtype, act=synth.ACT_SILU, layout=1,
-                             variant=vid, pad=16, ldc_pad=(-N) % 8)        # rows of C stay 16-byte aligned
+                             variant=vid, pad=16 * kx, ldc_pad=(-N) % 8)        # rows of C stay 16-byte aligned
     # one-hot rows of A pick single k positions: a piece of a vector in the wrong k slot cannot hide
-    M, N, K = 16, 128, 1024
+    M, N, K = 16, 128, 1024 * kx
     A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (61 * np.arange(M) + 7) % K] = 2.0
     check_against_oracle(A1, synth.integers(1530, "B", K, N, -8, 8), None, dtype=dtype, act=synth.ACT_NONE, layout=1,
                          variant=vid, exact=True)
