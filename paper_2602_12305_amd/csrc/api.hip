@@ -176,7 +176,10 @@ double tile_estimate_us(const Variant *v, const Cost &c, const Problem &p)
     // the direct kernels fetch 128-byte row segments: with a row pitch that is not a multiple of 128 bytes each
     // straddles two cache lines (3000^3 bf16: 101 us where the estimate without this says 64)
     if (v->family == FAM_DIRECT && ((p.lda * 2) % 128 != 0 || (p.ldb * 2) % 128 != 0)) rate *= 0.65;
-    if ((v->family == FAM_RING16 || v->family == FAM_RING8) && v->bm == 128 && p.K >= 1024) rate *= 0.93;
+    // (the 16-bit kernel with B column-major loses more: 8448^2 x 4096 594 against 522 us for the 256 x 256 kernel, where B
+    // row-major gives 522 against 507)
+    if ((v->family == FAM_RING16 || v->family == FAM_RING8) && v->bm == 128 && p.K >= 1024)
+        rate *= v->family == FAM_RING16 && p.b_col() ? 0.76 : 0.93;
     const double tile_us = c.fixed_us + 2.0 * v->bm * v->bn * (double)p.K / (rate * 1e6);
     if (c.share == 1.0f) return tile_us * (double)(int64_t)((tiles + kCUs - 1.0) / kCUs);
     const double n = tiles / kCUs;                                             // workgroups per CU

@@ -38,6 +38,10 @@ SETS = {
     # odd sizes and pitches: nothing but the copy path (xpad) and the fallback takes these
     "odd": [(dt, lay, 1) + s for dt in (1, 0) for lay in (0, 1, 3)
             for s in ((1025, 1031, 2051), (4097, 4097, 4097), (301, 395, 203), (17, 4099, 4099), (513, 515, 517))],
+    # tile counts a little over a multiple of the CU count (and one well over): the last round of tiles
+    "rounds": [(dt, lay, 1) + s for dt, lay in ((1, 0), (1, 1), (2, 0))
+               for s in ((4352, 4352, 4352), (4352, 4352, 8192), (4104, 4104, 4104), (4352, 4096, 4096), (4608, 4352, 4096),
+                         (8448, 8448, 4096), (4352, 4352, 2048))],
     "quick": [(1, 1, 1, 64, 4096, 4096), (0, 1, 1, 64, 4096, 4096), (1, 2, 1, 64, 4096, 4096), (0, 0, 1, 8, 4096, 4096),
               (1, 0, 1, 2048, 2048, 2048), (0, 0, 1, 4096, 512, 4096)],
 }
