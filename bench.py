@@ -44,7 +44,7 @@ DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1"}
 # which roof bounds each contraction workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma",
-         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
+         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_4352_tail_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
          "c2_f32_skinny16_rc_silu": "hbm"}
 # streaming siblings: (entry point, op, arrays read, arrays written) on 2^28 floats
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
@@ -80,42 +80,65 @@ TRANSPOSE_SRC = ("kernel_transpose.hip",)
 SKINNY_RC_SRC = ("kernel_skinny_rc.hpp", "kernel_skinny_rc.hip", "epilogue.hpp")
 RING_F8_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f8_rc.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
+RING_F4_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f4_rc.hip", "epilogue.hpp")
+XA_SRC = ("kernel_transpose.hip",) + RING_SRC
+GLN_SRC = ("kernel_linear_ln.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
+GLN_F32_SRC = ("kernel_linear_ln.hip", "kernel_ring_f32.hpp", "kernel_tile_ring.hpp", "epilogue.hpp")
+MX_SRC = ("kernel_mx.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
+    ("c1_f32_256_relu", "skinny_f32_wn1_wk4_cg2_nt0_split0"):
+        {"bytes": int((856.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "e3a49e46dc8bad6e"},
     ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
-        {"bytes": int((529551.0 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "d4ff8d1267cf9162"},
+        {"bytes": int((529548.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "e3a49e46dc8bad6e"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((385145.3 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "3d144bf02577476c"},
+        {"bytes": int((385170.1 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "bc649ac3034b36b7"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((806644.5 * 2.0 + 131072.1) * 1024), "files": RING_SRC, "src": "7a5f3f964118548f"},
+        {"bytes": int((797183.1 * 2.0 + 131086.6) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((813173.6 * 2.0 + 131072.0) * 1024), "files": RING_SRC, "src": "7a5f3f964118548f"},
-    ("c5_bf16_batched32_relu", "ringp_bf16_rr_256x256_w2x4_ns4"):
-        {"bytes": int((69975.3 * 2.0 + 266658.2) * 1024), "files": RINGP_SRC, "src": "b23f7957bb0ba2b5"},
+        {"bytes": int((799517.1 * 2.0 + 131073.2) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
+    ("c5_bf16_batched32_relu", "ring_bf16_rr_128x256_w1x4_ns3"):
+        {"bytes": int((65925.1 * 2.0 + 262163.2) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
-        {"bytes": int((266407.9 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "52329cc04db85d01"},
-    ("s_sigmoid", "s_sigmoid"):
-        {"bytes": int((524327.4 * 2.0 + 1048576.7) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
-    ("s_dot", "s_dot"):
-        {"bytes": int((1048631.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "e21a390bc9b59339"},
-    ("s_ce", "s_ce"):
-        {"bytes": int((524988.0 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
-    ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((527793.0 * 2.0 + 1053600.0) * 1024), "files": ROWS_SRC, "src": "c83f66083110762a"},
-    ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524321.3 * 2.0 + 1048587.4) * 1024), "files": ROWS_SRC, "src": "cf001e03e5c57dd6"},
+        {"bytes": int((266405.5 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "5f550a775ce04ec2"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393480.9 * 2.0 + 131206.4) * 1024), "files": RING_F8_SRC, "src": "1b37960b6cd1073e"},
+        {"bytes": int((393471.6 * 2.0 + 131087.7) * 1024), "files": RING_F8_SRC, "src": "594ff026bec2b866"},
+    ("c4_f4_8192_rc_silu", "ring_f4_rc_256x256_w2x4_ns5_pf"):
+        {"bytes": int((196876.3 * 2.0 + 131193.5) * 1024), "files": RING_F4_SRC, "src": "ca0c60068aaee75e"},
+    ("c4_bf16_8192_cr_silu", "xa_ring"):
+        {"bytes": int((862588.7 * 2.0 + 262249.1) * 1024), "files": XA_SRC, "src": "1f3589c2d44153ad"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((534597.0 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "6f4eda0d8690b915"},
+        {"bytes": int((534591.1 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "51a88e44a2dc274c"},
+    ("s_relu", "s_relu"):
+        {"bytes": int((524309.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+    ("s_sigmoid", "s_sigmoid"):
+        {"bytes": int((524325.0 * 2.0 + 1048576.8) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+    ("s_sum", "s_sum"):
+        {"bytes": int((524397.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+    ("s_dot", "s_dot"):
+        {"bytes": int((1048623.7 * 2.0 + 128.4) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+    ("s_mse", "s_mse"):
+        {"bytes": int((1048626.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
     ("s_transpose", "s_transpose"):
-        {"bytes": int((524327.0 * 2.0 + 1048910.0) * 1024), "files": TRANSPOSE_SRC, "src": "00f7350d0ac9d4a0"},
+        {"bytes": int((524319.6 * 2.0 + 1048869.8) * 1024), "files": TRANSPOSE_SRC, "src": "fed67c2f38f8f735"},
+    ("s_ce", "s_ce"):
+        {"bytes": int((524976.0 * 2.0 + 64.2) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
+    ("s_ln_sample", "s_ln_sample"):
+        {"bytes": int((527803.6 * 2.0 + 1053812.6) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
+    ("s_ln_token", "s_ln_token"):
+        {"bytes": int((524319.5 * 2.0 + 1048590.7) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
     ("s_mhsa", "mhsa_pingpong_bf16_dk128"):
-        {"bytes": int((98401.8 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "a4876881c0272702"},
+        {"bytes": int((98427.0 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "49041109d0e68a34"},
     ("s_lce", "ring_bf16_rr_lse"):
-        {"bytes": int((1590396.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "6afe4dac2e72a9c6"},
+        {"bytes": int((1590398.4 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "b9562500d67cc396"},
     ("s_lce_f32", "ring_f32_rr_lse"):
-        {"bytes": int((1583509.3 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "b2d898c0c56d34de"},
+        {"bytes": int((1583708.5 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "42fcb04da4dd9fa6"},
+    ("s_gln", "ring_bf16_rr_ln"):
+        {"bytes": int((541155.5 * 2.0 + 401408.8) * 1024), "files": GLN_SRC, "src": "439417ce7d7660e4"},
+    ("s_gln_f32", "ring_f32_rr_ln"):
+        {"bytes": int((427086.4 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "beec9390eec9dce1"},
+    ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4"):
+        {"bytes": int((209165.7 * 2.0 + 131249.1) * 1024), "files": MX_SRC, "src": "804c9bc72f21a026"},
 }
 
 

@@ -329,7 +329,7 @@ def _store(x, dtype, transpose=False):
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
 BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu",
-                     "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu")     # further dtypes on the same shapes
+                     "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu", "c4_bf16_4352_tail_silu")     # further dtypes and shapes
 
 
 # shape of every workload without its data: (batch, M, N, K, layout, dtype, act)
@@ -344,6 +344,7 @@ SPECS = {
     "c4_f8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E4M3, ACT_SILU),
     "c4_bf16_8192_cr_silu": (1, 8192, 8192, 8192, LAYOUT_CR, DTYPE_BF16, ACT_SILU),
     "c4_f4_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F4E2M1, ACT_SILU),
+    "c4_bf16_4352_tail_silu": (1, 4352, 4352, 8192, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
     "c2_f32_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F32, ACT_SILU),
 }
 
@@ -404,6 +405,11 @@ def make_workload(name: str, scale: int = 1) -> Workload:
                         _store(normal(3, "A", M, K), DTYPE_F4E2M1),                  # N(0, 1) rounded to 0, 0.5 .. 6
                         _store(normal(3, "B", K, N), DTYPE_F4E2M1, transpose=True),
                         normal(3, "bias", 1, N), check="full" if s >= 16 else "sampled")
+    if name == "c4_bf16_4352_tail_silu":       # 17 x 17 tiles of 256 x 256: one more than a round of 256, K as in config 4
+        M = N = 4352 // s; K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_RR, 3,
+                        _store(normal(3, "A", M, K), DTYPE_BF16), _store(normal(3, "B", K, N), DTYPE_BF16),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c4_bf16_8192_cr_silu":         # config 4 with A stored column-major ([K][M])
         M = N = K = 8192 // s
         return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_CR, 3,

@@ -86,7 +86,7 @@ struct AttnParams {
     float scale2;        // log2(e) / sqrt(d_k)
 };
 
-constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
+[[maybe_unused]] constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
 
 // The softmax of one key block, shared by the two matrix-pipe kernels.  A lane holds the raw scores of ONE
 // query (its 32 of the block's 64 keys; lane l ^ 32 has the others).  The maximum is taken on the raw scores
@@ -101,8 +101,8 @@ constexpr int kBQ = 128, kBK = 64;       // queries per workgroup, keys per step
 // division by the row sum cancels the reference point exactly.
 template <int DT> __device__ __forceinline__ float add_pair_16(unsigned int pair, float acc)
 {
-    typedef __bf16 bf16x2_ __attribute__((ext_vector_type(2)));
-    typedef _Float16 halfx2_ __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_ __attribute__((ext_vector_type(2), unused));
+    typedef _Float16 halfx2_ __attribute__((ext_vector_type(2), unused));
 #if defined(__HIP_DEVICE_COMPILE__)
     if constexpr (DT == DT_F16)
         return __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2_, pair), halfx2_{(_Float16)1.0f, (_Float16)1.0f}, acc, false);
