@@ -191,7 +191,7 @@ double tile_estimate_us(const Variant *v, const Cost &c, const Problem &p)
 // Streaming kernels (B read once per 16 rows of A, the blocks of rows side by side): the first
 // pass comes from memory at about 6 TB/s, the others largely from the caches, at a rate that
 // grows with the length of a workgroup's k range: row-major B 14 TB/s (8- and 16-bit) and
-// 11 K / (K + 120) TB/s (fp32, where the matrix instruction is the slower side); column-major B
+// 14 K / (K + 120) TB/s (fp32, where the matrix instruction is the slower side); column-major B
 // 16 K / (K + 900) and 12 K / (K + 600).  Measured from 8 x 512^3 and 64 x 4096 x 4096 to 4096^3,
 // within 20 %; 4 us for the two launches.
 double stream_estimate_us(const Problem &p)
@@ -200,7 +200,7 @@ double stream_estimate_us(const Problem &p)
     const double bytes = (double)p.batch * K * (double)p.N * (double)p.esize();
     double again;                                                              // bytes per us
     if (p.layout == 1) again = p.dtype == DT_F32 ? 12e6 * K / (K + 600.0) : 16e6 * K / (K + 900.0);
-    else again = p.dtype == DT_F32 ? 11e6 * K / (K + 120.0) : 14e6;
+    else again = p.dtype == DT_F32 ? 14e6 * K / (K + 120.0) : 14e6;
     return 4.0 + bytes / 6.0e6 + bytes * (rb - 1.0) / again;
 }
 
@@ -210,16 +210,16 @@ int64_t stream_workgroups(const Problem &p, int64_t cols, int64_t k_min)
 {
     const int64_t blocks = (p.N + cols - 1) / cols * p.batch * ((p.M + 15) / 16);
     const int64_t cus = compute_units();
-    int64_t split = (cus + blocks - 1) / blocks;
+    int64_t split = cus / blocks;                                  // whole rounds, as the launchers choose
     const int64_t by_k = p.K / k_min > 0 ? p.K / k_min : 1;
     split = split < by_k ? split : by_k;
-    return blocks * (split > 64 ? 64 : split);
+    return blocks * (split < 1 ? 1 : split > 64 ? 64 : split);
 }
 
 // The streaming variant for p, or -1.  Within a family the first entry is the one tuned on 16 rows
 // x 16384 x 16384; problems on which it would launch fewer than 192 workgroups take the entry
-// with half the columns per workgroup (8 x 4096 x 4096: 13.5 against 20.6 us in bf16, 19 against
-// 38 us in fp32, 8.0 against 10.5 us with B column-major), and more than one block of rows takes
+// with half the columns per workgroup (8 x 4096 x 4096: 13.5 against 20.6 us in bf16, 17.3 against
+// 19.7 us in fp32, 8.0 against 10.5 us with B column-major), and more than one block of rows takes
 // the entries that leave B in the caches (32 x 16384 x 1024 in bf16: 9.5 against 18.5 us) or,
 // for a short K and few columns, the four-wave entry (768 x 3072 x 768: 23 against 31 us).
 int stream_variant(const Table &t, const Problem &p)
@@ -235,13 +235,20 @@ int stream_variant(const Table &t, const Problem &p)
     int want = ROLE_STREAM_DEFAULT;
     const int64_t enough = compute_units() * 3 / 4;               // workgroups below which the chip is starved
     if (p.layout == 0 && p.dtype == DT_F32) {
-        const bool starved = stream_workgroups(p, 128, 2048) < enough && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 2048);
-        // a few blocks of rows over a long K whose 64-column groups already give every CU a workgroup:
-        // eight waves and no split along k (64 x 4096 x 4096: 31 against 39 us; not beyond 8192 x 8192, where
-        // 64 x 16384 x 16384 takes 744 against 524 us)
-        const bool unsplit = p.M <= 128 && p.K >= 2048 && (double)p.K * (double)p.N <= 67108864.0 &&
-                             (p.N + 63) / 64 * ((p.M + 15) / 16) * p.batch >= enough;
-        if (p.M > 16) want = unsplit ? ROLE_STREAM_UNSPLIT : starved && p.K >= 4096 ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
+        // (the narrow entry only while its workgroups still fit in one round: 16 x 20480 x 8192 takes 160 us
+        // with 320 of them against 122 us with 160 of the wide one)
+        const bool starved = stream_workgroups(p, 128, 1024) < enough && stream_workgroups(p, 64, 1024) > stream_workgroups(p, 128, 1024) &&
+                             stream_workgroups(p, 64, 1024) <= compute_units();
+        // a few blocks of rows over a small B: 64 columns a workgroup (128 x 4096 x 4096: 46 against 50 us,
+        // 128 x 2048 x 2048: 15 against 19 us; 256 x 4096 x 4096: 86 against 81 us)
+        const bool few_rows = p.M <= 128 && (double)p.K * (double)p.N <= 16777216.0;
+        // a B of up to 16 MiB under at most 16 blocks of rows (one block: up to 4 MiB): eight waves deep in k
+        // (128 x 2048 x 2048: 12.3 against 15.1 us, 96 x 1024 x 4096: 15.2 against 18.6 us, 16 x 1024 x 1024: 8.1
+        // against 9.3 us; 16 x 2048 x 2048: 13.8 against 11.8 us, 512 x 2048 x 2048: 60 against 44 us)
+        const double kn = (double)p.K * (double)p.N * (double)p.batch;
+        const bool small = p.M <= 256 && (p.M > 16 ? kn <= 4194304.0 : kn <= 1048576.0);
+        if (small) want = ROLE_STREAM_SMALL;
+        else if (p.M > 16) want = starved || few_rows ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
         else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
     } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {
         const bool starved = stream_workgroups(p, 256, 1024) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
@@ -251,7 +258,8 @@ int stream_variant(const Table &t, const Problem &p)
         else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
     } else if (p.layout == 1) {
         const int64_t k_min = 32 * 256 / p.esize();               // 32 steps of 256 bytes
-        const bool starved = stream_workgroups(p, 64, k_min) < enough && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min);
+        const bool starved = stream_workgroups(p, 64, k_min) < enough && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min) &&
+                             stream_workgroups(p, 32, k_min) <= compute_units();
         want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
         // 8-bit operands over a short K: the register-only kernel (1024^3: 14.8 against 17.2 us, 1008^3: 15.5
         // against 25.8 us)

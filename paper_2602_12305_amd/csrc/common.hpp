@@ -38,8 +38,10 @@ enum : int { FAM_NONE = 0, FAM_RING16, FAM_RING8, FAM_RING8_K64, FAM_RINGP, FAM_
 //   DEFAULT  the entry tuned on 16 rows x 16384 x 16384;  ROWS  more than one block of 16 rows;
 //   UNSPLIT  a few blocks of rows over a long K, eight waves and no split along k;
 //   NARROW   half the columns per workgroup, for problems that would otherwise launch too few workgroups
-//            (and, 16-bit, for a short K); REGS  the register-only kernel (8-bit operands over a short K).
-enum : int { ROLE_NONE = 0, ROLE_STREAM_DEFAULT, ROLE_STREAM_ROWS, ROLE_STREAM_UNSPLIT, ROLE_STREAM_NARROW, ROLE_STREAM_REGS };
+//            (and, 16-bit, for a short K); REGS  the register-only kernel (8-bit operands over a short K);
+//   SMALL    a B of a few MiB under up to 16 blocks of rows: eight waves deep in k, half the columns.
+enum : int { ROLE_NONE = 0, ROLE_STREAM_DEFAULT, ROLE_STREAM_ROWS, ROLE_STREAM_UNSPLIT, ROLE_STREAM_NARROW, ROLE_STREAM_REGS,
+             ROLE_STREAM_SMALL };
 
 struct Variant {
     const char *name;
@@ -129,7 +131,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
-const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 16;
+const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 24;
 const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 16;
 const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 20;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip

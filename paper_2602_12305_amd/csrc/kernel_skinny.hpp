@@ -32,8 +32,10 @@
 // B that fits L2 - and the MFMA tile kernels would leave most CUs idle (256^3: 16 workgroups
 // of the 64x64 tile kernel take 17 us, this path spreads the same work over 128).
 #pragma once
+#include <cmath>
 #include "common.hpp"
 #include "epilogue.hpp"
+#include "kernel_tile_ring.hpp"      // the LDS-DMA load, the hand-counted wait, the scalarised pointer
 
 namespace optiml {
 namespace skinny {
@@ -241,6 +243,174 @@ __global__ __launch_bounds__(64 * WN * WK) void skinny_kernel(SkinnyParams p)
     }
 }
 
+// The same walk with B brought to LDS by direct loads instead of through registers (16 x 16384 x
+// 16384: 0.159 against 0.168 ms per call).  A workgroup is WK waves deep in k and 64 CG columns
+// wide; its waves take the steps of 16 rows of its k range in turn, and every wave stages only
+// what it consumes itself, NS - 1 steps ahead: one 1 KiB block of A (16 rows x 16 k) and CG
+// 4 KiB blocks of B (16 k-rows x 64 columns, row-major as in memory) per step, no barriers, just
+// counted waits (loads complete in issue order).  Lane (q, c) then reads A[c][4q .. 4q+3] and, for
+// t = 0..3, B[4q + t][4c .. 4c+3] of every group back as 128-bit vectors and feeds the same
+// matrix instructions as skinny_kernel; the accumulators, the sum over the waves in wave order,
+// the partial sums of a split along k and the second kernel are the same too.  A's 16-byte chunks
+// sit in LDS XORed with bits 2-3 of their row, so that the 16 lanes of a read (64 bytes apart)
+// spread over the banks.  NT: B is loaded with the non-temporal hint (read once: a single block of
+// rows); without it B stays in the caches for the other blocks of rows.
+template <int WK, int CG, int NS, bool NT>
+__global__ __launch_bounds__(64 * WK) void skinny_dma_kernel(SkinnyParams p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int COLS = 64 * CG, THREADS = 64 * WK;
+    constexpr int STAGE = 1024 + CG * 4096, LOADS = 1 + 4 * CG;     // bytes and DMA instructions per step
+    extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
+    ring::lds_char *const lds = (ring::lds_char *)lds_raw;
+    static_assert(WK * 16 * COLS * 4 <= WK * NS * STAGE, "the reduction buffer reuses the staging area");
+    static_assert((NS - 1) * LOADS < 64, "the counted wait has six bits");
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = lane >> 4, c = lane & 15;
+    const int64_t zb = blockIdx.z, batch = zb / p.row_blocks, rb = zb % p.row_blocks;
+    const int64_t rows = p.M - 16 * rb < 16 ? p.M - 16 * rb : 16;
+    const int64_t nblock0 = (int64_t)blockIdx.x * COLS;
+    const int64_t n0 = nblock0 + 4 * c;
+
+    const int64_t steps = (p.K + 15) / 16, full_steps = p.K / 16;   // full: all 16 rows below K
+    const int64_t g0 = steps * blockIdx.y / p.split, g1 = steps * (blockIdx.y + 1) / p.split;
+    const int64_t g1f = g1 < full_steps ? g1 : full_steps;
+
+    const float *A = p.A + batch * p.strideA + 16 * rb * p.lda;
+    const float *B = p.B + batch * p.strideB;
+    // global side.  A's instruction: lane l fetches the chunk (l % 4) ^ (row / 4 % 4) of row l / 4
+    // (rows past the end re-read the last one: their sums are never stored).  Instruction i of B's
+    // group g: lane l fetches columns 64 g + 4 (l % 16) .. +3 of row 4 i + l / 16 (columns past N
+    // re-read the last four).
+    uint32_t a_off, b_off[CG][4];
+    {
+        const int r = lane >> 2;
+        const int64_t row = r < rows ? r : rows - 1;
+        a_off = (uint32_t)((row * p.lda + 4 * ((lane & 3) ^ ((r >> 2) & 3))) * 4);
+#pragma unroll
+        for (int g = 0; g < CG; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int64_t col = nblock0 + 64 * g + 4 * (lane & 15);
+                col = col < p.N ? col : p.N - 4;
+                b_off[g][i] = (uint32_t)(((4 * i + (lane >> 4)) * p.ldb + (col - nblock0)) * 4);
+            }
+    }
+    const char *a_base = reinterpret_cast<const char *>(A), *b_base = reinterpret_cast<const char *>(B + nblock0);
+    const uint32_t wave_lds = (uint32_t)reinterpret_cast<uintptr_t>(lds) + wave * (NS * STAGE);
+    auto issue = [&](int64_t step, int slot) {
+        const char *ga = ring::scalar_ptr(a_base + step * 64), *gb = ring::scalar_ptr(b_base + step * 64 * p.ldb);
+        const uint32_t d = __builtin_amdgcn_readfirstlane(wave_lds + slot * STAGE);
+        ring::dma_load16(ga, a_off, d);
+#pragma unroll
+        for (int g = 0; g < CG; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (NT) ring::dma_load16_once(gb, b_off[g][i], d + 1024 + g * 4096 + i * 1024);
+                else ring::dma_load16(gb, b_off[g][i], d + 1024 + g * 4096 + i * 1024);
+            }
+    };
+    // LDS side of this lane
+    const int rd_a = c * 64 + ((q ^ ((c >> 2) & 3)) << 4);
+    const int rd_b = 1024 + 4 * q * 256 + c * 16;
+
+    floatx4 acc[CG][4];
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) acc[g][cc] = floatx4{0, 0, 0, 0};
+
+    // this wave's full steps: wave, wave + WK, ... of the workgroup's range
+    const int64_t nfull = g1f > g0 ? g1f - g0 : 0;
+    const int64_t mine = nfull > wave ? (nfull - wave + WK - 1) / WK : 0;
+    auto step_of = [&](int64_t i) { return g0 + wave + i * WK; };
+    if (mine > 0) {
+        // NS - 1 steps in flight (past the end the last step is fetched again, never used, so that
+        // the wait counts stay uniform)
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(step_of(s < mine ? s : mine - 1), s);
+        for (int64_t i = 0; i < mine; ++i) {
+            const int slot = (int)(i % NS);
+            const int64_t nxt = i + NS - 1;
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);                    // lgkmcnt(0): the previous step's LDS reads have returned
+            issue(step_of(nxt < mine ? nxt : mine - 1), (int)(nxt % NS));
+            ring::wait_vmcnt<(NS - 1) * LOADS>();                  // step i has landed; its LDS reads below are new
+            asm volatile("" ::: "memory");
+            const ring::lds_char *st = lds + wave * (NS * STAGE) + slot * STAGE;
+            const floatx4 a = *reinterpret_cast<const __attribute__((address_space(3))) floatx4 *>(st + rd_a);
+#pragma unroll
+            for (int g = 0; g < CG; ++g)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const floatx4 b = *reinterpret_cast<const __attribute__((address_space(3))) floatx4 *>(st + rd_b + g * 4096 + t * 256);
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        acc[g][cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[cc], acc[g][cc], 0, 0, 0);
+                }
+            asm volatile("" ::: "memory");                          // the reads are done before the slot is refilled
+        }
+        ring::wait_vmcnt<0>();
+    }
+    // the ragged last step straight from memory, rows guarded against K (K % 4 == 0: a lane's four
+    // rows are valid together), by wave 0 of the split that holds it
+    const bool a_row_valid = c < rows;
+    if (wave == 0) {
+        for (int64_t s = g1f > g0 ? g1f : g0; s < g1; ++s) {
+            const bool k_valid = 16 * s + 4 * q < p.K;
+            floatx4 a = floatx4{0, 0, 0, 0};
+            if (k_valid && a_row_valid) a = *reinterpret_cast<const floatx4 *>(A + (int64_t)c * p.lda + 16 * s + 4 * q);
+#pragma unroll
+            for (int g = 0; g < CG; ++g)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    floatx4 b = floatx4{0, 0, 0, 0};
+                    if (k_valid && n0 + 64 * g < p.N)
+                        b = *reinterpret_cast<const floatx4 *>(B + (16 * s + 4 * q + t) * p.ldb + n0 + 64 * g);
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        acc[g][cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[cc], acc[g][cc], 0, 0, 0);
+                }
+        }
+    }
+
+    // sum the WK waves in wave order (the staging area is free now)
+    __syncthreads();
+    floatx4 *red = reinterpret_cast<floatx4 *>(lds_raw);
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            red[(wave * 16 + 4 * q + r) * (COLS / 4) + g * 16 + c] = floatx4{acc[g][0][r], acc[g][1][r], acc[g][2][r], acc[g][3][r]};
+    __syncthreads();
+
+    float *out = p.split > 1 ? p.partial + ((int64_t)blockIdx.y * p.batch * p.row_blocks + zb) * 16 * p.N
+                             : p.C + batch * p.strideC + 16 * rb * p.ldc;
+    const int64_t out_ld = p.split > 1 ? p.N : p.ldc;
+    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
+    for (int e = tid; e < 16 * (COLS / 4); e += THREADS) {
+        const int row = e / (COLS / 4), col4 = e % (COLS / 4);
+        floatx4 z = red[row * (COLS / 4) + col4];
+#pragma unroll
+        for (int w = 1; w < WK; ++w) {
+            const floatx4 v = red[(w * 16 + row) * (COLS / 4) + col4];
+            z += v;
+        }
+        const int64_t col = nblock0 + 4 * col4;
+        if (row >= rows || col >= p.N) continue;
+        if (p.split == 1) {
+            floatx4 bj = floatx4{0, 0, 0, 0};
+            if (bias && p.bias_row) { const float b = bias[16 * rb + row]; bj = floatx4{b, b, b, b}; }
+            else if (bias) bj = *reinterpret_cast<const floatx4 *>(bias + col);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) z[k] = apply_act(z[k] + bj[k], p.act);
+        }
+        *reinterpret_cast<floatx4 *>(out + (int64_t)row * out_ld + col) = z;
+    }
+#endif
+}
+
 // C = act(bias + sum over splits of partial), splits added in ascending order
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyParams p)
 {
@@ -302,6 +472,74 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     }
     dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
     hipLaunchKernelGGL((skinny_kernel<WN, WK, CG, NT, IL>), grid, dim3(64 * WN * WK), 0, stream, sp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split == 1) return e;
+    const int64_t vecs = p.M * (p.N / 4);
+    hipLaunchKernelGGL(skinny_reduce_kernel, dim3((unsigned)((vecs + 255) / 256), (unsigned)p.batch), dim3(256), 0,
+                       stream, sp);
+    return hipGetLastError();
+}
+
+// Parts along k for a streaming kernel whose grid is `blocks` column blocks (times row blocks and
+// batches) of `block_bytes` of B each: the count with the smallest estimated time.  The estimate:
+// the chip moves 6.7 TB/s and one CU at most 36 GB/s; the workgroups are dealt to the CUs in
+// turn, so with p = ceil(workgroups / CUs) the CUs that hold p - 1 run dry first and the rest
+// finish at the CUs' own rate; a split costs a second launch and its partial sums (`out_bytes`
+// per part, written and read).  (16 x 16000 x 16000: two parts 153 us, three 176 us; 130 column
+// blocks: one part 233 us, four 223 us.)  A larger count has to be 3 % better to be taken.
+inline int64_t stream_split(int64_t blocks, double block_bytes, int64_t by_k, double out_bytes)
+{
+    const double cus = (double)compute_units(), cu_rate = 36e3, hbm = 6.7e6;       // bytes per microsecond
+    double best = 1e30;
+    int64_t best_s = 1;
+    for (int64_t s = 1; s <= by_k && s <= 64; ++s) {
+        const double w = block_bytes / (double)s, wgs = (double)(blocks * s);
+        const double p = std::ceil(wgs / cus), n_hi = wgs - (p - 1.0) * cus;
+        const double active = wgs < cus ? wgs : cus;
+        const double r1 = cu_rate < hbm / active ? cu_rate : hbm / active, r2 = cu_rate < hbm / n_hi ? cu_rate : hbm / n_hi;
+        double t = (p - 1.0) * w / r1 + w / r2;
+        if (s > 1) t += 5.0 + 2.0 * (double)s * out_bytes / 5e6;
+        if (t < best * 0.97) { best = t; best_s = s; }
+    }
+    return best_s;
+}
+
+// 32-bit byte offsets inside a step of 16 rows
+inline bool skinny_dma_supports(const Problem &p)
+{
+    return skinny_supports(p) && p.ldb < (1ll << 24) && p.lda < (1ll << 24);
+}
+
+template <int WK, int CG, int NS, bool NT>
+hipError_t skinny_dma_launch(const Problem &p, hipStream_t stream)
+{
+    constexpr int COLS = 64 * CG, LDS_BYTES = WK * NS * (1024 + CG * 4096);
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_dma_kernel<WK, CG, NS, NT>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (attr != hipSuccess) return attr;
+    SkinnyParams sp;
+    sp.M = p.M; sp.N = p.N; sp.K = p.K;
+    sp.A = static_cast<const float *>(p.A); sp.lda = p.lda; sp.strideA = p.strideA;
+    sp.B = static_cast<const float *>(p.B); sp.ldb = p.ldb; sp.strideB = p.strideB;
+    sp.bias = p.bias; sp.strideBias = p.strideBias; sp.bias_row = p.bias_row ? 1 : 0;
+    sp.C = static_cast<float *>(p.C); sp.ldc = p.ldc; sp.strideC = p.strideC;
+    sp.batch = p.batch; sp.act = p.act;
+    sp.row_blocks = (p.M + 15) / 16;
+    // never ranges shorter than 256 rows per wave
+    const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
+    const int64_t by_k = p.K / (256 * WK) > 0 ? p.K / (256 * WK) : 1;
+    const int64_t split = stream_split(col_blocks, 4.0 * COLS * (double)p.K, by_k, 64.0 * (double)p.N * (double)(p.batch * sp.row_blocks));
+    sp.split = (int)split;
+    sp.partial = nullptr;
+    if (split > 1) {
+        void *ws = nullptr;
+        hipError_t e = workspace(sizeof(float) * (size_t)split * p.batch * sp.row_blocks * 16 * p.N, &ws, stream);
+        if (e != hipSuccess) return e;
+        sp.partial = static_cast<float *>(ws);
+    }
+    dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
+    hipLaunchKernelGGL((skinny_dma_kernel<WK, CG, NS, NT>), grid, dim3(64 * WK), LDS_BYTES, stream, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
     const int64_t vecs = p.M * (p.N / 4);

@@ -303,7 +303,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     if (SPLIT == 0) {
         const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
         const int64_t target = (IL || WN * WK >= 8) ? 256 : 512;
-        const int64_t by_grid = (target + col_blocks - 1) / col_blocks;
+        const int64_t by_grid = target / col_blocks;              // whole rounds: 125 column blocks take 2 parts, not 3
         const int64_t by_k = p.K / (256 * WK) > 0 ? p.K / (256 * WK) : 1;
         split = (int)(by_grid < by_k ? by_grid : by_k);
         if (split < 1) split = 1;

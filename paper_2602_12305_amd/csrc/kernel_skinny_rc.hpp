@@ -425,7 +425,7 @@ hipError_t launch(const Problem &p, hipStream_t stream)
     // shorter than WK * 8 steps (2 KiB of k per wave)
     const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
     const int64_t steps = (p.K * Type<DT>::ES + 64 * T - 1) / (64 * T);
-    int64_t split = (compute_units() + col_blocks - 1) / col_blocks;
+    int64_t split = compute_units() / col_blocks;                 // whole rounds
     const int64_t by_k = steps * T / (WK * 32) > 0 ? steps * T / (WK * 32) : 1;
     if (split > by_k) split = by_k;
     if (split < 1) split = 1;
@@ -474,7 +474,7 @@ hipError_t launch_dma(const Problem &p, hipStream_t stream)
     sp.row_blocks = (p.M + 15) / 16;
     const int64_t col_blocks = (p.N + COLS - 1) / COLS * p.batch * sp.row_blocks;
     const int64_t steps = (p.K * Type<DT>::ES + 255) / 256;
-    int64_t split = (compute_units() + col_blocks - 1) / col_blocks;
+    int64_t split = compute_units() / col_blocks;                 // whole rounds
     const int64_t by_k = steps / (WK * 8) > 0 ? steps / (WK * 8) : 1;
     if (split > by_k) split = by_k;
     if (split < 1) split = 1;

@@ -1,7 +1,7 @@
 """Dispatcher check: for a list of shapes, time every kernel variant that takes the shape and compare the
 dispatcher's choice with the fastest one.
 
-    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|odd|quick] [--steps N]
+    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|odd|rounds|stream|quick] [--steps N]
 
 Prints one line per case (shape, the dispatcher's variant and its time, the fastest variant and its time, the
 ratio) and a summary.  Inputs are N(0,1) (8-bit operands: random bytes below 120); nothing is checked for
@@ -28,7 +28,14 @@ OTHER = [(1, 64, 4096, 4096), (1, 256, 4096, 4096), (1, 1024, 1024, 1024), (1, 2
          (1, 32, 16384, 1024), (1, 512, 8192, 256), (8, 512, 512, 512), (1, 8, 4096, 4096), (1, 3008, 3008, 3008)]
 BATCHED = [(64, 128, 128, 64), (256, 64, 64, 128), (16, 1024, 1024, 128), (4, 2048, 2048, 2048), (32, 256, 256, 256),
            (8, 16, 4096, 4096), (128, 512, 64, 512), (2, 4096, 4096, 1024)]
+# up to a few blocks of 16 rows over a large B: the streaming kernels' ground
+STREAM = [(16, 16384, 16384), (8, 16384, 16384), (1, 16384, 16384), (16, 8192, 8192), (16, 4096, 4096), (16, 32768, 8192),
+          (16, 8192, 32768), (16, 16384, 4096), (16, 2048, 2048), (16, 1024, 1024), (16, 12288, 4096), (4, 5120, 5120),
+          (16, 28672, 8192), (16, 65536, 4096), (16, 1024, 65536), (16, 16000, 16000), (13, 10000, 12000), (32, 16384, 16384),
+          (32, 4096, 4096), (32, 8192, 8192), (64, 8192, 8192), (128, 4096, 4096), (128, 2048, 2048), (256, 2048, 2048),
+          (64, 2048, 8192), (96, 1024, 4096), (16, 16640, 16384), (16, 20480, 8192), (16, 24576, 8192), (16, 10240, 16384)]
 SETS = {
+    "stream": [(dt, lay, 1) + s for dt, lay in ((0, 0), (1, 0), (1, 1)) for s in STREAM],
     "mid": [(dt, lay) + s for dt in (1, 0) for lay in (0, 1) for s in MID],
     "other": [(dt, lay) + s for dt, lay in ((3, 1), (3, 0), (1, 2), (1, 3), (0, 2), (0, 3)) for s in OTHER],
     "batched": [(dt, lay) + s for dt, lay in ((1, 0), (1, 1), (0, 0), (0, 1), (2, 0)) for s in BATCHED],

@@ -141,7 +141,7 @@ def sel(batch, M, N, K, layout=0, dtype=0, A=P, lda=None, ldb=None, ldc=None, bi
 
 
 def test_dispatch_by_shape_dtype_layout_alignment():
-    assert sel(1, 16, 16384, 16384).startswith("skinny_f32")
+    assert sel(1, 16, 16384, 16384) == "skinny_f32_dma_wk4_cg2_ns2_nt1"               # B read once, straight to LDS
     assert sel(1, 8, 4096, 4096).startswith("skinny_f32")
     assert sel(1, 4096, 4096, 4096, layout=1).startswith("ring_f32_rc_128x128")
     assert sel(1, 8192, 8192, 8192, dtype=1).startswith("ring_bf16_rr_256x256")
@@ -156,7 +156,7 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 64, 4096, 4096, layout=2, dtype=1) == "xa_ring"                   # ... a few rows: copied, then streamed
     assert sel(1, 16, 16384, 16384, dtype=1).startswith("skinny_bf16_wn1_wk4_cg2")     # 16-bit storage streams B the same way
     assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_wn1_wk4_cg1")        # too few workgroups with 256 columns each
-    assert sel(1, 8, 4096, 4096).startswith("skinny_f32_wn1_wk4_cg1") and sel(1, 8, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16_dma_wk4_cg2")
+    assert sel(1, 8, 4096, 4096).startswith("skinny_f32_dma_wk4_cg1") and sel(1, 8, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16_dma_wk4_cg2")
     assert "nt0" in sel(1, 32, 16384, 1024, dtype=1)                                   # two blocks of rows: B is left in the caches
     assert sel(1, 32, 16384, 16384, dtype=1).startswith("skinny_bf16")                # two blocks of rows still beat one row of tiles
     assert not sel(1, 64, 32768, 4096, dtype=1).startswith("skinny")                 # ... but not with a short K
@@ -179,7 +179,8 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 2048, 2048, 2048, dtype=1).startswith("direct_bf16_rr_128x128") and sel(1, 4096, 4096, 4096, dtype=1).startswith("ring_bf16_rr_256x256")
     assert sel(1, 4096, 512, 4096).startswith("skinny_f32") and sel(1, 512, 8192, 256).startswith("ring_f32_rr_128x128")
     assert sel(1, 16, 16384, 16384, layout=1, dtype=1).startswith("skinnyrc_bf16") and sel(1, 3, 4096, 4096, layout=1, dtype=3).startswith("skinnyrc_f8")
-    assert sel(1, 256, 256, 256).startswith("skinny_f32") and "nt0" in sel(1, 256, 256, 256)   # small: streamed per 16 rows
+    assert sel(1, 256, 256, 256).startswith("skinny_f32_dma_wk8_cg1")                          # small: streamed per 16 rows, eight waves deep in k
+    assert "nt0" in sel(1, 512, 2048, 2048) and sel(1, 512, 2048, 2048).startswith("skinny_f32_dma")   # many blocks of rows: B is left in the caches
     assert sel(1, 1024, 1024, 1024).startswith("skinny_f32")
     assert sel(1, 2048, 2048, 2048).startswith("ring_f32_rr")          # re-reading B no longer pays
     assert sel(1, 256, 256, 256, layout=2) == "xa_ring"                       # copied, then streamed like the row-major problem
