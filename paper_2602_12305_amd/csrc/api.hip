@@ -189,19 +189,21 @@ double tile_estimate_us(const Variant *v, const Cost &c, const Problem &p)
 }
 
 // Streaming kernels (B read once per 16 rows of A, the blocks of rows side by side): the first
-// pass comes from memory at about 6 TB/s, the others largely from the caches, at a rate that
-// grows with the length of a workgroup's k range: row-major B 14 TB/s (8- and 16-bit) and
+// pass comes from memory at about 6.5 TB/s, the others largely from the caches, at a rate that
+// grows with the length of a workgroup's k range: row-major B 20 K / (K + 150) TB/s (16-bit) and
 // 14 K / (K + 120) TB/s (fp32, where the matrix instruction is the slower side); column-major B
 // 16 K / (K + 900) and 12 K / (K + 600).  Measured from 8 x 512^3 and 64 x 4096 x 4096 to 4096^3,
 // within 20 %; 4 us for the two launches.
 double stream_estimate_us(const Problem &p)
 {
     const double rb = (double)((p.M + 15) / 16), K = (double)p.K;
-    const double bytes = (double)p.batch * K * (double)p.N * (double)p.esize();
+    // whole column blocks are read: 64 columns (128 in 16-bit) at least, else multiples of 128 (256)
+    const int64_t cols = p.layout == 1 ? 16 : p.dtype == DT_F32 ? (p.N <= 64 ? 64 : 128) : (p.N <= 128 ? 128 : 256);
+    const double bytes = (double)p.batch * K * (double)((p.N + cols - 1) / cols * cols) * (double)p.esize();
     double again;                                                              // bytes per us
     if (p.layout == 1) again = p.dtype == DT_F32 ? 12e6 * K / (K + 600.0) : 16e6 * K / (K + 900.0);
-    else again = p.dtype == DT_F32 ? 14e6 * K / (K + 120.0) : 14e6;
-    return 4.0 + bytes / 6.0e6 + bytes * (rb - 1.0) / again;
+    else again = p.dtype == DT_F32 ? 14e6 * K / (K + 120.0) : 20e6 * K / (K + 150.0);
+    return 4.0 + bytes / 6.5e6 + bytes * (rb - 1.0) / again;
 }
 
 // workgroups the streaming kernels launch: column blocks x row blocks x batch x the split along k
@@ -241,7 +243,8 @@ int stream_variant(const Table &t, const Problem &p)
                              stream_workgroups(p, 64, 1024) <= compute_units();
         // a few blocks of rows over a small B: 64 columns a workgroup (128 x 4096 x 4096: 46 against 50 us,
         // 128 x 2048 x 2048: 15 against 19 us; 256 x 4096 x 4096: 86 against 81 us)
-        const bool few_rows = p.M <= 128 && (double)p.K * (double)p.N <= 16777216.0;
+        // (not over a short K: 32 x 16384 x 1024 takes 20.9 against 15.7 us), and whenever N is at most 64
+        const bool few_rows = (p.M <= 128 && p.K >= 2048 && (double)p.K * (double)p.N <= 16777216.0) || p.N <= 64;
         // a B of up to 16 MiB under at most 16 blocks of rows (one block: up to 4 MiB): eight waves deep in k
         // (128 x 2048 x 2048: 12.3 against 15.1 us, 96 x 1024 x 4096: 15.2 against 18.6 us, 16 x 1024 x 1024: 8.1
         // against 9.3 us; 16 x 2048 x 2048: 13.8 against 11.8 us, 512 x 2048 x 2048: 60 against 44 us)
@@ -251,11 +254,17 @@ int stream_variant(const Table &t, const Problem &p)
         else if (p.M > 16) want = starved || few_rows ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
         else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
     } else if (p.layout == 0 && (p.dtype == DT_BF16 || p.dtype == DT_F16)) {
-        const bool starved = stream_workgroups(p, 256, 1024) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024);
-        // more than 16 rows: the eight-wave entry (128 columns, k ranges of 2048 or more) unless it is starved too
-        const bool starved8 = stream_workgroups(p, 128, 2048) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 128, 2048);
-        if (p.M > 16) want = starved8 || (p.K <= 2048 && p.N <= 8192) ? ROLE_STREAM_NARROW : ROLE_STREAM_ROWS;
-        else want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
+        // 128 columns a workgroup while B has up to 100 M elements (16 x 8192 x 8192: 27.5 against 29.2 us,
+        // 13 x 10000 x 12000: 53.8 against 51.6 us, 16 x 28672 x 8192: 85.8 against 75.6 us) or the wide entry
+        // would leave CUs without a workgroup
+        const bool starved = stream_workgroups(p, 256, 1024) < enough && stream_workgroups(p, 128, 1024) > stream_workgroups(p, 256, 1024) &&
+                             stream_workgroups(p, 128, 1024) <= compute_units();
+        const double kn = (double)p.K * (double)p.N * (double)p.batch;
+        const bool narrow = starved || kn <= 100e6;
+        want = narrow ? ROLE_STREAM_NARROW : p.M > 16 ? ROLE_STREAM_ROWS : ROLE_STREAM_DEFAULT;
+        // a B of up to 8 MiB under at most 16 blocks of rows: eight waves deep in k (16 x 2048 x 2048: 10.1
+        // against 12.6 us, 128 x 2048 x 2048: 9.9 against 11.3 us)
+        if (kn <= 4194304.0 && p.M <= 256) want = ROLE_STREAM_SMALL;
     } else if (p.layout == 1) {
         const int64_t k_min = 32 * 256 / p.esize();               // 32 steps of 256 bytes
         const bool starved = stream_workgroups(p, 64, k_min) < enough && stream_workgroups(p, 32, k_min) > stream_workgroups(p, 64, k_min) &&

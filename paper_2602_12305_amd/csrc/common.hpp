@@ -1,6 +1,7 @@
 // Shared host/device declarations of the library: the problem descriptor that
 // every kernel launcher receives and the variant table entry.
 #pragma once
+#include <cmath>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -72,6 +73,31 @@ bool vector_friendly(const Problem &p);
 // number of compute units of the current device (256 if the query fails)
 int compute_units();
 
+// Parts along k for a streaming kernel whose grid is `blocks` column blocks (times row blocks and
+// batches) of `block_bytes` of B each: the count with the smallest estimated time.  The estimate:
+// the chip moves 6.7 TB/s and one CU at most 36 GB/s; the workgroups are dealt to the CUs in
+// turn, so with p = ceil(workgroups / CUs) the CUs that hold p - 1 run dry first and the rest
+// finish at the CUs' own rate; a split costs a second launch and its partial sums (`out_bytes`
+// per part, written and read).  (16 x 16000 x 16000: two parts 153 us, three 176 us; 130 column
+// blocks: one part 233 us, four 223 us.)  A larger count has to be 3 % better to be taken.
+inline int64_t stream_split(int64_t blocks, double block_bytes, int64_t by_k, double out_bytes)
+{
+    const double cus = (double)compute_units(), cu_rate = 36e3, hbm = 6.7e6;       // bytes per microsecond
+    double best = 1e30;
+    int64_t best_s = 1;
+    for (int64_t s = 1; s <= by_k && s <= 64; ++s) {
+        const double w = block_bytes / (double)s, wgs = (double)(blocks * s);
+        const double p = std::ceil(wgs / cus), n_hi = wgs - (p - 1.0) * cus;
+        const double active = wgs < cus ? wgs : cus;
+        const double r1 = cu_rate < hbm / active ? cu_rate : hbm / active, r2 = cu_rate < hbm / n_hi ? cu_rate : hbm / n_hi;
+        double t = (p - 1.0) * w / r1 + w / r2;
+        if (s > 1) t += 5.0 + 2.0 * (double)s * out_bytes / 5e6;
+        if (t < best * 0.97) { best = t; best_s = s; }
+    }
+    return best_s;
+}
+
+
 // per-device scratch (split-K partial sums, reduction partials, the row-major copy of a
 // column-major A): the caller's buffer if one was set, else the library's own, which is replaced
 // by a larger one on demand (the old one stays allocated) unless `stream` is being captured.
@@ -132,7 +158,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 // tables defined next to the kernels they launch
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 24;
-const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 16;
+const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 28;
 const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 20;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;

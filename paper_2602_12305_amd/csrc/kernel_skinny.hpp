@@ -32,7 +32,6 @@
 // B that fits L2 - and the MFMA tile kernels would leave most CUs idle (256^3: 16 workgroups
 // of the 64x64 tile kernel take 17 us, this path spreads the same work over 128).
 #pragma once
-#include <cmath>
 #include "common.hpp"
 #include "epilogue.hpp"
 #include "kernel_tile_ring.hpp"      // the LDS-DMA load, the hand-counted wait, the scalarised pointer
@@ -478,30 +477,6 @@ hipError_t skinny_launch(const Problem &p, hipStream_t stream)
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3((unsigned)((vecs + 255) / 256), (unsigned)p.batch), dim3(256), 0,
                        stream, sp);
     return hipGetLastError();
-}
-
-// Parts along k for a streaming kernel whose grid is `blocks` column blocks (times row blocks and
-// batches) of `block_bytes` of B each: the count with the smallest estimated time.  The estimate:
-// the chip moves 6.7 TB/s and one CU at most 36 GB/s; the workgroups are dealt to the CUs in
-// turn, so with p = ceil(workgroups / CUs) the CUs that hold p - 1 run dry first and the rest
-// finish at the CUs' own rate; a split costs a second launch and its partial sums (`out_bytes`
-// per part, written and read).  (16 x 16000 x 16000: two parts 153 us, three 176 us; 130 column
-// blocks: one part 233 us, four 223 us.)  A larger count has to be 3 % better to be taken.
-inline int64_t stream_split(int64_t blocks, double block_bytes, int64_t by_k, double out_bytes)
-{
-    const double cus = (double)compute_units(), cu_rate = 36e3, hbm = 6.7e6;       // bytes per microsecond
-    double best = 1e30;
-    int64_t best_s = 1;
-    for (int64_t s = 1; s <= by_k && s <= 64; ++s) {
-        const double w = block_bytes / (double)s, wgs = (double)(blocks * s);
-        const double p = std::ceil(wgs / cus), n_hi = wgs - (p - 1.0) * cus;
-        const double active = wgs < cus ? wgs : cus;
-        const double r1 = cu_rate < hbm / active ? cu_rate : hbm / active, r2 = cu_rate < hbm / n_hi ? cu_rate : hbm / n_hi;
-        double t = (p - 1.0) * w / r1 + w / r2;
-        if (s > 1) t += 5.0 + 2.0 * (double)s * out_bytes / 5e6;
-        if (t < best * 0.97) { best = t; best_s = s; }
-    }
-    return best_s;
 }
 
 // 32-bit byte offsets inside a step of 16 rows
