@@ -67,12 +67,12 @@ MXF4 = {"s_mxf4": (8192, 8192, 8192)}
 # library's 1 GiB copy kernel: FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000; summaries under
 # profiles/).  An entry is only reported while the sources of that kernel (its own files and the
 # shared epilogue arithmetic) still hash to the value recorded with it.
-SKINNY_SRC = ("kernel_skinny.hpp", "kernel_skinny.hip", "epilogue.hpp")
+SKINNY_SRC = ("kernel_skinny.hpp", "kernel_skinny.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 RING_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf16_rr.hip", "epilogue.hpp")
 RINGP_SRC = ("kernel_ring_persistent.hpp",) + RING_SRC
 RINGF_SRC = ("kernel_ring_f32.hpp", "ringf_instances.inc", "ring_f32_rc.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 STREAMS_SRC = ("kernel_streams.hip", "epilogue.hpp")
-SKINNY16_SRC = ('kernel_skinny16.hpp', 'kernel_skinny16.hip', 'epilogue.hpp')
+SKINNY16_SRC = ('kernel_skinny16.hpp', 'kernel_skinny16.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 LCE_SRC = ('kernel_linear_ce.hip', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 LCE_F32_SRC = ('kernel_linear_ce.hip', 'kernel_ring_f32.hpp', 'kernel_tile_ring.hpp', 'epilogue.hpp')
 ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
@@ -87,10 +87,10 @@ GLN_F32_SRC = ("kernel_linear_ln.hip", "kernel_ring_f32.hpp", "kernel_tile_ring.
 MX_SRC = ("kernel_mx.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
-    ("c1_f32_256_relu", "skinny_f32_wn1_wk4_cg2_nt0_split0"):
-        {"bytes": int((856.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "e3a49e46dc8bad6e"},
-    ("c2_f32_skinny16_silu", "skinny_f32_wn1_wk8_cg2_nt1_split0_il"):
-        {"bytes": int((529548.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "e3a49e46dc8bad6e"},
+    ("c1_f32_256_relu", "skinny_f32_dma_wk8_cg1_ns2_nt1"):
+        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "c0c7540508f0c86e"},
+    ("c2_f32_skinny16_silu", "skinny_f32_dma_wk4_cg2_ns2_nt1"):
+        {"bytes": int((531015.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "c0c7540508f0c86e"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
         {"bytes": int((385170.1 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "bc649ac3034b36b7"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
@@ -108,7 +108,7 @@ TRAFFIC = {
     ("c4_bf16_8192_cr_silu", "xa_ring"):
         {"bytes": int((862588.7 * 2.0 + 262249.1) * 1024), "files": XA_SRC, "src": "1f3589c2d44153ad"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((534591.1 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "51a88e44a2dc274c"},
+        {"bytes": int((534587.3 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "3fb2db49cb369908"},
     ("s_relu", "s_relu"):
         {"bytes": int((524309.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
     ("s_sigmoid", "s_sigmoid"):

@@ -483,6 +483,9 @@ hipError_t launch(const Problem &p, hipStream_t stream)
         split = (int)(by_grid < by_k ? by_grid : by_k);
         if (split < 1) split = 1;
         if (split > 64) split = 64;
+        // one workgroup per CU: by the estimate of the time
+        if (target == 256)
+            split = (int)stream_split(col_blocks, 2.0 * COLS * (double)p.K, by_k, 64.0 * (double)p.N * (double)(p.batch * sp.row_blocks));
     }
     sp.split = split;
     sp.partial = nullptr;

@@ -154,7 +154,8 @@ def test_dispatch_by_shape_dtype_layout_alignment():
     assert sel(1, 4096, 4096, 4096, layout=3) == "xa_ring"
     assert sel(1, 64, 64, 64, layout=2, dtype=1).startswith("tile_bf16_cr_")        # too little work to pay for the copy
     assert sel(1, 64, 4096, 4096, layout=2, dtype=1) == "xa_ring"                   # ... a few rows: copied, then streamed
-    assert sel(1, 16, 16384, 16384, dtype=1) == "skinny_bf16_dma_wk4_cg2_ns2_nt1"     # 16-bit storage streams B the same way
+    assert sel(1, 16, 16384, 16384, dtype=1).startswith("skinny_bf16_wn1_wk4_cg2")     # 16-bit storage streams B the same way
+    assert sel(1, 16, 8192, 8192, dtype=1) == "skinny_bf16_dma_wk4_cg1_ns4_nt0"           # a smaller B: straight to LDS, 128 columns a workgroup
     assert sel(1, 7, 4096, 4096, dtype=2).startswith("skinny_f16_dma_wk4_cg1")        # a small B: 128 columns a workgroup
     assert sel(1, 8, 4096, 4096).startswith("skinny_f32_dma_wk4_cg1") and sel(1, 8, 4096, 4096, layout=1, dtype=1).startswith("skinnyrc_bf16_dma_wk4_cg2")
     assert "nt0" in sel(1, 32, 16384, 1024, dtype=1)                                   # two blocks of rows: B is left in the caches
