@@ -137,7 +137,7 @@ TRAFFIC = {
         {"bytes": int((541155.5 * 2.0 + 401408.8) * 1024), "files": GLN_SRC, "src": "439417ce7d7660e4"},
     ("s_gln_f32", "ring_f32_rr_ln"):
         {"bytes": int((427086.4 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "beec9390eec9dce1"},
-    ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4"):
+    ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4_pf"):
         {"bytes": int((209165.7 * 2.0 + 131249.1) * 1024), "files": MX_SRC, "src": "804c9bc72f21a026"},
 }
 
@@ -532,7 +532,7 @@ def main():
         bound, dtype = "mfma", 4
 
         def __init__(self, name):
-            self.name, self.kernel = name, "ring_mxf4_rc_256x256_w2x4_ns4"
+            self.name, self.kernel = name, "ring_mxf4_rc_256x256_w2x4_ns4_pf"
             M, N, K = self.shape = MXF4[name]
             def operand(tag, rows):
                 x = synth.normal(17, tag, rows, K)

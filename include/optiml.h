@@ -387,10 +387,11 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
  * scaleB[j * lds_b + k / 32], value 2^(byte - 127), byte 255 = NaN; lds_a, lds_b >= K / 32 count bytes.  K must be
  * a multiple of 32.  C is M x N bfloat16, row-major, ldc >= N; bias (N floats) may be NULL; act as above.  All
  * pointers DEVICE.  Products are exact, block sums are scaled exactly and accumulated in fp32; C is rounded once.
- * dtype must be OPTIML_F4E2M1.  M == 0 or N == 0 writes nothing; K == 0 gives act(bias).  No workspace.
+ * dtype must be OPTIML_F4E2M1.  M == 0 or N == 0 writes nothing; K == 0 gives act(bias).
  * optiml_gemm_epilogue_mx_path: 0 when the call would run on the matrix-pipe tile kernel (K a multiple of 128,
- * 16-byte aligned operands and rows, 4-byte aligned scales and scale pitches, at least 65536 entries of C), 1 for
- * the one-thread-per-entry kernel, or an error.
+ * 16-byte aligned operands and rows, at least 65536 entries of C; any address and pitch of the scales), 1 for the
+ * one-thread-per-entry kernel, or an error.  The tile kernel keeps a copy of the scales, (M + N) K / 32 bytes, in
+ * the workspace (see Workspace above); the other kernel needs none.
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd or too small lda / ldb, lds_a or
  * lds_b < K / 32, ldc < N, another dtype, unknown act, a NULL pointer with work to do.
  */

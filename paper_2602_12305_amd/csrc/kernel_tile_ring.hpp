@@ -58,9 +58,9 @@ struct Params {
     float *picked;
     int bias_row;        // EPI == 0: bias[m] instead of bias[n]
     // block-scaled operands (Cfg::MX): one E8M0 byte per row of A (column of B) and 32 elements of k,
-    // scaleA[i * lds_a + k / 32], scaleB[j * lds_b + k / 32]
+    // the four scale bytes of k-tile t (128 k) of row i of A: scaleA + i * lds_a + t * sk_a, likewise for the columns of B
     const char *scaleA = nullptr, *scaleB = nullptr;
-    int64_t lds_a = 0, lds_b = 0;
+    int64_t lds_a = 0, lds_b = 0, sk_a = 4, sk_b = 4;
 };
 
 template <int NS_, bool B_KC_, bool PF_ = false, int WN_ = 4, int DT_ = DT_BF16, int EPI_ = 0, bool K64_ = false, int BAND_ = 8,
@@ -71,7 +71,7 @@ struct Cfg {
     // register of that lane.  The scales of a k-tile (four blocks = one dword per row) travel with the tile: one more
     // LDS-DMA load per wave and stage (4 bytes a lane) into 2 KiB behind the B tile.
     static constexpr bool MX = MX_;
-    static_assert(!MX_ || (DT_ == DT_F4 && B_KC_ && !PF_ && !K64_ && EPI_ == 0 && WM_ == 2 && WN_ == 4), "block scales: the plain 2 x 4 E2M1 kernel");
+    static_assert(!MX_ || (DT_ == DT_F4 && B_KC_ && PF_ && !K64_ && EPI_ == 0 && WM_ == 2 && WN_ == 4), "block scales: the 2 x 4 E2M1 kernel with fragment prefetch");
     // WM = 1: a 128 x 256 block computed by four waves (1 x 4, the same 128 x 64 wave tile) with 24 KiB
     // stages; with NS = 3 two such workgroups share a CU (144 KiB of LDS, at most 256 registers a lane),
     // so that one's first loads and epilogue run under the other's k loop: for many short tiles.
@@ -214,6 +214,25 @@ struct Frags {
     uintx4 a[C::TM], b[C::TN];
 };
 
+// MX: the scale dwords of a wave's rows and columns for one stage, shifted so that byte 0 is this lane's block of
+// k-step 0 and byte 2 that of k-step 1
+template <class C>
+struct Scales {
+    unsigned int a[C::TM], b[C::TN];
+};
+
+template <class C>
+__device__ __forceinline__ void load_scales(const Ctx<C> &c, const lds_char *rd, Scales<C> &sc)
+{
+    const int shift = (threadIdx.x & 32) ? 8 : 0;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+        sc.a[i] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sa_frag + i * 128) >> shift;
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+        sc.b[j] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sb_frag + j * 128) >> shift;
+}
+
 // MFMA operands of k-step s (16 k) of the tile held in stage `rd`
 template <class C>
 __device__ __forceinline__ void load_frags(const Ctx<C> &c, const lds_char *rd, int s, Frags<C> &f)
@@ -249,6 +268,26 @@ __device__ __forceinline__ void mma_frags(const Frags<C> &f, floatx16 (&acc)[C::
             acc[j][i] = mfma_32x32x16<C::DT>(f.b[j], f.a[i], acc[j][i]);
 }
 
+// The same with block scales: `sc` holds the scale dwords of the stage the fragments come from, SH = 0 for
+// its k-step 0 and 16 for k-step 1.  The instruction's first operand is the B fragment (the tile is computed
+// transposed), so its scale is the column's.
+template <class C, int SH, int J0 = 0, int J1 = C::TN>
+__device__ __forceinline__ void mma_frags_mx(const Frags<C> &f, const Scales<C> &sc, floatx16 (&acc)[C::TN][C::TM])
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef int intx8_ __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int j = J0; j < J1; ++j)
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i) {
+            const intx8_ b = {(int)f.b[j][0], (int)f.b[j][1], (int)f.b[j][2], (int)f.b[j][3], 0, 0, 0, 0};
+            const intx8_ a = {(int)f.a[i][0], (int)f.a[i][1], (int)f.a[i][2], (int)f.a[i][3], 0, 0, 0, 0};
+            // byte SH / 8 of the scale dwords
+            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc[j][i], 4, 4, SH / 8, (int)sc.b[j], SH / 8, (int)sc.a[i]);
+        }
+#endif
+}
+
 // One k-tile of 32: see the file header for the order of events.  With C::PF the operands of
 // the tile's first k-step arrive in `f0` (fetched during the previous step) and the step ends by
 // fetching the next tile's first k-step from `nxt`, which the barrier at the top has made
@@ -275,20 +314,30 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
         gb = scalar_ptr(gb);
         const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dma) + c.wave * 1024);
         constexpr int NR = C::TM + (C::B_KC ? C::TN : 2 * C::TN), H = C::TN / 2, NMH = C::TM * H;
+        Scales<C> sc;
+        if constexpr (C::MX) load_scales<C>(c, rd, sc);      // the first MFMAs wait for these six reads
         load_frags<C>(c, rd, 1, f1);
-        mma_frags<C, 0, H>(f0, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 0, 0, H>(f0, sc, acc);
+        else mma_frags<C, 0, H>(f0, acc);
 #pragma unroll
         for (int i = 0; i < NMH; ++i) {            // second k-step's operands under these MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, (NR + NMH - 1) / NMH, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NR + (C::MX ? C::TM + C::TN : 0) + NMH - 1) / NMH, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
 #pragma unroll
         for (int i = 0; i < C::A_INSTR; ++i) dma_load16(ga, c.a_off[i], d + i * C::NW * 1024);
-        mma_frags<C, H, C::TN>(f0, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 0, H, C::TN>(f0, sc, acc);
+        else mma_frags<C, H, C::TN>(f0, acc);
 #pragma unroll
         for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
+        if constexpr (C::MX) {
+            // wave w fills dwords 64 w .. 64 w + 63 of the scale area, as issue_stage does
+            const uint32_t ds = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dma) + C::A_BYTES + C::B_BYTES + c.wave * 256);
+            dma_load4(scalar_ptr(gs), c.s_off, ds);
+        }
         load_frags<C>(c, nxt, 0, f0);
-        mma_frags<C>(f1, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 16>(f1, sc, acc);
+        else mma_frags<C>(f1, acc);
 #pragma unroll
         for (int i = 0; i < 2 * NMH; ++i) {        // next tile's first operands under these MFMAs
             if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -301,40 +350,7 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
     {
         load_frags<C>(c, rd, 0, f0);
         load_frags<C>(c, rd, 1, f1);
-        if constexpr (C::MX) {
-#if defined(__HIP_DEVICE_COMPILE__)
-            // This lane's fragment of k-step s is block 2 s + half of the tile: byte 2 s + half of its row's scale
-            // dword, shifted down to byte 0 (the byte the instruction reads with a zero selector).  The
-            // instruction's first operand is the B fragment (the tile is computed transposed), so its scale is the
-            // column's.
-            typedef int intx8_ __attribute__((ext_vector_type(8)));
-            const int shift = (threadIdx.x & 32) ? 8 : 0;
-            unsigned int sa[C::TM], sb[C::TN];
-#pragma unroll
-            for (int i = 0; i < C::TM; ++i)
-                sa[i] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sa_frag + i * 128) >> shift;
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-                sb[j] = *reinterpret_cast<const __attribute__((address_space(3))) unsigned int *>(rd + c.sb_frag + j * 128) >> shift;
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-                for (int i = 0; i < C::TM; ++i) {
-                    const intx8_ b0 = {(int)f0.b[j][0], (int)f0.b[j][1], (int)f0.b[j][2], (int)f0.b[j][3], 0, 0, 0, 0};
-                    const intx8_ a0 = {(int)f0.a[i][0], (int)f0.a[i][1], (int)f0.a[i][2], (int)f0.a[i][3], 0, 0, 0, 0};
-                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a0, acc[j][i], 4, 4, 0, (int)sb[j], 0, (int)sa[i]);
-                }
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-                for (int i = 0; i < C::TM; ++i) {
-                    const intx8_ b1 = {(int)f1.b[j][0], (int)f1.b[j][1], (int)f1.b[j][2], (int)f1.b[j][3], 0, 0, 0, 0};
-                    const intx8_ a1 = {(int)f1.a[i][0], (int)f1.a[i][1], (int)f1.a[i][2], (int)f1.a[i][3], 0, 0, 0, 0};
-                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a1, acc[j][i], 4, 4, 0, (int)(sb[j] >> 16), 0,
-                                                                                (int)(sa[i] >> 16));
-                }
-#endif
-        } else if constexpr (C::K64) {
+        if constexpr (C::K64) {
             // both 16-byte fragments of a row are one 32-byte operand: 64 values of k (which value
             // sits in which byte only has to agree between the two operands)
 #pragma unroll
@@ -457,7 +473,8 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
         ctx.sa_frag = C::A_BYTES + C::B_BYTES + (wm * C::WTM + frag_row) * 4;
         ctx.sb_frag = C::A_BYTES + C::B_BYTES + C::BM * 4 + (wn * C::WTN + frag_row) * 4;
     }
-    auto gs = [&](int64_t kt) { return C::MX ? S + (kt < last ? kt : last) * 4 : nullptr; };
+    const int64_t s_step = C::MX ? (wave < 4 ? p.sk_a : p.sk_b) : 0;
+    auto gs = [&](int64_t kt) { return C::MX ? S + (kt < last ? kt : last) * s_step : nullptr; };
 
     // prologue: tiles 0 .. NS-2
 #pragma unroll

@@ -82,6 +82,11 @@ def _skinny_exprs(p, layout):
             f"skinny::skinny_kernel<{t}, {il}>")
 
 
+def _skinny_dma_exprs(p, layout):
+    t = f"{p['WK']}, {p['CG']}, {p['NS']}, {'true' if p['NT'] else 'false'}"
+    return ("skinny::skinny_dma_supports", f"skinny::skinny_dma_launch<{t}>", f"skinny::skinny_dma_kernel<{t}>")
+
+
 def _skinny16_exprs(dt):
     def exprs(p, layout):
         t = f"{p['WN']}, {p['WK']}, {p['CG']}, {'true' if p['NT'] else 'false'}"
@@ -110,6 +115,13 @@ FAMILIES = {
         {"WN": [1, 2, 4, 8], "WK": [1, 2, 4, 8, 16], "CG": [1, 2], "NT": [0, 1], "SPLIT": [0, 1, 2, 4, 8], "IL": [0, 1]},
         lambda p: p["WN"] * p["WK"] <= 16 and not (p["WN"] * p["WK"] > 8 and p["CG"] > 1),
         _skinny_exprs, {"WN": 1, "WK": 8, "CG": 2, "NT": 1, "SPLIT": 0, "IL": 1}),
+    # fp32 streaming kernels with B staged through LDS by direct loads: WK waves x NS stages of 1 + 4 CG KiB fit
+    # the 160 KiB of LDS, and the counted wait ((NS - 1) x (1 + 4 CG) loads outstanding) has six bits
+    "skinny_dma": Family(
+        "skinny_dma", "kernel_skinny.hpp",
+        {"WK": [2, 4, 8], "CG": [1, 2, 4], "NS": [2, 3, 4, 6, 8], "NT": [0, 1]},
+        lambda p: p["WK"] * p["NS"] * (1 + 4 * p["CG"]) <= 160 and (p["NS"] - 1) * (1 + 4 * p["CG"]) < 64,
+        _skinny_dma_exprs, {"WK": 4, "CG": 2, "NS": 2, "NT": 1}),
     # 16-bit streaming kernels: the cross-wave reduction buffer (WK x 16 rows x 128 CG WN columns of
     # fp32) must fit 64 KiB of static LDS
     "skinny16_bf16": Family(

@@ -28,14 +28,16 @@ def quantised(seed, tag, rows, K, spread):
     return np.ascontiguousarray(codes), np.ascontiguousarray(scales, dtype=np.uint8)          # codes come packed two to a byte
 
 
-def run(As, sA, Bs, sB, bias, M, N, K, act, *, pad_c=0, pitch=0, spitch=0, shift=0):
-    """pitch / spitch: extra bytes per row of the operands / of the scales; shift: bytes in front of every array."""
-    def dev(x, extra):
+def run(As, sA, Bs, sB, bias, M, N, K, act, *, pad_c=0, pitch=0, spitch=0, shift=0, sshift=0):
+    """pitch / spitch: extra bytes per row of the operands / of the scales; shift: bytes in front of every array;
+    sshift: more bytes in front of the scale arrays only."""
+    def dev(x, extra, front):
         rows, w = x.shape
-        buf = np.full(shift + rows * (w + extra), 0x5a, dtype=np.uint8)
-        buf[shift:].reshape(rows, w + extra)[:, :w] = x
-        return torch.from_numpy(buf).cuda(), w + extra
-    Ad, la = dev(As, pitch); Bd, lb = dev(Bs, pitch); sAd, lsa = dev(sA, spitch); sBd, lsb = dev(sB, spitch)
+        buf = np.full(front + rows * (w + extra), 0x5a, dtype=np.uint8)
+        buf[front:].reshape(rows, w + extra)[:, :w] = x
+        return torch.from_numpy(buf).cuda()[front - shift:], w + extra
+    Ad, la = dev(As, pitch, shift); Bd, lb = dev(Bs, pitch, shift)
+    sAd, lsa = dev(sA, spitch, shift + sshift); sBd, lsb = dev(sB, spitch, shift + sshift)
     bd = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
     ldc = N + pad_c
     Cd = torch.full((M, ldc), 0x4442, dtype=torch.int16, device="cuda")
@@ -95,8 +97,10 @@ def test_pitches_offsets_and_degenerate_shapes():
     As, sA = quantised(7200, "A", M, K, 4); Bs, sB = quantised(7200, "B", N, K, 4)
     bias = synth.normal(7200, "bias", 1, N)[0]
     ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, bias, M, N, K, dtype=F4, act=synth.ACT_NONE)
+    # the tile kernel takes any address and pitch of the scales (they are copied k-tile by k-tile first), but only
+    # operands whose rows start on 16 bytes
     for kw, want in ((dict(pitch=16, spitch=4), 0), (dict(pitch=16, spitch=4, shift=16), 0), (dict(pitch=2, spitch=1), 1),
-                     (dict(shift=3), 1), (dict(pitch=16, spitch=3), 1)):
+                     (dict(shift=3), 1), (dict(pitch=16, spitch=3), 0), (dict(sshift=1), 0), (dict(spitch=5, sshift=2), 0)):
         got, path, _ = run(As, sA, Bs, sB, bias, M, N, K, synth.ACT_NONE, **kw)
         assert path == want and e1(got, ref) <= 2e-2, kw
     # K = 0: act(bias); nothing to do for an empty C
