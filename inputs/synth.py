@@ -167,6 +167,32 @@ def f8e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.where(b >> 7 == 1, -v, v).astype(np.float32)
 
 
+def f32_to_f8e5m2_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to OCP E5M2 (nearest, ties to even; magnitudes that round beyond 57344 become infinity, as in
+    binary16, of which E5M2 is the upper byte; NaN -> 0x7F); uint8."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.abs(np.nan_to_num(x.astype(np.float64), nan=0.0, posinf=1e300, neginf=-1e300))
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -40)))
+    e = np.clip(e, -14.0, 15.0)                          # below 2^-14 the spacing stays 2^-16 (subnormals)
+    q = np.exp2(e - 2.0)                                 # spacing: 2 fraction bits
+    r = np.rint(np.minimum(a, 1e6) / q) * q              # numpy rounds half to even
+    over = r > 57344.0                                   # 61440 is the first value that rounds up
+    ee = np.floor(np.log2(np.maximum(r, 2.0 ** -40)))
+    normal = r >= 2.0 ** -14
+    field = np.where(normal, ee + 15.0, 0.0)
+    frac = np.where(normal, r / np.exp2(ee) * 4.0 - 4.0, r * 65536.0)
+    bits = (field.astype(np.int64) << 2 | frac.astype(np.int64)).astype(np.uint8)
+    bits = np.where(over, np.uint8(0x7C), bits)
+    bits = np.where(np.isnan(x), np.uint8(0x7F), bits)
+    return (bits | (np.signbit(x).astype(np.uint8) << 7)).astype(np.uint8)
+
+
+def f8e5m2_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """E5M2 is the upper byte of binary16."""
+    b = np.ascontiguousarray(b, dtype=np.uint8).astype(np.uint16)
+    return (b << 8).astype(np.uint16).view(np.float16).astype(np.float32)
+
+
 # the eight magnitudes of OCP E2M1, by code
 _F4_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
 
@@ -237,6 +263,8 @@ def to_bits(x, dtype):
         return f32_to_f16_bits(x)
     if dtype == DTYPE_F8E4M3:
         return f32_to_f8e4m3_bits(x)
+    if dtype == DTYPE_F8E5M2:
+        return f32_to_f8e5m2_bits(x)
     return np.ascontiguousarray(x, dtype=np.float32)
 
 
@@ -250,6 +278,8 @@ def from_bits(b, dtype):
         return f16_bits_to_f32(b)
     if dtype == DTYPE_F8E4M3:
         return f8e4m3_bits_to_f32(b)
+    if dtype == DTYPE_F8E5M2:
+        return f8e5m2_bits_to_f32(b)
     return np.asarray(b, dtype=np.float32)
 
 
@@ -283,7 +313,7 @@ def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
 # ----------------------------------------------------------------------------------------------
 # The five workloads
 
-DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3, DTYPE_F4E2M1 = 0, 1, 2, 3, 4
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3, DTYPE_F4E2M1, DTYPE_F8E5M2 = 0, 1, 2, 3, 4, 5
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 
@@ -314,7 +344,7 @@ class Workload:
     @property
     def algorithmic_bytes(self):
         """One read of A, B and bias, one write of C."""
-        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1, DTYPE_F4E2M1: 0.5}.get(self.dtype, 2)      # A and B
+        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1, DTYPE_F8E5M2: 1, DTYPE_F4E2M1: 0.5}.get(self.dtype, 2)      # A and B
         cs = 4 if self.dtype == DTYPE_F32 else 2                      # C
         per = int((self.M * self.K + self.K * self.N) * es) + self.M * self.N * cs + 4 * self.N
         return self.batch * per

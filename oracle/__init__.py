@@ -16,7 +16,7 @@ import numpy as np
 
 from .build import build as _build
 
-F32, BF16, F16, F8E4M3, F4E2M1 = 0, 1, 2, 3, 4
+F32, BF16, F16, F8E4M3, F4E2M1, F8E5M2 = 0, 1, 2, 3, 4, 5
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 EW_RELU, EW_SIGMOID = 0, 1
@@ -47,6 +47,8 @@ def lib():
         L.oracle_f16_to_double.argtypes = [C.c_uint16]
         L.oracle_f8e4m3_to_double.restype = C.c_double
         L.oracle_f8e4m3_to_double.argtypes = [C.c_uint8]
+        L.oracle_f8e5m2_to_double.restype = C.c_double
+        L.oracle_f8e5m2_to_double.argtypes = [C.c_uint8]
         L.oracle_f4e2m1_to_double.restype = C.c_double
         L.oracle_f4e2m1_to_double.argtypes = [C.c_uint8]
         L.oracle_e8m0_to_double.restype = C.c_double
@@ -81,7 +83,7 @@ def _ptr(a):
 
 
 def _check_operand(x, dtype, what):
-    want = {F32: np.float32, F8E4M3: np.uint8, F4E2M1: np.uint8}.get(dtype, np.uint16)
+    want = {F32: np.float32, F8E4M3: np.uint8, F4E2M1: np.uint8, F8E5M2: np.uint8}.get(dtype, np.uint16)
     if x.dtype != want or not x.flags.c_contiguous:
         raise TypeError(f"{what}: need C-contiguous {want.__name__} storage, got {x.dtype}")
 
@@ -167,6 +169,12 @@ def f16_from_double(y):
 def f8e4m3_to_double(bits):
     """fp64 value of each OCP E4M3 bit pattern (uint8)."""
     f = lib().oracle_f8e4m3_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(bits, dtype=np.uint8))
+
+
+def f8e5m2_to_double(bits):
+    """fp64 value of each OCP E5M2 bit pattern (uint8)."""
+    f = lib().oracle_f8e5m2_to_double
     return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(bits, dtype=np.uint8))
 
 

@@ -17,7 +17,7 @@
  * Bias, SiLU, GELU, bf16 storage and batching are not in the paper; they are
  * the standard definitions named by this repository's benchmark configuration.
  *
- * Arithmetic: the stored fp32 / bf16 / fp16 / 8-bit E4M3 inputs are widened exactly to fp64; every
+ * Arithmetic: the stored fp32 / bf16 / fp16 / 8-bit E4M3 or E5M2 / 4-bit E2M1 inputs are widened exactly to fp64; every
  * product of two of them is exact in fp64 (at most 48 significant bits); the
  * sum runs over k ascending in one fp64 accumulator starting from +0.0; the
  * bias is added after the sum; activations use fp64 libm.  The result is kept
@@ -38,7 +38,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3, ORACLE_F4E2M1 = 4 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3, ORACLE_F4E2M1 = 4, ORACLE_F8E5M2 = 5 };
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
 /* bit 0 of layout: B is column-major; bit 1: A is column-major */
 
@@ -73,6 +73,22 @@ double oracle_f8e4m3_to_double(uint8_t b)
     return sign ? -v : v;
 }
 
+/* OCP 8-bit floating point E5M2 (1 sign, 5 exponent bits with bias 15, 2 fraction bits: binary16 cut after
+ * its second fraction bit) to double, exactly: exponent field 0 is a subnormal f * 2^-16, field 31 is infinity
+ * (f = 0) or NaN; largest finite 57344. */
+double oracle_f8e5m2_to_double(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 2) & 31, f = b & 3;
+    double v;
+    if (e == 31)
+        v = f ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, -16);
+    else
+        v = ldexp((double)(4 + f), e - 17);
+    return sign ? -v : v;
+}
+
 /* OCP 4-bit floating point E2M1 (1 sign, 2 exponent bits with bias 1, 1 fraction bit; no infinities, no NaN)
  * to double, exactly: exponent field 0 is a subnormal f * 2^-1, else (2 + f) * 2^(e - 2).  The sixteen codes
  * are 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives.  Only the low four bits of `nibble` are read. */
@@ -100,6 +116,8 @@ static double widen(const void *base, int64_t idx, int dtype)
         return oracle_f16_to_double(((const uint16_t *)base)[idx]);
     if (dtype == ORACLE_F8E4M3)
         return oracle_f8e4m3_to_double(((const uint8_t *)base)[idx]);
+    if (dtype == ORACLE_F8E5M2)
+        return oracle_f8e5m2_to_double(((const uint8_t *)base)[idx]);
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -204,7 +222,7 @@ int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
                          int layout, int dtype, int act)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F4E2M1) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F8E5M2) || act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
     const int64_t rows = batch * M;
@@ -269,7 +287,7 @@ int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t
                                  int layout, int dtype, int act)
 {
     if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F4E2M1) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F8E5M2) || act < 0 || act > 3)
         return -1;
     for (int64_t t = 0; t < count; ++t)
         if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)

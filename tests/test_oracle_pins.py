@@ -339,6 +339,48 @@ def test_f8e4m3_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
     assert np.allclose(y, ref, rtol=0, atol=1e-13)
 
 
+def test_f8e5m2_decode_and_the_generator_encoding_agree_with_the_ocp_format():
+    import torch
+    bits = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(bits.copy()).view(torch.float8_e5m2).float().numpy().astype(np.float64)      # an independent decoder
+    got = oracle.f8e5m2_to_double(bits)
+    nan = np.isnan(want)
+    assert list(np.flatnonzero(nan)) == [0x7D, 0x7E, 0x7F, 0xFD, 0xFE, 0xFF]
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # E5M2 is binary16 cut after two fraction bits: a second independent decoder
+    assert np.array_equal(got[~nan], (bits.astype(np.uint16) << 8).view(np.float16).astype(np.float64)[~nan])
+    # landmarks typed by hand: largest finite 57344, infinity, smallest normal 2^-14, smallest subnormal 2^-16, one, -1.5, -1.75
+    assert list(oracle.f8e5m2_to_double([0x7B, 0x7C, 0x04, 0x01, 0x3C, 0xBE, 0xBF])) == [57344.0, np.inf, 2.0 ** -14, 2.0 ** -16, 1.0, -1.5, -1.75]
+    # the input generator's own decoder and encoder (numpy, no code shared with the oracle)
+    assert np.array_equal(synth.f8e5m2_bits_to_f32(bits)[~nan].astype(np.float64), want[~nan])
+    assert np.array_equal(synth.f32_to_f8e5m2_bits(got[~nan].astype(np.float32)), bits[~nan])          # every value to itself
+    x = np.concatenate([synth.normal(95, "x", 64, 1024, 0.0, 3.0).ravel(), synth.normal(96, "y", 8, 1024, 0.0, 3e-5).ravel(),
+                        synth.normal(97, "z", 8, 1024, 0.0, 2e4).ravel()])
+    enc = torch.from_numpy(x).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(synth.f32_to_f8e5m2_bits(x), enc)                                           # torch's rounding, subnormals and overflow included
+    fin = got[:0x7C]
+    mids = (fin[:-1] + fin[1:]) / 2                                                                   # ties go to the even neighbour
+    assert np.array_equal(synth.f32_to_f8e5m2_bits(mids.astype(np.float32)), np.where(bits[:0x7B] % 2 == 0, bits[:0x7B], bits[1:0x7C]))
+    assert list(synth.f32_to_f8e5m2_bits(np.array([1e9, -1e9, 61439.0, 61440.0, np.nan, -0.0, np.inf], np.float32))) == \
+        [0x7C, 0xFC, 0x7B, 0x7C, 0x7F, 0x80, 0x7C]
+
+
+def test_f8e5m2_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
+    M, N, K = 7, 9, 33
+    A = synth.to_bits(synth.normal(98, "A", M, K), oracle.F8E5M2); B = synth.to_bits(synth.normal(98, "B", N, K), oracle.F8E5M2)
+    bias = synth.normal(98, "bias", 1, N)[0]
+    y = oracle.gemm_epilogue(A, B, bias, M, N, K, dtype=oracle.F8E5M2, layout=synth.LAYOUT_RC)[0]
+    ref = synth.f8e5m2_bits_to_f32(A).astype(np.float64) @ synth.f8e5m2_bits_to_f32(B).astype(np.float64).T + bias.astype(np.float64)
+    assert np.allclose(y, ref, rtol=0, atol=1e-13)
+    # the two 8-bit types are told apart: the same bytes read as E4M3 give another product
+    y4 = oracle.gemm_epilogue(A, B, bias, M, N, K, dtype=oracle.F8E4M3, layout=synth.LAYOUT_RC)[0]
+    assert not np.allclose(y, y4, rtol=1e-3, atol=1e-3)
+    # row-major B and column-major A address the same elements
+    y2 = oracle.gemm_epilogue(np.ascontiguousarray(A.T), np.ascontiguousarray(B.T), bias, M, N, K, dtype=oracle.F8E5M2, layout=2)[0]
+    assert np.array_equal(y, y2)
+
+
 def test_f16_storage_reduces_to_the_fp64_product_of_the_decoded_operands():
     rng = np.random.default_rng(6)
     M, N, K = 7, 9, 33
