@@ -39,12 +39,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2, 4: 10066.3}          # fp32, bf16, fp16, fp8, fp4 MFMA (dense)
-DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1"}
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2, 4: 10066.3, 5: 5033.2}          # fp32, bf16, fp16, fp8 (E4M3), fp4, fp8 (E5M2) MFMA (dense)
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1", 5: "f8e5m2"}
 # which roof bounds each contraction workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma",
-         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_4352_tail_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
+         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_4352_tail_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
          "c2_f32_skinny16_rc_silu": "hbm"}
 # streaming siblings: (entry point, op, arrays read, arrays written) on 2^28 floats
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),

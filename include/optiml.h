@@ -36,6 +36,9 @@
  *              infinity).  OPTIML_F8E4M3: A and B are 8-bit OCP E4M3 (1 sign, 4 exponent
  *              bits with bias 7, 3 fraction bits; no infinities, largest finite 448), one
  *              byte per element, decoded exactly; C is bfloat16; no scale factors.
+ *              OPTIML_F8E5M2: the same with 8-bit OCP E5M2 operands (1 sign, 5 exponent bits
+ *              with bias 15, 2 fraction bits: the upper byte of binary16, with its
+ *              infinities and NaNs; largest finite 57344).
  *              OPTIML_F4E2M1: A and B are 4-bit OCP E2M1 (1 sign, 2 exponent bits with bias
  *              1, 1 fraction bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), two
  *              elements per byte along k, the element with the even k in the low half;
@@ -46,7 +49,7 @@
  *              mirror image with a column-major C; other layouts return
  *              OPTIML_ERR_UNSUPPORTED.
  *              bias is always float; NULL means no bias.  The
- *              contraction entry points take all five; the other entry points say
+ *              contraction entry points take all six; the other entry points say
  *              which they take.
  *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
  *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
@@ -97,7 +100,7 @@
 extern "C" {
 #endif
 
-typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3, OPTIML_F4E2M1 = 4 } optiml_dtype_t;
+typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3, OPTIML_F4E2M1 = 4, OPTIML_F8E5M2 = 5 } optiml_dtype_t;
 
 typedef enum {
     OPTIML_ACT_NONE = 0,

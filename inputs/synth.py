@@ -358,7 +358,7 @@ def _store(x, dtype, transpose=False):
 
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
-BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf16_8192_cr_silu",
+BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf8_8192_rc_silu", "c4_bf16_8192_cr_silu",
                      "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu", "c4_bf16_4352_tail_silu")     # further dtypes and shapes
 
 
@@ -372,6 +372,7 @@ SPECS = {
     "c4_f16_8192_silu": (1, 8192, 8192, 8192, LAYOUT_RR, DTYPE_F16, ACT_SILU),
     "c2_bf16_skinny16_silu": (1, 16, 16384, 16384, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
     "c4_f8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E4M3, ACT_SILU),
+    "c4_bf8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E5M2, ACT_SILU),
     "c4_bf16_8192_cr_silu": (1, 8192, 8192, 8192, LAYOUT_CR, DTYPE_BF16, ACT_SILU),
     "c4_f4_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F4E2M1, ACT_SILU),
     "c4_bf16_4352_tail_silu": (1, 4352, 4352, 8192, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
@@ -428,6 +429,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
         return Workload(name, 1, M, N, K, DTYPE_F8E4M3, ACT_SILU, LAYOUT_RC, 3,
                         _store(normal(3, "A", M, K), DTYPE_F8E4M3),
                         _store(normal(3, "B", K, N), DTYPE_F8E4M3, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
+    if name == "c4_bf8_8192_rc_silu":          # config 4's shape in 8-bit E5M2 operands (bf16 result), B column-major
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, DTYPE_F8E5M2, ACT_SILU, LAYOUT_RC, 3,
+                        _store(normal(3, "A", M, K), DTYPE_F8E5M2),
+                        _store(normal(3, "B", K, N), DTYPE_F8E5M2, transpose=True),
                         normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c4_f4_8192_rc_silu":           # config 4's shape in 4-bit E2M1 operands (bf16 result), k contiguous in both
         M = N = K = 8192 // s

@@ -59,7 +59,7 @@ const Table &table()
 
 bool enum_ok(int layout, int dtype, int act)
 {
-    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_F4 && act >= 0 && act <= 3;
+    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_BF8 && act >= 0 && act <= 3;
 }
 
 // OPTIML_OK when the arguments describe a valid problem (possibly an empty one).
@@ -272,7 +272,7 @@ int stream_variant(const Table &t, const Problem &p)
         want = starved ? ROLE_STREAM_NARROW : ROLE_STREAM_DEFAULT;
         // 8-bit operands over a short K: the register-only kernel (1024^3: 14.8 against 17.2 us, 1008^3: 15.5
         // against 25.8 us)
-        if (p.dtype == DT_F8 && p.K <= 2048 && p.M > 16) want = ROLE_STREAM_REGS;
+        if (is_f8(p.dtype) && p.K <= 2048 && p.M > 16) want = ROLE_STREAM_REGS;
     } else {
         return -1;
     }

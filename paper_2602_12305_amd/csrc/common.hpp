@@ -7,11 +7,12 @@
 
 namespace optiml {
 
-// DT_F8: A, B in OCP E4M3, C in bf16.  DT_F4: A, B in OCP E2M1, two values to a byte along k (the even k in the
+// DT_F8: A, B in OCP E4M3, C in bf16; DT_BF8: the same with OCP E5M2 operands.  DT_F4: A, B in OCP E2M1, two values to a byte along k (the even k in the
 // low half), C in bf16; inside the library such a problem is described in BYTES of k: K, lda, ldb and the operand
 // strides are halved on entry, an "element" of A or B is a byte holding two values.
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3, DT_F4 = 4 };
-constexpr bool is_8bit(int dt) { return dt == DT_F8 || dt == DT_F4; }   // one byte per stored element of A and B
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3, DT_F4 = 4, DT_BF8 = 5 };
+constexpr bool is_f8(int dt) { return dt == DT_F8 || dt == DT_BF8; }                   // one 8-bit value per byte
+constexpr bool is_8bit(int dt) { return is_f8(dt) || dt == DT_F4; }                     // one byte per stored element of A and B
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
 
 // C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.
@@ -159,7 +160,7 @@ hipError_t launch_transpose(int64_t rows, int64_t cols, const void *src, int64_t
 const Variant *generic_variants();         extern const int kNumGenericVariants;
 const Variant *skinny_variants();          constexpr int kNumSkinnyVariants = 24;
 const Variant *skinny16_variants();        constexpr int kNumSkinny16Variants = 28;
-const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 20;
+const Variant *skinny_rc_variants();       constexpr int kNumSkinnyRcVariants = 24;
 // the MFMA tile kernels are compiled per (dtype, layout) and gathered by tile_variants.hip
 const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;

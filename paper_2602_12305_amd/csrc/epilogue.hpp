@@ -85,15 +85,16 @@ __device__ __forceinline__ void dispatch_act(int act, F &&f)
     }
 }
 
-// One 32x32x64 matrix instruction on E4M3 operands given as two 16-byte halves each (the scale
-// operands of the builtin are zero: the unscaled instruction)
-template <class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x64_f8(V4 a_lo, V4 a_hi, V4 b_lo, V4 b_hi, ACC c)
+// One 32x32x64 matrix instruction on E4M3 (DT_F8, format code 0) or E5M2 (DT_BF8, format code 1) operands given
+// as two 16-byte halves each (the scale operands of the builtin are zero: the unscaled instruction)
+template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x64_f8(V4 a_lo, V4 a_hi, V4 b_lo, V4 b_hi, ACC c)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef int intx8_ __attribute__((ext_vector_type(8)));
     const intx8_ a = intx8_{(int)a_lo[0], (int)a_lo[1], (int)a_lo[2], (int)a_lo[3], (int)a_hi[0], (int)a_hi[1], (int)a_hi[2], (int)a_hi[3]};
     const intx8_ b = intx8_{(int)b_lo[0], (int)b_lo[1], (int)b_lo[2], (int)b_lo[3], (int)b_hi[0], (int)b_hi[1], (int)b_hi[2], (int)b_hi[3]};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+    if constexpr (DT == DT_BF8) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 1, 1, 0, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 #else
     return c;
 #endif
@@ -154,6 +155,17 @@ __device__ __forceinline__ float f8e4m3_to_f32(unsigned char b)
     return (b & 0x80u) ? -v : v;
 }
 
+// OCP 8-bit E5M2 (bias 15, infinities and NaNs as in binary16, of which it is the upper byte) to fp32, exactly
+__device__ __forceinline__ float f8e5m2_to_f32(unsigned char b)
+{
+    const unsigned e = (b >> 2) & 31u, f = b & 3u;
+    float v;
+    if (e == 31u) v = f ? __builtin_nanf("") : __builtin_inff();
+    else if (e == 0u) v = (float)f * 1.52587890625e-05f;                             // f * 2^-16
+    else v = __uint_as_float(((e + 112u) << 23) | (f << 21));                        // 1.f * 2^(e-15)
+    return (b & 0x80u) ? -v : v;
+}
+
 // OCP 4-bit E2M1 (bias 1, no infinities or NaN): sign, then 0, 0.5, 1, 1.5, 2, 3, 4, 6
 __device__ __forceinline__ float f4e2m1_to_f32(unsigned int code)
 {
@@ -198,6 +210,12 @@ template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32
         const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
         c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
         return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
+    } else if constexpr (DT == DT_BF8) {
+        // the same with E5M2 operands
+        typedef long longx2_ __attribute__((ext_vector_type(2)));
+        const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(a2[0], b2[0], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(a2[1], b2[1], c, 0, 0, 0);
     } else if constexpr (DT == DT_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8_, a), __builtin_bit_cast(halfx8_, b), c, 0, 0, 0);
     else

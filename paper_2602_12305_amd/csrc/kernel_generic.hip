@@ -22,6 +22,8 @@ template <> __device__ __forceinline__ float widen<float>(float v) { return v; }
 template <> __device__ __forceinline__ float widen<unsigned short>(unsigned short v) { return bf16_to_f32(v); }
 template <> __device__ __forceinline__ float widen<_Float16>(_Float16 v) { return (float)v; }
 template <> __device__ __forceinline__ float widen<unsigned char>(unsigned char v) { return f8e4m3_to_f32(v); }
+struct e5m2_t { unsigned char v; };          // a byte read as E5M2
+template <> __device__ __forceinline__ float widen<e5m2_t>(e5m2_t v) { return f8e5m2_to_f32(v.v); }
 
 __device__ __forceinline__ void put(float *p, float y) { *p = y; }
 __device__ __forceinline__ void put(unsigned short *p, float y) { *p = f32_to_bf16(y); }
@@ -124,6 +126,8 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
             hipLaunchKernelGGL(generic_kernel<_Float16>, grid, block, 0, s, p, blocks_m, y0);
         else if (p.dtype == DT_F8)
             hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short>), grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_BF8)
+            hipLaunchKernelGGL((generic_kernel<e5m2_t, unsigned short>), grid, block, 0, s, p, blocks_m, y0);
         else if (p.dtype == DT_F4)
             hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short, 2>), grid, block, 0, s, p, blocks_m, y0);
         else

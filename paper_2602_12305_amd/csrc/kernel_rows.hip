@@ -77,20 +77,24 @@ __global__ __launch_bounds__(kThreads) void ce_wave_rows_kernel(const float *__r
             // offset within their rows, i.e. on the same few memory channels.
             const int64_t slices = (c4 + U * 64 - 1) / (U * 64);
             const int64_t start = slices > 0 ? (j * 5) % slices : 0;
-            for (int64_t it = 0; it < slices; ++it) {
+            // the loads of slice it + 1 are in flight while slice it is summed
+            auto fetch = [&](int64_t it, floatx4 (&v)[U]) {
                 const int64_t sl = it + start < slices ? it + start : it + start - slices;
                 const int64_t base = lane + sl * (U * 64);
-                floatx4 v[U];
-                float mx = -__builtin_inff();
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const bool in = base + u * 64 < c4;
                     v[u] = in ? __builtin_nontemporal_load(row4 + base + u * 64)
                               : floatx4{-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff()};
+                }
+            };
+            auto fold = [&](const floatx4 (&v)[U]) {
+                float mx = -__builtin_inff();
+#pragma unroll
+                for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) mx = v[u][e] > mx ? v[u][e] : mx;
-                }
-                if (mx == -__builtin_inff()) continue;     // nothing (or only -inf) in this lane's part
+                if (mx == -__builtin_inff()) return;        // nothing (or only -inf) in this lane's part
                 const float m = r.m > mx ? r.m : mx;
                 float s = r.s * exp_neg(m - r.m);
 #pragma unroll
@@ -98,6 +102,16 @@ __global__ __launch_bounds__(kThreads) void ce_wave_rows_kernel(const float *__r
 #pragma unroll
                     for (int e = 0; e < 4; ++e) s += exp_neg(m - v[u][e]);
                 r = MaxSum{m, s};
+            };
+            floatx4 va[U], vb[U];
+            if (slices > 0) fetch(0, va);
+            for (int64_t it = 0; it < slices; it += 2) {
+                if (it + 1 < slices) fetch(it + 1, vb);
+                fold(va);
+                if (it + 1 < slices) {
+                    if (it + 2 < slices) fetch(it + 2, va);
+                    fold(vb);
+                }
             }
             for (int64_t k = 4 * c4 + lane; k < C; k += 64) r = merge(r, MaxSum{row[k], 1.0f});
         } else {

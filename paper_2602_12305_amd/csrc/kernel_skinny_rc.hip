@@ -20,7 +20,7 @@ using namespace skinny_rc;
 const Variant *skinny_rc_variants()
 {
     static const Variant v[kNumSkinnyRcVariants] = {SKRC_SET(DT_F32, "f32"), SKRC_SET(DT_BF16, "bf16"), SKRC_SET(DT_F16, "f16"),
-                                                    SKRC_SET(DT_F8, "f8"), SKRC_SET(DT_F4, "f4")};
+                                                    SKRC_SET(DT_F8, "f8"), SKRC_SET(DT_F4, "f4"), SKRC_SET(DT_BF8, "bf8")};
     return v;
 }
 

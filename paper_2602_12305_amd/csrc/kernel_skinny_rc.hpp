@@ -67,6 +67,11 @@ __device__ __forceinline__ floatx4 mma16(uintx4 a, uintx4 b, floatx4 acc)
         const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a2[0], b2[0], acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a2[1], b2[1], acc, 0, 0, 0);
+    } else if constexpr (DT == DT_BF8) {
+        typedef long longx2_ __attribute__((ext_vector_type(2)));
+        const longx2_ a2 = __builtin_bit_cast(longx2_, a), b2 = __builtin_bit_cast(longx2_, b);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(a2[0], b2[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(a2[1], b2[1], acc, 0, 0, 0);
     } else {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {

@@ -85,7 +85,7 @@ struct Cfg {
     // 8-bit operands only: one v_mfma_f32_32x32x64_f8f6f4 per k-tile and pair of fragments instead
     // of four v_mfma_f32_32x32x16_fp8_fp8
     static constexpr bool K64 = K64_;
-    static_assert(!K64_ || (DT_ == DT_F8 && !PF_), "the 64-deep instruction: 8-bit operands, no fragment prefetch");
+    static_assert(!K64_ || (is_f8(DT_) && !PF_), "the 64-deep instruction: 8-bit operands, no fragment prefetch");
     static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
     // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 64 columns of A.B + bias
     // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the
@@ -94,7 +94,7 @@ struct Cfg {
     // the sum of squared deviations from that mean: the row statistics of a LayerNorm over the N
     // columns come out of the registers that hold the product.
     static constexpr int EPI = EPI_;
-    // DT_F8: A and B in 8-bit E4M3 (column-major B only), C in bf16.  The tile geometry is in
+    // DT_F8 / DT_BF8: A and B in 8-bit E4M3 / E5M2 (column-major B only), C in bf16.  The tile geometry is in
     // bytes, so a k-tile is 64 elements instead of 32 and each 16-byte fragment feeds two matrix
     // instructions.  DT_F4: the same with two E2M1 values in every byte (the problem arrives with K
     // counted in bytes) and one 64-deep scaled matrix instruction per pair of 16-byte fragments.
@@ -357,7 +357,7 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
             for (int j = 0; j < C::TN; ++j)
 #pragma unroll
                 for (int i = 0; i < C::TM; ++i)
-                    acc[j][i] = mfma_32x32x64_f8(f0.b[j], f1.b[j], f0.a[i], f1.a[i], acc[j][i]);
+                    acc[j][i] = mfma_32x32x64_f8<C::DT>(f0.b[j], f1.b[j], f0.a[i], f1.a[i], acc[j][i]);
         } else {
             mma_frags<C>(f0, acc);
             mma_frags<C>(f1, acc);
@@ -540,7 +540,7 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
             for (int j = 0; j < C::TN; ++j)
 #pragma unroll
                 for (int i = 0; i < C::TM; ++i)
-                    acc[j][i] = mfma_32x32x64_f8(g0.b[j], g1.b[j], g0.a[i], g1.a[i], acc[j][i]);
+                    acc[j][i] = mfma_32x32x64_f8<C::DT>(g0.b[j], g1.b[j], g0.a[i], g1.a[i], acc[j][i]);
         } else {
             mma_frags<C>(g0, acc);
             mma_frags<C>(g1, acc);

@@ -109,7 +109,7 @@ int second_kernel(const Problem &p, double *us)
 
 bool xa_supports(const Problem &p)
 {
-    if (!p.a_col() || p.K < 1 || p.dtype == DT_F8 || !vector_friendly(p)) return false;
+    if (!p.a_col() || p.K < 1 || is_f8(p.dtype) || !vector_friendly(p)) return false;
     const int ch = 16 / p.esize();
     if (p.M % ch != 0 || p.K % ch != 0) return false;
     const int64_t T = 256 / p.esize();
@@ -186,7 +186,7 @@ const Variant *second_kernel_f8(const Problem &p)
 
 bool x8_supports(const Problem &p)
 {
-    if (p.dtype != DT_F8 || (!p.a_col() && p.b_col()) || p.K < 1 || !vector_friendly(p)) return false;
+    if (!is_f8(p.dtype) || (!p.a_col() && p.b_col()) || p.K < 1 || !vector_friendly(p)) return false;
     if (p.K % 16 != 0 || (p.a_col() && p.M % 16 != 0) || (!p.b_col() && p.N % 16 != 0)) return false;
     if (p.batch * ((p.M + 255) / 256 + (p.N + 255) / 256) * ((p.K + 255) / 256) > 0x7fffffffLL) return false;
     return second_kernel_f8(p) != nullptr;

@@ -7,11 +7,11 @@ const Variant *kTile_f32_rr(), *kTile_f32_rc(), *kTile_f32_cr(), *kTile_f32_cc()
 const Variant *kTile_bf16_rr(), *kTile_bf16_rc(), *kTile_bf16_cr(), *kTile_bf16_cc();
 const Variant *kTile_f16_rr(), *kTile_f16_rc(), *kTile_f16_cr(), *kTile_f16_cc();
 const Variant *kDirect_bf16_rr(), *kDirect_bf16_rc(), *kDirect_f16_rr(), *kDirect_f16_rc();
-const Variant *kRing_bf16_rr(), *kRing_bf16_rc(), *kRing_f16_rr(), *kRing_f16_rc(), *kRing_f8_rc(), *kRing_f4_rc();
+const Variant *kRing_bf16_rr(), *kRing_bf16_rc(), *kRing_f16_rr(), *kRing_f16_rc(), *kRing_f8_rc(), *kRing_f4_rc(), *kRing_bf8_rc();
 const Variant *kRing_f32_rr(), *kRing_f32_rc();
 
 namespace {
-constexpr int kTotal = 12 * kTilesPerUnit + 4 * kDirectPerUnit + 6 * kRingPerUnit + 2 * kRingF32PerUnit;
+constexpr int kTotal = 12 * kTilesPerUnit + 4 * kDirectPerUnit + 7 * kRingPerUnit + 2 * kRingF32PerUnit;
 struct Gather {
     Variant v[kTotal];
     Gather()
@@ -41,6 +41,7 @@ struct Gather {
         add(kTile_f16_cr(), kTilesPerUnit);
         add(kTile_f16_cc(), kTilesPerUnit);
         add(kRing_f8_rc(), kRingPerUnit);
+        add(kRing_bf8_rc(), kRingPerUnit);
         add(kRing_f4_rc(), kRingPerUnit);
     }
 };

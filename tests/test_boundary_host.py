@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=5), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=6), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])
@@ -318,7 +318,9 @@ def test_e2m1_operands_are_validated_and_dispatched_before_any_gpu_call():
     assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=513) == ERR_INVALID              # odd pitch
     assert sel(1, 512, 512, 512, layout=1, dtype=4, ldb=515) == ERR_INVALID
     assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=510) == ERR_INVALID              # pitch shorter than a row
-    assert sel(1, 512, 512, 512, layout=1, dtype=5) == ERR_INVALID                       # no such storage type
+    assert sel(1, 512, 512, 512, layout=1, dtype=6) == ERR_INVALID                       # no such storage type
+    assert sel(1, 8192, 8192, 8192, layout=1, dtype=5).startswith("ring_bf8_rc_256x256") and sel(1, 16, 16384, 16384, layout=1, dtype=5).startswith("skinnyrc_bf8")   # E5M2: the E4M3 kernels with the other format code
+    assert sel(1, 8192, 8192, 8192, layout=0, dtype=5) == "xk_ring_f8" and sel(1, 100, 100, 100, layout=0, dtype=5) == "generic_64x64"
 
 
 def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():

@@ -19,8 +19,10 @@ from helpers import e1, store
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16, F16, F8, F4 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1
-DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8, "f4": F4}
+F32, BF16, F16, F8, F4, BF8 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2
+DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8, "f4": F4, "bf8": BF8}
+BOTH_F8 = pytest.mark.parametrize("f8", [F8, BF8], ids=["e4m3", "e5m2"])      # the two 8-bit types share every kernel
+F8_TAG = {F8: "f8", BF8: "bf8"}
 ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
 LAYOUT_OF = {"rr": 0, "rc": 1, "cr": 2, "cc": 3}
 
@@ -49,7 +51,7 @@ def problem_for(name):
             # two whole summation blocks, one partial block, and a tail shorter than the ring
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
-        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, {"f8": 64, "f4": 128}.get(dt, 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
+        return DT_OF[dt], LAYOUT_OF[lay], 300, 392, {"f8": 64, "bf8": 64, "f4": 128}.get(dt, 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("xk_"):
         return F8, 0, 304, 400, 448                        # 8-bit operands, B row-major: copied with k contiguous
     if name.startswith("xa_"):
@@ -115,7 +117,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
     name = ob.optiml_variant_name(vid)
     dt = name.split("_")[1]
     dtype, layout = DT_OF[dt], LAYOUT_OF[name.split("_")[2]]
-    tile, chunk = {"f8": (64, 16), "f4": (128, 32), "f32": (16, 4)}.get(dt, (32, 8))
+    tile, chunk = {"f8": (64, 16), "bf8": (64, 16), "f4": (128, 32), "f32": (16, 4)}.get(dt, (32, 8))
     if name.startswith("direct_"):
         tile = 64                                                       # their k-tile: 1 .. 7 chunks beyond it
     extras = (1, 2, 3) if not name.startswith("direct_") else (1, 4, 7)
@@ -126,7 +128,7 @@ def test_ring_kernels_take_a_partial_last_k_tile(vid):
         check_against_oracle(Ai, Bi, bi, dtype=dtype, act=synth.ACT_NONE, layout=layout, variant=vid, exact=True)
     A = synth.normal(1610, "A", 300, tile * 7 + chunk, batch=2); B = synth.normal(1610, "B", tile * 7 + chunk, 392, batch=2)
     bias = synth.normal(1610, "bias", 1, 392, batch=2).reshape(2, 392)
-    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad={"f8": 16, "f4": 32, "f32": 4}.get(dt, 8))
+    check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_SILU, layout=layout, variant=vid, pad={"f8": 16, "bf8": 16, "f4": 32, "f32": 4}.get(dt, 8))
 
 
 # ---- L1: persistent kernels: more C tiles than CUs, so workgroups walk several tiles ----------
@@ -563,64 +565,69 @@ def test_column_major_c_with_few_columns_is_streamed(dtype, layout):
             check_against_oracle(A, B, bias, dtype=dtype, act=synth.ACT_GELU_TANH, layout=5, variant=vid)
 
 
+@BOTH_F8
 @pytest.mark.parametrize("t,M,N,K,layout,dtype,act,pad,use_bias", [c for c in fuzz_cases() if c[0] % 2 == 1])
-def test_dispatch_random_shapes_in_e4m3(t, M, N, K, layout, dtype, act, pad, use_bias):
+def test_dispatch_random_shapes_in_e4m3(t, M, N, K, layout, dtype, act, pad, use_bias, f8):
     A = synth.uniform(470 + t, "A", M, K, -4.0, 4.0); B = synth.uniform(470 + t, "B", K, N)
     bias = synth.uniform(470 + t, "bias", 1, N)[0] if use_bias else None
-    check_against_oracle(A, B, bias, dtype=F8, act=act, layout=layout, pad=pad, ldc_pad=pad)
+    check_against_oracle(A, B, bias, dtype=f8, act=act, layout=layout, pad=pad, ldc_pad=pad)
 
 
-def test_e4m3_matrix_pipe_kernel_is_the_dispatchers_choice_and_sees_every_k():
+@BOTH_F8
+def test_e4m3_matrix_pipe_kernel_is_the_dispatchers_choice_and_sees_every_k(f8):
     """A row-major, B column-major, K a multiple of 64: the ring kernel.  One-hot rows of A pick single k positions,
     so a fragment byte fed to the wrong k slot of the matrix instruction cannot hide."""
     M, N, K = 4096, 4096, 4096
-    v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, K, 0, 0x1000, 0, 0x1000, N, 0, 1, F8, 0)
-    assert ob.optiml_variant_name(v).startswith("ring_f8_rc")
+    v = ob.optiml_select_variant(1, M, N, K, 0x1000, K, 0, 0x1000, K, 0, 0x1000, 0, 0x1000, N, 0, 1, f8, 0)
+    assert ob.optiml_variant_name(v).startswith("ring_" + F8_TAG[f8] + "_rc")
     M, N, K = 256, 256, 512                   # (a problem this small is streamed by the dispatcher: forced here)
     A = np.zeros((M, K), dtype=np.float32); A[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
     B = synth.integers(977, "B", K, N, -8, 8)
-    check_against_oracle(A, B, None, dtype=F8, act=synth.ACT_NONE, layout=1, exact=True, variant=v)
+    check_against_oracle(A, B, None, dtype=f8, act=synth.ACT_NONE, layout=1, exact=True, variant=v)
     A = synth.normal(978, "A", 520, 1024); B = synth.normal(978, "B", 1024, 776); bias = synth.normal(978, "bias", 1, 776)[0]
-    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_GELU_TANH, layout=1, entry="ex")
+    check_against_oracle(A, B, bias, dtype=f8, act=synth.ACT_GELU_TANH, layout=1, entry="ex")
 
 
+@BOTH_F8
 @pytest.mark.parametrize("layout", [0, 2, 3])
-def test_e4m3_copies_followed_by_a_streaming_kernel(layout):
+def test_e4m3_copies_followed_by_a_streaming_kernel(layout, f8):
     """8-bit operands whose k is not contiguous, a few rows, a long K: after the copies the dispatcher's choice is the
     streaming kernel, whose split-k partial sums go behind the copies in the workspace."""
     for t, (batch, M, N, K) in enumerate([(1, 48, 1024, 4096), (2, 80, 2048, 2048), (1, 48, 1024, 4096)]):
         A = synth.normal(985 + t, "A", M, K, batch=batch); B = synth.normal(985 + t, "B", K, N, batch=batch)
         bias = synth.normal(985 + t, "bias", 1, N, batch=batch).reshape(batch, N)
-        check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout)
+        check_against_oracle(A, B, bias, dtype=f8, act=synth.ACT_SILU, layout=layout)
         Ai = synth.integers(990 + t, "A", M, K, batch=batch); Bi = synth.integers(990 + t, "B", K, N, batch=batch)
-        check_against_oracle(Ai, Bi, None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True)
+        check_against_oracle(Ai, Bi, None, dtype=f8, act=synth.ACT_NONE, layout=layout, exact=True)
 
 
+@BOTH_F8
 @pytest.mark.parametrize("layout", [0, 1, 2, 3, 5])
-def test_e4m3_storage_multi_tile_shapes_and_specials(layout):
-    """8-bit E4M3 operands, bf16 result: several tiles with a batch, exact on integers, and every one of the 256 bit
-    patterns (subnormals, +-448, the two NaN patterns) decoded as the format says."""
+def test_e4m3_storage_multi_tile_shapes_and_specials(layout, f8):
+    """8-bit E4M3 or E5M2 operands, bf16 result: several tiles with a batch, exact on integers, and every one of the 256
+    bit patterns (subnormals, the largest values, the NaN patterns, E5M2's infinities) decoded as the format says."""
     batch, M, N, K = 2, 264, 520, 192
     A = synth.normal(975, "A", M, K, batch=batch); B = synth.normal(975, "B", K, N, batch=batch)
     bias = synth.normal(975, "bias", 1, N, batch=batch).reshape(batch, N)
-    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout)
+    check_against_oracle(A, B, bias, dtype=f8, act=synth.ACT_SILU, layout=layout)
     Ai = synth.integers(976, "A", M, K, batch=batch); Bi = synth.integers(976, "B", K, N, batch=batch)
-    check_against_oracle(Ai, Bi, None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True)
+    check_against_oracle(Ai, Bi, None, dtype=f8, act=synth.ACT_NONE, layout=layout, exact=True)
     if layout == 1:
         # row i of A holds pattern i in column 0 (other columns zero), B is the identity's first row scaled by 1:
         # C[i, 0] = value of pattern i; NaN patterns give NaN
         pats = np.arange(256, dtype=np.uint8)
         As = np.zeros((256, 16), dtype=np.uint8); As[:, 0] = pats
-        Bs = np.zeros((8, 16), dtype=np.uint8); Bs[0, 0] = 0x38                       # 1.0
-        Y, _, _ = run_gpu(As, Bs, None, 1, 256, 8, 16, F8, synth.ACT_NONE, 1)
-        want = oracle.f8e4m3_to_double(pats)
+        Bs = np.zeros((8, 16), dtype=np.uint8); Bs[0, 0] = 0x38 if f8 == F8 else 0x3C  # 1.0
+        Y, _, _ = run_gpu(As, Bs, None, 1, 256, 8, 16, f8, synth.ACT_NONE, 1)
+        want = oracle.f8e4m3_to_double(pats) if f8 == F8 else oracle.f8e5m2_to_double(pats)
         nan = np.isnan(want)
         assert np.array_equal(np.isnan(Y[0, :, 0]), nan)
-        assert np.array_equal(Y[0, ~nan, 0], want[~nan])                              # every E4M3 value is exact in bf16
+        assert np.array_equal(Y[0, ~nan, 0], want[~nan])                              # every E4M3 / E5M2 value is exact in bf16
 
 
+@BOTH_F8
 @pytest.mark.parametrize("layout", [0, 2, 3, 4, 6])
-def test_e4m3_operands_copied_with_k_contiguous(layout):
+def test_e4m3_operands_copied_with_k_contiguous(layout, f8):
     """8-bit operands whose k is not contiguous (A column-major and / or B row-major, also under a column-major C):
     copied into the workspace, then the matrix-pipe kernel.  The dispatcher's own choice, a batch, one-hot rows."""
     M, N, K = 528, 784, 448
@@ -628,16 +635,16 @@ def test_e4m3_operands_copied_with_k_contiguous(layout):
     if layout & 4:
         a_col, b_col = 1 - b_col, 1 - a_col               # what the transposed problem looks like
     v = ob.optiml_select_variant(1, M, N, K, 0x1000, M if layout & 2 else K, 0, 0x1000, K if layout & 1 else N, 0, 0x1000, 0,
-                                 0x1000, M if layout & 4 else N, 0, layout, F8, 0)
-    assert ob.optiml_variant_name(v) == ("ring_f8_rc_256x256_w2x4_ns5_k64" if (not a_col and b_col) else "xk_ring_f8")
+                                 0x1000, M if layout & 4 else N, 0, layout, f8, 0)
+    assert ob.optiml_variant_name(v) == ("ring_" + F8_TAG[f8] + "_rc_256x256_w2x4_ns5_k64" if (not a_col and b_col) else "xk_ring_f8")
     A = synth.normal(980 + layout, "A", M, K); B = synth.normal(980 + layout, "B", K, N); bias = synth.normal(980, "bias", 1, N)[0]
-    check_against_oracle(A, B, bias, dtype=F8, act=synth.ACT_SILU, layout=layout, entry="ex")
+    check_against_oracle(A, B, bias, dtype=f8, act=synth.ACT_SILU, layout=layout, entry="ex")
     batch = 3
     Ai = synth.integers(981, "A", M, K, batch=batch); Bi = synth.integers(981, "B", K, N, batch=batch)
     bi = synth.integers(981, "bias", 1, N, -5, 5, batch=batch).reshape(batch, N)
-    check_against_oracle(Ai, Bi, bi, dtype=F8, act=synth.ACT_RELU, layout=layout, exact=True)
+    check_against_oracle(Ai, Bi, bi, dtype=f8, act=synth.ACT_RELU, layout=layout, exact=True)
     A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
-    check_against_oracle(A1, synth.integers(982, "B", K, N, -8, 8), None, dtype=F8, act=synth.ACT_NONE, layout=layout, exact=True, entry="ex")
+    check_against_oracle(A1, synth.integers(982, "B", K, N, -8, 8), None, dtype=f8, act=synth.ACT_NONE, layout=layout, exact=True, entry="ex")
 
 
 @pytest.mark.parametrize("vid", variant_ids("skinnyrc"))
