@@ -300,7 +300,8 @@ template <class C, int EXTRA = 0>
 __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restrict__ ga, const char *__restrict__ gb,
                                           lds_char *__restrict__ dma, const lds_char *__restrict__ rd,
                                           const lds_char *__restrict__ nxt, Frags<C> &f0,
-                                          floatx16 (&acc)[C::TN][C::TM], const char *__restrict__ gs = nullptr)
+                                          floatx16 (&acc)[C::TN][C::TM], const char *__restrict__ gs = nullptr,
+                                          Scales<C> *carried = nullptr)
 {
     static_assert(C::AHEAD * C::LOADS + EXTRA <= 63, "vmcnt is a 6-bit counter");
     wait_vmcnt<C::AHEAD * C::LOADS + EXTRA>();
@@ -314,19 +315,19 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
         gb = scalar_ptr(gb);
         const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)reinterpret_cast<uintptr_t>(dma) + c.wave * 1024);
         constexpr int NR = C::TM + (C::B_KC ? C::TN : 2 * C::TN), H = C::TN / 2, NMH = C::TM * H;
-        Scales<C> sc;
-        if constexpr (C::MX) load_scales<C>(c, rd, sc);      // the first MFMAs wait for these six reads
+        // MX: the scale dwords of this stage were fetched at the end of the previous step (below), into the
+        // registers its own matrix instructions had just read for the last time
         load_frags<C>(c, rd, 1, f1);
-        if constexpr (C::MX) mma_frags_mx<C, 0, 0, H>(f0, sc, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 0, 0, H>(f0, *carried, acc);
         else mma_frags<C, 0, H>(f0, acc);
 #pragma unroll
         for (int i = 0; i < NMH; ++i) {            // second k-step's operands under these MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, (NR + (C::MX ? C::TM + C::TN : 0) + NMH - 1) / NMH, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NR + NMH - 1) / NMH, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
 #pragma unroll
         for (int i = 0; i < C::A_INSTR; ++i) dma_load16(ga, c.a_off[i], d + i * C::NW * 1024);
-        if constexpr (C::MX) mma_frags_mx<C, 0, H, C::TN>(f0, sc, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 0, H, C::TN>(f0, *carried, acc);
         else mma_frags<C, H, C::TN>(f0, acc);
 #pragma unroll
         for (int i = 0; i < C::B_INSTR; ++i) dma_load16(gb, c.b_off[i], d + C::A_BYTES + i * C::NW * 1024);
@@ -336,12 +337,16 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
             dma_load4(scalar_ptr(gs), c.s_off, ds);
         }
         load_frags<C>(c, nxt, 0, f0);
-        if constexpr (C::MX) mma_frags_mx<C, 16>(f1, sc, acc);
+        if constexpr (C::MX) mma_frags_mx<C, 16>(f1, *carried, acc);
         else mma_frags<C>(f1, acc);
 #pragma unroll
         for (int i = 0; i < 2 * NMH; ++i) {        // next tile's first operands under these MFMAs
             if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        if constexpr (C::MX) {
+            __builtin_amdgcn_sched_barrier(0);     // behind the step's last matrix instruction
+            load_scales<C>(c, nxt, *carried);
         }
         return;
     }
@@ -480,10 +485,12 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) issue_stage<C>(ctx, ga(s), gb(s), stage[s], gs(s));
     Frags<C> f0;
+    Scales<C> sc;
     if constexpr (C::PF) {
         wait_vmcnt<(NS - 2) * C::LOADS>();   // tile 0 has landed
         block_barrier();
         load_frags<C>(ctx, stage[0], 0, f0);
+        if constexpr (C::MX) load_scales<C>(ctx, stage[0], sc);
     }
 
     int64_t kt = 0;
@@ -491,14 +498,14 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
 #pragma unroll
         for (int s = 0; s < NS; ++s)
             ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
-                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1));
+                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1), &sc);
     }
     // the last nk % NS tiles, same stage order
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (kt + s < nk)
             ring_step<C>(ctx, ga(kt + s + NS - 1), gb(kt + s + NS - 1), stage[(s + NS - 1) % NS], stage[s],
-                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1));
+                         stage[(s + 1) % NS], f0, acc, gs(kt + s + NS - 1), &sc);
     wait_vmcnt<0>();
     __syncthreads();                         // every load has landed, every wave is done with the stages
 
