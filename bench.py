@@ -79,6 +79,7 @@ ATTN_SRC = ("kernel_attention.hip", "epilogue.hpp")
 TRANSPOSE_SRC = ("kernel_transpose.hip",)
 SKINNY_RC_SRC = ("kernel_skinny_rc.hpp", "kernel_skinny_rc.hip", "epilogue.hpp")
 RING_F8_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f8_rc.hip", "epilogue.hpp")
+RING_BF8_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_bf8_rc.hip", "epilogue.hpp")
 ROWS_SRC = ("kernel_rows.hip", "epilogue.hpp")
 RING_F4_SRC = ("kernel_tile_ring.hpp", "ring_instances.inc", "ring_f4_rc.hip", "epilogue.hpp")
 XA_SRC = ("kernel_transpose.hip",) + RING_SRC
@@ -88,57 +89,59 @@ MX_SRC = ("kernel_mx.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
     ("c1_f32_256_relu", "skinny_f32_dma_wk8_cg1_ns2_nt1"):
-        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "c0c7540508f0c86e"},
+        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "8b5d6ba6ca35f499"},
     ("c2_f32_skinny16_silu", "skinny_f32_dma_wk4_cg2_ns2_nt1"):
-        {"bytes": int((531015.5 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "c0c7540508f0c86e"},
+        {"bytes": int((531018.0 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "8b5d6ba6ca35f499"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((385170.1 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "bc649ac3034b36b7"},
+        {"bytes": int((385106.4 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "58ac71ac4f6258e6"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((797183.1 * 2.0 + 131086.6) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
+        {"bytes": int((791532.0 * 2.0 + 131244.2) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((799517.1 * 2.0 + 131073.2) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
+        {"bytes": int((797056.1 * 2.0 + 131098.1) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
     ("c5_bf16_batched32_relu", "ring_bf16_rr_128x256_w1x4_ns3"):
-        {"bytes": int((65925.1 * 2.0 + 262163.2) * 1024), "files": RING_SRC, "src": "3c70b49c2b984f21"},
+        {"bytes": int((65943.5 * 2.0 + 262198.3) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
-        {"bytes": int((266405.5 * 2.0 + 4608.0) * 1024), "files": SKINNY16_SRC, "src": "5f550a775ce04ec2"},
+        {"bytes": int((265884.5 * 2.0 + 3584.0) * 1024), "files": SKINNY16_SRC, "src": "8bfc9340f295391f"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393471.6 * 2.0 + 131087.7) * 1024), "files": RING_F8_SRC, "src": "594ff026bec2b866"},
+        {"bytes": int((393472.1 * 2.0 + 131094.4) * 1024), "files": RING_F8_SRC, "src": "c62e8c9004a79794"},
     ("c4_f4_8192_rc_silu", "ring_f4_rc_256x256_w2x4_ns5_pf"):
-        {"bytes": int((196876.3 * 2.0 + 131193.5) * 1024), "files": RING_F4_SRC, "src": "ca0c60068aaee75e"},
+        {"bytes": int((196876.0 * 2.0 + 131280.4) * 1024), "files": RING_F4_SRC, "src": "68ca9c801dc0c9ab"},
     ("c4_bf16_8192_cr_silu", "xa_ring"):
-        {"bytes": int((862588.7 * 2.0 + 262249.1) * 1024), "files": XA_SRC, "src": "1f3589c2d44153ad"},
+        {"bytes": int((856812.0 * 2.0 + 262389.3) * 1024), "files": XA_SRC, "src": "77f6b0e72e841e55"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((534587.3 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "3fb2db49cb369908"},
+        {"bytes": int((534591.6 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "c1f42016ecdfaaad"},
     ("s_relu", "s_relu"):
-        {"bytes": int((524309.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+        {"bytes": int((524309.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
     ("s_sigmoid", "s_sigmoid"):
-        {"bytes": int((524325.0 * 2.0 + 1048576.8) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+        {"bytes": int((524325.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
     ("s_sum", "s_sum"):
-        {"bytes": int((524397.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+        {"bytes": int((524397.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
     ("s_dot", "s_dot"):
-        {"bytes": int((1048623.7 * 2.0 + 128.4) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+        {"bytes": int((1048623.7 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
     ("s_mse", "s_mse"):
-        {"bytes": int((1048626.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "d2e92f5b84052fbd"},
+        {"bytes": int((1048626.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
     ("s_transpose", "s_transpose"):
-        {"bytes": int((524319.6 * 2.0 + 1048869.8) * 1024), "files": TRANSPOSE_SRC, "src": "fed67c2f38f8f735"},
+        {"bytes": int((524319.6 * 2.0 + 1048880.6) * 1024), "files": TRANSPOSE_SRC, "src": "4c8326c86e66e7ac"},
     ("s_ce", "s_ce"):
-        {"bytes": int((524976.0 * 2.0 + 64.2) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
+        {"bytes": int((525007.3 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((527803.6 * 2.0 + 1053812.6) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
+        {"bytes": int((527804.2 * 2.0 + 1053808.9) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
     ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524319.5 * 2.0 + 1048590.7) * 1024), "files": ROWS_SRC, "src": "ce0d9313e72c9f5c"},
+        {"bytes": int((524319.5 * 2.0 + 1048588.9) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
     ("s_mhsa", "mhsa_pingpong_bf16_dk128"):
-        {"bytes": int((98427.0 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "49041109d0e68a34"},
+        {"bytes": int((98427.0 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "b07642d29737a3e9"},
     ("s_lce", "ring_bf16_rr_lse"):
-        {"bytes": int((1590398.4 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "b9562500d67cc396"},
+        {"bytes": int((1590397.4 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "b6551c90607c0565"},
     ("s_lce_f32", "ring_f32_rr_lse"):
-        {"bytes": int((1583708.5 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "42fcb04da4dd9fa6"},
+        {"bytes": int((1583577.7 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "cbf4ed219c4c97d3"},
     ("s_gln", "ring_bf16_rr_ln"):
-        {"bytes": int((541155.5 * 2.0 + 401408.8) * 1024), "files": GLN_SRC, "src": "439417ce7d7660e4"},
+        {"bytes": int((541088.3 * 2.0 + 401408.2) * 1024), "files": GLN_SRC, "src": "68bdab067cf959df"},
     ("s_gln_f32", "ring_f32_rr_ln"):
-        {"bytes": int((427086.4 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "beec9390eec9dce1"},
+        {"bytes": int((427088.0 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "9e667470c976f393"},
     ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4_pf"):
-        {"bytes": int((209165.7 * 2.0 + 131249.1) * 1024), "files": MX_SRC, "src": "804c9bc72f21a026"},
+        {"bytes": int((211248.9 * 2.0 + 135286.1) * 1024), "files": MX_SRC, "src": "c05c3cc9af7f96e1"},
+    ("c4_bf8_8192_rc_silu", "ring_bf8_rc_256x256_w2x4_ns5_k64"):
+        {"bytes": int((393471.7 * 2.0 + 131112.8) * 1024), "files": RING_BF8_SRC, "src": "089cb107d2a38c30"},
 }
 
 
