@@ -89,9 +89,9 @@ MX_SRC = ("kernel_mx.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
     ("c1_f32_256_relu", "skinny_f32_dma_wk8_cg1_ns2_nt1"):
-        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "8b5d6ba6ca35f499"},
+        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "18ab754f30462bbb"},
     ("c2_f32_skinny16_silu", "skinny_f32_dma_wk4_cg2_ns2_nt1"):
-        {"bytes": int((531018.0 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "8b5d6ba6ca35f499"},
+        {"bytes": int((531023.9 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "18ab754f30462bbb"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
         {"bytes": int((385106.4 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "58ac71ac4f6258e6"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
@@ -101,7 +101,7 @@ TRAFFIC = {
     ("c5_bf16_batched32_relu", "ring_bf16_rr_128x256_w1x4_ns3"):
         {"bytes": int((65943.5 * 2.0 + 262198.3) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
-        {"bytes": int((265884.5 * 2.0 + 3584.0) * 1024), "files": SKINNY16_SRC, "src": "8bfc9340f295391f"},
+        {"bytes": int((265884.5 * 2.0 + 3584.0) * 1024), "files": SKINNY16_SRC, "src": "68f5be84ca4adfcf"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393472.1 * 2.0 + 131094.4) * 1024), "files": RING_F8_SRC, "src": "c62e8c9004a79794"},
     ("c4_f4_8192_rc_silu", "ring_f4_rc_256x256_w2x4_ns5_pf"):
@@ -139,7 +139,7 @@ TRAFFIC = {
     ("s_gln_f32", "ring_f32_rr_ln"):
         {"bytes": int((427088.0 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "9e667470c976f393"},
     ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4_pf"):
-        {"bytes": int((211248.9 * 2.0 + 135286.1) * 1024), "files": MX_SRC, "src": "c05c3cc9af7f96e1"},
+        {"bytes": int((211259.7 * 2.0 + 135210.9) * 1024), "files": MX_SRC, "src": "54bc4bf2c108b92b"},
     ("c4_bf8_8192_rc_silu", "ring_bf8_rc_256x256_w2x4_ns5_k64"):
         {"bytes": int((393471.7 * 2.0 + 131112.8) * 1024), "files": RING_BF8_SRC, "src": "089cb107d2a38c30"},
 }

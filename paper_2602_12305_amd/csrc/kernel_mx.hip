@@ -113,6 +113,7 @@ hipError_t launch_mx(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda
         unsigned int *tA = static_cast<unsigned int *>(ws), *tB = tA + M * nk;
         const ScaleCopy ca{static_cast<const unsigned char *>(scaleA), lds_a, M, tA}, cb{static_cast<const unsigned char *>(scaleB), lds_b, N, tB};
         const int64_t rows = M > N ? M : N;
+        if ((nk + 63) / 64 > 65535) return hipErrorInvalidValue;
         hipLaunchKernelGGL(mx_scale_tiles_kernel, dim3((unsigned)((rows + 63) / 64), (unsigned)((nk + 63) / 64), 2), dim3(256), 0, stream, ca, cb, nk);
         e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -513,6 +513,7 @@ hipError_t skinny_dma_launch(const Problem &p, hipStream_t stream)
         if (e != hipSuccess) return e;
         sp.partial = static_cast<float *>(ws);
     }
+    if ((p.N + COLS - 1) / COLS > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)((p.N + COLS - 1) / COLS), (unsigned)split, (unsigned)(p.batch * sp.row_blocks));
     hipLaunchKernelGGL((skinny_dma_kernel<WK, CG, NS, NT>), grid, dim3(64 * WK), LDS_BYTES, stream, sp);
     hipError_t e = hipGetLastError();
