@@ -235,7 +235,7 @@ def f4e2m1_codes_to_f32(codes: np.ndarray) -> np.ndarray:
 def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
     """Block-scaled storage of an fp32 matrix [rows, K] in the way of the OCP microscaling formats: every `block`
     consecutive elements of a row share an E8M0 scale 2^(floor(log2(max |x|)) - emax) with emax the largest exponent of
-    the element type (2 for E2M1, 8 for E4M3), and the elements are x / scale rounded to that type.  Returns (stored
+    the element type (2 for E2M1, 8 for E4M3, 15 for E5M2), and the elements are x / scale rounded to that type.  Returns (stored
     elements as to_bits would give them, scale codes uint8 [rows, ceil(K / block)]).  An all-zero block gets scale code 127."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     rows, K = x.shape
@@ -243,12 +243,14 @@ def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
     pad = np.zeros((rows, nb * block), dtype=np.float32)
     pad[:, :K] = x
     amax = np.abs(pad.reshape(rows, nb, block)).max(axis=2)
-    emax = 2 if dtype == DTYPE_F4E2M1 else 8
+    emax = {DTYPE_F4E2M1: 2, DTYPE_F8E5M2: 15}.get(dtype, 8)
     with np.errstate(divide="ignore"):
         e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - emax, 0.0)
     e = np.clip(e, -127, 127)
     scale = np.exp2(e).astype(np.float32)
     q = (pad.reshape(rows, nb, block) / scale[:, :, None]).reshape(rows, nb * block)[:, :K]
+    if dtype == DTYPE_F8E5M2:
+        q = np.clip(q, -57344.0, 57344.0)                # saturating conversion, as the other two encoders do by themselves
     return to_bits(q, dtype), (e + 127).astype(np.uint8)
 
 

@@ -327,7 +327,7 @@ int oracle_num_threads(void)
  * Block-scaled operands (the OCP microscaling formats): every 32 consecutive k of a row of A and of a column
  * of B share one E8M0 scale,
  *     z_ij = bias_j + sum_k (sA[i][k / 32] a_ik) (sB[j][k / 32] b_kj),   y_ij = act(z_ij),
- * with a, b in E4M3 or E2M1 storage (dtype), decoded exactly; a scaled element is a power of two times a
+ * with a, b in E4M3, E5M2 or E2M1 storage (dtype), decoded exactly; a scaled element is a power of two times a
  * short significand, exact in fp64, and so is every product; one fp64 accumulator per output, k ascending,
  * bias after the sum.  scaleA is [M][ceil(K / 32)], scaleB [N][ceil(K / 32)] (row-major bytes); A and B in
  * the layouts of oracle_gemm_epilogue, leading dimensions in elements.  Y fp64 [M][N].
@@ -337,7 +337,7 @@ int oracle_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int6
                             const void *B, int64_t ldb, const uint8_t *scaleB, const float *bias, double *Y,
                             int layout, int dtype, int act)
 {
-    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 || (dtype != ORACLE_F8E4M3 && dtype != ORACLE_F4E2M1) ||
+    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 || (dtype != ORACLE_F8E4M3 && dtype != ORACLE_F4E2M1 && dtype != ORACLE_F8E5M2) ||
         act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;

@@ -10,7 +10,7 @@ import pytest
 import oracle
 from inputs import synth
 
-F4, F8 = oracle.F4E2M1, oracle.F8E4M3
+F4, F8, BF8 = oracle.F4E2M1, oracle.F8E4M3, oracle.F8E5M2
 TABLE = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]       # the OCP E2M1 magnitudes by code (sign in bit 3)
 
 
@@ -71,9 +71,9 @@ def test_one_hot_operands_make_the_nibble_order_visible():
     assert np.array_equal(got, Bf.astype(np.float64))
 
 
-@pytest.mark.parametrize("dtype", [F4, F8])
+@pytest.mark.parametrize("dtype", [F4, F8, BF8])
 def test_block_scaled_contraction(dtype):
-    sd = synth.DTYPE_F4E2M1 if dtype == F4 else synth.DTYPE_F8E4M3
+    sd = {F4: synth.DTYPE_F4E2M1, F8: synth.DTYPE_F8E4M3, BF8: synth.DTYPE_F8E5M2}[dtype]
     M, N, K = 5, 6, 80                                                          # two and a half blocks of 32
     A = synth.normal(91, "A", M, K) * np.float32(50.0); B = synth.normal(91, "B", K, N) * np.float32(0.01)
     Aq, sA = synth.mx_quantize(A, sd); Bq, sB = synth.mx_quantize(np.ascontiguousarray(B.T), sd)       # B stored [N][K]
@@ -90,7 +90,7 @@ def test_block_scaled_contraction(dtype):
             assert got[i, j] == pytest.approx(max(float(z), 0.0), rel=1e-14, abs=1e-300)
     # the quantised operands are close to what was quantised (the scales are the right powers of two)
     back = Ad * np.exp2(sA.astype(np.float64) - 127).repeat(32, axis=1)[:, :K]
-    assert np.max(np.abs(back - A)) <= (0.26 if dtype == F4 else 0.07) * np.abs(A).max()
+    assert np.max(np.abs(back - A)) <= {F4: 0.26, F8: 0.07, BF8: 0.13}[dtype] * np.abs(A).max()
     # unit scales: the unscaled contraction of the same stored elements
     one = np.full_like(sA, 127); oneB = np.full_like(sB, 127)
     plain = oracle.gemm_epilogue(Aq, Bq, bias, M, N, K, dtype=dtype, layout=oracle.LAYOUT_RC, act=oracle.ACT_RELU)[0]
@@ -106,7 +106,7 @@ def test_block_scaled_contraction(dtype):
     zn = oracle.gemm_epilogue_mx(Aq, bad, Bq, oneB, None, M, N, K, dtype=dtype)
     assert np.all(np.isnan(zn[4])) and not np.any(np.isnan(zn[:4]))
     # other layouts address the same elements: A column-major, B row-major
-    if dtype == F8:
+    if dtype != F4:
         At = np.ascontiguousarray(Aq.T); Bt = np.ascontiguousarray(Bq.T)
         assert np.array_equal(oracle.gemm_epilogue_mx(At, sA, Bt, sB, bias, M, N, K, dtype=dtype, layout=oracle.LAYOUT_CR,
                                                       act=oracle.ACT_RELU), got)
