@@ -13,7 +13,7 @@ the breadth workloads (other storage types and layouts on the same shapes) and t
 element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats (s_relu, s_sigmoid, s_sum, s_dot,
 s_mse), transpose (s_transpose), cross-entropy and LayerNorm (s_ce, s_ln_sample, s_ln_token),
 attention (s_mhsa), the contraction fused with the cross-entropy (s_lce, s_lce_f32) and with
-LayerNorm (s_gln, s_gln_f32), the block-scaled 4-bit contraction (s_mxf4).  Any of these names can be the headline.  One JSON line is printed.
+LayerNorm (s_gln, s_gln_f32), the block-scaled 4-bit and 8-bit contractions (s_mxf4, s_mxf8).  Any of these names can be the headline.  One JSON line is printed.
 
 The "roofline" object prices the dominant kernel of a workload against the published MI355X peak
 (HBM 8 TB/s, dense bf16 / fp16 MFMA 2516.6 TFLOP/s, fp8 5033.2, fp4 10066.3, fp32 MFMA 157.3) using algorithmic
@@ -59,8 +59,8 @@ MHSA = {"s_mhsa": (4, 4096, 2048, 16)}
 LCE = {"s_lce": (8192, 32768, 4096, 1), "s_lce_f32": (4096, 32768, 2048, 0)}
 # contraction fused with LayerNorm over each row of the product, B row-major: (M, N, K, dtype)
 GLN = {"s_gln": (8192, 8192, 4096, 1), "s_gln_f32": (4096, 4096, 4096, 0)}
-# contraction on block-scaled (E8M0 per 32 k) E2M1 operands, k contiguous in both, SiLU: (M, N, K)
-MXF4 = {"s_mxf4": (8192, 8192, 8192)}
+# contraction on block-scaled (E8M0 per 32 k) E2M1 or E4M3 operands, k contiguous in both, SiLU: (M, N, K, dtype)
+MXF4 = {"s_mxf4": (8192, 8192, 8192, 4), "s_mxf8": (8192, 8192, 8192, 3)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB summed over the kernels of one step, scaled by what the same counters read for the
@@ -530,31 +530,34 @@ def main():
                     float(np.max(np.abs(got - ref))))
 
     class Mx(Case):
-        """Block-scaled E2M1 contraction: N(0, 1) operands whose 32-blocks vary in magnitude over 2^+-3, quantised block
-        by block (scale = the block's largest magnitude brought into E2M1's range), bias N(0, 1), SiLU."""
-        bound, dtype = "mfma", 4
+        """Block-scaled E2M1 or E4M3 contraction: N(0, 1) operands whose 32-blocks vary in magnitude over 2^+-3, quantised
+        block by block (scale = the block's largest magnitude brought into the element type's range), bias N(0, 1), SiLU."""
+        bound = "mfma"
 
         def __init__(self, name):
-            self.name, self.kernel = name, "ring_mxf4_rc_256x256_w2x4_ns4_pf"
-            M, N, K = self.shape = MXF4[name]
+            M, N, K, self.dtype = MXF4[name]
+            self.shape = (M, N, K)
+            self.name = name
+            self.kernel = "ring_mxf4_rc_256x256_w2x4_ns4_pf" if self.dtype == 4 else "ring_mxf8_rc_256x256_w2x4_ns4_k64"
+            self.per = 2 if self.dtype == 4 else 1            # elements per stored byte
             def operand(tag, rows):
                 x = synth.normal(17, tag, rows, K)
                 e = synth.integers(18, tag + "e", rows, K // 32, -3, 3)
-                return synth.mx_quantize(x * np.repeat(np.exp2(e), 32, axis=1).astype(np.float32), 4)
+                return synth.mx_quantize(x * np.repeat(np.exp2(e), 32, axis=1).astype(np.float32), self.dtype)
             (self.A, self.sA), (self.B, self.sB) = operand("A", M), operand("B", N)
             self.bias = synth.normal(17, "bias", 1, N)[0]
             self.dev = [torch.from_numpy(np.ascontiguousarray(h)).cuda() for h in (self.A, self.sA, self.B, self.sB, self.bias)]
             self.C = torch.empty((M, N), dtype=torch.int16, device="cuda")
             Ad, sAd, Bd, sBd, bd = self.dev
-            assert ob.optiml_gemm_epilogue_mx_path(M, N, K, Ad, K, sAd, K // 32, Bd, K, sBd, K // 32, bd, self.C, N) == 0
+            assert ob.optiml_gemm_epilogue_mx_path(M, N, K, Ad, K, sAd, K // 32, Bd, K, sBd, K // 32, bd, self.C, N, self.dtype) == 0
             self.flops = 2.0 * M * N * K
-            self.nbytes = float((M + N) * (K // 2 + K // 32) + 2 * M * N + 4 * N)
+            self.nbytes = float((M + N) * (K // self.per + K // 32) + 2 * M * N + 4 * N)
             self.config = {"M": M, "N": N, "K": K, "layout": "rc", "act": "silu", "block": 32}
 
         def step(self, i):
             M, N, K = self.shape
             Ad, sAd, Bd, sBd, bd = self.dev
-            ob.optiml_gemm_epilogue_mx(M, N, K, Ad, K, sAd, K // 32, Bd, K, sBd, K // 32, bd, self.C, N, 4, 3)
+            ob.optiml_gemm_epilogue_mx(M, N, K, Ad, K, sAd, K // 32, Bd, K, sBd, K // 32, bd, self.C, N, self.dtype, 3)
 
         def check(self):
             import oracle
@@ -563,7 +566,7 @@ def main():
             t0 = time.perf_counter()
             take = lambda a, i: np.ascontiguousarray(a[i])
             ref = oracle.gemm_epilogue_mx(take(self.A, rows), take(self.sA, rows), take(self.B, cols), take(self.sB, cols),
-                                          self.bias[cols], len(rows), len(cols), K, dtype=4, act=3)
+                                          self.bias[cols], len(rows), len(cols), K, dtype=self.dtype, act=3)
             secs = time.perf_counter() - t0
             got = synth.bf16_bits_to_f32(self.C.cpu().numpy().view(np.uint16)[np.ix_(rows, cols)]).astype(np.float64)
             rho = float(np.sqrt(np.mean(ref * ref)))

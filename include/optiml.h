@@ -381,22 +381,24 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
                 void *O, int dtype, void *stream);
 
 /*
- * The contraction on block-scaled ("microscaling") 4-bit operands, the form the scaled matrix instructions of this
+ * The contraction on block-scaled ("microscaling") operands, the form the scaled matrix instructions of this
  * hardware take (one of the low-precision formats of the hot path's breadth row; the paper names none):
  *     C[i][j] = act( sum_k (sA[i][k/32] a[i][k]) (sB[j][k/32] b[j][k]) + bias[j] )
- * A is M x K row-major and B is N x K (column-major B: k contiguous in both), elements OPTIML_F4E2M1, two to a byte
- * along k as in the plain contraction; lda, ldb >= K count elements and must be even.  Every 32 consecutive k of a
- * row of A (a column of B) share one scale, a power of two stored as an OCP E8M0 byte: scaleA[i * lds_a + k / 32],
- * scaleB[j * lds_b + k / 32], value 2^(byte - 127), byte 255 = NaN; lds_a, lds_b >= K / 32 count bytes.  K must be
- * a multiple of 32.  C is M x N bfloat16, row-major, ldc >= N; bias (N floats) may be NULL; act as above.  All
- * pointers DEVICE.  Products are exact, block sums are scaled exactly and accumulated in fp32; C is rounded once.
- * dtype must be OPTIML_F4E2M1.  M == 0 or N == 0 writes nothing; K == 0 gives act(bias).
- * optiml_gemm_epilogue_mx_path: 0 when the call would run on the matrix-pipe tile kernel (K a multiple of 128,
- * 16-byte aligned operands and rows, at least 65536 entries of C; any address and pitch of the scales), 1 for the
- * one-thread-per-entry kernel, or an error.  The tile kernel keeps a copy of the scales, (M + N) K / 32 bytes, in
- * the workspace (see Workspace above); the other kernel needs none.
- * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd or too small lda / ldb, lds_a or
- * lds_b < K / 32, ldc < N, another dtype, unknown act, a NULL pointer with work to do.
+ * A is M x K row-major and B is N x K (column-major B: k contiguous in both).  dtype is OPTIML_F4E2M1 (two elements to
+ * a byte along k as in the plain contraction; lda, ldb >= K count elements and must be even), OPTIML_F8E4M3 or
+ * OPTIML_F8E5M2 (one element to a byte).  Every 32 consecutive k of a row of A (a column of B) share one scale, a
+ * power of two stored as an OCP E8M0 byte: scaleA[i * lds_a + k / 32], scaleB[j * lds_b + k / 32], value
+ * 2^(byte - 127), byte 255 = NaN; lds_a, lds_b >= K / 32 count bytes.  K must be a multiple of 32.  C is M x N
+ * bfloat16, row-major, ldc >= N; bias (N floats) may be NULL; act as above.  All pointers DEVICE.  Products are exact;
+ * block sums are scaled exactly and accumulated in fp32 (E2M1: the block sums themselves are exact too); C is
+ * rounded once.  M == 0 or N == 0 writes nothing; K == 0 gives act(bias).
+ * optiml_gemm_epilogue_mx_path: 0 when the call would run on the matrix-pipe tile kernel (K a multiple of 128 for
+ * E2M1, of 64 for the 8-bit types; 16-byte aligned operands and rows; at least 65536 entries of C; any address and
+ * pitch of the scales), 1 for the one-thread-per-entry kernel, or an error.  The tile kernel keeps a copy of the
+ * scales, (M + N) K / 32 bytes for E2M1 and (M + N) K / 16 for the 8-bit types, in the workspace (see Workspace
+ * above); the other kernel needs none.
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd (E2M1) or too small lda / ldb, lds_a
+ * or lds_b < K / 32, ldc < N, another dtype, unknown act, a NULL pointer with work to do.
  */
 int optiml_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
                             int64_t ldb, const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc, int dtype, int act,

@@ -853,8 +853,8 @@ int optiml_set_workspace(void *ptr, int64_t bytes)
 static int mx_validate(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
                        int64_t ldb, const void *scaleB, int64_t lds_b, void *C, int64_t ldc, int dtype, int act)
 {
-    if (dtype != DT_F4 || act < 0 || act > 3 || M < 0 || N < 0 || K < 0 || K % 32 != 0) return OPTIML_ERR_INVALID_ARG;
-    if (lda < 0 || ldb < 0 || ldc < 0 || lds_a < 0 || lds_b < 0 || (lda & 1) || (ldb & 1)) return OPTIML_ERR_INVALID_ARG;
+    if (!is_8bit(dtype) || act < 0 || act > 3 || M < 0 || N < 0 || K < 0 || K % 32 != 0) return OPTIML_ERR_INVALID_ARG;
+    if (lda < 0 || ldb < 0 || ldc < 0 || lds_a < 0 || lds_b < 0 || (dtype == DT_F4 && ((lda & 1) || (ldb & 1)))) return OPTIML_ERR_INVALID_ARG;
     constexpr int64_t kMaxSpan = int64_t(1) << 47;
     if (M >= kMaxSpan / (lda + 1) || N >= kMaxSpan / (ldb + 1) || M >= kMaxSpan / (ldc + 1)) return OPTIML_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return OPTIML_OK;
@@ -869,7 +869,7 @@ int optiml_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int6
 {
     const int st = mx_validate(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, C, ldc, dtype, act);
     if (st != OPTIML_OK || M == 0 || N == 0) return st;
-    return status_of(optiml::launch_mx(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc, act,
+    return status_of(optiml::launch_mx(dtype, M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc, act,
                                        static_cast<hipStream_t>(stream)));
 }
 
@@ -879,7 +879,7 @@ int optiml_gemm_epilogue_mx_path(int64_t M, int64_t N, int64_t K, const void *A,
 {
     const int st = mx_validate(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, C, ldc, dtype, 0);
     if (st != OPTIML_OK) return st;
-    return optiml::mx_path(M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc);
+    return optiml::mx_path(dtype, M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc);
 }
 
 void optiml_set_wait_limit(int64_t clocks) { optiml::set_wait_limit((long long)clocks); }

@@ -124,11 +124,11 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
                                 hipStream_t stream);
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
 void set_wait_limit(long long clocks);
-// kernel_mx.hip: the contraction on block-scaled E2M1 operands (K, lda, ldb in elements; scales one E8M0 byte per
+// kernel_mx.hip: the contraction on block-scaled E2M1, E4M3 or E5M2 operands (dtype; K, lda, ldb in elements; scales one E8M0 byte per
 // 32 elements of k, pitches lds_a, lds_b in bytes)
-int mx_path(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B, int64_t ldb,
+int mx_path(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B, int64_t ldb,
             const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc);
-hipError_t launch_mx(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
+hipError_t launch_mx(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
                      int64_t ldb, const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc, int act, hipStream_t stream);
 // kernel_linear_ln.hip: unrounded fp32 products of p.batch 16-bit problems by the ring kernel (used to split a
 // contraction along k); `pairs` needs 2 * 4 * ceil(N / 256) * M floats per batch

@@ -100,6 +100,22 @@ template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32
 #endif
 }
 
+// The same with block scales: byte 0 of sa / sb is an E8M0 scale of this lane's row of the first / second operand,
+// in lanes 0-31 that of k 0-31 of the 64, in lanes 32-63 that of k 32-63
+template <int DT, class V4, class ACC>
+__device__ __forceinline__ ACC mfma_32x32x64_f8_scaled(V4 a_lo, V4 a_hi, V4 b_lo, V4 b_hi, ACC c, unsigned sa, unsigned sb)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef int intx8_ __attribute__((ext_vector_type(8)));
+    const intx8_ a = intx8_{(int)a_lo[0], (int)a_lo[1], (int)a_lo[2], (int)a_lo[3], (int)a_hi[0], (int)a_hi[1], (int)a_hi[2], (int)a_hi[3]};
+    const intx8_ b = intx8_{(int)b_lo[0], (int)b_lo[1], (int)b_lo[2], (int)b_lo[3], (int)b_hi[0], (int)b_hi[1], (int)b_hi[2], (int)b_hi[3]};
+    if constexpr (DT == DT_BF8) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 1, 1, 0, (int)sa, 0, (int)sb);
+    else return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, (int)sa, 0, (int)sb);
+#else
+    return c;
+#endif
+}
+
 // fp32 -> bf16 bits, round to nearest even; NaN stays a (quiet) NaN
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
 {

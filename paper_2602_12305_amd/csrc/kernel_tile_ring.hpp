@@ -71,7 +71,8 @@ struct Cfg {
     // register of that lane.  The scales of a k-tile (four blocks = one dword per row) travel with the tile: one more
     // LDS-DMA load per wave and stage (4 bytes a lane) into 2 KiB behind the B tile.
     static constexpr bool MX = MX_;
-    static_assert(!MX_ || (DT_ == DT_F4 && B_KC_ && PF_ && !K64_ && EPI_ == 0 && WM_ == 2 && WN_ == 4), "block scales: the 2 x 4 E2M1 kernel with fragment prefetch");
+    static_assert(!MX_ || (B_KC_ && EPI_ == 0 && WM_ == 2 && WN_ == 4 && ((DT_ == DT_F4 && PF_ && !K64_) || (is_f8(DT_) && K64_))),
+                  "block scales: the 2 x 4 E2M1 kernel with fragment prefetch, or the 64-deep 8-bit kernel");
     // WM = 1: a 128 x 256 block computed by four waves (1 x 4, the same 128 x 64 wave tile) with 24 KiB
     // stages; with NS = 3 two such workgroups share a CU (144 KiB of LDS, at most 256 registers a lane),
     // so that one's first loads and epilogue run under the other's k loop: for many short tiles.
@@ -355,7 +356,17 @@ __device__ __forceinline__ void ring_step(const Ctx<C> &c, const char *__restric
     {
         load_frags<C>(c, rd, 0, f0);
         load_frags<C>(c, rd, 1, f1);
-        if constexpr (C::K64) {
+        if constexpr (C::K64 && C::MX) {
+            // block scales: lanes 0-31 supply the scale of the k-tile's first block, lanes 32-63 that of the second
+            // (byte 0 of the shifted dword); the first operand is B's
+            Scales<C> sc;
+            load_scales<C>(c, rd, sc);
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i)
+                    acc[j][i] = mfma_32x32x64_f8_scaled<C::DT>(f0.b[j], f1.b[j], f0.a[i], f1.a[i], acc[j][i], sc.b[j], sc.a[i]);
+        } else if constexpr (C::K64) {
             // both 16-byte fragments of a row are one 32-byte operand: 64 values of k (which value
             // sits in which byte only has to agree between the two operands)
 #pragma unroll
@@ -446,6 +457,10 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.0f;
 
     const int frag_row = lane & 31, half = lane >> 5;
+    // fragment s of this lane is chunk 2 s + half of the row's 64 bytes.  (Block scales on 8-bit operands: the
+    // 64-deep instruction takes the scale of k 0-31 from lanes 0-31 and that of k 32-63 from lanes 32-63, and reads
+    // k 16 half .. + 15 from a lane's first four registers and k 32 + 16 half .. + 15 from its last four - which is
+    // this very assignment; the tests with one-hot rows and single scale bytes changed pin it.)
 #pragma unroll
     for (int s = 0; s < 2; ++s) ctx.a_frag[s] = frag_row * 64 + (((2 * s + half) ^ ((frag_row >> 2) & 3)) << 4);
     ctx.a_wave = wm * C::WTM * 64;
@@ -512,7 +527,7 @@ __global__ __launch_bounds__(C::THREADS, C::MIN_WAVES_PER_SIMD) void gemm_ring_k
     // A K that ends inside a k-tile: the last, partial k-tile goes through stage 0 by ordinary
     // loads, 16-byte chunks at or beyond K written as zeros (K is a whole number of chunks), in
     // the places the DMA loads of a full tile would have filled.
-    if (p.K % C::BKE != 0) {
+    if (!C::MX && p.K % C::BKE != 0) {                       // (block scales: whole k-tiles only)
         constexpr int CHE = 16 / C::ES;                          // elements per chunk
         const int64_t k0 = nk * C::BKE;
         lds_char *const t0 = (lds_char *)st0;

@@ -331,7 +331,7 @@ def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
         return (L.optiml_gemm_epilogue_mx(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype, act, None),
                 L.optiml_gemm_epilogue_mx_path(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype))
     for kw in (dict(M=-1), dict(K=-32), dict(K=48), dict(lda=510), dict(lda=513), dict(ldb=511), dict(lds_a=15), dict(lds_b=3), dict(ldc=511),
-               dict(dtype=3), dict(dtype=1), dict(A=None), dict(B=None), dict(sA=None), dict(sB=None), dict(C=None)):
+               dict(dtype=6), dict(dtype=2), dict(dtype=1), dict(A=None), dict(B=None), dict(sA=None), dict(sB=None), dict(C=None)):
         assert call(**kw)[1] == ob.ERR_INVALID_ARG, kw
     assert call(act=7)[0] == ob.ERR_INVALID_ARG
     assert call(M=0, A=None, C=None)[0] == ob.OK and call(N=0)[0] == ob.OK                # nothing to do
@@ -340,3 +340,5 @@ def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
     assert call(A=P + 2)[1] == 1                                                          # an address the wide loads cannot take
     assert call(sA=P + 1)[1] == 0 and call(lds_a=18)[1] == 0                              # the scales are copied first: any address and pitch
     assert call(lda=514)[1] == 1
+    assert call(dtype=3)[1] == 0 and call(dtype=5)[1] == 0 and call(dtype=3, K=320)[1] == 0      # 8-bit elements: k-tiles of 64
+    assert call(dtype=3, K=480)[1] == 1 and call(dtype=5, K=192)[1] == 1 and call(dtype=3, lda=513)[1] == 1   # (odd pitches are valid there)
