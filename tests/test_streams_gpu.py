@@ -166,10 +166,11 @@ def test_runs_on_a_side_stream():
 @pytest.mark.parametrize("dtype", [np.float32, np.uint16])
 @pytest.mark.parametrize("rows,cols,pad_src,pad_dst", [(1, 1, 0, 0), (64, 64, 0, 0), (200, 136, 0, 0), (77, 131, 0, 0), (1000, 8, 8, 16),
                                                       (5, 3000, 3, 1), (1, 4096, 0, 0), (4096, 1, 0, 0), (520, 1032, 8, 8),
-                                                      (2104, 4208, 0, 8)])
+                                                      (2104, 4208, 0, 8), (4104, 16400, 0, 8)])
 def test_transpose_is_bit_exact(dtype, rows, cols, pad_src, pad_dst):
     """Table 4 task 8: every element at its mirror position, bit for bit (16-bit patterns include NaNs), padding untouched;
-    aligned shapes take the vectorised kernel, the others the element-wise one."""
+    aligned shapes take the vectorised kernel, the others the element-wise one; the last shape is large enough for the
+    launch with two tiles per workgroup, with an odd number of column tiles and ragged edges."""
     rng = np.random.default_rng(rows * 7 + cols)
     if dtype == np.float32:
         x = rng.standard_normal((rows, cols + pad_src)).astype(np.float32)
