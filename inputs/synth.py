@@ -232,10 +232,61 @@ def f4e2m1_codes_to_f32(codes: np.ndarray) -> np.ndarray:
     return np.where((c >> np.uint8(3)) & np.uint8(1) == 1, -v, v).astype(np.float32)
 
 
+# the 32 magnitudes of the OCP 6-bit types by code, written as runs of constant spacing: E2M3 (largest 7.5) has sixteen
+# values 1/8 apart below 2 (eight subnormals, then the binade of 1), E3M2 (largest 28) eight values 1/16 apart below 1/2
+_F6_VALUES = {
+    6: np.concatenate([np.arange(0, 2, 0.125), np.arange(2, 4, 0.25), np.arange(4, 8, 0.5)]).astype(np.float32),
+    7: np.concatenate([np.arange(0, 0.5, 0.0625), np.arange(0.5, 1, 0.125), np.arange(1, 2, 0.25), np.arange(2, 4, 0.5),
+                       np.arange(4, 8, 1.0), np.arange(8, 16, 2.0), np.arange(16, 32, 4.0)]).astype(np.float32),
+}
+
+
+def f32_to_f6_codes(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Nearest code of each fp32 value in OCP E2M3 (dtype 6) or E3M2 (dtype 7): ties to the even code, magnitudes beyond
+    the largest saturate, NaN -> +0; uint8 in 0..63 (sign in bit 5), one code per element (not yet packed)."""
+    table = _F6_VALUES[dtype]
+    x = np.nan_to_num(np.ascontiguousarray(x, dtype=np.float32), nan=0.0)
+    a = np.minimum(np.abs(x), table[-1])
+    mids = (table[:-1].astype(np.float64) + table[1:].astype(np.float64)) / 2.0
+    code = np.searchsorted(mids, a.astype(np.float64), side="left").astype(np.int64)      # a == mid -> the lower code
+    tie = np.isin(a.astype(np.float64), mids) & (code % 2 == 1)
+    code = code + tie.astype(np.int64)
+    return (code | (np.signbit(x).astype(np.int64) << 5)).astype(np.uint8)
+
+
+def f6_codes_to_f32(codes: np.ndarray, dtype: int) -> np.ndarray:
+    c = np.ascontiguousarray(codes, dtype=np.uint8)
+    v = _F6_VALUES[dtype][c & np.uint8(31)]
+    return np.where((c >> np.uint8(5)) & np.uint8(1) == 1, -v, v).astype(np.float32)
+
+
+def pack_f6(codes: np.ndarray) -> np.ndarray:
+    """Four 6-bit codes to three bytes along the last axis, as one little-endian bit stream (element i in bits 6 i ..
+    6 i + 5); the last axis must be a multiple of 4."""
+    c = np.ascontiguousarray(codes, dtype=np.uint8).astype(np.uint32)
+    if c.shape[-1] % 4:
+        raise ValueError("a multiple of four 6-bit elements per row expected")
+    word = c[..., 0::4] | (c[..., 1::4] << 6) | (c[..., 2::4] << 12) | (c[..., 3::4] << 18)       # 24 bits
+    out = np.empty(c.shape[:-1] + (c.shape[-1] // 4, 3), dtype=np.uint8)
+    for t in range(3):
+        out[..., t] = (word >> (8 * t)) & 0xFF
+    return out.reshape(c.shape[:-1] + (c.shape[-1] // 4 * 3,))
+
+
+def unpack_f6(packed: np.ndarray) -> np.ndarray:
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    g = p.reshape(p.shape[:-1] + (p.shape[-1] // 3, 3)).astype(np.uint32)
+    word = g[..., 0] | (g[..., 1] << 8) | (g[..., 2] << 16)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] // 3, 4), dtype=np.uint8)
+    for t in range(4):
+        out[..., t] = (word >> (6 * t)) & 63
+    return out.reshape(p.shape[:-1] + (p.shape[-1] // 3 * 4,))
+
+
 def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
     """Block-scaled storage of an fp32 matrix [rows, K] in the way of the OCP microscaling formats: every `block`
     consecutive elements of a row share an E8M0 scale 2^(floor(log2(max |x|)) - emax) with emax the largest exponent of
-    the element type (2 for E2M1, 8 for E4M3, 15 for E5M2), and the elements are x / scale rounded to that type.  Returns (stored
+    the element type (2 for E2M1 and E2M3, 4 for E3M2, 8 for E4M3, 15 for E5M2), and the elements are x / scale rounded to that type.  Returns (stored
     elements as to_bits would give them, scale codes uint8 [rows, ceil(K / block)]).  An all-zero block gets scale code 127."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     rows, K = x.shape
@@ -243,7 +294,7 @@ def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
     pad = np.zeros((rows, nb * block), dtype=np.float32)
     pad[:, :K] = x
     amax = np.abs(pad.reshape(rows, nb, block)).max(axis=2)
-    emax = {DTYPE_F4E2M1: 2, DTYPE_F8E5M2: 15}.get(dtype, 8)
+    emax = {DTYPE_F4E2M1: 2, DTYPE_F6E2M3: 2, DTYPE_F6E3M2: 4, DTYPE_F8E5M2: 15}.get(dtype, 8)
     with np.errstate(divide="ignore"):
         e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - emax, 0.0)
     e = np.clip(e, -127, 127)
@@ -256,9 +307,11 @@ def mx_quantize(x: np.ndarray, dtype: int, block: int = 32):
 
 def to_bits(x, dtype):
     """Storage of an fp32 array in the given dtype: fp32 itself, the uint16 patterns of bf16 / fp16, the uint8
-    patterns of E4M3, or E2M1 codes packed two to a byte (last axis halved)."""
+    patterns of E4M3 / E5M2, E2M1 codes packed two to a byte (last axis halved), or 6-bit codes packed four to three bytes."""
     if dtype == DTYPE_F4E2M1:
         return pack_f4(f32_to_f4e2m1_codes(x))
+    if dtype in (DTYPE_F6E2M3, DTYPE_F6E3M2):
+        return pack_f6(f32_to_f6_codes(x, dtype))
     if dtype == DTYPE_BF16:
         return f32_to_bf16_bits(x)
     if dtype == DTYPE_F16:
@@ -274,6 +327,8 @@ def from_bits(b, dtype):
     """fp32 values of stored data (inverse of to_bits)."""
     if dtype == DTYPE_F4E2M1:
         return f4e2m1_codes_to_f32(unpack_f4(b))
+    if dtype in (DTYPE_F6E2M3, DTYPE_F6E3M2):
+        return f6_codes_to_f32(unpack_f6(b), dtype)
     if dtype == DTYPE_BF16:
         return bf16_bits_to_f32(b)
     if dtype == DTYPE_F16:
@@ -315,7 +370,7 @@ def sample_entries(seed, count, batch, M, N, tile_m=256, tile_n=256):
 # ----------------------------------------------------------------------------------------------
 # The five workloads
 
-DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3, DTYPE_F4E2M1, DTYPE_F8E5M2 = 0, 1, 2, 3, 4, 5
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8E4M3, DTYPE_F4E2M1, DTYPE_F8E5M2, DTYPE_F6E2M3, DTYPE_F6E3M2 = 0, 1, 2, 3, 4, 5, 6, 7
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 
@@ -346,7 +401,7 @@ class Workload:
     @property
     def algorithmic_bytes(self):
         """One read of A, B and bias, one write of C."""
-        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1, DTYPE_F8E5M2: 1, DTYPE_F4E2M1: 0.5}.get(self.dtype, 2)      # A and B
+        es = {DTYPE_F32: 4, DTYPE_F8E4M3: 1, DTYPE_F8E5M2: 1, DTYPE_F4E2M1: 0.5, DTYPE_F6E2M3: 0.75, DTYPE_F6E3M2: 0.75}.get(self.dtype, 2)      # A and B
         cs = 4 if self.dtype == DTYPE_F32 else 2                      # C
         per = int((self.M * self.K + self.K * self.N) * es) + self.M * self.N * cs + 4 * self.N
         return self.batch * per
@@ -443,6 +498,12 @@ def make_workload(name: str, scale: int = 1) -> Workload:
         return Workload(name, 1, M, N, K, DTYPE_F4E2M1, ACT_SILU, LAYOUT_RC, 3,
                         _store(normal(3, "A", M, K), DTYPE_F4E2M1),                  # N(0, 1) rounded to 0, 0.5 .. 6
                         _store(normal(3, "B", K, N), DTYPE_F4E2M1, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 16 else "sampled")
+    if name in ("c4_f6_8192_rc_silu", "c4_bf6_8192_rc_silu"):      # config 4's shape in 6-bit E2M3 / E3M2 operands (bf16 result)
+        dt = DTYPE_F6E2M3 if name == "c4_f6_8192_rc_silu" else DTYPE_F6E3M2
+        M = N = K = 8192 // s
+        return Workload(name, 1, M, N, K, dt, ACT_SILU, LAYOUT_RC, 3,
+                        _store(normal(3, "A", M, K), dt), _store(normal(3, "B", K, N), dt, transpose=True),
                         normal(3, "bias", 1, N), check="full" if s >= 16 else "sampled")
     if name == "c4_bf16_4352_tail_silu":       # 17 x 17 tiles of 256 x 256: one more than a round of 256, K as in config 4
         M = N = 4352 // s; K = 8192 // s

@@ -16,7 +16,7 @@ import numpy as np
 
 from .build import build as _build
 
-F32, BF16, F16, F8E4M3, F4E2M1, F8E5M2 = 0, 1, 2, 3, 4, 5
+F32, BF16, F16, F8E4M3, F4E2M1, F8E5M2, F6E2M3, F6E3M2 = 0, 1, 2, 3, 4, 5, 6, 7
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 EW_RELU, EW_SIGMOID = 0, 1
@@ -51,6 +51,9 @@ def lib():
         L.oracle_f8e5m2_to_double.argtypes = [C.c_uint8]
         L.oracle_f4e2m1_to_double.restype = C.c_double
         L.oracle_f4e2m1_to_double.argtypes = [C.c_uint8]
+        for f in (L.oracle_f6e2m3_to_double, L.oracle_f6e3m2_to_double):
+            f.restype = C.c_double
+            f.argtypes = [C.c_uint8]
         L.oracle_e8m0_to_double.restype = C.c_double
         L.oracle_e8m0_to_double.argtypes = [C.c_uint8]
         L.oracle_gemm_epilogue_mx.restype = C.c_int
@@ -83,7 +86,7 @@ def _ptr(a):
 
 
 def _check_operand(x, dtype, what):
-    want = {F32: np.float32, F8E4M3: np.uint8, F4E2M1: np.uint8, F8E5M2: np.uint8}.get(dtype, np.uint16)
+    want = {F32: np.float32, F8E4M3: np.uint8, F4E2M1: np.uint8, F8E5M2: np.uint8, F6E2M3: np.uint8, F6E3M2: np.uint8}.get(dtype, np.uint16)
     if x.dtype != want or not x.flags.c_contiguous:
         raise TypeError(f"{what}: need C-contiguous {want.__name__} storage, got {x.dtype}")
 
@@ -91,11 +94,12 @@ def _check_operand(x, dtype, what):
 def _geometry(A, B, layout, batch, M, N, K, lda, ldb, strideA, strideB, dtype=F32):
     """Leading dimensions / strides default to those of dense [batch, rows, ld] arrays."""
     a_col, b_col = (layout >> 1) & 1, layout & 1
-    per_byte = 2 if dtype == F4E2M1 else 1          # E2M1: two elements to a byte, leading dimensions in elements
+    # leading dimensions in elements: E2M1 has two elements to a byte, the 6-bit types four to three bytes
+    num, den = (2, 1) if dtype == F4E2M1 else (4, 3) if dtype in (F6E2M3, F6E3M2) else (1, 1)
     if lda is None:
-        lda = A.shape[-1] * per_byte
+        lda = A.shape[-1] * num // den
     if ldb is None:
-        ldb = B.shape[-1] * per_byte
+        ldb = B.shape[-1] * num // den
     if strideA is None:
         strideA = (K if a_col else M) * lda if batch > 1 else 0
     if strideB is None:
@@ -184,6 +188,18 @@ def f4e2m1_to_double(nibbles):
     return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(nibbles, dtype=np.uint8))
 
 
+def f6e2m3_to_double(codes):
+    """fp64 value of each OCP E2M3 code (low six bits of each uint8)."""
+    f = lib().oracle_f6e2m3_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(codes, dtype=np.uint8))
+
+
+def f6e3m2_to_double(codes):
+    """fp64 value of each OCP E3M2 code (low six bits of each uint8)."""
+    f = lib().oracle_f6e3m2_to_double
+    return np.vectorize(lambda b: f(int(b)), otypes=[np.float64])(np.asarray(codes, dtype=np.uint8))
+
+
 def e8m0_to_double(codes):
     """fp64 value 2^(e - 127) of each OCP E8M0 scale code (255: NaN)."""
     f = lib().oracle_e8m0_to_double
@@ -191,8 +207,8 @@ def e8m0_to_double(codes):
 
 
 def gemm_epilogue_mx(A, scaleA, B, scaleB, bias, M, N, K, *, dtype=F4E2M1, act=ACT_NONE, layout=LAYOUT_RC, lda=None, ldb=None):
-    """Y[M, N] (fp64) = act((sA * A).(sB * B) + bias) for block-scaled operands: E4M3 or E2M1 elements (uint8 storage, E2M1
-    two to a byte) with one E8M0 scale per 32 consecutive k of every row of A (scaleA [M, ceil(K/32)]) and every column of
+    """Y[M, N] (fp64) = act((sA * A).(sB * B) + bias) for block-scaled operands: E4M3, E5M2, E2M3, E3M2 or E2M1 elements (uint8
+    storage; E2M1 two to a byte, the 6-bit types four to three bytes) with one E8M0 scale per 32 consecutive k of every row of A (scaleA [M, ceil(K/32)]) and every column of
     B (scaleB [N, ceil(K/32)])."""
     _check_operand(A, dtype, "A"); _check_operand(B, dtype, "B")
     lda, ldb, _, _ = _geometry(A, B, layout, 1, M, N, K, lda, ldb, 0, 0, dtype)

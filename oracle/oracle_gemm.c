@@ -17,7 +17,7 @@
  * Bias, SiLU, GELU, bf16 storage and batching are not in the paper; they are
  * the standard definitions named by this repository's benchmark configuration.
  *
- * Arithmetic: the stored fp32 / bf16 / fp16 / 8-bit E4M3 or E5M2 / 4-bit E2M1 inputs are widened exactly to fp64; every
+ * Arithmetic: the stored fp32 / bf16 / fp16 / 8-bit E4M3 or E5M2 / 6-bit E2M3 or E3M2 / 4-bit E2M1 inputs are widened exactly to fp64; every
  * product of two of them is exact in fp64 (at most 48 significant bits); the
  * sum runs over k ascending in one fp64 accumulator starting from +0.0; the
  * bias is added after the sum; activations use fp64 libm.  The result is kept
@@ -38,7 +38,8 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3, ORACLE_F4E2M1 = 4, ORACLE_F8E5M2 = 5 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_F8E4M3 = 3, ORACLE_F4E2M1 = 4, ORACLE_F8E5M2 = 5,
+       ORACLE_F6E2M3 = 6, ORACLE_F6E3M2 = 7 };
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_GELU_TANH = 2, ORACLE_ACT_SILU = 3 };
 /* bit 0 of layout: B is column-major; bit 1: A is column-major */
 
@@ -99,6 +100,39 @@ double oracle_f4e2m1_to_double(uint8_t nibble)
     return sign ? -v : v;
 }
 
+/* OCP 6-bit floating point E2M3 (1 sign, 2 exponent bits with bias 1, 3 fraction bits; no infinities, no NaN) to
+ * double, exactly: exponent field 0 is a subnormal f * 2^-3, else (8 + f) * 2^(e - 4); largest 7.5.  Only the low
+ * six bits of `code` are read. */
+double oracle_f6e2m3_to_double(uint8_t code)
+{
+    const int sign = (code >> 5) & 1, e = (code >> 3) & 3, f = code & 7;
+    const double v = e == 0 ? ldexp((double)f, -3) : ldexp((double)(8 + f), e - 4);
+    return sign ? -v : v;
+}
+
+/* OCP 6-bit floating point E3M2 (1 sign, 3 exponent bits with bias 3, 2 fraction bits; no infinities, no NaN) to
+ * double, exactly: exponent field 0 is a subnormal f * 2^-4, else (4 + f) * 2^(e - 5); largest 28. */
+double oracle_f6e3m2_to_double(uint8_t code)
+{
+    const int sign = (code >> 5) & 1, e = (code >> 2) & 7, f = code & 3;
+    const double v = e == 0 ? ldexp((double)f, -4) : ldexp((double)(4 + f), e - 5);
+    return sign ? -v : v;
+}
+
+/* Element idx of an array of 6-bit codes stored densely: the array is one little-endian bit stream (bit b of the
+ * stream is bit b % 8 of byte b / 8) and element idx occupies its bits 6 idx .. 6 idx + 5, so four elements fill
+ * three bytes. */
+static uint8_t six_bits(const void *base, int64_t idx)
+{
+    const uint8_t *p = (const uint8_t *)base;
+    uint8_t code = 0;
+    for (int t = 0; t < 6; ++t) {
+        const int64_t bit = 6 * idx + t;
+        code |= (uint8_t)(((p[bit / 8] >> (bit % 8)) & 1) << t);
+    }
+    return code;
+}
+
 /* OCP E8M0 block scale (8 exponent bits with bias 127, no sign, no fraction): 2^(e - 127); 255 is NaN. */
 double oracle_e8m0_to_double(uint8_t e)
 {
@@ -110,6 +144,10 @@ static double widen(const void *base, int64_t idx, int dtype)
     /* E2M1: two elements to a byte, element idx in the low (idx even) or high (idx odd) four bits */
     if (dtype == ORACLE_F4E2M1)
         return oracle_f4e2m1_to_double((uint8_t)(((const uint8_t *)base)[idx >> 1] >> ((idx & 1) * 4)));
+    if (dtype == ORACLE_F6E2M3)
+        return oracle_f6e2m3_to_double(six_bits(base, idx));
+    if (dtype == ORACLE_F6E3M2)
+        return oracle_f6e3m2_to_double(six_bits(base, idx));
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
     if (dtype == ORACLE_F16)
@@ -222,7 +260,7 @@ int oracle_gemm_epilogue(int64_t batch, int64_t M, int64_t N, int64_t K,
                          int layout, int dtype, int act)
 {
     if (batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F8E5M2) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F6E3M2) || act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
     const int64_t rows = batch * M;
@@ -287,7 +325,7 @@ int oracle_gemm_epilogue_sampled(int64_t count, const int64_t *sb, const int64_t
                                  int layout, int dtype, int act)
 {
     if (count < 0 || batch < 0 || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 ||
-        (dtype < ORACLE_F32 || dtype > ORACLE_F8E5M2) || act < 0 || act > 3)
+        (dtype < ORACLE_F32 || dtype > ORACLE_F6E3M2) || act < 0 || act > 3)
         return -1;
     for (int64_t t = 0; t < count; ++t)
         if (sb[t] < 0 || sb[t] >= batch || si[t] < 0 || si[t] >= M || sj[t] < 0 || sj[t] >= N)
@@ -327,7 +365,7 @@ int oracle_num_threads(void)
  * Block-scaled operands (the OCP microscaling formats): every 32 consecutive k of a row of A and of a column
  * of B share one E8M0 scale,
  *     z_ij = bias_j + sum_k (sA[i][k / 32] a_ik) (sB[j][k / 32] b_kj),   y_ij = act(z_ij),
- * with a, b in E4M3, E5M2 or E2M1 storage (dtype), decoded exactly; a scaled element is a power of two times a
+ * with a, b in E4M3, E5M2, E2M3, E3M2 or E2M1 storage (dtype), decoded exactly; a scaled element is a power of two times a
  * short significand, exact in fp64, and so is every product; one fp64 accumulator per output, k ascending,
  * bias after the sum.  scaleA is [M][ceil(K / 32)], scaleB [N][ceil(K / 32)] (row-major bytes); A and B in
  * the layouts of oracle_gemm_epilogue, leading dimensions in elements.  Y fp64 [M][N].
@@ -337,7 +375,7 @@ int oracle_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int6
                             const void *B, int64_t ldb, const uint8_t *scaleB, const float *bias, double *Y,
                             int layout, int dtype, int act)
 {
-    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 || (dtype != ORACLE_F8E4M3 && dtype != ORACLE_F4E2M1 && dtype != ORACLE_F8E5M2) ||
+    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3 || (dtype < ORACLE_F8E4M3 || dtype > ORACLE_F6E3M2) ||
         act < 0 || act > 3)
         return -1;
     const int a_col = (layout >> 1) & 1, b_col = layout & 1;
