@@ -39,12 +39,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0
-PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2, 4: 10066.3, 5: 5033.2}          # fp32, bf16, fp16, fp8 (E4M3), fp4, fp8 (E5M2) MFMA (dense)
-DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1", 5: "f8e5m2"}
+PEAK_TFLOPS = {0: 157.3, 1: 2516.6, 2: 2516.6, 3: 5033.2, 4: 10066.3, 5: 5033.2, 6: 10066.3, 7: 10066.3}   # fp32, bf16, fp16, fp8 (E4M3), fp4, fp8 (E5M2), fp6 (E2M3, E3M2) MFMA (dense)
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "f8e4m3", 4: "f4e2m1", 5: "f8e5m2", 6: "f6e2m3", 7: "f6e3m2"}
 # which roof bounds each contraction workload (flop per byte against the ridge of its dtype)
 BOUND = {"c1_f32_256_relu": "hbm", "c2_f32_skinny16_silu": "hbm", "c3_f32_4096_rc_gelu": "mfma",
          "c4_bf16_8192_silu": "mfma", "c5_bf16_batched32_relu": "mfma", "c4_f16_8192_silu": "mfma",
-         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_bf16_4352_tail_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
+         "c2_bf16_skinny16_silu": "hbm", "c4_f8_8192_rc_silu": "mfma", "c4_bf8_8192_rc_silu": "mfma", "c4_f4_8192_rc_silu": "mfma", "c4_f6_8192_rc_silu": "mfma", "c4_bf6_8192_rc_silu": "mfma", "c4_bf16_4352_tail_silu": "mfma", "c4_bf16_8192_cr_silu": "mfma",
          "c2_f32_skinny16_rc_silu": "hbm"}
 # streaming siblings: (entry point, op, arrays read, arrays written) on 2^28 floats
 STREAMS = {"s_relu": ("ew", 0, 1, 1), "s_sigmoid": ("ew", 1, 1, 1), "s_sum": ("red", 0, 1, 0),
@@ -60,7 +60,7 @@ LCE = {"s_lce": (8192, 32768, 4096, 1), "s_lce_f32": (4096, 32768, 2048, 0)}
 # contraction fused with LayerNorm over each row of the product, B row-major: (M, N, K, dtype)
 GLN = {"s_gln": (8192, 8192, 4096, 1), "s_gln_f32": (4096, 4096, 4096, 0)}
 # contraction on block-scaled (E8M0 per 32 k) E2M1 or E4M3 operands, k contiguous in both, SiLU: (M, N, K, dtype)
-MXF4 = {"s_mxf4": (8192, 8192, 8192, 4), "s_mxf8": (8192, 8192, 8192, 3)}
+MXF4 = {"s_mxf4": (8192, 8192, 8192, 4), "s_mxf8": (8192, 8192, 8192, 3), "s_mxf6": (8192, 8192, 8192, 6)}
 
 # HBM bytes per launch of a workload's kernels, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # passes (KiB summed over the kernels of one step, scaled by what the same counters read for the
@@ -292,8 +292,8 @@ def main():
             w = self.w = synth.make_workload(name)
             self.name, self.bound, self.dtype = name, BOUND[name], w.dtype
             self.flops, self.nbytes = float(w.flops), float(w.algorithmic_bytes)
-            pack = 2 if w.dtype == 4 else 1                          # E2M1: two elements a byte
-            self.lda, self.ldb = w.A.shape[-1] * pack, w.B.shape[-1] * pack
+            num, den = (2, 1) if w.dtype == 4 else (4, 3) if w.dtype in (6, 7) else (1, 1)     # E2M1: two elements a byte; 6-bit: four in three
+            self.lda, self.ldb = w.A.shape[-1] * num // den, w.B.shape[-1] * num // den
             self.sA = w.A.shape[-2] * self.lda if w.batch > 1 else 0
             self.sB = w.B.shape[-2] * self.ldb if w.batch > 1 else 0
             self.sBias = w.N if w.batch > 1 else 0
@@ -336,7 +336,7 @@ def main():
                 sample = f"{len(idx[0])} sampled output entries of {w.batch * w.M * w.N}"
             got = self.sets[self.last][3].cpu().numpy()
             if w.dtype != 0:
-                got = synth.from_bits(got.view(np.uint16), 1 if w.dtype in (3, 4) else w.dtype)      # E4M3 / E2M1 operands: bf16 result
+                got = synth.from_bits(got.view(np.uint16), 1 if w.dtype >= 3 else w.dtype)      # 8-, 6- and 4-bit operands: bf16 result
             got = got.astype(np.float64)
             if idx is not None:
                 got = got[idx]
@@ -530,7 +530,7 @@ def main():
                     float(np.max(np.abs(got - ref))))
 
     class Mx(Case):
-        """Block-scaled E2M1 or E4M3 contraction: N(0, 1) operands whose 32-blocks vary in magnitude over 2^+-3, quantised
+        """Block-scaled E2M1, E2M3 or E4M3 contraction: N(0, 1) operands whose 32-blocks vary in magnitude over 2^+-3, quantised
         block by block (scale = the block's largest magnitude brought into the element type's range), bias N(0, 1), SiLU."""
         bound = "mfma"
 
@@ -538,8 +538,8 @@ def main():
             M, N, K, self.dtype = MXF4[name]
             self.shape = (M, N, K)
             self.name = name
-            self.kernel = "ring_mxf4_rc_256x256_w2x4_ns4_pf" if self.dtype == 4 else "ring_mxf8_rc_256x256_w2x4_ns4_k64"
-            self.per = 2 if self.dtype == 4 else 1            # elements per stored byte
+            self.kernel = {4: "ring_mxf4_rc_256x256_w2x4_ns4_pf", 6: "ring_mxf6_rc_256x256_w2x4_ns4_k64"}.get(self.dtype, "ring_mxf8_rc_256x256_w2x4_ns4_k64")
+            bits = {4: 4, 6: 6}.get(self.dtype, 8)            # per stored element
             def operand(tag, rows):
                 x = synth.normal(17, tag, rows, K)
                 e = synth.integers(18, tag + "e", rows, K // 32, -3, 3)
@@ -551,7 +551,7 @@ def main():
             Ad, sAd, Bd, sBd, bd = self.dev
             assert ob.optiml_gemm_epilogue_mx_path(M, N, K, Ad, K, sAd, K // 32, Bd, K, sBd, K // 32, bd, self.C, N, self.dtype) == 0
             self.flops = 2.0 * M * N * K
-            self.nbytes = float((M + N) * (K // self.per + K // 32) + 2 * M * N + 4 * N)
+            self.nbytes = float((M + N) * (K * bits // 8 + K // 32) + 2 * M * N + 4 * N)
             self.config = {"M": M, "N": N, "K": K, "layout": "rc", "act": "silu", "block": 32}
 
         def step(self, i):

@@ -48,8 +48,20 @@
  *              operands: A row-major and B column-major, i.e. OPTIML_LAYOUT_RC, or its
  *              mirror image with a column-major C; other layouts return
  *              OPTIML_ERR_UNSUPPORTED.
+ *              OPTIML_F6E2M3, OPTIML_F6E3M2: A and B are 6-bit OCP E2M3 (1 sign, 2 exponent
+ *              bits with bias 1, 3 fraction bits; largest 7.5) or E3M2 (3 exponent bits with
+ *              bias 3, 2 fraction bits; largest 28); no infinities, no NaN.  Stored densely:
+ *              an operand is one little-endian bit stream in which element e (row * ld + k,
+ *              or k * ld + column, as for the other types) occupies bits 6 e .. 6 e + 5, so
+ *              four elements fill three bytes.  lda, ldb and the operand strides count
+ *              ELEMENTS and must be multiples of 4 (every row starts on a byte;
+ *              OPTIML_ERR_INVALID_ARG otherwise).  Decoded exactly, no scale factors; C is
+ *              bfloat16.  Every layout is accepted; the matrix-pipe kernel serves
+ *              OPTIML_LAYOUT_RC (and its mirror image with a column-major C) with K a
+ *              multiple of 4, after copying both operands into the workspace with every 32
+ *              elements in 32 bytes ((M + N) * max(320, K rounded up to 64) bytes per batch).
  *              bias is always float; NULL means no bias.  The
- *              contraction entry points take all six; the other entry points say
+ *              contraction entry points take all eight; the other entry points say
  *              which they take.
  *   Shapes     M, N, K, batch >= 0.  M == 0, N == 0 or batch == 0: nothing is
  *              written, OPTIML_OK.  K == 0: C = act(bias) (the empty sum is 0).
@@ -100,7 +112,10 @@
 extern "C" {
 #endif
 
-typedef enum { OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3, OPTIML_F4E2M1 = 4, OPTIML_F8E5M2 = 5 } optiml_dtype_t;
+typedef enum {
+    OPTIML_F32 = 0, OPTIML_BF16 = 1, OPTIML_F16 = 2, OPTIML_F8E4M3 = 3, OPTIML_F4E2M1 = 4, OPTIML_F8E5M2 = 5,
+    OPTIML_F6E2M3 = 6, OPTIML_F6E3M2 = 7
+} optiml_dtype_t;
 
 typedef enum {
     OPTIML_ACT_NONE = 0,
@@ -306,7 +321,7 @@ int optiml_transpose(int64_t rows, int64_t cols, const void *src, int64_t ld_src
  * The contraction feeding the cross-entropy (the paper's Table 4, task 2 into task 17), fused:
  *     *loss = (1/M) sum_i [ log sum_j exp(z[i][j]) - z[i][labels[i]] ],   z = A.B + bias
  * for M rows (samples) and N classes, with A, B, bias, layouts, leading dimensions and dtype
- * exactly as in optiml_gemm_epilogue_ex (no activation, no batch, not OPTIML_F8E4M3 or OPTIML_F4E2M1); labels are M 32-bit integers in
+ * exactly as in optiml_gemm_epilogue_ex (no activation, no batch, none of the 8-, 6- and 4-bit types); labels are M 32-bit integers in
  * [0, N), loss one float; all DEVICE pointers.  The logits are not written anywhere: products
  * are accumulated in fp32, each row's maximum and sum of exponentials are formed in fp32 from
  * the unrounded fp32 logits, the row losses and their mean in fp64 in a fixed order, rounded
@@ -386,18 +401,21 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
  *     C[i][j] = act( sum_k (sA[i][k/32] a[i][k]) (sB[j][k/32] b[j][k]) + bias[j] )
  * A is M x K row-major and B is N x K (column-major B: k contiguous in both).  dtype is OPTIML_F4E2M1 (two elements to
  * a byte along k as in the plain contraction; lda, ldb >= K count elements and must be even), OPTIML_F8E4M3 or
- * OPTIML_F8E5M2 (one element to a byte).  Every 32 consecutive k of a row of A (a column of B) share one scale, a
+ * OPTIML_F8E5M2 (one element to a byte), OPTIML_F6E2M3 or OPTIML_F6E3M2 (dense 6-bit codes as in the plain
+ * contraction; lda, ldb multiples of 4).  Every 32 consecutive k of a row of A (a column of B) share one scale, a
  * power of two stored as an OCP E8M0 byte: scaleA[i * lds_a + k / 32], scaleB[j * lds_b + k / 32], value
  * 2^(byte - 127), byte 255 = NaN; lds_a, lds_b >= K / 32 count bytes.  K must be a multiple of 32.  C is M x N
  * bfloat16, row-major, ldc >= N; bias (N floats) may be NULL; act as above.  All pointers DEVICE.  Products are exact;
  * block sums are scaled exactly and accumulated in fp32 (E2M1: the block sums themselves are exact too); C is
  * rounded once.  M == 0 or N == 0 writes nothing; K == 0 gives act(bias).
  * optiml_gemm_epilogue_mx_path: 0 when the call would run on the matrix-pipe tile kernel (K a multiple of 128 for
- * E2M1, of 64 for the 8-bit types; 16-byte aligned operands and rows; at least 65536 entries of C; any address and
- * pitch of the scales), 1 for the one-thread-per-entry kernel, or an error.  The tile kernel keeps a copy of the
- * scales, (M + N) K / 32 bytes for E2M1 and (M + N) K / 16 for the 8-bit types, in the workspace (see Workspace
- * above); the other kernel needs none.
- * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd (E2M1) or too small lda / ldb, lds_a
+ * E2M1, of 64 for the 8-bit and 6-bit types; 16-byte aligned operands and rows, except the 6-bit types, which are
+ * copied; at least 65536 entries of C; any address and pitch of the scales), 1 for the one-thread-per-entry kernel, or
+ * an error.  The tile kernel keeps a copy of the scales, (M + N) K / 32 bytes for E2M1 and (M + N) K / 16 for the
+ * others, in the workspace (see Workspace above), and for the 6-bit types also both operands with every 32 elements
+ * in 32 bytes ((M + N) * max(320, K) bytes); the other kernel needs none.
+ * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd (E2M1) or too small lda / ldb, lda
+ * or ldb not a multiple of 4 (6-bit), lds_a
  * or lds_b < K / 32, ldc < N, another dtype, unknown act, a NULL pointer with work to do.
  */
 int optiml_gemm_epilogue_mx(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,

@@ -416,7 +416,8 @@ def _store(x, dtype, transpose=False):
 WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
 BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf8_8192_rc_silu", "c4_bf16_8192_cr_silu",
-                     "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu", "c4_bf16_4352_tail_silu")     # further dtypes and shapes
+                     "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu", "c4_f6_8192_rc_silu", "c4_bf6_8192_rc_silu",
+                     "c4_bf16_4352_tail_silu")     # further dtypes and shapes
 
 
 # shape of every workload without its data: (batch, M, N, K, layout, dtype, act)
@@ -432,6 +433,8 @@ SPECS = {
     "c4_bf8_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F8E5M2, ACT_SILU),
     "c4_bf16_8192_cr_silu": (1, 8192, 8192, 8192, LAYOUT_CR, DTYPE_BF16, ACT_SILU),
     "c4_f4_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F4E2M1, ACT_SILU),
+    "c4_f6_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F6E2M3, ACT_SILU),
+    "c4_bf6_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F6E3M2, ACT_SILU),
     "c4_bf16_4352_tail_silu": (1, 4352, 4352, 8192, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
     "c2_f32_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F32, ACT_SILU),
 }

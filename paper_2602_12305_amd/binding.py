@@ -11,7 +11,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 
-F32, BF16, F16, F8E4M3, F4E2M1, F8E5M2 = 0, 1, 2, 3, 4, 5
+F32, BF16, F16, F8E4M3, F4E2M1, F8E5M2, F6E2M3, F6E3M2 = 0, 1, 2, 3, 4, 5, 6, 7
 ACT_NONE, ACT_RELU, ACT_GELU_TANH, ACT_SILU = 0, 1, 2, 3
 LAYOUT_RR, LAYOUT_RC, LAYOUT_CR, LAYOUT_CC = 0, 1, 2, 3
 LAYOUT_C_COLUMN_MAJOR = 4        # added to any of the four

@@ -48,6 +48,7 @@ struct Table {
         for (int i = 0; i < kNumTransposeVariants; ++i) v.push_back(&transpose_variants()[i]);
         for (int i = 0; i < kNumPadVariants; ++i) v.push_back(&pad_variants()[i]);
         for (int i = 0; i < kNumTailVariants; ++i) v.push_back(&tail_variants()[i]);
+        for (int i = 0; i < kNumF6Variants; ++i) v.push_back(&f6_variants()[i]);
     }
 };
 
@@ -59,7 +60,7 @@ const Table &table()
 
 bool enum_ok(int layout, int dtype, int act)
 {
-    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_BF8 && act >= 0 && act <= 3;
+    return layout >= 0 && layout <= 3 && dtype >= DT_F32 && dtype <= DT_BF6 && act >= 0 && act <= 3;
 }
 
 // OPTIML_OK when the arguments describe a valid problem (possibly an empty one).
@@ -387,6 +388,12 @@ Problem make(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int6
         if (K < 0 || (K & 1) || (p.lda & 1) || (p.ldb & 1) || (p.strideA & 1) || (p.strideB & 1)) p.pre_status = OPTIML_ERR_INVALID_ARG;
         else if (p.layout != 1) p.pre_status = OPTIML_ERR_UNSUPPORTED;
         p.K = K / 2; p.lda /= 2; p.ldb /= 2; p.strideA /= 2; p.strideB /= 2;
+    }
+    if (is_f6(dtype)) {
+        // Dense 6-bit codes, four to three bytes: every row and every matrix of a batch starts on a byte.  (Any
+        // layout: the element-wise fallback addresses single codes; the matrix-pipe path takes k contiguous in both
+        // operands and K a multiple of 4.)
+        if ((p.lda & 3) || (p.ldb & 3) || (p.strideA & 3) || (p.strideB & 3)) p.pre_status = OPTIML_ERR_INVALID_ARG;
     }
     return p;
 }
@@ -854,7 +861,8 @@ static int mx_validate(int64_t M, int64_t N, int64_t K, const void *A, int64_t l
                        int64_t ldb, const void *scaleB, int64_t lds_b, void *C, int64_t ldc, int dtype, int act)
 {
     if (!is_8bit(dtype) || act < 0 || act > 3 || M < 0 || N < 0 || K < 0 || K % 32 != 0) return OPTIML_ERR_INVALID_ARG;
-    if (lda < 0 || ldb < 0 || ldc < 0 || lds_a < 0 || lds_b < 0 || (dtype == DT_F4 && ((lda & 1) || (ldb & 1)))) return OPTIML_ERR_INVALID_ARG;
+    if (lda < 0 || ldb < 0 || ldc < 0 || lds_a < 0 || lds_b < 0 || (dtype == DT_F4 && ((lda & 1) || (ldb & 1))) ||
+        (is_f6(dtype) && ((lda & 3) || (ldb & 3)))) return OPTIML_ERR_INVALID_ARG;
     constexpr int64_t kMaxSpan = int64_t(1) << 47;
     if (M >= kMaxSpan / (lda + 1) || N >= kMaxSpan / (ldb + 1) || M >= kMaxSpan / (ldc + 1)) return OPTIML_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return OPTIML_OK;

@@ -10,9 +10,14 @@ namespace optiml {
 // DT_F8: A, B in OCP E4M3, C in bf16; DT_BF8: the same with OCP E5M2 operands.  DT_F4: A, B in OCP E2M1, two values to a byte along k (the even k in the
 // low half), C in bf16; inside the library such a problem is described in BYTES of k: K, lda, ldb and the operand
 // strides are halved on entry, an "element" of A or B is a byte holding two values.
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3, DT_F4 = 4, DT_BF8 = 5 };
+// DT_F6 / DT_BF6: A, B in OCP E2M3 / E3M2, stored densely (element i of an array in bits 6 i .. 6 i + 5 of its
+// little-endian bit stream; leading dimensions and strides in elements, multiples of 4), C in bf16.  The matrix-pipe
+// kernel sees such operands in SLOT form (kernel_f6.hip): a copy in the workspace with every 32 elements (24 bytes) in
+// a 32-byte slot, i.e. one byte per element position, which is what K, lda, ldb count there.
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_F8 = 3, DT_F4 = 4, DT_BF8 = 5, DT_F6 = 6, DT_BF6 = 7 };
 constexpr bool is_f8(int dt) { return dt == DT_F8 || dt == DT_BF8; }                   // one 8-bit value per byte
-constexpr bool is_8bit(int dt) { return is_f8(dt) || dt == DT_F4; }                     // one byte per stored element of A and B
+constexpr bool is_f6(int dt) { return dt == DT_F6 || dt == DT_BF6; }
+constexpr bool is_8bit(int dt) { return is_f8(dt) || is_f6(dt) || dt == DT_F4; }        // one byte per stored element of A and B
 enum : int { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
 
 // C = act(A.B + bias) for `batch` problems; leading dimensions and strides in elements.
@@ -124,12 +129,18 @@ hipError_t launch_cross_entropy(int64_t N, int64_t C, const float *z, int64_t ld
                                 hipStream_t stream);
 hipError_t launch_layernorm(int64_t rows, int64_t len, const float *x, float *y, float eps, hipStream_t stream);
 void set_wait_limit(long long clocks);
-// kernel_mx.hip: the contraction on block-scaled E2M1, E4M3 or E5M2 operands (dtype; K, lda, ldb in elements; scales one E8M0 byte per
+// kernel_mx.hip: the contraction on block-scaled E2M1, E4M3, E5M2, E2M3 or E3M2 operands (dtype; K, lda, ldb in elements; scales one E8M0 byte per
 // 32 elements of k, pitches lds_a, lds_b in bytes)
 int mx_path(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B, int64_t ldb,
             const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc);
 hipError_t launch_mx(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
                      int64_t ldb, const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc, int act, hipStream_t stream);
+// kernel_f6.hip: 6-bit operands.  Slot form of `batch` dense matrices of `rows` x K 6-bit elements (pitch ld, batch
+// stride `stride`, both in elements and multiples of 4): dst[b][r][Kp bytes], Kp = f6_slot_k(K), every k-tile of 64
+// elements (48 bytes) as four 16-byte chunks: bytes 0-15 of the first block of 32, bytes 0-15 of the second, bytes
+// 16-23 of the first + 8 zero bytes, bytes 16-23 of the second + 8 zero bytes; elements at or beyond K are zero.
+int64_t f6_slot_k(int64_t K);
+hipError_t launch_f6_slots(const void *src, int64_t ld, int64_t stride, int64_t batch, int64_t rows, int64_t K, void *dst, hipStream_t s);
 // kernel_linear_ln.hip: unrounded fp32 products of p.batch 16-bit problems by the ring kernel (used to split a
 // contraction along k); `pairs` needs 2 * 4 * ceil(N / 256) * M floats per batch
 bool unrounded_products_supported(const Problem &p);
@@ -166,6 +177,7 @@ const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;
 const Variant *pad_variants();             extern const int kNumPadVariants;      // kernel_pad.hip
 const Variant *tail_variants();            constexpr int kNumTailVariants = 1;    // kernel_tail.hip
+const Variant *f6_variants();              constexpr int kNumF6Variants = 2;      // kernel_f6.hip
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
 constexpr int kRingPerUnit = 5;            // ring-of-stages 16-bit kernels per B layout (three one-tile, one persistent, one 128 x 256)

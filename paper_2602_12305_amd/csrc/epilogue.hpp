@@ -86,15 +86,18 @@ __device__ __forceinline__ void dispatch_act(int act, F &&f)
 }
 
 // One 32x32x64 matrix instruction on E4M3 (DT_F8, format code 0) or E5M2 (DT_BF8, format code 1) operands given
-// as two 16-byte halves each (the scale operands of the builtin are zero: the unscaled instruction)
+// as two 16-byte halves each (the scale operands of the builtin are zero: the unscaled instruction).  E2M3 (DT_F6,
+// code 2) and E3M2 (DT_BF6, code 3): a lane's operand is 32 values in the first 24 of the 32 bytes, a little-endian
+// stream of 6-bit codes; the last two registers are not read.
+template <int DT> struct F8F6F4Code { static constexpr int value = DT == DT_BF8 ? 1 : DT == DT_F6 ? 2 : DT == DT_BF6 ? 3 : 0; };
 template <int DT, class V4, class ACC> __device__ __forceinline__ ACC mfma_32x32x64_f8(V4 a_lo, V4 a_hi, V4 b_lo, V4 b_hi, ACC c)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef int intx8_ __attribute__((ext_vector_type(8)));
     const intx8_ a = intx8_{(int)a_lo[0], (int)a_lo[1], (int)a_lo[2], (int)a_lo[3], (int)a_hi[0], (int)a_hi[1], (int)a_hi[2], (int)a_hi[3]};
     const intx8_ b = intx8_{(int)b_lo[0], (int)b_lo[1], (int)b_lo[2], (int)b_lo[3], (int)b_hi[0], (int)b_hi[1], (int)b_hi[2], (int)b_hi[3]};
-    if constexpr (DT == DT_BF8) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 1, 1, 0, 0, 0, 0);
-    else return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+    constexpr int F = F8F6F4Code<DT>::value;
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, F, F, 0, 0, 0, 0);
 #else
     return c;
 #endif
@@ -109,8 +112,8 @@ __device__ __forceinline__ ACC mfma_32x32x64_f8_scaled(V4 a_lo, V4 a_hi, V4 b_lo
     typedef int intx8_ __attribute__((ext_vector_type(8)));
     const intx8_ a = intx8_{(int)a_lo[0], (int)a_lo[1], (int)a_lo[2], (int)a_lo[3], (int)a_hi[0], (int)a_hi[1], (int)a_hi[2], (int)a_hi[3]};
     const intx8_ b = intx8_{(int)b_lo[0], (int)b_lo[1], (int)b_lo[2], (int)b_lo[3], (int)b_hi[0], (int)b_hi[1], (int)b_hi[2], (int)b_hi[3]};
-    if constexpr (DT == DT_BF8) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 1, 1, 0, (int)sa, 0, (int)sb);
-    else return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, (int)sa, 0, (int)sb);
+    constexpr int F = F8F6F4Code<DT>::value;
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, F, F, 0, (int)sa, 0, (int)sb);
 #else
     return c;
 #endif
@@ -188,6 +191,29 @@ __device__ __forceinline__ float f4e2m1_to_f32(unsigned int code)
     const unsigned e = (code >> 1) & 3u, f = code & 1u;
     const float v = e == 0u ? 0.5f * (float)f : __uint_as_float(((e + 126u) << 23) | (f << 22));   // 1.f * 2^(e-1)
     return (code & 8u) ? -v : v;
+}
+
+// OCP 6-bit E2M3 (bias 1) and E3M2 (bias 3), no infinities or NaN; the low six bits of `code`
+__device__ __forceinline__ float f6e2m3_to_f32(unsigned int code)
+{
+    const unsigned e = (code >> 3) & 3u, f = code & 7u;
+    const float v = e == 0u ? 0.125f * (float)f : __uint_as_float(((e + 126u) << 23) | (f << 20));   // 1.f * 2^(e-1)
+    return (code & 32u) ? -v : v;
+}
+__device__ __forceinline__ float f6e3m2_to_f32(unsigned int code)
+{
+    const unsigned e = (code >> 2) & 7u, f = code & 3u;
+    const float v = e == 0u ? 0.0625f * (float)f : __uint_as_float(((e + 124u) << 23) | (f << 21));  // 1.f * 2^(e-3)
+    return (code & 32u) ? -v : v;
+}
+// element i of a dense array of 6-bit codes: bits 6 i .. 6 i + 5 of its little-endian bit stream
+__device__ __forceinline__ unsigned int six_bit_code(const unsigned char *base, int64_t i)
+{
+    const int64_t bit = 6 * i, byte = bit >> 3;
+    const unsigned sh = (unsigned)(bit & 7);
+    unsigned v = base[byte];
+    if (sh > 2u) v |= (unsigned)base[byte + 1] << 8;             // the code runs into the next byte
+    return (v >> sh) & 63u;
 }
 
 // The two 16-bit storage types share every kernel; these pick the conversions and the matrix

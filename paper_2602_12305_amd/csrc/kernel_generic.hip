@@ -23,6 +23,10 @@ template <> __device__ __forceinline__ float widen<unsigned short>(unsigned shor
 template <> __device__ __forceinline__ float widen<_Float16>(_Float16 v) { return (float)v; }
 template <> __device__ __forceinline__ float widen<unsigned char>(unsigned char v) { return f8e4m3_to_f32(v); }
 struct e5m2_t { unsigned char v; };          // a byte read as E5M2
+struct f6e2m3_t { unsigned char v; };        // a 6-bit code read as E2M3
+struct f6e3m2_t { unsigned char v; };        // ... as E3M2
+template <> __device__ __forceinline__ float widen<f6e2m3_t>(f6e2m3_t v) { return f6e2m3_to_f32(v.v); }
+template <> __device__ __forceinline__ float widen<f6e3m2_t>(f6e3m2_t v) { return f6e3m2_to_f32(v.v); }
 template <> __device__ __forceinline__ float widen<e5m2_t>(e5m2_t v) { return f8e5m2_to_f32(v.v); }
 
 __device__ __forceinline__ void put(float *p, float y) { *p = y; }
@@ -31,18 +35,21 @@ __device__ __forceinline__ void put(_Float16 *p, float y) { *p = (_Float16)y; }
 
 // E: storage type of A and B, CE: of C (the same, except 8-bit operands with a bf16 result).  PACK = 2: every
 // stored byte holds two E2M1 values of consecutive k (the even one in the low half) and p.K counts bytes.
+// PACK = 6: dense 6-bit codes (E: f6e2m3_t or f6e3m2_t), element index = row * ld + k in the array's bit stream.
 template <typename E, typename CE = E, int PACK = 1>
 __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_m, int64_t y0)
 {
-    __shared__ float As[GK * PACK][PADDED];   // As[k][row]
-    __shared__ float Bs[GK * PACK][PADDED];   // Bs[k][col]
+    constexpr int KPS = PACK == 2 ? 2 : 1;      // values per stored element
+    __shared__ float As[GK * KPS][PADDED];    // As[k][row]
+    __shared__ float Bs[GK * KPS][PADDED];    // Bs[k][col]
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;
     const int64_t by = y0 + blockIdx.y;
     const int64_t b = by / blocks_m;
     const int64_t row0 = (by % blocks_m) * GT, col0 = (int64_t)blockIdx.x * GT;
-    const E *A = static_cast<const E *>(p.A) + b * p.strideA;
-    const E *B = static_cast<const E *>(p.B) + b * p.strideB;
+    // (dense 6-bit codes: the batch offset goes into the element index, E is one byte)
+    const E *A = static_cast<const E *>(p.A) + (PACK == 6 ? 0 : b * p.strideA);
+    const E *B = static_cast<const E *>(p.B) + (PACK == 6 ? 0 : b * p.strideB);
     const bool a_col = (p.layout & 2) != 0, b_col = (p.layout & 1) != 0;
 
     float acc[4][4] = {};
@@ -57,6 +64,12 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
                 const unsigned byte = (gr < p.M && gk < p.K) ? (unsigned)(a_col ? A[gk * p.lda + gr] : A[gr * p.lda + gk]) : 0u;
                 As[2 * ak][ar] = f4e2m1_to_f32(byte & 15u);
                 As[2 * ak + 1][ar] = f4e2m1_to_f32(byte >> 4);
+            } else if constexpr (PACK == 6) {
+                float v = 0.0f;
+                if (gr < p.M && gk < p.K)
+                    v = widen<E>(E{(unsigned char)six_bit_code(reinterpret_cast<const unsigned char *>(A),
+                                                               b * p.strideA + (a_col ? gk * p.lda + gr : gr * p.lda + gk))});
+                As[ak][ar] = v;
             } else {
                 float v = 0.0f;
                 if (gr < p.M && gk < p.K)
@@ -69,6 +82,12 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
                 const unsigned byte = (gc < p.N && gkb < p.K) ? (unsigned)(b_col ? B[gc * p.ldb + gkb] : B[gkb * p.ldb + gc]) : 0u;
                 Bs[2 * bk][bc] = f4e2m1_to_f32(byte & 15u);
                 Bs[2 * bk + 1][bc] = f4e2m1_to_f32(byte >> 4);
+            } else if constexpr (PACK == 6) {
+                float w = 0.0f;
+                if (gc < p.N && gkb < p.K)
+                    w = widen<E>(E{(unsigned char)six_bit_code(reinterpret_cast<const unsigned char *>(B),
+                                                               b * p.strideB + (b_col ? gc * p.ldb + gkb : gkb * p.ldb + gc))});
+                Bs[bk][bc] = w;
             } else {
                 float w = 0.0f;
                 if (gc < p.N && gkb < p.K)
@@ -78,7 +97,7 @@ __global__ __launch_bounds__(256) void generic_kernel(Problem p, int64_t blocks_
         }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < GK * PACK; ++k) {
+        for (int k = 0; k < GK * KPS; ++k) {
             float a[4], c[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; c[i] = Bs[k][tx * 4 + i]; }
@@ -130,6 +149,10 @@ hipError_t generic_launch(const Problem &p, hipStream_t s)
             hipLaunchKernelGGL((generic_kernel<e5m2_t, unsigned short>), grid, block, 0, s, p, blocks_m, y0);
         else if (p.dtype == DT_F4)
             hipLaunchKernelGGL((generic_kernel<unsigned char, unsigned short, 2>), grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_F6)
+            hipLaunchKernelGGL((generic_kernel<f6e2m3_t, unsigned short, 6>), grid, block, 0, s, p, blocks_m, y0);
+        else if (p.dtype == DT_BF6)
+            hipLaunchKernelGGL((generic_kernel<f6e3m2_t, unsigned short, 6>), grid, block, 0, s, p, blocks_m, y0);
         else
             hipLaunchKernelGGL(generic_kernel<unsigned short>, grid, block, 0, s, p, blocks_m, y0);
         hipError_t e = hipGetLastError();

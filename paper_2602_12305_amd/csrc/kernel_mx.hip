@@ -1,4 +1,4 @@
-// The contraction on block-scaled ("microscaling") 4-bit or 8-bit operands:
+// The contraction on block-scaled ("microscaling") 4-bit, 6-bit or 8-bit operands:
 //     C = act((sA * A) . (sB * B) + bias)
 // A is M x K and B is N x K (k contiguous in both), elements in OCP E2M1, two to a byte along k, or in OCP E4M3 / E5M2,
 // one to a byte; every
@@ -14,7 +14,9 @@
 // (mx_scale_tiles_kernel: dword [k-tile][row]), from where a wave's 64 loads are 256 contiguous bytes.
 // 8-bit elements take the 64-deep kernel of the unscaled 8-bit contraction the same way: a k-tile is 64 k = two
 // blocks (two scale bytes in the low half of the dword); lanes 0-31 supply the first block's scale, lanes 32-63 the
-// second's.
+// second's.  6-bit elements (E2M3, E3M2; stored densely, four to three bytes) are first copied into the slot form of
+// kernel_f6.hip - a lane of the first half then holds a row's first block of the k-tile, a lane of the second half
+// its second block - and take the same kernel with the instruction's 6-bit format codes.
 // Everything else - k not a whole number of k-tiles, pitches or
 // addresses that the 16-byte and 4-byte loads cannot take, small problems - goes to mx_fallback_kernel,
 // one thread per entry of C: block sums of the exact products, scaled by 2^(ea + eb - 254), added in
@@ -63,14 +65,19 @@ __global__ __launch_bounds__(256) void mx_fallback_kernel(int64_t M, int64_t N, 
                                                           const unsigned char *__restrict__ sB, int64_t lds_b,
                                                           const float *__restrict__ bias, unsigned short *__restrict__ C, int64_t ldc, int act)
 {
-    // lda, ldb in bytes here; a block of 32 elements is 16 bytes of E2M1 or 32 bytes of E4M3 / E5M2
+    // lda, ldb in bytes here; a block of 32 elements is 16 bytes of E2M1, 24 bytes of E2M3 / E3M2 or 32 bytes of E4M3 / E5M2
     const int64_t col = (int64_t)blockIdx.x * 16 + (threadIdx.x & 15), row = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
     if (row >= M || col >= N) return;
     const unsigned char *a = A + row * lda, *b = B + col * ldb;
     float acc = 0.0f;
     for (int64_t blk = 0; blk < K / 32; ++blk) {
         float sum = 0.0f;
-        if constexpr (DT == DT_F4) {
+        if constexpr (is_f6(DT)) {                          // dense 6-bit codes: a block is 24 bytes
+            for (int i = 0; i < 32; ++i) {
+                const unsigned x = six_bit_code(a, blk * 32 + i), y = six_bit_code(b, blk * 32 + i);
+                sum += DT == DT_F6 ? f6e2m3_to_f32(x) * f6e2m3_to_f32(y) : f6e3m2_to_f32(x) * f6e3m2_to_f32(y);
+            }
+        } else if constexpr (DT == DT_F4) {
             for (int i = 0; i < 16; ++i) {                  // at most 32 products, each a multiple of 0.25 up to 36: exact
                 const unsigned x = a[blk * 16 + i], y = b[blk * 16 + i];
                 sum += f4e2m1_to_f32(x & 15u) * f4e2m1_to_f32(y & 15u) + f4e2m1_to_f32(x >> 4) * f4e2m1_to_f32(y >> 4);
@@ -147,6 +154,14 @@ int mx_path(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t l
     if (M * N < 65536 || M >= (int64_t(1) << 30) || N >= (int64_t(1) << 30)) return 1;
     if (dtype == DT_F4) return K % 128 == 0 && ring::supports<MxCfg>(p) ? 0 : 1;
     if (K % 64 != 0) return 1;
+    if (is_f6(dtype)) {
+        // the slot form of both operands in the workspace (kernel_f6.hip), then the 8-bit kernel's geometry
+        const int64_t Kp = f6_slot_k(K);                          // the copies' pitch (K itself from five k-tiles on)
+        if ((lda | ldb) & 3 || (M + N) > (int64_t(1) << 40) / Kp) return 1;
+        const void *ws = reinterpret_cast<const void *>(uintptr_t(256));
+        const Problem q = byte_problem(dtype, M, N, K, ws, Kp, ws, Kp, bias, C, ldc, 0);
+        return (dtype == DT_F6 ? ring::supports<Mx8Cfg<DT_F6>>(q) : ring::supports<Mx8Cfg<DT_BF6>>(q)) ? 0 : 1;
+    }
     return (dtype == DT_F8 ? ring::supports<Mx8Cfg<DT_F8>>(p) : ring::supports<Mx8Cfg<DT_BF8>>(p)) ? 0 : 1;
 }
 
@@ -158,7 +173,22 @@ hipError_t launch_mx(int dtype, int64_t M, int64_t N, int64_t K, const void *A, 
         const Problem p = byte_problem(dtype, M, N, K, A, lda, B, ldb, bias, C, ldc, act);
         if (dtype == DT_F4) return launch_tiles<MxCfg>(p, K / 128, 4, scaleA, lds_a, scaleB, lds_b, stream);
         if (dtype == DT_F8) return launch_tiles<Mx8Cfg<DT_F8>>(p, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);
-        return launch_tiles<Mx8Cfg<DT_BF8>>(p, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);
+        if (dtype == DT_BF8) return launch_tiles<Mx8Cfg<DT_BF8>>(p, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);
+        // 6-bit elements: slot copies of A and B at the head of the workspace, the scale tiles behind them
+        const int64_t Kp = f6_slot_k(K);
+        const size_t a_bytes = ((size_t)M * Kp + 255) & ~size_t(255), b_bytes = ((size_t)N * Kp + 255) & ~size_t(255);
+        void *ws = nullptr;
+        hipError_t e = workspace(a_bytes + b_bytes + (size_t)(M + N) * (K / 64) * 4, &ws, stream);
+        if (e != hipSuccess) return e;
+        void *wa = ws, *wb = static_cast<char *>(ws) + a_bytes;
+        e = launch_f6_slots(A, lda, 0, 1, M, K, wa, stream);
+        if (e != hipSuccess) return e;
+        e = launch_f6_slots(B, ldb, 0, 1, N, K, wb, stream);
+        if (e != hipSuccess) return e;
+        const WorkspaceHead keep(a_bytes + b_bytes);
+        const Problem q = byte_problem(dtype, M, N, K, wa, Kp, wb, Kp, bias, C, ldc, act);
+        if (dtype == DT_F6) return launch_tiles<Mx8Cfg<DT_F6>>(q, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);
+        return launch_tiles<Mx8Cfg<DT_BF6>>(q, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);
     }
     const int64_t bx = (N + 15) / 16, by = (M + 15) / 16;
     if (bx > 0x7fffffffLL || by > 65535) return hipErrorInvalidValue;
@@ -169,6 +199,10 @@ hipError_t launch_mx(int dtype, int64_t M, int64_t N, int64_t K, const void *A, 
     unsigned short *c = static_cast<unsigned short *>(C);
     if (dtype == DT_F4)
         hipLaunchKernelGGL(mx_fallback_kernel<DT_F4>, grid, block, 0, stream, M, N, K, a, lda / per_byte, sa, lds_a, b, ldb / per_byte, sb, lds_b, bias, c, ldc, act);
+    else if (dtype == DT_F6)
+        hipLaunchKernelGGL(mx_fallback_kernel<DT_F6>, grid, block, 0, stream, M, N, K, a, lda / 4 * 3, sa, lds_a, b, ldb / 4 * 3, sb, lds_b, bias, c, ldc, act);
+    else if (dtype == DT_BF6)
+        hipLaunchKernelGGL(mx_fallback_kernel<DT_BF6>, grid, block, 0, stream, M, N, K, a, lda / 4 * 3, sa, lds_a, b, ldb / 4 * 3, sb, lds_b, bias, c, ldc, act);
     else if (dtype == DT_F8)
         hipLaunchKernelGGL(mx_fallback_kernel<DT_F8>, grid, block, 0, stream, M, N, K, a, lda, sa, lds_a, b, ldb, sb, lds_b, bias, c, ldc, act);
     else

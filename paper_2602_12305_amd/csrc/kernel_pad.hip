@@ -136,7 +136,7 @@ bool needs_padding(const Problem &p)
 
 bool pad_supports(const Problem &p)
 {
-    if (tls_inside || p.K < 1 || p.batch > 65535 || !needs_padding(p)) return false;
+    if (tls_inside || p.K < 1 || p.batch > 65535 || is_f6(p.dtype) || !needs_padding(p)) return false;   // (dense 6-bit codes: not whole bytes)
     return second_kernel(p, nullptr) != nullptr;
 }
 

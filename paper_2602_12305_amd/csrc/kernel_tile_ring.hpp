@@ -71,7 +71,7 @@ struct Cfg {
     // register of that lane.  The scales of a k-tile (four blocks = one dword per row) travel with the tile: one more
     // LDS-DMA load per wave and stage (4 bytes a lane) into 2 KiB behind the B tile.
     static constexpr bool MX = MX_;
-    static_assert(!MX_ || (B_KC_ && EPI_ == 0 && WM_ == 2 && WN_ == 4 && ((DT_ == DT_F4 && PF_ && !K64_) || (is_f8(DT_) && K64_))),
+    static_assert(!MX_ || (B_KC_ && EPI_ == 0 && WM_ == 2 && WN_ == 4 && ((DT_ == DT_F4 && PF_ && !K64_) || ((is_f8(DT_) || is_f6(DT_)) && K64_))),
                   "block scales: the 2 x 4 E2M1 kernel with fragment prefetch, or the 64-deep 8-bit kernel");
     // WM = 1: a 128 x 256 block computed by four waves (1 x 4, the same 128 x 64 wave tile) with 24 KiB
     // stages; with NS = 3 two such workgroups share a CU (144 KiB of LDS, at most 256 registers a lane),
@@ -86,7 +86,8 @@ struct Cfg {
     // 8-bit operands only: one v_mfma_f32_32x32x64_f8f6f4 per k-tile and pair of fragments instead
     // of four v_mfma_f32_32x32x16_fp8_fp8
     static constexpr bool K64 = K64_;
-    static_assert(!K64_ || (is_f8(DT_) && !PF_), "the 64-deep instruction: 8-bit operands, no fragment prefetch");
+    static_assert(!K64_ || ((is_f8(DT_) || is_f6(DT_)) && !PF_), "the 64-deep instruction: 8-bit or 6-bit operands, no fragment prefetch");
+    static_assert(!is_f6(DT_) || K64_, "6-bit operands (in slot form): the 64-deep instruction only");
     static constexpr int DT = DT_;       // DT_BF16 or DT_F16: same tiles, another matrix instruction and rounding
     // 0: C = act(A.B + bias).  1: C is not written; each wave reduces its 64 columns of A.B + bias
     // to a (maximum, sum of exponentials) pair per row and hands out the label's logit: the

@@ -138,7 +138,7 @@ int second_kernel(const Problem &p, double *us)
 
 bool xa_supports(const Problem &p)
 {
-    if (!p.a_col() || p.K < 1 || is_f8(p.dtype) || !vector_friendly(p)) return false;
+    if (!p.a_col() || p.K < 1 || is_8bit(p.dtype) || !vector_friendly(p)) return false;
     const int ch = 16 / p.esize();
     if (p.M % ch != 0 || p.K % ch != 0) return false;
     const int64_t T = 256 / p.esize();

@@ -15,7 +15,7 @@ import torch
 
 from . import binding as ob
 
-DT_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "e4m3", 4: "e2m1", 5: "e5m2"}
+DT_NAME = {0: "f32", 1: "bf16", 2: "f16", 3: "e4m3", 4: "e2m1", 5: "e5m2", 6: "e2m3", 7: "e3m2"}
 LAYOUT_NAME = {0: "rr", 1: "rc", 2: "cr", 3: "cc"}
 TORCH_DT = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}
 

@@ -12,16 +12,18 @@ from helpers import e1, store
 # binary16: one rounding of the output, half a step = 2^-12 .. 2^-11 relative across a binade (4.9e-4 at most),
 # plus fp32 accumulation: bar 1e-3
 TOL = {synth.DTYPE_F32: 1e-5, synth.DTYPE_BF16: 2e-2, synth.DTYPE_F16: 1e-3, synth.DTYPE_F8E4M3: 2e-2,
-       synth.DTYPE_F4E2M1: 2e-2, synth.DTYPE_F8E5M2: 2e-2}     # E4M3, E5M2 and E2M1 operands: bf16 result
+       synth.DTYPE_F4E2M1: 2e-2, synth.DTYPE_F8E5M2: 2e-2, synth.DTYPE_F6E2M3: 2e-2, synth.DTYPE_F6E3M2: 2e-2}     # 8-, 6- and 4-bit operands: bf16 result
 
 
 def c_dtype(dtype):
     """Storage type of C for a contraction dtype (8-bit and 4-bit operands give a bf16 result)."""
-    return synth.DTYPE_BF16 if dtype in (synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2) else dtype
+    return synth.DTYPE_BF16 if dtype in (synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2, synth.DTYPE_F6E2M3, synth.DTYPE_F6E3M2) else dtype
 
 
 def ld_elements(X, dtype):
-    """Leading dimension, in elements, of a storage array (E2M1 arrays hold two elements a byte)."""
+    """Leading dimension, in elements, of a storage array (E2M1 arrays hold two elements a byte, 6-bit arrays four in three)."""
+    if dtype in (synth.DTYPE_F6E2M3, synth.DTYPE_F6E3M2):
+        return X.shape[-1] * 4 // 3
     return X.shape[-1] * (2 if dtype == synth.DTYPE_F4E2M1 else 1)
 POISON = 12345.0
 

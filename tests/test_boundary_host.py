@@ -59,7 +59,7 @@ def call(batch=1, M=8, N=8, K=8, A=P, lda=8, sA=0, B=P, ldb=8, sB=0, bias=P, sBi
     dict(A=None), dict(B=None), dict(C=None),
     dict(lda=7), dict(ldb=7), dict(ldc=7),
     dict(layout=1, K=16, ldb=8), dict(layout=2, M=16, lda=8),
-    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=6), dict(dtype=-1), dict(act=4), dict(act=-1),
+    dict(layout=8), dict(layout=-1), dict(layout=4, M=16, ldc=8), dict(dtype=8), dict(dtype=-1), dict(act=4), dict(act=-1),
     dict(sA=-1), dict(sB=-1), dict(sBias=-1), dict(sC=-1),
     dict(batch=2, sC=63), dict(batch=2, sC=0),
 ])
@@ -318,9 +318,31 @@ def test_e2m1_operands_are_validated_and_dispatched_before_any_gpu_call():
     assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=513) == ERR_INVALID              # odd pitch
     assert sel(1, 512, 512, 512, layout=1, dtype=4, ldb=515) == ERR_INVALID
     assert sel(1, 512, 512, 512, layout=1, dtype=4, lda=510) == ERR_INVALID              # pitch shorter than a row
-    assert sel(1, 512, 512, 512, layout=1, dtype=6) == ERR_INVALID                       # no such storage type
+    assert sel(1, 512, 512, 512, layout=1, dtype=8) == ERR_INVALID                       # no such storage type
     assert sel(1, 8192, 8192, 8192, layout=1, dtype=5).startswith("ring_bf8_rc_256x256") and sel(1, 16, 16384, 16384, layout=1, dtype=5).startswith("skinnyrc_bf8")   # E5M2: the E4M3 kernels with the other format code
     assert sel(1, 8192, 8192, 8192, layout=0, dtype=5) == "xk_ring_f8" and sel(1, 100, 100, 100, layout=0, dtype=5) == "generic_64x64"
+
+
+def test_six_bit_operands_are_validated_and_dispatched_before_any_gpu_call():
+    """6-bit operands: a dense stream of 6-bit codes, so every row has to start on a byte (pitches and batch strides in
+    elements, multiples of 4); the matrix-pipe path takes k contiguous in both operands, the fallback every layout."""
+    ERR_INVALID = -1
+    for dtype, tag in ((6, "f6"), (7, "bf6")):
+        assert sel(1, 8192, 8192, 8192, layout=1, dtype=dtype) == f"xs_ring_{tag}_rc_256x256_w2x4_ns5_k64"
+        assert sel(1, 300, 520, 228, layout=1, dtype=dtype).startswith("xs_ring_" + tag)   # any K that is a multiple of 4
+        assert sel(1, 300, 520, 230, layout=1, dtype=dtype, lda=232, ldb=232) == "generic_64x64"
+        assert sel(1, 33, 65, 8, layout=1, dtype=dtype) == "generic_64x64"                  # too little work to copy for
+        assert sel(1, 300, 520, 100, layout=1, dtype=dtype) == "generic_64x64"
+        assert sel(1, 512, 512, 512, layout=5, dtype=dtype).startswith("xs_ring_" + tag)   # column-major C: the mirror image
+        for layout in (0, 2, 3, 4, 6, 7):
+            assert sel(1, 512, 512, 512, layout=layout, dtype=dtype) == "generic_64x64"
+        assert sel(1, 512, 512, 512, layout=1, dtype=dtype, lda=514) == ERR_INVALID        # a row would start inside a byte
+        assert sel(1, 512, 512, 512, layout=1, dtype=dtype, ldb=513) == ERR_INVALID
+        assert sel(1, 512, 512, 512, layout=1, dtype=dtype, lda=508) == ERR_INVALID        # pitch shorter than a row
+        # no other kernel claims the storage type
+        args = (1, 512, 512, 512, P, 512, 0, P, 512, 0, P, 0, P, 512, 0, 1, dtype, 0)
+        takers = [ob.optiml_variant_name(v) for v in range(ob.optiml_variant_count()) if ob.optiml_variant_supports(v, *args) == ob.OK]
+        assert takers == ["generic_64x64", f"xs_ring_{tag}_rc_256x256_w2x4_ns5_k64"]
 
 
 def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
@@ -331,7 +353,7 @@ def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
         return (L.optiml_gemm_epilogue_mx(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype, act, None),
                 L.optiml_gemm_epilogue_mx_path(M, N, K, A, lda, sA, lds_a, B, ldb, sB, lds_b, bias, C, ldc, dtype))
     for kw in (dict(M=-1), dict(K=-32), dict(K=48), dict(lda=510), dict(lda=513), dict(ldb=511), dict(lds_a=15), dict(lds_b=3), dict(ldc=511),
-               dict(dtype=6), dict(dtype=2), dict(dtype=1), dict(A=None), dict(B=None), dict(sA=None), dict(sB=None), dict(C=None)):
+               dict(dtype=8), dict(dtype=2), dict(dtype=1), dict(A=None), dict(B=None), dict(sA=None), dict(sB=None), dict(C=None)):
         assert call(**kw)[1] == ob.ERR_INVALID_ARG, kw
     assert call(act=7)[0] == ob.ERR_INVALID_ARG
     assert call(M=0, A=None, C=None)[0] == ob.OK and call(N=0)[0] == ob.OK                # nothing to do
@@ -342,3 +364,7 @@ def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
     assert call(lda=514)[1] == 1
     assert call(dtype=3)[1] == 0 and call(dtype=5)[1] == 0 and call(dtype=3, K=320)[1] == 0      # 8-bit elements: k-tiles of 64
     assert call(dtype=3, K=480)[1] == 1 and call(dtype=5, K=192)[1] == 1 and call(dtype=3, lda=513)[1] == 1   # (odd pitches are valid there)
+    # 6-bit elements: copied into 32-byte slots first, so any address and any pitch that is a multiple of 4 elements
+    assert call(dtype=6)[1] == 0 and call(dtype=7, K=320)[1] == 0 and call(dtype=6, A=P + 3, lda=516)[1] == 0
+    assert call(dtype=6, K=480)[1] == 1 and call(dtype=7, K=192)[1] == 1 and call(dtype=7, M=100, N=100)[1] == 1
+    assert call(dtype=6, lda=514)[1] == ob.ERR_INVALID_ARG and call(dtype=7, ldb=513)[1] == ob.ERR_INVALID_ARG

@@ -1,10 +1,13 @@
-"""The contraction on block-scaled (microscaling) E2M1, E4M3 and E5M2 operands against the CPU oracle, through the C-ABI.
+"""The contraction on block-scaled (microscaling) E2M1, E4M3, E5M2, E2M3 and E3M2 operands against the CPU oracle, through the C-ABI.
 
 Bar.  Every product a b is exact, a block's 32 products sum exactly in fp32, and scaling by a power of two is exact;
 what rounds is the fp32 accumulation of K / 32 scaled block sums (relative 2^-24 each, against sum |block|) and the one
 rounding of C to bf16: E1 <= 2e-2 as for every bf16 result, and, where all scales are equal (the sums are then the
 unscaled ones times a power of two, exact in fp32), equality with the bf16 rounding of the oracle's value.
 8-bit elements: the products are exact, a block's sum is not (36 binades of products against 24 bits), so only E1.
+6-bit elements (a dense stream of codes, four to three bytes): E2M3 products span 12 binades with 8 significant bits, a
+block's sum is exact in 24 bits and equal scales give equality as for E2M1; E3M2 products span 18 binades (2^-8 .. 784),
+more than a 24-bit sum holds next to its largest term, so there only E1.
 """
 import numpy as np
 import pytest
@@ -16,8 +19,9 @@ from paper_2602_12305_amd import binding as ob
 from helpers import e1
 
 pytestmark = pytest.mark.gpu
-F4, F8, BF8 = synth.DTYPE_F4E2M1, synth.DTYPE_F8E4M3, synth.DTYPE_F8E5M2
+F4, F8, BF8, F6, BF6 = synth.DTYPE_F4E2M1, synth.DTYPE_F8E4M3, synth.DTYPE_F8E5M2, synth.DTYPE_F6E2M3, synth.DTYPE_F6E3M2
 EIGHT = pytest.mark.parametrize("dt", [F8, BF8], ids=["e4m3", "e5m2"])
+SIX = pytest.mark.parametrize("dt", [F6, BF6], ids=["e2m3", "e3m2"])
 
 
 def quantised(seed, tag, rows, K, spread, dt=F4):
@@ -43,8 +47,8 @@ def run(As, sA, Bs, sB, bias, M, N, K, act, *, pad_c=0, pitch=0, spitch=0, shift
     bd = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
     ldc = N + pad_c
     Cd = torch.full((M, ldc), 0x4442, dtype=torch.int16, device="cuda")
-    per = 2 if dt == F4 else 1                       # elements per stored byte
-    args = (M, N, K, Ad[shift:], per * la, sAd[shift:], lsa, Bd[shift:], per * lb, sBd[shift:], lsb, bd, Cd, ldc)
+    num, den = (2, 1) if dt == F4 else (4, 3) if dt in (F6, BF6) else (1, 1)      # elements per stored byte
+    args = (M, N, K, Ad[shift:], la * num // den, sAd[shift:], lsa, Bd[shift:], lb * num // den, sBd[shift:], lsb, bd, Cd, ldc)
     path = ob.optiml_gemm_epilogue_mx_path(*args, dt)
     ob.optiml_gemm_epilogue_mx(*args, dt, act)
     torch.cuda.synchronize()
@@ -181,6 +185,75 @@ def test_8bit_pitches_offsets_and_the_benchmark_size(dt):
     M = N = K = 8192
     As, sA = quantised(7700, "A", M, K, 3, dt); Bs, sB = quantised(7700, "B", N, K, 3, dt)
     bias = synth.normal(7700, "bias", 1, N)[0]
+    got, path, _ = run(As, sA, Bs, sB, bias, M, N, K, synth.ACT_SILU, dt=dt)
+    assert path == 0
+    rows = np.array([0, 1, 255, 256, 4097, 8190, 8191]); cols = np.array([0, 31, 32, 63, 64, 300, 4096, 8190, 8191])
+    ref = oracle.gemm_epilogue_mx(np.ascontiguousarray(As[rows]), np.ascontiguousarray(sA[rows]), np.ascontiguousarray(Bs[cols]),
+                                  np.ascontiguousarray(sB[cols]), bias[cols], len(rows), len(cols), K, dtype=dt, act=synth.ACT_SILU)
+    assert e1(got[np.ix_(rows, cols)], ref) <= 2e-2
+
+
+@SIX
+@pytest.mark.parametrize("M,N,K,want_path", [(256, 256, 512, 0), (300, 520, 1024, 0), (1024, 1000, 2048, 0), (512, 264, 320, 0), (512, 264, 256, 0),
+                                             (512, 264, 192, 1), (300, 520, 480, 1), (100, 130, 256, 1), (17, 33, 32, 1)])
+def test_block_scaled_6bit_contraction_matches_the_oracle(M, N, K, want_path, dt):
+    As, sA = quantised(7800 + M + K, "A", M, K, 6, dt); Bs, sB = quantised(7800 + M + K, "B", N, K, 6, dt)
+    assert As.shape == (M, K * 3 // 4)
+    bias = synth.normal(7800 + M + K, "bias", 1, N)[0]
+    for act in (synth.ACT_NONE, synth.ACT_SILU):
+        got, path, raw = run(As, sA, Bs, sB, bias, M, N, K, act, pad_c=8, dt=dt)
+        assert path == want_path
+        ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, bias, M, N, K, dtype=dt, act=act)
+        assert np.all(np.isfinite(got)) and e1(got, ref) <= 2e-2
+        assert np.array_equal(run(As, sA, Bs, sB, bias, M, N, K, act, pad_c=8, dt=dt)[2], raw)      # bitwise repeatable
+
+
+@SIX
+def test_every_6bit_scale_byte_lands_on_its_block(dt):
+    """One-hot rows of A pick single k positions, so a code fed to the wrong k slot or block cannot hide; equal scales
+    give the exact result; then one block of one row (column) scaled by 2^20 changes exactly that row (column)."""
+    M, N, K = 300, 520, 1024
+    A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
+    As = synth.to_bits(A1, dt); Bs = synth.to_bits(synth.integers(7900, "B", N, K, -4, 4), dt)
+    sA = (120 + synth.integers(7901, "sa", M, K // 32, 0, 14)).astype(np.uint8); sB = (120 + synth.integers(7902, "sb", N, K // 32, 0, 14)).astype(np.uint8)
+    got, path, _ = run(As, sA, Bs, sB, None, M, N, K, synth.ACT_NONE, dt=dt)
+    ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, None, M, N, K, dtype=dt, act=synth.ACT_NONE)
+    assert path == 0 and np.array_equal(got, synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64))   # one product per entry: exact
+    As, _ = quantised(7910, "A", M, K, 0, dt); Bs, _ = quantised(7910, "B", N, K, 0, dt)
+    sA = np.full((M, K // 32), 127, dtype=np.uint8); sB = np.full((N, K // 32), 125, dtype=np.uint8)
+    base, _, _ = run(As, sA, Bs, sB, None, M, N, K, synth.ACT_NONE, dt=dt)
+    ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, None, M, N, K, dtype=dt, act=synth.ACT_NONE)
+    if dt == F6:
+        assert np.array_equal(base, synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64))            # equal scales: exact
+    else:
+        assert e1(base, ref) <= 2e-2
+    for row, blk in ((0, 0), (129, 5), (299, 31), (255, 16)):
+        s2 = sA.copy(); s2[row, blk] = 147
+        got, _, _ = run(As, s2, Bs, sB, None, M, N, K, synth.ACT_NONE, dt=dt)
+        assert e1(got, oracle.gemm_epilogue_mx(As, s2, Bs, sB, None, M, N, K, dtype=dt, act=synth.ACT_NONE)) <= 2e-2
+        others = np.delete(np.arange(M), row)
+        assert np.array_equal(got[others], base[others]) and not np.array_equal(got[row], base[row])
+    for col, blk in ((0, 1), (519, 30), (256, 9)):
+        s2 = sB.copy(); s2[col, blk] = 147
+        got, _, _ = run(As, sA, Bs, s2, None, M, N, K, synth.ACT_NONE, dt=dt)
+        assert e1(got, oracle.gemm_epilogue_mx(As, sA, Bs, s2, None, M, N, K, dtype=dt, act=synth.ACT_NONE)) <= 2e-2
+        others = np.delete(np.arange(N), col)
+        assert np.array_equal(got[:, others], base[:, others])
+
+
+@SIX
+def test_6bit_pitches_offsets_and_the_benchmark_size(dt):
+    M, N, K = 264, 304, 640
+    As, sA = quantised(8000, "A", M, K, 4, dt); Bs, sB = quantised(8000, "B", N, K, 4, dt)
+    bias = synth.normal(8000, "bias", 1, N)[0]
+    ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, bias, M, N, K, dtype=dt, act=synth.ACT_NONE)
+    # the operands are copied: any pitch that keeps rows on bytes (extra bytes a multiple of 3), any address
+    for kw in (dict(pitch=48, spitch=2), dict(pitch=48, spitch=4, shift=16), dict(pitch=3, spitch=1), dict(shift=3), dict(pitch=6, spitch=3, sshift=1)):
+        got, path, _ = run(As, sA, Bs, sB, bias, M, N, K, synth.ACT_NONE, dt=dt, **kw)
+        assert path == 0 and e1(got, ref) <= 2e-2, kw
+    M = N = K = 8192
+    As, sA = quantised(8100, "A", M, K, 3, dt); Bs, sB = quantised(8100, "B", N, K, 3, dt)
+    bias = synth.normal(8100, "bias", 1, N)[0]
     got, path, _ = run(As, sA, Bs, sB, bias, M, N, K, synth.ACT_SILU, dt=dt)
     assert path == 0
     rows = np.array([0, 1, 255, 256, 4097, 8190, 8191]); cols = np.array([0, 31, 32, 63, 64, 300, 4096, 8190, 8191])

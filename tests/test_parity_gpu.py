@@ -20,7 +20,8 @@ from helpers import e1, store
 pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, F8, F4, BF8 = synth.DTYPE_F32, synth.DTYPE_BF16, synth.DTYPE_F16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2
-DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8, "f4": F4, "bf8": BF8}
+F6, BF6 = synth.DTYPE_F6E2M3, synth.DTYPE_F6E3M2
+DT_OF = {"f32": F32, "bf16": BF16, "f16": F16, "f8": F8, "f4": F4, "bf8": BF8, "f6": F6, "bf6": BF6}
 BOTH_F8 = pytest.mark.parametrize("f8", [F8, BF8], ids=["e4m3", "e5m2"])      # the two 8-bit types share every kernel
 F8_TAG = {F8: "f8", BF8: "bf8"}
 ACTS = (synth.ACT_NONE, synth.ACT_RELU, synth.ACT_GELU_TANH, synth.ACT_SILU)
@@ -52,6 +53,8 @@ def problem_for(name):
             nk = 2 * (8 // ns) * ns + ns + (ns - 1)
             return F32, LAYOUT_OF[lay], 300, 392, 16 * nk
         return DT_OF[dt], LAYOUT_OF[lay], 300, 392, {"f8": 64, "bf8": 64, "f4": 128}.get(dt, 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
+    if name.startswith("xs_ring"):
+        return DT_OF[name.split("_")[2]], 1, 300, 392, 452    # 6-bit operands copied into 32-byte slots; K ends inside a block of 32
     if name.startswith("xk_"):
         return F8, 0, 304, 400, 448                        # 8-bit operands, B row-major: copied with k contiguous
     if name.startswith("xa_"):

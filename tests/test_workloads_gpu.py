@@ -46,7 +46,7 @@ def reference(w, Y):
 
 
 FULL_CHECK = {"c1_f32_256_relu": "full", "c2_f32_skinny16_silu": "full", "c3_f32_4096_rc_gelu": "full",
-              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full", "c4_f16_8192_silu": "sampled", "c2_bf16_skinny16_silu": "full", "c4_f8_8192_rc_silu": "sampled", "c4_bf8_8192_rc_silu": "sampled", "c4_bf16_8192_cr_silu": "sampled", "c2_f32_skinny16_rc_silu": "full", "c4_f4_8192_rc_silu": "sampled", "c4_bf16_4352_tail_silu": "sampled"}
+              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full", "c4_f16_8192_silu": "sampled", "c2_bf16_skinny16_silu": "full", "c4_f8_8192_rc_silu": "sampled", "c4_bf8_8192_rc_silu": "sampled", "c4_f6_8192_rc_silu": "sampled", "c4_bf6_8192_rc_silu": "sampled", "c4_bf16_8192_cr_silu": "sampled", "c2_f32_skinny16_rc_silu": "full", "c4_f4_8192_rc_silu": "sampled", "c4_bf16_4352_tail_silu": "sampled"}
 
 
 @pytest.mark.parametrize("name", synth.WORKLOADS + synth.BREADTH_WORKLOADS)
@@ -61,7 +61,8 @@ def test_workload_matches_oracle(name):
     # step of the value for the one rounding of a bf16 / binary16 output; below 1e-36 (SiLU of
     # z < -88, where exp(-z) overflows fp32) the kernel may return -0
     half_step = {synth.DTYPE_F32: 0.0, synth.DTYPE_BF16: 2.0 ** -8, synth.DTYPE_F16: 2.0 ** -11,
-                 synth.DTYPE_F8E4M3: 2.0 ** -8, synth.DTYPE_F4E2M1: 2.0 ** -8, synth.DTYPE_F8E5M2: 2.0 ** -8}[w.dtype]     # 8- and 4-bit operands: bf16 result
+                 synth.DTYPE_F8E4M3: 2.0 ** -8, synth.DTYPE_F4E2M1: 2.0 ** -8, synth.DTYPE_F8E5M2: 2.0 ** -8,
+                 synth.DTYPE_F6E2M3: 2.0 ** -8, synth.DTYPE_F6E3M2: 2.0 ** -8}[w.dtype]     # 8- and 4-bit operands: bf16 result
     step = half_step * 1.01 * np.abs(ref)
     e2 = float(np.max((np.abs(got - ref) - step - 1e-36) / den))
     print(f"{name}: E1 = {err:.3e}, E2 = {e2:.3e} over {ref.size} entries ({w.check})")
@@ -85,7 +86,7 @@ def test_workload_shape_is_exact_on_integers(name):
     w.check = "sampled"
     Y = run_workload(w)
     got, ref, _ = reference(w, Y)
-    if w.dtype in (synth.DTYPE_BF16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2):
+    if w.dtype in (synth.DTYPE_BF16, synth.DTYPE_F8E4M3, synth.DTYPE_F4E2M1, synth.DTYPE_F8E5M2, synth.DTYPE_F6E2M3, synth.DTYPE_F6E3M2):
         ref = synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64)
     elif w.dtype == synth.DTYPE_F16:
         ref = oracle.f16_to_double(oracle.f16_from_double(ref))
