@@ -86,62 +86,72 @@ XA_SRC = ("kernel_transpose.hip",) + RING_SRC
 GLN_SRC = ("kernel_linear_ln.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 GLN_F32_SRC = ("kernel_linear_ln.hip", "kernel_ring_f32.hpp", "kernel_tile_ring.hpp", "epilogue.hpp")
 MX_SRC = ("kernel_mx.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
+F6_SRC = ("kernel_f6.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
+MX6_SRC = ("kernel_mx.hip", "kernel_f6.hip", "kernel_tile_ring.hpp", "epilogue.hpp")
 TRAFFIC = {
     # (workload, kernel variant): per step, all of the step's kernels; KiB figures are FETCH_SIZE and WRITE_SIZE
     ("c1_f32_256_relu", "skinny_f32_dma_wk8_cg1_ns2_nt1"):
-        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "18ab754f30462bbb"},
+        {"bytes": int((827.5 * 2.0 + 256.0) * 1024), "files": SKINNY_SRC, "src": "01c09215cee846dc"},
     ("c2_f32_skinny16_silu", "skinny_f32_dma_wk4_cg2_ns2_nt1"):
-        {"bytes": int((531023.9 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "18ab754f30462bbb"},
+        {"bytes": int((531043.4 * 2.0 + 3072.0) * 1024), "files": SKINNY_SRC, "src": "01c09215cee846dc"},
     ("c3_f32_4096_rc_gelu", "ring_f32_rc_128x128_w2x4_ns4"):
-        {"bytes": int((385106.4 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "58ac71ac4f6258e6"},
+        {"bytes": int((385123.2 * 2.0 + 65536.0) * 1024), "files": RINGF_SRC, "src": "f797f1c137a37000"},
     ("c4_bf16_8192_silu", "ring_bf16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((791532.0 * 2.0 + 131244.2) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
+        {"bytes": int((798718.6 * 2.0 + 131173.1) * 1024), "files": RING_SRC, "src": "f13a7f529efa5e56"},
     ("c4_f16_8192_silu", "ring_f16_rr_256x256_w2x4_ns4_pf"):
-        {"bytes": int((797056.1 * 2.0 + 131098.1) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
+        {"bytes": int((802339.7 * 2.0 + 131101.7) * 1024), "files": RING_SRC, "src": "f13a7f529efa5e56"},
     ("c5_bf16_batched32_relu", "ring_bf16_rr_128x256_w1x4_ns3"):
-        {"bytes": int((65943.5 * 2.0 + 262198.3) * 1024), "files": RING_SRC, "src": "3d2e982616f3adf7"},
+        {"bytes": int((65939.9 * 2.0 + 262203.0) * 1024), "files": RING_SRC, "src": "f13a7f529efa5e56"},
     ("c2_bf16_skinny16_silu", "skinny_bf16_wn1_wk4_cg2_nt1_split0_il"):
-        {"bytes": int((265884.5 * 2.0 + 3584.0) * 1024), "files": SKINNY16_SRC, "src": "68f5be84ca4adfcf"},
+        {"bytes": int((265884.5 * 2.0 + 3584.0) * 1024), "files": SKINNY16_SRC, "src": "90ac2f4cb9357c61"},
     ("c4_f8_8192_rc_silu", "ring_f8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393472.1 * 2.0 + 131094.4) * 1024), "files": RING_F8_SRC, "src": "c62e8c9004a79794"},
+        {"bytes": int((393472.4 * 2.0 + 131087.5) * 1024), "files": RING_F8_SRC, "src": "13396d161ed5b389"},
     ("c4_f4_8192_rc_silu", "ring_f4_rc_256x256_w2x4_ns5_pf"):
-        {"bytes": int((196876.0 * 2.0 + 131280.4) * 1024), "files": RING_F4_SRC, "src": "68ca9c801dc0c9ab"},
+        {"bytes": int((196876.6 * 2.0 + 131181.8) * 1024), "files": RING_F4_SRC, "src": "cbc15b94695312f5"},
     ("c4_bf16_8192_cr_silu", "xa_ring"):
-        {"bytes": int((856812.0 * 2.0 + 262389.3) * 1024), "files": XA_SRC, "src": "77f6b0e72e841e55"},
+        {"bytes": int((863588.1 * 2.0 + 262487.9) * 1024), "files": XA_SRC, "src": "5258360b03c0e65c"},
     ("c2_f32_skinny16_rc_silu", "skinnyrc_f32_dma_wk4_cg4_ns2"):
-        {"bytes": int((534591.6 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "c1f42016ecdfaaad"},
+        {"bytes": int((534585.5 * 2.0 + 1024.0) * 1024), "files": SKINNY_RC_SRC, "src": "49f7af85372c758e"},
     ("s_relu", "s_relu"):
-        {"bytes": int((524309.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
+        {"bytes": int((524309.0 * 2.0 + 1048576.8) * 1024), "files": STREAMS_SRC, "src": "a9a12d5504a32b9e"},
     ("s_sigmoid", "s_sigmoid"):
-        {"bytes": int((524325.0 * 2.0 + 1048576.6) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
+        {"bytes": int((524325.0 * 2.0 + 1048577.4) * 1024), "files": STREAMS_SRC, "src": "a9a12d5504a32b9e"},
     ("s_sum", "s_sum"):
-        {"bytes": int((524397.7 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
+        {"bytes": int((524397.6 * 2.0 + 128.2) * 1024), "files": STREAMS_SRC, "src": "a9a12d5504a32b9e"},
     ("s_dot", "s_dot"):
-        {"bytes": int((1048623.7 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
+        {"bytes": int((1048623.7 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "a9a12d5504a32b9e"},
     ("s_mse", "s_mse"):
-        {"bytes": int((1048626.8 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "2e6f13a4d484cd33"},
+        {"bytes": int((1048626.9 * 2.0 + 128.3) * 1024), "files": STREAMS_SRC, "src": "a9a12d5504a32b9e"},
     ("s_transpose", "s_transpose"):
-        {"bytes": int((524319.6 * 2.0 + 1048880.6) * 1024), "files": TRANSPOSE_SRC, "src": "4c8326c86e66e7ac"},
+        {"bytes": int((524321.6 * 2.0 + 1048690.0) * 1024), "files": TRANSPOSE_SRC, "src": "6b1eb4f875ecc63c"},
     ("s_ce", "s_ce"):
-        {"bytes": int((525007.3 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
+        {"bytes": int((525007.2 * 2.0 + 64.1) * 1024), "files": ROWS_SRC, "src": "53d1735df9e83d00"},
     ("s_ln_sample", "s_ln_sample"):
-        {"bytes": int((527804.2 * 2.0 + 1053808.9) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
+        {"bytes": int((527805.5 * 2.0 + 1053770.3) * 1024), "files": ROWS_SRC, "src": "53d1735df9e83d00"},
     ("s_ln_token", "s_ln_token"):
-        {"bytes": int((524319.5 * 2.0 + 1048588.9) * 1024), "files": ROWS_SRC, "src": "88e3f1dbc34dd604"},
+        {"bytes": int((524319.5 * 2.0 + 1048587.9) * 1024), "files": ROWS_SRC, "src": "53d1735df9e83d00"},
     ("s_mhsa", "mhsa_pingpong_bf16_dk128"):
-        {"bytes": int((98427.0 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "b07642d29737a3e9"},
+        {"bytes": int((98427.0 * 2.0 + 65536.0) * 1024), "files": ATTN_SRC, "src": "25b9d901cd9d187e"},
     ("s_lce", "ring_bf16_rr_lse"):
-        {"bytes": int((1590397.4 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "b6551c90607c0565"},
+        {"bytes": int((1590397.8 * 2.0 + 33040.0) * 1024), "files": LCE_SRC, "src": "dbb033bc75a3f6a2"},
     ("s_lce_f32", "ring_f32_rr_lse"):
-        {"bytes": int((1583577.7 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "cbf4ed219c4c97d3"},
+        {"bytes": int((1583694.0 * 2.0 + 32904.0) * 1024), "files": LCE_F32_SRC, "src": "a70c8e7d881d8b06"},
     ("s_gln", "ring_bf16_rr_ln"):
-        {"bytes": int((541088.3 * 2.0 + 401408.2) * 1024), "files": GLN_SRC, "src": "68bdab067cf959df"},
+        {"bytes": int((542026.9 * 2.0 + 401408.3) * 1024), "files": GLN_SRC, "src": "11c6767e6b24ac43"},
     ("s_gln_f32", "ring_f32_rr_ln"):
-        {"bytes": int((427088.0 * 2.0 + 135284.0) * 1024), "files": GLN_F32_SRC, "src": "9e667470c976f393"},
+        {"bytes": int((427229.7 * 2.0 + 135282.1) * 1024), "files": GLN_F32_SRC, "src": "071ea73e701ef0ce"},
     ("s_mxf4", "ring_mxf4_rc_256x256_w2x4_ns4_pf"):
-        {"bytes": int((211259.7 * 2.0 + 135210.9) * 1024), "files": MX_SRC, "src": "54bc4bf2c108b92b"},
+        {"bytes": int((211267.7 * 2.0 + 135230.7) * 1024), "files": MX_SRC, "src": "e4049410cca208e6"},
     ("c4_bf8_8192_rc_silu", "ring_bf8_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((393471.7 * 2.0 + 131112.8) * 1024), "files": RING_BF8_SRC, "src": "089cb107d2a38c30"},
+        {"bytes": int((393468.5 * 2.0 + 131081.3) * 1024), "files": RING_BF8_SRC, "src": "ea8aadbc474ecf63"},
+    ("s_mxf8", "ring_mxf8_rc_256x256_w2x4_ns4_k64"):
+        {"bytes": int((420153.2 * 2.0 + 139265.0) * 1024), "files": MX_SRC, "src": "e4049410cca208e6"},
+    ("s_mxf6", "ring_mxf6_rc_256x256_w2x4_ns4_k64"):
+        {"bytes": int((469376.3 * 2.0 + 270387.8) * 1024), "files": MX6_SRC, "src": "4218b947c819c8f5"},
+    ("c4_f6_8192_rc_silu", "xs_ring_f6_rc_256x256_w2x4_ns5_k64"):
+        {"bytes": int((442683.4 * 2.0 + 262268.5) * 1024), "files": F6_SRC, "src": "e98326f20efaefcb"},
+    ("c4_bf6_8192_rc_silu", "xs_ring_bf6_rc_256x256_w2x4_ns5_k64"):
+        {"bytes": int((442683.1 * 2.0 + 262227.9) * 1024), "files": F6_SRC, "src": "e98326f20efaefcb"},
 }
 
 

@@ -23,40 +23,42 @@ typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 template <int DT> using F6Cfg = ring::Cfg<5, true, false, 4, DT, 0, true>;
 
-// One thread per (row, k-tile): 48 bytes in, 64 bytes out.  WIDE: every row starts on a 16-byte
-// boundary (three 16-byte loads); else byte loads.  Elements at or beyond K read as zero.
+// One thread per 16-byte chunk of the copy: chunk c of k-tile t holds bytes off .. off + 15 (c < 2) or off .. off + 7
+// and zeros (c >= 2) of the tile's 48 bytes, off = 0, 24, 16, 40, so a wave's stores are 1 KiB in a row and its loads
+// cover 768 contiguous bytes.  WIDE: every row starts on a 16-byte boundary (8-byte loads); else byte loads.
+// Elements at or beyond K read as zero.
 template <bool WIDE>
 __global__ __launch_bounds__(256) void f6_slots_kernel(const unsigned char *__restrict__ src, int64_t ld_bytes, int64_t stride_bytes,
                                                        int64_t rows, int64_t K, int64_t tiles, unsigned char *__restrict__ dst)
 {
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;          // k-tile
-    const int64_t r = blockIdx.y, b = blockIdx.z;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t t = id >> 2, r = blockIdx.y, b = blockIdx.z;          // k-tile, row, batch
+    const int c = (int)(id & 3);
     if (t >= tiles) return;
-    const unsigned char *in = src + b * stride_bytes + r * ld_bytes + t * 48;
+    const int off = c == 0 ? 0 : c == 1 ? 24 : c == 2 ? 16 : 40, len = c < 2 ? 16 : 8;
+    const unsigned char *in = src + b * stride_bytes + r * ld_bytes + t * 48 + off;
     const int64_t left = K - t * 64;                                      // elements of this k-tile inside K
-    const int valid = left >= 64 ? 48 : left <= 0 ? 0 : (int)(left * 3 / 4);   // bytes (K is a multiple of 4)
-    unsigned int w[12];
-    if (WIDE && valid == 48) {
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const uintx4 v = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(in) + i);
-            w[4 * i] = v[0]; w[4 * i + 1] = v[1]; w[4 * i + 2] = v[2]; w[4 * i + 3] = v[3];
+    const int valid = (left >= 64 ? 48 : left <= 0 ? 0 : (int)(left * 3 / 4)) - off;   // bytes of this chunk inside K (K is a multiple of 4)
+    typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+    uintx4 v = uintx4{0u, 0u, 0u, 0u};
+    if (WIDE && valid >= len) {
+        const uintx2 lo = __builtin_nontemporal_load(reinterpret_cast<const uintx2 *>(in));
+        v[0] = lo[0]; v[1] = lo[1];
+        if (c < 2) {
+            const uintx2 hi = __builtin_nontemporal_load(reinterpret_cast<const uintx2 *>(in + 8));
+            v[2] = hi[0]; v[3] = hi[1];
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < 12; ++i) {
-            unsigned int v = 0;
+        for (int i = 0; i < 4; ++i) {
+            unsigned int w = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (4 * i + j < valid) v |= (unsigned int)in[4 * i + j] << (8 * j);
-            w[i] = v;
+                if (4 * i + j < len && 4 * i + j < valid) w |= (unsigned int)in[4 * i + j] << (8 * j);
+            v[i] = w;
         }
     }
-    uintx4 *out = reinterpret_cast<uintx4 *>(dst + ((b * rows + r) * tiles + t) * 64);
-    out[0] = uintx4{w[0], w[1], w[2], w[3]};
-    out[1] = uintx4{w[6], w[7], w[8], w[9]};
-    out[2] = uintx4{w[4], w[5], 0u, 0u};
-    out[3] = uintx4{w[10], w[11], 0u, 0u};
+    *reinterpret_cast<uintx4 *>(dst + (((b * rows + r) * tiles + t) * 4 + c) * 16) = v;
 }
 
 Problem slot_problem(const Problem &p, const void *a, const void *b)
@@ -77,7 +79,7 @@ bool f6_supports(const Problem &p)
     if (p.dtype != DT || p.a_col() || !p.b_col() || p.K < 1 || p.M < 1 || p.N < 1 || p.batch < 1) return false;
     if ((p.K | p.lda | p.ldb | p.strideA | p.strideB) & 3) return false;
     const int64_t Kp = f6_slot_k(p.K);
-    if (p.batch > 65535 || Kp / 64 > int64_t(0x7fffffff) * 256) return false;                                            // the copy's grid
+    if (p.batch > 65535 || Kp / 64 > int64_t(0x7fffffff) * 64) return false;                                            // the copy's grid
     if (p.M > ((int64_t(1) << 40) / Kp) / p.batch || p.N > ((int64_t(1) << 40) / Kp) / p.batch) return false;            // 1 TiB of slots
     const void *ws = reinterpret_cast<const void *>(uintptr_t(256));
     return ring::supports<F6Cfg<DT>>(slot_problem(p, ws, ws));
@@ -121,7 +123,7 @@ int64_t f6_slot_k(int64_t K)
 hipError_t launch_f6_slots(const void *src, int64_t ld, int64_t stride, int64_t batch, int64_t rows, int64_t K, void *dst, hipStream_t s)
 {
     if (rows <= 0 || batch <= 0) return hipSuccess;
-    const int64_t tiles = f6_slot_k(K) / 64, bx = (tiles + 255) / 256;
+    const int64_t tiles = f6_slot_k(K) / 64, bx = (4 * tiles + 255) / 256;
     if (bx > 0x7fffffffLL || batch > 65535 || ((K | ld | stride) & 3)) return hipErrorInvalidValue;
     const int64_t ld_bytes = ld / 4 * 3, stride_bytes = stride / 4 * 3;
     const bool wide = (reinterpret_cast<uintptr_t>(src) & 15u) == 0 && ld_bytes % 16 == 0 && stride_bytes % 16 == 0;
