@@ -129,3 +129,22 @@ def test_benchmark_size_on_sampled_entries(dt):
     """8192^3 as the benchmark times it: sampled rows and columns against the oracle, exactly."""
     assert chosen(dt, 8192, 8192, 8192).startswith("xs_ring_" + TAG[dt])
     sampled_check(dt, 8192, 8192, 8192, 6100, synth.ACT_NONE, True)
+
+
+@BOTH
+def test_degenerate_shapes(dt):
+    """K = 0 gives act(bias); M = 0 or N = 0 writes nothing; a single row, a single column, K = 4 (one 3-byte group)."""
+    N = 40
+    bias = (np.arange(N, dtype=np.float32) - 20.0) / 4.0
+    empty = np.zeros((8, 0), dtype=np.uint8)
+    Y, _, _ = run_gpu(empty, np.zeros((N, 0), dtype=np.uint8), bias, 1, 8, N, 0, dt, synth.ACT_RELU, 1)
+    assert np.array_equal(Y[0], np.tile(np.maximum(bias, 0.0).astype(np.float64), (8, 1)))
+    P = torch.full((4, 64), 0x4442, dtype=torch.int16, device="cuda")
+    A = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    ob.optiml_gemm_epilogue_ex(0, 64, 64, A, 64, A, 64, None, P, 64, 1, dt, 0)
+    ob.optiml_gemm_epilogue_ex(4, 0, 64, A, 64, A, 64, None, P, 64, 1, dt, 0)
+    torch.cuda.synchronize()
+    assert bool((P == 0x4442).all())
+    for M, Nn, K in ((1, 8, 4), (8, 1, 4), (1, 1, 1024), (3, 5, 68)):
+        A, B, b = operands(6200 + M + K, M, Nn, K)
+        check_against_oracle(A, B, b, dtype=dt, act=synth.ACT_NONE, layout=1, exact=True)
