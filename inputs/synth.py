@@ -417,7 +417,7 @@ WORKLOADS = ("c1_f32_256_relu", "c2_f32_skinny16_silu", "c3_f32_4096_rc_gelu",
              "c4_bf16_8192_silu", "c5_bf16_batched32_relu")
 BREADTH_WORKLOADS = ("c4_f16_8192_silu", "c2_bf16_skinny16_silu", "c4_f8_8192_rc_silu", "c4_bf8_8192_rc_silu", "c4_bf16_8192_cr_silu",
                      "c2_f32_skinny16_rc_silu", "c4_f4_8192_rc_silu", "c4_f6_8192_rc_silu", "c4_bf6_8192_rc_silu",
-                     "c4_bf16_4352_tail_silu")     # further dtypes and shapes
+                     "c2_f6_skinny16_rc_silu", "c4_bf16_4352_tail_silu")     # further dtypes and shapes
 
 
 # shape of every workload without its data: (batch, M, N, K, layout, dtype, act)
@@ -435,6 +435,7 @@ SPECS = {
     "c4_f4_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F4E2M1, ACT_SILU),
     "c4_f6_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F6E2M3, ACT_SILU),
     "c4_bf6_8192_rc_silu": (1, 8192, 8192, 8192, LAYOUT_RC, DTYPE_F6E3M2, ACT_SILU),
+    "c2_f6_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F6E2M3, ACT_SILU),
     "c4_bf16_4352_tail_silu": (1, 4352, 4352, 8192, LAYOUT_RR, DTYPE_BF16, ACT_SILU),
     "c2_f32_skinny16_rc_silu": (1, 16, 16384, 16384, LAYOUT_RC, DTYPE_F32, ACT_SILU),
 }
@@ -508,6 +509,11 @@ def make_workload(name: str, scale: int = 1) -> Workload:
         return Workload(name, 1, M, N, K, dt, ACT_SILU, LAYOUT_RC, 3,
                         _store(normal(3, "A", M, K), dt), _store(normal(3, "B", K, N), dt, transpose=True),
                         normal(3, "bias", 1, N), check="full" if s >= 16 else "sampled")
+    if name == "c2_f6_skinny16_rc_silu":       # config 2's shape in 6-bit E2M3 operands, k contiguous in both: bound by reading B once
+        M, N, K = 16, 16384 // s, 16384 // s
+        return Workload(name, 1, M, N, K, DTYPE_F6E2M3, ACT_SILU, LAYOUT_RC, 3,
+                        _store(normal(3, "A", M, K), DTYPE_F6E2M3), _store(normal(3, "B", K, N), DTYPE_F6E2M3, transpose=True),
+                        normal(3, "bias", 1, N), check="full" if s >= 8 else "sampled")
     if name == "c4_bf16_4352_tail_silu":       # 17 x 17 tiles of 256 x 256: one more than a round of 256, K as in config 4
         M = N = 4352 // s; K = 8192 // s
         return Workload(name, 1, M, N, K, DTYPE_BF16, ACT_SILU, LAYOUT_RR, 3,

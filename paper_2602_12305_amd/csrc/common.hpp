@@ -177,7 +177,7 @@ const Variant *tile_variants();            extern const int kNumTileVariants;
 const Variant *transpose_variants();       extern const int kNumTransposeVariants;
 const Variant *pad_variants();             extern const int kNumPadVariants;      // kernel_pad.hip
 const Variant *tail_variants();            constexpr int kNumTailVariants = 1;    // kernel_tail.hip
-const Variant *f6_variants();              constexpr int kNumF6Variants = 2;      // kernel_f6.hip
+const Variant *f6_variants();              constexpr int kNumF6Variants = 16;      // kernel_f6.hip
 constexpr int kTilesPerUnit = 3;           // tile shapes per (dtype, layout) unit
 constexpr int kDirectPerUnit = 4;          // direct-to-LDS kernels per (16-bit dtype, B layout)
 constexpr int kRingPerUnit = 5;            // ring-of-stages 16-bit kernels per B layout (three one-tile, one persistent, one 128 x 256)

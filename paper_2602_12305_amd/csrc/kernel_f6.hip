@@ -111,6 +111,291 @@ hipError_t f6_launch(const Problem &p, hipStream_t s)
     return ring::launch<F6Cfg<DT>>(slot_problem(p, wa, wb), s);
 }
 
+// ---- up to 16 rows: the dense form straight into registers ---------------------------------------
+// C (M <= 16 rows) = act(A . B + bias) is bound by reading B once.  The 128-deep form of the matrix
+// instruction takes from lane l the 32 values k = 32 (l / 16) .. + 31 of row l % 16 of each operand: 24
+// contiguous bytes of a dense row, which three 8-byte loads fetch as they lie in memory - no copy, no
+// LDS.  A wave owns 16 columns of C (16 rows of B, stored [N][K]); the WK waves of a workgroup take
+// every WK-th run of U k-steps of 128 and add their 16 x 16 partial sums through LDS; the loads of
+// the next run are issued before the current run is multiplied.  A (16 x K, at most 192 KiB at K =
+// 16384) is re-read by every wave from the caches.  Needs rows that start on 8-byte boundaries
+// (pitches multiples of 32 elements = 24 bytes) and K a multiple of 32.
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx8 __attribute__((ext_vector_type(8)));
+
+// this lane's block of a k-step: inside K, or zeros (K is a whole number of blocks; a lane whose block lies beyond K
+// reads the first block of its row instead and drops it)
+template <bool ONCE>
+__device__ __forceinline__ void f6_fetch(const unsigned char *row, int64_t step, int grp, int64_t blocks, unsigned int (&f)[6])
+{
+    const bool inside = step * 4 + grp < blocks;
+    const uintx2 *src = reinterpret_cast<const uintx2 *>(row + (inside ? step * 96 : -(int64_t)grp * 24));   // 24 bytes on an 8-byte boundary
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uintx2 v = ONCE ? __builtin_nontemporal_load(src + i) : src[i];
+        f[2 * i] = inside ? v[0] : 0u;
+        f[2 * i + 1] = inside ? v[1] : 0u;
+    }
+}
+
+// first operand B: acc[r] of lane l = sum_k B[n0 + 4 (l / 16) + r][k] A[l % 16][k]
+template <int DT>
+__device__ __forceinline__ floatx4 f6_mma(const unsigned int (&a)[6], const unsigned int (&b)[6], floatx4 acc)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int F = F8F6F4Code<DT>::value;
+    const intx8 a8 = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)a[4], (int)a[5], 0, 0};
+    const intx8 b8 = {(int)b[0], (int)b[1], (int)b[2], (int)b[3], (int)b[4], (int)b[5], 0, 0};
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b8, a8, acc, F, F, 0, 0, 0, 0);
+#else
+    return acc;
+#endif
+}
+
+// CG groups of 16 columns per wave (an A fragment serves CG matrix instructions), WK waves along k, U k-steps per run
+template <int CG, int U> struct F6Set { unsigned int a[U][6], b[U][CG][6]; };
+
+template <int DT, int CG, int WK, int U>
+__global__ __launch_bounds__(64 * WK) void f6_stream_kernel(Problem p, int64_t lda_bytes, int64_t ldb_bytes, int64_t sa_bytes, int64_t sb_bytes)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __shared__ float part[WK][CG][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane & 15, grp = lane >> 4;
+    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG), batch = blockIdx.y;
+    const int64_t m = row < p.M ? row : p.M - 1;                           // lanes beyond M or N read the last row, store nothing
+    const unsigned char *a = static_cast<const unsigned char *>(p.A) + batch * sa_bytes + m * lda_bytes + grp * 24;
+    const unsigned char *b[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+        const int64_t n = n0 + 16 * g + row < p.N ? n0 + 16 * g + row : p.N - 1;
+        b[g] = static_cast<const unsigned char *>(p.B) + batch * sb_bytes + n * ldb_bytes + grp * 24;
+    }
+    const int64_t steps = (p.K + 127) / 128;                               // k-steps of 128 elements = 96 bytes a row
+    const int64_t blocks = p.K / 32;                                       // whole blocks of 32 elements in a row
+    floatx4 acc[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[g] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+    F6Set<CG, U> cur, nxt;
+    auto fetch = [&](int64_t run, F6Set<CG, U> &f) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            f6_fetch<false>(a, run * U + u, grp, blocks, f.a[u]);
+#pragma unroll
+            for (int g = 0; g < CG; ++g) f6_fetch<true>(b[g], run * U + u, grp, blocks, f.b[u][g]);
+        }
+    };
+    auto multiply = [&](const F6Set<CG, U> &f) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < CG; ++g) acc[g] = f6_mma<DT>(f.a[u], f.b[u][g], acc[g]);
+    };
+    // runs of U steps, dealt to the waves in turn; a fetch beyond the last step yields zeros without touching memory
+    // beyond the rows, so the two halves of the loop need no conditions
+    const int64_t runs = (steps + U - 1) / U;
+    fetch(wave, cur);
+    for (int64_t run = wave; run < runs; run += 2 * WK) {
+        fetch(run + WK, nxt);
+        multiply(cur);
+        fetch(run + 2 * WK, cur);
+        multiply(nxt);
+    }
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][g][r][lane] = acc[g][r];
+    __syncthreads();
+    unsigned short *C = static_cast<unsigned short *>(p.C) + batch * p.strideC;
+    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
+    // the WK waves share the CG x 4 values of every lane position
+    for (int idx = wave; idx < CG * 4; idx += WK) {
+        const int g = idx >> 2, r = idx & 3;
+        float z = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WK; ++w) z += part[w][g][r][lane];
+        const int64_t col = n0 + 16 * g + 4 * grp + r;                      // this lane: row `row` of C
+        if (row < p.M && col < p.N) {
+            if (bias) z += p.bias_row ? bias[row] : bias[col];
+            C[row * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
+        }
+    }
+#endif
+}
+
+// The same contraction with the rows brought in by LDS-DMA: a lane's three 8-byte loads at a 24-byte stride over 16
+// rows make poor use of the memory pipeline (2.4 TB/s at 16 x 16384 x 16384), whereas 16-byte chunks, consecutive lanes
+// on consecutive chunks of a row, stream at the rate of the other direct-to-LDS kernels.  Per wave and k-step of 128:
+// the 96 bytes of each of A's 16 rows (two instructions, the second half idle: its lanes fetch rows again into unused
+// space) and of 16 CG rows of B (3 CG / 2 instructions; chunk f = 64 j + lane of instruction j is chunk f % 6 of row
+// f / 6) land in a private stage with rows 96 bytes apart; NS - 1 steps in flight per wave, no barriers until the sum
+// over the waves.  A lane then reads its 24 bytes as three 8-byte LDS reads.  K a multiple of 128, rows on 16-byte
+// boundaries (pitches multiples of 64 elements).
+// SUB k-steps of 128 make one stage (rows 96 SUB bytes apart): with SUB = 2 a wave's runs are 192 bytes on 64-byte
+// boundaries, whole memory requests (96-byte runs straddle them: 1.24 x the operand's bytes came from HBM).
+template <int DT, int CG, int WK, int NS, int SUB>
+__global__ __launch_bounds__(64 * WK) void f6_dma_kernel(Problem p, int64_t lda_bytes, int64_t ldb_bytes, int64_t sa_bytes, int64_t sb_bytes)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int CH = 6 * SUB, PITCH = 16 * CH;                           // 16-byte chunks and bytes of a row in a stage
+    constexpr int A_INSTR = (16 * CH + 63) / 64, B_INSTR = 16 * CG * CH / 64, A_AREA = A_INSTR * 1024;
+    constexpr int STAGE = A_AREA + B_INSTR * 1024, LOADS = A_INSTR + B_INSTR;
+    static_assert((16 * CG * CH) % 64 == 0 && (NS - 1) * LOADS < 64, "whole instructions; the counted wait has six bits");
+    static_assert(WK * CG * 4 * 64 * 4 <= WK * NS * STAGE, "the reduction buffer reuses the staging area");
+    extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
+    ring::lds_char *const lds = (ring::lds_char *)lds_raw;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), row = lane & 15, grp = lane >> 4;
+    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG), batch = blockIdx.y;
+    const char *a_base = static_cast<const char *>(p.A) + batch * sa_bytes;
+    const char *b_base = static_cast<const char *>(p.B) + batch * sb_bytes + n0 * ldb_bytes;
+    // global side (rows beyond M or N fetch the last row again: their sums are never stored)
+    uint32_t a_off[A_INSTR], b_off[B_INSTR];
+#pragma unroll
+    for (int j = 0; j < A_INSTR; ++j) {
+        const int f = (64 * j + lane) % (16 * CH);
+        const int64_t r = f / CH < p.M ? f / CH : p.M - 1;
+        a_off[j] = (uint32_t)(r * lda_bytes + (f % CH) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < B_INSTR; ++j) {
+        const int f = 64 * j + lane;
+        const int64_t r = n0 + f / CH < p.N ? f / CH : p.N - 1 - n0;
+        b_off[j] = (uint32_t)(r * ldb_bytes + (f % CH) * 16);
+    }
+    const uint32_t wave_lds = (uint32_t)reinterpret_cast<uintptr_t>(lds) + wave * (NS * STAGE);
+    auto issue = [&](int64_t step, int slot) {
+        const char *ga = ring::scalar_ptr(a_base + step * PITCH), *gb = ring::scalar_ptr(b_base + step * PITCH);
+        const uint32_t d = __builtin_amdgcn_readfirstlane(wave_lds + slot * STAGE);
+#pragma unroll
+        for (int j = 0; j < A_INSTR; ++j) ring::dma_load16(ga, a_off[j], d + j * 1024);
+#pragma unroll
+        for (int j = 0; j < B_INSTR; ++j) ring::dma_load16_once(gb, b_off[j], d + A_AREA + j * 1024);
+    };
+    const int rd = row * PITCH + grp * 24;                                 // this lane's first block within a group of 16 rows
+    floatx4 acc[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[g] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // this wave's steps: wave, wave + WK, ...
+    const int64_t steps = p.K / (128 * SUB);
+    const int64_t mine = steps > wave ? (steps - wave + WK - 1) / WK : 0;
+    auto step_of = [&](int64_t i) { return wave + i * WK; };
+    if (mine > 0) {
+        // NS - 1 steps in flight (past the end the last step is fetched again, never used, so that the wait counts
+        // stay uniform)
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(step_of(s < mine ? s : mine - 1), s);
+        for (int64_t i = 0; i < mine; ++i) {
+            const int slot = (int)(i % NS);
+            const int64_t nxt = i + NS - 1;
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);                    // lgkmcnt(0): the previous step's LDS reads have returned
+            issue(step_of(nxt < mine ? nxt : mine - 1), (int)(nxt % NS));
+            ring::wait_vmcnt<(NS - 1) * LOADS>();                  // step i has landed; its LDS reads below are new
+            asm volatile("" ::: "memory");
+            const ring::lds_char *st = lds + wave * (NS * STAGE) + slot * STAGE;
+#pragma unroll
+            for (int u = 0; u < SUB; ++u) {
+                unsigned int a[6], b[CG][6];
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const uintx2 v = *reinterpret_cast<const __attribute__((address_space(3))) uintx2 *>(st + rd + u * 96 + 8 * t);
+                    a[2 * t] = v[0]; a[2 * t + 1] = v[1];
+                }
+#pragma unroll
+                for (int g = 0; g < CG; ++g)
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) {
+                        const uintx2 v = *reinterpret_cast<const __attribute__((address_space(3))) uintx2 *>(st + A_AREA + g * 16 * PITCH + rd + u * 96 + 8 * t);
+                        b[g][2 * t] = v[0]; b[g][2 * t + 1] = v[1];
+                    }
+#pragma unroll
+                for (int g = 0; g < CG; ++g) acc[g] = f6_mma<DT>(a, b[g], acc[g]);
+            }
+            asm volatile("" ::: "memory");                          // the reads are done before the slot is refilled
+        }
+        ring::wait_vmcnt<0>();
+    }
+    // sum the WK waves in wave order (the staging area is free now)
+    __syncthreads();
+    __attribute__((address_space(3))) float *part = (__attribute__((address_space(3))) float *)lds;
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[((wave * CG + g) * 4 + r) * 64 + lane] = acc[g][r];
+    __syncthreads();
+    unsigned short *C = static_cast<unsigned short *>(p.C) + batch * p.strideC;
+    const float *bias = p.bias ? p.bias + batch * p.strideBias : nullptr;
+    for (int idx = wave; idx < CG * 4; idx += WK) {
+        const int g = idx >> 2, r = idx & 3;
+        float z = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WK; ++w) z += part[((w * CG + g) * 4 + r) * 64 + lane];
+        const int64_t col = n0 + 16 * g + 4 * grp + r;                      // this lane: row `row` of C
+        if (row < p.M && col < p.N) {
+            if (bias) z += p.bias_row ? bias[row] : bias[col];
+            C[row * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
+        }
+    }
+#endif
+}
+
+template <int DT, int CG, int SUB>
+bool f6_dma_supports(const Problem &p)
+{
+    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 || p.N < 1 || p.K < 128 * SUB || p.K % (128 * SUB) != 0 || p.batch < 1 ||
+        p.batch > 65535)
+        return false;
+    // rows of 16-byte chunks; SUB >= 2: runs of 96 SUB bytes on 64-byte boundaries
+    constexpr int64_t kPitch = SUB == 1 ? 64 : 256, kBase = SUB == 1 ? 16 : 64;
+    if ((p.lda | p.ldb | p.strideA | p.strideB) & (kPitch - 1)) return false;
+    if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & (uintptr_t)(kBase - 1)) return false;
+    if (p.lda >= (int64_t(1) << 26) || p.ldb >= (int64_t(1) << 24)) return false;          // 32-bit offsets within a block of rows
+    return (p.N + 16 * CG - 1) / (16 * CG) <= 0x7fffffffLL;
+}
+
+template <int DT, int CG, int WK, int NS, int SUB>
+hipError_t f6_dma_launch(const Problem &p, hipStream_t s)
+{
+    constexpr int LDS_BYTES = WK * NS * ((16 * 6 * SUB + 63) / 64 * 1024 + 16 * CG * 6 * SUB / 64 * 1024);
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    if (!f6_dma_supports<DT, CG, SUB>(p)) return hipErrorInvalidValue;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&f6_dma_kernel<DT, CG, WK, NS, SUB>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((f6_dma_kernel<DT, CG, WK, NS, SUB>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)p.batch), dim3(64 * WK),
+                       LDS_BYTES, s, p, p.lda / 4 * 3, p.ldb / 4 * 3, p.strideA / 4 * 3, p.strideB / 4 * 3);
+    return hipGetLastError();
+}
+
+template <int DT>
+bool f6_stream_supports(const Problem &p)
+{
+    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 || p.N < 1 || p.K < 32 || p.batch < 1 || p.batch > 65535) return false;
+    if ((p.K | p.lda | p.ldb | p.strideA | p.strideB) & 31) return false;                   // rows of 24-byte blocks on 8-byte boundaries
+    if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 7u) return false;
+    return (p.N + 15) / 16 <= 0x7fffffffLL;
+}
+
+// B once at RATE GB/s (measured at 16 x 16384 x 16384) when every CU has a workgroup, proportionally longer below that;
+// one launch
+template <int CG, int RATE>
+double f6_stream_estimate(const Problem &p)
+{
+    const double wgs = (double)((p.N + 16 * CG - 1) / (16 * CG)) * (double)p.batch, full = (double)compute_units();
+    const double bytes = (double)p.batch * (double)p.N * (double)p.K * 0.75;
+    return 4.0 + bytes / (1e3 * RATE) * (wgs >= full ? 1.0 : full / wgs);
+}
+
+template <int DT, int CG, int WK, int U>
+hipError_t f6_stream_launch(const Problem &p, hipStream_t s)
+{
+    if (!f6_stream_supports<DT>(p)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((f6_stream_kernel<DT, CG, WK, U>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)p.batch), dim3(64 * WK), 0, s, p,
+                       p.lda / 4 * 3, p.ldb / 4 * 3, p.strideA / 4 * 3, p.strideB / 4 * 3);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // whole k-tiles of 64, at least as many as the ring is deep
@@ -151,7 +436,22 @@ const Variant *f6_variants()
         {"xs_ring_f6_rc_256x256_w2x4_ns5_k64", f6_supports<DT_F6>, f6_launch<DT_F6>, 256, 256,
          reinterpret_cast<const void *>(&ring::gemm_ring_kernel<F6Cfg<DT_F6>>), nullptr, true, f6_estimate},
         {"xs_ring_bf6_rc_256x256_w2x4_ns5_k64", f6_supports<DT_BF6>, f6_launch<DT_BF6>, 256, 256,
-         reinterpret_cast<const void *>(&ring::gemm_ring_kernel<F6Cfg<DT_BF6>>), nullptr, true, f6_estimate}};
+         reinterpret_cast<const void *>(&ring::gemm_ring_kernel<F6Cfg<DT_BF6>>), nullptr, true, f6_estimate},
+#define F6_STREAM(DT, TAG, CG, WK, U, RATE)                                                                                     \
+    {"stream6_" TAG "_rc_cg" #CG "_wk" #WK "_u" #U, f6_stream_supports<DT>, f6_stream_launch<DT, CG, WK, U>, 16, 16 * CG,       \
+     reinterpret_cast<const void *>(&f6_stream_kernel<DT, CG, WK, U>), nullptr, true, f6_stream_estimate<CG, RATE>}
+        F6_STREAM(DT_F6, "f6", 1, 4, 4, 2000), F6_STREAM(DT_BF6, "bf6", 1, 4, 4, 2000),
+        F6_STREAM(DT_F6, "f6", 2, 4, 4, 2300), F6_STREAM(DT_BF6, "bf6", 2, 4, 4, 2300),
+        F6_STREAM(DT_F6, "f6", 4, 8, 2, 2600), F6_STREAM(DT_BF6, "bf6", 4, 8, 2, 2600),
+#define F6_DMA(DT, TAG, CG, WK, NS, SUB, RATE)                                                                                            \
+    {"stream6_" TAG "_rc_dma_cg" #CG "_wk" #WK "_ns" #NS "_sub" #SUB, f6_dma_supports<DT, CG, SUB>, f6_dma_launch<DT, CG, WK, NS, SUB>, 16, \
+     16 * CG, reinterpret_cast<const void *>(&f6_dma_kernel<DT, CG, WK, NS, SUB>), nullptr, true, f6_stream_estimate<CG, RATE>}
+        F6_DMA(DT_F6, "f6", 2, 4, 4, 1, 4000), F6_DMA(DT_BF6, "bf6", 2, 4, 4, 1, 4000),
+        F6_DMA(DT_F6, "f6", 4, 8, 2, 1, 4100), F6_DMA(DT_BF6, "bf6", 4, 8, 2, 1, 4100),
+        F6_DMA(DT_F6, "f6", 2, 4, 3, 2, 4400), F6_DMA(DT_BF6, "bf6", 2, 4, 3, 2, 4400),
+        F6_DMA(DT_F6, "f6", 4, 4, 2, 2, 4900), F6_DMA(DT_BF6, "bf6", 4, 4, 2, 2, 4900)};
+#undef F6_DMA
+#undef F6_STREAM
     return v;
 }
 

@@ -38,11 +38,13 @@ def operands(seed, M, N, K, batch=None, scale=2.0):
 
 
 @BOTH
-@pytest.mark.parametrize("M,N,K,family", [(300, 520, 1024, "xs_ring"), (5, 1000, 2048, "xs_ring"), (129, 264, 228, "xs_ring"),
+@pytest.mark.parametrize("M,N,K,family", [(300, 520, 1024, "xs_ring"), (5, 1000, 2048, "stream6"), (16, 4100, 4128, "stream6"), (1, 17, 32, "stream6"), (16, 1030, 4224, "stream6"),
+                                          (3, 16400, 1152, "stream6"),
+                                          (5, 1000, 2052, "xs_ring"), (129, 264, 228, "xs_ring"),
                                           (64, 64, 512, "xs_ring"), (100, 130, 36, "generic"), (33, 65, 4, "generic"),
                                           (300, 520, 100, "generic")])
 def test_dispatched_kernels_are_exact_and_match_the_oracle(dt, M, N, K, family):
-    assert chosen(dt, M, N, K).startswith(family + ("_" + TAG[dt] if family == "xs_ring" else ""))
+    assert chosen(dt, M, N, K).startswith(family + ("_" + TAG[dt] if family != "generic" else ""))
     A, B, bias = operands(5600 + M + K, M, N, K)
     for act in (synth.ACT_NONE, synth.ACT_RELU):
         check_against_oracle(A, B, bias, dtype=dt, act=act, layout=1, exact=True)

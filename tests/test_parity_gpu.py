@@ -55,6 +55,9 @@ def problem_for(name):
         return DT_OF[dt], LAYOUT_OF[lay], 300, 392, {"f8": 64, "bf8": 64, "f4": 128}.get(dt, 32) * (4 * ns - 1)   # tile count not a multiple of the ring depth
     if name.startswith("xs_ring"):
         return DT_OF[name.split("_")[2]], 1, 300, 392, 452    # 6-bit operands copied into 32-byte slots; K ends inside a block of 32
+    if name.startswith("stream6"):
+        # 6-bit operands, up to 16 rows, read as they lie in memory: K whole blocks of 32 (through LDS: whole steps of 128)
+        return DT_OF[name.split("_")[1]], 1, 13, 1000, 1536 if "_dma_" in name else 1248
     if name.startswith("xk_"):
         return F8, 0, 304, 400, 448                        # 8-bit operands, B row-major: copied with k contiguous
     if name.startswith("xa_"):

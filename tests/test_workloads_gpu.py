@@ -46,7 +46,7 @@ def reference(w, Y):
 
 
 FULL_CHECK = {"c1_f32_256_relu": "full", "c2_f32_skinny16_silu": "full", "c3_f32_4096_rc_gelu": "full",
-              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full", "c4_f16_8192_silu": "sampled", "c2_bf16_skinny16_silu": "full", "c4_f8_8192_rc_silu": "sampled", "c4_bf8_8192_rc_silu": "sampled", "c4_f6_8192_rc_silu": "sampled", "c4_bf6_8192_rc_silu": "sampled", "c4_bf16_8192_cr_silu": "sampled", "c2_f32_skinny16_rc_silu": "full", "c4_f4_8192_rc_silu": "sampled", "c4_bf16_4352_tail_silu": "sampled"}
+              "c4_bf16_8192_silu": "sampled", "c5_bf16_batched32_relu": "full", "c4_f16_8192_silu": "sampled", "c2_bf16_skinny16_silu": "full", "c4_f8_8192_rc_silu": "sampled", "c4_bf8_8192_rc_silu": "sampled", "c4_f6_8192_rc_silu": "sampled", "c4_bf6_8192_rc_silu": "sampled", "c2_f6_skinny16_rc_silu": "sampled", "c4_bf16_8192_cr_silu": "sampled", "c2_f32_skinny16_rc_silu": "full", "c4_f4_8192_rc_silu": "sampled", "c4_bf16_4352_tail_silu": "sampled"}
 
 
 @pytest.mark.parametrize("name", synth.WORKLOADS + synth.BREADTH_WORKLOADS)
