@@ -377,14 +377,18 @@ bool f6_stream_supports(const Problem &p)
     return (p.N + 15) / 16 <= 0x7fffffffLL;
 }
 
-// B once at RATE GB/s (measured at 16 x 16384 x 16384) when every CU has a workgroup, proportionally longer below that;
-// one launch
-template <int CG, int RATE>
+// B once at RATE GB/s (measured at 16 x 16384 x 16384, every CU with a workgroup), one launch.  Fewer workgroups than
+// CUs: the rate falls with the square root of the share (16 x 8192 x 8192 at 64 columns a workgroup: 128 workgroups,
+// 18.6 us); more: whole rounds of workgroups (13 x 10016 x 12032 at 32 columns: 313 workgroups take two rounds, 30.9 us
+// against 25.4 us for 157 of 64 columns).
+// PER_CU: workgroups a CU holds at a time (registers or LDS).
+template <int CG, int RATE, int PER_CU>
 double f6_stream_estimate(const Problem &p)
 {
-    const double wgs = (double)((p.N + 16 * CG - 1) / (16 * CG)) * (double)p.batch, full = (double)compute_units();
+    const double wgs = (double)((p.N + 16 * CG - 1) / (16 * CG)) * (double)p.batch, full = (double)compute_units(), cap = full * PER_CU;
     const double bytes = (double)p.batch * (double)p.N * (double)p.K * 0.75;
-    return 4.0 + bytes / (1e3 * RATE) * (wgs >= full ? 1.0 : full / wgs);
+    const double slow = wgs >= cap ? std::ceil(wgs / cap) * cap / wgs : wgs >= full ? 1.0 : std::sqrt(full / wgs);
+    return 4.0 + bytes / (1e3 * RATE) * slow;
 }
 
 template <int DT, int CG, int WK, int U>
@@ -437,19 +441,19 @@ const Variant *f6_variants()
          reinterpret_cast<const void *>(&ring::gemm_ring_kernel<F6Cfg<DT_F6>>), nullptr, true, f6_estimate},
         {"xs_ring_bf6_rc_256x256_w2x4_ns5_k64", f6_supports<DT_BF6>, f6_launch<DT_BF6>, 256, 256,
          reinterpret_cast<const void *>(&ring::gemm_ring_kernel<F6Cfg<DT_BF6>>), nullptr, true, f6_estimate},
-#define F6_STREAM(DT, TAG, CG, WK, U, RATE)                                                                                     \
+#define F6_STREAM(DT, TAG, CG, WK, U, RATE, PER_CU)                                                                                  \
     {"stream6_" TAG "_rc_cg" #CG "_wk" #WK "_u" #U, f6_stream_supports<DT>, f6_stream_launch<DT, CG, WK, U>, 16, 16 * CG,       \
-     reinterpret_cast<const void *>(&f6_stream_kernel<DT, CG, WK, U>), nullptr, true, f6_stream_estimate<CG, RATE>}
-        F6_STREAM(DT_F6, "f6", 1, 4, 4, 2000), F6_STREAM(DT_BF6, "bf6", 1, 4, 4, 2000),
-        F6_STREAM(DT_F6, "f6", 2, 4, 4, 2300), F6_STREAM(DT_BF6, "bf6", 2, 4, 4, 2300),
-        F6_STREAM(DT_F6, "f6", 4, 8, 2, 2600), F6_STREAM(DT_BF6, "bf6", 4, 8, 2, 2600),
-#define F6_DMA(DT, TAG, CG, WK, NS, SUB, RATE)                                                                                            \
+     reinterpret_cast<const void *>(&f6_stream_kernel<DT, CG, WK, U>), nullptr, true, f6_stream_estimate<CG, RATE, PER_CU>}
+        F6_STREAM(DT_F6, "f6", 1, 4, 4, 2000, 4), F6_STREAM(DT_BF6, "bf6", 1, 4, 4, 2000, 4),
+        F6_STREAM(DT_F6, "f6", 2, 4, 4, 2300, 3), F6_STREAM(DT_BF6, "bf6", 2, 4, 4, 2300, 3),
+        F6_STREAM(DT_F6, "f6", 4, 8, 2, 2600, 1), F6_STREAM(DT_BF6, "bf6", 4, 8, 2, 2600, 1),
+#define F6_DMA(DT, TAG, CG, WK, NS, SUB, RATE, PER_CU)                                                                                      \
     {"stream6_" TAG "_rc_dma_cg" #CG "_wk" #WK "_ns" #NS "_sub" #SUB, f6_dma_supports<DT, CG, SUB>, f6_dma_launch<DT, CG, WK, NS, SUB>, 16, \
-     16 * CG, reinterpret_cast<const void *>(&f6_dma_kernel<DT, CG, WK, NS, SUB>), nullptr, true, f6_stream_estimate<CG, RATE>}
-        F6_DMA(DT_F6, "f6", 2, 4, 4, 1, 4000), F6_DMA(DT_BF6, "bf6", 2, 4, 4, 1, 4000),
-        F6_DMA(DT_F6, "f6", 4, 8, 2, 1, 4100), F6_DMA(DT_BF6, "bf6", 4, 8, 2, 1, 4100),
-        F6_DMA(DT_F6, "f6", 2, 4, 3, 2, 4400), F6_DMA(DT_BF6, "bf6", 2, 4, 3, 2, 4400),
-        F6_DMA(DT_F6, "f6", 4, 4, 2, 2, 4900), F6_DMA(DT_BF6, "bf6", 4, 4, 2, 2, 4900)};
+     16 * CG, reinterpret_cast<const void *>(&f6_dma_kernel<DT, CG, WK, NS, SUB>), nullptr, true, f6_stream_estimate<CG, RATE, PER_CU>}
+        F6_DMA(DT_F6, "f6", 2, 4, 4, 1, 4000, 1), F6_DMA(DT_BF6, "bf6", 2, 4, 4, 1, 4000, 1),
+        F6_DMA(DT_F6, "f6", 4, 8, 2, 1, 4100, 1), F6_DMA(DT_BF6, "bf6", 4, 8, 2, 1, 4100, 1),
+        F6_DMA(DT_F6, "f6", 2, 4, 3, 2, 4400, 1), F6_DMA(DT_BF6, "bf6", 2, 4, 3, 2, 4400, 1),
+        F6_DMA(DT_F6, "f6", 4, 4, 2, 2, 4900, 1), F6_DMA(DT_BF6, "bf6", 4, 4, 2, 2, 4900, 1)};
 #undef F6_DMA
 #undef F6_STREAM
     return v;

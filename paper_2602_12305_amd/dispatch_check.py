@@ -1,7 +1,7 @@
 """Dispatcher check: for a list of shapes, time every kernel variant that takes the shape and compare the
 dispatcher's choice with the fastest one.
 
-    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|odd|rounds|stream|quick] [--steps N]
+    python3 -m paper_2602_12305_amd.dispatch_check [--set mid|other|batched|ragged|odd|rounds|stream|six|quick] [--steps N]
 
 Prints one line per case (shape, the dispatcher's variant and its time, the fastest variant and its time, the
 ratio) and a summary.  Inputs are N(0,1) (8-bit operands: random bytes below 120); nothing is checked for
@@ -49,6 +49,12 @@ SETS = {
     "rounds": [(dt, lay, 1) + s for dt, lay in ((1, 0), (1, 1), (2, 0))
                for s in ((4352, 4352, 4352), (4352, 4352, 8192), (4104, 4104, 4104), (4352, 4096, 4096), (4608, 4352, 4096),
                          (8448, 8448, 4096), (4352, 4352, 2048))],
+    # 6-bit operands (dense), k contiguous in both: the streaming kernels up to 16 rows, else the copy into slots + ring kernel
+    "six": [(dt, 1, 1) + s for dt in (6, 7)
+            for s in ((16, 16384, 16384), (16, 28672, 8192), (16, 8192, 8192), (4, 8192, 8192), (16, 4096, 4096), (16, 512, 16384),
+                      (16, 16384, 1024), (8, 2048, 2048), (16, 16384, 16416), (16, 4100, 4128), (16, 1030, 4224), (13, 10016, 12032),
+                      (64, 64, 1024), (300, 520, 228), (300, 520, 100), (512, 512, 512), (1024, 1024, 1024), (2048, 2048, 2048),
+                      (4096, 4096, 4096), (8192, 8192, 8192), (17, 4096, 4096), (64, 8192, 8192))],
     "quick": [(1, 1, 1, 64, 4096, 4096), (0, 1, 1, 64, 4096, 4096), (1, 2, 1, 64, 4096, 4096), (0, 0, 1, 8, 4096, 4096),
               (1, 0, 1, 2048, 2048, 2048), (0, 0, 1, 4096, 512, 4096)],
 }
@@ -75,17 +81,18 @@ def _time(prob, vid, steps, preheat_ms=20.0):
 def check(dt, lay, b, M, N, K, steps=0, names=None):
     """(name of the dispatcher's variant, its us, name of the fastest variant, its us)."""
     names = names or ob.variant_names()
-    if dt == 3:
+    num, den = {4: (1, 2), 6: (3, 4), 7: (3, 4)}.get(dt, (1, 1))     # stored bytes per element of the sub-byte types
+    if dt >= 3:
         def mk(shape):
-            return torch.randint(0, 120, shape, device="cuda", dtype=torch.uint8)
+            return torch.randint(0, 120, shape[:-1] + (shape[-1] * num // den,), device="cuda", dtype=torch.uint8)
     else:
         def mk(shape):
             return torch.randn(shape, device="cuda", dtype=TORCH_DT[dt])
     A = mk((b, K, M) if lay & 2 else (b, M, K))
     B = mk((b, N, K) if lay & 1 else (b, K, N))
     bias = torch.randn((b, N), device="cuda", dtype=torch.float32)
-    C = torch.empty((b, M, N), device="cuda", dtype=torch.bfloat16 if dt == 3 else TORCH_DT[dt])
-    lda, ldb = A.shape[-1], B.shape[-1]
+    C = torch.empty((b, M, N), device="cuda", dtype=torch.bfloat16 if dt >= 3 else TORCH_DT[dt])
+    lda, ldb = A.shape[-1] * den // num, B.shape[-1] * den // num
     prob = (b, M, N, K, A, lda, A.shape[-2] * lda, B, ldb, B.shape[-2] * ldb, bias, N, C, N, M * N, lay, dt, 3)
     pick = ob.optiml_select_variant(*prob)
     flops = 2.0 * b * M * N * K
