@@ -60,7 +60,7 @@
  *              OPTIML_LAYOUT_RC (and its mirror image with a column-major C) with K a
  *              multiple of 4, after copying both operands into the workspace with every 32
  *              elements in 32 bytes ((M + N) * max(320, K rounded up to 64) bytes per batch).
- *              Up to 16 rows (OPTIML_LAYOUT_RC, K and the pitches multiples of 32) the dense form is
+ *              Up to 128 rows (OPTIML_LAYOUT_RC, K and the pitches multiples of 32) the dense form is
  *              streamed as it lies in memory, without a copy.
  *              bias is always float; NULL means no bias.  The
  *              contraction entry points take all eight; the other entry points say

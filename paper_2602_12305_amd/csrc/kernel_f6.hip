@@ -111,8 +111,9 @@ hipError_t f6_launch(const Problem &p, hipStream_t s)
     return ring::launch<F6Cfg<DT>>(slot_problem(p, wa, wb), s);
 }
 
-// ---- up to 16 rows: the dense form straight into registers ---------------------------------------
-// C (M <= 16 rows) = act(A . B + bias) is bound by reading B once.  The 128-deep form of the matrix
+// ---- a few rows: the dense form straight into registers -------------------------------------------
+// C (up to 16 rows per workgroup; up to kF6RowBlocks such blocks, each reading B again) = act(A . B + bias) is bound by
+// reading B.  The 128-deep form of the matrix
 // instruction takes from lane l the 32 values k = 32 (l / 16) .. + 31 of row l % 16 of each operand: 24
 // contiguous bytes of a dense row, which three 8-byte loads fetch as they lie in memory - no copy, no
 // LDS.  A wave owns 16 columns of C (16 rows of B, stored [N][K]); the WK waves of a workgroup take
@@ -153,6 +154,9 @@ __device__ __forceinline__ floatx4 f6_mma(const unsigned int (&a)[6], const unsi
 #endif
 }
 
+// blocks of 16 rows the streaming kernels take (each block reads B again, from the caches when it fits)
+constexpr int64_t kF6RowBlocks = 8;
+
 // CG groups of 16 columns per wave (an A fragment serves CG matrix instructions), WK waves along k, U k-steps per run
 template <int CG, int U> struct F6Set { unsigned int a[U][6], b[U][CG][6]; };
 
@@ -162,8 +166,10 @@ __global__ __launch_bounds__(64 * WK) void f6_stream_kernel(Problem p, int64_t l
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ float part[WK][CG][4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane & 15, grp = lane >> 4;
-    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG), batch = blockIdx.y;
-    const int64_t m = row < p.M ? row : p.M - 1;                           // lanes beyond M or N read the last row, store nothing
+    // blockIdx.y: (batch, block of 16 rows of A and C)
+    const int64_t row_blocks = (p.M + 15) / 16, batch = blockIdx.y / row_blocks, m0 = 16 * (blockIdx.y % row_blocks);
+    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG);
+    const int64_t m = m0 + row < p.M ? m0 + row : p.M - 1;                 // lanes beyond M or N read the last row, store nothing
     const unsigned char *a = static_cast<const unsigned char *>(p.A) + batch * sa_bytes + m * lda_bytes + grp * 24;
     const unsigned char *b[CG];
 #pragma unroll
@@ -215,9 +221,9 @@ __global__ __launch_bounds__(64 * WK) void f6_stream_kernel(Problem p, int64_t l
 #pragma unroll
         for (int w = 0; w < WK; ++w) z += part[w][g][r][lane];
         const int64_t col = n0 + 16 * g + 4 * grp + r;                      // this lane: row `row` of C
-        if (row < p.M && col < p.N) {
-            if (bias) z += p.bias_row ? bias[row] : bias[col];
-            C[row * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
+        if (m0 + row < p.M && col < p.N) {
+            if (bias) z += p.bias_row ? bias[m0 + row] : bias[col];
+            C[(m0 + row) * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
         }
     }
 #endif
@@ -245,15 +251,16 @@ __global__ __launch_bounds__(64 * WK) void f6_dma_kernel(Problem p, int64_t lda_
     extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
     ring::lds_char *const lds = (ring::lds_char *)lds_raw;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), row = lane & 15, grp = lane >> 4;
-    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG), batch = blockIdx.y;
-    const char *a_base = static_cast<const char *>(p.A) + batch * sa_bytes;
+    const int64_t row_blocks = (p.M + 15) / 16, batch = blockIdx.y / row_blocks, m0 = 16 * (blockIdx.y % row_blocks);
+    const int64_t n0 = (int64_t)blockIdx.x * (16 * CG);
+    const char *a_base = static_cast<const char *>(p.A) + batch * sa_bytes + m0 * lda_bytes;
     const char *b_base = static_cast<const char *>(p.B) + batch * sb_bytes + n0 * ldb_bytes;
     // global side (rows beyond M or N fetch the last row again: their sums are never stored)
     uint32_t a_off[A_INSTR], b_off[B_INSTR];
 #pragma unroll
     for (int j = 0; j < A_INSTR; ++j) {
         const int f = (64 * j + lane) % (16 * CH);
-        const int64_t r = f / CH < p.M ? f / CH : p.M - 1;
+        const int64_t r = m0 + f / CH < p.M ? f / CH : p.M - 1 - m0;
         a_off[j] = (uint32_t)(r * lda_bytes + (f % CH) * 16);
     }
 #pragma unroll
@@ -332,9 +339,9 @@ __global__ __launch_bounds__(64 * WK) void f6_dma_kernel(Problem p, int64_t lda_
 #pragma unroll
         for (int w = 0; w < WK; ++w) z += part[((w * CG + g) * 4 + r) * 64 + lane];
         const int64_t col = n0 + 16 * g + 4 * grp + r;                      // this lane: row `row` of C
-        if (row < p.M && col < p.N) {
-            if (bias) z += p.bias_row ? bias[row] : bias[col];
-            C[row * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
+        if (m0 + row < p.M && col < p.N) {
+            if (bias) z += p.bias_row ? bias[m0 + row] : bias[col];
+            C[(m0 + row) * p.ldc + col] = f32_to_bf16(apply_act(z, p.act));
         }
     }
 #endif
@@ -343,8 +350,8 @@ __global__ __launch_bounds__(64 * WK) void f6_dma_kernel(Problem p, int64_t lda_
 template <int DT, int CG, int SUB>
 bool f6_dma_supports(const Problem &p)
 {
-    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 || p.N < 1 || p.K < 128 * SUB || p.K % (128 * SUB) != 0 || p.batch < 1 ||
-        p.batch > 65535)
+    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 * kF6RowBlocks || p.N < 1 || p.K < 128 * SUB || p.K % (128 * SUB) != 0 || p.batch < 1 ||
+        p.batch > 65535 / kF6RowBlocks)
         return false;
     // rows of 16-byte chunks; SUB >= 2: runs of 96 SUB bytes on 64-byte boundaries
     constexpr int64_t kPitch = SUB == 1 ? 64 : 256, kBase = SUB == 1 ? 16 : 64;
@@ -363,15 +370,17 @@ hipError_t f6_dma_launch(const Problem &p, hipStream_t s)
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&f6_dma_kernel<DT, CG, WK, NS, SUB>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((f6_dma_kernel<DT, CG, WK, NS, SUB>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)p.batch), dim3(64 * WK),
-                       LDS_BYTES, s, p, p.lda / 4 * 3, p.ldb / 4 * 3, p.strideA / 4 * 3, p.strideB / 4 * 3);
+    hipLaunchKernelGGL((f6_dma_kernel<DT, CG, WK, NS, SUB>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)(p.batch * ((p.M + 15) / 16))),
+                       dim3(64 * WK), LDS_BYTES, s, p, p.lda / 4 * 3, p.ldb / 4 * 3, p.strideA / 4 * 3, p.strideB / 4 * 3);
     return hipGetLastError();
 }
 
 template <int DT>
 bool f6_stream_supports(const Problem &p)
 {
-    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 || p.N < 1 || p.K < 32 || p.batch < 1 || p.batch > 65535) return false;
+    if (p.dtype != DT || p.a_col() || !p.b_col() || p.M < 1 || p.M > 16 * kF6RowBlocks || p.N < 1 || p.K < 32 || p.batch < 1 ||
+        p.batch > 65535 / kF6RowBlocks)
+        return false;
     if ((p.K | p.lda | p.ldb | p.strideA | p.strideB) & 31) return false;                   // rows of 24-byte blocks on 8-byte boundaries
     if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 7u) return false;
     return (p.N + 15) / 16 <= 0x7fffffffLL;
@@ -385,8 +394,9 @@ bool f6_stream_supports(const Problem &p)
 template <int CG, int RATE, int PER_CU>
 double f6_stream_estimate(const Problem &p)
 {
-    const double wgs = (double)((p.N + 16 * CG - 1) / (16 * CG)) * (double)p.batch, full = (double)compute_units(), cap = full * PER_CU;
-    const double bytes = (double)p.batch * (double)p.N * (double)p.K * 0.75;
+    const double rb = (double)((p.M + 15) / 16);
+    const double wgs = (double)((p.N + 16 * CG - 1) / (16 * CG)) * (double)p.batch * rb, full = (double)compute_units(), cap = full * PER_CU;
+    const double bytes = (double)p.batch * (double)p.N * (double)p.K * 0.75 * rb;
     const double slow = wgs >= cap ? std::ceil(wgs / cap) * cap / wgs : wgs >= full ? 1.0 : std::sqrt(full / wgs);
     return 4.0 + bytes / (1e3 * RATE) * slow;
 }
@@ -395,7 +405,7 @@ template <int DT, int CG, int WK, int U>
 hipError_t f6_stream_launch(const Problem &p, hipStream_t s)
 {
     if (!f6_stream_supports<DT>(p)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((f6_stream_kernel<DT, CG, WK, U>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)p.batch), dim3(64 * WK), 0, s, p,
+    hipLaunchKernelGGL((f6_stream_kernel<DT, CG, WK, U>), dim3((unsigned)((p.N + 16 * CG - 1) / (16 * CG)), (unsigned)(p.batch * ((p.M + 15) / 16))), dim3(64 * WK), 0, s, p,
                        p.lda / 4 * 3, p.ldb / 4 * 3, p.strideA / 4 * 3, p.strideB / 4 * 3);
     return hipGetLastError();
 }

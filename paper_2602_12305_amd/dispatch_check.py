@@ -54,7 +54,8 @@ SETS = {
             for s in ((16, 16384, 16384), (16, 28672, 8192), (16, 8192, 8192), (4, 8192, 8192), (16, 4096, 4096), (16, 512, 16384),
                       (16, 16384, 1024), (8, 2048, 2048), (16, 16384, 16416), (16, 4100, 4128), (16, 1030, 4224), (13, 10016, 12032),
                       (64, 64, 1024), (300, 520, 228), (300, 520, 100), (512, 512, 512), (1024, 1024, 1024), (2048, 2048, 2048),
-                      (4096, 4096, 4096), (8192, 8192, 8192), (17, 4096, 4096), (64, 8192, 8192))],
+                      (4096, 4096, 4096), (8192, 8192, 8192), (17, 4096, 4096), (64, 8192, 8192), (32, 16384, 16384), (128, 8192, 8192),
+                      (128, 2048, 2048), (48, 16384, 4096), (129, 8192, 8192))],
     "quick": [(1, 1, 1, 64, 4096, 4096), (0, 1, 1, 64, 4096, 4096), (1, 2, 1, 64, 4096, 4096), (0, 0, 1, 8, 4096, 4096),
               (1, 0, 1, 2048, 2048, 2048), (0, 0, 1, 4096, 512, 4096)],
 }

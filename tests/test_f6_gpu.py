@@ -39,9 +39,9 @@ def operands(seed, M, N, K, batch=None, scale=2.0):
 
 @BOTH
 @pytest.mark.parametrize("M,N,K,family", [(300, 520, 1024, "xs_ring"), (5, 1000, 2048, "stream6"), (16, 4100, 4128, "stream6"), (1, 17, 32, "stream6"), (16, 1030, 4224, "stream6"),
-                                          (3, 16400, 1152, "stream6"),
+                                          (3, 16400, 1152, "stream6"), (40, 1000, 2048, "stream6"), (128, 520, 1056, "stream6"), (17, 4096, 4096, "stream6"),
                                           (5, 1000, 2052, "xs_ring"), (129, 264, 228, "xs_ring"),
-                                          (64, 64, 512, "xs_ring"), (100, 130, 36, "generic"), (33, 65, 4, "generic"),
+                                          (64, 64, 512, "stream6"), (100, 130, 36, "generic"), (33, 65, 4, "generic"),
                                           (300, 520, 100, "generic")])
 def test_dispatched_kernels_are_exact_and_match_the_oracle(dt, M, N, K, family):
     assert chosen(dt, M, N, K).startswith(family + ("_" + TAG[dt] if family != "generic" else ""))
@@ -68,16 +68,19 @@ def test_every_code_pair_multiplies_exactly_at_every_position_of_the_stream(dt):
     codes = np.arange(64, dtype=np.uint8)
     vals = synth.f6_codes_to_f32(codes, dt)
     want = np.outer(vals, vals).astype(np.float64)
+    xs = ob.variant_names().index("xs_ring_" + TAG[dt] + "_rc_256x256_w2x4_ns5_k64")
     for K, positions in ((4, (0, 1, 2, 3)), (128, (0, 5, 31, 32, 63, 64, 95, 127)), (320, (21, 42, 170, 319))):
-        for pos in positions:
-            rows = np.zeros((64, K), dtype=np.uint8); rows[:, pos] = codes
-            packed = synth.pack_f6(rows)
-            assert chosen(dt, 64, 64, K).startswith("xs_ring" if K >= 128 else "generic")
-            Y, _, _ = run_gpu(packed, packed, None, 1, 64, 64, K, dt, synth.ACT_NONE, 1)
-            assert np.array_equal(Y[0], want), (K, pos)
-            other = np.zeros((64, K), dtype=np.uint8); other[:, (pos + 1) % K] = codes
-            Y2, _, _ = run_gpu(synth.pack_f6(other), packed, None, 1, 64, 64, K, dt, synth.ACT_NONE, 1)
-            assert np.all(Y2[0] == 0.0), (K, pos)                                # neighbouring positions do not meet
+        # the dispatcher's kernel (the fallback for K = 4, a streaming kernel otherwise) and the copy into slots + ring kernel
+        assert chosen(dt, 64, 64, K).startswith("stream6" if K >= 128 else "generic")
+        for variant in (None, xs) if K >= 128 else (None,):
+            for pos in positions:
+                rows = np.zeros((64, K), dtype=np.uint8); rows[:, pos] = codes
+                packed = synth.pack_f6(rows)
+                Y, _, _ = run_gpu(packed, packed, None, 1, 64, 64, K, dt, synth.ACT_NONE, 1, variant=variant)
+                assert np.array_equal(Y[0], want), (K, pos, variant)
+                other = np.zeros((64, K), dtype=np.uint8); other[:, (pos + 1) % K] = codes
+                Y2, _, _ = run_gpu(synth.pack_f6(other), packed, None, 1, 64, 64, K, dt, synth.ACT_NONE, 1, variant=variant)
+                assert np.all(Y2[0] == 0.0), (K, pos, variant)                  # neighbouring positions do not meet
 
 
 @BOTH
