@@ -125,12 +125,12 @@ double oracle_f6e3m2_to_double(uint8_t code)
 static uint8_t six_bits(const void *base, int64_t idx)
 {
     const uint8_t *p = (const uint8_t *)base;
-    uint8_t code = 0;
-    for (int t = 0; t < 6; ++t) {
-        const int64_t bit = 6 * idx + t;
-        code |= (uint8_t)(((p[bit / 8] >> (bit % 8)) & 1) << t);
-    }
-    return code;
+    const int64_t bit = 6 * idx;                     /* first bit of the element in the stream */
+    const int sh = (int)(bit % 8);
+    unsigned v = p[bit / 8] >> sh;                   /* the 8 - sh bits of its first byte from there upwards */
+    if (sh > 2)                                      /* fewer than six: the rest are the low bits of the next byte */
+        v |= (unsigned)p[bit / 8 + 1] << (8 - sh);
+    return (uint8_t)(v & 63u);
 }
 
 /* OCP E8M0 block scale (8 exponent bits with bias 127, no sign, no fraction): 2^(e - 127); 255 is NaN. */
