@@ -286,7 +286,10 @@ __global__ __launch_bounds__(64 * WK) void f6_dma_kernel(Problem p, int64_t lda_
     // this wave's steps: wave, wave + WK, ...
     const int64_t steps = p.K / (128 * SUB);
     const int64_t mine = steps > wave ? (steps - wave + WK - 1) / WK : 0;
-    auto step_of = [&](int64_t i) { return wave + i * WK; };
+    // ... walked from a start that differs from workgroup to workgroup and wrapping: with a pitch that is a multiple of a
+    // few KiB, workgroups that all start at k = 0 sit on the same memory channels all the way
+    const int64_t rot = mine > 0 ? (int64_t)blockIdx.x % mine : 0;
+    auto step_of = [&](int64_t i) { return wave + ((i + rot) % mine) * WK; };
     if (mine > 0) {
         // NS - 1 steps in flight (past the end the last step is fetched again, never used, so that the wait counts
         // stay uniform)
