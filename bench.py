@@ -147,13 +147,13 @@ TRAFFIC = {
     ("s_mxf8", "ring_mxf8_rc_256x256_w2x4_ns4_k64"):
         {"bytes": int((420153.2 * 2.0 + 139265.0) * 1024), "files": MX_SRC, "src": "e4049410cca208e6"},
     ("s_mxf6", "ring_mxf6_rc_256x256_w2x4_ns4_k64"):
-        {"bytes": int((469368.6 * 2.0 + 270552.3) * 1024), "files": MX6_SRC, "src": "580fb241f891c168"},
+        {"bytes": int((469368.8 * 2.0 + 270567.0) * 1024), "files": MX6_SRC, "src": "d92288d459f78128"},
     ("c4_f6_8192_rc_silu", "xs_ring_f6_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((442681.9 * 2.0 + 262750.0) * 1024), "files": F6_SRC, "src": "cdff54bbe6d81efc"},
+        {"bytes": int((442679.1 * 2.0 + 262607.9) * 1024), "files": F6_SRC, "src": "2527cdc3f8431b39"},
     ("c2_f6_skinny16_rc_silu", "stream6_f6_rc_dma_cg4_wk4_ns2_sub2"):
-        {"bytes": int((115379.6 * 2.0 + 512.0) * 1024), "files": F6_SRC, "src": "cdff54bbe6d81efc"},
+        {"bytes": int((115500.3 * 2.0 + 512.0) * 1024), "files": F6_SRC, "src": "2527cdc3f8431b39"},
     ("c4_bf6_8192_rc_silu", "xs_ring_bf6_rc_256x256_w2x4_ns5_k64"):
-        {"bytes": int((442675.3 * 2.0 + 262515.9) * 1024), "files": F6_SRC, "src": "cdff54bbe6d81efc"},
+        {"bytes": int((442672.2 * 2.0 + 262616.3) * 1024), "files": F6_SRC, "src": "2527cdc3f8431b39"},
 }
 
 
