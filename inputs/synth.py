@@ -248,10 +248,11 @@ def f32_to_f6_codes(x: np.ndarray, dtype: int) -> np.ndarray:
     x = np.nan_to_num(np.ascontiguousarray(x, dtype=np.float32), nan=0.0)
     a = np.minimum(np.abs(x), table[-1])
     mids = (table[:-1].astype(np.float64) + table[1:].astype(np.float64)) / 2.0
-    code = np.searchsorted(mids, a.astype(np.float64), side="left").astype(np.int64)      # a == mid -> the lower code
-    tie = np.isin(a.astype(np.float64), mids) & (code % 2 == 1)
-    code = code + tie.astype(np.int64)
-    return (code | (np.signbit(x).astype(np.int64) << 5)).astype(np.uint8)
+    a64 = a.astype(np.float64)
+    code = np.searchsorted(mids, a64, side="left").astype(np.uint8)                       # a == mid -> the lower code
+    tie = (mids[np.minimum(code, len(mids) - 1)] == a64) & (code % 2 == 1)                # on a midpoint, lower code odd: the even one above
+    code = code + tie.astype(np.uint8)
+    return code | (np.signbit(x).astype(np.uint8) << np.uint8(5))
 
 
 def f6_codes_to_f32(codes: np.ndarray, dtype: int) -> np.ndarray:

@@ -72,7 +72,9 @@ def test_workload_matches_oracle(name):
 
 @pytest.mark.parametrize("name", synth.WORKLOADS + synth.BREADTH_WORKLOADS)
 def test_workload_shape_is_exact_on_integers(name):
-    w = synth.make_workload(name, scale=1 if name in ("c1_f32_256_relu", "c5_bf16_batched32_relu") else 1)
+    # (the few-row 6-bit shape at half its N and K: its 268 M elements take most of a minute to encode; the full size is
+    # checked by test_workload_matches_oracle)
+    w = synth.make_workload(name, scale=2 if name == "c2_f6_skinny16_rc_silu" else 1)
     lead = (w.batch,) if w.batch > 1 else ()
     def ints(tag, rows, cols, transpose):
         x = synth.integers(w.seed + 77, tag, rows, cols, batch=w.batch if w.batch > 1 else None)
