@@ -153,3 +153,13 @@ def test_degenerate_shapes(dt):
     for M, Nn, K in ((1, 8, 4), (8, 1, 4), (1, 1, 1024), (3, 5, 68)):
         A, B, b = operands(6200 + M + K, M, Nn, K)
         check_against_oracle(A, B, b, dtype=dt, act=synth.ACT_NONE, layout=1, exact=True)
+
+
+@BOTH
+@pytest.mark.parametrize("M,N,K", [(1000, 24, 2048), (520, 100, 1056), (4100, 16, 4096)])
+def test_few_columns_with_a_column_major_result(dt, M, N, K):
+    """Column-major C is served as the mirror-image problem (C^T = B^T A^T, the bias running down its rows): with few
+    columns that is a few-row problem for the streaming kernels, bias indexed by the row."""
+    A, B, bias = operands(6300 + N + K, M, N, K)
+    check_against_oracle(A, B, bias, dtype=dt, act=synth.ACT_RELU, layout=5, exact=True)
+    check_against_oracle(A * np.float32(0.25), B * np.float32(0.25), bias, dtype=dt, act=synth.ACT_SILU, layout=5, ldc_pad=8)
