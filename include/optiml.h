@@ -413,7 +413,8 @@ int optiml_mhsa(int64_t batch, int64_t N, int64_t d_model, int64_t heads, const 
  * optiml_gemm_epilogue_mx_path: 0 when the call would run on the matrix-pipe tile kernel (K a multiple of 128 for
  * E2M1, of 64 for the 8-bit and 6-bit types; 16-byte aligned operands and rows, except the 6-bit types, which are
  * copied; at least 65536 entries of C; any address and pitch of the scales), 1 for the one-thread-per-entry kernel, or
- * an error.  The tile kernel keeps a copy of the scales, (M + N) K / 32 bytes for E2M1 and (M + N) K / 16 for the
+ * an error; 2 for E2M1 with at most 128 rows (at most 48 when B is larger than 48 MB), at least 1024 columns and K a
+ * multiple of 128 (16-byte aligned operands and rows): a streaming kernel that reads operands and scales once, as they lie in memory, and needs no workspace.  The tile kernel keeps a copy of the scales, (M + N) K / 32 bytes for E2M1 and (M + N) K / 16 for the
  * others, in the workspace (see Workspace above), and for the 6-bit types also both operands with every 32 elements
  * in 32 bytes ((M + N) * max(320, K) bytes); the other kernel needs none.
  * OPTIML_ERR_INVALID_ARG (before any GPU call): negative sizes, K % 32 != 0, odd (E2M1) or too small lda / ldb, lda

@@ -21,6 +21,8 @@
 // addresses that the 16-byte and 4-byte loads cannot take, small problems - goes to mx_fallback_kernel,
 // one thread per entry of C: block sums of the exact products, scaled by 2^(ea + eb - 254), added in
 // fp32 in order of k.
+#include <type_traits>
+
 #include "kernel_tile_ring.hpp"
 
 namespace optiml {
@@ -94,6 +96,234 @@ __global__ __launch_bounds__(256) void mx_fallback_kernel(int64_t M, int64_t N, 
     C[row * ldc + col] = f32_to_bf16(apply_act(acc + (bias ? bias[col] : 0.0f), act));
 }
 
+// ---- a few rows of block-scaled E2M1: straight from memory into the 128-deep scaled instruction ----
+// Up to 128 rows of A over a large B the contraction is bound by reading B (N K / 2 bytes and N K / 32 scale bytes).
+// The 128-deep scaled instruction takes from lane l the block k = 32 (l / 16) .. + 31 of row l % 16 of each operand -
+// 16 contiguous bytes - and that block's scale from a register of the same lane: one 16-byte load and one byte load
+// per lane, operand and k-step, no LDS, no copy of the scales.  A wave owns 16 CG columns of C, the WK waves of a
+// workgroup take every WK-th run of U k-steps and add their partial sums through LDS; blockIdx.y is the block of 16
+// rows (each block reads B again).  K a multiple of 128, rows on 16-byte boundaries.
+typedef unsigned int mx_uintx4 __attribute__((ext_vector_type(4)));
+typedef float mx_floatx4 __attribute__((ext_vector_type(4)));
+typedef int mx_intx8 __attribute__((ext_vector_type(8)));
+
+template <int CG, int U> struct Mx4Set { mx_uintx4 a[U], b[U][CG]; unsigned int sa[U], sb[U][CG]; };
+
+template <int CG, int WK, int U>
+__global__ __launch_bounds__(64 * WK) void mx4_stream_kernel(int64_t M, int64_t N, int64_t K, const unsigned char *__restrict__ A, int64_t lda,
+                                                             const unsigned char *__restrict__ sA, int64_t lds_a,
+                                                             const unsigned char *__restrict__ B, int64_t ldb,
+                                                             const unsigned char *__restrict__ sB, int64_t lds_b,
+                                                             const float *__restrict__ bias, unsigned short *__restrict__ C, int64_t ldc, int act)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // lda, ldb in bytes here
+    __shared__ float part[WK][CG][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane & 15, grp = lane >> 4;
+    const int64_t m0 = 16 * (int64_t)blockIdx.y, n0 = (int64_t)blockIdx.x * (16 * CG);
+    const int64_t m = m0 + row < M ? m0 + row : M - 1;                     // lanes beyond M or N read the last row, store nothing
+    const unsigned char *a = A + m * lda + grp * 16, *as = sA + m * lds_a + grp;
+    const unsigned char *b[CG], *bs[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+        const int64_t n = n0 + 16 * g + row < N ? n0 + 16 * g + row : N - 1;
+        b[g] = B + n * ldb + grp * 16;
+        bs[g] = sB + n * lds_b + grp;
+    }
+    const int64_t steps = K / 128;
+    mx_floatx4 acc[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[g] = mx_floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+    Mx4Set<CG, U> cur, nxt;
+    // a k-step beyond the last one: the first step is read again and dropped (zero elements, unit scales)
+    auto fetch = [&](int64_t run, Mx4Set<CG, U> &f) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t step = run * U + u;
+            const bool inside = step < steps;
+            const int64_t s = inside ? step : 0;
+            const mx_uintx4 va = *reinterpret_cast<const mx_uintx4 *>(a + s * 64);
+            const unsigned int ea = as[s * 4];
+            f.a[u] = inside ? va : mx_uintx4{0u, 0u, 0u, 0u};
+            f.sa[u] = inside ? ea : 127u;
+#pragma unroll
+            for (int g = 0; g < CG; ++g) {
+                const mx_uintx4 vb = __builtin_nontemporal_load(reinterpret_cast<const mx_uintx4 *>(b[g] + s * 64));
+                const unsigned int eb = bs[g][s * 4];
+                f.b[u][g] = inside ? vb : mx_uintx4{0u, 0u, 0u, 0u};
+                f.sb[u][g] = inside ? eb : 127u;
+            }
+        }
+    };
+    auto multiply = [&](const Mx4Set<CG, U> &f) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const mx_intx8 a8 = {(int)f.a[u][0], (int)f.a[u][1], (int)f.a[u][2], (int)f.a[u][3], 0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < CG; ++g) {
+                const mx_intx8 b8 = {(int)f.b[u][g][0], (int)f.b[u][g][1], (int)f.b[u][g][2], (int)f.b[u][g][3], 0, 0, 0, 0};
+                // first operand B: acc[r] of lane l = sum over k of B[n0 + 16 g + 4 (l / 16) + r][k] A[l % 16][k], scaled per block
+                acc[g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b8, a8, acc[g], 4, 4, 0, (int)f.sb[u][g], 0, (int)f.sa[u]);
+            }
+        }
+    };
+    const int64_t runs = (steps + U - 1) / U;
+    fetch(wave, cur);
+    for (int64_t run = wave; run < runs; run += 2 * WK) {
+        fetch(run + WK, nxt);
+        multiply(cur);
+        fetch(run + 2 * WK, cur);
+        multiply(nxt);
+    }
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][g][r][lane] = acc[g][r];
+    __syncthreads();
+    for (int idx = wave; idx < CG * 4; idx += WK) {
+        const int g = idx >> 2, r = idx & 3;
+        float z = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WK; ++w) z += part[w][g][r][lane];
+        const int64_t col = n0 + 16 * g + 4 * grp + r;                      // this lane: row m0 + `row` of C
+        if (m0 + row < M && col < N) C[(m0 + row) * ldc + col] = f32_to_bf16(apply_act(z + (bias ? bias[col] : 0.0f), act));
+    }
+#endif
+}
+
+// The same through LDS-DMA (16-byte loads at 64-byte runs per row reach 2.5 TB/s): a stage is four k-steps = 256 bytes of
+// each row, 16-byte chunks by consecutive lanes, plus the stage's 16 scale bytes of each row as one more chunk; chunk c
+// of row r sits at position c ^ (r % 16) of the row's 16, so that the 16 rows a 16-byte read touches fall on different
+// banks.  Private stages per wave, NS - 1 in flight, hand-counted waits as in the other direct-to-LDS kernels; every
+// workgroup walks its stages from a start of its own.  Needs K a multiple of 512 and the scale rows on 16-byte
+// boundaries as well.
+template <int CG, int WK, int NS>
+__global__ __launch_bounds__(64 * WK) void mx4_dma_kernel(int64_t M, int64_t N, int64_t K, const unsigned char *__restrict__ A, int64_t lda,
+                                                          const unsigned char *__restrict__ sA, int64_t lds_a,
+                                                          const unsigned char *__restrict__ B, int64_t ldb,
+                                                          const unsigned char *__restrict__ sB, int64_t lds_b,
+                                                          const float *__restrict__ bias, unsigned short *__restrict__ C, int64_t ldc, int act)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    static_assert(CG == 2 || CG == 4, "the scale chunks of B: half or all of one instruction");
+    constexpr int A_DATA = 4096, A_SC = 1024, B_DATA = CG * 4096, B_SC = 1024;
+    constexpr int STAGE = A_DATA + A_SC + B_DATA + B_SC, LOADS = 4 + 1 + 4 * CG + 1;
+    static_assert((NS - 1) * LOADS < 64, "the counted wait has six bits");
+    static_assert(WK * CG * 4 * 64 * 4 <= WK * NS * STAGE, "the reduction buffer reuses the staging area");
+    extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
+    ring::lds_char *const lds = (ring::lds_char *)lds_raw;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), row = lane & 15, grp = lane >> 4;
+    const int64_t m0 = 16 * (int64_t)blockIdx.y, n0 = (int64_t)blockIdx.x * (16 * CG);
+    const char *a_base = reinterpret_cast<const char *>(A) + m0 * lda, *as_base = reinterpret_cast<const char *>(sA) + m0 * lds_a;
+    const char *b_base = reinterpret_cast<const char *>(B) + n0 * ldb, *bs_base = reinterpret_cast<const char *>(sB) + n0 * lds_b;
+    // global side (rows beyond M or N fetch the last row again: their sums are never stored).  Data: slot f = 64 j +
+    // lane of an operand holds chunk (f % 16) ^ (row % 16) of row f / 16; scales: slot f holds the chunk of row f
+    uint32_t a_off[4], b_off[4 * CG], as_off, bs_off;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int f = 64 * j + lane, r = f >> 4;
+        const int64_t rr = m0 + r < M ? r : M - 1 - m0;
+        a_off[j] = (uint32_t)(rr * lda + (((f & 15) ^ (r & 15)) << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < 4 * CG; ++j) {
+        const int f = 64 * j + lane, r = f >> 4;
+        const int64_t rr = n0 + r < N ? r : N - 1 - n0;
+        b_off[j] = (uint32_t)(rr * ldb + (((f & 15) ^ (r & 15)) << 4));
+    }
+    {
+        const int r = lane & 15;                                           // (lanes 16-63 fetch these rows again, into unused space)
+        as_off = (uint32_t)((m0 + r < M ? r : M - 1 - m0) * lds_a);
+        const int rb = lane % (16 * CG);
+        bs_off = (uint32_t)((n0 + rb < N ? rb : N - 1 - n0) * lds_b);
+    }
+    const uint32_t wave_lds = (uint32_t)reinterpret_cast<uintptr_t>(lds) + wave * (NS * STAGE);
+    auto issue = [&](int64_t stage, int slot) {
+        const char *ga = ring::scalar_ptr(a_base + stage * 256), *gb = ring::scalar_ptr(b_base + stage * 256);
+        const char *gas = ring::scalar_ptr(as_base + stage * 16), *gbs = ring::scalar_ptr(bs_base + stage * 16);
+        const uint32_t d = __builtin_amdgcn_readfirstlane(wave_lds + slot * STAGE);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ring::dma_load16(ga, a_off[j], d + j * 1024);
+        ring::dma_load16(gas, as_off, d + A_DATA);
+#pragma unroll
+        for (int j = 0; j < 4 * CG; ++j) ring::dma_load16_once(gb, b_off[j], d + A_DATA + A_SC + j * 1024);
+        ring::dma_load16_once(gbs, bs_off, d + A_DATA + A_SC + B_DATA);
+    };
+    mx_floatx4 acc[CG];
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[g] = mx_floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int64_t stages = K / 512;
+    const int64_t mine = stages > wave ? (stages - wave + WK - 1) / WK : 0;
+    const int64_t rot = mine > 0 ? (int64_t)blockIdx.x % mine : 0;
+    auto stage_of = [&](int64_t i) { return wave + ((i + rot) % mine) * WK; };
+    if (mine > 0) {
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(stage_of(s < mine ? s : mine - 1), s);
+        for (int64_t i = 0; i < mine; ++i) {
+            const int slot = (int)(i % NS);
+            const int64_t nxt = i + NS - 1;
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);                    // lgkmcnt(0): the previous stage's LDS reads have returned
+            issue(stage_of(nxt < mine ? nxt : mine - 1), (int)(nxt % NS));
+            ring::wait_vmcnt<(NS - 1) * LOADS>();                  // stage i has landed; its LDS reads below are new
+            asm volatile("" ::: "memory");
+            const ring::lds_char *st = lds + wave * (NS * STAGE) + slot * STAGE;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int pos = (((4 * u + grp) ^ row) << 4) + row * 256;                   // this lane's block of k-step u
+                const mx_uintx4 va = *reinterpret_cast<const __attribute__((address_space(3))) mx_uintx4 *>(st + pos);
+                const unsigned int ea = *reinterpret_cast<const __attribute__((address_space(3))) unsigned char *>(st + A_DATA + row * 16 + 4 * u + grp);
+                const mx_intx8 a8 = {(int)va[0], (int)va[1], (int)va[2], (int)va[3], 0, 0, 0, 0};
+#pragma unroll
+                for (int g = 0; g < CG; ++g) {
+                    const mx_uintx4 vb = *reinterpret_cast<const __attribute__((address_space(3))) mx_uintx4 *>(st + A_DATA + A_SC + g * 4096 + pos);
+                    const unsigned int eb =
+                        *reinterpret_cast<const __attribute__((address_space(3))) unsigned char *>(st + A_DATA + A_SC + B_DATA + (16 * g + row) * 16 + 4 * u + grp);
+                    const mx_intx8 b8 = {(int)vb[0], (int)vb[1], (int)vb[2], (int)vb[3], 0, 0, 0, 0};
+                    acc[g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b8, a8, acc[g], 4, 4, 0, (int)eb, 0, (int)ea);
+                }
+            }
+            asm volatile("" ::: "memory");                          // the reads are done before the slot is refilled
+        }
+        ring::wait_vmcnt<0>();
+    }
+    __syncthreads();                                                // the staging area is free now
+    __attribute__((address_space(3))) float *part = (__attribute__((address_space(3))) float *)lds;
+#pragma unroll
+    for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[((wave * CG + g) * 4 + r) * 64 + lane] = acc[g][r];
+    __syncthreads();
+    for (int idx = wave; idx < CG * 4; idx += WK) {
+        const int g = idx >> 2, r = idx & 3;
+        float z = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WK; ++w) z += part[((w * CG + g) * 4 + r) * 64 + lane];
+        const int64_t col = n0 + 16 * g + 4 * grp + r;
+        if (m0 + row < M && col < N) C[(m0 + row) * ldc + col] = f32_to_bf16(apply_act(z + (bias ? bias[col] : 0.0f), act));
+    }
+#endif
+}
+
+// ... and the DMA form's: whole stages of 512 k, scale rows on 16-byte boundaries, 32-bit offsets within a block of rows
+bool mx4_dma_streams(int64_t K, const void *sA, int64_t lds_a, const void *sB, int64_t lds_b, int64_t lda, int64_t ldb)
+{
+    if (K % 512 != 0 || ((lds_a | lds_b) & 15) || lda >= (int64_t(1) << 28) || ldb >= (int64_t(1) << 26)) return false;
+    return ((reinterpret_cast<uintptr_t>(sA) | reinterpret_cast<uintptr_t>(sB)) & 15u) == 0 && lds_a < (int64_t(1) << 26) && lds_b < (int64_t(1) << 24);
+}
+
+// the streaming kernel's ground: few rows, many columns, whole k-steps, rows the 16-byte loads can take
+bool mx4_streams(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
+{
+    if (M < 1 || M > 128 || N < 1024 || K < 128 || K % 128 != 0 || (N + 15) / 16 > 0x7fffffffLL) return false;
+    // every block of 16 rows reads B again: beyond three blocks only while B (N K / 2 bytes) stays in the Infinity Cache
+    // (64 x 8192 x 8192: 23.7 us against 55.9 us on the tile kernel; 128 x 16384 x 16384: 221 us against 100 us)
+    if (M > 48 && (double)N * (double)K > 96e6) return false;
+    if ((lda | ldb) & 31) return false;                                     // (elements: 16 bytes)
+    return ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0;
+}
+
 bool aligned_to(const void *q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) == 0; }
 
 // the problem in bytes of k, as the ring kernel sees it
@@ -145,12 +375,13 @@ hipError_t launch_tiles(const Problem &p, int64_t nk, int sb, const void *scaleA
 
 }  // namespace
 
-// 0: the ring kernel, 1: the fallback
+// 0: the ring kernel, 1: the fallback, 2: the streaming kernel for a few rows of E2M1
 int mx_path(int dtype, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *scaleA, int64_t lds_a, const void *B,
             int64_t ldb, const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc)
 {
     (void)scaleA; (void)scaleB; (void)lds_a; (void)lds_b;          // the copy takes any scale address and pitch
     const Problem p = byte_problem(dtype, M, N, K, A, lda, B, ldb, bias, C, ldc, 0);
+    if (dtype == DT_F4 && mx4_streams(M, N, K, A, lda, B, ldb)) return 2;
     if (M * N < 65536 || M >= (int64_t(1) << 30) || N >= (int64_t(1) << 30)) return 1;
     if (dtype == DT_F4) return K % 128 == 0 && ring::supports<MxCfg>(p) ? 0 : 1;
     if (K % 64 != 0) return 1;
@@ -169,7 +400,37 @@ hipError_t launch_mx(int dtype, int64_t M, int64_t N, int64_t K, const void *A, 
                      const void *B, int64_t ldb, const void *scaleB, int64_t lds_b, const float *bias, void *C, int64_t ldc, int act,
                      hipStream_t stream)
 {
-    if (mx_path(dtype, M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc) == 0) {
+    const int path = mx_path(dtype, M, N, K, A, lda, scaleA, lds_a, B, ldb, scaleB, lds_b, bias, C, ldc);
+    if (path == 2) {
+        const unsigned char *a = static_cast<const unsigned char *>(A), *b = static_cast<const unsigned char *>(B);
+        const unsigned char *sa = static_cast<const unsigned char *>(scaleA), *sb = static_cast<const unsigned char *>(scaleB);
+        unsigned short *c = static_cast<unsigned short *>(C);
+        const unsigned rb = (unsigned)((M + 15) / 16);
+        if (mx4_dma_streams(K, scaleA, lds_a, scaleB, lds_b, lda, ldb)) {
+            // 64 columns and three waves a workgroup (16 x 16384 x 16384: 28.6 us against 40.6 us for 32 columns and four
+            // waves) once that still gives three quarters of the CUs a workgroup
+            auto go = [&](auto cg, auto wk) -> hipError_t {
+                constexpr int CG = decltype(cg)::value, WK = decltype(wk)::value, NS = 2, LDS_BYTES = WK * NS * (4096 + 1024 + CG * 4096 + 1024);
+                static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+                static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx4_dma_kernel<CG, WK, NS>),
+                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+                if (attr != hipSuccess) return attr;
+                hipLaunchKernelGGL((mx4_dma_kernel<CG, WK, NS>), dim3((unsigned)((N + 16 * CG - 1) / (16 * CG)), rb), dim3(64 * WK), LDS_BYTES, stream,
+                                   M, N, K, a, lda / 2, sa, lds_a, b, ldb / 2, sb, lds_b, bias, c, ldc, act);
+                return hipGetLastError();
+            };
+            if ((N + 63) / 64 * (int64_t)rb >= (int64_t)compute_units() * 3 / 4) return go(std::integral_constant<int, 4>{}, std::integral_constant<int, 3>{});
+            return go(std::integral_constant<int, 2>{}, std::integral_constant<int, 4>{});
+        }
+        if (N >= 8192)
+            hipLaunchKernelGGL((mx4_stream_kernel<4, 8, 2>), dim3((unsigned)((N + 63) / 64), rb), dim3(512), 0, stream, M, N, K, a, lda / 2, sa, lds_a, b,
+                               ldb / 2, sb, lds_b, bias, c, ldc, act);
+        else
+            hipLaunchKernelGGL((mx4_stream_kernel<1, 4, 4>), dim3((unsigned)((N + 15) / 16), rb), dim3(256), 0, stream, M, N, K, a, lda / 2, sa, lds_a, b,
+                               ldb / 2, sb, lds_b, bias, c, ldc, act);
+        return hipGetLastError();
+    }
+    if (path == 0) {
         const Problem p = byte_problem(dtype, M, N, K, A, lda, B, ldb, bias, C, ldc, act);
         if (dtype == DT_F4) return launch_tiles<MxCfg>(p, K / 128, 4, scaleA, lds_a, scaleB, lds_b, stream);
         if (dtype == DT_F8) return launch_tiles<Mx8Cfg<DT_F8>>(p, K / 64, 2, scaleA, lds_a, scaleB, lds_b, stream);

@@ -260,3 +260,53 @@ def test_6bit_pitches_offsets_and_the_benchmark_size(dt):
     ref = oracle.gemm_epilogue_mx(np.ascontiguousarray(As[rows]), np.ascontiguousarray(sA[rows]), np.ascontiguousarray(Bs[cols]),
                                   np.ascontiguousarray(sB[cols]), bias[cols], len(rows), len(cols), K, dtype=dt, act=synth.ACT_SILU)
     assert e1(got[np.ix_(rows, cols)], ref) <= 2e-2
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 2048, 1024), (5, 1030, 384), (128, 1024, 512), (40, 8200, 256), (1, 16384, 128), (17, 8192, 2048)])
+def test_few_rows_of_block_scaled_e2m1_take_the_streaming_kernel(M, N, K):
+    As, sA = quantised(8200 + M + K, "A", M, K, 6); Bs, sB = quantised(8200 + M + K, "B", N, K, 6)
+    bias = synth.normal(8200 + M + K, "bias", 1, N)[0]
+    for act in (synth.ACT_NONE, synth.ACT_SILU):
+        got, path, raw = run(As, sA, Bs, sB, bias, M, N, K, act, pad_c=8)
+        assert path == 2
+        ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, bias, M, N, K, dtype=F4, act=act)
+        assert np.all(np.isfinite(got)) and e1(got, ref) <= 2e-2
+        assert np.array_equal(run(As, sA, Bs, sB, bias, M, N, K, act, pad_c=8)[2], raw)          # bitwise repeatable
+    # equal scales: exact; pitches and offsets that keep the rows on 16-byte boundaries, any scale address
+    one = np.full_like(sA, 125); oneB = np.full_like(sB, 130)
+    got, path, _ = run(As, one, Bs, oneB, None, M, N, K, synth.ACT_NONE, pitch=16, spitch=3, shift=16, sshift=1)
+    ref = oracle.gemm_epilogue_mx(As, one, Bs, oneB, None, M, N, K, dtype=F4, act=synth.ACT_NONE)
+    assert path == 2 and np.array_equal(got, synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64))
+    # rows off the 16-byte grid go elsewhere
+    assert run(As, sA, Bs, sB, bias, M, N, K, synth.ACT_NONE, shift=3)[1] != 2
+
+
+def test_every_scale_byte_lands_on_its_block_in_the_streaming_kernel():
+    """One-hot rows of A pick single k positions; then one block of one row (column) scaled by 2^20 changes exactly that
+    row (column)."""
+    M, N, K = 16, 1040, 1024
+    A1 = np.zeros((M, K), dtype=np.float32); A1[np.arange(M), (37 * np.arange(M) + 11) % K] = 2.0
+    As = synth.to_bits(A1, F4); Bs = synth.to_bits(synth.integers(8300, "B", N, K, -4, 4), F4)
+    sA = (120 + synth.integers(8301, "sa", M, K // 32, 0, 14)).astype(np.uint8); sB = (120 + synth.integers(8302, "sb", N, K // 32, 0, 14)).astype(np.uint8)
+    got, path, _ = run(As, sA, Bs, sB, None, M, N, K, synth.ACT_NONE)
+    ref = oracle.gemm_epilogue_mx(As, sA, Bs, sB, None, M, N, K, dtype=F4, act=synth.ACT_NONE)
+    assert path == 2 and np.array_equal(got, synth.bf16_bits_to_f32(oracle.bf16_from_double(ref)).astype(np.float64))   # one product per entry: exact
+    As, _ = quantised(8310, "A", M, K, 0); Bs, _ = quantised(8310, "B", N, K, 0)
+    sA = np.full((M, K // 32), 127, dtype=np.uint8); sB = np.full((N, K // 32), 127, dtype=np.uint8)
+    base, _, _ = run(As, sA, Bs, sB, None, M, N, K, synth.ACT_NONE)
+    for row, blk in ((0, 0), (9, 5), (15, 31)):
+        s2 = sA.copy(); s2[row, blk] = 147
+        got, _, _ = run(As, s2, Bs, sB, None, M, N, K, synth.ACT_NONE)
+        assert e1(got, oracle.gemm_epilogue_mx(As, s2, Bs, sB, None, M, N, K, dtype=F4, act=synth.ACT_NONE)) <= 2e-2
+        others = np.delete(np.arange(M), row)
+        assert np.array_equal(got[others], base[others]) and not np.array_equal(got[row], base[row])
+    for col, blk in ((0, 1), (1039, 30), (256, 9)):
+        s2 = sB.copy(); s2[col, blk] = 147
+        got, _, _ = run(As, sA, Bs, s2, None, M, N, K, synth.ACT_NONE)
+        assert e1(got, oracle.gemm_epilogue_mx(As, sA, Bs, s2, None, M, N, K, dtype=F4, act=synth.ACT_NONE)) <= 2e-2
+        others = np.delete(np.arange(N), col)
+        assert np.array_equal(got[:, others], base[:, others])
+    # a NaN scale poisons exactly its row
+    s2 = sA.copy(); s2[3, 7] = 255
+    got, _, _ = run(As, s2, Bs, sB, None, M, N, K, synth.ACT_NONE)
+    assert np.all(np.isnan(got[3])) and not np.any(np.isnan(np.delete(got, 3, 0)))
