@@ -13,10 +13,11 @@ the breadth workloads (other storage types and layouts on the same shapes) and t
 element-wise ReLU / sigmoid, sum, dot, MSE on 2^28 floats (s_relu, s_sigmoid, s_sum, s_dot,
 s_mse), transpose (s_transpose), cross-entropy and LayerNorm (s_ce, s_ln_sample, s_ln_token),
 attention (s_mhsa), the contraction fused with the cross-entropy (s_lce, s_lce_f32) and with
-LayerNorm (s_gln, s_gln_f32), the block-scaled 4-bit and 8-bit contractions (s_mxf4, s_mxf8).  Any of these names can be the headline.  One JSON line is printed.
+LayerNorm (s_gln, s_gln_f32), the block-scaled 4-, 6- and 8-bit contractions (s_mxf4, s_mxf6, s_mxf8; s_mxf4_rows16: 16 rows).
+Any of these names can be the headline.  One JSON line is printed.
 
 The "roofline" object prices the dominant kernel of a workload against the published MI355X peak
-(HBM 8 TB/s, dense bf16 / fp16 MFMA 2516.6 TFLOP/s, fp8 5033.2, fp4 10066.3, fp32 MFMA 157.3) using algorithmic
+(HBM 8 TB/s, dense bf16 / fp16 MFMA 2516.6 TFLOP/s, fp8 5033.2, fp6 and fp4 10066.3, fp32 MFMA 157.3) using algorithmic
 bytes / flops (one read of the inputs, one write of the outputs; 2*M*N*K flops).  "cpu_baseline" is
 the fp64 CPU oracle timed on this host as it stands.  "calibration" holds what the library's two
 measuring kernels reach on this board in the same run: the plain copy (HBM) and the register-only

@@ -360,6 +360,7 @@ def test_block_scaled_entry_point_validates_and_picks_its_kernel_on_the_host():
     assert call()[1] == 0 and call(M=4096, N=4096, K=4096)[1] == 0                        # the matrix-pipe tile kernel
     assert call(K=480)[1] == 1 and call(M=100, N=100)[1] == 1                             # K not whole k-tiles; a small C
     assert call(M=16, N=4096, K=1024)[1] == 2 and call(M=128, N=1024)[1] == 2 and call(M=129, N=1024)[1] == 0   # few rows of E2M1: streamed
+    assert call(M=48, N=16384, K=16384)[1] == 2 and call(M=49, N=16384, K=16384)[1] == 0 and call(M=128, N=8192, K=8192)[1] == 2   # more than three blocks of rows: only over a B the Infinity Cache holds
     assert call(M=16, N=4096, K=1056)[1] == 1 and call(M=16, N=4096, dtype=3)[1] == 0   # (other element types: the tile kernel)
     assert call(A=P + 2)[1] == 1                                                          # an address the wide loads cannot take
     assert call(sA=P + 1)[1] == 0 and call(lds_a=18)[1] == 0                              # the scales are copied first: any address and pitch
