@@ -112,15 +112,14 @@ hipError_t f6_launch(const Problem &p, hipStream_t s)
 }
 
 // ---- a few rows: the dense form straight into registers -------------------------------------------
-// C (up to 16 rows per workgroup; up to kF6RowBlocks such blocks, each reading B again) = act(A . B + bias) is bound by
-// reading B.  The 128-deep form of the matrix
-// instruction takes from lane l the 32 values k = 32 (l / 16) .. + 31 of row l % 16 of each operand: 24
-// contiguous bytes of a dense row, which three 8-byte loads fetch as they lie in memory - no copy, no
-// LDS.  A wave owns 16 columns of C (16 rows of B, stored [N][K]); the WK waves of a workgroup take
-// every WK-th run of U k-steps of 128 and add their 16 x 16 partial sums through LDS; the loads of
-// the next run are issued before the current run is multiplied.  A (16 x K, at most 192 KiB at K =
-// 16384) is re-read by every wave from the caches.  Needs rows that start on 8-byte boundaries
-// (pitches multiples of 32 elements = 24 bytes) and K a multiple of 32.
+// C (up to 16 rows per workgroup; up to kF6RowBlocks such blocks, each reading B again) = act(A . B + bias) is bound
+// by reading B.  The 128-deep form of the matrix instruction takes from lane l the 32 values k = 32 (l / 16) .. + 31
+// of row l % 16 of each operand: 24 contiguous bytes of a dense row, which three 8-byte loads fetch as they lie in
+// memory - no copy, no LDS.  A wave owns 16 CG columns of C (16 CG rows of B, stored [N][K]); the WK waves of a
+// workgroup take every WK-th run of U k-steps of 128 and add their partial sums through LDS; the loads of the next
+// run are issued before the current run is multiplied.  A (16 x K, at most 192 KiB at K = 16384) is re-read by every
+// wave from the caches.  Needs rows that start on 8-byte boundaries (pitches multiples of 32 elements = 24 bytes)
+// and K a multiple of 32.
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx8 __attribute__((ext_vector_type(8)));
